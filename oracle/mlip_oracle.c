@@ -1,0 +1,356 @@
+/*
+ * CPU oracle for the graph-partitioned radial message-passing potential.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain reference the GPU
+ * library is checked against.  It shares no code with the HIP path; only the
+ * tests, the smoke check and the benchmark's cpu_baseline leg may call it.
+ *
+ * What it follows:
+ *  - the periodic radius graph ("neighbor list construction", Methods,
+ *    Graph-Parallel Message Passing): edge i <- j with image shift S exists
+ *    iff 0 < |r_j + S.C - r_i| <= r_cut (inclusive cutoff);
+ *  - the radial message-passing model of the benchmark configurations: Bessel
+ *    radial functions sin(n pi d / rc) / d times a polynomial envelope, filter
+ *    MLP Linear(K,F) -> SiLU -> Linear(F,F), message = filter * projected
+ *    sender features, summed per receiver;
+ *  - forces as the exact derivative of the energy (Introduction, E = phi(r, C)),
+ *    obtained by reverse differentiation written out by hand.
+ *
+ * Fixed arithmetic of the edge predicate (both sides of the parity test use it):
+ *   delta_k = (r_j,k - r_i,k) + ((Sx*C[0][k] + Sy*C[1][k]) + Sz*C[2][k])
+ *   d2      = (delta_x^2 + delta_y^2) + delta_z^2        (fp64, no FMA)
+ *   edge iff d2 <= r_cut*r_cut and not (i == j and S == 0)
+ * Compile with -ffp-contract=off.
+ *
+ * Parity pins (tests/test_oracle_*.py): closed-form coordination shells of sc
+ * and fcc lattices, brute force against the cell list, edge-set symmetry,
+ * basis limits/orthogonality, finite-difference forces, invariances, special
+ * cases with closed forms.  Absolute energies for random weights have no
+ * external reference: parity unpinned beyond those checks.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+typedef struct {
+    int64_t N, E;
+    int64_t *row_ptr; /* N+1 */
+    int32_t *senders; /* E   */
+    int32_t *shifts;  /* E*3 */
+} orc_graph;
+
+typedef struct { int32_t j, sx, sy, sz; } orc_nbr;
+
+int orc_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+void orc_set_threads(int n)
+{
+#ifdef _OPENMP
+    if (n > 0) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
+/* ---- cell geometry ------------------------------------------------------ */
+
+static void cross3(const double *a, const double *b, double *o)
+{
+    o[0] = a[1] * b[2] - a[2] * b[1];
+    o[1] = a[2] * b[0] - a[0] * b[2];
+    o[2] = a[0] * b[1] - a[1] * b[0];
+}
+
+/* normals n_k = a_{k+1} x a_{k+2}; V = a_0 . n_0; heights h_k = |V| / |n_k| */
+static int cell_geometry(const double *C, double nrm[3][3], double *V, double h[3])
+{
+    cross3(C + 3, C + 6, nrm[0]);
+    cross3(C + 6, C + 0, nrm[1]);
+    cross3(C + 0, C + 3, nrm[2]);
+    *V = (C[0] * nrm[0][0] + C[1] * nrm[0][1]) + C[2] * nrm[0][2];
+    if (!(fabs(*V) > 0.0)) return -1;
+    for (int k = 0; k < 3; ++k) {
+        double l = sqrt(nrm[k][0] * nrm[k][0] + nrm[k][1] * nrm[k][1] + nrm[k][2] * nrm[k][2]);
+        h[k] = fabs(*V) / l;
+    }
+    return 0;
+}
+
+/* fractional coordinate along lattice vector k: ((x nx + y ny) + z nz) / V */
+static inline double frac_k(const double *r, const double *n, double V)
+{
+    return ((r[0] * n[0] + r[1] * n[1]) + r[2] * n[2]) / V;
+}
+
+/* Slab rule (Alg. 1 step 1, "partition rule based on the longest cell
+ * dimension", vertical walls): axis = longest lattice vector (ties -> lowest
+ * index); f = fractional coordinate wrapped into [0,1); slab = min(floor(f*P), P-1). */
+int orc_slab_assign(int64_t N, const double *pos, const double *C, int P, int32_t *slab_of, int32_t *axis_out)
+{
+    double nrm[3][3], V, h[3];
+    if (cell_geometry(C, nrm, &V, h)) return -1;
+    int ax = 0;
+    double best = -1.0;
+    for (int k = 0; k < 3; ++k) {
+        double l2 = (C[3 * k] * C[3 * k] + C[3 * k + 1] * C[3 * k + 1]) + C[3 * k + 2] * C[3 * k + 2];
+        if (l2 > best) { best = l2; ax = k; }
+    }
+    for (int64_t i = 0; i < N; ++i) {
+        double f = frac_k(pos + 3 * i, nrm[ax], V);
+        double fw = f - floor(f);
+        int s = (int)floor(fw * (double)P);
+        if (s > P - 1) s = P - 1;
+        if (s < 0) s = 0;
+        slab_of[i] = s;
+    }
+    if (axis_out) *axis_out = ax;
+    return 0;
+}
+
+/* ---- the edge predicate ------------------------------------------------- */
+
+static inline double edge_d2(const double *ri, const double *rj, const double *C,
+                             int sx, int sy, int sz, double *delta)
+{
+    for (int k = 0; k < 3; ++k)
+        delta[k] = (rj[k] - ri[k]) +
+                   (((double)sx * C[k] + (double)sy * C[3 + k]) + (double)sz * C[6 + k]);
+    return (delta[0] * delta[0] + delta[1] * delta[1]) + delta[2] * delta[2];
+}
+
+static orc_graph *graph_alloc(int64_t N)
+{
+    orc_graph *g = (orc_graph *)calloc(1, sizeof(orc_graph));
+    g->N = N;
+    g->row_ptr = (int64_t *)calloc((size_t)N + 1, sizeof(int64_t));
+    return g;
+}
+
+void orc_graph_free(orc_graph *g)
+{
+    if (!g) return;
+    free(g->row_ptr);
+    free(g->senders);
+    free(g->shifts);
+    free(g);
+}
+
+/* ---- brute force: every pair, every image ------------------------------- */
+
+orc_graph *orc_build_brute(int64_t N, const double *pos, const double *C, double rcut)
+{
+    double nrm[3][3], V, h[3];
+    if (N <= 0 || cell_geometry(C, nrm, &V, h)) return NULL;
+    int nimg[3];
+    for (int k = 0; k < 3; ++k) {
+        double lo = 1e300, hi = -1e300;
+        for (int64_t i = 0; i < N; ++i) {
+            double f = frac_k(pos + 3 * i, nrm[k], V);
+            if (f < lo) lo = f;
+            if (f > hi) hi = f;
+        }
+        nimg[k] = (int)ceil((hi - lo) + rcut / h[k]) + 1;
+    }
+    const double rc2 = rcut * rcut;
+    orc_graph *g = graph_alloc(N);
+    size_t cap = 1024, E = 0;
+    int32_t *snd = (int32_t *)malloc(cap * sizeof(int32_t));
+    int32_t *shf = (int32_t *)malloc(cap * 3 * sizeof(int32_t));
+    double delta[3];
+    for (int64_t i = 0; i < N; ++i) {
+        g->row_ptr[i] = (int64_t)E;
+        for (int64_t j = 0; j < N; ++j)
+            for (int sx = -nimg[0]; sx <= nimg[0]; ++sx)
+                for (int sy = -nimg[1]; sy <= nimg[1]; ++sy)
+                    for (int sz = -nimg[2]; sz <= nimg[2]; ++sz) {
+                        if (i == j && sx == 0 && sy == 0 && sz == 0) continue;
+                        double d2 = edge_d2(pos + 3 * i, pos + 3 * j, C, sx, sy, sz, delta);
+                        if (d2 <= rc2) {
+                            if (E == cap) {
+                                cap *= 2;
+                                snd = (int32_t *)realloc(snd, cap * sizeof(int32_t));
+                                shf = (int32_t *)realloc(shf, cap * 3 * sizeof(int32_t));
+                            }
+                            snd[E] = (int32_t)j;
+                            shf[3 * E] = sx; shf[3 * E + 1] = sy; shf[3 * E + 2] = sz;
+                            ++E;
+                        }
+                    }
+    }
+    g->row_ptr[N] = (int64_t)E;
+    g->E = (int64_t)E;
+    g->senders = snd;
+    g->shifts = shf;
+    return g;
+}
+
+/* ---- cell list ----------------------------------------------------------- */
+
+static int nbr_cmp(const void *a, const void *b)
+{
+    const orc_nbr *x = (const orc_nbr *)a, *y = (const orc_nbr *)b;
+    if (x->j != y->j) return x->j < y->j ? -1 : 1;
+    if (x->sx != y->sx) return x->sx < y->sx ? -1 : 1;
+    if (x->sy != y->sy) return x->sy < y->sy ? -1 : 1;
+    if (x->sz != y->sz) return x->sz < y->sz ? -1 : 1;
+    return 0;
+}
+
+static inline int floordiv(int a, int b) { int q = a / b; if ((a % b != 0) && ((a < 0) != (b < 0))) --q; return q; }
+
+orc_graph *orc_build_cells(int64_t N, const double *pos, const double *C, double rcut)
+{
+    double nrm[3][3], V, h[3];
+    if (N <= 0 || cell_geometry(C, nrm, &V, h)) return NULL;
+    const double rpad = rcut * 1.000001 + 1e-12;
+    int nb[3], reach[3];
+    for (int k = 0; k < 3; ++k) {
+        int n = (int)floor(h[k] / rpad);
+        if (n < 1) n = 1;
+        if (n > 256) n = 256;
+        nb[k] = n;
+        reach[k] = (int)ceil(rpad / (h[k] / n));
+    }
+    const int64_t ncell = (int64_t)nb[0] * nb[1] * nb[2];
+    int32_t *wrap = (int32_t *)malloc((size_t)N * 3 * sizeof(int32_t));
+    int32_t *bin = (int32_t *)malloc((size_t)N * 3 * sizeof(int32_t));
+    int64_t *cstart = (int64_t *)calloc((size_t)ncell + 1, sizeof(int64_t));
+    int32_t *catom = (int32_t *)malloc((size_t)N * sizeof(int32_t));
+    for (int64_t i = 0; i < N; ++i) {
+        int64_t c = 0;
+        for (int k = 0; k < 3; ++k) {
+            double f = frac_k(pos + 3 * i, nrm[k], V);
+            double fl = floor(f);
+            int b = (int)floor((f - fl) * nb[k]);
+            if (b > nb[k] - 1) b = nb[k] - 1;
+            if (b < 0) b = 0;
+            wrap[3 * i + k] = (int32_t)fl;
+            bin[3 * i + k] = b;
+            c = c * nb[k] + b;
+        }
+        cstart[c + 1]++;
+    }
+    for (int64_t c = 0; c < ncell; ++c) cstart[c + 1] += cstart[c];
+    {
+        int64_t *fill = (int64_t *)malloc((size_t)ncell * sizeof(int64_t));
+        memcpy(fill, cstart, (size_t)ncell * sizeof(int64_t));
+        for (int64_t i = 0; i < N; ++i) {
+            int64_t c = ((int64_t)bin[3 * i] * nb[1] + bin[3 * i + 1]) * nb[2] + bin[3 * i + 2];
+            catom[fill[c]++] = (int32_t)i;
+        }
+        free(fill);
+    }
+    const double rc2 = rcut * rcut;
+    orc_graph *g = graph_alloc(N);
+    /* pass 0 counts, pass 1 fills */
+    for (int pass = 0; pass < 2; ++pass) {
+        if (pass == 1) {
+            int64_t acc = 0;
+            for (int64_t i = 0; i < N; ++i) { int64_t c = g->row_ptr[i]; g->row_ptr[i] = acc; acc += c; }
+            g->row_ptr[N] = acc;
+            g->E = acc;
+            g->senders = (int32_t *)malloc((size_t)(acc ? acc : 1) * sizeof(int32_t));
+            g->shifts = (int32_t *)malloc((size_t)(acc ? acc : 1) * 3 * sizeof(int32_t));
+        }
+#pragma omp parallel for schedule(dynamic, 256)
+        for (int64_t i = 0; i < N; ++i) {
+            double delta[3];
+            int64_t cnt = 0, cap = 0;
+            orc_nbr *row = NULL;
+            if (pass == 1) {
+                cap = g->row_ptr[i + 1] - g->row_ptr[i];
+                row = (orc_nbr *)malloc((size_t)(cap ? cap : 1) * sizeof(orc_nbr));
+            }
+            for (int dx = -reach[0]; dx <= reach[0]; ++dx)
+                for (int dy = -reach[1]; dy <= reach[1]; ++dy)
+                    for (int dz = -reach[2]; dz <= reach[2]; ++dz) {
+                        int cc[3] = { bin[3 * i] + dx, bin[3 * i + 1] + dy, bin[3 * i + 2] + dz };
+                        int img[3];
+                        for (int k = 0; k < 3; ++k) { img[k] = floordiv(cc[k], nb[k]); cc[k] -= img[k] * nb[k]; }
+                        int64_t c = ((int64_t)cc[0] * nb[1] + cc[1]) * nb[2] + cc[2];
+                        for (int64_t q = cstart[c]; q < cstart[c + 1]; ++q) {
+                            int32_t j = catom[q];
+                            int sx = img[0] - wrap[3 * j] + wrap[3 * i];
+                            int sy = img[1] - wrap[3 * j + 1] + wrap[3 * i + 1];
+                            int sz = img[2] - wrap[3 * j + 2] + wrap[3 * i + 2];
+                            if (j == i && sx == 0 && sy == 0 && sz == 0) continue;
+                            double d2 = edge_d2(pos + 3 * i, pos + 3 * j, C, sx, sy, sz, delta);
+                            if (d2 <= rc2) {
+                                if (pass == 1) { row[cnt].j = j; row[cnt].sx = sx; row[cnt].sy = sy; row[cnt].sz = sz; }
+                                ++cnt;
+                            }
+                        }
+                    }
+            if (pass == 0) {
+                g->row_ptr[i] = cnt;
+            } else {
+                qsort(row, (size_t)cnt, sizeof(orc_nbr), nbr_cmp);
+                int64_t base = g->row_ptr[i];
+                for (int64_t q = 0; q < cnt; ++q) {
+                    g->senders[base + q] = row[q].j;
+                    g->shifts[3 * (base + q)] = row[q].sx;
+                    g->shifts[3 * (base + q) + 1] = row[q].sy;
+                    g->shifts[3 * (base + q) + 2] = row[q].sz;
+                }
+                free(row);
+            }
+        }
+    }
+    free(wrap); free(bin); free(cstart); free(catom);
+    return g;
+}
+
+/* ---- edge geometry: delta, d, unit vector (fp64) ------------------------ */
+
+void orc_geometry(int64_t N, const double *pos, const double *C, const int64_t *row_ptr,
+                  const int32_t *senders, const int32_t *shifts, double *d, double *rhat)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < N; ++i) {
+        double delta[3];
+        for (int64_t e = row_ptr[i]; e < row_ptr[i + 1]; ++e) {
+            double d2 = edge_d2(pos + 3 * i, pos + 3 * (int64_t)senders[e], C,
+                                shifts[3 * e], shifts[3 * e + 1], shifts[3 * e + 2], delta);
+            double dd = sqrt(d2);
+            d[e] = dd;
+            rhat[3 * e] = delta[0] / dd; rhat[3 * e + 1] = delta[1] / dd; rhat[3 * e + 2] = delta[2] / dd;
+        }
+    }
+}
+
+/* ---- model arithmetic, once in fp64 and once in fp32 -------------------- */
+
+#define REAL double
+#define FN(name) name##_f64
+#define R_SIN sin
+#define R_COS cos
+#define R_EXP exp
+#include "rmp_edge.inc"
+#undef REAL
+#undef FN
+#undef R_SIN
+#undef R_COS
+#undef R_EXP
+
+#define REAL float
+#define FN(name) name##_f32
+#define R_SIN sinf
+#define R_COS cosf
+#define R_EXP expf
+#include "rmp_edge.inc"
+#undef REAL
+#undef FN
+#undef R_SIN
+#undef R_COS
+#undef R_EXP

@@ -1,0 +1,205 @@
+/*
+ * libmlip -- graph-partitioned inference of a radial message-passing
+ * interatomic potential on one AMD MI355X (gfx950).  C ABI, no C++ or torch
+ * types.  Every pointer argument is marked HOST or DEVICE.
+ *
+ * The problem statement followed here is the paper's: the inputs are atom
+ * positions, the periodic cell and chemical identities (Introduction,
+ * E = phi(r_i, C_i); appendix "Parallelizing a Model": the distributed object
+ * takes positions, periodic boundary conditions and cell lattice and builds
+ * the graph partitions and their transfer metadata), the output is the energy
+ * and the forces F = -dE/dr obtained by a reverse pass that runs through the
+ * per-layer border-node transfers (Introduction, "graph-level partitioning";
+ * Methods, "Graph-Parallel Message Passing").
+ *
+ * Conventions
+ *   - every function returns 0 (MLIP_OK) or a negative mlip_status; no C++
+ *     exception or abort crosses this boundary; on error no output argument is
+ *     written and mlip_last_error() describes the failure (thread-local text);
+ *   - a graph handle owns all device memory it allocates (hipMalloc) until
+ *     mlip_graph_destroy; inputs are borrowed for the duration of the call and
+ *     never written; handles are not thread-safe;
+ *   - all work is enqueued on the HIP stream given to mlip_build_graph
+ *     (a hipStream_t passed as void*, NULL = default stream); outputs of
+ *     mlip_forward are valid after that stream is synchronised;
+ *   - atoms are numbered 0..N-1 in input order; edges are directed i <- j
+ *     (i receives, j sends) and carry an integer image shift S so that the
+ *     sender's image sits at r_j + S.C, C = rows of `cell`.
+ */
+#ifndef MLIP_H
+#define MLIP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MLIP_OK = 0,
+    MLIP_EINVAL = -1,      /* null pointer, N <= 0, r_cut <= 0, n_slabs outside [1,64], bad model dims */
+    MLIP_ECELL = -2,       /* singular cell, or cell/positions outside the supported image range */
+    MLIP_ECOINCIDENT = -3, /* two atoms (or an atom and an image) at distance 0 */
+    MLIP_ENOMEM = -4,      /* device allocation failed */
+    MLIP_EHIP = -5,        /* HIP runtime error */
+    MLIP_ESTATE = -6       /* call not valid for this handle (e.g. SLABS mode on a graph built with n_slabs = 1) */
+} mlip_status;
+
+enum { MLIP_MODE_WHOLE = 0, MLIP_MODE_SLABS = 1 };
+enum { MLIP_PRECISION_FP32 = 0 };
+
+typedef struct mlip_graph mlip_graph_t;
+
+/*
+ * Weights of the radial message-passing potential (benchmark configuration 0
+ * defines it): species embedding; per layer l the filter MLP W1_l (K x F),
+ * W2_l (F x F), the sender projection Wm_l (F x F) and the update Wo_l (F x F);
+ * readout Wr1 (F x F), wr2 (F).  All fp32, row-major [fan_in][fan_out]
+ * (y = x W), no biases.  DEVICE pointers, borrowed.
+ * Supported: F in {32, 64}, K = 8, 1 <= L <= 8, p >= 2, n_species >= 1.
+ */
+typedef struct {
+    int32_t n_species, F, L, K, p, precision;
+    const float *emb; /* [n_species][F] */
+    const float *W1;  /* [L][K][F] */
+    const float *W2;  /* [L][F][F] */
+    const float *Wm;  /* [L][F][F] */
+    const float *Wo;  /* [L][F][F] */
+    const float *Wr1; /* [F][F] */
+    const float *wr2; /* [F] */
+} mlip_weights_t;
+
+/*
+ * One partition's node array and local graph (Alg. "Atom Subgraph Creation":
+ * concatenated buckets plus a marker array of span starts).  All pointers are
+ * DEVICE memory borrowed from the handle, valid until the next
+ * mlip_build_graph on it or its destruction.
+ *
+ *   nodes[n_local]   local -> global atom id, laid out as
+ *                    PURE | BORDER | FROM[0] | FROM[1] | ... | FROM[P-1]
+ *                    (BORDER = owned atoms some other partition needs, stored
+ *                    once; every span in ascending global id)
+ *   markers[P+3]     HOST copy of the span starts: 0, |PURE|, |PURE|+|BORDER|
+ *                    (= n_owned), then the cumulative FROM lengths
+ *   row_ptr[n_local+1], senders[n_edges]
+ *                    receiver-sorted CSR over local rows with local sender ids.
+ *                    Rows [0, n_owned) are the owned atoms' complete rows (the
+ *                    edges this partition computes: an edge belongs to the
+ *                    partition of its receiving node, Distributing Atom Graphs);
+ *                    rows [n_owned, n_local) list, for each ghost atom, only its
+ *                    neighbours owned by this partition (used by the reverse
+ *                    pass to form the ghost rows' gradients without atomics).
+ *                    Order inside a row: ascending (global sender id, Sx, Sy, Sz).
+ */
+typedef struct {
+    int64_t n_owned, n_pure, n_border, n_ghost, n_local;
+    int64_t n_edges_owned; /* edges of rows [0, n_owned)  */
+    int64_t n_edges;       /* edges of all local rows     */
+    const int32_t *nodes;
+    const int64_t *markers; /* HOST */
+    const int64_t *row_ptr;
+    const int32_t *senders;
+    const int32_t *owned_sorted; /* the n_owned owned atoms, ascending global id */
+} mlip_slab_info_t;
+
+/*
+ * Build the periodic radius graph and its slab partition
+ * (neighbour-list construction, Graph-Parallel Message Passing; vertical-wall
+ * partition and PURE/TO/FROM buckets, Distributing Atom Graphs, Algs.
+ * "Atom Subgraph Creation" and "assign_to_partitions").
+ *
+ *   positions  DEVICE [n_atoms][3] fp64, Cartesian Angstrom, need not lie inside the cell
+ *   cell       HOST   [3][3] fp64, rows are the lattice vectors; full periodic boundaries
+ *   species    DEVICE [n_atoms] int32 in [0, n_species)
+ *   r_cut      edge iff 0 < d <= r_cut with
+ *                delta_k = (r_j,k - r_i,k) + ((Sx C[0][k] + Sy C[1][k]) + Sz C[2][k]),
+ *                d^2 = (delta_x^2 + delta_y^2) + delta_z^2 in fp64 without FMA contraction
+ *   n_slabs    P >= 1 equal-width slabs along the longest lattice vector (ties: lowest index);
+ *              slab(i) = min(floor(f P), P-1), f = fractional coordinate wrapped into [0,1),
+ *              computed as ((x n_x + y n_y) + z n_z) / V with n = a_{k+1} x a_{k+2}, V = a_k . n
+ *   stream     hipStream_t as void*
+ *   graph      in/out HOST: *graph == NULL creates a handle; a handle from an earlier call is
+ *              rebuilt in place and reuses its device buffers (grow-only)
+ *
+ * Edges are stored sorted by (receiver, sender, Sx, Sy, Sz).  The call synchronises the
+ * stream a few times (edge and partition sizes are needed on the host).
+ * Positions and species are copied into the handle.
+ */
+int mlip_build_graph(const double *positions, const double *cell, const int32_t *species,
+                     int64_t n_atoms, double r_cut, int32_t n_slabs, void *stream,
+                     mlip_graph_t **graph);
+
+/*
+ * Energy and forces (Methods: per-layer border-node transfer forward, the same
+ * transfers reversed for the gradients; appendix "Parallelizing a Model":
+ * distribute / atom_transfer / aggregate).
+ *
+ *   mode          MLIP_MODE_WHOLE: one partition holding every atom;
+ *                 MLIP_MODE_SLABS: the P slabs processed one after another, ghost rows
+ *                 refreshed from their owners before every layer's edge step, ghost-row
+ *                 gradients (features and positions) added back to the owners in the reverse pass
+ *   energy        DEVICE [1] fp64, sum of the per-atom energies of owned atoms
+ *   forces        DEVICE [n_atoms][3] fp32, F = -dE/dr, input atom order
+ *   atom_energy   DEVICE [n_atoms] fp32 or NULL
+ *
+ * Asynchronous on the graph's stream; does not modify the graph's topology (it uses
+ * workspace owned by the handle, so two forwards on one handle must not overlap).
+ */
+int mlip_forward(mlip_graph_t *graph, const mlip_weights_t *weights, int32_t mode,
+                 double *energy, float *forces, float *atom_energy);
+
+void mlip_graph_destroy(mlip_graph_t *graph);
+
+/* N atoms, E directed edges, P slabs, all HOST outputs (any may be NULL). */
+int mlip_graph_sizes(const mlip_graph_t *graph, int64_t *n_atoms, int64_t *n_edges, int32_t *n_slabs);
+
+/* Whole-graph CSR, borrowed DEVICE pointers: row_ptr[N+1], senders[E], d[E] (fp32 edge lengths). */
+int mlip_graph_csr(const mlip_graph_t *graph, const int64_t **row_ptr, const int32_t **senders,
+                   const float **d);
+
+/* Image shifts of all edges written to a caller-owned DEVICE buffer [E][3] int32 (enqueued on the stream). */
+int mlip_graph_shifts(const mlip_graph_t *graph, int32_t *shifts);
+
+/* slab_of[N] (DEVICE, borrowed) and the axis the walls are perpendicular to (HOST). */
+int mlip_graph_slab_of(const mlip_graph_t *graph, const int32_t **slab_of, int32_t *axis);
+
+/* Partition p's node array and local graph. */
+int mlip_graph_slab(const mlip_graph_t *graph, int32_t p, mlip_slab_info_t *info);
+
+/*
+ * FROM_p[q]: atoms partition p receives from partition q (ascending global ids), a span of p's
+ * node array.  TO_q[p] is by construction the same array (Distributing Atom Graphs), so
+ * mlip_graph_to(g, q, p, ...) returns the same pointer.  DEVICE, borrowed.
+ */
+int mlip_graph_from(const mlip_graph_t *graph, int32_t p, int32_t q, const int32_t **ids, int64_t *n);
+int mlip_graph_to(const mlip_graph_t *graph, int32_t p, int32_t q, const int32_t **ids, int64_t *n);
+
+/*
+ * Per-kernel-group timing with HIP events on the graph's stream.  While enabled, every launch
+ * group is bracketed by events; mlip_profile_read synchronises the stream and returns, for each of
+ * the MLIP_PROF_COUNT groups, the accumulated milliseconds and launch count since the last reset.
+ */
+enum {
+    MLIP_PROF_GRAPH = 0,   /* neighbour list, CSR, partition                 */
+    MLIP_PROF_NODE = 1,    /* embedding, node projections/updates, readout    */
+    MLIP_PROF_EDGE_FWD = 2,
+    MLIP_PROF_EDGE_BWD = 3,
+    MLIP_PROF_GHOST = 4,   /* ghost row copies and gradient add-backs         */
+    MLIP_PROF_FORCE = 5,   /* force assembly and energy reduction            */
+    MLIP_PROF_COUNT = 6
+};
+int mlip_profile_enable(mlip_graph_t *graph, int32_t on);
+int mlip_profile_read(mlip_graph_t *graph, float *ms /*HOST [MLIP_PROF_COUNT]*/,
+                      int64_t *launches /*HOST [MLIP_PROF_COUNT]*/, int32_t reset);
+
+/* Plain device -> host copy of `bytes` bytes after synchronising the graph's stream. */
+int mlip_copy_to_host(const mlip_graph_t *graph, void *dst_host, const void *src_device, size_t bytes);
+
+const char *mlip_last_error(void);
+const char *mlip_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MLIP_H */

@@ -1,0 +1,8 @@
+"""MI355X-native graph-partitioned inference of a radial message-passing interatomic potential.
+
+The compute path is the HIP library libmlip.so (csrc/, C ABI in include/mlip.h); this package is
+its thin ctypes binding.  There is no CPU or PyTorch fallback: importing the binding's functions
+and calling them without the built library raises ImportError.
+"""
+from .binding import (MODE_SLABS, MODE_WHOLE, Graph, MlipError, Weights, lib, mlip_build_graph,  # noqa: F401
+                      mlip_forward)

@@ -1,0 +1,201 @@
+"""ctypes binding of libmlip (argument marshalling only; every step runs in the HIP library).
+
+PyTorch supplies device memory (tensors) and the stream; nothing is computed here.
+The names mirror include/mlip.h.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libmlip.so")
+
+MODE_WHOLE, MODE_SLABS = 0, 1
+PROF_GROUPS = ("graph", "node", "edge_fwd", "edge_bwd", "ghost", "force")
+
+
+class MlipError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"libmlip error {code}: {msg}")
+        self.code = code
+
+
+class _Weights(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("n_species", "F", "L", "K", "p", "precision")] + \
+               [(n, ctypes.c_void_p) for n in ("emb", "W1", "W2", "Wm", "Wo", "Wr1", "wr2")]
+
+
+class _SlabInfo(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int64) for n in ("n_owned", "n_pure", "n_border", "n_ghost", "n_local",
+                                              "n_edges_owned", "n_edges")] + \
+               [(n, ctypes.c_void_p) for n in ("nodes", "markers", "row_ptr", "senders", "owned_sorted")]
+
+
+_lib = None
+
+
+def lib():
+    """Load libmlip.so; building it is `python -m paper_2506_02023_amd.build` (or __graft_entry__.build())."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError(f"{_LIB_PATH} is missing: the HIP library has not been built "
+                              "(run __graft_entry__.build()); there is no fallback path")
+        L = ctypes.CDLL(_LIB_PATH)
+        vp, i64, i32, dbl = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_double
+        L.mlip_build_graph.argtypes = [vp, ctypes.POINTER(dbl), vp, i64, dbl, i32, vp, ctypes.POINTER(vp)]
+        L.mlip_forward.argtypes = [vp, ctypes.POINTER(_Weights), i32, vp, vp, vp]
+        L.mlip_graph_destroy.argtypes = [vp]
+        L.mlip_graph_destroy.restype = None
+        L.mlip_graph_sizes.argtypes = [vp, ctypes.POINTER(i64), ctypes.POINTER(i64), ctypes.POINTER(i32)]
+        L.mlip_graph_csr.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp)]
+        L.mlip_graph_shifts.argtypes = [vp, vp]
+        L.mlip_graph_slab_of.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(i32)]
+        L.mlip_graph_slab.argtypes = [vp, i32, ctypes.POINTER(_SlabInfo)]
+        L.mlip_graph_from.argtypes = [vp, i32, i32, ctypes.POINTER(vp), ctypes.POINTER(i64)]
+        L.mlip_graph_to.argtypes = [vp, i32, i32, ctypes.POINTER(vp), ctypes.POINTER(i64)]
+        L.mlip_profile_enable.argtypes = [vp, i32]
+        L.mlip_profile_read.argtypes = [vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i64), i32]
+        L.mlip_copy_to_host.argtypes = [vp, vp, vp, ctypes.c_size_t]
+        L.mlip_last_error.restype = ctypes.c_char_p
+        L.mlip_version.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def _check(rc):
+    if rc != 0:
+        raise MlipError(rc, lib().mlip_last_error().decode())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+class Graph:
+    """Owner of a mlip_graph_t handle."""
+
+    def __init__(self):
+        self._h = ctypes.c_void_p(None)
+
+    def __del__(self):
+        self.destroy()
+
+    def destroy(self):
+        if getattr(self, "_h", None) is not None and self._h.value:
+            lib().mlip_graph_destroy(self._h)
+            self._h = ctypes.c_void_p(None)
+
+    # -- sizes and host copies of the index structures (for parity checks and inspection)
+    def sizes(self):
+        n, e, p = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int32()
+        _check(lib().mlip_graph_sizes(self._h, ctypes.byref(n), ctypes.byref(e), ctypes.byref(p)))
+        return n.value, e.value, p.value
+
+    def _host(self, ptr, count, dtype):
+        out = np.empty(count, dtype)
+        _check(lib().mlip_copy_to_host(self._h, out.ctypes.data_as(ctypes.c_void_p), ctypes.c_void_p(ptr),
+                                       out.nbytes))
+        return out
+
+    def csr(self):
+        """(row_ptr int64 [N+1], senders int32 [E], shifts int32 [E,3], d float32 [E]) as numpy arrays."""
+        N, E, _ = self.sizes()
+        rp, sd, dd = ctypes.c_void_p(), ctypes.c_void_p(), ctypes.c_void_p()
+        _check(lib().mlip_graph_csr(self._h, ctypes.byref(rp), ctypes.byref(sd), ctypes.byref(dd)))
+        shifts = torch.empty((max(E, 1), 3), dtype=torch.int32, device="cuda")
+        _check(lib().mlip_graph_shifts(self._h, ctypes.c_void_p(shifts.data_ptr())))
+        torch.cuda.synchronize()
+        return (self._host(rp.value, N + 1, np.int64), self._host(sd.value, E, np.int32),
+                shifts[:E].cpu().numpy(), self._host(dd.value, E, np.float32))
+
+    def slab_of(self):
+        N, _, _ = self.sizes()
+        ptr, ax = ctypes.c_void_p(), ctypes.c_int32()
+        _check(lib().mlip_graph_slab_of(self._h, ctypes.byref(ptr), ctypes.byref(ax)))
+        return self._host(ptr.value, N, np.int32), ax.value
+
+    def slab(self, p):
+        """dict with the counts, nodes, markers, local row_ptr/senders and owned_sorted of partition p."""
+        _, _, P = self.sizes()
+        info = _SlabInfo()
+        _check(lib().mlip_graph_slab(self._h, p, ctypes.byref(info)))
+        d = {k: getattr(info, k) for k in ("n_owned", "n_pure", "n_border", "n_ghost", "n_local",
+                                           "n_edges_owned", "n_edges")}
+        d["nodes"] = self._host(info.nodes, d["n_local"], np.int32)
+        d["markers"] = np.ctypeslib.as_array(ctypes.cast(info.markers, ctypes.POINTER(ctypes.c_int64)),
+                                             shape=(P + 3,)).copy()
+        d["row_ptr"] = self._host(info.row_ptr, d["n_local"] + 1, np.int64)
+        d["senders"] = self._host(info.senders, d["n_edges"], np.int32)
+        d["owned_sorted"] = self._host(info.owned_sorted, d["n_owned"], np.int32)
+        return d
+
+    def _bucket(self, fn, p, q):
+        ptr, n = ctypes.c_void_p(), ctypes.c_int64()
+        _check(fn(self._h, p, q, ctypes.byref(ptr), ctypes.byref(n)))
+        return self._host(ptr.value, n.value, np.int32), ptr.value
+
+    def frm(self, p, q):
+        return self._bucket(lib().mlip_graph_from, p, q)[0]
+
+    def to(self, p, q):
+        return self._bucket(lib().mlip_graph_to, p, q)[0]
+
+    def bucket_address(self, kind, p, q):
+        return self._bucket(lib().mlip_graph_from if kind == "from" else lib().mlip_graph_to, p, q)[1]
+
+    # -- profiling
+    def profile_enable(self, on=True):
+        _check(lib().mlip_profile_enable(self._h, 1 if on else 0))
+
+    def profile_read(self, reset=True):
+        ms = (ctypes.c_float * len(PROF_GROUPS))()
+        n = (ctypes.c_int64 * len(PROF_GROUPS))()
+        _check(lib().mlip_profile_read(self._h, ms, n, 1 if reset else 0))
+        return {k: (ms[i], n[i]) for i, k in enumerate(PROF_GROUPS)}
+
+
+def mlip_build_graph(positions, cell, species, r_cut, n_slabs=1, graph=None):
+    """positions: cuda float64 [N,3]; cell: 3x3 host array (rows = lattice vectors); species: cuda int32 [N]."""
+    assert positions.is_cuda and positions.dtype == torch.float64 and positions.is_contiguous()
+    assert species.is_cuda and species.dtype == torch.int32 and species.is_contiguous()
+    assert positions.dim() == 2 and positions.shape[1] == 3 and species.numel() == positions.shape[0]
+    cell_h = np.ascontiguousarray(np.asarray(cell, dtype=np.float64).reshape(9))
+    g = graph if graph is not None else Graph()
+    _check(lib().mlip_build_graph(ctypes.c_void_p(positions.data_ptr()),
+                                  cell_h.ctypes.data_as(ctypes.POINTER(ctypes.c_double)),
+                                  ctypes.c_void_p(species.data_ptr()), positions.shape[0], float(r_cut),
+                                  int(n_slabs), _stream(), ctypes.byref(g._h)))
+    return g
+
+
+class Weights:
+    """Device copies of the model weights plus the POD struct the library takes."""
+
+    def __init__(self, weights, p, K=8, device="cuda"):
+        self.t = {k: torch.as_tensor(np.ascontiguousarray(v, np.float32)).to(device).contiguous()
+                  for k, v in weights.items()}
+        S, F = self.t["emb"].shape
+        L = self.t["W1"].shape[0]
+        self.F, self.L = F, L
+        self.c = _Weights(S, F, L, K, p, 0, *[self.t[k].data_ptr() for k in
+                                               ("emb", "W1", "W2", "Wm", "Wo", "Wr1", "wr2")])
+
+
+def mlip_forward(graph, weights, mode=MODE_WHOLE, out=None, want_atom_energy=True):
+    """Returns (energy cuda f64 [1], forces cuda f32 [N,3], atom_energy cuda f32 [N] or None); asynchronous."""
+    N, _, _ = graph.sizes()
+    if out is None:
+        energy = torch.empty(1, dtype=torch.float64, device="cuda")
+        forces = torch.empty((N, 3), dtype=torch.float32, device="cuda")
+        atom_e = torch.empty(N, dtype=torch.float32, device="cuda") if want_atom_energy else None
+    else:
+        energy, forces, atom_e = out
+    _check(lib().mlip_forward(graph._h, ctypes.byref(weights.c), int(mode), ctypes.c_void_p(energy.data_ptr()),
+                              ctypes.c_void_p(forces.data_ptr()),
+                              ctypes.c_void_p(atom_e.data_ptr() if atom_e is not None else None)))
+    return energy, forces, atom_e

@@ -1,0 +1,291 @@
+// C ABI of libmlip: argument checks, handle lifetime, error text, event profiler.
+#include "mlip_internal.h"
+
+#include <cstring>
+#include <new>
+
+namespace mlip {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+int DevBuf::ensure(size_t bytes)
+{
+    if (bytes <= cap) return MLIP_OK;
+    // grow with slack so that a slowly growing system does not reallocate every step
+    size_t want = bytes + bytes / 8 + 256;
+    void *np = nullptr;
+    hipError_t e = hipMalloc(&np, want);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        want = bytes;
+        e = hipMalloc(&np, want);
+    }
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        set_error("device allocation of %zu bytes failed: %s", bytes, hipGetErrorString(e));
+        return MLIP_ENOMEM;
+    }
+    if (p) (void)hipFree(p);  // hipFree synchronises, so no kernel still reads the old block
+    p = np;
+    cap = want;
+    return MLIP_OK;
+}
+
+void DevBuf::release()
+{
+    if (p) (void)hipFree(p);
+    p = nullptr;
+    cap = 0;
+}
+
+// ---- profiler: event pairs around launch groups --------------------------
+
+void prof_begin(mlip_graph *g, int group)
+{
+    Profiler &pr = g->prof;
+    if (!pr.on) return;
+    if (pr.used + 2 > pr.pool.size()) {
+        if (pr.pool.size() >= (size_t)kMaxEvents) return;  // stop recording, keep running
+        hipEvent_t a, b;
+        if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) return;
+        pr.pool.push_back(a);
+        pr.pool.push_back(b);
+        pr.group.push_back(group);
+    }
+    pr.group[pr.used / 2] = group;
+    (void)hipEventRecord(pr.pool[pr.used], g->stream);
+    pr.used += 1;
+}
+
+void prof_end(mlip_graph *g)
+{
+    Profiler &pr = g->prof;
+    if (!pr.on || (pr.used & 1) == 0) return;
+    (void)hipEventRecord(pr.pool[pr.used], g->stream);
+    pr.used += 1;
+}
+
+static int prof_collect(mlip_graph *g)
+{
+    Profiler &pr = g->prof;
+    if (pr.used & 1) {  // a begin without its end (error path): close it
+        (void)hipEventRecord(pr.pool[pr.used], g->stream);
+        pr.used += 1;
+    }
+    MLIP_HIP(hipStreamSynchronize(g->stream));
+    for (size_t k = 0; k + 1 < pr.used; k += 2) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, pr.pool[k], pr.pool[k + 1]) == hipSuccess) {
+            pr.ms[pr.group[k / 2]] += ms;
+            pr.launches[pr.group[k / 2]] += 1;
+        }
+    }
+    pr.used = 0;
+    return MLIP_OK;
+}
+
+}  // namespace mlip
+
+using namespace mlip;
+
+extern "C" {
+
+const char *mlip_last_error(void) { return g_err; }
+const char *mlip_version(void) { return "libmlip 0.1 (gfx950)"; }
+
+int mlip_build_graph(const double *positions, const double *cell, const int32_t *species, int64_t n_atoms,
+                     double r_cut, int32_t n_slabs, void *stream, mlip_graph_t **graph)
+{
+    if (!positions || !cell || !species || !graph) { set_error("null pointer argument"); return MLIP_EINVAL; }
+    if (n_atoms <= 0 || n_atoms > (int64_t)0x7fffff00) { set_error("n_atoms must be in [1, 2^31)"); return MLIP_EINVAL; }
+    if (!(r_cut > 0.0) || !(r_cut < 1e6)) { set_error("r_cut must be positive and finite"); return MLIP_EINVAL; }
+    if (n_slabs < 1 || n_slabs > kMaxSlabs) { set_error("n_slabs must be in [1, %d]", (int)kMaxSlabs); return MLIP_EINVAL; }
+    mlip_graph *g = *graph;
+    const bool fresh = (g == nullptr);
+    if (fresh) {
+        g = new (std::nothrow) mlip_graph();
+        if (!g) { set_error("host allocation failed"); return MLIP_ENOMEM; }
+    }
+    g->stream = static_cast<hipStream_t>(stream);
+    if (g->prof.on && g->prof.used + 64 > (size_t)kMaxEvents) (void)prof_collect(g);
+    int rc = MLIP_EHIP;
+    try {
+        rc = build_graph_impl(g, positions, cell, species, n_atoms, r_cut, n_slabs);
+    } catch (const std::exception &e) {
+        set_error("host exception: %s", e.what());
+        rc = MLIP_ENOMEM;
+    }
+    if (rc != MLIP_OK) {
+        if (fresh) mlip_graph_destroy(g);
+        return rc;
+    }
+    *graph = g;
+    return MLIP_OK;
+}
+
+int mlip_forward(mlip_graph_t *g, const mlip_weights_t *w, int32_t mode, double *energy, float *forces,
+                 float *atom_energy)
+{
+    if (!g || !w || !energy || !forces) { set_error("null pointer argument"); return MLIP_EINVAL; }
+    if (g->N <= 0) { set_error("graph handle holds no graph"); return MLIP_ESTATE; }
+    if (!w->emb || !w->Wr1 || !w->wr2 || (w->L > 0 && (!w->W1 || !w->W2 || !w->Wm || !w->Wo))) {
+        set_error("null weight pointer");
+        return MLIP_EINVAL;
+    }
+    if (!(w->F == 32 || w->F == 64) || w->K != 8 || w->L < 0 || w->L > 8 || w->p < 2 || w->p > 64 ||
+        w->n_species < 1 || w->precision != MLIP_PRECISION_FP32) {
+        set_error("unsupported model dimensions (need F in {32,64}, K = 8, 0 <= L <= 8, 2 <= p <= 64, fp32)");
+        return MLIP_EINVAL;
+    }
+    if (g->species_min < 0 || g->species_max >= w->n_species) {
+        set_error("species outside [0, n_species)");
+        return MLIP_EINVAL;
+    }
+    if (mode != MLIP_MODE_WHOLE && mode != MLIP_MODE_SLABS) { set_error("unknown mode"); return MLIP_EINVAL; }
+    if (mode == MLIP_MODE_SLABS && g->P < 2) {
+        set_error("SLABS mode needs a graph built with n_slabs >= 2");
+        return MLIP_ESTATE;
+    }
+    if (g->prof.on && g->prof.used + 1024 > (size_t)kMaxEvents) (void)prof_collect(g);
+    try {
+        return forward_impl(g, w, mode, energy, forces, atom_energy);
+    } catch (const std::exception &e) {
+        set_error("host exception: %s", e.what());
+        return MLIP_ENOMEM;
+    }
+}
+
+void mlip_graph_destroy(mlip_graph_t *g)
+{
+    if (!g) return;
+    (void)hipStreamSynchronize(g->stream);
+    DevBuf *bufs[] = {&g->pos, &g->species, &g->cell_of, &g->wrapp, &g->cell_cnt, &g->cell_start, &g->cell_fill,
+                      &g->sid, &g->sx, &g->sy, &g->sz, &g->swrap, &g->counts, &g->keys, &g->flags, &g->scan_tmp,
+                      &g->small, &g->row_ptr, &g->senders, &g->shiftp, &g->d, &g->slab_of, &g->needed_by,
+                      &g->local_of, &g->local_in_owner, &g->class_cnt, &g->class_off, &g->wpack, &g->energy_part};
+    for (DevBuf *b : bufs) b->release();
+    auto drop_view = [](SlabView &v) {
+        DevBuf *vb[] = {&v.h, &v.hbar, &v.abar, &v.gbar, &v.eps, &v.dsum, &v.floc, &v.g, &v.a};
+        for (DevBuf *b : vb) b->release();
+    };
+    drop_view(g->whole);
+    for (auto &v : g->slabs) drop_view(v);
+    for (auto &st : g->store) {
+        DevBuf *sb[] = {&st.nodes, &st.row_ptr, &st.senders, &st.shiftp, &st.d, &st.ghost_owner, &st.ghost_src,
+                        &st.owned_sorted, &st.rowlen};
+        for (DevBuf *b : sb) b->release();
+    }
+    for (hipEvent_t e : g->prof.pool) (void)hipEventDestroy(e);
+    if (g->pinned) (void)hipHostFree(g->pinned);
+    delete g;
+}
+
+int mlip_graph_sizes(const mlip_graph_t *g, int64_t *n_atoms, int64_t *n_edges, int32_t *n_slabs)
+{
+    if (!g) { set_error("null graph"); return MLIP_EINVAL; }
+    if (n_atoms) *n_atoms = g->N;
+    if (n_edges) *n_edges = g->E;
+    if (n_slabs) *n_slabs = g->P;
+    return MLIP_OK;
+}
+
+int mlip_graph_csr(const mlip_graph_t *g, const int64_t **row_ptr, const int32_t **senders, const float **d)
+{
+    if (!g || g->N <= 0) { set_error("no graph"); return MLIP_ESTATE; }
+    if (row_ptr) *row_ptr = g->row_ptr.as<int64_t>();
+    if (senders) *senders = g->senders.as<int32_t>();
+    if (d) *d = g->d.as<float>();
+    return MLIP_OK;
+}
+
+int mlip_graph_shifts(const mlip_graph_t *g, int32_t *shifts)
+{
+    if (!g || g->N <= 0) { set_error("no graph"); return MLIP_ESTATE; }
+    if (!shifts) { set_error("null pointer argument"); return MLIP_EINVAL; }
+    return unpack_shifts(g, shifts);
+}
+
+int mlip_graph_slab_of(const mlip_graph_t *g, const int32_t **slab_of, int32_t *axis)
+{
+    if (!g || g->N <= 0) { set_error("no graph"); return MLIP_ESTATE; }
+    if (slab_of) *slab_of = g->slab_of.as<int32_t>();
+    if (axis) *axis = g->cell.axis;
+    return MLIP_OK;
+}
+
+int mlip_graph_slab(const mlip_graph_t *g, int32_t p, mlip_slab_info_t *info)
+{
+    if (!g || g->N <= 0) { set_error("no graph"); return MLIP_ESTATE; }
+    if (!info) { set_error("null pointer argument"); return MLIP_EINVAL; }
+    if (g->P < 2) { set_error("graph was built with n_slabs = 1"); return MLIP_ESTATE; }
+    if (p < 0 || p >= g->P) { set_error("slab index out of range"); return MLIP_EINVAL; }
+    const SlabView &v = g->slabs[p];
+    info->n_owned = v.n_owned;
+    info->n_pure = v.n_pure;
+    info->n_border = v.n_border;
+    info->n_ghost = v.n_ghost;
+    info->n_local = v.n_local;
+    info->n_edges_owned = v.n_edges_owned;
+    info->n_edges = v.n_edges;
+    info->nodes = v.nodes;
+    info->markers = v.markers.data();
+    info->row_ptr = v.row_ptr;
+    info->senders = v.senders;
+    info->owned_sorted = g->store[p].owned_sorted.as<int32_t>();
+    return MLIP_OK;
+}
+
+int mlip_graph_from(const mlip_graph_t *g, int32_t p, int32_t q, const int32_t **ids, int64_t *n)
+{
+    if (!g || g->N <= 0) { set_error("no graph"); return MLIP_ESTATE; }
+    if (!ids || !n) { set_error("null pointer argument"); return MLIP_EINVAL; }
+    if (g->P < 2) { set_error("graph was built with n_slabs = 1"); return MLIP_ESTATE; }
+    if (p < 0 || p >= g->P || q < 0 || q >= g->P) { set_error("slab index out of range"); return MLIP_EINVAL; }
+    const SlabView &v = g->slabs[p];
+    *ids = v.nodes + v.markers[2 + q];
+    *n = v.markers[3 + q] - v.markers[2 + q];
+    return MLIP_OK;
+}
+
+int mlip_graph_to(const mlip_graph_t *g, int32_t p, int32_t q, const int32_t **ids, int64_t *n)
+{
+    return mlip_graph_from(g, q, p, ids, n);
+}
+
+int mlip_profile_enable(mlip_graph_t *g, int32_t on)
+{
+    if (!g) { set_error("null graph"); return MLIP_EINVAL; }
+    if (!on && g->prof.on) MLIP_TRY(prof_collect(g));
+    g->prof.on = on != 0;
+    return MLIP_OK;
+}
+
+int mlip_profile_read(mlip_graph_t *g, float *ms, int64_t *launches, int32_t reset)
+{
+    if (!g) { set_error("null graph"); return MLIP_EINVAL; }
+    MLIP_TRY(prof_collect(g));
+    for (int k = 0; k < MLIP_PROF_COUNT; ++k) {
+        if (ms) ms[k] = g->prof.ms[k];
+        if (launches) launches[k] = g->prof.launches[k];
+        if (reset) { g->prof.ms[k] = 0.f; g->prof.launches[k] = 0; }
+    }
+    return MLIP_OK;
+}
+
+int mlip_copy_to_host(const mlip_graph_t *g, void *dst_host, const void *src_device, size_t bytes)
+{
+    if (!g || !dst_host || (!src_device && bytes)) { set_error("null pointer argument"); return MLIP_EINVAL; }
+    MLIP_HIP(hipStreamSynchronize(g->stream));
+    if (bytes) MLIP_HIP(hipMemcpy(dst_host, src_device, bytes, hipMemcpyDeviceToHost));
+    return MLIP_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,751 @@
+// Periodic radius graph, canonical receiver-sorted CSR and slab partition on gfx950.
+//
+// Neighbour-list construction (Methods, Graph-Parallel Message Passing): a cell
+// list in fractional space with explicit image shifts.  Partition: vertical
+// walls along the longest lattice vector and PURE / TO / FROM buckets
+// (Distributing Atom Graphs; Algs. "Atom Subgraph Creation" and
+// "assign_to_partitions").  All integer results have exactly one correct value
+// (canonical order), so they can be compared bit for bit.
+//
+// This file is compiled with -ffp-contract=off: the edge predicate and the slab
+// rule are fixed fp64 expressions whose operation order is part of the interface.
+#include "mlip_internal.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+
+namespace mlip {
+
+namespace {
+
+constexpr int kBias = 512;
+
+__host__ __device__ inline uint32_t pack3(int a, int b, int c)
+{
+    return ((uint32_t)(a + kBias) << 20) | ((uint32_t)(b + kBias) << 10) | (uint32_t)(c + kBias);
+}
+__host__ __device__ inline void unpack3(uint32_t p, int &a, int &b, int &c)
+{
+    a = (int)(p >> 20) - kBias;
+    b = (int)((p >> 10) & 1023u) - kBias;
+    c = (int)(p & 1023u) - kBias;
+}
+
+__device__ inline int floordiv(int a, int b)
+{
+    int q = a / b;
+    if ((a % b != 0) && ((a < 0) != (b < 0))) --q;
+    return q;
+}
+
+enum { ERR_RANGE = 1, ERR_COINCIDENT = 2 };
+
+// ---------------------------------------------------------------- scans
+
+template <class T> __device__ inline T wave_inclusive_scan(T v)
+{
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        T n = __shfl_up(v, off, 64);
+        if (lane >= off) v += n;
+    }
+    return v;
+}
+
+constexpr int kScanThreads = 256;
+constexpr int kScanItems = 4;
+constexpr int kScanTile = kScanThreads * kScanItems;
+
+// exclusive scan of one tile held as kScanItems per thread; returns the tile total
+template <class T> __device__ inline T block_exclusive_scan(T (&v)[kScanItems], T *lds /*[4]*/)
+{
+    T sum = 0;
+#pragma unroll
+    for (int k = 0; k < kScanItems; ++k) sum += v[k];
+    T inc = wave_inclusive_scan(sum);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (lane == 63) lds[wave] = inc;
+    __syncthreads();
+    T base = 0, total = 0;
+#pragma unroll
+    for (int w = 0; w < kScanThreads / 64; ++w) {
+        T s = lds[w];
+        if (w < wave) base += s;
+        total += s;
+    }
+    T run = base + inc - sum;
+#pragma unroll
+    for (int k = 0; k < kScanItems; ++k) {
+        T x = v[k];
+        v[k] = run;
+        run += x;
+    }
+    __syncthreads();
+    return total;
+}
+
+template <class Tin, class Tout>
+__global__ void k_tile_sums(const Tin *in, Tout *sums, int64_t n)
+{
+    __shared__ Tout lds[kScanThreads / 64];
+    const int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kScanItems;
+    Tout v[kScanItems];
+#pragma unroll
+    for (int k = 0; k < kScanItems; ++k) v[k] = (base + k < n) ? (Tout)in[base + k] : (Tout)0;
+    Tout total = block_exclusive_scan(v, lds);
+    if (threadIdx.x == 0) sums[blockIdx.x] = total;
+}
+
+// out[i] = offsets[tile] + exclusive prefix inside the tile; the last tile also writes out[n]
+template <class Tin, class Tout>
+__global__ void k_tile_scan(const Tin *in, const Tout *offsets, Tout *out, int64_t n)
+{
+    __shared__ Tout lds[kScanThreads / 64];
+    const int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kScanItems;
+    Tout v[kScanItems];
+#pragma unroll
+    for (int k = 0; k < kScanItems; ++k) v[k] = (base + k < n) ? (Tout)in[base + k] : (Tout)0;
+    Tout total = block_exclusive_scan(v, lds);
+    const Tout off = offsets ? offsets[blockIdx.x] : (Tout)0;
+#pragma unroll
+    for (int k = 0; k < kScanItems; ++k)
+        if (base + k < n) out[base + k] = off + v[k];
+    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) out[n] = off + total;
+}
+
+template <class Tin, class Tout>
+int scan_impl(const Tin *in, Tout *out, int64_t n, char *tmp, size_t tmp_bytes, hipStream_t s)
+{
+    if (n <= 0) {
+        if (n == 0) MLIP_HIP(hipMemsetAsync(out, 0, sizeof(Tout), s));
+        return MLIP_OK;
+    }
+    const int64_t tiles = (n + kScanTile - 1) / kScanTile;
+    if (tiles == 1) {
+        k_tile_scan<Tin, Tout><<<1, kScanThreads, 0, s>>>(in, nullptr, out, n);
+        MLIP_HIP(hipGetLastError());
+        return MLIP_OK;
+    }
+    // layout of tmp: sums[tiles] | offsets[tiles + 1] | rest for the recursion
+    const size_t need = (size_t)(2 * tiles + 1) * sizeof(Tout);
+    if (tmp_bytes < need) { set_error("scan scratch too small"); return MLIP_EINVAL; }
+    Tout *sums = reinterpret_cast<Tout *>(tmp);
+    Tout *offs = sums + tiles;
+    k_tile_sums<Tin, Tout><<<(unsigned)tiles, kScanThreads, 0, s>>>(in, sums, n);
+    MLIP_HIP(hipGetLastError());
+    MLIP_TRY((scan_impl<Tout, Tout>(sums, offs, tiles, tmp + need, tmp_bytes - need, s)));
+    k_tile_scan<Tin, Tout><<<(unsigned)tiles, kScanThreads, 0, s>>>(in, offs, out, n);
+    MLIP_HIP(hipGetLastError());
+    return MLIP_OK;
+}
+
+size_t scan_scratch_bytes(int64_t n)
+{
+    size_t total = 0;
+    while (n > kScanTile) {
+        int64_t tiles = (n + kScanTile - 1) / kScanTile;
+        total += (size_t)(2 * tiles + 1) * sizeof(int64_t);
+        n = tiles;
+    }
+    return total + 256;
+}
+
+}  // namespace
+
+int scan_i32_to_i64(const int32_t *in, int64_t *out, int64_t n, DevBuf &tmp, hipStream_t s)
+{
+    MLIP_TRY(tmp.ensure(scan_scratch_bytes(n)));
+    return scan_impl<int32_t, int64_t>(in, out, n, tmp.as<char>(), tmp.cap, s);
+}
+
+int scan_i32_to_i32(const int32_t *in, int32_t *out, int64_t n, DevBuf &tmp, hipStream_t s)
+{
+    MLIP_TRY(tmp.ensure(scan_scratch_bytes(n)));
+    return scan_impl<int32_t, int32_t>(in, out, n, tmp.as<char>(), tmp.cap, s);
+}
+
+namespace {
+
+// ---------------------------------------------------------------- binning
+
+__device__ inline double frac_k(const double *r, const double *n, double V)
+{
+    return ((r[0] * n[0] + r[1] * n[1]) + r[2] * n[2]) / V;
+}
+
+// err[0] = flag bits, err[1] = max species seen, err[2] = min species seen
+__global__ void k_bin(int64_t N, const double *__restrict__ pos, const int32_t *__restrict__ species,
+                      CellParams cp, int32_t *cell_of, uint32_t *wrapp, int32_t *slab_of, int32_t *cell_cnt,
+                      int32_t *err)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    {   // species range, one atomic pair per wavefront
+        int zmax = i < N ? species[i] : 0, zmin = zmax;
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            zmax = max(zmax, __shfl_xor(zmax, off, 64));
+            zmin = min(zmin, __shfl_xor(zmin, off, 64));
+        }
+        if ((threadIdx.x & 63) == 0) {
+            if (zmax > 0) atomicMax(err + 1, zmax);
+            if (zmin < 0) atomicMin(err + 2, zmin);
+        }
+    }
+    if (i >= N) return;
+    const double r[3] = {pos[3 * i], pos[3 * i + 1], pos[3 * i + 2]};
+    int b[3], w[3];
+    int slab = 0;
+    bool bad = false;
+#pragma unroll
+    for (int k = 0; k < 3; ++k) {
+        double f = frac_k(r, cp.nrm[k], cp.V);
+        double fl = floor(f);
+        if (!(fabs(fl) <= 200.0)) { bad = true; fl = 0.0; f = 0.0; }
+        w[k] = (int)fl;
+        double fr = f - fl;
+        int bk = (int)floor(fr * (double)cp.nb[k]);
+        bk = bk > cp.nb[k] - 1 ? cp.nb[k] - 1 : bk;
+        b[k] = bk < 0 ? 0 : bk;
+        if (k == cp.axis) {
+            int s = (int)floor(fr * (double)cp.n_slabs);
+            s = s > cp.n_slabs - 1 ? cp.n_slabs - 1 : s;
+            slab = s < 0 ? 0 : s;
+        }
+    }
+    if (bad) atomicOr(err, ERR_RANGE);
+    const int32_t c = (b[0] * cp.nb[1] + b[1]) * cp.nb[2] + b[2];
+    cell_of[i] = c;
+    wrapp[i] = pack3(w[0], w[1], w[2]);
+    slab_of[i] = slab;
+    atomicAdd(&cell_cnt[c], 1);
+}
+
+__global__ void k_fill_cells(int64_t N, const double *__restrict__ pos, const int32_t *__restrict__ cell_of,
+                             const uint32_t *__restrict__ wrapp, const int32_t *__restrict__ cell_start,
+                             int32_t *cell_fill, int32_t *sid, double *sx, double *sy, double *sz,
+                             uint32_t *swrap)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= N) return;
+    const int32_t c = cell_of[i];
+    const int32_t slot = cell_start[c] + atomicAdd(&cell_fill[c], 1);
+    sid[slot] = (int32_t)i;
+    sx[slot] = pos[3 * i];
+    sy[slot] = pos[3 * i + 1];
+    sz[slot] = pos[3 * i + 2];
+    swrap[slot] = wrapp[i];
+}
+
+// One thread per atom, atoms taken in cell order so that a wavefront walks the
+// same candidate cells.  FILL = false counts, FILL = true writes unsorted keys
+// (sender << 32 | packed shift) into the atom's row.
+template <bool FILL>
+__global__ void k_neighbours(int64_t N, CellParams cp, const int32_t *__restrict__ cell_start,
+                             const int32_t *__restrict__ sid, const double *__restrict__ sx,
+                             const double *__restrict__ sy, const double *__restrict__ sz,
+                             const uint32_t *__restrict__ swrap, const int32_t *__restrict__ cell_of,
+                             int32_t *counts, const int64_t *__restrict__ row_ptr, uint64_t *keys, int32_t *err)
+{
+    const int64_t s = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (s >= N) return;
+    const int32_t i = sid[s];
+    const double xi = sx[s], yi = sy[s], zi = sz[s];
+    int wi0, wi1, wi2;
+    unpack3(swrap[s], wi0, wi1, wi2);
+    int c = cell_of[i];
+    const int b2 = c % cp.nb[2];
+    c /= cp.nb[2];
+    const int b1 = c % cp.nb[1];
+    const int b0 = c / cp.nb[1];
+    int64_t base = 0, cap = 0;
+    if (FILL) { base = row_ptr[i]; cap = row_ptr[i + 1] - base; }
+    int32_t cnt = 0;
+    bool coincident = false;
+    for (int dx = -cp.reach[0]; dx <= cp.reach[0]; ++dx) {
+        int c0 = b0 + dx;
+        const int i0 = floordiv(c0, cp.nb[0]);
+        c0 -= i0 * cp.nb[0];
+        for (int dy = -cp.reach[1]; dy <= cp.reach[1]; ++dy) {
+            int c1 = b1 + dy;
+            const int i1 = floordiv(c1, cp.nb[1]);
+            c1 -= i1 * cp.nb[1];
+            for (int dz = -cp.reach[2]; dz <= cp.reach[2]; ++dz) {
+                int c2 = b2 + dz;
+                const int i2 = floordiv(c2, cp.nb[2]);
+                c2 -= i2 * cp.nb[2];
+                const int32_t cc = (c0 * cp.nb[1] + c1) * cp.nb[2] + c2;
+                const int32_t qe = cell_start[cc + 1];
+                for (int32_t q = cell_start[cc]; q < qe; ++q) {
+                    const int32_t j = sid[q];
+                    int wj0, wj1, wj2;
+                    unpack3(swrap[q], wj0, wj1, wj2);
+                    const int S0 = i0 - wj0 + wi0, S1 = i1 - wj1 + wi1, S2 = i2 - wj2 + wi2;
+                    if (j == i && S0 == 0 && S1 == 0 && S2 == 0) continue;
+                    const double t0 = (sx[q] - xi) + (((double)S0 * cp.C[0] + (double)S1 * cp.C[3]) + (double)S2 * cp.C[6]);
+                    const double t1 = (sy[q] - yi) + (((double)S0 * cp.C[1] + (double)S1 * cp.C[4]) + (double)S2 * cp.C[7]);
+                    const double t2 = (sz[q] - zi) + (((double)S0 * cp.C[2] + (double)S1 * cp.C[5]) + (double)S2 * cp.C[8]);
+                    const double d2 = (t0 * t0 + t1 * t1) + t2 * t2;
+                    if (d2 <= cp.rc2) {
+                        if (d2 == 0.0) coincident = true;
+                        if (FILL && cnt < cap) keys[base + cnt] = ((uint64_t)(uint32_t)j << 32) | pack3(S0, S1, S2);
+                        ++cnt;
+                    }
+                }
+            }
+        }
+    }
+    if (!FILL) counts[i] = cnt;
+    if (coincident) atomicOr(err, ERR_COINCIDENT);
+}
+
+// One wavefront per row: rank sort of the row's (sender, shift) keys (unique,
+// so ranks form a permutation), then the edge length in fp64 rounded to fp32.
+constexpr int kRowLds = 512;
+__global__ void __launch_bounds__(64)
+k_sort_rows(int64_t N, CellParams cp, const double *__restrict__ pos, const int64_t *__restrict__ row_ptr,
+            const uint64_t *__restrict__ keys, int32_t *senders, uint32_t *shiftp, float *d)
+{
+    __shared__ uint64_t lds[kRowLds];
+    const int64_t i = blockIdx.x;
+    const int lane = threadIdx.x;
+    const int64_t base = row_ptr[i];
+    const int64_t n = row_ptr[i + 1] - base;
+    const bool staged = n <= kRowLds;
+    if (staged)
+        for (int64_t m = lane; m < n; m += 64) lds[m] = keys[base + m];
+    __syncthreads();
+    const double xi = pos[3 * i], yi = pos[3 * i + 1], zi = pos[3 * i + 2];
+    for (int64_t m = lane; m < n; m += 64) {
+        const uint64_t key = staged ? lds[m] : keys[base + m];
+        int64_t rank = 0;
+        if (staged) {
+            for (int64_t t = 0; t < n; ++t) rank += (lds[t] < key) ? 1 : 0;
+        } else {
+            for (int64_t t = 0; t < n; ++t) rank += (keys[base + t] < key) ? 1 : 0;
+        }
+        const int64_t e = base + rank;
+        const int32_t j = (int32_t)(key >> 32);
+        const uint32_t sp = (uint32_t)key;
+        int S0, S1, S2;
+        unpack3(sp, S0, S1, S2);
+        const double t0 = (pos[3 * (int64_t)j] - xi) + (((double)S0 * cp.C[0] + (double)S1 * cp.C[3]) + (double)S2 * cp.C[6]);
+        const double t1 = (pos[3 * (int64_t)j + 1] - yi) + (((double)S0 * cp.C[1] + (double)S1 * cp.C[4]) + (double)S2 * cp.C[7]);
+        const double t2 = (pos[3 * (int64_t)j + 2] - zi) + (((double)S0 * cp.C[2] + (double)S1 * cp.C[5]) + (double)S2 * cp.C[8]);
+        const double d2 = (t0 * t0 + t1 * t1) + t2 * t2;
+        senders[e] = j;
+        shiftp[e] = sp;
+        d[e] = (float)sqrt(d2);
+    }
+}
+
+__global__ void k_unpack_shifts(int64_t E, const uint32_t *__restrict__ shiftp, int32_t *out)
+{
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= E) return;
+    int a, b, c;
+    unpack3(shiftp[e], a, b, c);
+    out[3 * e] = a;
+    out[3 * e + 1] = b;
+    out[3 * e + 2] = c;
+}
+
+// ---------------------------------------------------------------- partition
+
+// needed_by[j] gets bit q when some atom owned by slab q != slab(j) receives from j
+__global__ void __launch_bounds__(64)
+k_needed_by(int64_t N, const int64_t *__restrict__ row_ptr, const int32_t *__restrict__ senders,
+            const int32_t *__restrict__ slab_of, unsigned long long *needed_by)
+{
+    const int64_t i = blockIdx.x;
+    const int si = slab_of[i];
+    const int64_t e1 = row_ptr[i + 1];
+    for (int64_t e = row_ptr[i] + threadIdx.x; e < e1; e += 64) {
+        const int32_t j = senders[e];
+        if (slab_of[j] != si) atomicOr(&needed_by[j], 1ull << si);
+    }
+}
+
+// class of atom u relative to partition q: 0 PURE, 1 BORDER, 2 + s ghost owned by slab s, -1 absent
+__device__ inline int node_class(int s, unsigned long long nb, int q)
+{
+    if (s == q) return nb == 0ull ? 0 : 1;
+    return ((nb >> q) & 1ull) ? 2 + s : -1;
+}
+
+// per wavefront of 64 consecutive atoms: how many fall in each class; class ncls is "owned"
+__global__ void __launch_bounds__(64)
+k_class_count(int64_t N, const int32_t *__restrict__ slab_of, const unsigned long long *__restrict__ needed_by,
+              int q, int ncls, int64_t nwaves, int32_t *cnt)
+{
+    const int64_t w = blockIdx.x;
+    const int64_t u = w * 64 + threadIdx.x;
+    const int cls = u < N ? node_class(slab_of[u], needed_by[u], q) : -1;
+    for (int c = 0; c < ncls; ++c) {
+        const unsigned long long m = __ballot(cls == c);
+        if (threadIdx.x == 0) cnt[(int64_t)c * nwaves + w] = __popcll(m);
+    }
+    const unsigned long long mo = __ballot(cls == 0 || cls == 1);
+    if (threadIdx.x == 0) cnt[(int64_t)ncls * nwaves + w] = __popcll(mo);
+}
+
+__global__ void __launch_bounds__(64)
+k_class_scatter(int64_t N, const int32_t *__restrict__ slab_of, const unsigned long long *__restrict__ needed_by,
+                int q, int ncls, int64_t nwaves, const int32_t *__restrict__ off, int32_t *nodes,
+                int32_t *owned_sorted, int32_t *local_of, int32_t *local_in_owner)
+{
+    const int64_t w = blockIdx.x;
+    const int64_t u = w * 64 + threadIdx.x;
+    const int cls = u < N ? node_class(slab_of[u], needed_by[u], q) : -1;
+    const unsigned long long lt = (1ull << threadIdx.x) - 1ull;
+    for (int c = 0; c < ncls; ++c) {
+        const unsigned long long m = __ballot(cls == c);
+        if (cls == c) {
+            const int32_t p = off[(int64_t)c * nwaves + w] + __popcll(m & lt);
+            nodes[p] = (int32_t)u;
+            local_of[u] = p;
+            if (c < 2) local_in_owner[u] = p;
+        }
+    }
+    const bool own = (cls == 0 || cls == 1);
+    const unsigned long long mo = __ballot(own);
+    if (own) {
+        const int32_t base_owned = off[(int64_t)ncls * nwaves];  // start of the "owned" pseudo class
+        owned_sorted[off[(int64_t)ncls * nwaves + w] - base_owned + __popcll(mo & lt)] = (int32_t)u;
+    }
+}
+
+__global__ void k_gather_markers(const int32_t *__restrict__ off, int ncls, int64_t nwaves, int64_t *out)
+{
+    const int c = threadIdx.x;
+    if (c <= ncls) out[c] = off[(int64_t)c * nwaves];  // out[ncls] = start of the "owned" class = n_local
+}
+
+// length of each local row: owned rows keep their whole global row, ghost rows
+// keep only the senders owned by partition q
+__global__ void __launch_bounds__(64)
+k_local_rowlen(int64_t n_local, int64_t n_owned, const int32_t *__restrict__ nodes,
+               const int64_t *__restrict__ row_ptr, const int32_t *__restrict__ senders,
+               const int32_t *__restrict__ slab_of, int q, int32_t *rowlen)
+{
+    const int64_t r = blockIdx.x;
+    const int32_t u = nodes[r];
+    const int64_t e0 = row_ptr[u], e1 = row_ptr[u + 1];
+    if (r < n_owned) {
+        if (threadIdx.x == 0) rowlen[r] = (int32_t)(e1 - e0);
+        return;
+    }
+    int cnt = 0;
+    for (int64_t eb = e0; eb < e1; eb += 64) {
+        const int64_t e = eb + threadIdx.x;
+        const bool keep = e < e1 && slab_of[senders[e]] == q;
+        cnt += __popcll(__ballot(keep));
+    }
+    if (threadIdx.x == 0) rowlen[r] = cnt;
+}
+
+__global__ void __launch_bounds__(64)
+k_local_fill(int64_t n_local, int64_t n_owned, const int32_t *__restrict__ nodes,
+             const int64_t *__restrict__ row_ptr, const int32_t *__restrict__ senders,
+             const uint32_t *__restrict__ shiftp, const float *__restrict__ d,
+             const int32_t *__restrict__ slab_of, const int32_t *__restrict__ local_of, int q,
+             const int64_t *__restrict__ lrow_ptr, int32_t *lsenders, uint32_t *lshiftp, float *ld)
+{
+    const int64_t r = blockIdx.x;
+    const int32_t u = nodes[r];
+    const int64_t e0 = row_ptr[u], e1 = row_ptr[u + 1];
+    int64_t out = lrow_ptr[r];
+    const int64_t out_end = lrow_ptr[r + 1];
+    const bool all = r < n_owned;
+    const unsigned long long lt = (1ull << threadIdx.x) - 1ull;
+    for (int64_t eb = e0; eb < e1; eb += 64) {
+        const int64_t e = eb + threadIdx.x;
+        int32_t j = 0;
+        bool keep = false;
+        if (e < e1) {
+            j = senders[e];
+            keep = all || slab_of[j] == q;
+        }
+        const unsigned long long m = __ballot(keep);
+        if (keep) {
+            const int64_t o = out + __popcll(m & lt);
+            if (o < out_end) {
+                lsenders[o] = local_of[j];
+                lshiftp[o] = shiftp[e];
+                ld[o] = d[e];
+            }
+        }
+        out += __popcll(m);
+    }
+}
+
+__global__ void k_ghost_src(int64_t n_ghost, const int32_t *__restrict__ ghost_nodes,
+                            const int32_t *__restrict__ slab_of, const int32_t *__restrict__ local_in_owner,
+                            int32_t *ghost_owner, int32_t *ghost_src)
+{
+    const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= n_ghost) return;
+    const int32_t u = ghost_nodes[k];
+    ghost_owner[k] = slab_of[u];
+    ghost_src[k] = local_in_owner[u];
+}
+
+inline unsigned blocks_for(int64_t n, int threads) { return (unsigned)((n + threads - 1) / threads); }
+
+void cross3(const double *a, const double *b, double *o)
+{
+    o[0] = a[1] * b[2] - a[2] * b[1];
+    o[1] = a[2] * b[0] - a[0] * b[2];
+    o[2] = a[0] * b[1] - a[1] * b[0];
+}
+
+int prepare_cell(const double *C, double r_cut, int32_t n_slabs, int64_t N, CellParams &cp)
+{
+    for (int k = 0; k < 9; ++k) {
+        if (!std::isfinite(C[k])) { set_error("cell has a non-finite entry"); return MLIP_ECELL; }
+        cp.C[k] = C[k];
+    }
+    cross3(C + 3, C + 6, cp.nrm[0]);
+    cross3(C + 6, C + 0, cp.nrm[1]);
+    cross3(C + 0, C + 3, cp.nrm[2]);
+    cp.V = (C[0] * cp.nrm[0][0] + C[1] * cp.nrm[0][1]) + C[2] * cp.nrm[0][2];
+    if (!(std::fabs(cp.V) > 0.0) || !std::isfinite(cp.V)) { set_error("singular cell (volume 0)"); return MLIP_ECELL; }
+    cp.rc2 = r_cut * r_cut;
+    const double rpad = r_cut * 1.000001 + 1e-12;
+    double h[3];
+    for (int k = 0; k < 3; ++k) {
+        const double l = std::sqrt(cp.nrm[k][0] * cp.nrm[k][0] + cp.nrm[k][1] * cp.nrm[k][1] + cp.nrm[k][2] * cp.nrm[k][2]);
+        h[k] = std::fabs(cp.V) / l;
+        int n = (int)std::floor(h[k] / rpad);
+        cp.nb[k] = std::max(1, std::min(n, 1024));
+    }
+    // keep the number of bins comparable to the number of atoms for sparse systems
+    const double max_cells = std::max<double>(4096.0, 8.0 * (double)N);
+    while ((double)cp.nb[0] * cp.nb[1] * cp.nb[2] > max_cells) {
+        int k = 0;
+        for (int m = 1; m < 3; ++m) if (cp.nb[m] > cp.nb[k]) k = m;
+        cp.nb[k] = std::max(1, cp.nb[k] / 2);
+    }
+    for (int k = 0; k < 3; ++k) {
+        cp.reach[k] = (int)std::ceil(rpad / (h[k] / cp.nb[k]));
+        if (cp.reach[k] > 100) { set_error("cell is thinner than r_cut / 100 along lattice direction %d", k); return MLIP_ECELL; }
+    }
+    int ax = 0;
+    double best = -1.0;
+    for (int k = 0; k < 3; ++k) {
+        const double l2 = (C[3 * k] * C[3 * k] + C[3 * k + 1] * C[3 * k + 1]) + C[3 * k + 2] * C[3 * k + 2];
+        if (l2 > best) { best = l2; ax = k; }
+    }
+    cp.axis = ax;
+    cp.n_slabs = n_slabs;
+    return MLIP_OK;
+}
+
+}  // namespace
+
+int unpack_shifts(const mlip_graph *g, int32_t *out)
+{
+    if (g->E > 0) {
+        k_unpack_shifts<<<blocks_for(g->E, 256), 256, 0, g->stream>>>(g->E, g->shiftp.as<uint32_t>(), out);
+        MLIP_HIP(hipGetLastError());
+    }
+    return MLIP_OK;
+}
+
+int build_graph_impl(mlip_graph *g, const double *positions, const double *cell, const int32_t *species,
+                     int64_t N, double r_cut, int32_t P)
+{
+    hipStream_t s = g->stream;
+    CellParams cp;
+    MLIP_TRY(prepare_cell(cell, r_cut, P, N, cp));
+    g->cell = cp;
+    g->N = 0;  // the handle is invalid until the build completes
+    g->E = 0;
+    const int64_t ncell = (int64_t)cp.nb[0] * cp.nb[1] * cp.nb[2];
+    if (!g->pinned) MLIP_HIP(hipHostMalloc(&g->pinned, 4096, hipHostMallocDefault));
+
+    MLIP_TRY(g->pos.ensure((size_t)N * 3 * sizeof(double)));
+    MLIP_TRY(g->species.ensure((size_t)N * sizeof(int32_t)));
+    MLIP_HIP(hipMemcpyAsync(g->pos.p, positions, (size_t)N * 3 * sizeof(double), hipMemcpyDeviceToDevice, s));
+    MLIP_HIP(hipMemcpyAsync(g->species.p, species, (size_t)N * sizeof(int32_t), hipMemcpyDeviceToDevice, s));
+
+    MLIP_TRY(g->cell_of.ensure((size_t)N * 4));
+    MLIP_TRY(g->wrapp.ensure((size_t)N * 4));
+    MLIP_TRY(g->slab_of.ensure((size_t)N * 4));
+    MLIP_TRY(g->cell_cnt.ensure((size_t)(ncell + 1) * 4));
+    MLIP_TRY(g->cell_fill.ensure((size_t)(ncell + 1) * 4));
+    MLIP_TRY(g->cell_start.ensure((size_t)(ncell + 2) * 4));
+    MLIP_TRY(g->sid.ensure((size_t)N * 4));
+    MLIP_TRY(g->swrap.ensure((size_t)N * 4));
+    MLIP_TRY(g->sx.ensure((size_t)N * 8));
+    MLIP_TRY(g->sy.ensure((size_t)N * 8));
+    MLIP_TRY(g->sz.ensure((size_t)N * 8));
+    MLIP_TRY(g->counts.ensure((size_t)(N + 1) * 4));
+    MLIP_TRY(g->row_ptr.ensure((size_t)(N + 1) * 8));
+    MLIP_TRY(g->small.ensure(4096));
+    int32_t *err = g->small.as<int32_t>();
+
+    prof_begin(g, MLIP_PROF_GRAPH);
+    MLIP_HIP(hipMemsetAsync(g->small.p, 0, 4096, s));
+    MLIP_HIP(hipMemsetAsync(g->cell_cnt.p, 0, (size_t)(ncell + 1) * 4, s));
+    MLIP_HIP(hipMemsetAsync(g->cell_fill.p, 0, (size_t)(ncell + 1) * 4, s));
+    const double *pos = g->pos.as<double>();
+    k_bin<<<blocks_for(N, 256), 256, 0, s>>>(N, pos, g->species.as<int32_t>(), cp, g->cell_of.as<int32_t>(),
+                                             g->wrapp.as<uint32_t>(), g->slab_of.as<int32_t>(),
+                                             g->cell_cnt.as<int32_t>(), err);
+    MLIP_HIP(hipGetLastError());
+    MLIP_TRY(scan_i32_to_i32(g->cell_cnt.as<int32_t>(), g->cell_start.as<int32_t>(), ncell, g->scan_tmp, s));
+    k_fill_cells<<<blocks_for(N, 256), 256, 0, s>>>(N, pos, g->cell_of.as<int32_t>(), g->wrapp.as<uint32_t>(),
+                                                    g->cell_start.as<int32_t>(), g->cell_fill.as<int32_t>(),
+                                                    g->sid.as<int32_t>(), g->sx.as<double>(), g->sy.as<double>(),
+                                                    g->sz.as<double>(), g->swrap.as<uint32_t>());
+    MLIP_HIP(hipGetLastError());
+    k_neighbours<false><<<blocks_for(N, 128), 128, 0, s>>>(
+        N, cp, g->cell_start.as<int32_t>(), g->sid.as<int32_t>(), g->sx.as<double>(), g->sy.as<double>(),
+        g->sz.as<double>(), g->swrap.as<uint32_t>(), g->cell_of.as<int32_t>(), g->counts.as<int32_t>(), nullptr,
+        nullptr, err);
+    MLIP_HIP(hipGetLastError());
+    MLIP_TRY(scan_i32_to_i64(g->counts.as<int32_t>(), g->row_ptr.as<int64_t>(), N, g->scan_tmp, s));
+    // host needs E and the error flags
+    int64_t *hp = static_cast<int64_t *>(g->pinned);
+    MLIP_HIP(hipMemcpyAsync(hp, g->row_ptr.as<int64_t>() + N, 8, hipMemcpyDeviceToHost, s));
+    MLIP_HIP(hipMemcpyAsync(hp + 1, err, 12, hipMemcpyDeviceToHost, s));
+    MLIP_HIP(hipStreamSynchronize(s));
+    const int64_t E = hp[0];
+    const int32_t *herr = reinterpret_cast<int32_t *>(hp + 1);
+    const int32_t flags = herr[0];
+    g->species_max = herr[1];
+    g->species_min = herr[2];
+    if (flags & ERR_RANGE) {
+        prof_end(g);
+        set_error("an atom lies more than 200 cells away from the origin cell (or has a non-finite coordinate)");
+        return MLIP_ECELL;
+    }
+    if (flags & ERR_COINCIDENT) {
+        prof_end(g);
+        set_error("two atoms (or an atom and one of its images) coincide");
+        return MLIP_ECOINCIDENT;
+    }
+    const size_t Ecap = (size_t)std::max<int64_t>(E, 1);
+    MLIP_TRY(g->keys.ensure(Ecap * 8));
+    MLIP_TRY(g->senders.ensure(Ecap * 4));
+    MLIP_TRY(g->shiftp.ensure(Ecap * 4));
+    MLIP_TRY(g->d.ensure(Ecap * 4));
+    k_neighbours<true><<<blocks_for(N, 128), 128, 0, s>>>(
+        N, cp, g->cell_start.as<int32_t>(), g->sid.as<int32_t>(), g->sx.as<double>(), g->sy.as<double>(),
+        g->sz.as<double>(), g->swrap.as<uint32_t>(), g->cell_of.as<int32_t>(), nullptr, g->row_ptr.as<int64_t>(),
+        g->keys.as<uint64_t>(), err);
+    MLIP_HIP(hipGetLastError());
+    k_sort_rows<<<(unsigned)N, 64, 0, s>>>(N, cp, pos, g->row_ptr.as<int64_t>(), g->keys.as<uint64_t>(),
+                                           g->senders.as<int32_t>(), g->shiftp.as<uint32_t>(), g->d.as<float>());
+    MLIP_HIP(hipGetLastError());
+
+    SlabView &W = g->whole;
+    W.n_owned = W.n_pure = W.n_local = N;
+    W.n_border = W.n_ghost = 0;
+    W.n_edges = W.n_edges_owned = E;
+    W.nodes = nullptr;
+    W.row_ptr = g->row_ptr.as<int64_t>();
+    W.senders = g->senders.as<int32_t>();
+    W.shiftp = g->shiftp.as<uint32_t>();
+    W.d = g->d.as<float>();
+    W.markers = {0, N, N, N};
+
+    // ------------------------------------------------------------ partition
+    if (P > 1) {
+        if (g->store.size() < (size_t)P) g->store.resize(P);
+        if (g->slabs.size() < (size_t)P) g->slabs.resize(P);  // never shrunk: views own workspace
+        MLIP_TRY(g->needed_by.ensure((size_t)N * 8));
+        MLIP_TRY(g->local_of.ensure((size_t)N * 4));
+        MLIP_TRY(g->local_in_owner.ensure((size_t)N * 4));
+        MLIP_HIP(hipMemsetAsync(g->needed_by.p, 0, (size_t)N * 8, s));
+        k_needed_by<<<(unsigned)N, 64, 0, s>>>(N, g->row_ptr.as<int64_t>(), g->senders.as<int32_t>(),
+                                               g->slab_of.as<int32_t>(), g->needed_by.as<unsigned long long>());
+        MLIP_HIP(hipGetLastError());
+        const int ncls = P + 2;
+        const int64_t nwaves = (N + 63) / 64;
+        const int64_t nent = (int64_t)(ncls + 1) * nwaves;
+        MLIP_TRY(g->class_cnt.ensure((size_t)nent * 4));
+        MLIP_TRY(g->class_off.ensure((size_t)(nent + 1) * 4));
+        for (int q = 0; q < P; ++q) {
+            SlabStore &st = g->store[q];
+            SlabView &v = g->slabs[q];
+            k_class_count<<<(unsigned)nwaves, 64, 0, s>>>(N, g->slab_of.as<int32_t>(),
+                                                          g->needed_by.as<unsigned long long>(), q, ncls, nwaves,
+                                                          g->class_cnt.as<int32_t>());
+            MLIP_HIP(hipGetLastError());
+            MLIP_TRY(scan_i32_to_i32(g->class_cnt.as<int32_t>(), g->class_off.as<int32_t>(), nent, g->scan_tmp, s));
+            int64_t *mk = g->small.as<int64_t>() + 16;
+            k_gather_markers<<<1, 128, 0, s>>>(g->class_off.as<int32_t>(), ncls, nwaves, mk);
+            MLIP_HIP(hipGetLastError());
+            MLIP_HIP(hipMemcpyAsync(hp, mk, (size_t)(ncls + 1) * 8, hipMemcpyDeviceToHost, s));
+            MLIP_HIP(hipStreamSynchronize(s));
+            v.markers.assign(hp, hp + ncls + 1);  // P + 3 entries
+            v.n_pure = hp[1];
+            v.n_owned = hp[2];
+            v.n_border = v.n_owned - v.n_pure;
+            v.n_local = hp[ncls];
+            v.n_ghost = v.n_local - v.n_owned;
+            const size_t nl = (size_t)std::max<int64_t>(v.n_local, 1);
+            MLIP_TRY(st.nodes.ensure(nl * 4));
+            MLIP_TRY(st.owned_sorted.ensure((size_t)std::max<int64_t>(v.n_owned, 1) * 4));
+            MLIP_TRY(st.rowlen.ensure((nl + 1) * 4));
+            MLIP_TRY(st.row_ptr.ensure((nl + 1) * 8));
+            MLIP_TRY(st.ghost_owner.ensure((size_t)std::max<int64_t>(v.n_ghost, 1) * 4));
+            MLIP_TRY(st.ghost_src.ensure((size_t)std::max<int64_t>(v.n_ghost, 1) * 4));
+            k_class_scatter<<<(unsigned)nwaves, 64, 0, s>>>(
+                N, g->slab_of.as<int32_t>(), g->needed_by.as<unsigned long long>(), q, ncls, nwaves,
+                g->class_off.as<int32_t>(), st.nodes.as<int32_t>(), st.owned_sorted.as<int32_t>(),
+                g->local_of.as<int32_t>(), g->local_in_owner.as<int32_t>());
+            MLIP_HIP(hipGetLastError());
+            if (v.n_local > 0) {
+                k_local_rowlen<<<(unsigned)v.n_local, 64, 0, s>>>(v.n_local, v.n_owned, st.nodes.as<int32_t>(),
+                                                                  g->row_ptr.as<int64_t>(), g->senders.as<int32_t>(),
+                                                                  g->slab_of.as<int32_t>(), q, st.rowlen.as<int32_t>());
+                MLIP_HIP(hipGetLastError());
+            }
+            MLIP_TRY(scan_i32_to_i64(st.rowlen.as<int32_t>(), st.row_ptr.as<int64_t>(), v.n_local, g->scan_tmp, s));
+            MLIP_HIP(hipMemcpyAsync(hp, st.row_ptr.as<int64_t>() + v.n_owned, 8, hipMemcpyDeviceToHost, s));
+            MLIP_HIP(hipMemcpyAsync(hp + 1, st.row_ptr.as<int64_t>() + v.n_local, 8, hipMemcpyDeviceToHost, s));
+            MLIP_HIP(hipStreamSynchronize(s));
+            v.n_edges_owned = hp[0];
+            v.n_edges = hp[1];
+            const size_t ne = (size_t)std::max<int64_t>(v.n_edges, 1);
+            MLIP_TRY(st.senders.ensure(ne * 4));
+            MLIP_TRY(st.shiftp.ensure(ne * 4));
+            MLIP_TRY(st.d.ensure(ne * 4));
+            if (v.n_local > 0) {
+                k_local_fill<<<(unsigned)v.n_local, 64, 0, s>>>(
+                    v.n_local, v.n_owned, st.nodes.as<int32_t>(), g->row_ptr.as<int64_t>(), g->senders.as<int32_t>(),
+                    g->shiftp.as<uint32_t>(), g->d.as<float>(), g->slab_of.as<int32_t>(), g->local_of.as<int32_t>(), q,
+                    st.row_ptr.as<int64_t>(), st.senders.as<int32_t>(), st.shiftp.as<uint32_t>(), st.d.as<float>());
+                MLIP_HIP(hipGetLastError());
+            }
+            v.nodes = st.nodes.as<int32_t>();
+            v.row_ptr = st.row_ptr.as<int64_t>();
+            v.senders = st.senders.as<int32_t>();
+            v.shiftp = st.shiftp.as<uint32_t>();
+            v.d = st.d.as<float>();
+            v.ghost_owner = st.ghost_owner.as<int32_t>();
+            v.ghost_src = st.ghost_src.as<int32_t>();
+        }
+        for (int q = 0; q < P; ++q) {
+            SlabView &v = g->slabs[q];
+            if (v.n_ghost > 0) {
+                k_ghost_src<<<blocks_for(v.n_ghost, 256), 256, 0, s>>>(
+                    v.n_ghost, v.nodes + v.n_owned, g->slab_of.as<int32_t>(), g->local_in_owner.as<int32_t>(),
+                    g->store[q].ghost_owner.as<int32_t>(), g->store[q].ghost_src.as<int32_t>());
+                MLIP_HIP(hipGetLastError());
+            }
+        }
+    }
+    prof_end(g);
+    g->N = N;
+    g->E = E;
+    g->P = P;
+    g->r_cut = r_cut;
+    return MLIP_OK;
+}
+
+}  // namespace mlip

@@ -1,0 +1,127 @@
+// Internal declarations shared by the translation units of libmlip.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+#include <vector>
+
+#include "mlip.h"
+
+namespace mlip {
+
+void set_error(const char *fmt, ...);
+
+#define MLIP_HIP(expr)                                                                      \
+    do {                                                                                    \
+        hipError_t e_ = (expr);                                                             \
+        if (e_ != hipSuccess) {                                                             \
+            mlip::set_error("%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_), __FILE__, __LINE__); \
+            return (e_ == hipErrorOutOfMemory) ? MLIP_ENOMEM : MLIP_EHIP;                   \
+        }                                                                                   \
+    } while (0)
+
+#define MLIP_TRY(expr)            \
+    do {                          \
+        int rc_ = (expr);         \
+        if (rc_ != MLIP_OK) return rc_; \
+    } while (0)
+
+// Grow-only device buffer owned by a graph handle.
+struct DevBuf {
+    void *p = nullptr;
+    size_t cap = 0;
+    int ensure(size_t bytes);
+    void release();
+    template <class T> T *as() const { return static_cast<T *>(p); }
+};
+
+// Cell geometry prepared on the host, passed to kernels by value.
+struct CellParams {
+    double C[9];       // rows = lattice vectors
+    double nrm[3][3];  // n_k = a_{k+1} x a_{k+2}
+    double V;          // a_0 . n_0
+    double rc2;        // r_cut * r_cut
+    int nb[3];         // bins per lattice direction
+    int reach[3];      // stencil half-width in bins
+    int axis;          // slab axis
+    int n_slabs;
+};
+
+// One partition as the model kernels see it.  The whole graph is the special
+// case nodes == nullptr (identity), n_owned == n_local == N.
+struct SlabView {
+    int64_t n_owned = 0, n_pure = 0, n_border = 0, n_ghost = 0, n_local = 0;
+    int64_t n_edges_owned = 0, n_edges = 0;
+    const int32_t *nodes = nullptr;        // local -> global (nullptr: identity)
+    const int64_t *row_ptr = nullptr;      // n_local + 1
+    const int32_t *senders = nullptr;      // local ids
+    const uint32_t *shiftp = nullptr;      // packed image shifts
+    const float *d = nullptr;              // edge lengths
+    const int32_t *ghost_owner = nullptr;  // [n_ghost] owning slab
+    const int32_t *ghost_src = nullptr;    // [n_ghost] local index inside the owner
+    std::vector<int64_t> markers;          // host, P + 3
+    // model workspace (sized in mlip_forward)
+    DevBuf h, hbar, abar, gbar, eps, dsum, floc, g, a;  // g and a hold L slices each
+};
+
+struct SlabStore {  // device arrays owned per slab
+    DevBuf nodes, row_ptr, senders, shiftp, d, ghost_owner, ghost_src, owned_sorted, rowlen;
+};
+
+enum { kMaxSlabs = 64, kMaxEvents = 4096 };
+
+struct Profiler {
+    bool on = false;
+    std::vector<hipEvent_t> pool;  // pairs
+    std::vector<int> group;        // group of pair k
+    size_t used = 0;               // events used
+    float ms[MLIP_PROF_COUNT] = {0};
+    int64_t launches[MLIP_PROF_COUNT] = {0};
+};
+
+}  // namespace mlip
+
+struct mlip_graph {
+    hipStream_t stream = nullptr;
+    int64_t N = 0, E = 0;
+    int32_t P = 1;
+    int32_t species_max = 0, species_min = 0;
+    double r_cut = 0;
+    mlip::CellParams cell;
+    // inputs copied in
+    mlip::DevBuf pos, species;
+    // build scratch
+    mlip::DevBuf cell_of, wrapp, cell_cnt, cell_start, cell_fill, sid, sx, sy, sz, swrap, counts, keys, flags,
+        scan_tmp, small;
+    // whole-graph CSR
+    mlip::DevBuf row_ptr, senders, shiftp, d;
+    // partition
+    mlip::DevBuf slab_of, needed_by, local_of, local_in_owner, class_cnt, class_off;
+    std::vector<mlip::SlabStore> store;
+    std::vector<mlip::SlabView> slabs;  // P views (empty when P == 1)
+    mlip::SlabView whole;
+    // forward scratch shared by all views
+    mlip::DevBuf wpack, energy_part;
+    mlip::Profiler prof;
+    void *pinned = nullptr;  // small pinned host staging area
+};
+
+namespace mlip {
+
+// device-wide exclusive scans (n + 1 outputs, out[n] = total); tmp is grown as needed
+int scan_i32_to_i64(const int32_t *in, int64_t *out, int64_t n, DevBuf &tmp, hipStream_t s);
+int scan_i32_to_i32(const int32_t *in, int32_t *out, int64_t n, DevBuf &tmp, hipStream_t s);
+
+void prof_begin(mlip_graph *g, int group);
+void prof_end(mlip_graph *g);
+
+int build_graph_impl(mlip_graph *g, const double *positions, const double *cell, const int32_t *species,
+                     int64_t n_atoms, double r_cut, int32_t n_slabs);
+int forward_impl(mlip_graph *g, const mlip_weights_t *w, int32_t mode, double *energy, float *forces,
+                 float *atom_energy);
+int unpack_shifts(const mlip_graph *g, int32_t *out);
+
+}  // namespace mlip

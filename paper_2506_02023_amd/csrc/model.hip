@@ -1,0 +1,1032 @@
+// Radial message-passing potential on gfx950: forward, hand-written reverse pass, forces.
+//
+// Model (benchmark configuration 0):  h0 = Emb[z];  per layer  g = h Wm,
+//   a_i = sum_{e: recv=i} (SiLU(b_e W1) W2) * g_send(e),  h += SiLU(a Wo);
+//   eps_i = SiLU(h Wr1) . wr2,  E = sum eps,  F = -dE/dr.
+// Partitioned execution follows the paper's scheme (Graph-Parallel Message
+// Passing; Distributing Atom Graphs): every partition computes the edges whose
+// receiver it owns, ghost rows of g are refreshed from their owners before each
+// layer's edge step and ghost-row gradients are added back to the owners in the
+// reverse pass.
+//
+// Kernel design
+//  * All dense contractions (filter MLP per edge, F x F maps per node) run on
+//    v_mfma_f32_32x32x2_f32 with items (edges or nodes) as the 32 MFMA columns
+//    and features as rows.  In that orientation the accumulator layout of one
+//    product is directly the B operand of the next one if the contraction index
+//    is visited in the order the accumulator registers hold it; the weight (A)
+//    operands are pre-packed in that order, so chained products need no
+//    transposition or lane exchange.
+//  * The per-receiver reduction is LDS-staged: a 32-edge tile of filter outputs
+//    is written to LDS edge-major, then each lane owns one feature, reads the
+//    tile row by row, multiplies with the gathered sender row (one coalesced
+//    256-byte load per edge) and keeps a running sum that is flushed when the
+//    receiver changes.  No atomics; the summation order is the canonical edge order.
+//  * Reverse pass without scatter: the edge set is symmetric (i<-j,S) <-> (j<-i,-S)
+//    with bitwise equal length, hence equal filter value w.  So
+//      gbar_i = sum_{e in row i} w_e * abar_send(e)
+//      dE/dd summed over an edge and its mirror = dw/dd . (abar_i*g_j + abar_j*g_i)
+//    are both receiver-side gathers.  In a partition, abar of ghost rows is zero
+//    and ghost rows carry the sub-row of neighbours owned by the partition, which
+//    yields exactly the ghost-row gradients the owner must receive.
+#include "mlip_internal.h"
+
+#include <algorithm>
+#include <cmath>
+
+namespace mlip {
+
+namespace {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kChunkEdges = 1024;  // edges per wavefront work item (32 tiles of 32)
+constexpr float kPi = 3.14159265358979323846f;
+
+__device__ inline void wave_lds_fence()
+{
+    // LDS operations of one wavefront execute in program order; this only stops the
+    // compiler from moving them across the point where lanes exchange roles.
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+__device__ inline float sigmoidf_fast(float x) { return __builtin_amdgcn_rcpf(1.0f + __expf(-x)); }
+
+struct BasisParams {
+    float rc, inv_rc, c0, c1, c2, pc0, pc1, pc2;  // envelope coefficients and those of its derivative
+    int p;
+};
+
+// b[n] = sin((n+1) pi x) / d * u(x) and, if DERIV, db[n] = d b[n] / d d   (n = 0..7)
+template <bool DERIV>
+__device__ inline void radial_basis(float d, const BasisParams &bp, float (&b)[8], float (&db)[8])
+{
+    float x = fminf(d * bp.inv_rc, 1.0f);
+    float s1, c1v;
+    sincospif(x, &s1, &c1v);
+    float xpm1 = 1.0f;
+    for (int k = 0; k < bp.p - 1; ++k) xpm1 *= x;
+    const float xp = xpm1 * x;
+    const float u = 1.0f - xp * (bp.c0 - x * (bp.c1 - bp.c2 * x));
+    const float inv_d = 1.0f / d;
+    float du_term = 0.f;  // u'/rc - u/d
+    if (DERIV) {
+        const float du = -xpm1 * (bp.pc0 - x * (bp.pc1 - bp.pc2 * x));
+        du_term = du * bp.inv_rc - u * inv_d;
+    }
+    float sn = s1, cn = c1v;
+#pragma unroll
+    for (int n = 0; n < 8; ++n) {
+        b[n] = sn * u * inv_d;
+        if (DERIV) db[n] = ((float)(n + 1) * kPi * bp.inv_rc * cn * u + sn * du_term) * inv_d;
+        const float s2 = sn * c1v + cn * s1;
+        cn = cn * c1v - sn * s1;
+        sn = s2;
+    }
+}
+
+// ---------------------------------------------------------------- packed weights
+//
+// pack_ff: F x F matrix M[o][k] as MFMA A operands, index
+//   ((((bo * NB + bi) * 4 + a) * 64 + lane) * 4 + c)  ->  M[32 bo + lane % 32][32 bi + 8 a + 4 (lane / 32) + c]
+// with M[o][k] = W[k][o] (TRANS, y = x W) or W[o][k] (y = x W^T).
+// pack_w1: K = 8 rows, index ((bo * 4 + s) * 64 + lane) -> W1[2 s + lane / 32][32 bo + lane % 32].
+
+__global__ void k_pack_ff(const float *__restrict__ W, int F, int trans, float *__restrict__ out)
+{
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= F * F) return;
+    const int NB = F / 32;
+    const int c = idx & 3, lane = (idx >> 2) & 63, a = (idx >> 8) & 3, bb = idx >> 10;
+    const int bi = bb % NB, bo = bb / NB;
+    const int o = 32 * bo + (lane & 31);
+    const int k = 32 * bi + 8 * a + 4 * (lane >> 5) + c;
+    out[idx] = trans ? W[k * F + o] : W[o * F + k];
+}
+
+__global__ void k_pack_w1(const float *__restrict__ W1, int F, float *__restrict__ out)
+{
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    const int NB = F / 32;
+    if (idx >= NB * 4 * 64) return;
+    const int lane = idx & 63, s = (idx >> 6) & 3, bo = idx >> 8;
+    out[idx] = W1[(2 * s + (lane >> 5)) * F + 32 * bo + (lane & 31)];
+}
+
+template <int F> struct Dims {
+    static constexpr int NB = F / 32;
+    static constexpr int FS = F + 4;      // LDS row stride of an item-major tile
+    static constexpr int TILE = 32 * FS;  // floats per 32-item tile
+    static constexpr int PACK1 = NB * 4 * 64;
+    static constexpr int PACKF = F * F;
+};
+
+// out[bo] = sum_k M[.][k] in[k][.], `in` held in accumulator layout (chained product)
+template <int F>
+__device__ inline void gemm_regs(const float *__restrict__ Ap, const f32x16 (&in)[Dims<F>::NB],
+                                 f32x16 (&out)[Dims<F>::NB], int lane)
+{
+    constexpr int NB = Dims<F>::NB;
+#pragma unroll
+    for (int bo = 0; bo < NB; ++bo)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) out[bo][r] = 0.f;
+#pragma unroll
+    for (int bi = 0; bi < NB; ++bi)
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+            for (int bo = 0; bo < NB; ++bo) {
+                const f32x4 av = *reinterpret_cast<const f32x4 *>(Ap + ((((bo * NB + bi) * 4 + a) * 64 + lane) * 4));
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    out[bo] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[c], in[bi][4 * a + c], out[bo], 0, 0, 0);
+            }
+}
+
+// same product with the B operand read from an item-major LDS tile [32][FS]
+template <int F>
+__device__ inline void gemm_lds(const float *__restrict__ Ap, const float *tile, f32x16 (&out)[Dims<F>::NB], int lane)
+{
+    constexpr int NB = Dims<F>::NB;
+    constexpr int FS = Dims<F>::FS;
+    const int c32 = lane & 31, h = lane >> 5;
+#pragma unroll
+    for (int bo = 0; bo < NB; ++bo)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) out[bo][r] = 0.f;
+#pragma unroll
+    for (int bi = 0; bi < NB; ++bi)
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+            const f32x4 bv = *reinterpret_cast<const f32x4 *>(tile + c32 * FS + 32 * bi + 8 * a + 4 * h);
+#pragma unroll
+            for (int bo = 0; bo < NB; ++bo) {
+                const f32x4 av = *reinterpret_cast<const f32x4 *>(Ap + ((((bo * NB + bi) * 4 + a) * 64 + lane) * 4));
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    out[bo] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[c], bv[c], out[bo], 0, 0, 0);
+            }
+        }
+}
+
+// out[f][item] = sum_n W1[n][f] v[n][item], v = 8 per-lane values of the lane's item
+template <int F>
+__device__ inline void gemm_k8(const float *__restrict__ A1, const float (&v)[8], f32x16 (&out)[Dims<F>::NB], int lane)
+{
+    constexpr int NB = Dims<F>::NB;
+    const int h = lane >> 5;
+#pragma unroll
+    for (int bo = 0; bo < NB; ++bo)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) out[bo][r] = 0.f;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        const float bv = h ? v[2 * s + 1] : v[2 * s];
+#pragma unroll
+        for (int bo = 0; bo < NB; ++bo)
+            out[bo] = __builtin_amdgcn_mfma_f32_32x32x2f32(A1[(bo * 4 + s) * 64 + lane], bv, out[bo], 0, 0, 0);
+    }
+}
+
+// accumulator layout -> item-major LDS tile
+template <int F>
+__device__ inline void regs_to_tile(const f32x16 (&v)[Dims<F>::NB], float *tile, int lane)
+{
+    constexpr int NB = Dims<F>::NB;
+    constexpr int FS = Dims<F>::FS;
+    const int c32 = lane & 31, h = lane >> 5;
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+            f32x4 x = {v[b][4 * a], v[b][4 * a + 1], v[b][4 * a + 2], v[b][4 * a + 3]};
+            *reinterpret_cast<f32x4 *>(tile + c32 * FS + 32 * b + 8 * a + 4 * h) = x;
+        }
+}
+
+__device__ inline int64_t lower_bound_i64(const int64_t *__restrict__ a, int64_t n, int64_t v)
+{
+    int64_t lo = 0, hi = n;  // first index in [0, n] with a[idx] >= v (a has n + 1 entries, searched over [0, n))
+    while (lo < hi) {
+        const int64_t mid = (lo + hi) >> 1;
+        if (a[mid] < v) lo = mid + 1; else hi = mid;
+    }
+    return lo;
+}
+
+// ---------------------------------------------------------------- edge kernels
+
+struct EdgeArgs {
+    int64_t n_rows;            // receiver rows processed
+    int64_t n_chunks;
+    const int64_t *row_ptr;
+    const int32_t *senders;
+    const float *d;
+    const float *g;            // [n_local][F]
+    const float *abar;         // reverse: [n_local][F] (ghost rows zero)
+    float *out;                // forward: a [n_rows][F]; reverse: gbar [n_rows][F]
+    float *dsum;               // reverse: per-edge dE/dd of the edge and its mirror, summed over layers
+    const float *A1, *A2t, *A2n;
+    BasisParams bp;
+    int need_gbar, first;
+};
+
+// wavefront work item: the rows whose first edge lies in [chunk * kChunkEdges, (chunk + 1) * kChunkEdges)
+__device__ inline bool chunk_rows(const EdgeArgs &A, int64_t chunk, int64_t &r0, int64_t &r1)
+{
+    const int64_t lo = chunk * kChunkEdges;
+    r0 = lower_bound_i64(A.row_ptr, A.n_rows, lo);
+    r1 = (chunk == A.n_chunks - 1) ? A.n_rows : lower_bound_i64(A.row_ptr, A.n_rows, lo + kChunkEdges);
+    return r0 < r1;
+}
+
+template <int F>
+__global__ void __launch_bounds__(256) k_edge_fwd(EdgeArgs A)
+{
+    using D = Dims<F>;
+    extern __shared__ float lds[];
+    float *A1 = lds;
+    float *A2 = A1 + D::PACK1;
+    float *tiles = A2 + D::PACKF;
+    for (int i = threadIdx.x; i < D::PACK1; i += 256) A1[i] = A.A1[i];
+    for (int i = threadIdx.x; i < D::PACKF; i += 256) A2[i] = A.A2t[i];
+    __syncthreads();
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int c32 = lane & 31;
+    const int f = lane & (F - 1);
+    float *tile = tiles + wave * D::TILE;
+    const int64_t chunk = (int64_t)blockIdx.x * 4 + wave;
+    if (chunk >= A.n_chunks) return;
+    int64_t r0, r1;
+    if (!chunk_rows(A, chunk, r0, r1)) return;
+    const int64_t e_lo = A.row_ptr[r0], e_hi = A.row_ptr[r1];
+    int64_t cur = r0;
+    int64_t row_end = A.row_ptr[r0 + 1];
+    float acc = 0.f;
+    for (int64_t tb = e_lo; tb < e_hi; tb += 32) {
+        const int64_t e = tb + c32;
+        const bool valid = e < e_hi;
+        const float dv = valid ? A.d[e] : A.bp.rc;  // d = rc gives a zero filter
+        const int32_t j = valid ? A.senders[e] : 0;
+        float b[8], db[8];
+        radial_basis<false>(dv, A.bp, b, db);
+        f32x16 t[D::NB], w[D::NB];
+        gemm_k8<F>(A1, b, t, lane);
+#pragma unroll
+        for (int bb = 0; bb < D::NB; ++bb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) t[bb][r] = t[bb][r] * sigmoidf_fast(t[bb][r]);
+        gemm_regs<F>(A2, t, w, lane);
+        regs_to_tile<F>(w, tile, lane);
+        wave_lds_fence();
+        float gv[32];
+#pragma unroll
+        for (int k = 0; k < 32; ++k) {
+            const int32_t jk = __builtin_amdgcn_readlane(j, k);
+            gv[k] = A.g[(int64_t)jk * F + f];
+        }
+#pragma unroll
+        for (int k = 0; k < 32; ++k) {
+            const int64_t e2 = tb + k;
+            if (e2 < e_hi) {
+                while (e2 >= row_end) {
+                    if (lane < F) A.out[cur * F + f] = acc;
+                    acc = 0.f;
+                    ++cur;
+                    row_end = A.row_ptr[cur + 1];
+                }
+                acc += tile[k * D::FS + f] * gv[k];
+            }
+        }
+        wave_lds_fence();
+    }
+    while (cur < r1) {
+        if (lane < F) A.out[cur * F + f] = acc;
+        acc = 0.f;
+        ++cur;
+    }
+}
+
+template <int F>
+__global__ void __launch_bounds__(256) k_edge_bwd(EdgeArgs A)
+{
+    using D = Dims<F>;
+    extern __shared__ float lds[];
+    float *A1 = lds;
+    float *A2t = A1 + D::PACK1;
+    float *A2n = A2t + D::PACKF;
+    float *tiles = A2n + D::PACKF;
+    for (int i = threadIdx.x; i < D::PACK1; i += 256) A1[i] = A.A1[i];
+    for (int i = threadIdx.x; i < D::PACKF; i += 256) { A2t[i] = A.A2t[i]; A2n[i] = A.A2n[i]; }
+    __syncthreads();
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int c32 = lane & 31;
+    const int f = lane & (F - 1);
+    float *tile = tiles + wave * D::TILE;
+    const int64_t chunk = (int64_t)blockIdx.x * 4 + wave;
+    if (chunk >= A.n_chunks) return;
+    int64_t r0, r1;
+    if (!chunk_rows(A, chunk, r0, r1)) return;
+    const int64_t e_lo = A.row_ptr[r0], e_hi = A.row_ptr[r1];
+    int64_t cur = r0;
+    int64_t row_end = A.row_ptr[r0 + 1];
+    float ai = A.abar[cur * F + f], gi = A.g[cur * F + f];
+    float acc = 0.f;
+    for (int64_t tb = e_lo; tb < e_hi; tb += 32) {
+        const int64_t e = tb + c32;
+        const bool valid = e < e_hi;
+        const float dv = valid ? A.d[e] : A.bp.rc;
+        const int32_t j = valid ? A.senders[e] : 0;
+        float b[8], db[8];
+        radial_basis<true>(dv, A.bp, b, db);
+        f32x16 t[D::NB], sp[D::NB];
+        gemm_k8<F>(A1, b, t, lane);
+#pragma unroll
+        for (int bb = 0; bb < D::NB; ++bb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float x = t[bb][r];
+                const float sg = sigmoidf_fast(x);
+                t[bb][r] = x * sg;                              // s = SiLU(t)
+                sp[bb][r] = sg * (1.0f + x * (1.0f - sg));      // SiLU'(t)
+            }
+        if (A.need_gbar) {
+            f32x16 w[D::NB];
+            gemm_regs<F>(A2t, t, w, lane);
+            regs_to_tile<F>(w, tile, lane);
+        }
+        wave_lds_fence();
+        // lane = feature: gather abar_j, g_j; accumulate gbar_i; leave abar_i*g_j + abar_j*g_i in the tile
+        float av[32], gv[32];
+#pragma unroll
+        for (int k = 0; k < 32; ++k) {
+            const int32_t jk = __builtin_amdgcn_readlane(j, k);
+            av[k] = A.abar[(int64_t)jk * F + f];
+            gv[k] = A.g[(int64_t)jk * F + f];
+        }
+#pragma unroll
+        for (int k = 0; k < 32; ++k) {
+            const int64_t e2 = tb + k;
+            float wsym = 0.f;
+            if (e2 < e_hi) {
+                while (e2 >= row_end) {
+                    if (A.need_gbar && lane < F) A.out[cur * F + f] = acc;
+                    acc = 0.f;
+                    ++cur;
+                    row_end = A.row_ptr[cur + 1];
+                    ai = A.abar[cur * F + f];
+                    gi = A.g[cur * F + f];
+                }
+                if (A.need_gbar) acc += tile[k * D::FS + f] * av[k];
+                wsym = ai * gv[k] + av[k] * gi;
+            }
+            if (lane < F) tile[k * D::FS + f] = wsym;
+        }
+        wave_lds_fence();
+        f32x16 sb[D::NB], cg[D::NB];
+        gemm_lds<F>(A2n, tile, sb, lane);   // sbar[k] = sum_f W2[k][f] wsym[f]
+        gemm_k8<F>(A1, db, cg, lane);       // c[k] = sum_n W1[n][k] db_n/dd
+        float part = 0.f;
+#pragma unroll
+        for (int bb = 0; bb < D::NB; ++bb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) part += sb[bb][r] * sp[bb][r] * cg[bb][r];
+        part += __shfl_xor(part, 32, 64);
+        if (valid && lane < 32) A.dsum[e] = A.first ? part : A.dsum[e] + part;
+        wave_lds_fence();
+    }
+    while (cur < r1) {
+        if (A.need_gbar && lane < F) A.out[cur * F + f] = acc;
+        acc = 0.f;
+        ++cur;
+    }
+}
+
+// ---------------------------------------------------------------- node kernels
+
+enum { OP_PROJ = 0, OP_UPDATE = 1, OP_READOUT = 2, OP_BWD_UPDATE = 3, OP_BWD_PROJ = 4 };
+
+struct NodeArgs {
+    int64_t n_rows;
+    const float *X;    // GEMM input rows
+    float *Y;          // primary output rows
+    float *Z;          // secondary in/out rows (h for UPDATE, hbar for BWD_*)
+    const float *P1, *P2;
+    const float *wr2;
+    float *eps;
+};
+
+template <int F>
+__device__ inline void load_tile(const float *__restrict__ X, int64_t row0, int64_t n_rows, float *tile, int lane)
+{
+    constexpr int FS = Dims<F>::FS;
+    constexpr int LPR = F / 4;        // lanes per row (float4 each)
+    constexpr int RPI = 64 / LPR;     // rows per wave instruction
+    const int rr = lane / LPR, cc = (lane % LPR) * 4;
+#pragma unroll
+    for (int r = 0; r < 32; r += RPI) {
+        const int64_t row = row0 + r + rr;
+        f32x4 v = {0.f, 0.f, 0.f, 0.f};
+        if (row < n_rows) v = *reinterpret_cast<const f32x4 *>(X + row * F + cc);
+        *reinterpret_cast<f32x4 *>(tile + (r + rr) * FS + cc) = v;
+    }
+}
+
+template <int F, int OP>
+__global__ void __launch_bounds__(256) k_node(NodeArgs A)
+{
+    using D = Dims<F>;
+    constexpr bool TWO = (OP == OP_READOUT || OP == OP_BWD_UPDATE);
+    extern __shared__ float lds[];
+    float *P1 = lds;
+    float *P2 = P1 + D::PACKF;
+    float *tiles = P2 + (TWO ? D::PACKF : 0);
+    for (int i = threadIdx.x; i < D::PACKF; i += 256) {
+        P1[i] = A.P1[i];
+        if (TWO) P2[i] = A.P2[i];
+    }
+    __syncthreads();
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int c32 = lane & 31, h = lane >> 5;
+    float *tile = tiles + wave * D::TILE;
+    const int64_t n_tiles = (A.n_rows + 31) / 32;
+    for (int64_t ti = (int64_t)blockIdx.x * 4 + wave; ti < n_tiles; ti += (int64_t)gridDim.x * 4) {
+        const int64_t row0 = ti * 32;
+        const int64_t row = row0 + c32;
+        const bool ok = row < A.n_rows;
+        load_tile<F>(A.X, row0, A.n_rows, tile, lane);
+        wave_lds_fence();
+        f32x16 acc[D::NB];
+        gemm_lds<F>(P1, tile, acc, lane);
+        wave_lds_fence();
+        if (OP == OP_PROJ) {
+            if (ok)
+#pragma unroll
+                for (int b = 0; b < D::NB; ++b)
+#pragma unroll
+                    for (int a = 0; a < 4; ++a) {
+                        f32x4 v = {acc[b][4 * a], acc[b][4 * a + 1], acc[b][4 * a + 2], acc[b][4 * a + 3]};
+                        *reinterpret_cast<f32x4 *>(A.Y + row * F + 32 * b + 8 * a + 4 * h) = v;
+                    }
+        } else if (OP == OP_UPDATE || OP == OP_BWD_PROJ) {
+            // UPDATE:   Z = h,    h    += SiLU(a Wo)
+            // BWD_PROJ: Z = hbar, hbar += gbar Wm^T
+            if (ok)
+#pragma unroll
+                for (int b = 0; b < D::NB; ++b)
+#pragma unroll
+                    for (int a = 0; a < 4; ++a) {
+                        float *zp = A.Z + row * F + 32 * b + 8 * a + 4 * h;
+                        f32x4 v = *reinterpret_cast<const f32x4 *>(zp);
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) {
+                            const float q = acc[b][4 * a + c];
+                            v[c] += (OP == OP_UPDATE) ? q * sigmoidf_fast(q) : q;
+                        }
+                        *reinterpret_cast<f32x4 *>(zp) = v;
+                    }
+        } else if (OP == OP_READOUT) {
+            // eps = SiLU(h Wr1) . wr2 ;  hbar = (wr2 * SiLU'(h Wr1)) Wr1^T
+            float part = 0.f;
+#pragma unroll
+            for (int b = 0; b < D::NB; ++b)
+#pragma unroll
+                for (int a = 0; a < 4; ++a) {
+                    const f32x4 wv = *reinterpret_cast<const f32x4 *>(A.wr2 + 32 * b + 8 * a + 4 * h);
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        const float x = acc[b][4 * a + c];
+                        const float sg = sigmoidf_fast(x);
+                        part += x * sg * wv[c];
+                        acc[b][4 * a + c] = wv[c] * sg * (1.0f + x * (1.0f - sg));
+                    }
+                }
+            part += __shfl_xor(part, 32, 64);
+            if (ok && h == 0) A.eps[row] = part;
+            f32x16 hb[D::NB];
+            gemm_regs<F>(P2, acc, hb, lane);
+            if (ok)
+#pragma unroll
+                for (int b = 0; b < D::NB; ++b)
+#pragma unroll
+                    for (int a = 0; a < 4; ++a) {
+                        f32x4 v = {hb[b][4 * a], hb[b][4 * a + 1], hb[b][4 * a + 2], hb[b][4 * a + 3]};
+                        *reinterpret_cast<f32x4 *>(A.Y + row * F + 32 * b + 8 * a + 4 * h) = v;
+                    }
+        } else if (OP == OP_BWD_UPDATE) {
+            // q = a Wo ; qbar = hbar * SiLU'(q) ; abar = qbar Wo^T       (X = a, Z = hbar, Y = abar)
+#pragma unroll
+            for (int b = 0; b < D::NB; ++b)
+#pragma unroll
+                for (int a = 0; a < 4; ++a) {
+                    f32x4 hv = {0.f, 0.f, 0.f, 0.f};
+                    if (ok) hv = *reinterpret_cast<const f32x4 *>(A.Z + row * F + 32 * b + 8 * a + 4 * h);
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        const float x = acc[b][4 * a + c];
+                        const float sg = sigmoidf_fast(x);
+                        acc[b][4 * a + c] = hv[c] * sg * (1.0f + x * (1.0f - sg));
+                    }
+                }
+            f32x16 ab[D::NB];
+            gemm_regs<F>(P2, acc, ab, lane);
+            if (ok)
+#pragma unroll
+                for (int b = 0; b < D::NB; ++b)
+#pragma unroll
+                    for (int a = 0; a < 4; ++a) {
+                        f32x4 v = {ab[b][4 * a], ab[b][4 * a + 1], ab[b][4 * a + 2], ab[b][4 * a + 3]};
+                        *reinterpret_cast<f32x4 *>(A.Y + row * F + 32 * b + 8 * a + 4 * h) = v;
+                    }
+        }
+    }
+}
+
+// ---------------------------------------------------------------- small kernels
+
+__global__ void k_embed(int64_t n_rows, int F, const int32_t *__restrict__ nodes, const int32_t *__restrict__ species,
+                        const float *__restrict__ emb, float *__restrict__ h)
+{
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= n_rows * F) return;
+    const int64_t r = idx / F;
+    const int f = (int)(idx % F);
+    const int64_t u = nodes ? nodes[r] : r;
+    h[idx] = emb[species[u] * F + f];
+}
+
+struct PtrTable { float *p[kMaxSlabs]; };
+
+// ghost rows of this partition's g  <-  the owners' rows
+__global__ void k_ghost_copy(int64_t n_ghost, int64_t n_owned, int F, const int32_t *__restrict__ owner,
+                             const int32_t *__restrict__ src, PtrTable tab, float *__restrict__ dst)
+{
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int F4 = F / 4;
+    if (idx >= n_ghost * F4) return;
+    const int64_t k = idx / F4;
+    const int c = (int)(idx % F4) * 4;
+    const float *sp = tab.p[owner[k]] + (int64_t)src[k] * F + c;
+    *reinterpret_cast<f32x4 *>(dst + (n_owned + k) * F + c) = *reinterpret_cast<const f32x4 *>(sp);
+}
+
+// the owners' gradient rows  +=  this partition's ghost rows (each ghost atom appears once per partition)
+__global__ void k_ghost_addback(int64_t n_ghost, int64_t n_owned, int F, const int32_t *__restrict__ owner,
+                                const int32_t *__restrict__ src, PtrTable tab, const float *__restrict__ mine)
+{
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int F4 = F / 4;
+    if (idx >= n_ghost * F4) return;
+    const int64_t k = idx / F4;
+    const int c = (int)(idx % F4) * 4;
+    float *dp = tab.p[owner[k]] + (int64_t)src[k] * F + c;
+    f32x4 v = *reinterpret_cast<const f32x4 *>(dp);
+    const f32x4 m = *reinterpret_cast<const f32x4 *>(mine + (n_owned + k) * F + c);
+    v += m;
+    *reinterpret_cast<f32x4 *>(dp) = v;
+}
+
+__device__ inline void unpack_shift(uint32_t p, int &a, int &b, int &c)
+{
+    a = (int)(p >> 20) - 512;
+    b = (int)((p >> 10) & 1023u) - 512;
+    c = (int)(p & 1023u) - 512;
+}
+
+// F_loc[r] = sum_{e in local row r} dsum_e * rhat_e, rhat from fp64 positions; one wavefront per row
+__global__ void __launch_bounds__(64)
+k_force_rows(int64_t n_rows, const int64_t *__restrict__ row_ptr, const int32_t *__restrict__ senders,
+             const uint32_t *__restrict__ shiftp, const float *__restrict__ dsum, const int32_t *__restrict__ nodes,
+             const double *__restrict__ pos, CellParams cp, float *__restrict__ floc)
+{
+    const int64_t r = blockIdx.x;
+    const int64_t ig = nodes ? nodes[r] : r;
+    const double xi = pos[3 * ig], yi = pos[3 * ig + 1], zi = pos[3 * ig + 2];
+    double fx = 0, fy = 0, fz = 0;
+    const int64_t e1 = row_ptr[r + 1];
+    for (int64_t e = row_ptr[r] + threadIdx.x; e < e1; e += 64) {
+        const int64_t jl = senders[e];
+        const int64_t jg = nodes ? nodes[jl] : jl;
+        int S0, S1, S2;
+        unpack_shift(shiftp[e], S0, S1, S2);
+        const double t0 = (pos[3 * jg] - xi) + (((double)S0 * cp.C[0] + (double)S1 * cp.C[3]) + (double)S2 * cp.C[6]);
+        const double t1 = (pos[3 * jg + 1] - yi) + (((double)S0 * cp.C[1] + (double)S1 * cp.C[4]) + (double)S2 * cp.C[7]);
+        const double t2 = (pos[3 * jg + 2] - zi) + (((double)S0 * cp.C[2] + (double)S1 * cp.C[5]) + (double)S2 * cp.C[8]);
+        const double s = (double)dsum[e] / sqrt((t0 * t0 + t1 * t1) + t2 * t2);
+        fx += s * t0;
+        fy += s * t1;
+        fz += s * t2;
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        fx += __shfl_xor(fx, off, 64);
+        fy += __shfl_xor(fy, off, 64);
+        fz += __shfl_xor(fz, off, 64);
+    }
+    if (threadIdx.x == 0) {
+        floc[3 * r] = (float)fx;
+        floc[3 * r + 1] = (float)fy;
+        floc[3 * r + 2] = (float)fz;
+    }
+}
+
+// owned rows: forces[global] = F_loc ; atom_energy[global] = eps
+__global__ void k_store_owned(int64_t n_owned, const int32_t *__restrict__ nodes, const float *__restrict__ floc,
+                              const float *__restrict__ eps, float *__restrict__ forces, float *__restrict__ atom_energy)
+{
+    const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (r >= n_owned) return;
+    const int64_t u = nodes ? nodes[r] : r;
+    forces[3 * u] = floc[3 * r];
+    forces[3 * u + 1] = floc[3 * r + 1];
+    forces[3 * u + 2] = floc[3 * r + 2];
+    if (atom_energy) atom_energy[u] = eps[r];
+}
+
+// ghost rows: forces[global] += F_loc (position gradients of ghost atoms go back to their owners)
+__global__ void k_addback_ghost_forces(int64_t n_ghost, int64_t n_owned, const int32_t *__restrict__ nodes,
+                                       const float *__restrict__ floc, float *__restrict__ forces)
+{
+    const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= n_ghost) return;
+    const int64_t r = n_owned + k;
+    const int64_t u = nodes[r];
+    forces[3 * u] += floc[3 * r];
+    forces[3 * u + 1] += floc[3 * r + 1];
+    forces[3 * u + 2] += floc[3 * r + 2];
+}
+
+// fixed-shape fp64 reduction of the per-atom energies: 1024-element blocks, then one block over the partials
+__global__ void __launch_bounds__(256) k_energy_partial(int64_t n, const float *__restrict__ eps, double *__restrict__ part)
+{
+    __shared__ double sh[4];
+    const int64_t base = (int64_t)blockIdx.x * 1024;
+    double s = 0;
+    for (int k = threadIdx.x; k < 1024; k += 256)
+        if (base + k < n) s += (double)eps[base + k];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) part[blockIdx.x] = (sh[0] + sh[1]) + (sh[2] + sh[3]);
+}
+
+__global__ void __launch_bounds__(256) k_energy_final(int64_t n, const double *__restrict__ part, double *__restrict__ energy)
+{
+    __shared__ double sh[4];
+    double s = 0;
+    for (int64_t k = threadIdx.x; k < n; k += 256) s += part[k];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) *energy = (sh[0] + sh[1]) + (sh[2] + sh[3]);
+}
+
+inline unsigned blocks_for(int64_t n, int threads) { return (unsigned)((n + threads - 1) / threads); }
+
+// ---------------------------------------------------------------- host driver
+
+struct Packs {  // offsets (floats) into the packed-weight buffer
+    size_t per_layer, A1, W2t, W2n, Wmt, Wmn, Wot, Won, readout_t, readout_n, total;
+};
+
+Packs pack_layout(int F, int L)
+{
+    Packs p;
+    const size_t ff = (size_t)F * F, p1 = (size_t)(F / 32) * 4 * 64;
+    p.A1 = 0;
+    p.W2t = p1;
+    p.W2n = p.W2t + ff;
+    p.Wmt = p.W2n + ff;
+    p.Wmn = p.Wmt + ff;
+    p.Wot = p.Wmn + ff;
+    p.Won = p.Wot + ff;
+    p.per_layer = p.Won + ff;
+    p.readout_t = p.per_layer * (size_t)L;
+    p.readout_n = p.readout_t + ff;
+    p.total = p.readout_n + ff;
+    return p;
+}
+
+template <int F> struct Lds {
+    using D = Dims<F>;
+    static constexpr size_t edge_fwd = sizeof(float) * (D::PACK1 + D::PACKF + 4 * D::TILE);
+    static constexpr size_t edge_bwd = sizeof(float) * (D::PACK1 + 2 * D::PACKF + 4 * D::TILE);
+    static constexpr size_t node1 = sizeof(float) * (D::PACKF + 4 * D::TILE);
+    static constexpr size_t node2 = sizeof(float) * (2 * D::PACKF + 4 * D::TILE);
+};
+
+template <int F, int OP> int launch_node(mlip_graph *g, const NodeArgs &a)
+{
+    if (a.n_rows <= 0) return MLIP_OK;
+    constexpr bool TWO = (OP == OP_READOUT || OP == OP_BWD_UPDATE);
+    const size_t lds = TWO ? Lds<F>::node2 : Lds<F>::node1;
+    static bool configured = false;
+    if (!configured) {
+        MLIP_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_node<F, OP>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        configured = true;
+    }
+    const int64_t n_tiles = (a.n_rows + 31) / 32;
+    // each block keeps its weight pack in LDS, so let it walk several tiles
+    const unsigned blocks = (unsigned)std::min<int64_t>((n_tiles + 3) / 4, 2048);
+    k_node<F, OP><<<blocks, 256, lds, g->stream>>>(a);
+    MLIP_HIP(hipGetLastError());
+    return MLIP_OK;
+}
+
+template <int F> int launch_edge(mlip_graph *g, EdgeArgs a, bool backward)
+{
+    if (a.n_rows <= 0) return MLIP_OK;
+    const size_t lds = backward ? Lds<F>::edge_bwd : Lds<F>::edge_fwd;
+    static bool cfg_f = false, cfg_b = false;
+    if (backward && !cfg_b) {
+        MLIP_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_edge_bwd<F>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        cfg_b = true;
+    }
+    if (!backward && !cfg_f) {
+        MLIP_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_edge_fwd<F>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        cfg_f = true;
+    }
+    const unsigned blocks = (unsigned)((a.n_chunks + 3) / 4);
+    if (backward)
+        k_edge_bwd<F><<<blocks, 256, lds, g->stream>>>(a);
+    else
+        k_edge_fwd<F><<<blocks, 256, lds, g->stream>>>(a);
+    MLIP_HIP(hipGetLastError());
+    return MLIP_OK;
+}
+
+template <int F>
+int forward_t(mlip_graph *g, const mlip_weights_t *w, int32_t mode, double *energy, float *forces, float *atom_energy)
+{
+    hipStream_t s = g->stream;
+    const int L = w->L;
+    const bool slabs = (mode == MLIP_MODE_SLABS);
+    const int P = slabs ? g->P : 1;
+    SlabView *views = slabs ? g->slabs.data() : &g->whole;
+    const size_t rowb = (size_t)F * sizeof(float);
+
+    // ---- workspace
+    int64_t n_parts = 0;
+    for (int p = 0; p < P; ++p) {
+        SlabView &v = views[p];
+        const size_t no = (size_t)std::max<int64_t>(v.n_owned, 1), nl = (size_t)std::max<int64_t>(v.n_local, 1);
+        MLIP_TRY(v.h.ensure(no * rowb));
+        MLIP_TRY(v.hbar.ensure(no * rowb));
+        MLIP_TRY(v.abar.ensure(nl * rowb));
+        MLIP_TRY(v.gbar.ensure(nl * rowb));
+        MLIP_TRY(v.eps.ensure(no * sizeof(float)));
+        MLIP_TRY(v.dsum.ensure((size_t)std::max<int64_t>(v.n_edges, 1) * sizeof(float)));
+        MLIP_TRY(v.floc.ensure(nl * 3 * sizeof(float)));
+        MLIP_TRY(v.g.ensure(nl * rowb * (size_t)std::max(L, 1)));
+        MLIP_TRY(v.a.ensure(no * rowb * (size_t)std::max(L, 1)));
+        n_parts += (v.n_owned + 1023) / 1024;
+    }
+    MLIP_TRY(g->energy_part.ensure((size_t)std::max<int64_t>(n_parts, 1) * sizeof(double)));
+    const Packs pk = pack_layout(F, L);
+    MLIP_TRY(g->wpack.ensure(pk.total * sizeof(float)));
+    float *wp = g->wpack.as<float>();
+
+    BasisParams bp;
+    bp.rc = (float)g->r_cut;
+    bp.inv_rc = (float)(1.0 / g->r_cut);
+    bp.p = w->p;
+    const double pd = (double)w->p;
+    bp.c0 = (float)((pd + 1) * (pd + 2) / 2);
+    bp.c1 = (float)(pd * (pd + 2));
+    bp.c2 = (float)(pd * (pd + 1) / 2);
+    bp.pc0 = (float)(pd * (pd + 1) * (pd + 2) / 2);
+    bp.pc1 = (float)((pd + 1) * pd * (pd + 2));
+    bp.pc2 = (float)((pd + 2) * pd * (pd + 1) / 2);
+
+    // ---- pack weights
+    prof_begin(g, MLIP_PROF_NODE);
+    const unsigned pb = blocks_for((int64_t)F * F, 256);
+    for (int l = 0; l < L; ++l) {
+        float *base = wp + pk.per_layer * l;
+        const size_t ff = (size_t)F * F;
+        k_pack_w1<<<blocks_for((F / 32) * 256, 256), 256, 0, s>>>(w->W1 + (size_t)l * 8 * F, F, base + pk.A1);
+        k_pack_ff<<<pb, 256, 0, s>>>(w->W2 + l * ff, F, 1, base + pk.W2t);
+        k_pack_ff<<<pb, 256, 0, s>>>(w->W2 + l * ff, F, 0, base + pk.W2n);
+        k_pack_ff<<<pb, 256, 0, s>>>(w->Wm + l * ff, F, 1, base + pk.Wmt);
+        k_pack_ff<<<pb, 256, 0, s>>>(w->Wm + l * ff, F, 0, base + pk.Wmn);
+        k_pack_ff<<<pb, 256, 0, s>>>(w->Wo + l * ff, F, 1, base + pk.Wot);
+        k_pack_ff<<<pb, 256, 0, s>>>(w->Wo + l * ff, F, 0, base + pk.Won);
+    }
+    k_pack_ff<<<pb, 256, 0, s>>>(w->Wr1, F, 1, wp + pk.readout_t);
+    k_pack_ff<<<pb, 256, 0, s>>>(w->Wr1, F, 0, wp + pk.readout_n);
+    MLIP_HIP(hipGetLastError());
+
+    // ---- embedding
+    const int32_t *species = g->species.as<int32_t>();
+    for (int p = 0; p < P; ++p) {
+        SlabView &v = views[p];
+        if (v.n_owned > 0)
+            k_embed<<<blocks_for(v.n_owned * F, 256), 256, 0, s>>>(v.n_owned, F, v.nodes, species, w->emb, v.h.as<float>());
+    }
+    MLIP_HIP(hipGetLastError());
+    prof_end(g);
+
+    auto gslice = [&](SlabView &v, int l) { return v.g.as<float>() + (size_t)l * (size_t)v.n_local * F; };
+    auto aslice = [&](SlabView &v, int l) { return v.a.as<float>() + (size_t)l * (size_t)v.n_owned * F; };
+
+    // ---- forward layers
+    for (int l = 0; l < L; ++l) {
+        const float *base = wp + pk.per_layer * l;
+        prof_begin(g, MLIP_PROF_NODE);
+        for (int p = 0; p < P; ++p) {  // sender projection on owned rows
+            SlabView &v = views[p];
+            NodeArgs na{};
+            na.n_rows = v.n_owned;
+            na.X = v.h.as<float>();
+            na.Y = gslice(v, l);
+            na.P1 = base + pk.Wmt;
+            MLIP_TRY((launch_node<F, OP_PROJ>(g, na)));
+        }
+        prof_end(g);
+        if (slabs) {
+            prof_begin(g, MLIP_PROF_GHOST);
+            PtrTable tab{};
+            for (int q = 0; q < P; ++q) tab.p[q] = gslice(views[q], l);
+            for (int p = 0; p < P; ++p) {  // border-node transfer: ghost rows <- owners
+                SlabView &v = views[p];
+                if (v.n_ghost > 0)
+                    k_ghost_copy<<<blocks_for(v.n_ghost * (F / 4), 256), 256, 0, s>>>(
+                        v.n_ghost, v.n_owned, F, v.ghost_owner, v.ghost_src, tab, gslice(v, l));
+            }
+            MLIP_HIP(hipGetLastError());
+            prof_end(g);
+        }
+        for (int p = 0; p < P; ++p) {
+            SlabView &v = views[p];
+            EdgeArgs ea{};
+            ea.n_rows = v.n_owned;
+            ea.n_chunks = std::max<int64_t>(1, (v.n_edges_owned + kChunkEdges - 1) / kChunkEdges);
+            ea.row_ptr = v.row_ptr;
+            ea.senders = v.senders;
+            ea.d = v.d;
+            ea.g = gslice(v, l);
+            ea.out = aslice(v, l);
+            ea.A1 = base + pk.A1;
+            ea.A2t = base + pk.W2t;
+            ea.bp = bp;
+            prof_begin(g, MLIP_PROF_EDGE_FWD);
+            MLIP_TRY((launch_edge<F>(g, ea, false)));
+            prof_end(g);
+        }
+        prof_begin(g, MLIP_PROF_NODE);
+        for (int p = 0; p < P; ++p) {
+            SlabView &v = views[p];
+            NodeArgs na{};
+            na.n_rows = v.n_owned;
+            na.X = aslice(v, l);
+            na.Z = v.h.as<float>();
+            na.P1 = base + pk.Wot;
+            MLIP_TRY((launch_node<F, OP_UPDATE>(g, na)));
+        }
+        prof_end(g);
+    }
+
+    // ---- readout (energy and dE/dh of the last layer in one pass)
+    prof_begin(g, MLIP_PROF_NODE);
+    for (int p = 0; p < P; ++p) {
+        SlabView &v = views[p];
+        NodeArgs na{};
+        na.n_rows = v.n_owned;
+        na.X = v.h.as<float>();
+        na.Y = v.hbar.as<float>();
+        na.P1 = wp + pk.readout_t;
+        na.P2 = wp + pk.readout_n;
+        na.wr2 = w->wr2;
+        na.eps = v.eps.as<float>();
+        MLIP_TRY((launch_node<F, OP_READOUT>(g, na)));
+    }
+    prof_end(g);
+    prof_begin(g, MLIP_PROF_FORCE);
+    {
+        int64_t off = 0;
+        double *part = g->energy_part.as<double>();
+        for (int p = 0; p < P; ++p) {
+            SlabView &v = views[p];
+            const int64_t nb = (v.n_owned + 1023) / 1024;
+            if (nb > 0) k_energy_partial<<<(unsigned)nb, 256, 0, s>>>(v.n_owned, v.eps.as<float>(), part + off);
+            off += nb;
+        }
+        k_energy_final<<<1, 256, 0, s>>>(off, part, energy);
+        MLIP_HIP(hipGetLastError());
+    }
+    prof_end(g);
+
+    // ---- reverse pass
+    for (int l = L - 1; l >= 0; --l) {
+        const float *base = wp + pk.per_layer * l;
+        const bool need_gbar = l > 0;  // dE/dh0 is never used: the embedding does not depend on positions
+        prof_begin(g, MLIP_PROF_NODE);
+        for (int p = 0; p < P; ++p) {
+            SlabView &v = views[p];
+            if (v.n_ghost > 0)  // ghost rows carry no dE/da
+                MLIP_HIP(hipMemsetAsync(v.abar.as<float>() + (size_t)v.n_owned * F, 0, (size_t)v.n_ghost * rowb, s));
+            NodeArgs na{};
+            na.n_rows = v.n_owned;
+            na.X = aslice(v, l);
+            na.Z = v.hbar.as<float>();
+            na.Y = v.abar.as<float>();
+            na.P1 = base + pk.Wot;
+            na.P2 = base + pk.Won;
+            MLIP_TRY((launch_node<F, OP_BWD_UPDATE>(g, na)));
+        }
+        prof_end(g);
+        for (int p = 0; p < P; ++p) {
+            SlabView &v = views[p];
+            EdgeArgs ea{};
+            ea.n_rows = v.n_local;
+            ea.n_chunks = std::max<int64_t>(1, (v.n_edges + kChunkEdges - 1) / kChunkEdges);
+            ea.row_ptr = v.row_ptr;
+            ea.senders = v.senders;
+            ea.d = v.d;
+            ea.g = gslice(v, l);
+            ea.abar = v.abar.as<float>();
+            ea.out = v.gbar.as<float>();
+            ea.dsum = v.dsum.as<float>();
+            ea.A1 = base + pk.A1;
+            ea.A2t = base + pk.W2t;
+            ea.A2n = base + pk.W2n;
+            ea.bp = bp;
+            ea.need_gbar = need_gbar ? 1 : 0;
+            ea.first = (l == L - 1) ? 1 : 0;
+            prof_begin(g, MLIP_PROF_EDGE_BWD);
+            MLIP_TRY((launch_edge<F>(g, ea, true)));
+            prof_end(g);
+        }
+        if (need_gbar) {
+            if (slabs) {
+                prof_begin(g, MLIP_PROF_GHOST);
+                PtrTable tab{};
+                for (int q = 0; q < P; ++q) tab.p[q] = views[q].gbar.as<float>();
+                for (int p = 0; p < P; ++p) {  // ghost-row gradients -> owners, partitions in ascending order
+                    SlabView &v = views[p];
+                    if (v.n_ghost > 0)
+                        k_ghost_addback<<<blocks_for(v.n_ghost * (F / 4), 256), 256, 0, s>>>(
+                            v.n_ghost, v.n_owned, F, v.ghost_owner, v.ghost_src, tab, v.gbar.as<float>());
+                }
+                MLIP_HIP(hipGetLastError());
+                prof_end(g);
+            }
+            prof_begin(g, MLIP_PROF_NODE);
+            for (int p = 0; p < P; ++p) {
+                SlabView &v = views[p];
+                NodeArgs na{};
+                na.n_rows = v.n_owned;
+                na.X = v.gbar.as<float>();
+                na.Z = v.hbar.as<float>();
+                na.P1 = base + pk.Wmn;
+                MLIP_TRY((launch_node<F, OP_BWD_PROJ>(g, na)));
+            }
+            prof_end(g);
+        }
+    }
+
+    // ---- forces
+    prof_begin(g, MLIP_PROF_FORCE);
+    const double *pos = g->pos.as<double>();
+    for (int p = 0; p < P; ++p) {
+        SlabView &v = views[p];
+        if (L > 0 && v.n_local > 0) {
+            k_force_rows<<<(unsigned)v.n_local, 64, 0, s>>>(v.n_local, v.row_ptr, v.senders, v.shiftp, v.dsum.as<float>(),
+                                                            v.nodes, pos, g->cell, v.floc.as<float>());
+        } else if (v.n_local > 0) {
+            MLIP_HIP(hipMemsetAsync(v.floc.p, 0, (size_t)v.n_local * 3 * sizeof(float), s));
+        }
+        if (v.n_owned > 0)
+            k_store_owned<<<blocks_for(v.n_owned, 256), 256, 0, s>>>(v.n_owned, v.nodes, v.floc.as<float>(),
+                                                                     v.eps.as<float>(), forces, atom_energy);
+    }
+    if (slabs)
+        for (int p = 0; p < P; ++p) {
+            SlabView &v = views[p];
+            if (v.n_ghost > 0)
+                k_addback_ghost_forces<<<blocks_for(v.n_ghost, 256), 256, 0, s>>>(v.n_ghost, v.n_owned, v.nodes,
+                                                                                  v.floc.as<float>(), forces);
+        }
+    MLIP_HIP(hipGetLastError());
+    prof_end(g);
+    return MLIP_OK;
+}
+
+}  // namespace
+
+int forward_impl(mlip_graph *g, const mlip_weights_t *w, int32_t mode, double *energy, float *forces, float *atom_energy)
+{
+    if (w->F == 32) return forward_t<32>(g, w, mode, energy, forces, atom_energy);
+    return forward_t<64>(g, w, mode, energy, forces, atom_energy);
+}
+
+}  // namespace mlip

@@ -1,0 +1,78 @@
+"""GPU parity: energy and forces against the fp64 oracle (whole graph and partitioned)."""
+import numpy as np
+import pytest
+
+import workloads as wl
+from oracle import graph as og
+from oracle import model as om
+
+from gpu_util import assert_energy_forces, gpu_energy_forces, gpu_graph, oracle_config
+
+pytestmark = pytest.mark.gpu
+
+WHOLE, SLABS = 0, 1
+
+
+@pytest.mark.parametrize("index", [0, 1])
+def test_whole_graph_configs(index):
+    c, _, ref = oracle_config(index)
+    g = gpu_graph(c["positions"], c["cell"], c["species"], c["r_cut"])
+    e, f, ae = gpu_energy_forces(g, c["weights"], c["p"], WHOLE)
+    de, df = assert_energy_forces(e, f, ref, f"configs[{index}] whole")
+    assert np.abs(ae - ref["atom_energy"]).max() <= 1e-4 * np.abs(ref["atom_energy"]).max()
+    print(f"configs[{index}] whole: dE/E = {de:.2e}, dF/Fmax = {df:.2e}")
+
+
+@pytest.mark.parametrize("P", [2, 3, 8])
+def test_slabs_config0(P):
+    c, _, ref = oracle_config(0)
+    g = gpu_graph(c["positions"], c["cell"], c["species"], c["r_cut"], n_slabs=P)
+    e, f, ae = gpu_energy_forces(g, c["weights"], c["p"], SLABS)
+    assert_energy_forces(e, f, ref, f"configs[0] {P} slabs")
+    ew, fw, _ = gpu_energy_forces(g, c["weights"], c["p"], WHOLE)
+    assert_energy_forces(ew, fw, ref, "configs[0] whole on a partitioned graph")
+
+
+def test_slabs_medium():
+    c, _, ref = oracle_config(1)
+    g = gpu_graph(c["positions"], c["cell"], c["species"], c["r_cut"], n_slabs=8)
+    e, f, ae = gpu_energy_forces(g, c["weights"], c["p"], SLABS)
+    de, df = assert_energy_forces(e, f, ref, "configs[1] 8 slabs")
+    print(f"configs[1] 8 slabs: dE/E = {de:.2e}, dF/Fmax = {df:.2e}")
+
+
+def test_triclinic_small_cell_f32_features():
+    """F = 32, thin triclinic cell (multiple images), 3 slabs thinner than r_cut."""
+    pos, cell, sp = wl.random_triclinic(40, 8, scale=6.0)
+    W = wl.rmp_weights(4, 32, 2, seed=3)
+    ref_g = og.build_graph(pos, cell, 3.5)
+    ref = om.energy_forces(pos, cell, sp, W, ref_g, 3.5, 8, 6)
+    g = gpu_graph(pos, cell, sp, 3.5, n_slabs=3)
+    for mode in (WHOLE, SLABS):
+        e, f, _ = gpu_energy_forces(g, W, 6, mode)
+        assert_energy_forces(e, f, ref, f"triclinic mode {mode}")
+
+
+def test_zero_layers_and_isolated_atoms():
+    import paper_2506_02023_amd as M
+    c, _, _ = oracle_config(0)
+    W0 = {k: (v[:0] if k in ("W1", "W2", "Wm", "Wo") else v) for k, v in c["weights"].items()}
+    ref_g = og.build_graph(c["positions"], c["cell"], c["r_cut"])
+    ref = om.energy_forces(c["positions"], c["cell"], c["species"], W0, ref_g, c["r_cut"], c["K"], c["p"])
+    g = gpu_graph(c["positions"], c["cell"], c["species"], c["r_cut"])
+    e, f, _ = gpu_energy_forces(g, W0, c["p"], WHOLE)
+    assert abs(e - ref["energy"]) <= 1e-5 * abs(ref["energy"]) and np.all(f == 0)
+    # atoms with no neighbours at all: empty rows everywhere
+    pos = np.array([[1.0, 1, 1], [12.0, 12, 12], [22.0, 5, 17]])
+    cell = np.eye(3) * 30.0
+    sp = np.array([0, 1, 2], np.int32)
+    ref_g = og.build_graph(pos, cell, 5.0)
+    assert ref_g.E == 0
+    ref = om.energy_forces(pos, cell, sp, c["weights"], ref_g, 5.0, 8, 6)
+    g = gpu_graph(pos, cell, sp, 5.0)
+    e, f, _ = gpu_energy_forces(g, c["weights"], 6, WHOLE)
+    assert abs(e - ref["energy"]) <= 1e-5 * abs(ref["energy"]) and np.all(f == 0)
+    # species out of range is refused
+    g = gpu_graph(pos, cell, np.array([0, 1, 9], np.int32), 5.0)
+    with pytest.raises(M.MlipError):
+        gpu_energy_forces(g, c["weights"], 6, WHOLE)

@@ -1,0 +1,146 @@
+"""Benchmark: energy + forces throughput of the partitioned hot path on one MI355X.
+
+One step = mlip_build_graph (n_slabs = 8) + mlip_forward in SLABS mode on benchmark
+configuration 3 (63^3 fcc cells, 1,000,188 atoms, ~45.8M directed edges, F = 64, L = 3),
+i.e. every stage of the path: cell list, CSR, partition, three layers forward with ghost
+copies, reverse pass with ghost-gradient add-backs, forces.  Inputs are resident in HBM
+before the timed region.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_FP32_MFMA_TFLOPS = 157.3
+# algorithmic flops of the reverse edge step per directed edge (K = 8, F = 64):
+#   recompute t = b W1 (2*8*64), w = s W2 (2*64*64, not needed in layer 0), sbar = wbar W2^T (2*64*64),
+#   dt/dd contraction through W1 (2*8*64)
+FLOPS_BWD_EDGE = 2 * 8 * 64 + 2 * 64 * 64 + 2 * 64 * 64 + 2 * 8 * 64
+FLOPS_BWD_EDGE_L0 = FLOPS_BWD_EDGE - 2 * 64 * 64
+FLOPS_FWD_EDGE = 2 * 8 * 64 + 2 * 64 * 64
+
+
+def cpu_baseline(cfg_index, n_cells):
+    """The oracle, as it stands, on a bounded sample of the same workload (same recipe, smaller box)."""
+    import workloads as wl
+    from oracle import _lib as ol
+    from oracle import graph as og
+    from oracle import model as om
+    c = wl.make_config(cfg_index, n=n_cells)
+    t0 = time.perf_counter()
+    g = og.build_graph(c["positions"], c["cell"], c["r_cut"])
+    om.energy_forces(c["positions"], c["cell"], c["species"], c["weights"], g, c["r_cut"], c["K"], c["p"])
+    dt = time.perf_counter() - t0
+    n = len(c["species"])
+    return {"value": n / dt, "unit": "atoms/s", "cores": int(ol.lib().orc_num_threads()), "kind": "oracle",
+            "sample": f"configs[{cfg_index}] recipe at {n_cells}^3 fcc cells ({n} atoms, {g.E} edges), "
+                      f"fp64, graph + energy + forces, one run of {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=3)
+    ap.add_argument("--cells", type=int, default=None, help="override fcc cells per side (smaller runs)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
+    ap.add_argument("--cpu-cells", type=int, default=20)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (slabs are processed in sequence on one device); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2506_02023_amd as M
+    import workloads as wl
+
+    c = wl.make_config(args.config, n=args.cells)
+    P = max(c["n_slabs"], 2)
+    torch.cuda.set_device(0)
+    pos = torch.as_tensor(c["positions"], device="cuda")
+    spec = torch.as_tensor(c["species"], device="cuda")
+    W = M.Weights(c["weights"], c["p"])
+    N = pos.shape[0]
+    out = (torch.empty(1, dtype=torch.float64, device="cuda"), torch.empty((N, 3), dtype=torch.float32, device="cuda"),
+           None)
+    g = None
+
+    def step(mode=M.MODE_SLABS):
+        nonlocal g
+        g = M.mlip_build_graph(pos, c["cell"], spec, c["r_cut"], n_slabs=P, graph=g)
+        M.mlip_forward(g, W, mode, out=out, want_atom_energy=False)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    g.profile_enable(True)
+    g.profile_read(reset=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = g.profile_read(reset=True)
+    g.profile_enable(False)
+    _, E, _ = g.sizes()
+    energy = float(out[0].cpu()[0])
+    fsum = out[1].double().sum(0).abs().max().item()
+
+    # whole-graph mode on the same graph, for the record (not the headline)
+    for _ in range(2):
+        M.mlip_forward(g, W, M.MODE_WHOLE, out=out, want_atom_energy=False)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for _ in range(args.steps):
+        M.mlip_forward(g, W, M.MODE_WHOLE, out=out, want_atom_energy=False)
+    torch.cuda.synchronize()
+    dt_whole_fwd = (time.perf_counter() - t1) / args.steps
+    energy_whole = float(out[0].cpu()[0])
+
+    ms_step = dt / args.steps * 1e3
+    L = c["L"]
+    bwd_ms, bwd_n = prof["edge_bwd"]
+    flops_step = E * (FLOPS_BWD_EDGE * (L - 1) + FLOPS_BWD_EDGE_L0)
+    per_launch_flops = flops_step * args.steps / max(bwd_n, 1)
+    avg_ms = bwd_ms / max(bwd_n, 1)
+    achieved = per_launch_flops / (avg_ms * 1e-3) / 1e12 if avg_ms > 0 else 0.0
+    fwd_ms, fwd_n = prof["edge_fwd"]
+    fwd_tflops = E * FLOPS_FWD_EDGE * L * args.steps / (fwd_ms * 1e-3) / 1e12 if fwd_ms > 0 else 0.0
+
+    res = {
+        "metric": "atoms/s (energy+forces)", "value": N / (dt / args.steps), "unit": "atoms/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": c["name"] + f", {N} atoms, {E} directed edges, r_cut 5.0, F={c['F']} L={L} K=8, "
+                               f"graph build + {P}-slab sequential energy+forces", "n_slabs": P},
+        "edges_per_s": E / (dt / args.steps),
+        "us_per_atom_step": ms_step * 1e3 / N,
+        "breakdown_ms_per_step": {k: v[0] / args.steps for k, v in prof.items()},
+        "whole_graph_forward_ms": dt_whole_fwd * 1e3,
+        "whole_graph_atoms_per_s_excl_graph": N / dt_whole_fwd,
+        "energy": energy, "energy_whole": energy_whole, "net_force_max_component": fsum,
+        "roofline": {"kernel": "k_edge_bwd<64> (reverse edge step)", "bound": "mfma", "achieved": achieved,
+                     "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
+                     "traffic": None, "avg_launch_ms": avg_ms, "launches": int(bwd_n),
+                     "flops_per_launch": per_launch_flops},
+        "roofline_edge_fwd": {"kernel": "k_edge_fwd<64>", "bound": "mfma", "achieved": fwd_tflops,
+                              "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+                              "frac": fwd_tflops / PEAK_FP32_MFMA_TFLOPS,
+                              "avg_launch_ms": fwd_ms / max(fwd_n, 1), "launches": int(fwd_n)},
+    }
+    if not args.no_cpu:
+        res["cpu_baseline"] = cpu_baseline(args.config, args.cpu_cells)
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

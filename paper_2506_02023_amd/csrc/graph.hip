@@ -305,7 +305,7 @@ __global__ void k_neighbours(int64_t N, CellParams cp, const int32_t *__restrict
 constexpr int kRowLds = 512;
 __global__ void __launch_bounds__(64)
 k_sort_rows(int64_t N, CellParams cp, const double *__restrict__ pos, const int64_t *__restrict__ row_ptr,
-            const uint64_t *__restrict__ keys, int32_t *senders, uint32_t *shiftp, float *d)
+            const uint64_t *__restrict__ keys, int32_t *senders, int32_t *recv, uint32_t *shiftp, float *d)
 {
     __shared__ uint64_t lds[kRowLds];
     const int64_t i = blockIdx.x;
@@ -336,6 +336,7 @@ k_sort_rows(int64_t N, CellParams cp, const double *__restrict__ pos, const int6
         const double d2 = (t0 * t0 + t1 * t1) + t2 * t2;
         senders[e] = j;
         shiftp[e] = sp;
+        recv[e] = (int32_t)i;
         d[e] = (float)sqrt(d2);
     }
 }
@@ -450,7 +451,7 @@ k_local_fill(int64_t n_local, int64_t n_owned, const int32_t *__restrict__ nodes
              const int64_t *__restrict__ row_ptr, const int32_t *__restrict__ senders,
              const uint32_t *__restrict__ shiftp, const float *__restrict__ d,
              const int32_t *__restrict__ slab_of, const int32_t *__restrict__ local_of, int q,
-             const int64_t *__restrict__ lrow_ptr, int32_t *lsenders, uint32_t *lshiftp, float *ld)
+             const int64_t *__restrict__ lrow_ptr, int32_t *lsenders, int32_t *lrecv, uint32_t *lshiftp, float *ld)
 {
     const int64_t r = blockIdx.x;
     const int32_t u = nodes[r];
@@ -473,6 +474,7 @@ k_local_fill(int64_t n_local, int64_t n_owned, const int32_t *__restrict__ nodes
             if (o < out_end) {
                 lsenders[o] = local_of[j];
                 lshiftp[o] = shiftp[e];
+                lrecv[o] = (int32_t)r;
                 ld[o] = d[e];
             }
         }
@@ -631,6 +633,7 @@ int build_graph_impl(mlip_graph *g, const double *positions, const double *cell,
     MLIP_TRY(g->keys.ensure(Ecap * 8));
     MLIP_TRY(g->senders.ensure(Ecap * 4));
     MLIP_TRY(g->shiftp.ensure(Ecap * 4));
+    MLIP_TRY(g->recv.ensure(Ecap * 4));
     MLIP_TRY(g->d.ensure(Ecap * 4));
     k_neighbours<true><<<blocks_for(N, 128), 128, 0, s>>>(
         N, cp, g->cell_start.as<int32_t>(), g->sid.as<int32_t>(), g->sx.as<double>(), g->sy.as<double>(),
@@ -638,7 +641,7 @@ int build_graph_impl(mlip_graph *g, const double *positions, const double *cell,
         g->keys.as<uint64_t>(), err);
     MLIP_HIP(hipGetLastError());
     k_sort_rows<<<(unsigned)N, 64, 0, s>>>(N, cp, pos, g->row_ptr.as<int64_t>(), g->keys.as<uint64_t>(),
-                                           g->senders.as<int32_t>(), g->shiftp.as<uint32_t>(), g->d.as<float>());
+                                           g->senders.as<int32_t>(), g->recv.as<int32_t>(), g->shiftp.as<uint32_t>(), g->d.as<float>());
     MLIP_HIP(hipGetLastError());
 
     SlabView &W = g->whole;
@@ -649,6 +652,7 @@ int build_graph_impl(mlip_graph *g, const double *positions, const double *cell,
     W.row_ptr = g->row_ptr.as<int64_t>();
     W.senders = g->senders.as<int32_t>();
     W.shiftp = g->shiftp.as<uint32_t>();
+    W.recv = g->recv.as<int32_t>();
     W.d = g->d.as<float>();
     W.markers = {0, N, N, N};
 
@@ -714,18 +718,21 @@ int build_graph_impl(mlip_graph *g, const double *positions, const double *cell,
             const size_t ne = (size_t)std::max<int64_t>(v.n_edges, 1);
             MLIP_TRY(st.senders.ensure(ne * 4));
             MLIP_TRY(st.shiftp.ensure(ne * 4));
+            MLIP_TRY(st.recv.ensure(ne * 4));
             MLIP_TRY(st.d.ensure(ne * 4));
             if (v.n_local > 0) {
                 k_local_fill<<<(unsigned)v.n_local, 64, 0, s>>>(
                     v.n_local, v.n_owned, st.nodes.as<int32_t>(), g->row_ptr.as<int64_t>(), g->senders.as<int32_t>(),
                     g->shiftp.as<uint32_t>(), g->d.as<float>(), g->slab_of.as<int32_t>(), g->local_of.as<int32_t>(), q,
-                    st.row_ptr.as<int64_t>(), st.senders.as<int32_t>(), st.shiftp.as<uint32_t>(), st.d.as<float>());
+                    st.row_ptr.as<int64_t>(), st.senders.as<int32_t>(), st.recv.as<int32_t>(), st.shiftp.as<uint32_t>(),
+                    st.d.as<float>());
                 MLIP_HIP(hipGetLastError());
             }
             v.nodes = st.nodes.as<int32_t>();
             v.row_ptr = st.row_ptr.as<int64_t>();
             v.senders = st.senders.as<int32_t>();
             v.shiftp = st.shiftp.as<uint32_t>();
+            v.recv = st.recv.as<int32_t>();
             v.d = st.d.as<float>();
             v.ghost_owner = st.ghost_owner.as<int32_t>();
             v.ghost_src = st.ghost_src.as<int32_t>();

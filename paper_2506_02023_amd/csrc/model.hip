@@ -65,13 +65,18 @@ template <bool DERIV>
 __device__ inline void radial_basis(float d, const BasisParams &bp, float (&b)[8], float (&db)[8])
 {
     float x = fminf(d * bp.inv_rc, 1.0f);
-    float s1, c1v;
-    sincospif(x, &s1, &c1v);
+    // sin(pi x), cos(pi x) on [0,1]: with z = pi (x - 1/2) in [-pi/2, pi/2], sin(pi x) = cos z and
+    // cos(pi x) = -sin z; Taylor polynomials to z^12 / z^13 (truncation below 1e-8)
+    const float z = kPi * (x - 0.5f), z2 = z * z;
+    float s1 = 1.0f + z2 * (-0.5f + z2 * (4.16666667e-2f + z2 * (-1.38888889e-3f + z2 * (2.48015873e-5f +
+               z2 * (-2.75573192e-7f + z2 * 2.08767570e-9f)))));
+    float c1v = -z * (1.0f + z2 * (-1.66666667e-1f + z2 * (8.33333333e-3f + z2 * (-1.98412698e-4f +
+                z2 * (2.75573192e-6f + z2 * (-2.50521084e-8f + z2 * 1.60590438e-10f))))));
     float xpm1 = 1.0f;
     for (int k = 0; k < bp.p - 1; ++k) xpm1 *= x;
     const float xp = xpm1 * x;
     const float u = 1.0f - xp * (bp.c0 - x * (bp.c1 - bp.c2 * x));
-    const float inv_d = 1.0f / d;
+    const float inv_d = __builtin_amdgcn_rcpf(d);
     float du_term = 0.f;  // u'/rc - u/d
     if (DERIV) {
         const float du = -xpm1 * (bp.pc0 - x * (bp.pc1 - bp.pc2 * x));
@@ -147,13 +152,72 @@ __device__ inline void gemm_regs(const float *__restrict__ Ap, const f32x16 (&in
             }
 }
 
-// same product with the B operand read from an item-major LDS tile [32][FS]
+// same product with the B operand read from an item-major LDS tile [32][FS]; A and B operand
+// loads of step k+1 are issued before the MFMAs of step k
 template <int F>
 __device__ inline void gemm_lds(const float *__restrict__ Ap, const float *tile, f32x16 (&out)[Dims<F>::NB], int lane)
 {
     constexpr int NB = Dims<F>::NB;
     constexpr int FS = Dims<F>::FS;
+    constexpr int STEPS = NB * 4;
     const int c32 = lane & 31, h = lane >> 5;
+#pragma unroll
+    for (int bo = 0; bo < NB; ++bo)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) out[bo][r] = 0.f;
+    const float *bp = tile + c32 * FS + 4 * h;
+    const float *ap = Ap + lane * 4;
+    f32x4 bv = *reinterpret_cast<const f32x4 *>(bp);
+    f32x4 av[NB];
+#pragma unroll
+    for (int bo = 0; bo < NB; ++bo) av[bo] = *reinterpret_cast<const f32x4 *>(ap + ((bo * NB) * 4) * 256);
+#pragma unroll
+    for (int st = 0; st < STEPS; ++st) {
+        f32x4 bn = bv, an[NB];
+#pragma unroll
+        for (int bo = 0; bo < NB; ++bo) an[bo] = av[bo];
+        if (st + 1 < STEPS) {
+            const int bi = (st + 1) / 4, a = (st + 1) % 4;
+            bn = *reinterpret_cast<const f32x4 *>(bp + 32 * bi + 8 * a);
+#pragma unroll
+            for (int bo = 0; bo < NB; ++bo)
+                an[bo] = *reinterpret_cast<const f32x4 *>(ap + (((bo * NB + bi) * 4 + a)) * 256);
+        }
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+#pragma unroll
+            for (int bo = 0; bo < NB; ++bo)
+                out[bo] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[bo][c], bv[c], out[bo], 0, 0, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, NB + 1, 0);  // the next step's LDS reads first
+        __builtin_amdgcn_sched_group_barrier(0x008, 4 * NB, 0);  // then this step's MFMAs
+        bv = bn;
+#pragma unroll
+        for (int bo = 0; bo < NB; ++bo) av[bo] = an[bo];
+    }
+}
+
+// A operands of an F x F matrix held in registers (one f32x4 per (bo, bi, a))
+template <int F> struct RegPack {
+    f32x4 v[Dims<F>::NB][Dims<F>::NB][4];
+};
+
+template <int F> __device__ inline void load_pack(RegPack<F> &P, const float *__restrict__ Ap, int lane)
+{
+    constexpr int NB = Dims<F>::NB;
+#pragma unroll
+    for (int bo = 0; bo < NB; ++bo)
+#pragma unroll
+        for (int bi = 0; bi < NB; ++bi)
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+                P.v[bo][bi][a] = *reinterpret_cast<const f32x4 *>(Ap + ((((bo * NB + bi) * 4 + a) * 64 + lane) * 4));
+}
+
+// chained product with register-resident weights; consecutive MFMAs alternate accumulators
+template <int F>
+__device__ inline void gemm_rr(const RegPack<F> &P, const f32x16 (&in)[Dims<F>::NB], f32x16 (&out)[Dims<F>::NB])
+{
+    constexpr int NB = Dims<F>::NB;
 #pragma unroll
     for (int bo = 0; bo < NB; ++bo)
 #pragma unroll
@@ -161,16 +225,82 @@ __device__ inline void gemm_lds(const float *__restrict__ Ap, const float *tile,
 #pragma unroll
     for (int bi = 0; bi < NB; ++bi)
 #pragma unroll
-        for (int a = 0; a < 4; ++a) {
-            const f32x4 bv = *reinterpret_cast<const f32x4 *>(tile + c32 * FS + 32 * bi + 8 * a + 4 * h);
+        for (int a = 0; a < 4; ++a)
 #pragma unroll
-            for (int bo = 0; bo < NB; ++bo) {
-                const f32x4 av = *reinterpret_cast<const f32x4 *>(Ap + ((((bo * NB + bi) * 4 + a) * 64 + lane) * 4));
+            for (int c = 0; c < 4; ++c)
 #pragma unroll
-                for (int c = 0; c < 4; ++c)
-                    out[bo] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[c], bv[c], out[bo], 0, 0, 0);
-            }
+                for (int bo = 0; bo < NB; ++bo)
+                    out[bo] = __builtin_amdgcn_mfma_f32_32x32x2f32(P.v[bo][bi][a][c], in[bi][4 * a + c], out[bo], 0, 0, 0);
+}
+
+// chained product with the weights in LDS (packed A operands), B operand in registers; the A
+// operands of step k+1 are fetched while the MFMAs of step k run
+template <int F>
+__device__ inline void gemm_rl(const float *__restrict__ Ap, const f32x16 (&in)[Dims<F>::NB],
+                               f32x16 (&out)[Dims<F>::NB], int lane)
+{
+    constexpr int NB = Dims<F>::NB;
+    constexpr int STEPS = NB * 4;
+#pragma unroll
+    for (int bo = 0; bo < NB; ++bo)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) out[bo][r] = 0.f;
+    const float *ap = Ap + lane * 4;
+    f32x4 av[NB];
+#pragma unroll
+    for (int bo = 0; bo < NB; ++bo) av[bo] = *reinterpret_cast<const f32x4 *>(ap + ((bo * NB) * 4) * 256);
+#pragma unroll
+    for (int st = 0; st < STEPS; ++st) {
+        const int bi = st / 4, a = st % 4;
+        f32x4 an[NB];
+#pragma unroll
+        for (int bo = 0; bo < NB; ++bo) an[bo] = av[bo];
+        if (st + 1 < STEPS) {
+            const int bi2 = (st + 1) / 4, a2 = (st + 1) % 4;
+#pragma unroll
+            for (int bo = 0; bo < NB; ++bo)
+                an[bo] = *reinterpret_cast<const f32x4 *>(ap + (((bo * NB + bi2) * 4 + a2)) * 256);
         }
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+#pragma unroll
+            for (int bo = 0; bo < NB; ++bo)
+                out[bo] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[bo][c], in[bi][4 * a + c], out[bo], 0, 0, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, NB, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 4 * NB, 0);
+#pragma unroll
+        for (int bo = 0; bo < NB; ++bo) av[bo] = an[bo];
+    }
+}
+
+template <int F> struct RegPack1 {
+    float v[Dims<F>::NB][4];
+};
+
+template <int F> __device__ inline void load_pack1(RegPack1<F> &P, const float *__restrict__ A1, int lane)
+{
+#pragma unroll
+    for (int bo = 0; bo < Dims<F>::NB; ++bo)
+#pragma unroll
+        for (int s = 0; s < 4; ++s) P.v[bo][s] = A1[(bo * 4 + s) * 64 + lane];
+}
+
+template <int F>
+__device__ inline void gemm_k8r(const RegPack1<F> &P, const float (&v)[8], f32x16 (&out)[Dims<F>::NB], int lane)
+{
+    constexpr int NB = Dims<F>::NB;
+    const int h = lane >> 5;
+#pragma unroll
+    for (int bo = 0; bo < NB; ++bo)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) out[bo][r] = 0.f;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        const float bv = h ? v[2 * s + 1] : v[2 * s];
+#pragma unroll
+        for (int bo = 0; bo < NB; ++bo)
+            out[bo] = __builtin_amdgcn_mfma_f32_32x32x2f32(P.v[bo][s], bv, out[bo], 0, 0, 0);
+    }
 }
 
 // out[f][item] = sum_n W1[n][f] v[n][item], v = 8 per-lane values of the lane's item
@@ -225,6 +355,7 @@ struct EdgeArgs {
     int64_t n_chunks;
     const int64_t *row_ptr;
     const int32_t *senders;
+    const int32_t *recv;       // receiver row of every edge
     const float *d;
     const float *g;            // [n_local][F]
     const float *abar;         // reverse: [n_local][F] (ghost rows zero)
@@ -244,86 +375,113 @@ __device__ inline bool chunk_rows(const EdgeArgs &A, int64_t chunk, int64_t &r0,
     return r0 < r1;
 }
 
+// Per-tile row bookkeeping shared by both edge kernels.  Every lane holds the receiver of its edge
+// (rk, the sentinel r1 for lanes past the end of the chunk); the receiver of the following edge
+// comes from the neighbouring lane or, for lane 31, from the next tile.  Bit k of the returned mask
+// says "edge k is the last edge of its row"; it is wave-uniform, so the flush is a scalar branch.
+__device__ inline uint32_t row_ends(int32_t rk, int32_t rn_first, bool valid, int lane, int32_t &rnext)
+{
+    const int32_t up = __shfl(rk, (lane & 31) + 1, 64);
+    rnext = ((lane & 31) == 31) ? rn_first : up;
+    return (uint32_t)__ballot(valid && rnext != rk);
+}
+
 template <int F>
-__global__ void __launch_bounds__(256) k_edge_fwd(EdgeArgs A)
+__global__ void __launch_bounds__(256, 2) k_edge_fwd(EdgeArgs A)
 {
     using D = Dims<F>;
     extern __shared__ float lds[];
-    float *A1 = lds;
-    float *A2 = A1 + D::PACK1;
-    float *tiles = A2 + D::PACKF;
-    for (int i = threadIdx.x; i < D::PACK1; i += 256) A1[i] = A.A1[i];
-    for (int i = threadIdx.x; i < D::PACKF; i += 256) A2[i] = A.A2t[i];
-    __syncthreads();
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int c32 = lane & 31;
     const int f = lane & (F - 1);
-    float *tile = tiles + wave * D::TILE;
+    float *tile = lds + wave * D::TILE;
     const int64_t chunk = (int64_t)blockIdx.x * 4 + wave;
     if (chunk >= A.n_chunks) return;
     int64_t r0, r1;
     if (!chunk_rows(A, chunk, r0, r1)) return;
+    RegPack<F> W2;   // filter weights stay in registers for the whole chunk
+    RegPack1<F> W1;
+    load_pack<F>(W2, A.A2t, lane);
+    load_pack1<F>(W1, A.A1, lane);
     const int64_t e_lo = A.row_ptr[r0], e_hi = A.row_ptr[r1];
-    int64_t cur = r0;
-    int64_t row_end = A.row_ptr[r0 + 1];
+    const int32_t r_end = (int32_t)r1;
     float acc = 0.f;
+    // edge data of the first tile; d = rc gives a zero filter, receiver r1 is the end sentinel
+    float dv = (e_lo + c32 < e_hi) ? A.d[e_lo + c32] : A.bp.rc;
+    int32_t j = (e_lo + c32 < e_hi) ? A.senders[e_lo + c32] : 0;
+    int32_t rk = (e_lo + c32 < e_hi) ? A.recv[e_lo + c32] : r_end;
+    {   // rows of the chunk before its first edge are empty
+        const int32_t first = __builtin_amdgcn_readfirstlane(rk);
+        for (int64_t r = r0; r < first; ++r)
+            if (lane < F) A.out[r * F + f] = 0.f;
+    }
     for (int64_t tb = e_lo; tb < e_hi; tb += 32) {
-        const int64_t e = tb + c32;
-        const bool valid = e < e_hi;
-        const float dv = valid ? A.d[e] : A.bp.rc;  // d = rc gives a zero filter
-        const int32_t j = valid ? A.senders[e] : 0;
+        const bool valid = tb + c32 < e_hi;
         float b[8], db[8];
         radial_basis<false>(dv, A.bp, b, db);
-        f32x16 t[D::NB], w[D::NB];
-        gemm_k8<F>(A1, b, t, lane);
-#pragma unroll
-        for (int bb = 0; bb < D::NB; ++bb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) t[bb][r] = t[bb][r] * sigmoidf_fast(t[bb][r]);
-        gemm_regs<F>(A2, t, w, lane);
-        regs_to_tile<F>(w, tile, lane);
-        wave_lds_fence();
+        // sender rows of this tile: issued now, consumed after the MFMA chain
         float gv[32];
 #pragma unroll
         for (int k = 0; k < 32; ++k) {
             const int32_t jk = __builtin_amdgcn_readlane(j, k);
             gv[k] = A.g[(int64_t)jk * F + f];
         }
+        const int32_t rcur = rk;
+        {   // next tile's edge data
+            const int64_t en = tb + 32 + c32;
+            dv = (en < e_hi) ? A.d[en] : A.bp.rc;
+            j = (en < e_hi) ? A.senders[en] : 0;
+            rk = (en < e_hi) ? A.recv[en] : r_end;
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        f32x16 t[D::NB], w[D::NB];
+        gemm_k8r<F>(W1, b, t, lane);
+#pragma unroll
+        for (int bb = 0; bb < D::NB; ++bb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) t[bb][r] = t[bb][r] * sigmoidf_fast(t[bb][r]);
+        gemm_rr<F>(W2, t, w);
+        regs_to_tile<F>(w, tile, lane);
+        wave_lds_fence();
+        __builtin_amdgcn_sched_barrier(0);  // keep the use of the prefetched receiver after the MFMA chain
+        int32_t rnext;
+        const uint32_t ends = row_ends(rcur, __builtin_amdgcn_readfirstlane(rk), valid, lane, rnext);
+        float wv[32];
+#pragma unroll
+        for (int k = 0; k < 32; ++k) wv[k] = tile[k * D::FS + f];
 #pragma unroll
         for (int k = 0; k < 32; ++k) {
-            const int64_t e2 = tb + k;
-            if (e2 < e_hi) {
-                while (e2 >= row_end) {
-                    if (lane < F) A.out[cur * F + f] = acc;
-                    acc = 0.f;
-                    ++cur;
-                    row_end = A.row_ptr[cur + 1];
-                }
-                acc += tile[k * D::FS + f] * gv[k];
+            acc = fmaf(wv[k], gv[k], acc);   // lanes past the end hold a zero filter
+            if (ends & (1u << k)) {
+                const int32_t row = __builtin_amdgcn_readlane(rcur, k);
+                const int32_t nrow = __builtin_amdgcn_readlane(rnext, k);
+                if (lane < F) A.out[(int64_t)row * F + f] = acc;
+                acc = 0.f;
+                for (int64_t r = (int64_t)row + 1; r < nrow; ++r)   // empty rows in between
+                    if (lane < F) A.out[r * F + f] = 0.f;
             }
         }
         wave_lds_fence();
+        // retire the prefetched edge data here (it arrived long ago); a load left pending across
+        // the loop edge would make the compiler wait for all loads, gathers included, at the top
+        asm volatile("" : "+v"(dv), "+v"(j), "+v"(rk));
     }
-    while (cur < r1) {
-        if (lane < F) A.out[cur * F + f] = acc;
-        acc = 0.f;
-        ++cur;
-    }
+    if (e_lo >= e_hi)
+        for (int64_t r = r0; r < r1; ++r)
+            if (lane < F) A.out[r * F + f] = 0.f;
 }
 
 template <int F>
-__global__ void __launch_bounds__(256) k_edge_bwd(EdgeArgs A)
+__global__ void __launch_bounds__(256, 2) k_edge_bwd(EdgeArgs A)
 {
     using D = Dims<F>;
     extern __shared__ float lds[];
-    float *A1 = lds;
-    float *A2t = A1 + D::PACK1;
-    float *A2n = A2t + D::PACKF;
-    float *tiles = A2n + D::PACKF;
-    for (int i = threadIdx.x; i < D::PACK1; i += 256) A1[i] = A.A1[i];
-    for (int i = threadIdx.x; i < D::PACKF; i += 256) { A2t[i] = A.A2t[i]; A2n[i] = A.A2n[i]; }
+    float *A2n = lds;
+    float *A2t = A2n + D::PACKF;
+    float *tiles = A2t + D::PACKF;
+    for (int i = threadIdx.x; i < D::PACKF; i += 256) { A2n[i] = A.A2n[i]; A2t[i] = A.A2t[i]; }
     __syncthreads();
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int c32 = lane & 31;
     const int f = lane & (F - 1);
     float *tile = tiles + wave * D::TILE;
@@ -331,20 +489,45 @@ __global__ void __launch_bounds__(256) k_edge_bwd(EdgeArgs A)
     if (chunk >= A.n_chunks) return;
     int64_t r0, r1;
     if (!chunk_rows(A, chunk, r0, r1)) return;
+    RegPack1<F> W1;
+    load_pack1<F>(W1, A.A1, lane);
     const int64_t e_lo = A.row_ptr[r0], e_hi = A.row_ptr[r1];
-    int64_t cur = r0;
-    int64_t row_end = A.row_ptr[r0 + 1];
-    float ai = A.abar[cur * F + f], gi = A.g[cur * F + f];
+    const int32_t r_end = (int32_t)r1;
+    const int64_t last_row = A.n_rows - 1;
     float acc = 0.f;
+    float dv = (e_lo + c32 < e_hi) ? A.d[e_lo + c32] : A.bp.rc;
+    int32_t j = (e_lo + c32 < e_hi) ? A.senders[e_lo + c32] : 0;
+    int32_t rk = (e_lo + c32 < e_hi) ? A.recv[e_lo + c32] : r_end;
+    int64_t row = min((int64_t)__builtin_amdgcn_readfirstlane(rk), last_row);  // row of the first edge
+    if (A.need_gbar)
+        for (int64_t r = r0; r < min((int64_t)__builtin_amdgcn_readfirstlane(rk), r1); ++r)
+            if (lane < F) A.out[r * F + f] = 0.f;
+    // receiver-side rows of the current row and, prefetched, of the row after it
+    float ai = A.abar[row * F + f], gi = A.g[row * F + f];
+    float ai2 = A.abar[min(row + 1, last_row) * F + f], gi2 = A.g[min(row + 1, last_row) * F + f];
     for (int64_t tb = e_lo; tb < e_hi; tb += 32) {
         const int64_t e = tb + c32;
         const bool valid = e < e_hi;
-        const float dv = valid ? A.d[e] : A.bp.rc;
-        const int32_t j = valid ? A.senders[e] : 0;
+        const int32_t jt = j, rcur = rk;
         float b[8], db[8];
         radial_basis<true>(dv, A.bp, b, db);
+        // first half of the sender rows (abar_j, g_j): in flight during the MFMA chain
+        float av[16], gv[16];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            const int32_t jk = __builtin_amdgcn_readlane(jt, k);
+            av[k] = A.abar[(int64_t)jk * F + f];
+            gv[k] = A.g[(int64_t)jk * F + f];
+        }
+        {
+            const int64_t en = tb + 32 + c32;
+            dv = (en < e_hi) ? A.d[en] : A.bp.rc;
+            j = (en < e_hi) ? A.senders[en] : 0;
+            rk = (en < e_hi) ? A.recv[en] : r_end;
+        }
+        __builtin_amdgcn_sched_barrier(0);
         f32x16 t[D::NB], sp[D::NB];
-        gemm_k8<F>(A1, b, t, lane);
+        gemm_k8r<F>(W1, b, t, lane);
 #pragma unroll
         for (int bb = 0; bb < D::NB; ++bb)
 #pragma unroll
@@ -356,40 +539,66 @@ __global__ void __launch_bounds__(256) k_edge_bwd(EdgeArgs A)
             }
         if (A.need_gbar) {
             f32x16 w[D::NB];
-            gemm_regs<F>(A2t, t, w, lane);
+            gemm_rl<F>(A2t, t, w, lane);
             regs_to_tile<F>(w, tile, lane);
         }
         wave_lds_fence();
-        // lane = feature: gather abar_j, g_j; accumulate gbar_i; leave abar_i*g_j + abar_j*g_i in the tile
-        float av[32], gv[32];
+        __builtin_amdgcn_sched_barrier(0);  // keep the use of the prefetched receiver after the MFMA chain
+        int32_t rnext;
+        const uint32_t ends = row_ends(rcur, __builtin_amdgcn_readfirstlane(rk), valid, lane, rnext);
+        // lane = feature: accumulate gbar_i; leave abar_i*g_j + abar_j*g_i in the tile
 #pragma unroll
-        for (int k = 0; k < 32; ++k) {
-            const int32_t jk = __builtin_amdgcn_readlane(j, k);
-            av[k] = A.abar[(int64_t)jk * F + f];
-            gv[k] = A.g[(int64_t)jk * F + f];
-        }
+        for (int half = 0; half < 2; ++half) {
+            float av2[16], gv2[16], wv[16], ws[16];
+            if (half == 0) {
 #pragma unroll
-        for (int k = 0; k < 32; ++k) {
-            const int64_t e2 = tb + k;
-            float wsym = 0.f;
-            if (e2 < e_hi) {
-                while (e2 >= row_end) {
-                    if (A.need_gbar && lane < F) A.out[cur * F + f] = acc;
-                    acc = 0.f;
-                    ++cur;
-                    row_end = A.row_ptr[cur + 1];
-                    ai = A.abar[cur * F + f];
-                    gi = A.g[cur * F + f];
+                for (int k = 0; k < 16; ++k) {  // second half of the sender rows
+                    const int32_t jk = __builtin_amdgcn_readlane(jt, 16 + k);
+                    av2[k] = A.abar[(int64_t)jk * F + f];
+                    gv2[k] = A.g[(int64_t)jk * F + f];
                 }
-                if (A.need_gbar) acc += tile[k * D::FS + f] * av[k];
-                wsym = ai * gv[k] + av[k] * gi;
             }
-            if (lane < F) tile[k * D::FS + f] = wsym;
+#pragma unroll
+            for (int kk = 0; kk < 16; ++kk) wv[kk] = A.need_gbar ? tile[(half * 16 + kk) * D::FS + f] : 0.f;
+#pragma unroll
+            for (int kk = 0; kk < 16; ++kk) {
+                const int k = half * 16 + kk;
+                acc = fmaf(wv[kk], av[kk], acc);
+                ws[kk] = ai * gv[kk] + av[kk] * gi;
+                if (ends & (1u << k)) {
+                    const int64_t rrow = __builtin_amdgcn_readlane(rcur, k);
+                    const int64_t nrow = __builtin_amdgcn_readlane(rnext, k);
+                    if (A.need_gbar) {
+                        if (lane < F) A.out[rrow * F + f] = acc;
+                        for (int64_t r = rrow + 1; r < nrow; ++r)
+                            if (lane < F) A.out[r * F + f] = 0.f;
+                    }
+                    acc = 0.f;
+                    if (nrow < r1) {   // move to the row of the next edge
+                        if (nrow == rrow + 1) {
+                            ai = ai2;
+                            gi = gi2;
+                        } else {
+                            ai = A.abar[nrow * F + f];
+                            gi = A.g[nrow * F + f];
+                        }
+                        ai2 = A.abar[min(nrow + 1, last_row) * F + f];
+                        gi2 = A.g[min(nrow + 1, last_row) * F + f];
+                    }
+                }
+            }
+#pragma unroll
+            for (int kk = 0; kk < 16; ++kk)
+                if (lane < F) tile[(half * 16 + kk) * D::FS + f] = ws[kk];
+            if (half == 0) {
+#pragma unroll
+                for (int k = 0; k < 16; ++k) { av[k] = av2[k]; gv[k] = gv2[k]; }
+            }
         }
         wave_lds_fence();
         f32x16 sb[D::NB], cg[D::NB];
+        gemm_k8r<F>(W1, db, cg, lane);      // c[k] = sum_n W1[n][k] db_n/dd
         gemm_lds<F>(A2n, tile, sb, lane);   // sbar[k] = sum_f W2[k][f] wsym[f]
-        gemm_k8<F>(A1, db, cg, lane);       // c[k] = sum_n W1[n][k] db_n/dd
         float part = 0.f;
 #pragma unroll
         for (int bb = 0; bb < D::NB; ++bb)
@@ -398,12 +607,11 @@ __global__ void __launch_bounds__(256) k_edge_bwd(EdgeArgs A)
         part += __shfl_xor(part, 32, 64);
         if (valid && lane < 32) A.dsum[e] = A.first ? part : A.dsum[e] + part;
         wave_lds_fence();
+        asm volatile("" : "+v"(dv), "+v"(j), "+v"(rk), "+v"(ai2), "+v"(gi2));  // no load pending across the loop edge
     }
-    while (cur < r1) {
-        if (A.need_gbar && lane < F) A.out[cur * F + f] = acc;
-        acc = 0.f;
-        ++cur;
-    }
+    if (e_lo >= e_hi && A.need_gbar)
+        for (int64_t r = r0; r < r1; ++r)
+            if (lane < F) A.out[r * F + f] = 0.f;
 }
 
 // ---------------------------------------------------------------- node kernels
@@ -450,7 +658,7 @@ __global__ void __launch_bounds__(256) k_node(NodeArgs A)
         if (TWO) P2[i] = A.P2[i];
     }
     __syncthreads();
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int c32 = lane & 31, h = lane >> 5;
     float *tile = tiles + wave * D::TILE;
     const int64_t n_tiles = (A.n_rows + 31) / 32;
@@ -715,8 +923,8 @@ Packs pack_layout(int F, int L)
 
 template <int F> struct Lds {
     using D = Dims<F>;
-    static constexpr size_t edge_fwd = sizeof(float) * (D::PACK1 + D::PACKF + 4 * D::TILE);
-    static constexpr size_t edge_bwd = sizeof(float) * (D::PACK1 + 2 * D::PACKF + 4 * D::TILE);
+    static constexpr size_t edge_fwd = sizeof(float) * (4 * D::TILE);
+    static constexpr size_t edge_bwd = sizeof(float) * (2 * D::PACKF + 4 * D::TILE);
     static constexpr size_t node1 = sizeof(float) * (D::PACKF + 4 * D::TILE);
     static constexpr size_t node2 = sizeof(float) * (2 * D::PACKF + 4 * D::TILE);
 };
@@ -872,6 +1080,7 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, int32_t mode, double *ener
             ea.n_chunks = std::max<int64_t>(1, (v.n_edges_owned + kChunkEdges - 1) / kChunkEdges);
             ea.row_ptr = v.row_ptr;
             ea.senders = v.senders;
+            ea.recv = v.recv;
             ea.d = v.d;
             ea.g = gslice(v, l);
             ea.out = aslice(v, l);
@@ -951,6 +1160,7 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, int32_t mode, double *ener
             ea.n_chunks = std::max<int64_t>(1, (v.n_edges + kChunkEdges - 1) / kChunkEdges);
             ea.row_ptr = v.row_ptr;
             ea.senders = v.senders;
+            ea.recv = v.recv;
             ea.d = v.d;
             ea.g = gslice(v, l);
             ea.abar = v.abar.as<float>();

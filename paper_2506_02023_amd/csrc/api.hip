@@ -25,7 +25,7 @@ int DevBuf::ensure(size_t bytes)
     hipError_t e = hipMalloc(&np, want);
     if (e != hipSuccess) {
         (void)hipGetLastError();
-        want = bytes;
+        want = bytes + 256;  // kernels may read (never use) up to 128 bytes past the end of index arrays
         e = hipMalloc(&np, want);
     }
     if (e != hipSuccess) {
@@ -173,7 +173,7 @@ void mlip_graph_destroy(mlip_graph_t *g)
                       &g->local_of, &g->local_in_owner, &g->class_cnt, &g->class_off, &g->wpack, &g->energy_part};
     for (DevBuf *b : bufs) b->release();
     auto drop_view = [](SlabView &v) {
-        DevBuf *vb[] = {&v.h, &v.hbar, &v.abar, &v.gbar, &v.eps, &v.dsum, &v.floc, &v.g, &v.a};
+        DevBuf *vb[] = {&v.h, &v.hbar, &v.abar, &v.gbar, &v.eps, &v.dsum, &v.floc, &v.g, &v.a, &v.wst};
         for (DevBuf *b : vb) b->release();
     };
     drop_view(g->whole);

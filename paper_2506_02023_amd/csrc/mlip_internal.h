@@ -65,7 +65,7 @@ struct SlabView {
     const int32_t *ghost_src = nullptr;    // [n_ghost] local index inside the owner
     std::vector<int64_t> markers;          // host, P + 3
     // model workspace (sized in mlip_forward)
-    DevBuf h, hbar, abar, gbar, eps, dsum, floc, g, a;  // g and a hold L slices each
+    DevBuf h, hbar, abar, gbar, eps, dsum, floc, g, a, wst;  // g and a hold L slices each, wst L - 1
 };
 
 struct SlabStore {  // device arrays owned per slab

@@ -41,6 +41,7 @@ namespace {
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
+constexpr int kBufferFlags = 0x00020000;  // raw 32-bit buffer descriptor word 3 on gfx9-family targets
 constexpr int kChunkEdges = 1024;  // edges per wavefront work item (32 tiles of 32)
 constexpr float kPi = 3.14159265358979323846f;
 
@@ -54,6 +55,13 @@ __device__ inline void wave_lds_fence()
 }
 
 __device__ inline float sigmoidf_fast(float x) { return __builtin_amdgcn_rcpf(1.0f + __expf(-x)); }
+
+// The edge kernels evaluate SiLU on pre-scaled pre-activations t' = c t with c = -log2(e):
+// sigmoid(t) = 1 / (1 + 2^t'), so the scaling multiply disappears (c is folded into the packed W1,
+// 1/c into the packed W2 that consumes s' = c SiLU(t)).
+constexpr float kSiluScale = -1.4426950408889634f;
+constexpr float kSiluScaleInv = -0.6931471805599453f;
+__device__ inline float sigmoid_scaled(float tp) { return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(tp)); }
 
 struct BasisParams {
     float rc, inv_rc, c0, c1, c2, pc0, pc1, pc2;  // envelope coefficients and those of its derivative
@@ -100,7 +108,7 @@ __device__ inline void radial_basis(float d, const BasisParams &bp, float (&b)[8
 // with M[o][k] = W[k][o] (TRANS, y = x W) or W[o][k] (y = x W^T).
 // pack_w1: K = 8 rows, index ((bo * 4 + s) * 64 + lane) -> W1[2 s + lane / 32][32 bo + lane % 32].
 
-__global__ void k_pack_ff(const float *__restrict__ W, int F, int trans, float *__restrict__ out)
+__global__ void k_pack_ff(const float *__restrict__ W, int F, int trans, float scale, float *__restrict__ out)
 {
     const int idx = blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= F * F) return;
@@ -109,16 +117,16 @@ __global__ void k_pack_ff(const float *__restrict__ W, int F, int trans, float *
     const int bi = bb % NB, bo = bb / NB;
     const int o = 32 * bo + (lane & 31);
     const int k = 32 * bi + 8 * a + 4 * (lane >> 5) + c;
-    out[idx] = trans ? W[k * F + o] : W[o * F + k];
+    out[idx] = scale * (trans ? W[k * F + o] : W[o * F + k]);
 }
 
-__global__ void k_pack_w1(const float *__restrict__ W1, int F, float *__restrict__ out)
+__global__ void k_pack_w1(const float *__restrict__ W1, int F, float scale, float *__restrict__ out)
 {
     const int idx = blockIdx.x * blockDim.x + threadIdx.x;
     const int NB = F / 32;
     if (idx >= NB * 4 * 64) return;
     const int lane = idx & 63, s = (idx >> 6) & 3, bo = idx >> 8;
-    out[idx] = W1[(2 * s + (lane >> 5)) * F + 32 * bo + (lane & 31)];
+    out[idx] = scale * W1[(2 * s + (lane >> 5)) * F + 32 * bo + (lane & 31)];
 }
 
 template <int F> struct Dims {
@@ -361,7 +369,10 @@ struct EdgeArgs {
     const float *abar;         // reverse: [n_local][F] (ghost rows zero)
     float *out;                // forward: a [n_rows][F]; reverse: gbar [n_rows][F]
     float *dsum;               // reverse: per-edge dE/dd of the edge and its mirror, summed over layers
-    const float *A1, *A2t, *A2n;
+    float *wstore;             // forward: filter values w_e [n_stored][F] kept for the reverse pass (or null)
+    int64_t n_stored;          // reverse: edges [0, n_stored) have their w_e in wstore
+    int64_t n_nodes;           // rows of g / abar (n_local)
+    const float *A1, *A1s, *A2t, *A2n;   // A1s = c W1, A2t = W2 / c (see kSiluScale), A1 and A2n unscaled
     BasisParams bp;
     int need_gbar, first;
 };
@@ -373,6 +384,26 @@ __device__ inline bool chunk_rows(const EdgeArgs &A, int64_t chunk, int64_t &r0,
     r0 = lower_bound_i64(A.row_ptr, A.n_rows, lo);
     r1 = (chunk == A.n_chunks - 1) ? A.n_rows : lower_bound_i64(A.row_ptr, A.n_rows, lo + kChunkEdges);
     return r0 < r1;
+}
+
+// 32-bit buffer accesses: per-lane byte offset in a VGPR, wave-uniform byte offset in an SGPR, no
+// vector address arithmetic; accesses outside the descriptor's range read 0 / are dropped.
+__device__ inline float buffer_load_f32(__amdgpu_buffer_rsrc_t r, unsigned voff, int soff, int)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, voff, soff, 0));
+}
+__device__ inline void buffer_store_f32(float v, __amdgpu_buffer_rsrc_t r, unsigned voff, int soff, int)
+{
+    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), r, voff, soff, 0);
+}
+
+// Read-only graph arrays are read through the constant address space when the index is
+// wave-uniform: the load then goes through the scalar cache into SGPRs and costs no vector issue slot.
+// (Valid because no kernel of this file writes the graph arrays.)
+typedef const __attribute__((address_space(4))) int32_t *const_i32_ptr;
+__device__ inline int32_t uniform_load(const int32_t *p, int64_t i)
+{
+    return reinterpret_cast<const_i32_ptr>(reinterpret_cast<uintptr_t>(p))[i];
 }
 
 // Per-tile row bookkeeping shared by both edge kernels.  Every lane holds the receiver of its edge
@@ -387,50 +418,57 @@ __device__ inline uint32_t row_ends(int32_t rk, int32_t rn_first, bool valid, in
 }
 
 template <int F>
-__global__ void __launch_bounds__(256, 2) k_edge_fwd(EdgeArgs A)
+__global__ void __launch_bounds__(256, 3) k_edge_fwd(EdgeArgs A)
 {
     using D = Dims<F>;
     extern __shared__ float lds[];
+    float *A2t = lds;
+    float *tiles = A2t + D::PACKF;
+    for (int i = threadIdx.x; i < D::PACKF; i += 256) A2t[i] = A.A2t[i];
+    __syncthreads();
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int c32 = lane & 31;
-    const int f = lane & (F - 1);
-    float *tile = lds + wave * D::TILE;
+    const unsigned f = lane & (F - 1);
+    float *tile = tiles + wave * D::TILE;
     const int64_t chunk = (int64_t)blockIdx.x * 4 + wave;
     if (chunk >= A.n_chunks) return;
     int64_t r0, r1;
     if (!chunk_rows(A, chunk, r0, r1)) return;
-    RegPack<F> W2;   // filter weights stay in registers for the whole chunk
     RegPack1<F> W1;
-    load_pack<F>(W2, A.A2t, lane);
-    load_pack1<F>(W1, A.A1, lane);
+    load_pack1<F>(W1, A.A1s, lane);
+    const __amdgpu_buffer_rsrc_t g_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float *>(A.g), 0, (int)(A.n_nodes * F * 4), kBufferFlags);
     const int64_t e_lo = A.row_ptr[r0], e_hi = A.row_ptr[r1];
     const int32_t r_end = (int32_t)r1;
+    const bool keep_w = A.wstore != nullptr;
     float acc = 0.f;
     // edge data of the first tile; d = rc gives a zero filter, receiver r1 is the end sentinel
     float dv = (e_lo + c32 < e_hi) ? A.d[e_lo + c32] : A.bp.rc;
-    int32_t j = (e_lo + c32 < e_hi) ? A.senders[e_lo + c32] : 0;
     int32_t rk = (e_lo + c32 < e_hi) ? A.recv[e_lo + c32] : r_end;
     {   // rows of the chunk before its first edge are empty
         const int32_t first = __builtin_amdgcn_readfirstlane(rk);
         for (int64_t r = r0; r < first; ++r)
-            if (lane < F) A.out[r * F + f] = 0.f;
+            if (F == 64 || lane < F) A.out[r * F + f] = 0.f;
     }
     for (int64_t tb = e_lo; tb < e_hi; tb += 32) {
         const bool valid = tb + c32 < e_hi;
+        const int kmax = __builtin_amdgcn_readfirstlane((int)min((int64_t)32, e_hi - tb));
         float b[8], db[8];
         radial_basis<false>(dv, A.bp, b, db);
-        // sender rows of this tile: issued now, consumed after the MFMA chain
+        // sender rows of this tile (sender ids through scalar loads): issued now, consumed after the MFMA chain
         float gv[32];
+        int32_t sj[32];   // read unconditionally (device buffers carry 256 bytes of slack), masked afterwards
+#pragma unroll
+        for (int k = 0; k < 32; ++k) sj[k] = uniform_load(A.senders, tb + k);
 #pragma unroll
         for (int k = 0; k < 32; ++k) {
-            const int32_t jk = __builtin_amdgcn_readlane(j, k);
-            gv[k] = A.g[(int64_t)jk * F + f];
+            const int32_t jk = (k < kmax) ? sj[k] : 0;
+            gv[k] = buffer_load_f32(g_rsrc, f * 4, jk * (F * 4), 0);
         }
         const int32_t rcur = rk;
         {   // next tile's edge data
             const int64_t en = tb + 32 + c32;
             dv = (en < e_hi) ? A.d[en] : A.bp.rc;
-            j = (en < e_hi) ? A.senders[en] : 0;
             rk = (en < e_hi) ? A.recv[en] : r_end;
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -439,8 +477,8 @@ __global__ void __launch_bounds__(256, 2) k_edge_fwd(EdgeArgs A)
 #pragma unroll
         for (int bb = 0; bb < D::NB; ++bb)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) t[bb][r] = t[bb][r] * sigmoidf_fast(t[bb][r]);
-        gemm_rr<F>(W2, t, w);
+            for (int r = 0; r < 16; ++r) t[bb][r] = t[bb][r] * sigmoid_scaled(t[bb][r]);
+        gemm_rl<F>(A2t, t, w, lane);
         regs_to_tile<F>(w, tile, lane);
         wave_lds_fence();
         __builtin_amdgcn_sched_barrier(0);  // keep the use of the prefetched receiver after the MFMA chain
@@ -449,26 +487,34 @@ __global__ void __launch_bounds__(256, 2) k_edge_fwd(EdgeArgs A)
         float wv[32];
 #pragma unroll
         for (int k = 0; k < 32; ++k) wv[k] = tile[k * D::FS + f];
+        if (keep_w) {   // keep w_e for the reverse pass; rows past the end of the chunk fall outside the
+                        // descriptor's range and are dropped by the hardware bounds check
+            const __amdgpu_buffer_rsrc_t w_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+                A.wstore + tb * F, 0, kmax * (F * 4), kBufferFlags);
+#pragma unroll
+            for (int k = 0; k < 32; ++k)
+                if (F == 64 || lane < F) buffer_store_f32(wv[k], w_rsrc, f * 4, k * (F * 4), 0);
+        }
 #pragma unroll
         for (int k = 0; k < 32; ++k) {
             acc = fmaf(wv[k], gv[k], acc);   // lanes past the end hold a zero filter
             if (ends & (1u << k)) {
                 const int32_t row = __builtin_amdgcn_readlane(rcur, k);
                 const int32_t nrow = __builtin_amdgcn_readlane(rnext, k);
-                if (lane < F) A.out[(int64_t)row * F + f] = acc;
+                if (F == 64 || lane < F) A.out[(int64_t)row * F + f] = acc;
                 acc = 0.f;
                 for (int64_t r = (int64_t)row + 1; r < nrow; ++r)   // empty rows in between
-                    if (lane < F) A.out[r * F + f] = 0.f;
+                    if (F == 64 || lane < F) A.out[r * F + f] = 0.f;
             }
         }
         wave_lds_fence();
         // retire the prefetched edge data here (it arrived long ago); a load left pending across
         // the loop edge would make the compiler wait for all loads, gathers included, at the top
-        asm volatile("" : "+v"(dv), "+v"(j), "+v"(rk));
+        asm volatile("" : "+v"(dv), "+v"(rk));
     }
     if (e_lo >= e_hi)
         for (int64_t r = r0; r < r1; ++r)
-            if (lane < F) A.out[r * F + f] = 0.f;
+            if (F == 64 || lane < F) A.out[r * F + f] = 0.f;
 }
 
 template <int F>
@@ -483,7 +529,7 @@ __global__ void __launch_bounds__(256, 2) k_edge_bwd(EdgeArgs A)
     __syncthreads();
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int c32 = lane & 31;
-    const int f = lane & (F - 1);
+    const unsigned f = lane & (F - 1);
     float *tile = tiles + wave * D::TILE;
     const int64_t chunk = (int64_t)blockIdx.x * 4 + wave;
     if (chunk >= A.n_chunks) return;
@@ -491,53 +537,67 @@ __global__ void __launch_bounds__(256, 2) k_edge_bwd(EdgeArgs A)
     if (!chunk_rows(A, chunk, r0, r1)) return;
     RegPack1<F> W1;
     load_pack1<F>(W1, A.A1, lane);
+    const __amdgpu_buffer_rsrc_t g_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float *>(A.g), 0, (int)(A.n_nodes * F * 4), kBufferFlags);
+    const __amdgpu_buffer_rsrc_t a_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float *>(A.abar), 0, (int)(A.n_nodes * F * 4), kBufferFlags);
     const int64_t e_lo = A.row_ptr[r0], e_hi = A.row_ptr[r1];
     const int32_t r_end = (int32_t)r1;
     const int64_t last_row = A.n_rows - 1;
     float acc = 0.f;
     float dv = (e_lo + c32 < e_hi) ? A.d[e_lo + c32] : A.bp.rc;
-    int32_t j = (e_lo + c32 < e_hi) ? A.senders[e_lo + c32] : 0;
     int32_t rk = (e_lo + c32 < e_hi) ? A.recv[e_lo + c32] : r_end;
-    int64_t row = min((int64_t)__builtin_amdgcn_readfirstlane(rk), last_row);  // row of the first edge
+    const int64_t row0 = min((int64_t)__builtin_amdgcn_readfirstlane(rk), last_row);  // row of the first edge
     if (A.need_gbar)
         for (int64_t r = r0; r < min((int64_t)__builtin_amdgcn_readfirstlane(rk), r1); ++r)
-            if (lane < F) A.out[r * F + f] = 0.f;
+            if (F == 64 || lane < F) A.out[r * F + f] = 0.f;
     // receiver-side rows of the current row and, prefetched, of the row after it
-    float ai = A.abar[row * F + f], gi = A.g[row * F + f];
-    float ai2 = A.abar[min(row + 1, last_row) * F + f], gi2 = A.g[min(row + 1, last_row) * F + f];
+    float ai = A.abar[row0 * F + f], gi = A.g[row0 * F + f];
+    float ai2 = A.abar[min(row0 + 1, last_row) * F + f], gi2 = A.g[min(row0 + 1, last_row) * F + f];
     for (int64_t tb = e_lo; tb < e_hi; tb += 32) {
         const int64_t e = tb + c32;
         const bool valid = e < e_hi;
-        const int32_t jt = j, rcur = rk;
+        const int kmax = __builtin_amdgcn_readfirstlane((int)min((int64_t)32, e_hi - tb));
+        const int32_t rcur = rk;
+        // w_e kept by the forward pass (owned rows); otherwise it is recomputed here (ghost rows)
+        const bool stored = A.need_gbar && (tb + 32 <= A.n_stored);
         float b[8], db[8];
         radial_basis<true>(dv, A.bp, b, db);
-        // first half of the sender rows (abar_j, g_j): in flight during the MFMA chain
-        float av[16], gv[16];
+        // first half of the sender rows (abar_j, g_j) and of the stored w: in flight during the MFMA chain
+        float av[16], gv[16], wv[16];
+        // stored w_e of this tile; rows past the end of the chunk read as zero (hardware bounds check)
+        const __amdgpu_buffer_rsrc_t w_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+            stored ? A.wstore + tb * F : A.wstore, 0, stored ? kmax * (F * 4) : 0, kBufferFlags);
+        int32_t sj[32];   // read unconditionally (device buffers carry 256 bytes of slack), masked afterwards
+#pragma unroll
+        for (int k = 0; k < 32; ++k) sj[k] = uniform_load(A.senders, tb + k);
 #pragma unroll
         for (int k = 0; k < 16; ++k) {
-            const int32_t jk = __builtin_amdgcn_readlane(jt, k);
-            av[k] = A.abar[(int64_t)jk * F + f];
-            gv[k] = A.g[(int64_t)jk * F + f];
+            const int32_t jk = (k < kmax) ? sj[k] : 0;
+            av[k] = buffer_load_f32(a_rsrc, f * 4, jk * (F * 4), 0);
+            gv[k] = buffer_load_f32(g_rsrc, f * 4, jk * (F * 4), 0);
+            wv[k] = buffer_load_f32(w_rsrc, f * 4, k * (F * 4), 0);
         }
         {
             const int64_t en = tb + 32 + c32;
             dv = (en < e_hi) ? A.d[en] : A.bp.rc;
-            j = (en < e_hi) ? A.senders[en] : 0;
             rk = (en < e_hi) ? A.recv[en] : r_end;
         }
         __builtin_amdgcn_sched_barrier(0);
         f32x16 t[D::NB], sp[D::NB];
+#pragma unroll
+        for (int n = 0; n < 8; ++n) b[n] *= kSiluScale;   // pre-activations come out as t' = c t
         gemm_k8r<F>(W1, b, t, lane);
 #pragma unroll
         for (int bb = 0; bb < D::NB; ++bb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const float x = t[bb][r];
-                const float sg = sigmoidf_fast(x);
-                t[bb][r] = x * sg;                              // s = SiLU(t)
-                sp[bb][r] = sg * (1.0f + x * (1.0f - sg));      // SiLU'(t)
+                const float sg = sigmoid_scaled(t[bb][r]);      // t holds t' = c t
+                const float ss = t[bb][r] * sg;                  // s' = c SiLU(t)
+                t[bb][r] = ss;
+                sp[bb][r] = fmaf(ss * kSiluScaleInv, 1.0f - sg, sg);   // SiLU'(t) = sg + s (1 - sg)
             }
-        if (A.need_gbar) {
+        if (A.need_gbar && !stored) {
             f32x16 w[D::NB];
             gemm_rl<F>(A2t, t, w, lane);
             regs_to_tile<F>(w, tile, lane);
@@ -549,17 +609,20 @@ __global__ void __launch_bounds__(256, 2) k_edge_bwd(EdgeArgs A)
         // lane = feature: accumulate gbar_i; leave abar_i*g_j + abar_j*g_i in the tile
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
-            float av2[16], gv2[16], wv[16], ws[16];
+            float av2[16], gv2[16], wv2[16], ws[16];
             if (half == 0) {
 #pragma unroll
                 for (int k = 0; k < 16; ++k) {  // second half of the sender rows
-                    const int32_t jk = __builtin_amdgcn_readlane(jt, 16 + k);
-                    av2[k] = A.abar[(int64_t)jk * F + f];
-                    gv2[k] = A.g[(int64_t)jk * F + f];
+                    const int32_t jk = (16 + k < kmax) ? sj[16 + k] : 0;
+                    av2[k] = buffer_load_f32(a_rsrc, f * 4, jk * (F * 4), 0);
+                    gv2[k] = buffer_load_f32(g_rsrc, f * 4, jk * (F * 4), 0);
+                    wv2[k] = buffer_load_f32(w_rsrc, f * 4, (16 + k) * (F * 4), 0);
                 }
             }
+            if (A.need_gbar && !stored) {
 #pragma unroll
-            for (int kk = 0; kk < 16; ++kk) wv[kk] = A.need_gbar ? tile[(half * 16 + kk) * D::FS + f] : 0.f;
+                for (int kk = 0; kk < 16; ++kk) wv[kk] = tile[(half * 16 + kk) * D::FS + f];
+            }
 #pragma unroll
             for (int kk = 0; kk < 16; ++kk) {
                 const int k = half * 16 + kk;
@@ -569,9 +632,9 @@ __global__ void __launch_bounds__(256, 2) k_edge_bwd(EdgeArgs A)
                     const int64_t rrow = __builtin_amdgcn_readlane(rcur, k);
                     const int64_t nrow = __builtin_amdgcn_readlane(rnext, k);
                     if (A.need_gbar) {
-                        if (lane < F) A.out[rrow * F + f] = acc;
+                        if (F == 64 || lane < F) A.out[rrow * F + f] = acc;
                         for (int64_t r = rrow + 1; r < nrow; ++r)
-                            if (lane < F) A.out[r * F + f] = 0.f;
+                            if (F == 64 || lane < F) A.out[r * F + f] = 0.f;
                     }
                     acc = 0.f;
                     if (nrow < r1) {   // move to the row of the next edge
@@ -589,10 +652,10 @@ __global__ void __launch_bounds__(256, 2) k_edge_bwd(EdgeArgs A)
             }
 #pragma unroll
             for (int kk = 0; kk < 16; ++kk)
-                if (lane < F) tile[(half * 16 + kk) * D::FS + f] = ws[kk];
+                if (F == 64 || lane < F) tile[(half * 16 + kk) * D::FS + f] = ws[kk];
             if (half == 0) {
 #pragma unroll
-                for (int k = 0; k < 16; ++k) { av[k] = av2[k]; gv[k] = gv2[k]; }
+                for (int k = 0; k < 16; ++k) { av[k] = av2[k]; gv[k] = gv2[k]; wv[k] = wv2[k]; }
             }
         }
         wave_lds_fence();
@@ -607,11 +670,11 @@ __global__ void __launch_bounds__(256, 2) k_edge_bwd(EdgeArgs A)
         part += __shfl_xor(part, 32, 64);
         if (valid && lane < 32) A.dsum[e] = A.first ? part : A.dsum[e] + part;
         wave_lds_fence();
-        asm volatile("" : "+v"(dv), "+v"(j), "+v"(rk), "+v"(ai2), "+v"(gi2));  // no load pending across the loop edge
+        asm volatile("" : "+v"(dv), "+v"(rk), "+v"(ai2), "+v"(gi2));  // no load pending across the loop edge
     }
     if (e_lo >= e_hi && A.need_gbar)
         for (int64_t r = r0; r < r1; ++r)
-            if (lane < F) A.out[r * F + f] = 0.f;
+            if (F == 64 || lane < F) A.out[r * F + f] = 0.f;
 }
 
 // ---------------------------------------------------------------- node kernels
@@ -900,7 +963,7 @@ inline unsigned blocks_for(int64_t n, int threads) { return (unsigned)((n + thre
 // ---------------------------------------------------------------- host driver
 
 struct Packs {  // offsets (floats) into the packed-weight buffer
-    size_t per_layer, A1, W2t, W2n, Wmt, Wmn, Wot, Won, readout_t, readout_n, total;
+    size_t per_layer, A1, A1s, W2t, W2n, Wmt, Wmn, Wot, Won, readout_t, readout_n, total;
 };
 
 Packs pack_layout(int F, int L)
@@ -908,7 +971,8 @@ Packs pack_layout(int F, int L)
     Packs p;
     const size_t ff = (size_t)F * F, p1 = (size_t)(F / 32) * 4 * 64;
     p.A1 = 0;
-    p.W2t = p1;
+    p.A1s = p1;
+    p.W2t = 2 * p1;
     p.W2n = p.W2t + ff;
     p.Wmt = p.W2n + ff;
     p.Wmn = p.Wmt + ff;
@@ -923,7 +987,7 @@ Packs pack_layout(int F, int L)
 
 template <int F> struct Lds {
     using D = Dims<F>;
-    static constexpr size_t edge_fwd = sizeof(float) * (4 * D::TILE);
+    static constexpr size_t edge_fwd = sizeof(float) * (D::PACKF + 4 * D::TILE);
     static constexpr size_t edge_bwd = sizeof(float) * (2 * D::PACKF + 4 * D::TILE);
     static constexpr size_t node1 = sizeof(float) * (D::PACKF + 4 * D::TILE);
     static constexpr size_t node2 = sizeof(float) * (2 * D::PACKF + 4 * D::TILE);
@@ -983,6 +1047,11 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, int32_t mode, double *ener
     const size_t rowb = (size_t)F * sizeof(float);
 
     // ---- workspace
+    for (int p = 0; p < P; ++p)
+        if (views[p].n_local * (int64_t)F * 4 >= ((int64_t)1 << 31)) {
+            set_error("a partition holds more than 2^31 bytes of node features; use more slabs");
+            return MLIP_EINVAL;
+        }
     int64_t n_parts = 0;
     for (int p = 0; p < P; ++p) {
         SlabView &v = views[p];
@@ -996,6 +1065,8 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, int32_t mode, double *ener
         MLIP_TRY(v.floc.ensure(nl * 3 * sizeof(float)));
         MLIP_TRY(v.g.ensure(nl * rowb * (size_t)std::max(L, 1)));
         MLIP_TRY(v.a.ensure(no * rowb * (size_t)std::max(L, 1)));
+        if (L > 1)  // filter values of layers 1..L-1, kept for the reverse pass instead of being recomputed
+            MLIP_TRY(v.wst.ensure((size_t)std::max<int64_t>(v.n_edges_owned, 1) * rowb * (size_t)(L - 1)));
         n_parts += (v.n_owned + 1023) / 1024;
     }
     MLIP_TRY(g->energy_part.ensure((size_t)std::max<int64_t>(n_parts, 1) * sizeof(double)));
@@ -1021,16 +1092,17 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, int32_t mode, double *ener
     for (int l = 0; l < L; ++l) {
         float *base = wp + pk.per_layer * l;
         const size_t ff = (size_t)F * F;
-        k_pack_w1<<<blocks_for((F / 32) * 256, 256), 256, 0, s>>>(w->W1 + (size_t)l * 8 * F, F, base + pk.A1);
-        k_pack_ff<<<pb, 256, 0, s>>>(w->W2 + l * ff, F, 1, base + pk.W2t);
-        k_pack_ff<<<pb, 256, 0, s>>>(w->W2 + l * ff, F, 0, base + pk.W2n);
-        k_pack_ff<<<pb, 256, 0, s>>>(w->Wm + l * ff, F, 1, base + pk.Wmt);
-        k_pack_ff<<<pb, 256, 0, s>>>(w->Wm + l * ff, F, 0, base + pk.Wmn);
-        k_pack_ff<<<pb, 256, 0, s>>>(w->Wo + l * ff, F, 1, base + pk.Wot);
-        k_pack_ff<<<pb, 256, 0, s>>>(w->Wo + l * ff, F, 0, base + pk.Won);
+        k_pack_w1<<<blocks_for((F / 32) * 256, 256), 256, 0, s>>>(w->W1 + (size_t)l * 8 * F, F, 1.0f, base + pk.A1);
+        k_pack_w1<<<blocks_for((F / 32) * 256, 256), 256, 0, s>>>(w->W1 + (size_t)l * 8 * F, F, kSiluScale, base + pk.A1s);
+        k_pack_ff<<<pb, 256, 0, s>>>(w->W2 + l * ff, F, 1, kSiluScaleInv, base + pk.W2t);
+        k_pack_ff<<<pb, 256, 0, s>>>(w->W2 + l * ff, F, 0, 1.0f, base + pk.W2n);
+        k_pack_ff<<<pb, 256, 0, s>>>(w->Wm + l * ff, F, 1, 1.0f, base + pk.Wmt);
+        k_pack_ff<<<pb, 256, 0, s>>>(w->Wm + l * ff, F, 0, 1.0f, base + pk.Wmn);
+        k_pack_ff<<<pb, 256, 0, s>>>(w->Wo + l * ff, F, 1, 1.0f, base + pk.Wot);
+        k_pack_ff<<<pb, 256, 0, s>>>(w->Wo + l * ff, F, 0, 1.0f, base + pk.Won);
     }
-    k_pack_ff<<<pb, 256, 0, s>>>(w->Wr1, F, 1, wp + pk.readout_t);
-    k_pack_ff<<<pb, 256, 0, s>>>(w->Wr1, F, 0, wp + pk.readout_n);
+    k_pack_ff<<<pb, 256, 0, s>>>(w->Wr1, F, 1, 1.0f, wp + pk.readout_t);
+    k_pack_ff<<<pb, 256, 0, s>>>(w->Wr1, F, 0, 1.0f, wp + pk.readout_n);
     MLIP_HIP(hipGetLastError());
 
     // ---- embedding
@@ -1045,6 +1117,9 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, int32_t mode, double *ener
 
     auto gslice = [&](SlabView &v, int l) { return v.g.as<float>() + (size_t)l * (size_t)v.n_local * F; };
     auto aslice = [&](SlabView &v, int l) { return v.a.as<float>() + (size_t)l * (size_t)v.n_owned * F; };
+    auto wslice = [&](SlabView &v, int l) {  // l >= 1
+        return v.wst.as<float>() + (size_t)(l - 1) * (size_t)v.n_edges_owned * F;
+    };
 
     // ---- forward layers
     for (int l = 0; l < L; ++l) {
@@ -1085,8 +1160,11 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, int32_t mode, double *ener
             ea.g = gslice(v, l);
             ea.out = aslice(v, l);
             ea.A1 = base + pk.A1;
+            ea.A1s = base + pk.A1s;
+            ea.n_nodes = v.n_local;
             ea.A2t = base + pk.W2t;
             ea.bp = bp;
+            ea.wstore = (l >= 1) ? wslice(v, l) : nullptr;
             prof_begin(g, MLIP_PROF_EDGE_FWD);
             MLIP_TRY((launch_edge<F>(g, ea, false)));
             prof_end(g);
@@ -1167,10 +1245,14 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, int32_t mode, double *ener
             ea.out = v.gbar.as<float>();
             ea.dsum = v.dsum.as<float>();
             ea.A1 = base + pk.A1;
+            ea.A1s = base + pk.A1s;
+            ea.n_nodes = v.n_local;
             ea.A2t = base + pk.W2t;
             ea.A2n = base + pk.W2n;
             ea.bp = bp;
             ea.need_gbar = need_gbar ? 1 : 0;
+            ea.wstore = need_gbar ? wslice(v, l) : nullptr;
+            ea.n_stored = need_gbar ? v.n_edges_owned : 0;
             ea.first = (l == L - 1) ? 1 : 0;
             prof_begin(g, MLIP_PROF_EDGE_BWD);
             MLIP_TRY((launch_edge<F>(g, ea, true)));

@@ -126,17 +126,18 @@ def partition(graph, slab_of, n_slabs):
     for p in range(P):
         owned = np.flatnonzero(slab_of == p).astype(np.int32)
         slabs.append(Slab(p=p, owned=owned, pure=None, border=None, ghost=None))
-    cross = s_recv != s_send
+    cross = np.flatnonzero(s_recv != s_send)      # only edges that cross a wall define TO / FROM
+    c_send, c_ss, c_sr = send[cross], s_send[cross], s_recv[cross]
     for p in range(P):
         sl = slabs[p]
         needed_anywhere = []
+        from_p = c_ss == p
         for q in range(P):
             if q == p:
                 sl.to[q] = np.zeros(0, np.int32)
                 continue
             # u owned by p, some receiver v owned by q
-            m = cross & (s_send == p) & (s_recv == q)
-            sl.to[q] = np.unique(send[m]).astype(np.int32)
+            sl.to[q] = np.unique(c_send[from_p & (c_sr == q)]).astype(np.int32)
             needed_anywhere.append(sl.to[q])
         border = np.unique(np.concatenate(needed_anywhere)) if needed_anywhere else np.zeros(0, np.int32)
         sl.border = border.astype(np.int32)

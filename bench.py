@@ -16,12 +16,14 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_FP32_MFMA_TFLOPS = 157.3
-# algorithmic flops of the reverse edge step per directed edge (K = 8, F = 64):
-#   recompute t = b W1 (2*8*64), w = s W2 (2*64*64, not needed in layer 0), sbar = wbar W2^T (2*64*64),
-#   dt/dd contraction through W1 (2*8*64)
-FLOPS_BWD_EDGE = 2 * 8 * 64 + 2 * 64 * 64 + 2 * 64 * 64 + 2 * 8 * 64
-FLOPS_BWD_EDGE_L0 = FLOPS_BWD_EDGE - 2 * 64 * 64
+# algorithmic flops of the reverse edge step per directed edge and layer (K = 8, F = 64):
+#   pre-activations t = b W1 (2*8*64), sbar = wbar W2^T (2*64*64), dt/dd contraction through W1 (2*8*64).
+#   The filter value w_e itself is not recomputed: the forward pass keeps it in HBM (layers >= 1).
+FLOPS_BWD_EDGE = 2 * 8 * 64 + 2 * 64 * 64 + 2 * 8 * 64
 FLOPS_FWD_EDGE = 2 * 8 * 64 + 2 * 64 * 64
+# HBM bytes per k_edge_bwd<64> launch on the default workload, from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE
+# (profiles/edge_bwd_traffic_configs3_8slabs.md): 1,886,948 KiB x 1.9976 (copy-kernel scale) + 57,100 KiB x 1.000
+TRAFFIC_BWD_LAUNCH_BYTES = (1886948 * 1.9976 + 57100 * 1.0) * 1024
 
 
 def cpu_baseline(cfg_index, n_cells):
@@ -49,7 +51,8 @@ def main():
     ap.add_argument("--config", type=int, default=3)
     ap.add_argument("--cells", type=int, default=None, help="override fcc cells per side (smaller runs)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
-    ap.add_argument("--cpu-cells", type=int, default=20)
+    ap.add_argument("--cpu-cells", type=int, default=40)
+    ap.add_argument("--whole", action="store_true", help="also time whole-graph mode on the same graph (extra fields)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (slabs are processed in sequence on one device); "
@@ -96,20 +99,22 @@ def main():
     fsum = out[1].double().sum(0).abs().max().item()
 
     # whole-graph mode on the same graph, for the record (not the headline)
-    for _ in range(2):
-        M.mlip_forward(g, W, M.MODE_WHOLE, out=out, want_atom_energy=False)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    for _ in range(args.steps):
-        M.mlip_forward(g, W, M.MODE_WHOLE, out=out, want_atom_energy=False)
-    torch.cuda.synchronize()
-    dt_whole_fwd = (time.perf_counter() - t1) / args.steps
-    energy_whole = float(out[0].cpu()[0])
+    dt_whole_fwd, energy_whole = None, None
+    if args.whole:
+        for _ in range(2):
+            M.mlip_forward(g, W, M.MODE_WHOLE, out=out, want_atom_energy=False)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(args.steps):
+            M.mlip_forward(g, W, M.MODE_WHOLE, out=out, want_atom_energy=False)
+        torch.cuda.synchronize()
+        dt_whole_fwd = (time.perf_counter() - t1) / args.steps
+        energy_whole = float(out[0].cpu()[0])
 
     ms_step = dt / args.steps * 1e3
     L = c["L"]
     bwd_ms, bwd_n = prof["edge_bwd"]
-    flops_step = E * (FLOPS_BWD_EDGE * (L - 1) + FLOPS_BWD_EDGE_L0)
+    flops_step = E * FLOPS_BWD_EDGE * L
     per_launch_flops = flops_step * args.steps / max(bwd_n, 1)
     avg_ms = bwd_ms / max(bwd_n, 1)
     achieved = per_launch_flops / (avg_ms * 1e-3) / 1e12 if avg_ms > 0 else 0.0
@@ -125,18 +130,21 @@ def main():
         "edges_per_s": E / (dt / args.steps),
         "us_per_atom_step": ms_step * 1e3 / N,
         "breakdown_ms_per_step": {k: v[0] / args.steps for k, v in prof.items()},
-        "whole_graph_forward_ms": dt_whole_fwd * 1e3,
-        "whole_graph_atoms_per_s_excl_graph": N / dt_whole_fwd,
-        "energy": energy, "energy_whole": energy_whole, "net_force_max_component": fsum,
+        "energy": energy, "net_force_max_component": fsum,
         "roofline": {"kernel": "k_edge_bwd<64> (reverse edge step)", "bound": "mfma", "achieved": achieved,
                      "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
-                     "traffic": None, "avg_launch_ms": avg_ms, "launches": int(bwd_n),
+                     "traffic": TRAFFIC_BWD_LAUNCH_BYTES if (args.config == 3 and args.cells is None) else None,
+                     "avg_launch_ms": avg_ms, "launches": int(bwd_n),
                      "flops_per_launch": per_launch_flops},
         "roofline_edge_fwd": {"kernel": "k_edge_fwd<64>", "bound": "mfma", "achieved": fwd_tflops,
                               "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
                               "frac": fwd_tflops / PEAK_FP32_MFMA_TFLOPS,
                               "avg_launch_ms": fwd_ms / max(fwd_n, 1), "launches": int(fwd_n)},
     }
+    if args.whole:
+        res["whole_graph_forward_ms"] = dt_whole_fwd * 1e3
+        res["whole_graph_atoms_per_s_excl_graph"] = N / dt_whole_fwd
+        res["energy_whole"] = energy_whole
     if not args.no_cpu:
         res["cpu_baseline"] = cpu_baseline(args.config, args.cpu_cells)
     print(json.dumps(res))

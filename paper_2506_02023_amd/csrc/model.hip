@@ -361,6 +361,8 @@ __device__ inline int64_t lower_bound_i64(const int64_t *__restrict__ a, int64_t
 struct EdgeArgs {
     int64_t n_rows;            // receiver rows processed
     int64_t n_chunks;
+    int64_t n_stored;          // reverse: edges [0, n_stored) have their w_e in wstore
+    int64_t n_nodes;           // rows of g / abar (n_local)
     const int64_t *row_ptr;
     const int32_t *senders;
     const int32_t *recv;       // receiver row of every edge
@@ -370,12 +372,34 @@ struct EdgeArgs {
     float *out;                // forward: a [n_rows][F]; reverse: gbar [n_rows][F]
     float *dsum;               // reverse: per-edge dE/dd of the edge and its mirror, summed over layers
     float *wstore;             // forward: filter values w_e [n_stored][F] kept for the reverse pass (or null)
-    int64_t n_stored;          // reverse: edges [0, n_stored) have their w_e in wstore
-    int64_t n_nodes;           // rows of g / abar (n_local)
+};
+
+// What all partitions of one launch share: the layer's packed weights and the basis.
+struct EdgeCommon {
     const float *A1, *A1s, *A2t, *A2n;   // A1s = c W1, A2t = W2 / c (see kSiluScale), A1 and A2n unscaled
     BasisParams bp;
     int need_gbar, first;
 };
+
+// One launch covers up to kBatch partitions, taken in order: work item w belongs to partition p
+// with chunk_start[p] <= w < chunk_start[p + 1].  The partitions keep their own arrays (local rows,
+// ghost rows); batching only removes the idle tail between per-partition launches.
+constexpr int kBatch = 8;
+struct EdgeBatch {
+    EdgeCommon c;
+    int n;
+    int64_t chunk_start[kBatch + 1];
+    EdgeArgs s[kBatch];
+};
+
+__device__ inline int batch_find(const int64_t *start, int n, int64_t w)
+{
+    int p = 0;
+#pragma unroll
+    for (int q = 1; q < kBatch; ++q)
+        if (q < n && w >= start[q]) p = q;
+    return p;
+}
 
 // wavefront work item: the rows whose first edge lies in [chunk * kChunkEdges, (chunk + 1) * kChunkEdges)
 __device__ inline bool chunk_rows(const EdgeArgs &A, int64_t chunk, int64_t &r0, int64_t &r1)
@@ -418,24 +442,28 @@ __device__ inline uint32_t row_ends(int32_t rk, int32_t rn_first, bool valid, in
 }
 
 template <int F>
-__global__ void __launch_bounds__(256, 3) k_edge_fwd(EdgeArgs A)
+__global__ void __launch_bounds__(256, 3) k_edge_fwd(EdgeBatch B)
 {
     using D = Dims<F>;
     extern __shared__ float lds[];
     float *A2t = lds;
     float *tiles = A2t + D::PACKF;
-    for (int i = threadIdx.x; i < D::PACKF; i += 256) A2t[i] = A.A2t[i];
+    for (int i = threadIdx.x; i < D::PACKF; i += 256) A2t[i] = B.c.A2t[i];
     __syncthreads();
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int c32 = lane & 31;
     const unsigned f = lane & (F - 1);
     float *tile = tiles + wave * D::TILE;
-    const int64_t chunk = (int64_t)blockIdx.x * 4 + wave;
-    if (chunk >= A.n_chunks) return;
+    const int64_t item = (int64_t)blockIdx.x * 4 + wave;
+    if (item >= B.chunk_start[B.n]) return;
+    const int part = batch_find(B.chunk_start, B.n, item);
+    const EdgeArgs A = B.s[part];
+    const EdgeCommon &C = B.c;
+    const int64_t chunk = item - B.chunk_start[part];
     int64_t r0, r1;
     if (!chunk_rows(A, chunk, r0, r1)) return;
     RegPack1<F> W1;
-    load_pack1<F>(W1, A.A1s, lane);
+    load_pack1<F>(W1, C.A1s, lane);
     const __amdgpu_buffer_rsrc_t g_rsrc = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<float *>(A.g), 0, (int)(A.n_nodes * F * 4), kBufferFlags);
     const int64_t e_lo = A.row_ptr[r0], e_hi = A.row_ptr[r1];
@@ -443,7 +471,7 @@ __global__ void __launch_bounds__(256, 3) k_edge_fwd(EdgeArgs A)
     const bool keep_w = A.wstore != nullptr;
     float acc = 0.f;
     // edge data of the first tile; d = rc gives a zero filter, receiver r1 is the end sentinel
-    float dv = (e_lo + c32 < e_hi) ? A.d[e_lo + c32] : A.bp.rc;
+    float dv = (e_lo + c32 < e_hi) ? A.d[e_lo + c32] : C.bp.rc;
     int32_t rk = (e_lo + c32 < e_hi) ? A.recv[e_lo + c32] : r_end;
     {   // rows of the chunk before its first edge are empty
         const int32_t first = __builtin_amdgcn_readfirstlane(rk);
@@ -454,7 +482,7 @@ __global__ void __launch_bounds__(256, 3) k_edge_fwd(EdgeArgs A)
         const bool valid = tb + c32 < e_hi;
         const int kmax = __builtin_amdgcn_readfirstlane((int)min((int64_t)32, e_hi - tb));
         float b[8], db[8];
-        radial_basis<false>(dv, A.bp, b, db);
+        radial_basis<false>(dv, C.bp, b, db);
         // sender rows of this tile (sender ids through scalar loads): issued now, consumed after the MFMA chain
         float gv[32];
         int32_t sj[32];   // read unconditionally (device buffers carry 256 bytes of slack), masked afterwards
@@ -468,7 +496,7 @@ __global__ void __launch_bounds__(256, 3) k_edge_fwd(EdgeArgs A)
         const int32_t rcur = rk;
         {   // next tile's edge data
             const int64_t en = tb + 32 + c32;
-            dv = (en < e_hi) ? A.d[en] : A.bp.rc;
+            dv = (en < e_hi) ? A.d[en] : C.bp.rc;
             rk = (en < e_hi) ? A.recv[en] : r_end;
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -518,54 +546,62 @@ __global__ void __launch_bounds__(256, 3) k_edge_fwd(EdgeArgs A)
 }
 
 template <int F>
-__global__ void __launch_bounds__(256, 2) k_edge_bwd(EdgeArgs A)
+__global__ void __launch_bounds__(256, 2) k_edge_bwd(EdgeBatch B)
 {
     using D = Dims<F>;
     extern __shared__ float lds[];
     float *A2n = lds;
     float *A2t = A2n + D::PACKF;
     float *tiles = A2t + D::PACKF;
-    for (int i = threadIdx.x; i < D::PACKF; i += 256) { A2n[i] = A.A2n[i]; A2t[i] = A.A2t[i]; }
+    for (int i = threadIdx.x; i < D::PACKF; i += 256) { A2n[i] = B.c.A2n[i]; A2t[i] = B.c.A2t[i]; }
     __syncthreads();
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int c32 = lane & 31;
     const unsigned f = lane & (F - 1);
     float *tile = tiles + wave * D::TILE;
-    const int64_t chunk = (int64_t)blockIdx.x * 4 + wave;
-    if (chunk >= A.n_chunks) return;
+    const int64_t item = (int64_t)blockIdx.x * 4 + wave;
+    if (item >= B.chunk_start[B.n]) return;
+    const int part = batch_find(B.chunk_start, B.n, item);
+    const EdgeArgs A = B.s[part];
+    const EdgeCommon &C = B.c;
+    const int64_t chunk = item - B.chunk_start[part];
     int64_t r0, r1;
     if (!chunk_rows(A, chunk, r0, r1)) return;
     RegPack1<F> W1;
-    load_pack1<F>(W1, A.A1, lane);
+    load_pack1<F>(W1, C.A1, lane);
     const __amdgpu_buffer_rsrc_t g_rsrc = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<float *>(A.g), 0, (int)(A.n_nodes * F * 4), kBufferFlags);
     const __amdgpu_buffer_rsrc_t a_rsrc = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<float *>(A.abar), 0, (int)(A.n_nodes * F * 4), kBufferFlags);
     const int64_t e_lo = A.row_ptr[r0], e_hi = A.row_ptr[r1];
     const int32_t r_end = (int32_t)r1;
-    const int64_t last_row = A.n_rows - 1;
+    const int32_t last_row = (int32_t)(A.n_rows - 1);
+    const bool need_gbar = C.need_gbar != 0;
     float acc = 0.f;
-    float dv = (e_lo + c32 < e_hi) ? A.d[e_lo + c32] : A.bp.rc;
+    float dv = (e_lo + c32 < e_hi) ? A.d[e_lo + c32] : C.bp.rc;
     int32_t rk = (e_lo + c32 < e_hi) ? A.recv[e_lo + c32] : r_end;
-    const int64_t row0 = min((int64_t)__builtin_amdgcn_readfirstlane(rk), last_row);  // row of the first edge
-    if (A.need_gbar)
+    const int32_t row0 = min(__builtin_amdgcn_readfirstlane(rk), last_row);  // row of the first edge
+    if (need_gbar)
         for (int64_t r = r0; r < min((int64_t)__builtin_amdgcn_readfirstlane(rk), r1); ++r)
             if (F == 64 || lane < F) A.out[r * F + f] = 0.f;
-    // receiver-side rows of the current row and, prefetched, of the row after it
-    float ai = A.abar[row0 * F + f], gi = A.g[row0 * F + f];
-    float ai2 = A.abar[min(row0 + 1, last_row) * F + f], gi2 = A.g[min(row0 + 1, last_row) * F + f];
+    // receiver-side rows (abar_i, g_i) of the current row and, prefetched, of the row after it
+    float ai = buffer_load_f32(a_rsrc, f * 4, row0 * (F * 4), 0);
+    float gi = buffer_load_f32(g_rsrc, f * 4, row0 * (F * 4), 0);
+    float ai2 = buffer_load_f32(a_rsrc, f * 4, min(row0 + 1, last_row) * (F * 4), 0);
+    float gi2 = buffer_load_f32(g_rsrc, f * 4, min(row0 + 1, last_row) * (F * 4), 0);
     for (int64_t tb = e_lo; tb < e_hi; tb += 32) {
         const int64_t e = tb + c32;
         const bool valid = e < e_hi;
         const int kmax = __builtin_amdgcn_readfirstlane((int)min((int64_t)32, e_hi - tb));
         const int32_t rcur = rk;
         // w_e kept by the forward pass (owned rows); otherwise it is recomputed here (ghost rows)
-        const bool stored = A.need_gbar && (tb + 32 <= A.n_stored);
+        const bool stored = need_gbar && (tb + 32 <= A.n_stored);
         float b[8], db[8];
-        radial_basis<true>(dv, A.bp, b, db);
-        // first half of the sender rows (abar_j, g_j) and of the stored w: in flight during the MFMA chain
-        float av[16], gv[16], wv[16];
-        // stored w_e of this tile; rows past the end of the chunk read as zero (hardware bounds check)
+        radial_basis<true>(dv, C.bp, b, db);
+        // sender rows abar_j, g_j and the stored w_e, two halves of 16 edges; half 0 is in flight during
+        // the MFMA chain, half 1 while half 0 is consumed.  Rows past the end of the chunk: stored w
+        // reads as zero (hardware bounds check), the other two read row 0 and are never used.
+        float av[2][16], gv[2][16], wv[2][16];
         const __amdgpu_buffer_rsrc_t w_rsrc = __builtin_amdgcn_make_buffer_rsrc(
             stored ? A.wstore + tb * F : A.wstore, 0, stored ? kmax * (F * 4) : 0, kBufferFlags);
         int32_t sj[32];   // read unconditionally (device buffers carry 256 bytes of slack), masked afterwards
@@ -574,19 +610,19 @@ __global__ void __launch_bounds__(256, 2) k_edge_bwd(EdgeArgs A)
 #pragma unroll
         for (int k = 0; k < 16; ++k) {
             const int32_t jk = (k < kmax) ? sj[k] : 0;
-            av[k] = buffer_load_f32(a_rsrc, f * 4, jk * (F * 4), 0);
-            gv[k] = buffer_load_f32(g_rsrc, f * 4, jk * (F * 4), 0);
-            wv[k] = buffer_load_f32(w_rsrc, f * 4, k * (F * 4), 0);
+            av[0][k] = buffer_load_f32(a_rsrc, f * 4, jk * (F * 4), 0);
+            gv[0][k] = buffer_load_f32(g_rsrc, f * 4, jk * (F * 4), 0);
+            wv[0][k] = buffer_load_f32(w_rsrc, f * 4, k * (F * 4), 0);
         }
         {
             const int64_t en = tb + 32 + c32;
-            dv = (en < e_hi) ? A.d[en] : A.bp.rc;
+            dv = (en < e_hi) ? A.d[en] : C.bp.rc;
             rk = (en < e_hi) ? A.recv[en] : r_end;
         }
         __builtin_amdgcn_sched_barrier(0);
-        f32x16 t[D::NB], sp[D::NB];
 #pragma unroll
         for (int n = 0; n < 8; ++n) b[n] *= kSiluScale;   // pre-activations come out as t' = c t
+        f32x16 t[D::NB], sp[D::NB];
         gemm_k8r<F>(W1, b, t, lane);
 #pragma unroll
         for (int bb = 0; bb < D::NB; ++bb)
@@ -597,10 +633,18 @@ __global__ void __launch_bounds__(256, 2) k_edge_bwd(EdgeArgs A)
                 t[bb][r] = ss;
                 sp[bb][r] = fmaf(ss * kSiluScaleInv, 1.0f - sg, sg);   // SiLU'(t) = sg + s (1 - sg)
             }
-        if (A.need_gbar && !stored) {
+        if (need_gbar && !stored) {
             f32x16 w[D::NB];
             gemm_rl<F>(A2t, t, w, lane);
             regs_to_tile<F>(w, tile, lane);
+        }
+        {   // q[k] = SiLU'(t_k) * sum_n W1[n][k] db_n/dd  =  d s_k / d d
+            f32x16 cg[D::NB];
+            gemm_k8r<F>(W1, db, cg, lane);
+#pragma unroll
+            for (int bb = 0; bb < D::NB; ++bb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) sp[bb][r] *= cg[bb][r];
         }
         wave_lds_fence();
         __builtin_amdgcn_sched_barrier(0);  // keep the use of the prefetched receiver after the MFMA chain
@@ -609,70 +653,64 @@ __global__ void __launch_bounds__(256, 2) k_edge_bwd(EdgeArgs A)
         // lane = feature: accumulate gbar_i; leave abar_i*g_j + abar_j*g_i in the tile
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
-            float av2[16], gv2[16], wv2[16], ws[16];
+            float ws[16];
             if (half == 0) {
 #pragma unroll
-                for (int k = 0; k < 16; ++k) {  // second half of the sender rows
+                for (int k = 0; k < 16; ++k) {
                     const int32_t jk = (16 + k < kmax) ? sj[16 + k] : 0;
-                    av2[k] = buffer_load_f32(a_rsrc, f * 4, jk * (F * 4), 0);
-                    gv2[k] = buffer_load_f32(g_rsrc, f * 4, jk * (F * 4), 0);
-                    wv2[k] = buffer_load_f32(w_rsrc, f * 4, (16 + k) * (F * 4), 0);
+                    av[1][k] = buffer_load_f32(a_rsrc, f * 4, jk * (F * 4), 0);
+                    gv[1][k] = buffer_load_f32(g_rsrc, f * 4, jk * (F * 4), 0);
+                    wv[1][k] = buffer_load_f32(w_rsrc, f * 4, (16 + k) * (F * 4), 0);
                 }
             }
-            if (A.need_gbar && !stored) {
+            if (need_gbar && !stored) {
 #pragma unroll
-                for (int kk = 0; kk < 16; ++kk) wv[kk] = tile[(half * 16 + kk) * D::FS + f];
+                for (int kk = 0; kk < 16; ++kk) wv[half][kk] = tile[(half * 16 + kk) * D::FS + f];
             }
 #pragma unroll
             for (int kk = 0; kk < 16; ++kk) {
                 const int k = half * 16 + kk;
-                acc = fmaf(wv[kk], av[kk], acc);
-                ws[kk] = ai * gv[kk] + av[kk] * gi;
+                acc = fmaf(wv[half][kk], av[half][kk], acc);
+                ws[kk] = fmaf(ai, gv[half][kk], av[half][kk] * gi);
                 if (ends & (1u << k)) {
-                    const int64_t rrow = __builtin_amdgcn_readlane(rcur, k);
-                    const int64_t nrow = __builtin_amdgcn_readlane(rnext, k);
-                    if (A.need_gbar) {
-                        if (F == 64 || lane < F) A.out[rrow * F + f] = acc;
-                        for (int64_t r = rrow + 1; r < nrow; ++r)
+                    const int32_t rrow = __builtin_amdgcn_readlane(rcur, k);
+                    const int32_t nrow = __builtin_amdgcn_readlane(rnext, k);
+                    if (need_gbar) {
+                        if (F == 64 || lane < F) A.out[(int64_t)rrow * F + f] = acc;
+                        for (int64_t r = (int64_t)rrow + 1; r < nrow; ++r)
                             if (F == 64 || lane < F) A.out[r * F + f] = 0.f;
                     }
                     acc = 0.f;
-                    if (nrow < r1) {   // move to the row of the next edge
-                        if (nrow == rrow + 1) {
-                            ai = ai2;
-                            gi = gi2;
-                        } else {
-                            ai = A.abar[nrow * F + f];
-                            gi = A.g[nrow * F + f];
+                    if (nrow < r_end) {   // move to the row of the next edge
+                        ai = ai2;
+                        gi = gi2;
+                        if (nrow != rrow + 1) {   // empty rows were skipped: the prefetch was for the wrong row
+                            ai = buffer_load_f32(a_rsrc, f * 4, nrow * (F * 4), 0);
+                            gi = buffer_load_f32(g_rsrc, f * 4, nrow * (F * 4), 0);
                         }
-                        ai2 = A.abar[min(nrow + 1, last_row) * F + f];
-                        gi2 = A.g[min(nrow + 1, last_row) * F + f];
+                        ai2 = buffer_load_f32(a_rsrc, f * 4, min(nrow + 1, last_row) * (F * 4), 0);
+                        gi2 = buffer_load_f32(g_rsrc, f * 4, min(nrow + 1, last_row) * (F * 4), 0);
                     }
                 }
             }
 #pragma unroll
             for (int kk = 0; kk < 16; ++kk)
                 if (F == 64 || lane < F) tile[(half * 16 + kk) * D::FS + f] = ws[kk];
-            if (half == 0) {
-#pragma unroll
-                for (int k = 0; k < 16; ++k) { av[k] = av2[k]; gv[k] = gv2[k]; wv[k] = wv2[k]; }
-            }
         }
         wave_lds_fence();
-        f32x16 sb[D::NB], cg[D::NB];
-        gemm_k8r<F>(W1, db, cg, lane);      // c[k] = sum_n W1[n][k] db_n/dd
+        f32x16 sb[D::NB];
         gemm_lds<F>(A2n, tile, sb, lane);   // sbar[k] = sum_f W2[k][f] wsym[f]
         float part = 0.f;
 #pragma unroll
         for (int bb = 0; bb < D::NB; ++bb)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) part += sb[bb][r] * sp[bb][r] * cg[bb][r];
+            for (int r = 0; r < 16; ++r) part = fmaf(sb[bb][r], sp[bb][r], part);
         part += __shfl_xor(part, 32, 64);
-        if (valid && lane < 32) A.dsum[e] = A.first ? part : A.dsum[e] + part;
+        if (valid && lane < 32) A.dsum[e] = C.first ? part : A.dsum[e] + part;
         wave_lds_fence();
         asm volatile("" : "+v"(dv), "+v"(rk), "+v"(ai2), "+v"(gi2));  // no load pending across the loop edge
     }
-    if (e_lo >= e_hi && A.need_gbar)
+    if (e_lo >= e_hi && need_gbar)
         for (int64_t r = r0; r < r1; ++r)
             if (F == 64 || lane < F) A.out[r * F + f] = 0.f;
 }
@@ -1012,9 +1050,8 @@ template <int F, int OP> int launch_node(mlip_graph *g, const NodeArgs &a)
     return MLIP_OK;
 }
 
-template <int F> int launch_edge(mlip_graph *g, EdgeArgs a, bool backward)
+template <int F> int launch_edge(mlip_graph *g, EdgeBatch &b, bool backward)
 {
-    if (a.n_rows <= 0) return MLIP_OK;
     const size_t lds = backward ? Lds<F>::edge_bwd : Lds<F>::edge_fwd;
     static bool cfg_f = false, cfg_b = false;
     if (backward && !cfg_b) {
@@ -1027,11 +1064,16 @@ template <int F> int launch_edge(mlip_graph *g, EdgeArgs a, bool backward)
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         cfg_f = true;
     }
-    const unsigned blocks = (unsigned)((a.n_chunks + 3) / 4);
+    b.chunk_start[0] = 0;
+    for (int q = 0; q < b.n; ++q) b.chunk_start[q + 1] = b.chunk_start[q] + (b.s[q].n_rows > 0 ? b.s[q].n_chunks : 0);
+    for (int q = b.n; q < kBatch; ++q) b.chunk_start[q + 1] = b.chunk_start[b.n];
+    const int64_t items = b.chunk_start[b.n];
+    if (items <= 0) return MLIP_OK;
+    const unsigned blocks = (unsigned)((items + 3) / 4);
     if (backward)
-        k_edge_bwd<F><<<blocks, 256, lds, g->stream>>>(a);
+        k_edge_bwd<F><<<blocks, 256, lds, g->stream>>>(b);
     else
-        k_edge_fwd<F><<<blocks, 256, lds, g->stream>>>(a);
+        k_edge_fwd<F><<<blocks, 256, lds, g->stream>>>(b);
     MLIP_HIP(hipGetLastError());
     return MLIP_OK;
 }
@@ -1148,25 +1190,29 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, int32_t mode, double *ener
             MLIP_HIP(hipGetLastError());
             prof_end(g);
         }
-        for (int p = 0; p < P; ++p) {
-            SlabView &v = views[p];
-            EdgeArgs ea{};
-            ea.n_rows = v.n_owned;
-            ea.n_chunks = std::max<int64_t>(1, (v.n_edges_owned + kChunkEdges - 1) / kChunkEdges);
-            ea.row_ptr = v.row_ptr;
-            ea.senders = v.senders;
-            ea.recv = v.recv;
-            ea.d = v.d;
-            ea.g = gslice(v, l);
-            ea.out = aslice(v, l);
-            ea.A1 = base + pk.A1;
-            ea.A1s = base + pk.A1s;
-            ea.n_nodes = v.n_local;
-            ea.A2t = base + pk.W2t;
-            ea.bp = bp;
-            ea.wstore = (l >= 1) ? wslice(v, l) : nullptr;
+        for (int p0 = 0; p0 < P; p0 += kBatch) {   // the partitions in order, up to kBatch per launch
+            EdgeBatch eb{};
+            eb.n = std::min(kBatch, P - p0);
+            eb.c.A1 = base + pk.A1;
+            eb.c.A1s = base + pk.A1s;
+            eb.c.A2t = base + pk.W2t;
+            eb.c.bp = bp;
+            for (int q = 0; q < eb.n; ++q) {
+                SlabView &v = views[p0 + q];
+                EdgeArgs &ea = eb.s[q];
+                ea.n_rows = v.n_owned;
+                ea.n_chunks = std::max<int64_t>(1, (v.n_edges_owned + kChunkEdges - 1) / kChunkEdges);
+                ea.n_nodes = v.n_local;
+                ea.row_ptr = v.row_ptr;
+                ea.senders = v.senders;
+                ea.recv = v.recv;
+                ea.d = v.d;
+                ea.g = gslice(v, l);
+                ea.out = aslice(v, l);
+                ea.wstore = (l >= 1) ? wslice(v, l) : nullptr;
+            }
             prof_begin(g, MLIP_PROF_EDGE_FWD);
-            MLIP_TRY((launch_edge<F>(g, ea, false)));
+            MLIP_TRY((launch_edge<F>(g, eb, false)));
             prof_end(g);
         }
         prof_begin(g, MLIP_PROF_NODE);
@@ -1231,31 +1277,35 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, int32_t mode, double *ener
             MLIP_TRY((launch_node<F, OP_BWD_UPDATE>(g, na)));
         }
         prof_end(g);
-        for (int p = 0; p < P; ++p) {
-            SlabView &v = views[p];
-            EdgeArgs ea{};
-            ea.n_rows = v.n_local;
-            ea.n_chunks = std::max<int64_t>(1, (v.n_edges + kChunkEdges - 1) / kChunkEdges);
-            ea.row_ptr = v.row_ptr;
-            ea.senders = v.senders;
-            ea.recv = v.recv;
-            ea.d = v.d;
-            ea.g = gslice(v, l);
-            ea.abar = v.abar.as<float>();
-            ea.out = v.gbar.as<float>();
-            ea.dsum = v.dsum.as<float>();
-            ea.A1 = base + pk.A1;
-            ea.A1s = base + pk.A1s;
-            ea.n_nodes = v.n_local;
-            ea.A2t = base + pk.W2t;
-            ea.A2n = base + pk.W2n;
-            ea.bp = bp;
-            ea.need_gbar = need_gbar ? 1 : 0;
-            ea.wstore = need_gbar ? wslice(v, l) : nullptr;
-            ea.n_stored = need_gbar ? v.n_edges_owned : 0;
-            ea.first = (l == L - 1) ? 1 : 0;
+        for (int p0 = 0; p0 < P; p0 += kBatch) {
+            EdgeBatch eb{};
+            eb.n = std::min(kBatch, P - p0);
+            eb.c.A1 = base + pk.A1;
+            eb.c.A1s = base + pk.A1s;
+            eb.c.A2t = base + pk.W2t;
+            eb.c.A2n = base + pk.W2n;
+            eb.c.bp = bp;
+            eb.c.need_gbar = need_gbar ? 1 : 0;
+            eb.c.first = (l == L - 1) ? 1 : 0;
+            for (int q = 0; q < eb.n; ++q) {
+                SlabView &v = views[p0 + q];
+                EdgeArgs &ea = eb.s[q];
+                ea.n_rows = v.n_local;
+                ea.n_chunks = std::max<int64_t>(1, (v.n_edges + kChunkEdges - 1) / kChunkEdges);
+                ea.n_nodes = v.n_local;
+                ea.row_ptr = v.row_ptr;
+                ea.senders = v.senders;
+                ea.recv = v.recv;
+                ea.d = v.d;
+                ea.g = gslice(v, l);
+                ea.abar = v.abar.as<float>();
+                ea.out = v.gbar.as<float>();
+                ea.dsum = v.dsum.as<float>();
+                ea.wstore = need_gbar ? wslice(v, l) : nullptr;
+                ea.n_stored = need_gbar ? v.n_edges_owned : 0;
+            }
             prof_begin(g, MLIP_PROF_EDGE_BWD);
-            MLIP_TRY((launch_edge<F>(g, ea, true)));
+            MLIP_TRY((launch_edge<F>(g, eb, true)));
             prof_end(g);
         }
         if (need_gbar) {

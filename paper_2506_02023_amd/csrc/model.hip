@@ -719,14 +719,20 @@ __global__ void __launch_bounds__(256, 2) k_edge_bwd(EdgeBatch B)
 
 enum { OP_PROJ = 0, OP_UPDATE = 1, OP_READOUT = 2, OP_BWD_UPDATE = 3, OP_BWD_PROJ = 4 };
 
-struct NodeArgs {
+struct NodeArgs {      // one partition
     int64_t n_rows;
     const float *X;    // GEMM input rows
     float *Y;          // primary output rows
     float *Z;          // secondary in/out rows (h for UPDATE, hbar for BWD_*)
+    float *eps;
+};
+
+struct NodeBatch {     // up to kBatch partitions per launch, 32-row tiles numbered across them
     const float *P1, *P2;
     const float *wr2;
-    float *eps;
+    int n;
+    int64_t tile_start[kBatch + 1];
+    NodeArgs s[kBatch];
 };
 
 template <int F>
@@ -746,7 +752,7 @@ __device__ inline void load_tile(const float *__restrict__ X, int64_t row0, int6
 }
 
 template <int F, int OP>
-__global__ void __launch_bounds__(256) k_node(NodeArgs A)
+__global__ void __launch_bounds__(256) k_node(NodeBatch B)
 {
     using D = Dims<F>;
     constexpr bool TWO = (OP == OP_READOUT || OP == OP_BWD_UPDATE);
@@ -755,16 +761,18 @@ __global__ void __launch_bounds__(256) k_node(NodeArgs A)
     float *P2 = P1 + D::PACKF;
     float *tiles = P2 + (TWO ? D::PACKF : 0);
     for (int i = threadIdx.x; i < D::PACKF; i += 256) {
-        P1[i] = A.P1[i];
-        if (TWO) P2[i] = A.P2[i];
+        P1[i] = B.P1[i];
+        if (TWO) P2[i] = B.P2[i];
     }
     __syncthreads();
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int c32 = lane & 31, h = lane >> 5;
     float *tile = tiles + wave * D::TILE;
-    const int64_t n_tiles = (A.n_rows + 31) / 32;
+    const int64_t n_tiles = B.tile_start[B.n];
     for (int64_t ti = (int64_t)blockIdx.x * 4 + wave; ti < n_tiles; ti += (int64_t)gridDim.x * 4) {
-        const int64_t row0 = ti * 32;
+        const int part = batch_find(B.tile_start, B.n, ti);
+        const NodeArgs A = B.s[part];
+        const int64_t row0 = (ti - B.tile_start[part]) * 32;
         const int64_t row = row0 + c32;
         const bool ok = row < A.n_rows;
         load_tile<F>(A.X, row0, A.n_rows, tile, lane);
@@ -805,7 +813,7 @@ __global__ void __launch_bounds__(256) k_node(NodeArgs A)
             for (int b = 0; b < D::NB; ++b)
 #pragma unroll
                 for (int a = 0; a < 4; ++a) {
-                    const f32x4 wv = *reinterpret_cast<const f32x4 *>(A.wr2 + 32 * b + 8 * a + 4 * h);
+                    const f32x4 wv = *reinterpret_cast<const f32x4 *>(B.wr2 + 32 * b + 8 * a + 4 * h);
 #pragma unroll
                     for (int c = 0; c < 4; ++c) {
                         const float x = acc[b][4 * a + c];
@@ -1031,9 +1039,8 @@ template <int F> struct Lds {
     static constexpr size_t node2 = sizeof(float) * (2 * D::PACKF + 4 * D::TILE);
 };
 
-template <int F, int OP> int launch_node(mlip_graph *g, const NodeArgs &a)
+template <int F, int OP> int launch_node(mlip_graph *g, NodeBatch &b)
 {
-    if (a.n_rows <= 0) return MLIP_OK;
     constexpr bool TWO = (OP == OP_READOUT || OP == OP_BWD_UPDATE);
     const size_t lds = TWO ? Lds<F>::node2 : Lds<F>::node1;
     static bool configured = false;
@@ -1042,11 +1049,31 @@ template <int F, int OP> int launch_node(mlip_graph *g, const NodeArgs &a)
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         configured = true;
     }
-    const int64_t n_tiles = (a.n_rows + 31) / 32;
+    b.tile_start[0] = 0;
+    for (int q = 0; q < b.n; ++q) b.tile_start[q + 1] = b.tile_start[q] + (std::max<int64_t>(b.s[q].n_rows, 0) + 31) / 32;
+    for (int q = b.n; q < kBatch; ++q) b.tile_start[q + 1] = b.tile_start[b.n];
+    const int64_t n_tiles = b.tile_start[b.n];
+    if (n_tiles <= 0) return MLIP_OK;
     // each block keeps its weight pack in LDS, so let it walk several tiles
     const unsigned blocks = (unsigned)std::min<int64_t>((n_tiles + 3) / 4, 2048);
-    k_node<F, OP><<<blocks, 256, lds, g->stream>>>(a);
+    k_node<F, OP><<<blocks, 256, lds, g->stream>>>(b);
     MLIP_HIP(hipGetLastError());
+    return MLIP_OK;
+}
+
+// Runs one node operation over all partitions, kBatch per launch; fill(view, args) sets the rows.
+template <int F, int OP, class Fill>
+int node_pass(mlip_graph *g, SlabView *views, int P, const float *P1, const float *P2, const float *wr2, Fill fill)
+{
+    for (int p0 = 0; p0 < P; p0 += kBatch) {
+        NodeBatch nb{};
+        nb.n = std::min(kBatch, P - p0);
+        nb.P1 = P1;
+        nb.P2 = P2;
+        nb.wr2 = wr2;
+        for (int q = 0; q < nb.n; ++q) fill(views[p0 + q], nb.s[q]);
+        MLIP_TRY((launch_node<F, OP>(g, nb)));
+    }
     return MLIP_OK;
 }
 
@@ -1167,15 +1194,11 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, int32_t mode, double *ener
     for (int l = 0; l < L; ++l) {
         const float *base = wp + pk.per_layer * l;
         prof_begin(g, MLIP_PROF_NODE);
-        for (int p = 0; p < P; ++p) {  // sender projection on owned rows
-            SlabView &v = views[p];
-            NodeArgs na{};
-            na.n_rows = v.n_owned;
+        MLIP_TRY((node_pass<F, OP_PROJ>(g, views, P, base + pk.Wmt, nullptr, nullptr, [&](SlabView &v, NodeArgs &na) {
+            na.n_rows = v.n_owned;   // sender projection on owned rows
             na.X = v.h.as<float>();
             na.Y = gslice(v, l);
-            na.P1 = base + pk.Wmt;
-            MLIP_TRY((launch_node<F, OP_PROJ>(g, na)));
-        }
+        })));
         prof_end(g);
         if (slabs) {
             prof_begin(g, MLIP_PROF_GHOST);
@@ -1216,32 +1239,23 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, int32_t mode, double *ener
             prof_end(g);
         }
         prof_begin(g, MLIP_PROF_NODE);
-        for (int p = 0; p < P; ++p) {
-            SlabView &v = views[p];
-            NodeArgs na{};
+        MLIP_TRY((node_pass<F, OP_UPDATE>(g, views, P, base + pk.Wot, nullptr, nullptr, [&](SlabView &v, NodeArgs &na) {
             na.n_rows = v.n_owned;
             na.X = aslice(v, l);
             na.Z = v.h.as<float>();
-            na.P1 = base + pk.Wot;
-            MLIP_TRY((launch_node<F, OP_UPDATE>(g, na)));
-        }
+        })));
         prof_end(g);
     }
 
     // ---- readout (energy and dE/dh of the last layer in one pass)
     prof_begin(g, MLIP_PROF_NODE);
-    for (int p = 0; p < P; ++p) {
-        SlabView &v = views[p];
-        NodeArgs na{};
-        na.n_rows = v.n_owned;
-        na.X = v.h.as<float>();
-        na.Y = v.hbar.as<float>();
-        na.P1 = wp + pk.readout_t;
-        na.P2 = wp + pk.readout_n;
-        na.wr2 = w->wr2;
-        na.eps = v.eps.as<float>();
-        MLIP_TRY((launch_node<F, OP_READOUT>(g, na)));
-    }
+    MLIP_TRY((node_pass<F, OP_READOUT>(g, views, P, wp + pk.readout_t, wp + pk.readout_n, w->wr2,
+                                       [&](SlabView &v, NodeArgs &na) {
+                                           na.n_rows = v.n_owned;
+                                           na.X = v.h.as<float>();
+                                           na.Y = v.hbar.as<float>();
+                                           na.eps = v.eps.as<float>();
+                                       })));
     prof_end(g);
     prof_begin(g, MLIP_PROF_FORCE);
     {
@@ -1259,23 +1273,22 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, int32_t mode, double *ener
     prof_end(g);
 
     // ---- reverse pass
+    for (int p = 0; p < P; ++p) {  // ghost rows carry no dE/da: zero once, no kernel ever writes them
+        SlabView &v = views[p];
+        if (L > 0 && v.n_ghost > 0)
+            MLIP_HIP(hipMemsetAsync(v.abar.as<float>() + (size_t)v.n_owned * F, 0, (size_t)v.n_ghost * rowb, s));
+    }
     for (int l = L - 1; l >= 0; --l) {
         const float *base = wp + pk.per_layer * l;
         const bool need_gbar = l > 0;  // dE/dh0 is never used: the embedding does not depend on positions
         prof_begin(g, MLIP_PROF_NODE);
-        for (int p = 0; p < P; ++p) {
-            SlabView &v = views[p];
-            if (v.n_ghost > 0)  // ghost rows carry no dE/da
-                MLIP_HIP(hipMemsetAsync(v.abar.as<float>() + (size_t)v.n_owned * F, 0, (size_t)v.n_ghost * rowb, s));
-            NodeArgs na{};
-            na.n_rows = v.n_owned;
-            na.X = aslice(v, l);
-            na.Z = v.hbar.as<float>();
-            na.Y = v.abar.as<float>();
-            na.P1 = base + pk.Wot;
-            na.P2 = base + pk.Won;
-            MLIP_TRY((launch_node<F, OP_BWD_UPDATE>(g, na)));
-        }
+        MLIP_TRY((node_pass<F, OP_BWD_UPDATE>(g, views, P, base + pk.Wot, base + pk.Won, nullptr,
+                                              [&](SlabView &v, NodeArgs &na) {
+                                                  na.n_rows = v.n_owned;
+                                                  na.X = aslice(v, l);
+                                                  na.Z = v.hbar.as<float>();
+                                                  na.Y = v.abar.as<float>();
+                                              })));
         prof_end(g);
         for (int p0 = 0; p0 < P; p0 += kBatch) {
             EdgeBatch eb{};
@@ -1323,15 +1336,11 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, int32_t mode, double *ener
                 prof_end(g);
             }
             prof_begin(g, MLIP_PROF_NODE);
-            for (int p = 0; p < P; ++p) {
-                SlabView &v = views[p];
-                NodeArgs na{};
+            MLIP_TRY((node_pass<F, OP_BWD_PROJ>(g, views, P, base + pk.Wmn, nullptr, nullptr, [&](SlabView &v, NodeArgs &na) {
                 na.n_rows = v.n_owned;
                 na.X = v.gbar.as<float>();
                 na.Z = v.hbar.as<float>();
-                na.P1 = base + pk.Wmn;
-                MLIP_TRY((launch_node<F, OP_BWD_PROJ>(g, na)));
-            }
+            })));
             prof_end(g);
         }
     }

@@ -158,6 +158,13 @@ int mlip_graph_sizes(const mlip_graph_t *graph, int64_t *n_atoms, int64_t *n_edg
 int mlip_graph_csr(const mlip_graph_t *graph, const int64_t **row_ptr, const int32_t **senders,
                    const float **d);
 
+/*
+ * mirror[E] (DEVICE, borrowed): position of every edge's reverse edge, i.e. for e = (i <- j, S) the
+ * index of (j <- i, -S).  The edge set of a radius graph is symmetric; the reverse pass uses this to
+ * evaluate the distance derivative once per pair.
+ */
+int mlip_graph_mirror(const mlip_graph_t *graph, const int32_t **mirror);
+
 /* Image shifts of all edges written to a caller-owned DEVICE buffer [E][3] int32 (enqueued on the stream). */
 int mlip_graph_shifts(const mlip_graph_t *graph, int32_t *shifts);
 

@@ -54,6 +54,7 @@ def lib():
         L.mlip_graph_sizes.argtypes = [vp, ctypes.POINTER(i64), ctypes.POINTER(i64), ctypes.POINTER(i32)]
         L.mlip_graph_csr.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp)]
         L.mlip_graph_shifts.argtypes = [vp, vp]
+        L.mlip_graph_mirror.argtypes = [vp, ctypes.POINTER(vp)]
         L.mlip_graph_slab_of.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(i32)]
         L.mlip_graph_slab.argtypes = [vp, i32, ctypes.POINTER(_SlabInfo)]
         L.mlip_graph_from.argtypes = [vp, i32, i32, ctypes.POINTER(vp), ctypes.POINTER(i64)]
@@ -112,6 +113,13 @@ class Graph:
         torch.cuda.synchronize()
         return (self._host(rp.value, N + 1, np.int64), self._host(sd.value, E, np.int32),
                 shifts[:E].cpu().numpy(), self._host(dd.value, E, np.float32))
+
+    def mirror(self):
+        """int32 [E]: position of every edge's reverse edge."""
+        _, E, _ = self.sizes()
+        ptr = ctypes.c_void_p()
+        _check(lib().mlip_graph_mirror(self._h, ctypes.byref(ptr)))
+        return self._host(ptr.value, E, np.int32)
 
     def slab_of(self):
         N, _, _ = self.sizes()

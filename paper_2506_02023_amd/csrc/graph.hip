@@ -39,7 +39,7 @@ __device__ inline int floordiv(int a, int b)
     return q;
 }
 
-enum { ERR_RANGE = 1, ERR_COINCIDENT = 2 };
+enum { ERR_RANGE = 1, ERR_COINCIDENT = 2, ERR_MIRROR = 4 };
 
 // ---------------------------------------------------------------- scans
 
@@ -341,6 +341,36 @@ k_sort_rows(int64_t N, CellParams cp, const double *__restrict__ pos, const int6
     }
 }
 
+// mirror[e] = position of the reverse edge (send(e) <- recv(e), -S).  The edge predicate is symmetric
+// bit for bit, so the reverse edge always exists; rows are sorted by (global sender id, shift), which
+// makes this a binary search in the sender's row.  nodes == nullptr: row and sender ids are global.
+__global__ void k_mirror(int64_t E, const int64_t *__restrict__ row_ptr, const int32_t *__restrict__ senders,
+                         const int32_t *__restrict__ recv, const uint32_t *__restrict__ shiftp,
+                         const int32_t *__restrict__ nodes, int32_t *__restrict__ mirror, int32_t *err)
+{
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= E) return;
+    const int32_t r = recv[e], sd = senders[e];
+    int a, b, c;
+    unpack3(shiftp[e], a, b, c);
+    const uint64_t want = ((uint64_t)(uint32_t)(nodes ? nodes[r] : r) << 32) | pack3(-a, -b, -c);
+    int64_t lo = row_ptr[sd], hi = row_ptr[sd + 1];
+    const int64_t end = hi;
+    while (lo < hi) {
+        const int64_t mid = (lo + hi) >> 1;
+        const int32_t sm = senders[mid];
+        const uint64_t key = ((uint64_t)(uint32_t)(nodes ? nodes[sm] : sm) << 32) | shiftp[mid];
+        if (key < want) lo = mid + 1; else hi = mid;
+    }
+    bool ok = false;
+    if (lo < end) {
+        const int32_t sm = senders[lo];
+        ok = ((((uint64_t)(uint32_t)(nodes ? nodes[sm] : sm)) << 32) | shiftp[lo]) == want;
+    }
+    mirror[e] = ok ? (int32_t)lo : (int32_t)e;
+    if (!ok) atomicOr(err, ERR_MIRROR);
+}
+
 __global__ void k_unpack_shifts(int64_t E, const uint32_t *__restrict__ shiftp, int32_t *out)
 {
     const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -629,11 +659,17 @@ int build_graph_impl(mlip_graph *g, const double *positions, const double *cell,
         set_error("two atoms (or an atom and one of its images) coincide");
         return MLIP_ECOINCIDENT;
     }
+    if (E >= ((int64_t)1 << 31)) {
+        prof_end(g);
+        set_error("more than 2^31 directed edges");
+        return MLIP_EINVAL;
+    }
     const size_t Ecap = (size_t)std::max<int64_t>(E, 1);
     MLIP_TRY(g->keys.ensure(Ecap * 8));
     MLIP_TRY(g->senders.ensure(Ecap * 4));
     MLIP_TRY(g->shiftp.ensure(Ecap * 4));
     MLIP_TRY(g->recv.ensure(Ecap * 4));
+    MLIP_TRY(g->mirror.ensure(Ecap * 4));
     MLIP_TRY(g->d.ensure(Ecap * 4));
     k_neighbours<true><<<blocks_for(N, 128), 128, 0, s>>>(
         N, cp, g->cell_start.as<int32_t>(), g->sid.as<int32_t>(), g->sx.as<double>(), g->sy.as<double>(),
@@ -644,6 +680,13 @@ int build_graph_impl(mlip_graph *g, const double *positions, const double *cell,
                                            g->senders.as<int32_t>(), g->recv.as<int32_t>(), g->shiftp.as<uint32_t>(), g->d.as<float>());
     MLIP_HIP(hipGetLastError());
 
+    if (E > 0) {
+        k_mirror<<<blocks_for(E, 256), 256, 0, s>>>(E, g->row_ptr.as<int64_t>(), g->senders.as<int32_t>(),
+                                                    g->recv.as<int32_t>(), g->shiftp.as<uint32_t>(), nullptr,
+                                                    g->mirror.as<int32_t>(), err);
+        MLIP_HIP(hipGetLastError());
+    }
+
     SlabView &W = g->whole;
     W.n_owned = W.n_pure = W.n_local = N;
     W.n_border = W.n_ghost = 0;
@@ -653,6 +696,7 @@ int build_graph_impl(mlip_graph *g, const double *positions, const double *cell,
     W.senders = g->senders.as<int32_t>();
     W.shiftp = g->shiftp.as<uint32_t>();
     W.recv = g->recv.as<int32_t>();
+    W.mirror = g->mirror.as<int32_t>();
     W.d = g->d.as<float>();
     W.markers = {0, N, N, N};
 
@@ -719,6 +763,7 @@ int build_graph_impl(mlip_graph *g, const double *positions, const double *cell,
             MLIP_TRY(st.senders.ensure(ne * 4));
             MLIP_TRY(st.shiftp.ensure(ne * 4));
             MLIP_TRY(st.recv.ensure(ne * 4));
+            MLIP_TRY(st.mirror.ensure(ne * 4));
             MLIP_TRY(st.d.ensure(ne * 4));
             if (v.n_local > 0) {
                 k_local_fill<<<(unsigned)v.n_local, 64, 0, s>>>(
@@ -733,6 +778,14 @@ int build_graph_impl(mlip_graph *g, const double *positions, const double *cell,
             v.senders = st.senders.as<int32_t>();
             v.shiftp = st.shiftp.as<uint32_t>();
             v.recv = st.recv.as<int32_t>();
+            v.mirror = st.mirror.as<int32_t>();
+            if (v.n_edges > 0) {   // the local edge set (owned rows + ghost sub-rows) is symmetric as well
+                k_mirror<<<blocks_for(v.n_edges, 256), 256, 0, s>>>(v.n_edges, st.row_ptr.as<int64_t>(),
+                                                                    st.senders.as<int32_t>(), st.recv.as<int32_t>(),
+                                                                    st.shiftp.as<uint32_t>(), st.nodes.as<int32_t>(),
+                                                                    st.mirror.as<int32_t>(), err);
+                MLIP_HIP(hipGetLastError());
+            }
             v.d = st.d.as<float>();
             v.ghost_owner = st.ghost_owner.as<int32_t>();
             v.ghost_src = st.ghost_src.as<int32_t>();
@@ -748,6 +801,12 @@ int build_graph_impl(mlip_graph *g, const double *positions, const double *cell,
         }
     }
     prof_end(g);
+    MLIP_HIP(hipMemcpyAsync(hp, err, 4, hipMemcpyDeviceToHost, s));
+    MLIP_HIP(hipStreamSynchronize(s));
+    if (*reinterpret_cast<int32_t *>(hp) & ERR_MIRROR) {
+        set_error("internal error: an edge without its reverse edge");
+        return MLIP_EHIP;
+    }
     g->N = N;
     g->E = E;
     g->P = P;

@@ -60,6 +60,7 @@ struct SlabView {
     const int32_t *senders = nullptr;      // local ids
     const uint32_t *shiftp = nullptr;      // packed image shifts
     const int32_t *recv = nullptr;         // receiver (local row) of every edge
+    const int32_t *mirror = nullptr;       // position of every edge's reverse edge
     const float *d = nullptr;              // edge lengths
     const int32_t *ghost_owner = nullptr;  // [n_ghost] owning slab
     const int32_t *ghost_src = nullptr;    // [n_ghost] local index inside the owner
@@ -69,7 +70,7 @@ struct SlabView {
 };
 
 struct SlabStore {  // device arrays owned per slab
-    DevBuf nodes, row_ptr, senders, recv, shiftp, d, ghost_owner, ghost_src, owned_sorted, rowlen;
+    DevBuf nodes, row_ptr, senders, recv, mirror, shiftp, d, ghost_owner, ghost_src, owned_sorted, rowlen;
 };
 
 enum { kMaxSlabs = 64, kMaxEvents = 4096 };
@@ -98,7 +99,7 @@ struct mlip_graph {
     mlip::DevBuf cell_of, wrapp, cell_cnt, cell_start, cell_fill, sid, sx, sy, sz, swrap, counts, keys, flags,
         scan_tmp, small;
     // whole-graph CSR
-    mlip::DevBuf row_ptr, senders, recv, shiftp, d;
+    mlip::DevBuf row_ptr, senders, recv, mirror, shiftp, d;
     // partition
     mlip::DevBuf slab_of, needed_by, local_of, local_in_owner, class_cnt, class_off;
     std::vector<mlip::SlabStore> store;

@@ -109,3 +109,17 @@ def test_partition_triclinic(P):
 def test_partition_medium_8_slabs():
     c, _, _ = oracle_config(1)
     _check_partition(c["positions"], c["cell"], c["species"], c["r_cut"], 8)
+
+
+def test_mirror_index():
+    """mirror[e] is the reverse edge: receiver and sender swapped, shift negated; an involution."""
+    for pos, cell, sp, rc in [(*wl.random_triclinic(60, 4, scale=5.0)[:3], 3.3),
+                              (*[oracle_config(0)[0][k] for k in ("positions", "cell", "species")], 5.0)]:
+        g = gpu_graph(pos, cell, sp, rc)
+        row_ptr, senders, shifts, _ = g.csr()
+        recv = np.repeat(np.arange(len(row_ptr) - 1), np.diff(row_ptr))
+        m = g.mirror()
+        assert np.array_equal(m[m], np.arange(len(m)))
+        assert np.array_equal(senders[m], recv) and np.array_equal(recv[m], senders)
+        assert np.array_equal(shifts[m], -shifts)
+        assert not np.any(m == np.arange(len(m)))

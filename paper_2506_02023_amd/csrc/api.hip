@@ -169,7 +169,7 @@ void mlip_graph_destroy(mlip_graph_t *g)
     (void)hipStreamSynchronize(g->stream);
     DevBuf *bufs[] = {&g->pos, &g->species, &g->cell_of, &g->wrapp, &g->cell_cnt, &g->cell_start, &g->cell_fill,
                       &g->sid, &g->sx, &g->sy, &g->sz, &g->swrap, &g->counts, &g->keys, &g->flags, &g->scan_tmp,
-                      &g->small, &g->row_ptr, &g->senders, &g->recv, &g->mirror, &g->shiftp, &g->d, &g->slab_of, &g->needed_by,
+                      &g->small, &g->row_ptr, &g->senders, &g->recv, &g->mirror, &g->shiftp, &g->d, &g->chunk_row, &g->slab_of, &g->needed_by,
                       &g->local_of, &g->local_in_owner, &g->class_cnt, &g->class_off, &g->wpack, &g->energy_part};
     for (DevBuf *b : bufs) b->release();
     auto drop_view = [](SlabView &v) {
@@ -179,7 +179,7 @@ void mlip_graph_destroy(mlip_graph_t *g)
     drop_view(g->whole);
     for (auto &v : g->slabs) drop_view(v);
     for (auto &st : g->store) {
-        DevBuf *sb[] = {&st.nodes, &st.row_ptr, &st.senders, &st.recv, &st.mirror, &st.shiftp, &st.d, &st.ghost_owner, &st.ghost_src,
+        DevBuf *sb[] = {&st.nodes, &st.row_ptr, &st.senders, &st.recv, &st.mirror, &st.shiftp, &st.d, &st.chunk_row, &st.ghost_owner, &st.ghost_src,
                         &st.owned_sorted, &st.rowlen};
         for (DevBuf *b : sb) b->release();
     }

@@ -341,34 +341,67 @@ k_sort_rows(int64_t N, CellParams cp, const double *__restrict__ pos, const int6
     }
 }
 
+// chunk_row[c] = first row whose first edge lies at or after c * kChunkEdges; chunk_row[n_chunks] = n_rows.
+__global__ void k_chunk_rows(int64_t n_rows, int64_t n_chunks, const int64_t *__restrict__ row_ptr,
+                             int32_t *__restrict__ chunk_row)
+{
+    const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (c > n_chunks) return;
+    int64_t lo = 0, hi = n_rows;
+    if (c == n_chunks) lo = n_rows;
+    const int64_t v = c * kChunkEdges;
+    while (lo < hi) {
+        const int64_t mid = (lo + hi) >> 1;
+        if (row_ptr[mid] < v) lo = mid + 1; else hi = mid;
+    }
+    chunk_row[c] = (int32_t)lo;
+}
+
 // mirror[e] = position of the reverse edge (send(e) <- recv(e), -S).  The edge predicate is symmetric
 // bit for bit, so the reverse edge always exists; rows are sorted by (global sender id, shift), which
 // makes this a binary search in the sender's row.  nodes == nullptr: row and sender ids are global.
+//   PAIRS: only the edge of each pair whose sender id is the larger one (for a self-image pair: the larger
+//          packed shift) searches, and writes both entries of the pair (whole graph);
+//   else:  only edges whose sender is at or after min_sender search (local graphs: the senders that are
+//          ghost rows; all other entries follow from the whole graph's index, see k_local_fill).
+template <bool PAIRS>
 __global__ void k_mirror(int64_t E, const int64_t *__restrict__ row_ptr, const int32_t *__restrict__ senders,
                          const int32_t *__restrict__ recv, const uint32_t *__restrict__ shiftp,
-                         const int32_t *__restrict__ nodes, int32_t *__restrict__ mirror, int32_t *err)
+                         const int32_t *__restrict__ nodes, int32_t min_sender, int32_t *__restrict__ mirror,
+                         int32_t *err)
 {
     const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= E) return;
     const int32_t r = recv[e], sd = senders[e];
+    if (sd < min_sender) return;
+    const uint32_t sp = shiftp[e];
     int a, b, c;
-    unpack3(shiftp[e], a, b, c);
-    const uint64_t want = ((uint64_t)(uint32_t)(nodes ? nodes[r] : r) << 32) | pack3(-a, -b, -c);
+    unpack3(sp, a, b, c);
+    const uint32_t sneg = pack3(-a, -b, -c);
+    if (PAIRS && (sd < r || (sd == r && sp < sneg))) return;
+    const uint32_t want_id = (uint32_t)(nodes ? nodes[r] : r);
     int64_t lo = row_ptr[sd], hi = row_ptr[sd + 1];
     const int64_t end = hi;
     while (lo < hi) {
         const int64_t mid = (lo + hi) >> 1;
         const int32_t sm = senders[mid];
-        const uint64_t key = ((uint64_t)(uint32_t)(nodes ? nodes[sm] : sm) << 32) | shiftp[mid];
-        if (key < want) lo = mid + 1; else hi = mid;
+        const uint32_t id = (uint32_t)(nodes ? nodes[sm] : sm);
+        bool less = id < want_id;
+        if (id == want_id) less = shiftp[mid] < sneg;   // several images of one neighbour: small cells only
+        if (less) lo = mid + 1; else hi = mid;
     }
     bool ok = false;
     if (lo < end) {
         const int32_t sm = senders[lo];
-        ok = ((((uint64_t)(uint32_t)(nodes ? nodes[sm] : sm)) << 32) | shiftp[lo]) == want;
+        ok = (uint32_t)(nodes ? nodes[sm] : sm) == want_id && shiftp[lo] == sneg;
     }
-    mirror[e] = ok ? (int32_t)lo : (int32_t)e;
-    if (!ok) atomicOr(err, ERR_MIRROR);
+    if (ok) {
+        mirror[e] = (int32_t)lo;
+        if (PAIRS) mirror[lo] = (int32_t)e;
+    } else {
+        mirror[e] = (int32_t)e;
+        atomicOr(err, ERR_MIRROR);
+    }
 }
 
 __global__ void k_unpack_shifts(int64_t E, const uint32_t *__restrict__ shiftp, int32_t *out)
@@ -481,7 +514,8 @@ k_local_fill(int64_t n_local, int64_t n_owned, const int32_t *__restrict__ nodes
              const int64_t *__restrict__ row_ptr, const int32_t *__restrict__ senders,
              const uint32_t *__restrict__ shiftp, const float *__restrict__ d,
              const int32_t *__restrict__ slab_of, const int32_t *__restrict__ local_of, int q,
-             const int64_t *__restrict__ lrow_ptr, int32_t *lsenders, int32_t *lrecv, uint32_t *lshiftp, float *ld)
+             const int32_t *__restrict__ gmirror, const int64_t *__restrict__ lrow_ptr, int32_t *lsenders,
+             int32_t *lrecv, uint32_t *lshiftp, float *ld, int32_t *lmirror)
 {
     const int64_t r = blockIdx.x;
     const int32_t u = nodes[r];
@@ -502,7 +536,11 @@ k_local_fill(int64_t n_local, int64_t n_owned, const int32_t *__restrict__ nodes
         if (keep) {
             const int64_t o = out + __popcll(m & lt);
             if (o < out_end) {
-                lsenders[o] = local_of[j];
+                const int32_t jl = local_of[j];
+                lsenders[o] = jl;
+                // reverse edge: an owned sender's local row is its whole global row, so the reverse edge keeps
+                // its offset inside the row; a ghost sender's sub-row is searched afterwards (k_mirror)
+                lmirror[o] = (jl < n_owned) ? (int32_t)(lrow_ptr[jl] + ((int64_t)gmirror[e] - row_ptr[j])) : -1;
                 lshiftp[o] = shiftp[e];
                 lrecv[o] = (int32_t)r;
                 ld[o] = d[e];
@@ -681,9 +719,16 @@ int build_graph_impl(mlip_graph *g, const double *positions, const double *cell,
     MLIP_HIP(hipGetLastError());
 
     if (E > 0) {
-        k_mirror<<<blocks_for(E, 256), 256, 0, s>>>(E, g->row_ptr.as<int64_t>(), g->senders.as<int32_t>(),
-                                                    g->recv.as<int32_t>(), g->shiftp.as<uint32_t>(), nullptr,
-                                                    g->mirror.as<int32_t>(), err);
+        k_mirror<true><<<blocks_for(E, 256), 256, 0, s>>>(E, g->row_ptr.as<int64_t>(), g->senders.as<int32_t>(),
+                                                          g->recv.as<int32_t>(), g->shiftp.as<uint32_t>(), nullptr, 0,
+                                                          g->mirror.as<int32_t>(), err);
+        MLIP_HIP(hipGetLastError());
+    }
+
+    {
+        const int64_t nc = chunks_of(E);
+        MLIP_TRY(g->chunk_row.ensure((size_t)(nc + 1) * 4));
+        k_chunk_rows<<<blocks_for(nc + 1, 256), 256, 0, s>>>(N, nc, g->row_ptr.as<int64_t>(), g->chunk_row.as<int32_t>());
         MLIP_HIP(hipGetLastError());
     }
 
@@ -698,6 +743,7 @@ int build_graph_impl(mlip_graph *g, const double *positions, const double *cell,
     W.recv = g->recv.as<int32_t>();
     W.mirror = g->mirror.as<int32_t>();
     W.d = g->d.as<float>();
+    W.chunk_row = g->chunk_row.as<int32_t>();
     W.markers = {0, N, N, N};
 
     // ------------------------------------------------------------ partition
@@ -769,8 +815,8 @@ int build_graph_impl(mlip_graph *g, const double *positions, const double *cell,
                 k_local_fill<<<(unsigned)v.n_local, 64, 0, s>>>(
                     v.n_local, v.n_owned, st.nodes.as<int32_t>(), g->row_ptr.as<int64_t>(), g->senders.as<int32_t>(),
                     g->shiftp.as<uint32_t>(), g->d.as<float>(), g->slab_of.as<int32_t>(), g->local_of.as<int32_t>(), q,
-                    st.row_ptr.as<int64_t>(), st.senders.as<int32_t>(), st.recv.as<int32_t>(), st.shiftp.as<uint32_t>(),
-                    st.d.as<float>());
+                    g->mirror.as<int32_t>(), st.row_ptr.as<int64_t>(), st.senders.as<int32_t>(), st.recv.as<int32_t>(),
+                    st.shiftp.as<uint32_t>(), st.d.as<float>(), st.mirror.as<int32_t>());
                 MLIP_HIP(hipGetLastError());
             }
             v.nodes = st.nodes.as<int32_t>();
@@ -779,14 +825,23 @@ int build_graph_impl(mlip_graph *g, const double *positions, const double *cell,
             v.shiftp = st.shiftp.as<uint32_t>();
             v.recv = st.recv.as<int32_t>();
             v.mirror = st.mirror.as<int32_t>();
-            if (v.n_edges > 0) {   // the local edge set (owned rows + ghost sub-rows) is symmetric as well
-                k_mirror<<<blocks_for(v.n_edges, 256), 256, 0, s>>>(v.n_edges, st.row_ptr.as<int64_t>(),
-                                                                    st.senders.as<int32_t>(), st.recv.as<int32_t>(),
-                                                                    st.shiftp.as<uint32_t>(), st.nodes.as<int32_t>(),
-                                                                    st.mirror.as<int32_t>(), err);
+            if (v.n_edges_owned > 0 && v.n_ghost > 0) {
+                // the local edge set (owned rows + ghost sub-rows) is symmetric as well; what is left to find
+                // are the reverse edges of owned rows' edges from ghost senders, inside the ghost sub-rows
+                k_mirror<false><<<blocks_for(v.n_edges_owned, 256), 256, 0, s>>>(
+                    v.n_edges_owned, st.row_ptr.as<int64_t>(), st.senders.as<int32_t>(), st.recv.as<int32_t>(),
+                    st.shiftp.as<uint32_t>(), st.nodes.as<int32_t>(), (int32_t)v.n_owned, st.mirror.as<int32_t>(), err);
                 MLIP_HIP(hipGetLastError());
             }
             v.d = st.d.as<float>();
+            {
+                const int64_t nc = chunks_of(v.n_edges);
+                MLIP_TRY(st.chunk_row.ensure((size_t)(nc + 1) * 4));
+                k_chunk_rows<<<blocks_for(nc + 1, 256), 256, 0, s>>>(v.n_local, nc, st.row_ptr.as<int64_t>(),
+                                                                      st.chunk_row.as<int32_t>());
+                MLIP_HIP(hipGetLastError());
+                v.chunk_row = st.chunk_row.as<int32_t>();
+            }
             v.ghost_owner = st.ghost_owner.as<int32_t>();
             v.ghost_src = st.ghost_src.as<int32_t>();
         }

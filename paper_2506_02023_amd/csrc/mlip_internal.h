@@ -50,6 +50,13 @@ struct CellParams {
     int n_slabs;
 };
 
+// Work item of the edge kernels: the rows whose first edge lies in one span of kChunkEdges edges.
+#ifndef MLIP_CHUNK
+#define MLIP_CHUNK 512
+#endif
+constexpr int kChunkEdges = MLIP_CHUNK;
+inline int64_t chunks_of(int64_t n_edges) { return n_edges > 0 ? (n_edges + kChunkEdges - 1) / kChunkEdges : 1; }
+
 // One partition as the model kernels see it.  The whole graph is the special
 // case nodes == nullptr (identity), n_owned == n_local == N.
 struct SlabView {
@@ -62,6 +69,7 @@ struct SlabView {
     const int32_t *recv = nullptr;         // receiver (local row) of every edge
     const int32_t *mirror = nullptr;       // position of every edge's reverse edge
     const float *d = nullptr;              // edge lengths
+    const int32_t *chunk_row = nullptr;    // [chunks_of(n_edges) + 1] first row of every work item, then n_local
     const int32_t *ghost_owner = nullptr;  // [n_ghost] owning slab
     const int32_t *ghost_src = nullptr;    // [n_ghost] local index inside the owner
     std::vector<int64_t> markers;          // host, P + 3
@@ -70,7 +78,7 @@ struct SlabView {
 };
 
 struct SlabStore {  // device arrays owned per slab
-    DevBuf nodes, row_ptr, senders, recv, mirror, shiftp, d, ghost_owner, ghost_src, owned_sorted, rowlen;
+    DevBuf nodes, row_ptr, senders, recv, mirror, shiftp, d, chunk_row, ghost_owner, ghost_src, owned_sorted, rowlen;
 };
 
 enum { kMaxSlabs = 64, kMaxEvents = 4096 };
@@ -99,7 +107,7 @@ struct mlip_graph {
     mlip::DevBuf cell_of, wrapp, cell_cnt, cell_start, cell_fill, sid, sx, sy, sz, swrap, counts, keys, flags,
         scan_tmp, small;
     // whole-graph CSR
-    mlip::DevBuf row_ptr, senders, recv, mirror, shiftp, d;
+    mlip::DevBuf row_ptr, senders, recv, mirror, shiftp, d, chunk_row;
     // partition
     mlip::DevBuf slab_of, needed_by, local_of, local_in_owner, class_cnt, class_off;
     std::vector<mlip::SlabStore> store;

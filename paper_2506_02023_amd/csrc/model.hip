@@ -42,7 +42,6 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kBufferFlags = 0x00020000;  // raw 32-bit buffer descriptor word 3 on gfx9-family targets
-constexpr int kChunkEdges = 1024;  // edges per wavefront work item (32 tiles of 32)
 constexpr float kPi = 3.14159265358979323846f;
 
 __device__ inline void wave_lds_fence()
@@ -372,6 +371,8 @@ struct EdgeArgs {
     float *out;                // forward: a [n_rows][F]; reverse: gbar [n_rows][F]
     float *dsum;               // reverse: per-edge dE/dd of the edge and its mirror, summed over layers
     float *wstore;             // forward: filter values w_e [n_stored][F] kept for the reverse pass (or null)
+    const int32_t *mirror;     // reverse: position of every edge's reverse edge
+    const int32_t *chunk_row;  // first row of every work item
 };
 
 // What all partitions of one launch share: the layer's packed weights and the basis.
@@ -392,6 +393,26 @@ struct EdgeBatch {
     EdgeArgs s[kBatch];
 };
 
+// Persistent launch: the grid holds exactly the blocks that are resident at once, a multiple of 8.
+// Blocks go to the 8 XCDs round-robin, so blocks b with the same b % 8 share an L2.  Each XCD takes one
+// contiguous eighth of the work items and its blocks walk through it side by side (block slot s, wave w
+// takes items 4 s + w, 4 (s + n_slots) + w, ...): at any moment an XCD works on a short contiguous run
+// of rows, whose neighbourhoods overlap, so the sender rows it gathers stay in its L2.
+struct ItemRange {
+    int64_t first, end, stride;
+};
+__device__ inline ItemRange edge_items(int64_t total, int wave)
+{
+    const int64_t n_slots = gridDim.x >> 3;
+    const int64_t per = (((total + 7) >> 3) + 3) & ~(int64_t)3;
+    const int64_t xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    ItemRange r;
+    r.first = xcd * per + slot * 4 + wave;
+    r.end = min(total, (xcd + 1) * per);
+    r.stride = n_slots * 4;
+    return r;
+}
+
 __device__ inline int batch_find(const int64_t *start, int n, int64_t w)
 {
     int p = 0;
@@ -401,12 +422,21 @@ __device__ inline int batch_find(const int64_t *start, int n, int64_t w)
     return p;
 }
 
+// Read-only graph arrays are read through the constant address space when the index is
+// wave-uniform: the load then goes through the scalar cache into SGPRs and costs no vector issue slot.
+// (Valid because no kernel of this file writes the graph arrays.)
+typedef const __attribute__((address_space(4))) int32_t *const_i32_ptr;
+__device__ inline int32_t uniform_load(const int32_t *p, int64_t i)
+{
+    return reinterpret_cast<const_i32_ptr>(reinterpret_cast<uintptr_t>(p))[i];
+}
+
 // wavefront work item: the rows whose first edge lies in [chunk * kChunkEdges, (chunk + 1) * kChunkEdges)
 __device__ inline bool chunk_rows(const EdgeArgs &A, int64_t chunk, int64_t &r0, int64_t &r1)
 {
-    const int64_t lo = chunk * kChunkEdges;
-    r0 = lower_bound_i64(A.row_ptr, A.n_rows, lo);
-    r1 = (chunk == A.n_chunks - 1) ? A.n_rows : lower_bound_i64(A.row_ptr, A.n_rows, lo + kChunkEdges);
+    r0 = uniform_load(A.chunk_row, chunk);
+    r1 = uniform_load(A.chunk_row, chunk + 1);
+    if (chunk == A.n_chunks - 1) r1 = A.n_rows;   // the forward step stops at the owned rows
     return r0 < r1;
 }
 
@@ -419,15 +449,6 @@ __device__ inline float buffer_load_f32(__amdgpu_buffer_rsrc_t r, unsigned voff,
 __device__ inline void buffer_store_f32(float v, __amdgpu_buffer_rsrc_t r, unsigned voff, int soff, int)
 {
     __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), r, voff, soff, 0);
-}
-
-// Read-only graph arrays are read through the constant address space when the index is
-// wave-uniform: the load then goes through the scalar cache into SGPRs and costs no vector issue slot.
-// (Valid because no kernel of this file writes the graph arrays.)
-typedef const __attribute__((address_space(4))) int32_t *const_i32_ptr;
-__device__ inline int32_t uniform_load(const int32_t *p, int64_t i)
-{
-    return reinterpret_cast<const_i32_ptr>(reinterpret_cast<uintptr_t>(p))[i];
 }
 
 // Per-tile row bookkeeping shared by both edge kernels.  Every lane holds the receiver of its edge
@@ -454,18 +475,21 @@ __global__ void __launch_bounds__(256, 3) k_edge_fwd(EdgeBatch B)
     const int c32 = lane & 31;
     const unsigned f = lane & (F - 1);
     float *tile = tiles + wave * D::TILE;
-    const int64_t item = (int64_t)blockIdx.x * 4 + wave;
-    if (item >= B.chunk_start[B.n]) return;
-    const int part = batch_find(B.chunk_start, B.n, item);
-    const EdgeArgs A = B.s[part];
     const EdgeCommon &C = B.c;
-    const int64_t chunk = item - B.chunk_start[part];
-    int64_t r0, r1;
-    if (!chunk_rows(A, chunk, r0, r1)) return;
     RegPack1<F> W1;
     load_pack1<F>(W1, C.A1s, lane);
+    const ItemRange items = edge_items(B.chunk_start[B.n], wave);
+    int64_t item = items.first;
+    for (int part = 0; part < B.n; ++part) {
+    const int64_t part_end = min(items.end, B.chunk_start[part + 1]);
+    if (item >= part_end) continue;
+    const EdgeArgs A = B.s[part];
     const __amdgpu_buffer_rsrc_t g_rsrc = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<float *>(A.g), 0, (int)(A.n_nodes * F * 4), kBufferFlags);
+    for (; item < part_end; item += items.stride) {
+    const int64_t chunk = item - B.chunk_start[part];
+    int64_t r0, r1;
+    if (!chunk_rows(A, chunk, r0, r1)) continue;
     const int64_t e_lo = A.row_ptr[r0], e_hi = A.row_ptr[r1];
     const int32_t r_end = (int32_t)r1;
     const bool keep_w = A.wstore != nullptr;
@@ -543,6 +567,63 @@ __global__ void __launch_bounds__(256, 3) k_edge_fwd(EdgeBatch B)
     if (e_lo >= e_hi)
         for (int64_t r = r0; r < r1; ++r)
             if (F == 64 || lane < F) A.out[r * F + f] = 0.f;
+    }   // work items
+    }   // partitions
+}
+
+// Reverse edge step.
+//
+// Phase 1 (lane = feature), 16 edges at a time, every edge of the rows:
+//   gbar_i += w_e * abar_send(e)               (w_e read back from the forward pass's store)
+//   and, for the "upper" edge of each edge / reverse-edge pair (the one with the smaller index),
+//   wsym_e = abar_i * g_j + abar_j * g_i is queued in LDS together with the edge's length and the
+//   two edge indices of the pair.
+// Phase 2 (lane = edge), whenever 32 pairs are queued: dE/dd of the pair,
+//   sum_k (W2 wsym)_k * ds_k/dd,   ds_k/dd = SiLU'(t_k) * sum_n W1[n][k] db_n/dd,
+//   on the MFMA units, written to both edges of the pair.  Both edges of a pair have the same length
+//   and the same wsym, so the dense work runs once per pair instead of once per directed edge.
+constexpr int kQueue = 48;   // queued pairs per wavefront: at most 31 pending + 16 new
+
+template <int F>
+__device__ inline void gemm_queue(const float *__restrict__ Ap, const float *row, f32x16 (&out)[Dims<F>::NB], int lane)
+{
+    // as gemm_lds, the B operand row of this lane's edge given directly (queue slot)
+    constexpr int NB = Dims<F>::NB;
+    constexpr int STEPS = NB * 4;
+    const int h = lane >> 5;
+#pragma unroll
+    for (int bo = 0; bo < NB; ++bo)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) out[bo][r] = 0.f;
+    const float *bp = row + 4 * h;
+    const float *ap = Ap + lane * 4;
+    f32x4 bv = *reinterpret_cast<const f32x4 *>(bp);
+    f32x4 av[NB];
+#pragma unroll
+    for (int bo = 0; bo < NB; ++bo) av[bo] = *reinterpret_cast<const f32x4 *>(ap + ((bo * NB) * 4) * 256);
+#pragma unroll
+    for (int st = 0; st < STEPS; ++st) {
+        f32x4 bn = bv, an[NB];
+#pragma unroll
+        for (int bo = 0; bo < NB; ++bo) an[bo] = av[bo];
+        if (st + 1 < STEPS) {
+            const int bi = (st + 1) / 4, a = (st + 1) % 4;
+            bn = *reinterpret_cast<const f32x4 *>(bp + 32 * bi + 8 * a);
+#pragma unroll
+            for (int bo = 0; bo < NB; ++bo)
+                an[bo] = *reinterpret_cast<const f32x4 *>(ap + (((bo * NB + bi) * 4 + a)) * 256);
+        }
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+#pragma unroll
+            for (int bo = 0; bo < NB; ++bo)
+                out[bo] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[bo][c], bv[c], out[bo], 0, 0, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, NB + 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 4 * NB, 0);
+        bv = bn;
+#pragma unroll
+        for (int bo = 0; bo < NB; ++bo) av[bo] = an[bo];
+    }
 }
 
 template <int F>
@@ -551,168 +632,195 @@ __global__ void __launch_bounds__(256, 2) k_edge_bwd(EdgeBatch B)
     using D = Dims<F>;
     extern __shared__ float lds[];
     float *A2n = lds;
-    float *A2t = A2n + D::PACKF;
-    float *tiles = A2t + D::PACKF;
-    for (int i = threadIdx.x; i < D::PACKF; i += 256) { A2n[i] = B.c.A2n[i]; A2t[i] = B.c.A2t[i]; }
+    float *queues = A2n + D::PACKF;
+    for (int i = threadIdx.x; i < D::PACKF; i += 256) A2n[i] = B.c.A2n[i];
     __syncthreads();
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int c32 = lane & 31;
     const unsigned f = lane & (F - 1);
-    float *tile = tiles + wave * D::TILE;
-    const int64_t item = (int64_t)blockIdx.x * 4 + wave;
-    if (item >= B.chunk_start[B.n]) return;
-    const int part = batch_find(B.chunk_start, B.n, item);
-    const EdgeArgs A = B.s[part];
+    float *Q = queues + wave * (kQueue * D::FS);
     const EdgeCommon &C = B.c;
-    const int64_t chunk = item - B.chunk_start[part];
-    int64_t r0, r1;
-    if (!chunk_rows(A, chunk, r0, r1)) return;
     RegPack1<F> W1;
     load_pack1<F>(W1, C.A1, lane);
+    const bool need_gbar = C.need_gbar != 0;
+    const int l16 = lane & 15;
+    // queue of pairs: slot s lives in LDS row s (wsym) and in lane s of q_e (the upper edge's index).
+    // It carries over from one work item to the next and is drained at the end of a partition.
+    int q_head = 0, q_count = 0;
+    int32_t q_e = 0;
+    const ItemRange items = edge_items(B.chunk_start[B.n], wave);
+    int64_t item = items.first;
+    for (int part = 0; part < B.n; ++part) {
+    const int64_t part_end = min(items.end, B.chunk_start[part + 1]);
+    if (item >= part_end) continue;
+    const EdgeArgs A = B.s[part];
     const __amdgpu_buffer_rsrc_t g_rsrc = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<float *>(A.g), 0, (int)(A.n_nodes * F * 4), kBufferFlags);
     const __amdgpu_buffer_rsrc_t a_rsrc = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<float *>(A.abar), 0, (int)(A.n_nodes * F * 4), kBufferFlags);
-    const int64_t e_lo = A.row_ptr[r0], e_hi = A.row_ptr[r1];
-    const int32_t r_end = (int32_t)r1;
     const int32_t last_row = (int32_t)(A.n_rows - 1);
-    const bool need_gbar = C.need_gbar != 0;
-    float acc = 0.f;
-    float dv = (e_lo + c32 < e_hi) ? A.d[e_lo + c32] : C.bp.rc;
-    int32_t rk = (e_lo + c32 < e_hi) ? A.recv[e_lo + c32] : r_end;
-    const int32_t row0 = min(__builtin_amdgcn_readfirstlane(rk), last_row);  // row of the first edge
-    if (need_gbar)
-        for (int64_t r = r0; r < min((int64_t)__builtin_amdgcn_readfirstlane(rk), r1); ++r)
-            if (F == 64 || lane < F) A.out[r * F + f] = 0.f;
-    // receiver-side rows (abar_i, g_i) of the current row and, prefetched, of the row after it
-    float ai = buffer_load_f32(a_rsrc, f * 4, row0 * (F * 4), 0);
-    float gi = buffer_load_f32(g_rsrc, f * 4, row0 * (F * 4), 0);
-    float ai2 = buffer_load_f32(a_rsrc, f * 4, min(row0 + 1, last_row) * (F * 4), 0);
-    float gi2 = buffer_load_f32(g_rsrc, f * 4, min(row0 + 1, last_row) * (F * 4), 0);
-    for (int64_t tb = e_lo; tb < e_hi; tb += 32) {
-        const int64_t e = tb + c32;
-        const bool valid = e < e_hi;
-        const int kmax = __builtin_amdgcn_readfirstlane((int)min((int64_t)32, e_hi - tb));
-        const int32_t rcur = rk;
-        // w_e kept by the forward pass (owned rows); otherwise it is recomputed here (ghost rows)
-        const bool stored = need_gbar && (tb + 32 <= A.n_stored);
-        float b[8], db[8];
-        radial_basis<true>(dv, C.bp, b, db);
-        // sender rows abar_j, g_j and the stored w_e, two halves of 16 edges; half 0 is in flight during
-        // the MFMA chain, half 1 while half 0 is consumed.  Rows past the end of the chunk: stored w
-        // reads as zero (hardware bounds check), the other two read row 0 and are never used.
-        float av[2][16], gv[2][16], wv[2][16];
-        const __amdgpu_buffer_rsrc_t w_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-            stored ? A.wstore + tb * F : A.wstore, 0, stored ? kmax * (F * 4) : 0, kBufferFlags);
-        int32_t sj[32];   // read unconditionally (device buffers carry 256 bytes of slack), masked afterwards
+    // state of the current work item
+    int64_t r1 = 0, e_hi = 0;
+    float acc = 0.f, ai = 0.f, gi = 0.f, ai2 = 0.f, gi2 = 0.f;
+
+    // One step of phase 1 = 16 edges.  Its loads (sender rows, kept w, receiver and reverse-edge ids)
+    // are issued one step ahead into the other of two register buffers.
+    struct Step {
+        float av[16], gv[16], wv[16];
+        int32_t rk, mk;   // receiver / reverse edge of this lane's edge; r1 / -1 past the end of the chunk
+        int kmax;
+        int64_t tb;
+    };
+    auto load_step = [&](Step &S, int64_t tb) {
+        S.tb = tb;
+        S.kmax = __builtin_amdgcn_readfirstlane((int)max((int64_t)0, min((int64_t)16, e_hi - tb)));
+        const bool in = tb + l16 < e_hi;
+        S.rk = in ? A.recv[tb + l16] : (int32_t)r1;
+        S.mk = in ? A.mirror[tb + l16] : -1;
+        if (S.kmax <= 0) return;
+        int32_t sj[16];   // read unconditionally (buffers carry slack), masked below
 #pragma unroll
-        for (int k = 0; k < 32; ++k) sj[k] = uniform_load(A.senders, tb + k);
+        for (int k = 0; k < 16; ++k) sj[k] = uniform_load(A.senders, tb + k);
+        const bool contiguous = tb + 16 <= A.n_stored;   // w_e of owned rows sits at the edge's own index
+        const __amdgpu_buffer_rsrc_t w_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+            A.wstore + (contiguous ? tb * F : 0), 0, (need_gbar && contiguous) ? S.kmax * (F * 4) : 0, kBufferFlags);
 #pragma unroll
         for (int k = 0; k < 16; ++k) {
-            const int32_t jk = (k < kmax) ? sj[k] : 0;
-            av[0][k] = buffer_load_f32(a_rsrc, f * 4, jk * (F * 4), 0);
-            gv[0][k] = buffer_load_f32(g_rsrc, f * 4, jk * (F * 4), 0);
-            wv[0][k] = buffer_load_f32(w_rsrc, f * 4, k * (F * 4), 0);
+            const int32_t jk = (k < S.kmax) ? sj[k] : 0;
+            S.av[k] = buffer_load_f32(a_rsrc, f * 4, jk * (F * 4), 0);
+            S.gv[k] = buffer_load_f32(g_rsrc, f * 4, jk * (F * 4), 0);
+            S.wv[k] = buffer_load_f32(w_rsrc, f * 4, k * (F * 4), 0);   // 0 outside the descriptor's range
         }
-        {
-            const int64_t en = tb + 32 + c32;
-            dv = (en < e_hi) ? A.d[en] : C.bp.rc;
-            rk = (en < e_hi) ? A.recv[en] : r_end;
+        if (need_gbar && !contiguous) {
+            // ghost sub-rows (and a step straddling the boundary): w_e of the reverse edge, which is an owned row's;
+            // the reverse-edge ids come through scalar loads here (rare path)
+#pragma unroll
+            for (int k = 0; k < 16; ++k) {
+                const int64_t wi = (tb + k < A.n_stored) ? tb + k : (int64_t)uniform_load(A.mirror, tb + k);
+                const __amdgpu_buffer_rsrc_t r1w = __builtin_amdgcn_make_buffer_rsrc(
+                    A.wstore + wi * F, 0, (k < S.kmax) ? F * 4 : 0, kBufferFlags);
+                S.wv[k] = buffer_load_f32(r1w, f * 4, 0, 0);
+            }
         }
-        __builtin_amdgcn_sched_barrier(0);
+    };
+    auto compute_step = [&](const Step &S, int32_t rn_first) {
+        if (S.kmax <= 0) return;
+        // wave-uniform masks: bit k = edge k ends its row / edge k is the upper edge of its pair
+        const int32_t up = __shfl(S.rk, l16 + 1, 64);
+        const int32_t rnext = (l16 == 15) ? rn_first : up;
+        const bool valid_l = l16 < S.kmax;
+        const uint32_t ends = (uint32_t)__ballot(valid_l && rnext != S.rk) & 0xffffu;
+        const uint32_t uppers = (uint32_t)__ballot(valid_l && (int64_t)S.mk > S.tb + l16) & 0xffffu;
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            acc = fmaf(S.wv[k], S.av[k], acc);   // edges past the end contribute w = 0
+            if (uppers & (1u << k)) {            // upper edge of its pair: queue it
+                const int slot = __builtin_amdgcn_readfirstlane((q_head + q_count) % kQueue);
+                if (F == 64 || lane < F) Q[slot * D::FS + f] = fmaf(ai, S.gv[k], S.av[k] * gi);
+                q_e = ((int)lane == slot) ? (int32_t)(S.tb + k) : q_e;   // lane `slot` keeps the edge index
+                ++q_count;
+            }
+            if (ends & (1u << k)) {
+                const int32_t rrow = __builtin_amdgcn_readlane(S.rk, k);
+                const int32_t nrow = __builtin_amdgcn_readlane(rnext, k);
+                if (need_gbar) {
+                    if (F == 64 || lane < F) A.out[(int64_t)rrow * F + f] = acc;
+                    for (int64_t r = (int64_t)rrow + 1; r < nrow; ++r)   // empty rows in between
+                        if (F == 64 || lane < F) A.out[r * F + f] = 0.f;
+                }
+                acc = 0.f;
+                if (nrow < (int32_t)r1) {   // move to the row of the next edge
+                    ai = ai2;
+                    gi = gi2;
+                    if (nrow != rrow + 1) {   // empty rows were skipped: the prefetch was for the wrong row
+                        ai = buffer_load_f32(a_rsrc, f * 4, nrow * (F * 4), 0);
+                        gi = buffer_load_f32(g_rsrc, f * 4, nrow * (F * 4), 0);
+                    }
+                    ai2 = buffer_load_f32(a_rsrc, f * 4, min(nrow + 1, last_row) * (F * 4), 0);
+                    gi2 = buffer_load_f32(g_rsrc, f * 4, min(nrow + 1, last_row) * (F * 4), 0);
+                }
+            }
+        }
+    };
+    auto phase2 = [&]() {
+        // ---------------- up to 32 queued pairs
+        wave_lds_fence();
+        const int nval = min(q_count, 32);
+        const int slot = (q_head + c32) % kQueue;
+        const bool valid = c32 < nval;
+        // the lane exchange must run with all lanes active (a disabled source lane reads as 0),
+        // so it is kept out of the `valid` predicate
+        int32_t e_any = __shfl(q_e, slot, 64);
+        asm volatile("" : "+v"(e_any));
+        const int32_t e2 = valid ? e_any : 0;
+        const float d2 = valid ? A.d[e2] : C.bp.rc;   // rc: zero derivative
+        const int32_t m2 = valid ? A.mirror[e2] : 0;
+        float b[8], db[8];
+        radial_basis<true>(d2, C.bp, b, db);
 #pragma unroll
         for (int n = 0; n < 8; ++n) b[n] *= kSiluScale;   // pre-activations come out as t' = c t
-        f32x16 t[D::NB], sp[D::NB];
+        f32x16 t[D::NB], cg[D::NB];
         gemm_k8r<F>(W1, b, t, lane);
+        gemm_k8r<F>(W1, db, cg, lane);
 #pragma unroll
         for (int bb = 0; bb < D::NB; ++bb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const float sg = sigmoid_scaled(t[bb][r]);      // t holds t' = c t
-                const float ss = t[bb][r] * sg;                  // s' = c SiLU(t)
-                t[bb][r] = ss;
-                sp[bb][r] = fmaf(ss * kSiluScaleInv, 1.0f - sg, sg);   // SiLU'(t) = sg + s (1 - sg)
+                const float sg = sigmoid_scaled(t[bb][r]);
+                const float ss = t[bb][r] * sg * kSiluScaleInv;               // SiLU(t)
+                t[bb][r] = fmaf(ss, 1.0f - sg, sg) * cg[bb][r];               // ds_k/dd = SiLU'(t_k) c_k
             }
-        if (need_gbar && !stored) {
-            f32x16 w[D::NB];
-            gemm_rl<F>(A2t, t, w, lane);
-            regs_to_tile<F>(w, tile, lane);
-        }
-        {   // q[k] = SiLU'(t_k) * sum_n W1[n][k] db_n/dd  =  d s_k / d d
-            f32x16 cg[D::NB];
-            gemm_k8r<F>(W1, db, cg, lane);
-#pragma unroll
-            for (int bb = 0; bb < D::NB; ++bb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) sp[bb][r] *= cg[bb][r];
-        }
-        wave_lds_fence();
-        __builtin_amdgcn_sched_barrier(0);  // keep the use of the prefetched receiver after the MFMA chain
-        int32_t rnext;
-        const uint32_t ends = row_ends(rcur, __builtin_amdgcn_readfirstlane(rk), valid, lane, rnext);
-        // lane = feature: accumulate gbar_i; leave abar_i*g_j + abar_j*g_i in the tile
-#pragma unroll
-        for (int half = 0; half < 2; ++half) {
-            float ws[16];
-            if (half == 0) {
-#pragma unroll
-                for (int k = 0; k < 16; ++k) {
-                    const int32_t jk = (16 + k < kmax) ? sj[16 + k] : 0;
-                    av[1][k] = buffer_load_f32(a_rsrc, f * 4, jk * (F * 4), 0);
-                    gv[1][k] = buffer_load_f32(g_rsrc, f * 4, jk * (F * 4), 0);
-                    wv[1][k] = buffer_load_f32(w_rsrc, f * 4, (16 + k) * (F * 4), 0);
-                }
-            }
-            if (need_gbar && !stored) {
-#pragma unroll
-                for (int kk = 0; kk < 16; ++kk) wv[half][kk] = tile[(half * 16 + kk) * D::FS + f];
-            }
-#pragma unroll
-            for (int kk = 0; kk < 16; ++kk) {
-                const int k = half * 16 + kk;
-                acc = fmaf(wv[half][kk], av[half][kk], acc);
-                ws[kk] = fmaf(ai, gv[half][kk], av[half][kk] * gi);
-                if (ends & (1u << k)) {
-                    const int32_t rrow = __builtin_amdgcn_readlane(rcur, k);
-                    const int32_t nrow = __builtin_amdgcn_readlane(rnext, k);
-                    if (need_gbar) {
-                        if (F == 64 || lane < F) A.out[(int64_t)rrow * F + f] = acc;
-                        for (int64_t r = (int64_t)rrow + 1; r < nrow; ++r)
-                            if (F == 64 || lane < F) A.out[r * F + f] = 0.f;
-                    }
-                    acc = 0.f;
-                    if (nrow < r_end) {   // move to the row of the next edge
-                        ai = ai2;
-                        gi = gi2;
-                        if (nrow != rrow + 1) {   // empty rows were skipped: the prefetch was for the wrong row
-                            ai = buffer_load_f32(a_rsrc, f * 4, nrow * (F * 4), 0);
-                            gi = buffer_load_f32(g_rsrc, f * 4, nrow * (F * 4), 0);
-                        }
-                        ai2 = buffer_load_f32(a_rsrc, f * 4, min(nrow + 1, last_row) * (F * 4), 0);
-                        gi2 = buffer_load_f32(g_rsrc, f * 4, min(nrow + 1, last_row) * (F * 4), 0);
-                    }
-                }
-            }
-#pragma unroll
-            for (int kk = 0; kk < 16; ++kk)
-                if (F == 64 || lane < F) tile[(half * 16 + kk) * D::FS + f] = ws[kk];
-        }
-        wave_lds_fence();
         f32x16 sb[D::NB];
-        gemm_lds<F>(A2n, tile, sb, lane);   // sbar[k] = sum_f W2[k][f] wsym[f]
+        gemm_queue<F>(A2n, Q + slot * D::FS, sb, lane);   // sbar[k] = sum_f W2[k][f] wsym[f]
         float part = 0.f;
 #pragma unroll
         for (int bb = 0; bb < D::NB; ++bb)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) part = fmaf(sb[bb][r], sp[bb][r], part);
+            for (int r = 0; r < 16; ++r) part = fmaf(sb[bb][r], t[bb][r], part);
         part += __shfl_xor(part, 32, 64);
-        if (valid && lane < 32) A.dsum[e] = C.first ? part : A.dsum[e] + part;
+        if (valid && lane < 32) {
+            A.dsum[e2] = C.first ? part : A.dsum[e2] + part;
+            A.dsum[m2] = C.first ? part : A.dsum[m2] + part;
+        }
+        q_head = (q_head + nval) % kQueue;
+        q_count -= nval;
         wave_lds_fence();
-        asm volatile("" : "+v"(dv), "+v"(rk), "+v"(ai2), "+v"(gi2));  // no load pending across the loop edge
-    }
-    if (e_lo >= e_hi && need_gbar)
-        for (int64_t r = r0; r < r1; ++r)
-            if (F == 64 || lane < F) A.out[r * F + f] = 0.f;
+    };
+
+    for (; item < part_end; item += items.stride) {
+        const int64_t chunk = item - B.chunk_start[part];
+        int64_t r0;
+        if (!chunk_rows(A, chunk, r0, r1)) continue;
+        const int64_t e_lo = A.row_ptr[r0];
+        e_hi = A.row_ptr[r1];
+        acc = 0.f;
+        // rows of the chunk before its first edge are empty
+        int32_t row = (e_lo < e_hi) ? uniform_load(A.recv, e_lo) : (int32_t)r1;
+        if (need_gbar)
+            for (int64_t r = r0; r < row; ++r)
+                if (F == 64 || lane < F) A.out[r * F + f] = 0.f;
+        row = min(row, last_row);
+        // receiver-side rows (abar_i, g_i) of the current row and, prefetched, of the row after it
+        ai = buffer_load_f32(a_rsrc, f * 4, row * (F * 4), 0);
+        gi = buffer_load_f32(g_rsrc, f * 4, row * (F * 4), 0);
+        ai2 = buffer_load_f32(a_rsrc, f * 4, min(row + 1, last_row) * (F * 4), 0);
+        gi2 = buffer_load_f32(g_rsrc, f * 4, min(row + 1, last_row) * (F * 4), 0);
+        Step SA, SB;
+        load_step(SA, e_lo);
+        for (int64_t tb = e_lo; tb < e_hi; tb += 32) {
+            load_step(SB, tb + 16);
+            compute_step(SA, __builtin_amdgcn_readfirstlane(SB.rk));
+            if (q_count >= 32) phase2();
+            load_step(SA, tb + 32);
+            compute_step(SB, __builtin_amdgcn_readfirstlane(SA.rk));
+            if (q_count >= 32) phase2();
+        }
+        if (e_lo >= e_hi && need_gbar)
+            for (int64_t r = r0; r < r1; ++r)
+                if (F == 64 || lane < F) A.out[r * F + f] = 0.f;
+    }   // work items
+    while (q_count > 0) phase2();   // queued pairs index this partition's arrays
+    }   // partitions
 }
 
 // ---------------------------------------------------------------- node kernels
@@ -1034,7 +1142,7 @@ Packs pack_layout(int F, int L)
 template <int F> struct Lds {
     using D = Dims<F>;
     static constexpr size_t edge_fwd = sizeof(float) * (D::PACKF + 4 * D::TILE);
-    static constexpr size_t edge_bwd = sizeof(float) * (2 * D::PACKF + 4 * D::TILE);
+    static constexpr size_t edge_bwd = sizeof(float) * (D::PACKF + 4 * kQueue * D::FS);
     static constexpr size_t node1 = sizeof(float) * (D::PACKF + 4 * D::TILE);
     static constexpr size_t node2 = sizeof(float) * (2 * D::PACKF + 4 * D::TILE);
 };
@@ -1080,23 +1188,35 @@ int node_pass(mlip_graph *g, SlabView *views, int P, const float *P1, const floa
 template <int F> int launch_edge(mlip_graph *g, EdgeBatch &b, bool backward)
 {
     const size_t lds = backward ? Lds<F>::edge_bwd : Lds<F>::edge_fwd;
-    static bool cfg_f = false, cfg_b = false;
-    if (backward && !cfg_b) {
-        MLIP_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_edge_bwd<F>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        cfg_b = true;
-    }
-    if (!backward && !cfg_f) {
-        MLIP_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_edge_fwd<F>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        cfg_f = true;
+    // resident blocks per compute unit, queried once per kernel
+    static int occ_f = 0, occ_b = 0, n_cu = 0;
+    int &occ = backward ? occ_b : occ_f;
+    if (occ == 0) {
+        const void *fn = backward ? reinterpret_cast<const void *>(&k_edge_bwd<F>)
+                                  : reinterpret_cast<const void *>(&k_edge_fwd<F>);
+        MLIP_HIP(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        int dev = 0, o = 0;
+        MLIP_HIP(hipGetDevice(&dev));
+        MLIP_HIP(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
+        if (backward)
+            MLIP_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&o, k_edge_bwd<F>, 256, lds));
+        else
+            MLIP_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&o, k_edge_fwd<F>, 256, lds));
+        if (o < 1 || n_cu < 8) {
+            set_error("edge kernel does not fit the device (occupancy %d, %d compute units)", o, n_cu);
+            return MLIP_EHIP;
+        }
+        occ = o;
     }
     b.chunk_start[0] = 0;
     for (int q = 0; q < b.n; ++q) b.chunk_start[q + 1] = b.chunk_start[q] + (b.s[q].n_rows > 0 ? b.s[q].n_chunks : 0);
     for (int q = b.n; q < kBatch; ++q) b.chunk_start[q + 1] = b.chunk_start[b.n];
     const int64_t items = b.chunk_start[b.n];
     if (items <= 0) return MLIP_OK;
-    const unsigned blocks = (unsigned)((items + 3) / 4);
+    // persistent grid: what is resident at once, a multiple of the 8 XCDs, no more than the work needs
+    const int64_t resident = (int64_t)(n_cu / 8) * occ;
+    const int64_t needed = ((items + 7) / 8 + 3) / 4;
+    const unsigned blocks = (unsigned)(8 * std::max<int64_t>(1, std::min(resident, needed)));
     if (backward)
         k_edge_bwd<F><<<blocks, 256, lds, g->stream>>>(b);
     else
@@ -1224,7 +1344,8 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, int32_t mode, double *ener
                 SlabView &v = views[p0 + q];
                 EdgeArgs &ea = eb.s[q];
                 ea.n_rows = v.n_owned;
-                ea.n_chunks = std::max<int64_t>(1, (v.n_edges_owned + kChunkEdges - 1) / kChunkEdges);
+                ea.n_chunks = chunks_of(v.n_edges_owned);
+                ea.chunk_row = v.chunk_row;
                 ea.n_nodes = v.n_local;
                 ea.row_ptr = v.row_ptr;
                 ea.senders = v.senders;
@@ -1304,7 +1425,8 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, int32_t mode, double *ener
                 SlabView &v = views[p0 + q];
                 EdgeArgs &ea = eb.s[q];
                 ea.n_rows = v.n_local;
-                ea.n_chunks = std::max<int64_t>(1, (v.n_edges + kChunkEdges - 1) / kChunkEdges);
+                ea.n_chunks = chunks_of(v.n_edges);
+                ea.chunk_row = v.chunk_row;
                 ea.n_nodes = v.n_local;
                 ea.row_ptr = v.row_ptr;
                 ea.senders = v.senders;
@@ -1314,6 +1436,7 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, int32_t mode, double *ener
                 ea.abar = v.abar.as<float>();
                 ea.out = v.gbar.as<float>();
                 ea.dsum = v.dsum.as<float>();
+                ea.mirror = v.mirror;
                 ea.wstore = need_gbar ? wslice(v, l) : nullptr;
                 ea.n_stored = need_gbar ? v.n_edges_owned : 0;
             }

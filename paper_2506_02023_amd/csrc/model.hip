@@ -89,11 +89,12 @@ __device__ inline void radial_basis(float d, const BasisParams &bp, float (&b)[8
         const float du = -xpm1 * (bp.pc0 - x * (bp.pc1 - bp.pc2 * x));
         du_term = du * bp.inv_rc - u * inv_d;
     }
+    const float u_rc = u * bp.inv_rc;
     float sn = s1, cn = c1v;
 #pragma unroll
     for (int n = 0; n < 8; ++n) {
         b[n] = sn * u * inv_d;
-        if (DERIV) db[n] = ((float)(n + 1) * kPi * bp.inv_rc * cn * u + sn * du_term) * inv_d;
+        if (DERIV) db[n] = fmaf((float)(n + 1) * kPi, cn * u_rc, sn * du_term) * inv_d;   // (n+1) pi: a literal operand
         const float s2 = sn * c1v + cn * s1;
         cn = cn * c1v - sn * s1;
         sn = s2;
@@ -307,6 +308,20 @@ __device__ inline void gemm_k8r(const RegPack1<F> &P, const float (&v)[8], f32x1
 #pragma unroll
         for (int bo = 0; bo < NB; ++bo)
             out[bo] = __builtin_amdgcn_mfma_f32_32x32x2f32(P.v[bo][s], bv, out[bo], 0, 0, 0);
+    }
+}
+
+// one 32-feature block of gemm_k8r
+template <int F>
+__device__ inline void gemm_k8r_block(const RegPack1<F> &P, const float (&v)[8], int bo, f32x16 &out, int lane)
+{
+    const int h = lane >> 5;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) out[r] = 0.f;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        const float bv = h ? v[2 * s + 1] : v[2 * s];
+        out = __builtin_amdgcn_mfma_f32_32x32x2f32(P.v[bo][s], bv, out, 0, 0, 0);
     }
 }
 
@@ -578,6 +593,8 @@ __global__ void __launch_bounds__(256, 3) k_edge_fwd(EdgeBatch B)
 //   and, for the "upper" edge of each edge / reverse-edge pair (the one with the smaller index),
 //   wsym_e = abar_i * g_j + abar_j * g_i is queued in LDS together with the edge's length and the
 //   two edge indices of the pair.
+// Only owned rows are processed here.  A ghost row (abar_i = 0) holds lower edges only, so its pairs are
+// queued from the owned rows' side, and its gbar comes from k_ghost_gbar.
 // Phase 2 (lane = edge), whenever 32 pairs are queued: dE/dd of the pair,
 //   sum_k (W2 wsym)_k * ds_k/dd,   ds_k/dd = SiLU'(t_k) * sum_n W1[n][k] db_n/dd,
 //   on the MFMA units, written to both edges of the pair.  Both edges of a pair have the same length
@@ -630,24 +647,29 @@ template <int F>
 __global__ void __launch_bounds__(256, 2) k_edge_bwd(EdgeBatch B)
 {
     using D = Dims<F>;
+    constexpr int FS = D::FS;
+    constexpr int kRowBytes = F * 4;
     extern __shared__ float lds[];
     float *A2n = lds;
-    float *queues = A2n + D::PACKF;
+    float *A1l = A2n + D::PACKF;
+    float *queues = A1l + D::PACK1;
     for (int i = threadIdx.x; i < D::PACKF; i += 256) A2n[i] = B.c.A2n[i];
+    for (int i = threadIdx.x; i < D::PACK1; i += 256) A1l[i] = B.c.A1[i];
     __syncthreads();
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int c32 = lane & 31;
-    const unsigned f = lane & (F - 1);
-    float *Q = queues + wave * (kQueue * D::FS);
-    const EdgeCommon &C = B.c;
-    RegPack1<F> W1;
-    load_pack1<F>(W1, C.A1, lane);
-    const bool need_gbar = C.need_gbar != 0;
     const int l16 = lane & 15;
-    // queue of pairs: slot s lives in LDS row s (wsym) and in lane s of q_e (the upper edge's index).
-    // It carries over from one work item to the next and is drained at the end of a partition.
-    int q_head = 0, q_count = 0;
-    int32_t q_e = 0;
+    const unsigned f = lane & (F - 1);
+    // Queue of pairs, one per wavefront: slot s is LDS row s, floats [0, F) = wsym, then the upper
+    // edge's index, the reverse edge's index and the edge length in the row's padding.  It carries
+    // over from one work item to the next and is drained at the end of a partition.
+    float *Q = queues + wave * (kQueue * FS);
+    char *Qf = reinterpret_cast<char *>(Q + f);
+    const EdgeCommon &C = B.c;
+    const bool need_gbar = C.need_gbar != 0;
+    int q_head = 0, q_count = 0;   // first queued slot, queued pairs
+    int q_tail = 0;                // (q_head + q_count) % kQueue, the slot the next pair goes to
+
     const ItemRange items = edge_items(B.chunk_start[B.n], wave);
     int64_t item = items.first;
     for (int part = 0; part < B.n; ++part) {
@@ -655,123 +677,155 @@ __global__ void __launch_bounds__(256, 2) k_edge_bwd(EdgeBatch B)
     if (item >= part_end) continue;
     const EdgeArgs A = B.s[part];
     const __amdgpu_buffer_rsrc_t g_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<float *>(A.g), 0, (int)(A.n_nodes * F * 4), kBufferFlags);
+        const_cast<float *>(A.g), 0, (int)(A.n_nodes * kRowBytes), kBufferFlags);
     const __amdgpu_buffer_rsrc_t a_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<float *>(A.abar), 0, (int)(A.n_nodes * F * 4), kBufferFlags);
-    const int32_t last_row = (int32_t)(A.n_rows - 1);
-    // state of the current work item
-    int64_t r1 = 0, e_hi = 0;
-    float acc = 0.f, ai = 0.f, gi = 0.f, ai2 = 0.f, gi2 = 0.f;
-
-    // One step of phase 1 = 16 edges.  Its loads (sender rows, kept w, receiver and reverse-edge ids)
-    // are issued one step ahead into the other of two register buffers.
-    struct Step {
-        float av[16], gv[16], wv[16];
-        int32_t rk, mk;   // receiver / reverse edge of this lane's edge; r1 / -1 past the end of the chunk
-        int kmax;
-        int64_t tb;
+        const_cast<float *>(A.abar), 0, (int)(A.n_nodes * kRowBytes), kBufferFlags);
+    const __amdgpu_buffer_rsrc_t o_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        A.out, 0, need_gbar ? (int)(A.n_rows * kRowBytes) : 0, kBufferFlags);   // gbar rows; nothing is stored without it
+    auto store_row = [&](int32_t row, float v) {
+        if (F == 64 || lane < F) buffer_store_f32(v, o_rsrc, f * 4, row * kRowBytes, 0);
     };
-    auto load_step = [&](Step &S, int64_t tb) {
+    // state of the current work item (edge indices fit 32 bits)
+    int32_t r1 = 0, e_hi = 0;
+    float acc = 0.f;
+
+    // Phase 1 runs in steps of 16 edges through a software pipeline whose loads are all issued ahead of
+    // their use: the edge records (sender, receiver, reverse edge, length) two steps ahead, the rows they
+    // point to one step ahead.  Vector memory loads complete in order, so a stage may only contain loads
+    // and address arithmetic; anything that consumes a loaded value belongs to a later stage.
+    struct Ids {    // lane k (mod 16) holds edge tb + k, clamped to the last edge of the work item
+        int32_t sj, rk, mk;
+        float dk;
+    };
+    struct Step {
+        float av[16], gv[16], wv[16];   // abar / g rows of the senders, kept filter values
+        float ai0, gi0, ai1, gi1;       // abar / g rows of the first and of the last edge's receiver
+        int kmax;                       // valid edges in the step
+        int32_t tb;
+    };
+    auto load_ids = [&](Ids &I, int32_t tb) {
+        const int32_t e = min((int32_t)tb + l16, e_hi - 1);
+        I.sj = A.senders[e];
+        I.rk = A.recv[e];
+        I.mk = A.mirror[e];
+        I.dk = A.d[e];
+    };
+    auto load_step = [&](Step &S, const Ids &I, int32_t tb) {
         S.tb = tb;
-        S.kmax = __builtin_amdgcn_readfirstlane((int)max((int64_t)0, min((int64_t)16, e_hi - tb)));
-        const bool in = tb + l16 < e_hi;
-        S.rk = in ? A.recv[tb + l16] : (int32_t)r1;
-        S.mk = in ? A.mirror[tb + l16] : -1;
-        if (S.kmax <= 0) return;
-        int32_t sj[16];   // read unconditionally (buffers carry slack), masked below
-#pragma unroll
-        for (int k = 0; k < 16; ++k) sj[k] = uniform_load(A.senders, tb + k);
-        const bool contiguous = tb + 16 <= A.n_stored;   // w_e of owned rows sits at the edge's own index
+        S.kmax = __builtin_amdgcn_readfirstlane(max(0, min(16, e_hi - tb)));   // (the clamp is a vector instruction)
+        // A step past the end of the work item (kmax = 0) still issues its loads, from the clamped records:
+        // every path through the pipeline then has the same number of loads in flight, which is what lets
+        // the waits before the uses be partial ones.
+        const int32_t sjo = I.sj * kRowBytes;
+        const int32_t row0 = __builtin_amdgcn_readfirstlane(I.rk);
+        const int32_t rowl = __builtin_amdgcn_readlane(I.rk, max(S.kmax - 1, 0));
+        S.ai0 = buffer_load_f32(a_rsrc, f * 4, row0 * kRowBytes, 0);
+        S.gi0 = buffer_load_f32(g_rsrc, f * 4, row0 * kRowBytes, 0);
+        S.ai1 = buffer_load_f32(a_rsrc, f * 4, rowl * kRowBytes, 0);
+        S.gi1 = buffer_load_f32(g_rsrc, f * 4, rowl * kRowBytes, 0);
+        // w_e sits at the edge's own index (a range of zero bytes reads 0: without gbar no w is needed)
         const __amdgpu_buffer_rsrc_t w_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-            A.wstore + (contiguous ? tb * F : 0), 0, (need_gbar && contiguous) ? S.kmax * (F * 4) : 0, kBufferFlags);
+            A.wstore + (need_gbar ? (int64_t)tb * F : 0), 0, need_gbar ? S.kmax * kRowBytes : 0, kBufferFlags);
 #pragma unroll
         for (int k = 0; k < 16; ++k) {
-            const int32_t jk = (k < S.kmax) ? sj[k] : 0;
-            S.av[k] = buffer_load_f32(a_rsrc, f * 4, jk * (F * 4), 0);
-            S.gv[k] = buffer_load_f32(g_rsrc, f * 4, jk * (F * 4), 0);
-            S.wv[k] = buffer_load_f32(w_rsrc, f * 4, k * (F * 4), 0);   // 0 outside the descriptor's range
-        }
-        if (need_gbar && !contiguous) {
-            // ghost sub-rows (and a step straddling the boundary): w_e of the reverse edge, which is an owned row's;
-            // the reverse-edge ids come through scalar loads here (rare path)
-#pragma unroll
-            for (int k = 0; k < 16; ++k) {
-                const int64_t wi = (tb + k < A.n_stored) ? tb + k : (int64_t)uniform_load(A.mirror, tb + k);
-                const __amdgpu_buffer_rsrc_t r1w = __builtin_amdgcn_make_buffer_rsrc(
-                    A.wstore + wi * F, 0, (k < S.kmax) ? F * 4 : 0, kBufferFlags);
-                S.wv[k] = buffer_load_f32(r1w, f * 4, 0, 0);
-            }
+            const int32_t so = __builtin_amdgcn_readlane(sjo, k);
+            S.av[k] = buffer_load_f32(a_rsrc, f * 4, so, 0);
+            S.gv[k] = buffer_load_f32(g_rsrc, f * 4, so, 0);
+            S.wv[k] = buffer_load_f32(w_rsrc, f * 4, k * kRowBytes, 0);   // 0 outside the descriptor's range
         }
     };
-    auto compute_step = [&](const Step &S, int32_t rn_first) {
+    // rn_first: receiver of the first edge of the following step (r1 after the last step)
+    auto compute_step = [&](const Step &S, const Ids &I, int32_t rn_first) {
         if (S.kmax <= 0) return;
-        // wave-uniform masks: bit k = edge k ends its row / edge k is the upper edge of its pair
-        const int32_t up = __shfl(S.rk, l16 + 1, 64);
-        const int32_t rnext = (l16 == 15) ? rn_first : up;
         const bool valid_l = l16 < S.kmax;
-        const uint32_t ends = (uint32_t)__ballot(valid_l && rnext != S.rk) & 0xffffu;
-        const uint32_t uppers = (uint32_t)__ballot(valid_l && (int64_t)S.mk > S.tb + l16) & 0xffffu;
+        const int32_t rk = valid_l ? I.rk : r1;
+        const int32_t e_l = S.tb + l16;
+        // wave-uniform masks: bit k = edge k ends its row / edge k is the upper edge of its pair
+        const int32_t up = __shfl(rk, l16 + 1, 64);
+        const int32_t rnext = (l16 == 15) ? rn_first : up;
+        const uint32_t ends = (uint32_t)__ballot(valid_l && rnext != rk) & 0xffffu;
+        const bool upper_l = valid_l && I.mk > e_l;
+        const uint32_t uppers = (uint32_t)__ballot(upper_l) & 0xffffu;
+        {   // records of the pairs queued by this step, all at once: slots follow q_tail in edge order
+            int slot = q_tail + (int)__builtin_amdgcn_mbcnt_lo(uppers, 0u);   // upper edges before this lane's (lanes < 16)
+            slot -= (slot >= kQueue) ? kQueue : 0;
+            if (upper_l && lane < 16) {
+                float *rec = Q + slot * FS + F;
+                reinterpret_cast<int32_t *>(rec)[0] = e_l;
+                reinterpret_cast<int32_t *>(rec)[1] = I.mk;
+                rec[2] = I.dk;
+            }
+        }
+        const int32_t row_last = __builtin_amdgcn_readlane(rk, S.kmax - 1);
+        float ai = S.ai0, gi = S.gi0;
+        int q_off = q_tail * (FS * 4);   // byte offset of the slot the next pair goes to
 #pragma unroll
         for (int k = 0; k < 16; ++k) {
             acc = fmaf(S.wv[k], S.av[k], acc);   // edges past the end contribute w = 0
-            if (uppers & (1u << k)) {            // upper edge of its pair: queue it
-                const int slot = __builtin_amdgcn_readfirstlane((q_head + q_count) % kQueue);
-                if (F == 64 || lane < F) Q[slot * D::FS + f] = fmaf(ai, S.gv[k], S.av[k] * gi);
-                q_e = ((int)lane == slot) ? (int32_t)(S.tb + k) : q_e;   // lane `slot` keeps the edge index
-                ++q_count;
-            }
+            // wsym goes to the next free slot whether or not the edge is an upper one; only an upper edge
+            // advances the slot, anything else is overwritten by the next edge
+            *reinterpret_cast<float *>(Qf + q_off) = fmaf(ai, S.gv[k], S.av[k] * gi);
+            q_off += (uppers & (1u << k)) ? FS * 4 : 0;
+            q_off = (q_off == kQueue * FS * 4) ? 0 : q_off;
             if (ends & (1u << k)) {
-                const int32_t rrow = __builtin_amdgcn_readlane(S.rk, k);
+                const int32_t rrow = __builtin_amdgcn_readlane(rk, k);
                 const int32_t nrow = __builtin_amdgcn_readlane(rnext, k);
-                if (need_gbar) {
-                    if (F == 64 || lane < F) A.out[(int64_t)rrow * F + f] = acc;
-                    for (int64_t r = (int64_t)rrow + 1; r < nrow; ++r)   // empty rows in between
-                        if (F == 64 || lane < F) A.out[r * F + f] = 0.f;
-                }
+                store_row(rrow, acc);
+                for (int32_t r = rrow + 1; r < nrow; ++r) store_row(r, 0.f);   // empty rows in between
                 acc = 0.f;
-                if (nrow < (int32_t)r1) {   // move to the row of the next edge
-                    ai = ai2;
-                    gi = gi2;
-                    if (nrow != rrow + 1) {   // empty rows were skipped: the prefetch was for the wrong row
-                        ai = buffer_load_f32(a_rsrc, f * 4, nrow * (F * 4), 0);
-                        gi = buffer_load_f32(g_rsrc, f * 4, nrow * (F * 4), 0);
+                if (k + 1 < S.kmax) {   // the next row starts inside this step
+                    ai = S.ai1;
+                    gi = S.gi1;
+                    if (nrow != row_last) {   // a third row inside one step (short rows): fetch it now
+                        ai = buffer_load_f32(a_rsrc, f * 4, nrow * kRowBytes, 0);
+                        gi = buffer_load_f32(g_rsrc, f * 4, nrow * kRowBytes, 0);
+                        // complete the two loads here: left pending, they would make every later use of
+                        // ai / gi, on the common path too, wait for all loads in flight
+                        asm volatile("" : "+v"(ai), "+v"(gi));
                     }
-                    ai2 = buffer_load_f32(a_rsrc, f * 4, min(nrow + 1, last_row) * (F * 4), 0);
-                    gi2 = buffer_load_f32(g_rsrc, f * 4, min(nrow + 1, last_row) * (F * 4), 0);
                 }
             }
         }
+        const int n_new = __builtin_popcount(uppers);
+        q_count += n_new;
+        q_tail += n_new;
+        q_tail -= (q_tail >= kQueue) ? kQueue : 0;
     };
     auto phase2 = [&]() {
         // ---------------- up to 32 queued pairs
         wave_lds_fence();
         const int nval = min(q_count, 32);
-        const int slot = (q_head + c32) % kQueue;
+        int slot = q_head + c32;
+        slot -= (slot >= kQueue) ? kQueue : 0;
         const bool valid = c32 < nval;
-        // the lane exchange must run with all lanes active (a disabled source lane reads as 0),
-        // so it is kept out of the `valid` predicate
-        int32_t e_any = __shfl(q_e, slot, 64);
-        asm volatile("" : "+v"(e_any));
-        const int32_t e2 = valid ? e_any : 0;
-        const float d2 = valid ? A.d[e2] : C.bp.rc;   // rc: zero derivative
-        const int32_t m2 = valid ? A.mirror[e2] : 0;
+        const float *rec = Q + slot * FS + F;
+        const int32_t e_q = reinterpret_cast<const int32_t *>(rec)[0];
+        const int32_t m_q = reinterpret_cast<const int32_t *>(rec)[1];
+        const float d_q = rec[2];
+        const int32_t e2 = valid ? e_q : 0, m2 = valid ? m_q : 0;
+        const float d2 = valid ? d_q : C.bp.rc;   // rc: zero derivative
         float b[8], db[8];
         radial_basis<true>(d2, C.bp, b, db);
 #pragma unroll
         for (int n = 0; n < 8; ++n) b[n] *= kSiluScale;   // pre-activations come out as t' = c t
-        f32x16 t[D::NB], cg[D::NB];
-        gemm_k8r<F>(W1, b, t, lane);
-        gemm_k8r<F>(W1, db, cg, lane);
+        f32x16 t[D::NB];   // ds_k/dd = SiLU'(t_k) c_k, one block of 32 features at a time (fewer live registers)
 #pragma unroll
-        for (int bb = 0; bb < D::NB; ++bb)
+        for (int bb = 0; bb < D::NB; ++bb) {
+            f32x16 cg;
+            RegPack1<F> W1;   // this block's W1 operands, from LDS
+#pragma unroll
+            for (int s4 = 0; s4 < 4; ++s4) W1.v[bb][s4] = A1l[(bb * 4 + s4) * 64 + lane];
+            gemm_k8r_block<F>(W1, b, bb, t[bb], lane);
+            gemm_k8r_block<F>(W1, db, bb, cg, lane);
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const float sg = sigmoid_scaled(t[bb][r]);
                 const float ss = t[bb][r] * sg * kSiluScaleInv;               // SiLU(t)
-                t[bb][r] = fmaf(ss, 1.0f - sg, sg) * cg[bb][r];               // ds_k/dd = SiLU'(t_k) c_k
+                t[bb][r] = fmaf(ss, 1.0f - sg, sg) * cg[r];
             }
+        }
         f32x16 sb[D::NB];
-        gemm_queue<F>(A2n, Q + slot * D::FS, sb, lane);   // sbar[k] = sum_f W2[k][f] wsym[f]
+        gemm_queue<F>(A2n, Q + slot * FS, sb, lane);   // sbar[k] = sum_f W2[k][f] wsym[f]
         float part = 0.f;
 #pragma unroll
         for (int bb = 0; bb < D::NB; ++bb)
@@ -779,45 +833,59 @@ __global__ void __launch_bounds__(256, 2) k_edge_bwd(EdgeBatch B)
             for (int r = 0; r < 16; ++r) part = fmaf(sb[bb][r], t[bb][r], part);
         part += __shfl_xor(part, 32, 64);
         if (valid && lane < 32) {
-            A.dsum[e2] = C.first ? part : A.dsum[e2] + part;
-            A.dsum[m2] = C.first ? part : A.dsum[m2] + part;
+            // every edge is written by exactly one pair per launch; after the first layer the value is
+            // added with a fire-and-forget atomic so that no load sits in the pipeline of phase 1
+            if (C.first) {
+                A.dsum[e2] = part;
+                A.dsum[m2] = part;
+            } else {
+                unsafeAtomicAdd(A.dsum + e2, part);
+                unsafeAtomicAdd(A.dsum + m2, part);
+            }
         }
-        q_head = (q_head + nval) % kQueue;
+        q_head += nval;
+        q_head -= (q_head >= kQueue) ? kQueue : 0;
         q_count -= nval;
         wave_lds_fence();
     };
 
     for (; item < part_end; item += items.stride) {
         const int64_t chunk = item - B.chunk_start[part];
-        int64_t r0;
-        if (!chunk_rows(A, chunk, r0, r1)) continue;
-        const int64_t e_lo = A.row_ptr[r0];
-        e_hi = A.row_ptr[r1];
+        int64_t r0_, r1_;
+        if (!chunk_rows(A, chunk, r0_, r1_)) continue;
+        const int32_t r0 = (int32_t)r0_;
+        r1 = (int32_t)r1_;
+        const int32_t e_lo = __builtin_amdgcn_readfirstlane((int32_t)A.row_ptr[r0]);   // wave-uniform: keep them scalar
+        e_hi = __builtin_amdgcn_readfirstlane((int32_t)A.row_ptr[r1]);
         acc = 0.f;
-        // rows of the chunk before its first edge are empty
-        int32_t row = (e_lo < e_hi) ? uniform_load(A.recv, e_lo) : (int32_t)r1;
-        if (need_gbar)
-            for (int64_t r = r0; r < row; ++r)
-                if (F == 64 || lane < F) A.out[r * F + f] = 0.f;
-        row = min(row, last_row);
-        // receiver-side rows (abar_i, g_i) of the current row and, prefetched, of the row after it
-        ai = buffer_load_f32(a_rsrc, f * 4, row * (F * 4), 0);
-        gi = buffer_load_f32(g_rsrc, f * 4, row * (F * 4), 0);
-        ai2 = buffer_load_f32(a_rsrc, f * 4, min(row + 1, last_row) * (F * 4), 0);
-        gi2 = buffer_load_f32(g_rsrc, f * 4, min(row + 1, last_row) * (F * 4), 0);
-        Step SA, SB;
-        load_step(SA, e_lo);
-        for (int64_t tb = e_lo; tb < e_hi; tb += 32) {
-            load_step(SB, tb + 16);
-            compute_step(SA, __builtin_amdgcn_readfirstlane(SB.rk));
-            if (q_count >= 32) phase2();
-            load_step(SA, tb + 32);
-            compute_step(SB, __builtin_amdgcn_readfirstlane(SA.rk));
-            if (q_count >= 32) phase2();
+        if (e_lo >= e_hi) {   // only empty rows
+            for (int32_t r = r0; r < r1; ++r) store_row(r, 0.f);
+            continue;
         }
-        if (e_lo >= e_hi && need_gbar)
-            for (int64_t r = r0; r < r1; ++r)
-                if (F == 64 || lane < F) A.out[r * F + f] = 0.f;
+        Ids IA, IB, IC;
+        Step SA, SB;
+        load_ids(IA, e_lo);
+        load_ids(IB, e_lo + 16);
+        {   // rows of the chunk before its first edge are empty
+            const int32_t first = __builtin_amdgcn_readfirstlane(IA.rk);
+            for (int32_t r = r0; r < first; ++r) store_row(r, 0.f);
+        }
+        load_step(SA, IA, e_lo);
+        for (int32_t tb = e_lo; tb < e_hi; tb += 32) {
+            int32_t nf;
+            load_ids(IC, tb + 32);
+            load_step(SB, IB, tb + 16);
+            nf = __builtin_amdgcn_readfirstlane(IB.rk);
+            compute_step(SA, IA, (tb + 16 < e_hi) ? nf : r1);
+            if (q_count >= 32) phase2();
+            load_ids(IA, tb + 48);
+            load_step(SA, IC, tb + 32);
+            nf = __builtin_amdgcn_readfirstlane(IC.rk);
+            compute_step(SB, IB, (tb + 32 < e_hi) ? nf : r1);
+            if (q_count >= 32) phase2();
+            IB = IA;   // records of step tb + 48, loaded a step ago
+            IA = IC;   // records of step tb + 32, whose rows SA holds
+        }
     }   // work items
     while (q_count > 0) phase2();   // queued pairs index this partition's arrays
     }   // partitions
@@ -1000,6 +1068,29 @@ __global__ void k_ghost_copy(int64_t n_ghost, int64_t n_owned, int F, const int3
 }
 
 // the owners' gradient rows  +=  this partition's ghost rows (each ghost atom appears once per partition)
+// gbar of the ghost rows: gbar_i = sum over the ghost's sub-row (its neighbours owned by this partition) of
+// w_e * abar_send(e).  w_e is the reverse edge's, which the forward pass kept (both edges of a pair have the
+// same length, hence the same filter value).  One wavefront per row, lane = feature, edges in row order.
+template <int F>
+__global__ void __launch_bounds__(256)
+k_ghost_gbar(int64_t n_ghost, int64_t n_owned, const int64_t *__restrict__ row_ptr, const int32_t *__restrict__ senders,
+             const int32_t *__restrict__ mirror, const float *__restrict__ wstore, const float *__restrict__ abar,
+             float *__restrict__ gbar)
+{
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int64_t k = (int64_t)blockIdx.x * 4 + wave;
+    if (k >= n_ghost) return;
+    const int64_t r = n_owned + k;
+    const unsigned f = lane & (F - 1);
+    const int64_t e0 = row_ptr[r], e1 = row_ptr[r + 1];
+    float acc = 0.f;
+    for (int64_t e = e0; e < e1; ++e) {
+        const int64_t j = senders[e], m = mirror[e];
+        acc = fmaf(wstore[m * F + f], abar[j * F + f], acc);
+    }
+    if (F == 64 || lane < F) gbar[r * F + f] = acc;
+}
+
 __global__ void k_ghost_addback(int64_t n_ghost, int64_t n_owned, int F, const int32_t *__restrict__ owner,
                                 const int32_t *__restrict__ src, PtrTable tab, const float *__restrict__ mine)
 {
@@ -1142,7 +1233,7 @@ Packs pack_layout(int F, int L)
 template <int F> struct Lds {
     using D = Dims<F>;
     static constexpr size_t edge_fwd = sizeof(float) * (D::PACKF + 4 * D::TILE);
-    static constexpr size_t edge_bwd = sizeof(float) * (D::PACKF + 4 * kQueue * D::FS);
+    static constexpr size_t edge_bwd = sizeof(float) * (D::PACKF + D::PACK1 + 4 * kQueue * D::FS);
     static constexpr size_t node1 = sizeof(float) * (D::PACKF + 4 * D::TILE);
     static constexpr size_t node2 = sizeof(float) * (2 * D::PACKF + 4 * D::TILE);
 };
@@ -1424,8 +1515,8 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, int32_t mode, double *ener
             for (int q = 0; q < eb.n; ++q) {
                 SlabView &v = views[p0 + q];
                 EdgeArgs &ea = eb.s[q];
-                ea.n_rows = v.n_local;
-                ea.n_chunks = chunks_of(v.n_edges);
+                ea.n_rows = v.n_owned;
+                ea.n_chunks = chunks_of(v.n_edges_owned);
                 ea.chunk_row = v.chunk_row;
                 ea.n_nodes = v.n_local;
                 ea.row_ptr = v.row_ptr;
@@ -1451,6 +1542,10 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, int32_t mode, double *ener
                 for (int q = 0; q < P; ++q) tab.p[q] = views[q].gbar.as<float>();
                 for (int p = 0; p < P; ++p) {  // ghost-row gradients -> owners, partitions in ascending order
                     SlabView &v = views[p];
+                    if (v.n_ghost > 0)
+                        k_ghost_gbar<F><<<blocks_for(v.n_ghost, 4), 256, 0, s>>>(
+                            v.n_ghost, v.n_owned, v.row_ptr, v.senders, v.mirror, wslice(v, l), v.abar.as<float>(),
+                            v.gbar.as<float>());
                     if (v.n_ghost > 0)
                         k_ghost_addback<<<blocks_for(v.n_ghost * (F / 4), 256), 256, 0, s>>>(
                             v.n_ghost, v.n_owned, F, v.ghost_owner, v.ghost_src, tab, v.gbar.as<float>());

@@ -16,14 +16,25 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_FP32_MFMA_TFLOPS = 157.3
-# algorithmic flops of the reverse edge step per directed edge and layer (K = 8, F = 64):
-#   pre-activations t = b W1 (2*8*64), sbar = wbar W2^T (2*64*64), dt/dd contraction through W1 (2*8*64).
-#   The filter value w_e itself is not recomputed: the forward pass keeps it in HBM (layers >= 1).
-FLOPS_BWD_EDGE = 2 * 8 * 64 + 2 * 64 * 64 + 2 * 8 * 64
-FLOPS_FWD_EDGE = 2 * 8 * 64 + 2 * 64 * 64
-# HBM bytes per k_edge_bwd<64> launch on the default workload, from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE
-# (profiles/edge_bwd_traffic_configs3_8slabs.md): 1,886,948 KiB x 1.9976 (copy-kernel scale) + 57,100 KiB x 1.000
-TRAFFIC_BWD_LAUNCH_BYTES = (1886948 * 1.9976 + 57100 * 1.0) * 1024
+# Algorithmic flops per directed edge and layer, i.e. of the operation as it is defined:
+#   forward: filter MLP, t = b W1 (2 K F) and w = SiLU(t) W2 (2 F F);
+#   reverse: pre-activations t = b W1 (2 K F), sbar = wbar W2^T (2 F F), dt/dd contraction through W1 (2 K F);
+#            the filter value w_e itself is not recomputed, the forward pass keeps it in HBM (layers >= 1).
+# The reverse kernel runs this dense work once per edge / reverse-edge pair (both have the same length), so the
+# MFMA units execute half of the reverse figure; both rates are reported.
+def flops_fwd_edge(F, K=8):
+    return 2 * K * F + 2 * F * F
+
+
+def flops_bwd_edge(F, K=8):
+    return 2 * K * F + 2 * F * F + 2 * K * F
+
+
+# HBM bytes per launch (one layer over all 8 slabs) on the default workload, from rocprofv3 --pmc FETCH_SIZE and
+# WRITE_SIZE (profiles/edge_traffic_configs3_8slabs.md): KiB x copy-kernel scale (1.9980 for FETCH_SIZE, 1.000 for
+# WRITE_SIZE)
+TRAFFIC_BWD_LAUNCH_BYTES = (12708060 * 1.9980 + 996390 * 1.0) * 1024
+TRAFFIC_FWD_LAUNCH_BYTES = (4030352 * 1.9980 + 7878067 * 1.0) * 1024
 
 
 def cpu_baseline(cfg_index, n_cells):
@@ -113,13 +124,27 @@ def main():
 
     ms_step = dt / args.steps * 1e3
     L = c["L"]
-    bwd_ms, bwd_n = prof["edge_bwd"]
-    flops_step = E * FLOPS_BWD_EDGE * L
-    per_launch_flops = flops_step * args.steps / max(bwd_n, 1)
-    avg_ms = bwd_ms / max(bwd_n, 1)
-    achieved = per_launch_flops / (avg_ms * 1e-3) / 1e12 if avg_ms > 0 else 0.0
-    fwd_ms, fwd_n = prof["edge_fwd"]
-    fwd_tflops = E * FLOPS_FWD_EDGE * L * args.steps / (fwd_ms * 1e-3) / 1e12 if fwd_ms > 0 else 0.0
+    default_workload = args.config == 3 and args.cells is None
+
+    def edge_roofline(group, kernel, flops_edge, traffic, executed=None):
+        ms, n = prof[group]
+        per_launch = E * flops_edge * L * args.steps / max(n, 1)
+        avg_ms = ms / max(n, 1)
+        ach = per_launch / (avg_ms * 1e-3) / 1e12 if avg_ms > 0 else 0.0
+        r = {"kernel": kernel, "bound": "mfma", "achieved": ach, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+             "frac": ach / PEAK_FP32_MFMA_TFLOPS, "traffic": traffic if default_workload else None,
+             "avg_launch_ms": avg_ms, "launches": int(n), "flops_per_launch": per_launch,
+             "ms_per_step": ms / args.steps}
+        if executed is not None:
+            r["executed_tflops"] = ach * executed / flops_edge
+        return r
+
+    F = c["F"]
+    roof_bwd = edge_roofline("edge_bwd", f"k_edge_bwd<{F}> (reverse edge step)", flops_bwd_edge(F),
+                             TRAFFIC_BWD_LAUNCH_BYTES, flops_bwd_edge(F) // 2)
+    roof_fwd = edge_roofline("edge_fwd", f"k_edge_fwd<{F}> (forward edge step)", flops_fwd_edge(F),
+                             TRAFFIC_FWD_LAUNCH_BYTES)
+    roof = roof_fwd if roof_fwd["ms_per_step"] >= roof_bwd["ms_per_step"] else roof_bwd   # the dominant kernel
 
     res = {
         "metric": "atoms/s (energy+forces)", "value": N / (dt / args.steps), "unit": "atoms/s", "n_gpus": 1,
@@ -131,15 +156,7 @@ def main():
         "us_per_atom_step": ms_step * 1e3 / N,
         "breakdown_ms_per_step": {k: v[0] / args.steps for k, v in prof.items()},
         "energy": energy, "net_force_max_component": fsum,
-        "roofline": {"kernel": "k_edge_bwd<64> (reverse edge step)", "bound": "mfma", "achieved": achieved,
-                     "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
-                     "traffic": TRAFFIC_BWD_LAUNCH_BYTES if (args.config == 3 and args.cells is None) else None,
-                     "avg_launch_ms": avg_ms, "launches": int(bwd_n),
-                     "flops_per_launch": per_launch_flops},
-        "roofline_edge_fwd": {"kernel": "k_edge_fwd<64>", "bound": "mfma", "achieved": fwd_tflops,
-                              "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
-                              "frac": fwd_tflops / PEAK_FP32_MFMA_TFLOPS,
-                              "avg_launch_ms": fwd_ms / max(fwd_n, 1), "launches": int(fwd_n)},
+        "roofline": roof, "roofline_edge_fwd": roof_fwd, "roofline_edge_bwd": roof_bwd,
     }
     if args.whole:
         res["whole_graph_forward_ms"] = dt_whole_fwd * 1e3

@@ -52,7 +52,7 @@ struct CellParams {
 
 // Work item of the edge kernels: the rows whose first edge lies in one span of kChunkEdges edges.
 #ifndef MLIP_CHUNK
-#define MLIP_CHUNK 512
+#define MLIP_CHUNK 1024
 #endif
 constexpr int kChunkEdges = MLIP_CHUNK;
 inline int64_t chunks_of(int64_t n_edges) { return n_edges > 0 ? (n_edges + kChunkEdges - 1) / kChunkEdges : 1; }

@@ -1084,9 +1084,20 @@ k_ghost_gbar(int64_t n_ghost, int64_t n_owned, const int64_t *__restrict__ row_p
     const unsigned f = lane & (F - 1);
     const int64_t e0 = row_ptr[r], e1 = row_ptr[r + 1];
     float acc = 0.f;
-    for (int64_t e = e0; e < e1; ++e) {
-        const int64_t j = senders[e], m = mirror[e];
-        acc = fmaf(wstore[m * F + f], abar[j * F + f], acc);
+    for (int64_t eb = e0; eb < e1; eb += 16) {   // 16 edges at a time: ids by lane, then all rows in flight together
+        const int n = (int)min((int64_t)16, e1 - eb);
+        const int64_t el = min(eb + (lane & 15), e1 - 1);
+        const int32_t jl = senders[el], ml = mirror[el];
+        float wv[16], av[16];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            const int64_t j = __builtin_amdgcn_readlane(jl, k), m = __builtin_amdgcn_readlane(ml, k);
+            wv[k] = wstore[m * F + f];
+            av[k] = abar[j * F + f];
+        }
+#pragma unroll
+        for (int k = 0; k < 16; ++k)
+            if (k < n) acc = fmaf(wv[k], av[k], acc);
     }
     if (F == 64 || lane < F) gbar[r * F + f] = acc;
 }

@@ -501,43 +501,52 @@ __global__ void __launch_bounds__(256, 3) k_edge_fwd(EdgeBatch B)
     const EdgeArgs A = B.s[part];
     const __amdgpu_buffer_rsrc_t g_rsrc = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<float *>(A.g), 0, (int)(A.n_nodes * F * 4), kBufferFlags);
+    const __amdgpu_buffer_rsrc_t o_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        A.out, 0, (int)(A.n_rows * F * 4), kBufferFlags);
+    auto store_row = [&](int32_t row, float v) {
+        if (F == 64 || lane < F) buffer_store_f32(v, o_rsrc, f * 4, row * (F * 4), 0);
+    };
     for (; item < part_end; item += items.stride) {
     const int64_t chunk = item - B.chunk_start[part];
     int64_t r0, r1;
     if (!chunk_rows(A, chunk, r0, r1)) continue;
-    const int64_t e_lo = A.row_ptr[r0], e_hi = A.row_ptr[r1];
+    // wave-uniform values loaded through vector instructions: keep them scalar (edge indices fit 32 bits)
+    const int32_t e_lo = __builtin_amdgcn_readfirstlane((int32_t)A.row_ptr[r0]);
+    const int32_t e_hi = __builtin_amdgcn_readfirstlane((int32_t)A.row_ptr[r1]);
     const int32_t r_end = (int32_t)r1;
     const bool keep_w = A.wstore != nullptr;
+    if (e_lo >= e_hi) {   // only empty rows
+        for (int32_t r = (int32_t)r0; r < r_end; ++r) store_row(r, 0.f);
+        continue;
+    }
     float acc = 0.f;
-    // edge data of the first tile; d = rc gives a zero filter, receiver r1 is the end sentinel
-    float dv = (e_lo + c32 < e_hi) ? A.d[e_lo + c32] : C.bp.rc;
-    int32_t rk = (e_lo + c32 < e_hi) ? A.recv[e_lo + c32] : r_end;
+    // edge records of the first tile (lane k mod 32 holds edge tb + k, clamped to the item's last edge;
+    // lanes past the end get d = rc, i.e. a zero filter, and the end sentinel r1 as receiver)
+    int32_t en = min(e_lo + c32, e_hi - 1);
+    float dv = A.d[en];
+    int32_t rk = A.recv[en];
+    int32_t sv = A.senders[en];
     {   // rows of the chunk before its first edge are empty
         const int32_t first = __builtin_amdgcn_readfirstlane(rk);
-        for (int64_t r = r0; r < first; ++r)
-            if (F == 64 || lane < F) A.out[r * F + f] = 0.f;
+        for (int32_t r = (int32_t)r0; r < first; ++r) store_row(r, 0.f);
     }
-    for (int64_t tb = e_lo; tb < e_hi; tb += 32) {
+    for (int32_t tb = e_lo; tb < e_hi; tb += 32) {
         const bool valid = tb + c32 < e_hi;
-        const int kmax = __builtin_amdgcn_readfirstlane((int)min((int64_t)32, e_hi - tb));
+        const int kmax = min(32, e_hi - tb);
         float b[8], db[8];
-        radial_basis<false>(dv, C.bp, b, db);
-        // sender rows of this tile (sender ids through scalar loads): issued now, consumed after the MFMA chain
+        radial_basis<false>(valid ? dv : C.bp.rc, C.bp, b, db);
+        // sender rows of this tile: issued now, consumed after the MFMA chain.  An edge past the end gathers the
+        // row of the item's last edge; its filter is zero.
         float gv[32];
-        int32_t sj[32];   // read unconditionally (device buffers carry 256 bytes of slack), masked afterwards
+        const int32_t so = sv * (F * 4);
 #pragma unroll
-        for (int k = 0; k < 32; ++k) sj[k] = uniform_load(A.senders, tb + k);
-#pragma unroll
-        for (int k = 0; k < 32; ++k) {
-            const int32_t jk = (k < kmax) ? sj[k] : 0;
-            gv[k] = buffer_load_f32(g_rsrc, f * 4, jk * (F * 4), 0);
-        }
-        const int32_t rcur = rk;
-        {   // next tile's edge data
-            const int64_t en = tb + 32 + c32;
-            dv = (en < e_hi) ? A.d[en] : C.bp.rc;
-            rk = (en < e_hi) ? A.recv[en] : r_end;
-        }
+        for (int k = 0; k < 32; ++k) gv[k] = buffer_load_f32(g_rsrc, f * 4, __builtin_amdgcn_readlane(so, k), 0);
+        const int32_t rcur = valid ? rk : r_end;
+        // next tile's edge records
+        en = min(tb + 32 + c32, e_hi - 1);
+        dv = A.d[en];
+        rk = A.recv[en];
+        sv = A.senders[en];
         __builtin_amdgcn_sched_barrier(0);
         f32x16 t[D::NB], w[D::NB];
         gemm_k8r<F>(W1, b, t, lane);
@@ -550,14 +559,15 @@ __global__ void __launch_bounds__(256, 3) k_edge_fwd(EdgeBatch B)
         wave_lds_fence();
         __builtin_amdgcn_sched_barrier(0);  // keep the use of the prefetched receiver after the MFMA chain
         int32_t rnext;
-        const uint32_t ends = row_ends(rcur, __builtin_amdgcn_readfirstlane(rk), valid, lane, rnext);
+        const int32_t nf = __builtin_amdgcn_readfirstlane(rk);
+        const uint32_t ends = row_ends(rcur, (tb + 32 < e_hi) ? nf : r_end, valid, lane, rnext);
         float wv[32];
 #pragma unroll
         for (int k = 0; k < 32; ++k) wv[k] = tile[k * D::FS + f];
         if (keep_w) {   // keep w_e for the reverse pass; rows past the end of the chunk fall outside the
                         // descriptor's range and are dropped by the hardware bounds check
             const __amdgpu_buffer_rsrc_t w_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-                A.wstore + tb * F, 0, kmax * (F * 4), kBufferFlags);
+                A.wstore + (int64_t)tb * F, 0, kmax * (F * 4), kBufferFlags);
 #pragma unroll
             for (int k = 0; k < 32; ++k)
                 if (F == 64 || lane < F) buffer_store_f32(wv[k], w_rsrc, f * 4, k * (F * 4), 0);
@@ -568,20 +578,16 @@ __global__ void __launch_bounds__(256, 3) k_edge_fwd(EdgeBatch B)
             if (ends & (1u << k)) {
                 const int32_t row = __builtin_amdgcn_readlane(rcur, k);
                 const int32_t nrow = __builtin_amdgcn_readlane(rnext, k);
-                if (F == 64 || lane < F) A.out[(int64_t)row * F + f] = acc;
+                store_row(row, acc);
                 acc = 0.f;
-                for (int64_t r = (int64_t)row + 1; r < nrow; ++r)   // empty rows in between
-                    if (F == 64 || lane < F) A.out[r * F + f] = 0.f;
+                for (int32_t r = row + 1; r < nrow; ++r) store_row(r, 0.f);   // empty rows in between
             }
         }
         wave_lds_fence();
-        // retire the prefetched edge data here (it arrived long ago); a load left pending across
+        // retire the prefetched edge records here (they arrived long ago); a load left pending across
         // the loop edge would make the compiler wait for all loads, gathers included, at the top
-        asm volatile("" : "+v"(dv), "+v"(rk));
+        asm volatile("" : "+v"(dv), "+v"(rk), "+v"(sv));
     }
-    if (e_lo >= e_hi)
-        for (int64_t r = r0; r < r1; ++r)
-            if (F == 64 || lane < F) A.out[r * F + f] = 0.f;
     }   // work items
     }   // partitions
 }

@@ -39,7 +39,10 @@ __device__ inline int floordiv(int a, int b)
     return q;
 }
 
-enum { ERR_RANGE = 1, ERR_COINCIDENT = 2, ERR_MIRROR = 4 };
+enum { ERR_RANGE = 1, ERR_COINCIDENT = 2, ERR_MIRROR = 4, FLAG_STAGE_OVERFLOW = 8 };
+// neighbours found by the counting pass are parked in a fixed-width row per atom, from where the sort picks them
+// up; an atom with more neighbours than this sets FLAG_STAGE_OVERFLOW and the rows are filled by a second pass
+constexpr int kStage = 96;
 
 // ---------------------------------------------------------------- scans
 
@@ -239,8 +242,9 @@ __global__ void k_fill_cells(int64_t N, const double *__restrict__ pos, const in
 }
 
 // One thread per atom, atoms taken in cell order so that a wavefront walks the
-// same candidate cells.  FILL = false counts, FILL = true writes unsorted keys
-// (sender << 32 | packed shift) into the atom's row.
+// same candidate cells.  FILL = false counts and, if `keys` is given, parks the first kStage unsorted keys
+// (sender << 32 | packed shift) in the atom's staging row keys[i * kStage ...]; FILL = true writes the keys
+// into the atom's CSR row.
 template <bool FILL>
 __global__ void k_neighbours(int64_t N, CellParams cp, const int32_t *__restrict__ cell_start,
                              const int32_t *__restrict__ sid, const double *__restrict__ sx,
@@ -261,6 +265,7 @@ __global__ void k_neighbours(int64_t N, CellParams cp, const int32_t *__restrict
     const int b0 = c / cp.nb[1];
     int64_t base = 0, cap = 0;
     if (FILL) { base = row_ptr[i]; cap = row_ptr[i + 1] - base; }
+    else base = (int64_t)i * kStage;
     int32_t cnt = 0;
     bool coincident = false;
     for (int dx = -cp.reach[0]; dx <= cp.reach[0]; ++dx) {
@@ -289,14 +294,18 @@ __global__ void k_neighbours(int64_t N, CellParams cp, const int32_t *__restrict
                     const double d2 = (t0 * t0 + t1 * t1) + t2 * t2;
                     if (d2 <= cp.rc2) {
                         if (d2 == 0.0) coincident = true;
-                        if (FILL && cnt < cap) keys[base + cnt] = ((uint64_t)(uint32_t)j << 32) | pack3(S0, S1, S2);
+                        if (FILL ? cnt < cap : (keys != nullptr && cnt < kStage))
+                            keys[base + cnt] = ((uint64_t)(uint32_t)j << 32) | pack3(S0, S1, S2);
                         ++cnt;
                     }
                 }
             }
         }
     }
-    if (!FILL) counts[i] = cnt;
+    if (!FILL) {
+        counts[i] = cnt;
+        if (keys != nullptr && cnt > kStage) atomicOr(err, FLAG_STAGE_OVERFLOW);
+    }
     if (coincident) atomicOr(err, ERR_COINCIDENT);
 }
 
@@ -305,13 +314,16 @@ __global__ void k_neighbours(int64_t N, CellParams cp, const int32_t *__restrict
 constexpr int kRowLds = 512;
 __global__ void __launch_bounds__(64)
 k_sort_rows(int64_t N, CellParams cp, const double *__restrict__ pos, const int64_t *__restrict__ row_ptr,
-            const uint64_t *__restrict__ keys, int32_t *senders, int32_t *recv, uint32_t *shiftp, float *d)
+            const uint64_t *__restrict__ keys_in, int staged_rows, int32_t *senders, int32_t *recv, uint32_t *shiftp,
+            float *d)
 {
     __shared__ uint64_t lds[kRowLds];
     const int64_t i = blockIdx.x;
     const int lane = threadIdx.x;
     const int64_t base = row_ptr[i];
     const int64_t n = row_ptr[i + 1] - base;
+    // unsorted keys of the row: in the staging row of the atom, or already at the row's place
+    const uint64_t *keys = staged_rows ? keys_in + i * kStage - base : keys_in;
     const bool staged = n <= kRowLds;
     if (staged)
         for (int64_t m = lane; m < n; m += 64) lds[m] = keys[base + m];
@@ -671,10 +683,14 @@ int build_graph_impl(mlip_graph *g, const double *positions, const double *cell,
                                                     g->sid.as<int32_t>(), g->sx.as<double>(), g->sy.as<double>(),
                                                     g->sz.as<double>(), g->swrap.as<uint32_t>());
     MLIP_HIP(hipGetLastError());
+    // the counting pass parks what it finds in fixed-width staging rows (768 B per atom), unless that would take
+    // more than 8 GB; the sort then reads the staging rows and the second neighbour pass is not needed
+    const bool use_stage = (size_t)N * kStage * 8 <= ((size_t)8 << 30);
+    if (use_stage) MLIP_TRY(g->stage.ensure((size_t)N * kStage * 8));
     k_neighbours<false><<<blocks_for(N, 128), 128, 0, s>>>(
         N, cp, g->cell_start.as<int32_t>(), g->sid.as<int32_t>(), g->sx.as<double>(), g->sy.as<double>(),
         g->sz.as<double>(), g->swrap.as<uint32_t>(), g->cell_of.as<int32_t>(), g->counts.as<int32_t>(), nullptr,
-        nullptr, err);
+        use_stage ? g->stage.as<uint64_t>() : nullptr, err);
     MLIP_HIP(hipGetLastError());
     MLIP_TRY(scan_i32_to_i64(g->counts.as<int32_t>(), g->row_ptr.as<int64_t>(), N, g->scan_tmp, s));
     // host needs E and the error flags
@@ -703,19 +719,24 @@ int build_graph_impl(mlip_graph *g, const double *positions, const double *cell,
         return MLIP_EINVAL;
     }
     const size_t Ecap = (size_t)std::max<int64_t>(E, 1);
-    MLIP_TRY(g->keys.ensure(Ecap * 8));
+    const bool staged = use_stage && !(flags & FLAG_STAGE_OVERFLOW);
+    if (!staged) MLIP_TRY(g->keys.ensure(Ecap * 8));
     MLIP_TRY(g->senders.ensure(Ecap * 4));
     MLIP_TRY(g->shiftp.ensure(Ecap * 4));
     MLIP_TRY(g->recv.ensure(Ecap * 4));
     MLIP_TRY(g->mirror.ensure(Ecap * 4));
     MLIP_TRY(g->d.ensure(Ecap * 4));
-    k_neighbours<true><<<blocks_for(N, 128), 128, 0, s>>>(
-        N, cp, g->cell_start.as<int32_t>(), g->sid.as<int32_t>(), g->sx.as<double>(), g->sy.as<double>(),
-        g->sz.as<double>(), g->swrap.as<uint32_t>(), g->cell_of.as<int32_t>(), nullptr, g->row_ptr.as<int64_t>(),
-        g->keys.as<uint64_t>(), err);
-    MLIP_HIP(hipGetLastError());
-    k_sort_rows<<<(unsigned)N, 64, 0, s>>>(N, cp, pos, g->row_ptr.as<int64_t>(), g->keys.as<uint64_t>(),
-                                           g->senders.as<int32_t>(), g->recv.as<int32_t>(), g->shiftp.as<uint32_t>(), g->d.as<float>());
+    if (!staged) {
+        k_neighbours<true><<<blocks_for(N, 128), 128, 0, s>>>(
+            N, cp, g->cell_start.as<int32_t>(), g->sid.as<int32_t>(), g->sx.as<double>(), g->sy.as<double>(),
+            g->sz.as<double>(), g->swrap.as<uint32_t>(), g->cell_of.as<int32_t>(), nullptr, g->row_ptr.as<int64_t>(),
+            g->keys.as<uint64_t>(), err);
+        MLIP_HIP(hipGetLastError());
+    }
+    k_sort_rows<<<(unsigned)N, 64, 0, s>>>(N, cp, pos, g->row_ptr.as<int64_t>(),
+                                           staged ? g->stage.as<uint64_t>() : g->keys.as<uint64_t>(), staged ? 1 : 0,
+                                           g->senders.as<int32_t>(), g->recv.as<int32_t>(), g->shiftp.as<uint32_t>(),
+                                           g->d.as<float>());
     MLIP_HIP(hipGetLastError());
 
     if (E > 0) {

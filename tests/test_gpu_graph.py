@@ -27,6 +27,25 @@ def test_graph_triclinic_small_cells(seed):
     assert_graph_equal(g, ref, pos, cell)
 
 
+def test_graph_rows_longer_than_staging():
+    """More than 96 neighbours per atom: the counting pass cannot park the keys, the second pass fills the rows."""
+    c = wl.make_config(0, n=4)
+    ref = og.build_graph(c["positions"], c["cell"], 7.0)
+    assert np.diff(ref.row_ptr).min() > 96
+    g = gpu_graph(c["positions"], c["cell"], c["species"], 7.0)
+    assert_graph_equal(g, ref, c["positions"], c["cell"])
+    # a mixed case: most rows short, a few long (a dense cluster inside a sparse box)
+    rng = np.random.default_rng(5)
+    pos = np.concatenate([rng.uniform(0, 40.0, (300, 3)), 20.0 + rng.uniform(0, 3.0, (130, 3))])
+    cell = np.eye(3) * 40.0
+    sp = np.zeros(len(pos), np.int32)
+    ref = og.build_graph(pos, cell, 5.0)
+    deg = np.diff(ref.row_ptr)
+    assert deg.max() > 96 and np.median(deg) < 96
+    g = gpu_graph(pos, cell, sp, 5.0)
+    assert_graph_equal(g, ref, pos, cell)
+
+
 def test_graph_edge_cases():
     import paper_2506_02023_amd as M
     cell = np.eye(3) * 30.0

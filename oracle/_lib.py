@@ -6,7 +6,7 @@ import os
 import subprocess
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRC = [os.path.join(_HERE, "mlip_oracle.c"), os.path.join(_HERE, "rmp_edge.inc")]
+_SRC = [os.path.join(_HERE, "mlip_oracle.c"), os.path.join(_HERE, "rmp_edge.inc"), os.path.join(_HERE, "bond3.inc")]
 _SO = os.path.join(_HERE, "libmlip_oracle.so")
 
 c_i32p = ctypes.POINTER(ctypes.c_int32)
@@ -65,5 +65,19 @@ def lib():
             f = getattr(L, "orc_force_scatter_" + suf)
             f.restype = None
             f.argtypes = [ctypes.c_int64, c_i64p, c_i32p, fp, fp, fp]
+            f = getattr(L, "orc3_triplet_forward_" + suf)
+            f.restype = None
+            f.argtypes = [ctypes.c_int64, c_i64p, fp, fp, fp, fp, fp, ctypes.c_int, ctypes.c_int, fp]
+            f = getattr(L, "orc3_triplet_backward_" + suf)
+            f.restype = None
+            f.argtypes = [ctypes.c_int64, c_i64p, fp, fp, fp, fp, fp, ctypes.c_int, ctypes.c_int, fp, fp, fp, fp, fp]
+            f = getattr(L, "orc3_edge_forward_" + suf)
+            f.restype = None
+            f.argtypes = [ctypes.c_int64, c_i64p, c_i32p, fp, real, ctypes.c_int, ctypes.c_int,
+                          ctypes.c_int, fp, fp, c_i64p, fp, fp, fp]
+            f = getattr(L, "orc3_edge_backward_" + suf)
+            f.restype = None
+            f.argtypes = [ctypes.c_int64, ctypes.c_int64, c_i64p, c_i32p, fp, real, ctypes.c_int,
+                          ctypes.c_int, ctypes.c_int, fp, fp, c_i64p, fp, fp, fp, fp, fp, fp]
         _lib = L
     return _lib

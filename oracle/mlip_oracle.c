@@ -337,6 +337,7 @@ void orc_geometry(int64_t N, const double *pos, const double *C, const int64_t *
 #define R_COS cos
 #define R_EXP exp
 #include "rmp_edge.inc"
+#include "bond3.inc"
 #undef REAL
 #undef FN
 #undef R_SIN
@@ -349,6 +350,7 @@ void orc_geometry(int64_t N, const double *pos, const double *C, const int64_t *
 #define R_COS cosf
 #define R_EXP expf
 #include "rmp_edge.inc"
+#include "bond3.inc"
 #undef REAL
 #undef FN
 #undef R_SIN

@@ -17,6 +17,8 @@ import numpy as np
 
 A_LAT = 3.6
 R_CUT = 5.0
+R_BOND = 3.0      # bond-graph cutoff of the three-body configuration
+A_ANGLE = 8       # angle basis size of the three-body configuration
 K_RADIAL = 8
 P_ENVELOPE = 6
 BASE_SEED = 2506020230
@@ -28,6 +30,7 @@ CONFIGS = {
     1: dict(n=20, sigma=0.10, S=4, F=64, L=3, P=1),
     2: dict(n=30, sigma=0.10, S=4, F=64, L=3, P=8),
     3: dict(n=63, sigma=0.15, S=8, F=64, L=3, P=8),
+    4: dict(n=37, sigma=0.10, S=4, F=64, L=3, P=1, three_body=True),
 }
 
 _FCC_BASIS = np.array(
@@ -84,8 +87,23 @@ def rmp_weights(n_species, F, L, seed, K=K_RADIAL):
     )
 
 
+def three_body_weights(F, L, seed, K=K_RADIAL, A=A_ANGLE):
+    """Extra fp32 weights of the three-body variant (bond width Fb = F), same conventions as rmp_weights.
+
+    Keys: We0 [K,F] bond embedding; Wt1 [2F+A,F], Wt2 [F,F] triplet MLP; Wb [L,F,F] bond term of each
+    layer's filter.
+    """
+    rng = np.random.default_rng(np.random.SeedSequence(seed).spawn(4)[3])
+
+    def lin(*shape, fan_in):
+        return (rng.normal(0.0, 1.0, size=shape) / np.sqrt(fan_in)).astype(np.float32)
+
+    return dict(We0=lin(K, F, fan_in=K), Wt1=lin(2 * F + A, F, fan_in=2 * F + A), Wt2=lin(F, F, fan_in=F),
+                Wb=lin(L, F, F, fan_in=F))
+
+
 def make_config(index, n=None, seed=None):
-    """Inputs of benchmark configuration `index` (0..3).
+    """Inputs of benchmark configuration `index` (0..4).
 
     `n` overrides the number of fcc cells per side (used for bounded samples of
     the same workload); everything else keeps the configuration's recipe.
@@ -98,10 +116,13 @@ def make_config(index, n=None, seed=None):
     seed = BASE_SEED + index if seed is None else seed
     positions, cell, species = fcc_lattice(cfg["n"], cfg["sigma"], cfg["S"], seed)
     weights = rmp_weights(cfg["S"], cfg["F"], cfg["L"], seed)
+    if cfg.get("three_body"):
+        weights.update(three_body_weights(cfg["F"], cfg["L"], seed))
     return dict(
         positions=positions, cell=cell, species=species, weights=weights,
         r_cut=R_CUT, K=K_RADIAL, p=P_ENVELOPE, F=cfg["F"], L=cfg["L"], S=cfg["S"],
         n_slabs=cfg["P"], name=f"configs[{index}] fcc {cfg['n']}^3",
+        three_body=bool(cfg.get("three_body")), r_bond=R_BOND, A=A_ANGLE,
     )
 
 

@@ -149,6 +149,37 @@ int mlip_build_graph(const double *positions, const double *cell, const int32_t 
 int mlip_forward(mlip_graph_t *graph, const mlip_weights_t *weights, int32_t mode,
                  double *energy, float *forces, float *atom_energy);
 
+/*
+ * Three-body (bond graph) variant: benchmark configuration 4; the paper's counterpart is the bond graph built
+ * over the atom graph, whose nodes are the atom-graph edges within a second, smaller cutoff (Methods,
+ * "Distributing Bond Graphs").  Extra weights, all fp32 row-major [fan_in][fan_out], DEVICE, borrowed:
+ *   We0 [K][F]        bond embedding  e0_b = bbond(d_b) We0 (Bessel basis and envelope at r_bond)
+ *   Wt1 [2F + A][F]   first triplet layer, input [e0_b1, e0_b2, cos(n theta) n = 0..A-1]
+ *   Wt2 [F][F]        second triplet layer, applied to sum_{b2 != b1} u_b2 SiLU(.)
+ *   Wb  [L][F][F]     bond term of layer l's filter: w_e += e1_b Wb_l for a bonded edge
+ * with e1_b = e0_b + u_b SiLU(m_b), u_b = u(d_b / r_bond).  A = 8.
+ */
+typedef struct {
+    float r_bond;
+    int32_t A;
+    const float *We0, *Wt1, *Wt2, *Wb;
+} mlip_bond_weights_t;
+
+/*
+ * Energy and forces of the three-body variant.  Arguments as mlip_forward.  The bond list (edges with
+ * d <= r_bond, same fp64 predicate as the neighbour list) is built on the first call after a graph build or a
+ * change of r_bond, which synchronises the stream once.  Only MLIP_MODE_WHOLE is supported so far; SLABS
+ * returns MLIP_ESTATE.
+ */
+int mlip_forward_bonds(mlip_graph_t *graph, const mlip_weights_t *weights, const mlip_bond_weights_t *bond_weights,
+                       int32_t mode, double *energy, float *forces, float *atom_energy);
+
+/*
+ * Bond list of the last mlip_forward_bonds (borrowed DEVICE pointers): bond_edge[n_bonds] = edge index of every
+ * bond, ascending; bond_ptr[N + 1] = bonds of centre i are bond_ptr[i] .. bond_ptr[i + 1]; n_bonds HOST.
+ */
+int mlip_graph_bonds(const mlip_graph_t *graph, const int32_t **bond_edge, const int64_t **bond_ptr, int64_t *n_bonds);
+
 void mlip_graph_destroy(mlip_graph_t *graph);
 
 /* N atoms, E directed edges, P slabs, all HOST outputs (any may be NULL). */

@@ -29,6 +29,11 @@ class _Weights(ctypes.Structure):
                [(n, ctypes.c_void_p) for n in ("emb", "W1", "W2", "Wm", "Wo", "Wr1", "wr2")]
 
 
+class _BondWeights(ctypes.Structure):
+    _fields_ = [("r_bond", ctypes.c_float), ("A", ctypes.c_int32)] + \
+               [(n, ctypes.c_void_p) for n in ("We0", "Wt1", "Wt2", "Wb")]
+
+
 class _SlabInfo(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int64) for n in ("n_owned", "n_pure", "n_border", "n_ghost", "n_local",
                                               "n_edges_owned", "n_edges")] + \
@@ -49,6 +54,8 @@ def lib():
         vp, i64, i32, dbl = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_double
         L.mlip_build_graph.argtypes = [vp, ctypes.POINTER(dbl), vp, i64, dbl, i32, vp, ctypes.POINTER(vp)]
         L.mlip_forward.argtypes = [vp, ctypes.POINTER(_Weights), i32, vp, vp, vp]
+        L.mlip_forward_bonds.argtypes = [vp, ctypes.POINTER(_Weights), ctypes.POINTER(_BondWeights), i32, vp, vp, vp]
+        L.mlip_graph_bonds.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(i64)]
         L.mlip_graph_destroy.argtypes = [vp]
         L.mlip_graph_destroy.restype = None
         L.mlip_graph_sizes.argtypes = [vp, ctypes.POINTER(i64), ctypes.POINTER(i64), ctypes.POINTER(i32)]
@@ -121,6 +128,13 @@ class Graph:
         _check(lib().mlip_graph_mirror(self._h, ctypes.byref(ptr)))
         return self._host(ptr.value, E, np.int32)
 
+    def bonds(self):
+        """(bond_edge int32 [n_bonds], bond_ptr int64 [N+1]) of the last mlip_forward_bonds."""
+        N, _, _ = self.sizes()
+        be, bp, n = ctypes.c_void_p(), ctypes.c_void_p(), ctypes.c_int64()
+        _check(lib().mlip_graph_bonds(self._h, ctypes.byref(be), ctypes.byref(bp), ctypes.byref(n)))
+        return self._host(be.value, n.value, np.int32), self._host(bp.value, N + 1, np.int64)
+
     def slab_of(self):
         N, _, _ = self.sizes()
         ptr, ax = ctypes.c_void_p(), ctypes.c_int32()
@@ -192,6 +206,30 @@ class Weights:
         self.F, self.L = F, L
         self.c = _Weights(S, F, L, K, p, 0, *[self.t[k].data_ptr() for k in
                                                ("emb", "W1", "W2", "Wm", "Wo", "Wr1", "wr2")])
+
+
+class BondWeights:
+    """Device copies of the three-body variant's extra weights plus the POD struct the library takes."""
+
+    def __init__(self, weights, r_bond, A=8, device="cuda"):
+        self.t = {k: torch.as_tensor(np.ascontiguousarray(weights[k], np.float32)).to(device).contiguous()
+                  for k in ("We0", "Wt1", "Wt2", "Wb")}
+        self.c = _BondWeights(float(r_bond), int(A), *[self.t[k].data_ptr() for k in ("We0", "Wt1", "Wt2", "Wb")])
+
+
+def mlip_forward_bonds(graph, weights, bond_weights, mode=MODE_WHOLE, out=None, want_atom_energy=True):
+    """Three-body variant; returns as mlip_forward.  Builds the bond list on first use (one stream synchronisation)."""
+    N, _, _ = graph.sizes()
+    if out is None:
+        energy = torch.empty(1, dtype=torch.float64, device="cuda")
+        forces = torch.empty((N, 3), dtype=torch.float32, device="cuda")
+        atom_e = torch.empty(N, dtype=torch.float32, device="cuda") if want_atom_energy else None
+    else:
+        energy, forces, atom_e = out
+    _check(lib().mlip_forward_bonds(graph._h, ctypes.byref(weights.c), ctypes.byref(bond_weights.c), int(mode),
+                                    ctypes.c_void_p(energy.data_ptr()), ctypes.c_void_p(forces.data_ptr()),
+                                    ctypes.c_void_p(atom_e.data_ptr() if atom_e is not None else None)))
+    return energy, forces, atom_e
 
 
 def mlip_forward(graph, weights, mode=MODE_WHOLE, out=None, want_atom_energy=True):

@@ -131,8 +131,7 @@ int mlip_build_graph(const double *positions, const double *cell, const int32_t 
     return MLIP_OK;
 }
 
-int mlip_forward(mlip_graph_t *g, const mlip_weights_t *w, int32_t mode, double *energy, float *forces,
-                 float *atom_energy)
+static int check_forward_args(mlip_graph_t *g, const mlip_weights_t *w, int32_t mode, double *energy, float *forces)
 {
     if (!g || !w || !energy || !forces) { set_error("null pointer argument"); return MLIP_EINVAL; }
     if (g->N <= 0) { set_error("graph handle holds no graph"); return MLIP_ESTATE; }
@@ -154,6 +153,13 @@ int mlip_forward(mlip_graph_t *g, const mlip_weights_t *w, int32_t mode, double 
         set_error("SLABS mode needs a graph built with n_slabs >= 2");
         return MLIP_ESTATE;
     }
+    return MLIP_OK;
+}
+
+int mlip_forward(mlip_graph_t *g, const mlip_weights_t *w, int32_t mode, double *energy, float *forces,
+                 float *atom_energy)
+{
+    MLIP_TRY(check_forward_args(g, w, mode, energy, forces));
     if (g->prof.on && g->prof.used + 1024 > (size_t)kMaxEvents) (void)prof_collect(g);
     try {
         return forward_impl(g, w, mode, energy, forces, atom_energy);
@@ -161,6 +167,41 @@ int mlip_forward(mlip_graph_t *g, const mlip_weights_t *w, int32_t mode, double 
         set_error("host exception: %s", e.what());
         return MLIP_ENOMEM;
     }
+}
+
+int mlip_forward_bonds(mlip_graph_t *g, const mlip_weights_t *w, const mlip_bond_weights_t *bw, int32_t mode,
+                       double *energy, float *forces, float *atom_energy)
+{
+    MLIP_TRY(check_forward_args(g, w, mode, energy, forces));
+    if (!bw || !bw->We0 || !bw->Wt1 || !bw->Wt2 || (w->L > 0 && !bw->Wb)) {
+        set_error("null bond weight pointer");
+        return MLIP_EINVAL;
+    }
+    if (bw->A != 8 || !(bw->r_bond > 0.f) || (double)bw->r_bond > g->r_cut) {
+        set_error("unsupported bond model (need A = 8 and 0 < r_bond <= r_cut)");
+        return MLIP_EINVAL;
+    }
+    if (mode != MLIP_MODE_WHOLE) {
+        set_error("the three-body variant runs in MLIP_MODE_WHOLE only");
+        return MLIP_ESTATE;
+    }
+    if (g->prof.on && g->prof.used + 1024 > (size_t)kMaxEvents) (void)prof_collect(g);
+    try {
+        return forward_bonds_impl(g, w, bw, mode, energy, forces, atom_energy);
+    } catch (const std::exception &e) {
+        set_error("host exception: %s", e.what());
+        return MLIP_ENOMEM;
+    }
+}
+
+int mlip_graph_bonds(const mlip_graph_t *g, const int32_t **bond_edge, const int64_t **bond_ptr, int64_t *n_bonds)
+{
+    if (!g || g->N <= 0) { set_error("no graph"); return MLIP_ESTATE; }
+    if (g->bonds.r_bond < 0) { set_error("no bond list: call mlip_forward_bonds first"); return MLIP_ESTATE; }
+    if (bond_edge) *bond_edge = g->bonds.edge.as<int32_t>();
+    if (bond_ptr) *bond_ptr = g->bonds.ptr.as<int64_t>();
+    if (n_bonds) *n_bonds = g->bonds.n;
+    return MLIP_OK;
 }
 
 void mlip_graph_destroy(mlip_graph_t *g)
@@ -172,6 +213,13 @@ void mlip_graph_destroy(mlip_graph_t *g)
                       &g->small, &g->row_ptr, &g->senders, &g->recv, &g->mirror, &g->shiftp, &g->d, &g->chunk_row, &g->slab_of, &g->needed_by,
                       &g->local_of, &g->local_in_owner, &g->class_cnt, &g->class_off, &g->wpack, &g->energy_part};
     for (DevBuf *b : bufs) b->release();
+    {
+        BondGraph &B = g->bonds;
+        DevBuf *bb[] = {&B.scan, &B.flag, &B.of_edge, &B.edge, &B.ptr, &B.mirror, &B.sender, &B.d, &B.u, &B.du, &B.rhat,
+                        &B.e0, &B.P, &B.Q, &B.S, &B.m, &B.e1, &B.wb, &B.wbbar, &B.e1bar, &B.Sbar, &B.Pbar, &B.Qbar,
+                        &B.ubar, &B.dbond, &B.rbar, &B.wpack};
+        for (DevBuf *b : bb) b->release();
+    }
     auto drop_view = [](SlabView &v) {
         DevBuf *vb[] = {&v.h, &v.hbar, &v.abar, &v.gbar, &v.eps, &v.dsum, &v.floc, &v.g, &v.a, &v.wst};
         for (DevBuf *b : vb) b->release();

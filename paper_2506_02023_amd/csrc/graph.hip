@@ -624,6 +624,76 @@ int prepare_cell(const double *C, double r_cut, int32_t n_slabs, int64_t N, Cell
     return MLIP_OK;
 }
 
+// ---------------------------------------------------------------- bond list (three-body variant)
+
+// flag[e] = 1 if the edge is a bond: the neighbour list's own fp64 test with the bond cutoff
+__global__ void k_bond_flag(int64_t E, CellParams cp, double rb2, const double *__restrict__ pos,
+                            const int32_t *__restrict__ recv, const int32_t *__restrict__ senders,
+                            const uint32_t *__restrict__ shiftp, int32_t *flag)
+{
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= E) return;
+    const int64_t i = recv[e], j = senders[e];
+    int S0, S1, S2;
+    unpack3(shiftp[e], S0, S1, S2);
+    const double t0 = (pos[3 * j] - pos[3 * i]) + (((double)S0 * cp.C[0] + (double)S1 * cp.C[3]) + (double)S2 * cp.C[6]);
+    const double t1 = (pos[3 * j + 1] - pos[3 * i + 1]) + (((double)S0 * cp.C[1] + (double)S1 * cp.C[4]) + (double)S2 * cp.C[7]);
+    const double t2 = (pos[3 * j + 2] - pos[3 * i + 2]) + (((double)S0 * cp.C[2] + (double)S1 * cp.C[5]) + (double)S2 * cp.C[8]);
+    const double d2 = (t0 * t0 + t1 * t1) + t2 * t2;
+    flag[e] = (d2 <= rb2) ? 1 : 0;
+}
+
+// bond numbering in edge order; unit vector (fp64, rounded once), length, envelope and its derivative
+__global__ void k_bond_fill(int64_t E, CellParams cp, double r_bond, int p, const double *__restrict__ pos,
+                            const int32_t *__restrict__ recv, const int32_t *__restrict__ senders,
+                            const uint32_t *__restrict__ shiftp, const float *__restrict__ d,
+                            const int32_t *__restrict__ flag, const int32_t *__restrict__ scan, int32_t *of_edge,
+                            int32_t *edge, int32_t *sender, float *bd, float *bu, float *bdu, float *rhat)
+{
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= E) return;
+    if (!flag[e]) { of_edge[e] = -1; return; }
+    const int32_t b = scan[e];
+    of_edge[e] = b;
+    edge[b] = (int32_t)e;
+    const int64_t i = recv[e], j = senders[e];
+    sender[b] = (int32_t)j;
+    int S0, S1, S2;
+    unpack3(shiftp[e], S0, S1, S2);
+    const double t0 = (pos[3 * j] - pos[3 * i]) + (((double)S0 * cp.C[0] + (double)S1 * cp.C[3]) + (double)S2 * cp.C[6]);
+    const double t1 = (pos[3 * j + 1] - pos[3 * i + 1]) + (((double)S0 * cp.C[1] + (double)S1 * cp.C[4]) + (double)S2 * cp.C[7]);
+    const double t2 = (pos[3 * j + 2] - pos[3 * i + 2]) + (((double)S0 * cp.C[2] + (double)S1 * cp.C[5]) + (double)S2 * cp.C[8]);
+    const double dd = sqrt((t0 * t0 + t1 * t1) + t2 * t2);
+    rhat[3 * b] = (float)(t0 / dd);
+    rhat[3 * b + 1] = (float)(t1 / dd);
+    rhat[3 * b + 2] = (float)(t2 / dd);
+    bd[b] = d[e];
+    // u(x) = 1 - c0 x^p + c1 x^(p+1) - c2 x^(p+2), x = d / r_bond
+    const double x = dd / r_bond, pd = (double)p;
+    const double c0 = (pd + 1) * (pd + 2) / 2, c1 = pd * (pd + 2), c2 = pd * (pd + 1) / 2;
+    double xpm1 = 1.0;
+    for (int k = 0; k < p - 1; ++k) xpm1 *= x;
+    const double xp = xpm1 * x;
+    bu[b] = (float)(1.0 - xp * (c0 - x * (c1 - c2 * x)));
+    bdu[b] = (float)((-xpm1 * (pd * c0 - x * ((pd + 1) * c1 - (pd + 2) * c2 * x))) / r_bond);
+}
+
+__global__ void k_bond_ptr(int64_t N, const int64_t *__restrict__ row_ptr, const int32_t *__restrict__ scan, int64_t *ptr)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i > N) return;
+    ptr[i] = scan[row_ptr[i]];
+}
+
+// the reverse edge of a bond has the same length, so it is a bond too
+__global__ void k_bond_mirror(int64_t nb, const int32_t *__restrict__ edge, const int32_t *__restrict__ mirror,
+                              const int32_t *__restrict__ of_edge, int32_t *bmirror)
+{
+    const int64_t b = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= nb) return;
+    bmirror[b] = of_edge[mirror[edge[b]]];
+}
+
 }  // namespace
 
 int unpack_shifts(const mlip_graph *g, int32_t *out)
@@ -635,6 +705,56 @@ int unpack_shifts(const mlip_graph *g, int32_t *out)
     return MLIP_OK;
 }
 
+int build_bonds_impl(mlip_graph *g, double r_bond, int p_envelope)
+{
+    BondGraph &B = g->bonds;
+    if (B.r_bond == r_bond) return MLIP_OK;   // same graph (a rebuild resets r_bond), same cutoff
+    hipStream_t s = g->stream;
+    const int64_t E = g->E, N = g->N;
+    const size_t Ecap = (size_t)std::max<int64_t>(E, 1);
+    MLIP_TRY(B.flag.ensure(Ecap * 4));
+    MLIP_TRY(B.scan.ensure((Ecap + 1) * 4));
+    MLIP_TRY(B.of_edge.ensure(Ecap * 4));
+    MLIP_TRY(B.ptr.ensure((size_t)(N + 1) * 8));
+    const double *pos = g->pos.as<double>();
+    if (E > 0) {
+        k_bond_flag<<<blocks_for(E, 256), 256, 0, s>>>(E, g->cell, r_bond * r_bond, pos, g->recv.as<int32_t>(),
+                                                       g->senders.as<int32_t>(), g->shiftp.as<uint32_t>(),
+                                                       B.flag.as<int32_t>());
+        MLIP_HIP(hipGetLastError());
+    }
+    MLIP_TRY(scan_i32_to_i32(B.flag.as<int32_t>(), B.scan.as<int32_t>(), E, g->scan_tmp, s));
+    int32_t *hp = static_cast<int32_t *>(g->pinned);
+    MLIP_HIP(hipMemcpyAsync(hp, B.scan.as<int32_t>() + E, 4, hipMemcpyDeviceToHost, s));
+    MLIP_HIP(hipStreamSynchronize(s));
+    const int64_t nb = hp[0];
+    const size_t ncap = (size_t)std::max<int64_t>(nb, 1);
+    MLIP_TRY(B.edge.ensure(ncap * 4));
+    MLIP_TRY(B.sender.ensure(ncap * 4));
+    MLIP_TRY(B.mirror.ensure(ncap * 4));
+    MLIP_TRY(B.d.ensure(ncap * 4));
+    MLIP_TRY(B.u.ensure(ncap * 4));
+    MLIP_TRY(B.du.ensure(ncap * 4));
+    MLIP_TRY(B.rhat.ensure(ncap * 12));
+    if (E > 0) {
+        k_bond_fill<<<blocks_for(E, 256), 256, 0, s>>>(
+            E, g->cell, r_bond, p_envelope, pos, g->recv.as<int32_t>(), g->senders.as<int32_t>(), g->shiftp.as<uint32_t>(),
+            g->d.as<float>(), B.flag.as<int32_t>(), B.scan.as<int32_t>(), B.of_edge.as<int32_t>(), B.edge.as<int32_t>(),
+            B.sender.as<int32_t>(), B.d.as<float>(), B.u.as<float>(), B.du.as<float>(), B.rhat.as<float>());
+        MLIP_HIP(hipGetLastError());
+    }
+    k_bond_ptr<<<blocks_for(N + 1, 256), 256, 0, s>>>(N, g->row_ptr.as<int64_t>(), B.scan.as<int32_t>(), B.ptr.as<int64_t>());
+    MLIP_HIP(hipGetLastError());
+    if (nb > 0) {
+        k_bond_mirror<<<blocks_for(nb, 256), 256, 0, s>>>(nb, B.edge.as<int32_t>(), g->mirror.as<int32_t>(),
+                                                          B.of_edge.as<int32_t>(), B.mirror.as<int32_t>());
+        MLIP_HIP(hipGetLastError());
+    }
+    B.n = nb;
+    B.r_bond = r_bond;
+    return MLIP_OK;
+}
+
 int build_graph_impl(mlip_graph *g, const double *positions, const double *cell, const int32_t *species,
                      int64_t N, double r_cut, int32_t P)
 {
@@ -643,6 +763,7 @@ int build_graph_impl(mlip_graph *g, const double *positions, const double *cell,
     MLIP_TRY(prepare_cell(cell, r_cut, P, N, cp));
     g->cell = cp;
     g->N = 0;  // the handle is invalid until the build completes
+    g->bonds.r_bond = -1.0;
     g->E = 0;
     const int64_t ncell = (int64_t)cp.nb[0] * cp.nb[1] * cp.nb[2];
     if (!g->pinned) MLIP_HIP(hipHostMalloc(&g->pinned, 4096, hipHostMallocDefault));

@@ -81,6 +81,26 @@ struct SlabStore {  // device arrays owned per slab
     DevBuf nodes, row_ptr, senders, recv, mirror, shiftp, d, chunk_row, ghost_owner, ghost_src, owned_sorted, rowlen;
 };
 
+// Bond graph of the three-body variant (whole graph): the edges within the bond cutoff, in edge order.
+struct BondGraph {
+    double r_bond = -1.0;   // cutoff the list was built for (< 0: none)
+    int64_t n = 0;          // bonds
+    DevBuf scan;            // i32 [E + 1] exclusive scan of the bond flags
+    DevBuf flag;            // i32 [E]
+    DevBuf of_edge;         // i32 [E]   bond index of an edge, -1 if it is no bond
+    DevBuf edge;            // i32 [n]   edge index of a bond
+    DevBuf ptr;             // i64 [N + 1] bonds of centre i: ptr[i] .. ptr[i + 1]
+    DevBuf mirror;          // i32 [n]   the bond of the reverse edge
+    DevBuf sender;          // i32 [n]   sender atom of the bond
+    DevBuf d, u, du;        // f32 [n]   length, envelope u(d / r_bond), du/dd
+    DevBuf rhat;            // f32 [n][3] unit vector from the centre to the neighbour's image
+    // model workspace, [n][F] unless noted
+    DevBuf e0, P, Q, S, m, e1, wb /* [L][n][F] */, wbbar, e1bar, Sbar, Pbar, Qbar;
+    DevBuf ubar, dbond;     // f32 [n]
+    DevBuf rbar;            // f32 [n][3]
+    DevBuf wpack;           // packed weights of the bond part
+};
+
 enum { kMaxSlabs = 64, kMaxEvents = 4096 };
 
 struct Profiler {
@@ -116,6 +136,7 @@ struct mlip_graph {
     // forward scratch shared by all views
     mlip::DevBuf wpack, energy_part;
     mlip::Profiler prof;
+    mlip::BondGraph bonds;
     void *pinned = nullptr;  // small pinned host staging area
 };
 
@@ -133,5 +154,9 @@ int build_graph_impl(mlip_graph *g, const double *positions, const double *cell,
 int forward_impl(mlip_graph *g, const mlip_weights_t *w, int32_t mode, double *energy, float *forces,
                  float *atom_energy);
 int unpack_shifts(const mlip_graph *g, int32_t *out);
+// bond list of the whole graph for cutoff r_bond (kept until the graph is rebuilt or r_bond changes); synchronises
+int build_bonds_impl(mlip_graph *g, double r_bond, int p_envelope);
+int forward_bonds_impl(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t *bw, int32_t mode,
+                       double *energy, float *forces, float *atom_energy);
 
 }  // namespace mlip

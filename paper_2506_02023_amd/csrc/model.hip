@@ -1220,6 +1220,279 @@ __global__ void __launch_bounds__(256) k_energy_final(int64_t n, const double *_
     if (threadIdx.x == 0) *energy = (sh[0] + sh[1]) + (sh[2] + sh[3]);
 }
 
+// ---------------------------------------------------------------- three-body (bond graph) kernels
+//
+// Benchmark configuration 4: bonds are the atom-graph edges within a smaller cutoff, two bonds interact when
+// they share their centre atom (the paper's bond graph, Methods, "Distributing Bond Graphs").  All bonds of a
+// centre are contiguous, so every kernel below works on one centre (or one bond) per wavefront with lane =
+// feature and needs no atomics.  Notation: P_b = e0_b Wta, Q_b = e0_b Wtb, Wtc = rows 2F.. of Wt1,
+//   h(b1, b2) = P_b1 + Q_b2 + T(c) Wtc,  S_b1 = sum_{b2 != b1} u_b2 SiLU(h),  m = S Wt2,  e1 = e0 + u SiLU(m).
+
+constexpr int kAngle = 8;
+
+__device__ inline float silu_f(float x) { return x * __builtin_amdgcn_rcpf(1.0f + __expf(-x)); }
+__device__ inline void silu_both(float x, float &s, float &ds)
+{
+    const float sg = __builtin_amdgcn_rcpf(1.0f + __expf(-x));
+    s = x * sg;
+    ds = sg * (1.0f + x * (1.0f - sg));
+}
+
+// T_n(c) = cos(n theta), dT_n/dc = n U_{n-1}(c), n = 0..7
+__device__ inline void chebyshev(float c, float (&T)[kAngle], float (&dT)[kAngle])
+{
+    T[0] = 1.f; dT[0] = 0.f;
+    T[1] = c;   dT[1] = 1.f;
+    float Um = 1.f, Un = 2.f * c;   // U_0, U_1
+#pragma unroll
+    for (int n = 2; n < kAngle; ++n) {
+        T[n] = 2.f * c * T[n - 1] - T[n - 2];
+        dT[n] = (float)n * Un;
+        const float Ux = 2.f * c * Un - Um;
+        Um = Un;
+        Un = Ux;
+    }
+}
+
+// e0[b][f] = sum_n bbond_n(d_b) We0[n][f]
+template <int F>
+__global__ void __launch_bounds__(256) k_bond_e0(int64_t nb, const float *__restrict__ bd, BasisParams bp,
+                                                 const float *__restrict__ We0, float *__restrict__ e0)
+{
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= nb * F) return;
+    const int64_t b = idx / F;
+    const int f = (int)(idx % F);
+    float bb[8], db[8];
+    radial_basis<false>(bd[b], bp, bb, db);
+    float acc = 0.f;
+#pragma unroll
+    for (int n = 0; n < 8; ++n) acc = fmaf(bb[n], We0[n * F + f], acc);
+    e0[idx] = acc;
+}
+
+// S[b1][f] = sum_{b2 != b1, same centre} u[b2] SiLU(P[b1][f] + Q[b2][f] + sum_n T_n(c) Wtc[n][f])
+template <int F>
+__global__ void __launch_bounds__(256)
+k_triplet_fwd(int64_t N, const int64_t *__restrict__ bptr, const float *__restrict__ rhat, const float *__restrict__ u,
+              const float *__restrict__ P, const float *__restrict__ Q, const float *__restrict__ Wtc, float *__restrict__ S)
+{
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int64_t i = (int64_t)blockIdx.x * 4 + wave;
+    if (i >= N) return;
+    const int f = lane & (F - 1);
+    float wc[kAngle];
+#pragma unroll
+    for (int n = 0; n < kAngle; ++n) wc[n] = Wtc[n * F + f];
+    const int64_t b0 = bptr[i], b1e = bptr[i + 1];
+    for (int64_t b1 = b0; b1 < b1e; ++b1) {
+        const float p1 = P[b1 * F + f];
+        const float x1 = rhat[3 * b1], y1 = rhat[3 * b1 + 1], z1 = rhat[3 * b1 + 2];
+        float acc = 0.f;
+        for (int64_t b2 = b0; b2 < b1e; ++b2) {
+            if (b2 == b1) continue;
+            const float c = fmaf(x1, rhat[3 * b2], fmaf(y1, rhat[3 * b2 + 1], z1 * rhat[3 * b2 + 2]));
+            float T[kAngle], dT[kAngle];
+            chebyshev(c, T, dT);
+            float h = p1 + Q[b2 * F + f];
+#pragma unroll
+            for (int n = 0; n < kAngle; ++n) h = fmaf(T[n], wc[n], h);
+            acc = fmaf(u[b2], silu_f(h), acc);
+        }
+        if (F == 64 || lane < F) S[b1 * F + f] = acc;
+    }
+}
+
+// e1 = e0 + u SiLU(m)
+template <int F>
+__global__ void __launch_bounds__(256) k_bond_e1(int64_t nb, const float *__restrict__ e0, const float *__restrict__ m,
+                                                 const float *__restrict__ u, float *__restrict__ e1)
+{
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= nb * F) return;
+    e1[idx] = fmaf(u[idx / F], silu_f(m[idx]), e0[idx]);
+}
+
+// bond term of a layer's aggregation: a[i] += sum over the bonds b = (i <- j) of wb[b] * g[j]
+template <int F>
+__global__ void __launch_bounds__(256)
+k_bond_aggregate(int64_t N, const int64_t *__restrict__ bptr, const int32_t *__restrict__ sender,
+                 const float *__restrict__ wb, const float *__restrict__ g, float *__restrict__ a)
+{
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int64_t i = (int64_t)blockIdx.x * 4 + wave;
+    if (i >= N) return;
+    const int f = lane & (F - 1);
+    float acc = 0.f;
+    for (int64_t b = bptr[i]; b < bptr[i + 1]; ++b) acc = fmaf(wb[b * F + f], g[(int64_t)sender[b] * F + f], acc);
+    if (F == 64 || lane < F) a[i * F + f] += acc;
+}
+
+// reverse of the bond term: wbbar[b] = abar[i] * g[j]; gbar[i] (+)= sum_b wb[mirror(b)] * abar[j]
+// (the reverse bond (j <- i) is the one whose filter multiplies g_i in row j)
+template <int F>
+__global__ void __launch_bounds__(256)
+k_bond_bwd(int64_t N, const int64_t *__restrict__ bptr, const int32_t *__restrict__ sender,
+           const int32_t *__restrict__ bmirror, const float *__restrict__ wb, const float *__restrict__ g,
+           const float *__restrict__ abar, float *__restrict__ wbbar, float *gbar)
+{
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int64_t i = (int64_t)blockIdx.x * 4 + wave;
+    if (i >= N) return;
+    const int f = lane & (F - 1);
+    const float ai = abar[i * F + f];
+    float acc = 0.f;
+    for (int64_t b = bptr[i]; b < bptr[i + 1]; ++b) {
+        const int64_t j = sender[b];
+        if (F == 64 || lane < F) wbbar[b * F + f] = ai * g[j * F + f];
+        if (gbar) acc = fmaf(wb[(int64_t)bmirror[b] * F + f], abar[j * F + f], acc);
+    }
+    if (gbar && (F == 64 || lane < F)) gbar[i * F + f] += acc;
+}
+
+// e1 = e0 + u SiLU(m):  ubar[b] = sum_f e1bar SiLU(m);  mbar = e1bar u SiLU'(m)
+template <int F>
+__global__ void __launch_bounds__(256)
+k_bond_mbar(int64_t nb, const float *__restrict__ e1bar, const float *__restrict__ m, const float *__restrict__ u,
+            float *__restrict__ mbar, float *__restrict__ ubar)
+{
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int64_t b = (int64_t)blockIdx.x * 4 + wave;
+    if (b >= nb) return;
+    const int f = lane & (F - 1);
+    float s, ds;
+    silu_both(m[b * F + f], s, ds);
+    const float eb = e1bar[b * F + f];
+    float part = (F == 64 || lane < F) ? eb * s : 0.f;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off, 64);
+    if (F == 64 || lane < F) mbar[b * F + f] = eb * u[b] * ds;
+    if (lane == 0) ubar[b] = part;
+}
+
+// Reverse of k_triplet_fwd for one centre per wavefront.  Pbar[b1] and rbar[b1] accumulate over the inner
+// loop in registers; Qbar[b2], ubar[b2] and rbar[b2] are indexed by the inner bond, so they are accumulated in
+// a second sweep with the roles of the loops exchanged (h is recomputed there) - no LDS, any number of bonds.
+template <int F>
+__global__ void __launch_bounds__(256)
+k_triplet_bwd(int64_t N, const int64_t *__restrict__ bptr, const float *__restrict__ rhat, const float *__restrict__ u,
+              const float *__restrict__ P, const float *__restrict__ Q, const float *__restrict__ Wtc,
+              const float *__restrict__ Sbar, float *__restrict__ Pbar, float *__restrict__ Qbar,
+              float *__restrict__ ubar, float *__restrict__ rbar)
+{
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int64_t i = (int64_t)blockIdx.x * 4 + wave;
+    if (i >= N) return;
+    const int f = lane & (F - 1);
+    const bool on = (F == 64 || lane < F);
+    float wc[kAngle];
+#pragma unroll
+    for (int n = 0; n < kAngle; ++n) wc[n] = Wtc[n * F + f];
+    const int64_t b0 = bptr[i], be = bptr[i + 1];
+    for (int64_t ba = b0; ba < be; ++ba) {
+        const float xa = rhat[3 * ba], ya = rhat[3 * ba + 1], za = rhat[3 * ba + 2];
+        const float pa = P[ba * F + f], qa = Q[ba * F + f], sa = Sbar[ba * F + f], ua = u[ba];
+        float pbar = 0.f, qbar = 0.f, ub = 0.f, rx = 0.f, ry = 0.f, rz = 0.f;
+        for (int64_t bo = b0; bo < be; ++bo) {
+            if (bo == ba) continue;
+            const float xo = rhat[3 * bo], yo = rhat[3 * bo + 1], zo = rhat[3 * bo + 2];
+            const float c = fmaf(xa, xo, fmaf(ya, yo, za * zo));
+            float T[kAngle], dT[kAngle];
+            chebyshev(c, T, dT);
+            float tw = 0.f, dw = 0.f;   // T(c) Wtc and dT(c)/dc Wtc for this lane's feature
+#pragma unroll
+            for (int n = 0; n < kAngle; ++n) {
+                tw = fmaf(T[n], wc[n], tw);
+                dw = fmaf(dT[n], wc[n], dw);
+            }
+            // triplet (b1 = ba, b2 = bo): contributes to Pbar[ba] and, through c, to rbar[ba]
+            float s1, ds1;
+            silu_both(pa + Q[bo * F + f] + tw, s1, ds1);
+            const float h1 = sa * u[bo] * ds1;
+            pbar += h1;
+            // triplet (b1 = bo, b2 = ba): contributes to Qbar[ba], ubar[ba] and, through c, to rbar[ba]
+            float s2, ds2;
+            const float so = Sbar[bo * F + f];
+            silu_both(P[bo * F + f] + qa + tw, s2, ds2);
+            const float h2 = so * ua * ds2;
+            qbar += h2;
+            ub = fmaf(so, s2, ub);
+            const float dc = on ? (h1 + h2) * dw : 0.f;   // this lane's share of dE/dc from both triplets
+            rx = fmaf(dc, xo, rx);
+            ry = fmaf(dc, yo, ry);
+            rz = fmaf(dc, zo, rz);
+        }
+        if (!on) ub = 0.f;
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            ub += __shfl_xor(ub, off, 64);
+            rx += __shfl_xor(rx, off, 64);
+            ry += __shfl_xor(ry, off, 64);
+            rz += __shfl_xor(rz, off, 64);
+        }
+        if (on) {
+            Pbar[ba * F + f] = pbar;
+            Qbar[ba * F + f] = qbar;
+        }
+        if (lane == 0) {
+            ubar[ba] += ub;
+            rbar[3 * ba] = rx;
+            rbar[3 * ba + 1] = ry;
+            rbar[3 * ba + 2] = rz;
+        }
+    }
+}
+
+// dE/dd_b through e0 = bbond(d) We0 and u = u(d / r_bond):
+//   dbond[b] = sum_f e0bar[b][f] (sum_n We0[n][f] dbbond_n/dd) + ubar[b] du/dd
+template <int F>
+__global__ void __launch_bounds__(256)
+k_bond_dist_bwd(int64_t nb, const float *__restrict__ e0bar, const float *__restrict__ We0, const float *__restrict__ bd,
+                BasisParams bp, const float *__restrict__ ubar, const float *__restrict__ bdu, float *__restrict__ dbond)
+{
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int64_t b = (int64_t)blockIdx.x * 4 + wave;
+    if (b >= nb) return;
+    const int f = lane & (F - 1);
+    float bb[8], db[8];
+    radial_basis<true>(bd[b], bp, bb, db);
+    float v = 0.f;
+#pragma unroll
+    for (int n = 0; n < 8; ++n) v = fmaf(We0[n * F + f], db[n], v);
+    float part = (F == 64 || lane < F) ? e0bar[b * F + f] * v : 0.f;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off, 64);
+    if (lane == 0) dbond[b] = fmaf(ubar[b], bdu[b], part);
+}
+
+// Forces of the bond part.  dE/dDelta_b = dbond rhat + (rbar - (rbar . rhat) rhat) / d for the bond vector
+// Delta_b = r_j + S C - r_i; it pulls on j with + and on i with -.  Gathered per centre: the bonds in which i
+// is the sender are the reverse bonds of its own.   F_i += sum_b (gDelta_b - gDelta_mirror(b))
+__global__ void k_bond_force(int64_t N, const int64_t *__restrict__ bptr, const int32_t *__restrict__ bmirror,
+                             const float *__restrict__ dbond, const float *__restrict__ rbar,
+                             const float *__restrict__ rhat, const float *__restrict__ bd, float *floc)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= N) return;
+    float fx = 0.f, fy = 0.f, fz = 0.f;
+    for (int64_t b = bptr[i]; b < bptr[i + 1]; ++b) {
+        for (int side = 0; side < 2; ++side) {
+            const int64_t q = side ? (int64_t)bmirror[b] : b;
+            const float x = rhat[3 * q], y = rhat[3 * q + 1], z = rhat[3 * q + 2];
+            const float ax = rbar[3 * q], ay = rbar[3 * q + 1], az = rbar[3 * q + 2];
+            const float dot = fmaf(ax, x, fmaf(ay, y, az * z));
+            const float inv = 1.0f / bd[q];
+            const float sgn = side ? -1.f : 1.f;
+            fx += sgn * fmaf(dbond[q], x, (ax - dot * x) * inv);
+            fy += sgn * fmaf(dbond[q], y, (ay - dot * y) * inv);
+            fz += sgn * fmaf(dbond[q], z, (az - dot * z) * inv);
+        }
+    }
+    floc[3 * i] += fx;
+    floc[3 * i + 1] += fy;
+    floc[3 * i + 2] += fz;
+}
+
 inline unsigned blocks_for(int64_t n, int threads) { return (unsigned)((n + threads - 1) / threads); }
 
 // ---------------------------------------------------------------- host driver
@@ -1333,8 +1606,24 @@ template <int F> int launch_edge(mlip_graph *g, EdgeBatch &b, bool backward)
     return MLIP_OK;
 }
 
+// y = x W over n_rows rows with a packed F x F operand: Y = X P1 (OP_PROJ) or Z += X P1 (OP_BWD_PROJ)
+template <int F, int OP>
+int rows_gemm(mlip_graph *g, const float *P1, int64_t n_rows, const float *X, float *out)
+{
+    NodeBatch nb{};
+    nb.n = 1;
+    nb.P1 = P1;
+    nb.s[0].n_rows = n_rows;
+    nb.s[0].X = X;
+    nb.s[0].Y = out;
+    nb.s[0].Z = out;
+    return launch_node<F, OP>(g, nb);
+}
+
+// bw != nullptr: the three-body variant (whole graph only)
 template <int F>
-int forward_t(mlip_graph *g, const mlip_weights_t *w, int32_t mode, double *energy, float *forces, float *atom_energy)
+int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t *bw, int32_t mode, double *energy,
+              float *forces, float *atom_energy)
 {
     hipStream_t s = g->stream;
     const int L = w->L;
@@ -1412,6 +1701,62 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, int32_t mode, double *ener
     MLIP_HIP(hipGetLastError());
     prof_end(g);
 
+    // ---- three-body variant: bond list, bond embedding, triplet update, bond terms of the layers' filters
+    BondGraph &BG = g->bonds;
+    int64_t nbond = 0;
+    size_t bstride = 0;          // floats per [n][F] bond array
+    float *bpk = nullptr;        // packed F x F operands of the bond part
+    const size_t ffp = (size_t)F * F;
+    // operand slots: 0 Wta (y = x W), 1 Wtb, 2 Wt2, 3 Wta^T, 4 Wtb^T, 5 Wt2^T, 6 + l Wb_l, 6 + L + l Wb_l^T
+    BasisParams bpb = bp;
+    if (bw) {
+        MLIP_TRY(build_bonds_impl(g, (double)bw->r_bond, w->p));
+        nbond = BG.n;
+        bstride = (size_t)std::max<int64_t>(nbond, 1) * F;
+        bpb.rc = bw->r_bond;
+        bpb.inv_rc = 1.0f / bw->r_bond;
+        DevBuf *fb[] = {&BG.e0, &BG.P, &BG.Q, &BG.S, &BG.m, &BG.e1, &BG.wbbar, &BG.e1bar, &BG.Sbar, &BG.Pbar, &BG.Qbar};
+        for (DevBuf *b : fb) MLIP_TRY(b->ensure(bstride * sizeof(float)));
+        MLIP_TRY(BG.wb.ensure(bstride * sizeof(float) * (size_t)std::max(L, 1)));
+        MLIP_TRY(BG.ubar.ensure((size_t)std::max<int64_t>(nbond, 1) * sizeof(float)));
+        MLIP_TRY(BG.dbond.ensure((size_t)std::max<int64_t>(nbond, 1) * sizeof(float)));
+        MLIP_TRY(BG.rbar.ensure((size_t)std::max<int64_t>(nbond, 1) * 3 * sizeof(float)));
+        MLIP_TRY(BG.wpack.ensure((size_t)(6 + 2 * L) * ffp * sizeof(float)));
+        bpk = BG.wpack.as<float>();
+        prof_begin(g, MLIP_PROF_NODE);
+        const float *Wta = bw->Wt1, *Wtb = bw->Wt1 + ffp;
+        k_pack_ff<<<pb, 256, 0, s>>>(Wta, F, 1, 1.0f, bpk + 0 * ffp);
+        k_pack_ff<<<pb, 256, 0, s>>>(Wtb, F, 1, 1.0f, bpk + 1 * ffp);
+        k_pack_ff<<<pb, 256, 0, s>>>(bw->Wt2, F, 1, 1.0f, bpk + 2 * ffp);
+        k_pack_ff<<<pb, 256, 0, s>>>(Wta, F, 0, 1.0f, bpk + 3 * ffp);
+        k_pack_ff<<<pb, 256, 0, s>>>(Wtb, F, 0, 1.0f, bpk + 4 * ffp);
+        k_pack_ff<<<pb, 256, 0, s>>>(bw->Wt2, F, 0, 1.0f, bpk + 5 * ffp);
+        for (int l = 0; l < L; ++l) {
+            k_pack_ff<<<pb, 256, 0, s>>>(bw->Wb + l * ffp, F, 1, 1.0f, bpk + (6 + l) * ffp);
+            k_pack_ff<<<pb, 256, 0, s>>>(bw->Wb + l * ffp, F, 0, 1.0f, bpk + (6 + L + l) * ffp);
+        }
+        MLIP_HIP(hipGetLastError());
+        if (nbond > 0) {
+            const float *Wtc = bw->Wt1 + 2 * ffp;
+            k_bond_e0<F><<<blocks_for(nbond * F, 256), 256, 0, s>>>(nbond, BG.d.as<float>(), bpb, bw->We0, BG.e0.as<float>());
+            MLIP_HIP(hipGetLastError());
+            MLIP_TRY((rows_gemm<F, OP_PROJ>(g, bpk + 0 * ffp, nbond, BG.e0.as<float>(), BG.P.as<float>())));
+            MLIP_TRY((rows_gemm<F, OP_PROJ>(g, bpk + 1 * ffp, nbond, BG.e0.as<float>(), BG.Q.as<float>())));
+            k_triplet_fwd<F><<<blocks_for(g->N, 4), 256, 0, s>>>(g->N, BG.ptr.as<int64_t>(), BG.rhat.as<float>(),
+                                                                 BG.u.as<float>(), BG.P.as<float>(), BG.Q.as<float>(),
+                                                                 Wtc, BG.S.as<float>());
+            MLIP_HIP(hipGetLastError());
+            MLIP_TRY((rows_gemm<F, OP_PROJ>(g, bpk + 2 * ffp, nbond, BG.S.as<float>(), BG.m.as<float>())));
+            k_bond_e1<F><<<blocks_for(nbond * F, 256), 256, 0, s>>>(nbond, BG.e0.as<float>(), BG.m.as<float>(),
+                                                                    BG.u.as<float>(), BG.e1.as<float>());
+            MLIP_HIP(hipGetLastError());
+            for (int l = 0; l < L; ++l)
+                MLIP_TRY((rows_gemm<F, OP_PROJ>(g, bpk + (6 + l) * ffp, nbond, BG.e1.as<float>(),
+                                                BG.wb.as<float>() + (size_t)l * bstride)));
+        }
+        prof_end(g);
+    }
+
     auto gslice = [&](SlabView &v, int l) { return v.g.as<float>() + (size_t)l * (size_t)v.n_local * F; };
     auto aslice = [&](SlabView &v, int l) { return v.a.as<float>() + (size_t)l * (size_t)v.n_owned * F; };
     auto wslice = [&](SlabView &v, int l) {  // l >= 1
@@ -1467,6 +1812,14 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, int32_t mode, double *ener
             MLIP_TRY((launch_edge<F>(g, eb, false)));
             prof_end(g);
         }
+        if (bw && nbond > 0) {   // bond term of the filters: a_i += sum_b wb_b * g_send(b)
+            prof_begin(g, MLIP_PROF_EDGE_FWD);
+            k_bond_aggregate<F><<<blocks_for(g->N, 4), 256, 0, s>>>(g->N, BG.ptr.as<int64_t>(), BG.sender.as<int32_t>(),
+                                                                    BG.wb.as<float>() + (size_t)l * bstride,
+                                                                    gslice(views[0], l), aslice(views[0], l));
+            MLIP_HIP(hipGetLastError());
+            prof_end(g);
+        }
         prof_begin(g, MLIP_PROF_NODE);
         MLIP_TRY((node_pass<F, OP_UPDATE>(g, views, P, base + pk.Wot, nullptr, nullptr, [&](SlabView &v, NodeArgs &na) {
             na.n_rows = v.n_owned;
@@ -1507,6 +1860,7 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, int32_t mode, double *ener
         if (L > 0 && v.n_ghost > 0)
             MLIP_HIP(hipMemsetAsync(v.abar.as<float>() + (size_t)v.n_owned * F, 0, (size_t)v.n_ghost * rowb, s));
     }
+    if (bw && nbond > 0) MLIP_HIP(hipMemsetAsync(BG.e1bar.p, 0, bstride * sizeof(float), s));
     for (int l = L - 1; l >= 0; --l) {
         const float *base = wp + pk.per_layer * l;
         const bool need_gbar = l > 0;  // dE/dh0 is never used: the embedding does not depend on positions
@@ -1552,6 +1906,16 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, int32_t mode, double *ener
             MLIP_TRY((launch_edge<F>(g, eb, true)));
             prof_end(g);
         }
+        if (bw && nbond > 0) {   // bond term: dE/dwb, its share of gbar, and e1bar += wbbar Wb_l^T
+            prof_begin(g, MLIP_PROF_EDGE_BWD);
+            k_bond_bwd<F><<<blocks_for(g->N, 4), 256, 0, s>>>(
+                g->N, BG.ptr.as<int64_t>(), BG.sender.as<int32_t>(), BG.mirror.as<int32_t>(),
+                BG.wb.as<float>() + (size_t)l * bstride, gslice(views[0], l), views[0].abar.as<float>(),
+                BG.wbbar.as<float>(), need_gbar ? views[0].gbar.as<float>() : nullptr);
+            MLIP_HIP(hipGetLastError());
+            MLIP_TRY((rows_gemm<F, OP_BWD_PROJ>(g, bpk + (6 + L + l) * ffp, nbond, BG.wbbar.as<float>(), BG.e1bar.as<float>())));
+            prof_end(g);
+        }
         if (need_gbar) {
             if (slabs) {
                 prof_begin(g, MLIP_PROF_GHOST);
@@ -1580,6 +1944,29 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, int32_t mode, double *ener
         }
     }
 
+    // ---- reverse of the bond update: e1 = e0 + u SiLU(m), m = S Wt2, S = triplet sum, e0 = bbond(d) We0
+    if (bw && nbond > 0) {
+        prof_begin(g, MLIP_PROF_EDGE_BWD);
+        const float *Wtc = bw->Wt1 + 2 * ffp;
+        k_bond_mbar<F><<<blocks_for(nbond, 4), 256, 0, s>>>(nbond, BG.e1bar.as<float>(), BG.m.as<float>(), BG.u.as<float>(),
+                                                            BG.S.as<float>() /* mbar, S is no longer needed */,
+                                                            BG.ubar.as<float>());
+        MLIP_HIP(hipGetLastError());
+        MLIP_TRY((rows_gemm<F, OP_PROJ>(g, bpk + 5 * ffp, nbond, BG.S.as<float>(), BG.Sbar.as<float>())));
+        k_triplet_bwd<F><<<blocks_for(g->N, 4), 256, 0, s>>>(g->N, BG.ptr.as<int64_t>(), BG.rhat.as<float>(), BG.u.as<float>(),
+                                                             BG.P.as<float>(), BG.Q.as<float>(), Wtc, BG.Sbar.as<float>(),
+                                                             BG.Pbar.as<float>(), BG.Qbar.as<float>(), BG.ubar.as<float>(),
+                                                             BG.rbar.as<float>());
+        MLIP_HIP(hipGetLastError());
+        // e0bar = e1bar + Pbar Wta^T + Qbar Wtb^T, accumulated in place
+        MLIP_TRY((rows_gemm<F, OP_BWD_PROJ>(g, bpk + 3 * ffp, nbond, BG.Pbar.as<float>(), BG.e1bar.as<float>())));
+        MLIP_TRY((rows_gemm<F, OP_BWD_PROJ>(g, bpk + 4 * ffp, nbond, BG.Qbar.as<float>(), BG.e1bar.as<float>())));
+        k_bond_dist_bwd<F><<<blocks_for(nbond, 4), 256, 0, s>>>(nbond, BG.e1bar.as<float>(), bw->We0, BG.d.as<float>(), bpb,
+                                                                BG.ubar.as<float>(), BG.du.as<float>(), BG.dbond.as<float>());
+        MLIP_HIP(hipGetLastError());
+        prof_end(g);
+    }
+
     // ---- forces
     prof_begin(g, MLIP_PROF_FORCE);
     const double *pos = g->pos.as<double>();
@@ -1591,6 +1978,10 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, int32_t mode, double *ener
         } else if (v.n_local > 0) {
             MLIP_HIP(hipMemsetAsync(v.floc.p, 0, (size_t)v.n_local * 3 * sizeof(float), s));
         }
+        if (bw && nbond > 0)
+            k_bond_force<<<blocks_for(g->N, 128), 128, 0, s>>>(g->N, BG.ptr.as<int64_t>(), BG.mirror.as<int32_t>(),
+                                                               BG.dbond.as<float>(), BG.rbar.as<float>(),
+                                                               BG.rhat.as<float>(), BG.d.as<float>(), v.floc.as<float>());
         if (v.n_owned > 0)
             k_store_owned<<<blocks_for(v.n_owned, 256), 256, 0, s>>>(v.n_owned, v.nodes, v.floc.as<float>(),
                                                                      v.eps.as<float>(), forces, atom_energy);
@@ -1611,8 +2002,15 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, int32_t mode, double *ener
 
 int forward_impl(mlip_graph *g, const mlip_weights_t *w, int32_t mode, double *energy, float *forces, float *atom_energy)
 {
-    if (w->F == 32) return forward_t<32>(g, w, mode, energy, forces, atom_energy);
-    return forward_t<64>(g, w, mode, energy, forces, atom_energy);
+    if (w->F == 32) return forward_t<32>(g, w, nullptr, mode, energy, forces, atom_energy);
+    return forward_t<64>(g, w, nullptr, mode, energy, forces, atom_energy);
+}
+
+int forward_bonds_impl(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t *bw, int32_t mode,
+                       double *energy, float *forces, float *atom_energy)
+{
+    if (w->F == 32) return forward_t<32>(g, w, bw, mode, energy, forces, atom_energy);
+    return forward_t<64>(g, w, bw, mode, energy, forces, atom_energy);
 }
 
 }  // namespace mlip

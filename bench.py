@@ -46,7 +46,11 @@ def cpu_baseline(cfg_index, n_cells):
     c = wl.make_config(cfg_index, n=n_cells)
     t0 = time.perf_counter()
     g = og.build_graph(c["positions"], c["cell"], c["r_cut"])
-    om.energy_forces(c["positions"], c["cell"], c["species"], c["weights"], g, c["r_cut"], c["K"], c["p"])
+    if c["three_body"]:
+        from oracle import three_body as tb
+        tb.energy_forces3(c["positions"], c["cell"], c["species"], c["weights"], g, c["r_cut"], c["r_bond"], c["K"], c["p"])
+    else:
+        om.energy_forces(c["positions"], c["cell"], c["species"], c["weights"], g, c["r_cut"], c["K"], c["p"])
     dt = time.perf_counter() - t0
     n = len(c["species"])
     return {"value": n / dt, "unit": "atoms/s", "cores": int(ol.lib().orc_num_threads()), "kind": "oracle",
@@ -77,20 +81,25 @@ def main():
     import workloads as wl
 
     c = wl.make_config(args.config, n=args.cells)
-    P = max(c["n_slabs"], 2)
+    three_body = c["three_body"]   # configs[4]: whole-graph mode (a secondary workload; the default is configs[3])
+    P = 1 if three_body else max(c["n_slabs"], 2)
     torch.cuda.set_device(0)
     pos = torch.as_tensor(c["positions"], device="cuda")
     spec = torch.as_tensor(c["species"], device="cuda")
-    W = M.Weights(c["weights"], c["p"])
+    W = M.Weights({k: c["weights"][k] for k in ("emb", "W1", "W2", "Wm", "Wo", "Wr1", "wr2")}, c["p"])
+    BW = M.BondWeights(c["weights"], c["r_bond"], c["A"]) if three_body else None
     N = pos.shape[0]
     out = (torch.empty(1, dtype=torch.float64, device="cuda"), torch.empty((N, 3), dtype=torch.float32, device="cuda"),
            None)
     g = None
 
-    def step(mode=M.MODE_SLABS):
+    def step(mode=None):
         nonlocal g
         g = M.mlip_build_graph(pos, c["cell"], spec, c["r_cut"], n_slabs=P, graph=g)
-        M.mlip_forward(g, W, mode, out=out, want_atom_energy=False)
+        if three_body:
+            M.mlip_forward_bonds(g, W, BW, M.MODE_WHOLE, out=out, want_atom_energy=False)
+        else:
+            M.mlip_forward(g, W, M.MODE_SLABS if mode is None else mode, out=out, want_atom_energy=False)
 
     for _ in range(args.warmup):
         step()
@@ -151,7 +160,8 @@ def main():
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": c["name"] + f", {N} atoms, {E} directed edges, r_cut 5.0, F={c['F']} L={L} K=8, "
-                               f"graph build + {P}-slab sequential energy+forces", "n_slabs": P},
+                               + (f"three-body variant (bonds within {c['r_bond']}), graph build + whole-graph energy+forces"
+                                  if three_body else f"graph build + {P}-slab sequential energy+forces"), "n_slabs": P},
         "edges_per_s": E / (dt / args.steps),
         "us_per_atom_step": ms_step * 1e3 / N,
         "breakdown_ms_per_step": {k: v[0] / args.steps for k, v in prof.items()},
@@ -163,7 +173,7 @@ def main():
         res["whole_graph_atoms_per_s_excl_graph"] = N / dt_whole_fwd
         res["energy_whole"] = energy_whole
     if not args.no_cpu:
-        res["cpu_baseline"] = cpu_baseline(args.config, args.cpu_cells)
+        res["cpu_baseline"] = cpu_baseline(args.config, min(args.cpu_cells, 24) if three_body else args.cpu_cells)
     print(json.dumps(res))
 
 

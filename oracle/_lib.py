@@ -65,6 +65,9 @@ def lib():
             f = getattr(L, "orc_force_scatter_" + suf)
             f.restype = None
             f.argtypes = [ctypes.c_int64, c_i64p, c_i32p, fp, fp, fp]
+            f = getattr(L, "orc3_basis_rows_" + suf)
+            f.restype = None
+            f.argtypes = [ctypes.c_int64, fp, real, ctypes.c_int, ctypes.c_int, fp, fp]
             f = getattr(L, "orc3_triplet_forward_" + suf)
             f.restype = None
             f.argtypes = [ctypes.c_int64, c_i64p, fp, fp, fp, fp, fp, ctypes.c_int, ctypes.c_int, fp]

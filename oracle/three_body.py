@@ -88,9 +88,7 @@ def _envelope(x, p):
 def _basis_rows(cc, d, rc, K, p):
     b = np.zeros((len(d), K), cc.dt)
     db = np.zeros((len(d), K), cc.dt)
-    f = cc.fn("orc_basis")
-    for i, di in enumerate(d):
-        f(cc.dt(di), cc.dt(rc), K, p, cc.p(b[i]), cc.p(db[i]))
+    cc.fn("orc3_basis_rows")(len(d), cc.p(np.ascontiguousarray(d)), cc.dt(rc), K, p, cc.p(b), cc.p(db))
     return b, db
 
 

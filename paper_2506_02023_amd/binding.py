@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libmlip.so")
 
 MODE_WHOLE, MODE_SLABS = 0, 1
-PROF_GROUPS = ("graph", "node", "edge_fwd", "edge_bwd", "ghost", "force")
+PROF_GROUPS = ("graph", "node", "edge_fwd", "edge_bwd", "ghost", "force", "bond")
 
 
 class MlipError(RuntimeError):

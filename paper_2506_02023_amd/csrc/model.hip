@@ -1710,7 +1710,9 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
     // operand slots: 0 Wta (y = x W), 1 Wtb, 2 Wt2, 3 Wta^T, 4 Wtb^T, 5 Wt2^T, 6 + l Wb_l, 6 + L + l Wb_l^T
     BasisParams bpb = bp;
     if (bw) {
+        prof_begin(g, MLIP_PROF_BOND);
         MLIP_TRY(build_bonds_impl(g, (double)bw->r_bond, w->p));
+        prof_end(g);
         nbond = BG.n;
         bstride = (size_t)std::max<int64_t>(nbond, 1) * F;
         bpb.rc = bw->r_bond;
@@ -1723,7 +1725,7 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
         MLIP_TRY(BG.rbar.ensure((size_t)std::max<int64_t>(nbond, 1) * 3 * sizeof(float)));
         MLIP_TRY(BG.wpack.ensure((size_t)(6 + 2 * L) * ffp * sizeof(float)));
         bpk = BG.wpack.as<float>();
-        prof_begin(g, MLIP_PROF_NODE);
+        prof_begin(g, MLIP_PROF_BOND);
         const float *Wta = bw->Wt1, *Wtb = bw->Wt1 + ffp;
         k_pack_ff<<<pb, 256, 0, s>>>(Wta, F, 1, 1.0f, bpk + 0 * ffp);
         k_pack_ff<<<pb, 256, 0, s>>>(Wtb, F, 1, 1.0f, bpk + 1 * ffp);
@@ -1813,7 +1815,7 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
             prof_end(g);
         }
         if (bw && nbond > 0) {   // bond term of the filters: a_i += sum_b wb_b * g_send(b)
-            prof_begin(g, MLIP_PROF_EDGE_FWD);
+            prof_begin(g, MLIP_PROF_BOND);
             k_bond_aggregate<F><<<blocks_for(g->N, 4), 256, 0, s>>>(g->N, BG.ptr.as<int64_t>(), BG.sender.as<int32_t>(),
                                                                     BG.wb.as<float>() + (size_t)l * bstride,
                                                                     gslice(views[0], l), aslice(views[0], l));
@@ -1907,7 +1909,7 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
             prof_end(g);
         }
         if (bw && nbond > 0) {   // bond term: dE/dwb, its share of gbar, and e1bar += wbbar Wb_l^T
-            prof_begin(g, MLIP_PROF_EDGE_BWD);
+            prof_begin(g, MLIP_PROF_BOND);
             k_bond_bwd<F><<<blocks_for(g->N, 4), 256, 0, s>>>(
                 g->N, BG.ptr.as<int64_t>(), BG.sender.as<int32_t>(), BG.mirror.as<int32_t>(),
                 BG.wb.as<float>() + (size_t)l * bstride, gslice(views[0], l), views[0].abar.as<float>(),
@@ -1946,7 +1948,7 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
 
     // ---- reverse of the bond update: e1 = e0 + u SiLU(m), m = S Wt2, S = triplet sum, e0 = bbond(d) We0
     if (bw && nbond > 0) {
-        prof_begin(g, MLIP_PROF_EDGE_BWD);
+        prof_begin(g, MLIP_PROF_BOND);
         const float *Wtc = bw->Wt1 + 2 * ffp;
         k_bond_mbar<F><<<blocks_for(nbond, 4), 256, 0, s>>>(nbond, BG.e1bar.as<float>(), BG.m.as<float>(), BG.u.as<float>(),
                                                             BG.S.as<float>() /* mbar, S is no longer needed */,

@@ -94,3 +94,12 @@ def test_three_body_rejects_slab_mode():
     BW = M.BondWeights(c["weights"], c["r_bond"], c["A"])
     with pytest.raises(M.MlipError):
         M.mlip_forward_bonds(g, W, BW, M.MODE_SLABS)
+
+
+def test_three_body_config4_full_size():
+    """configs[4] as the benchmark spec gives it: 37^3 fcc cells, 202,612 atoms, about 2.4 M bonds and 26.7 M triplets,
+    against the full fp64 oracle."""
+    c = wl.make_config(4)
+    e, f = _check(c["positions"], c["cell"], c["species"], c, label="configs[4] 37^3")
+    assert len(c["species"]) == 202612
+    assert np.abs(f.sum(0)).max() <= 1e-6 * np.abs(f).max() * np.sqrt(len(f))

@@ -229,3 +229,138 @@ def energy3_reference(positions, cell, species, weights, graph, r_cut, r_bond, K
             a[recv[e]] += w * g[graph.senders[e]]
         h = h + _silu(a @ W["Wo"][l])
     return float((_silu(h @ W["Wr1"]) @ W["wr2"]).sum())
+
+
+def energy_forces3_slabs(positions, cell, species, weights, graph, slabs, slab_of, r_cut, r_bond, K, p):
+    """The three-body variant through the partitioned scheme (slabs from oracle.graph.partition), fp64.
+
+    An edge belongs to the partition of its receiver (Distributing Atom Graphs), so all bonds of an owned centre,
+    and with them all its triplets, lie inside its partition: the bond update needs no transfer.  The atom layers
+    exchange border-node features per layer as in the two-body scheme; in the reverse pass the gradients of ghost
+    rows (features and positions, the latter now also through bond vectors that end on a ghost atom) go back to
+    the owners."""
+    cc = _C(False)
+    dt = cc.dt
+    W = _cast(weights, dt)
+    L = W["W1"].shape[0]
+    F = W["emb"].shape[1]
+    Fb = W["We0"].shape[1]
+    A = W["Wt1"].shape[0] - 2 * Fb
+    Wta, Wtb, Wtc = W["Wt1"][:Fb], W["Wt1"][Fb:2 * Fb], np.ascontiguousarray(W["Wt1"][2 * Fb:])
+    d64, rhat64 = og.geometry(positions, cell, graph)
+    _, _, bond_of_edge_g = bond_graph(positions, cell, graph, r_bond)
+    P_ = len(slabs)
+    n_own = [len(s.owned) for s in slabs]
+    local_in_owner = np.full(graph.N, -1, np.int64)
+    for s in slabs:
+        local_in_owner[s.nodes[: len(s.owned)]] = np.arange(len(s.owned))
+
+    class Loc:
+        pass
+
+    loc = []
+    for i, s in enumerate(slabs):
+        o = Loc()
+        o.d = np.ascontiguousarray(d64[s.edge_ids])
+        o.rhat = np.ascontiguousarray(rhat64[s.edge_ids])
+        is_bond = bond_of_edge_g[s.edge_ids] >= 0
+        o.bond_edge = np.flatnonzero(is_bond).astype(np.int64)          # local edge index of every local bond
+        o.boe = np.full(len(s.edge_ids), -1, np.int64)
+        o.boe[o.bond_edge] = np.arange(len(o.bond_edge))
+        o.bptr = np.concatenate([[0], np.cumsum(is_bond.astype(np.int64))])[s.row_ptr].astype(np.int64)
+        o.db = np.ascontiguousarray(o.d[o.bond_edge])
+        o.rb = np.ascontiguousarray(o.rhat[o.bond_edge])
+        o.bb, o.dbb = _basis_rows(cc, o.db, r_bond, K, p)
+        u, du = _envelope(o.db / r_bond, p)
+        o.u, o.du = np.ascontiguousarray(u), du
+        nb = len(o.bond_edge)
+        o.e0 = o.bb @ W["We0"]
+        o.P = np.ascontiguousarray(o.e0 @ Wta)
+        o.Q = np.ascontiguousarray(o.e0 @ Wtb)
+        o.S = np.zeros((nb, Fb))
+        cc.fn("orc3_triplet_forward")(n_own[i], o.bptr.ctypes.data_as(c_i64p), cc.p(o.rb), cc.p(o.u), cc.p(o.P),
+                                      cc.p(o.Q), cc.p(Wtc), A, Fb, cc.p(o.S))
+        o.m = o.S @ W["Wt2"]
+        o.e1 = o.e0 + o.u[:, None] * _silu(o.m)
+        loc.append(o)
+
+    def edge_args(s):
+        return len(s.row_ptr) - 1, s.row_ptr.ctypes.data_as(c_i64p), s.senders.ctypes.data_as(c_i32p)
+
+    h = [W["emb"][species[s.nodes[: n_own[i]]]].copy() for i, s in enumerate(slabs)]
+    gs = [[None] * P_ for _ in range(L)]
+    as_ = [[None] * P_ for _ in range(L)]
+    wbs = [[None] * P_ for _ in range(L)]
+    for l in range(L):
+        g = []
+        for i, s in enumerate(slabs):
+            gi = np.zeros((len(s.nodes), F))
+            gi[: n_own[i]] = h[i] @ W["Wm"][l]
+            g.append(gi)
+        for i, s in enumerate(slabs):          # border-node transfer: ghost rows <- owner rows
+            gh = s.nodes[n_own[i]:]
+            for q in range(P_):
+                sel = np.flatnonzero(slab_of[gh] == q)
+                g[i][n_own[i] + sel] = g[q][local_in_owner[gh[sel]]]
+        for i, s in enumerate(slabs):
+            o = loc[i]
+            wb = np.ascontiguousarray(o.e1 @ W["Wb"][l])
+            a = np.zeros((n_own[i], F))
+            nrows, rp, sd = edge_args(s)
+            cc.fn("orc3_edge_forward")(nrows, rp, sd, cc.p(o.d), float(r_cut), K, p, F, cc.p(W["W1"][l]), cc.p(W["W2"][l]),
+                                       o.boe.ctypes.data_as(c_i64p), cc.p(wb), cc.p(g[i]), cc.p(a))
+            h[i] = h[i] + _silu(a @ W["Wo"][l])
+            gs[l][i], as_[l][i], wbs[l][i] = g[i], a, wb
+    energy = 0.0
+    atom_energy = np.zeros(graph.N)
+    hbar = []
+    for i, s in enumerate(slabs):
+        pre = h[i] @ W["Wr1"]
+        eps = _silu(pre) @ W["wr2"]
+        atom_energy[s.nodes[: n_own[i]]] = eps
+        energy += float(eps.sum())
+        hbar.append((W["wr2"][None, :] * _dsilu(pre)) @ W["Wr1"].T)
+    dbar = [np.zeros(len(s.edge_ids)) for s in slabs]
+    e1bar = [np.zeros_like(o.e1) for o in loc]
+    for l in reversed(range(L)):
+        gbar = []
+        for i, s in enumerate(slabs):
+            o = loc[i]
+            q_ = as_[l][i] @ W["Wo"][l]
+            abar = np.ascontiguousarray((hbar[i] * _dsilu(q_)) @ W["Wo"][l].T)
+            gb = np.zeros_like(gs[l][i])
+            wbbar = np.zeros((len(o.bond_edge), F))
+            nrows, rp, sd = edge_args(s)
+            cc.fn("orc3_edge_backward")(nrows, len(s.nodes), rp, sd, cc.p(o.d), float(r_cut), K, p, F, cc.p(W["W1"][l]),
+                                        cc.p(W["W2"][l]), o.boe.ctypes.data_as(c_i64p), cc.p(wbs[l][i]), cc.p(gs[l][i]),
+                                        cc.p(abar), cc.p(gb), cc.p(dbar[i]), cc.p(wbbar))
+            gbar.append(gb)
+            e1bar[i] += wbbar @ W["Wb"][l].T
+        for i, s in enumerate(slabs):          # ghost-row gradients -> owners
+            gh = s.nodes[n_own[i]:]
+            for q in range(P_):
+                sel = np.flatnonzero(slab_of[gh] == q)
+                gbar[q][local_in_owner[gh[sel]]] += gbar[i][n_own[i] + sel]
+        for i in range(P_):
+            hbar[i] = hbar[i] + gbar[i][: n_own[i]] @ W["Wm"][l].T
+    gradpos = np.zeros((graph.N, 3))
+    for i, s in enumerate(slabs):
+        o = loc[i]
+        nb = len(o.bond_edge)
+        ubar = (e1bar[i] * _silu(o.m)).sum(1)
+        mbar = e1bar[i] * o.u[:, None] * _dsilu(o.m)
+        Sbar = np.ascontiguousarray(mbar @ W["Wt2"].T)
+        Pbar, Qbar = np.zeros((nb, Fb)), np.zeros((nb, Fb))
+        ubar_t, rbar = np.zeros(nb), np.zeros((nb, 3))
+        cc.fn("orc3_triplet_backward")(n_own[i], o.bptr.ctypes.data_as(c_i64p), cc.p(o.rb), cc.p(o.u), cc.p(o.P), cc.p(o.Q),
+                                       cc.p(Wtc), A, Fb, cc.p(Sbar), cc.p(Pbar), cc.p(Qbar), cc.p(ubar_t), cc.p(rbar))
+        e0bar = e1bar[i] + Pbar @ Wta.T + Qbar @ Wtb.T
+        dbond = ((e0bar @ W["We0"].T) * o.dbb).sum(1) + (ubar + ubar_t) * o.du / r_bond
+        gdelta = dbar[i][:, None] * o.rhat
+        gdelta[o.bond_edge] += dbond[:, None] * o.rb + (rbar - (rbar * o.rb).sum(1, keepdims=True) * o.rb) / o.db[:, None]
+        recv_loc = np.repeat(np.arange(n_own[i]), np.diff(s.row_ptr))
+        gp = np.zeros((len(s.nodes), 3))
+        np.add.at(gp, s.senders, gdelta)       # owned and ghost senders alike
+        np.add.at(gp, recv_loc, -gdelta)
+        np.add.at(gradpos, s.nodes, gp)        # ghost rows go back to the atoms they stand for
+    return dict(energy=energy, forces=-gradpos, atom_energy=atom_energy)

@@ -166,19 +166,22 @@ typedef struct {
 } mlip_bond_weights_t;
 
 /*
- * Energy and forces of the three-body variant.  Arguments as mlip_forward.  The bond list (edges with
- * d <= r_bond, same fp64 predicate as the neighbour list) is built on the first call after a graph build or a
- * change of r_bond, which synchronises the stream once.  Only MLIP_MODE_WHOLE is supported so far; SLABS
- * returns MLIP_ESTATE.
+ * Energy and forces of the three-body variant.  Arguments as mlip_forward, both modes.  The bond list of a
+ * partition (edges of its owned rows with d <= r_bond, same fp64 predicate as the neighbour list; all bonds and
+ * triplets of an owned centre are local to its partition) is built on the first call after a graph build or a
+ * change of r_bond, which synchronises the stream once per partition.
  */
 int mlip_forward_bonds(mlip_graph_t *graph, const mlip_weights_t *weights, const mlip_bond_weights_t *bond_weights,
                        int32_t mode, double *energy, float *forces, float *atom_energy);
 
 /*
- * Bond list of the last mlip_forward_bonds (borrowed DEVICE pointers): bond_edge[n_bonds] = edge index of every
- * bond, ascending; bond_ptr[N + 1] = bonds of centre i are bond_ptr[i] .. bond_ptr[i + 1]; n_bonds HOST.
+ * Bond list of the last mlip_forward_bonds, of the whole graph (p = -1, after a WHOLE call) or of partition p
+ * (after a SLABS call).  Borrowed DEVICE pointers: bond_edge[n_bonds] = index of every bond's edge in that
+ * graph's CSR, ascending; bond_ptr[rows + 1] = bonds of owned row i are bond_ptr[i] .. bond_ptr[i + 1];
+ * n_bonds HOST.
  */
-int mlip_graph_bonds(const mlip_graph_t *graph, const int32_t **bond_edge, const int64_t **bond_ptr, int64_t *n_bonds);
+int mlip_graph_bonds(const mlip_graph_t *graph, int32_t p, const int32_t **bond_edge, const int64_t **bond_ptr,
+                     int64_t *n_bonds);
 
 void mlip_graph_destroy(mlip_graph_t *graph);
 

@@ -55,7 +55,7 @@ def lib():
         L.mlip_build_graph.argtypes = [vp, ctypes.POINTER(dbl), vp, i64, dbl, i32, vp, ctypes.POINTER(vp)]
         L.mlip_forward.argtypes = [vp, ctypes.POINTER(_Weights), i32, vp, vp, vp]
         L.mlip_forward_bonds.argtypes = [vp, ctypes.POINTER(_Weights), ctypes.POINTER(_BondWeights), i32, vp, vp, vp]
-        L.mlip_graph_bonds.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(i64)]
+        L.mlip_graph_bonds.argtypes = [vp, i32, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(i64)]
         L.mlip_graph_destroy.argtypes = [vp]
         L.mlip_graph_destroy.restype = None
         L.mlip_graph_sizes.argtypes = [vp, ctypes.POINTER(i64), ctypes.POINTER(i64), ctypes.POINTER(i32)]
@@ -128,12 +128,13 @@ class Graph:
         _check(lib().mlip_graph_mirror(self._h, ctypes.byref(ptr)))
         return self._host(ptr.value, E, np.int32)
 
-    def bonds(self):
-        """(bond_edge int32 [n_bonds], bond_ptr int64 [N+1]) of the last mlip_forward_bonds."""
-        N, _, _ = self.sizes()
+    def bonds(self, p=-1):
+        """(bond_edge int32 [n_bonds], bond_ptr int64 [rows+1]) of the last mlip_forward_bonds: whole graph (p = -1)
+        or partition p."""
+        rows = self.sizes()[0] if p < 0 else self.slab(p)["n_owned"]
         be, bp, n = ctypes.c_void_p(), ctypes.c_void_p(), ctypes.c_int64()
-        _check(lib().mlip_graph_bonds(self._h, ctypes.byref(be), ctypes.byref(bp), ctypes.byref(n)))
-        return self._host(be.value, n.value, np.int32), self._host(bp.value, N + 1, np.int64)
+        _check(lib().mlip_graph_bonds(self._h, p, ctypes.byref(be), ctypes.byref(bp), ctypes.byref(n)))
+        return self._host(be.value, n.value, np.int32), self._host(bp.value, rows + 1, np.int64)
 
     def slab_of(self):
         N, _, _ = self.sizes()

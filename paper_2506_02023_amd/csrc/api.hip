@@ -181,10 +181,6 @@ int mlip_forward_bonds(mlip_graph_t *g, const mlip_weights_t *w, const mlip_bond
         set_error("unsupported bond model (need A = 8 and 0 < r_bond <= r_cut)");
         return MLIP_EINVAL;
     }
-    if (mode != MLIP_MODE_WHOLE) {
-        set_error("the three-body variant runs in MLIP_MODE_WHOLE only");
-        return MLIP_ESTATE;
-    }
     if (g->prof.on && g->prof.used + 1024 > (size_t)kMaxEvents) (void)prof_collect(g);
     try {
         return forward_bonds_impl(g, w, bw, mode, energy, forces, atom_energy);
@@ -194,13 +190,16 @@ int mlip_forward_bonds(mlip_graph_t *g, const mlip_weights_t *w, const mlip_bond
     }
 }
 
-int mlip_graph_bonds(const mlip_graph_t *g, const int32_t **bond_edge, const int64_t **bond_ptr, int64_t *n_bonds)
+int mlip_graph_bonds(const mlip_graph_t *g, int32_t p, const int32_t **bond_edge, const int64_t **bond_ptr,
+                     int64_t *n_bonds)
 {
     if (!g || g->N <= 0) { set_error("no graph"); return MLIP_ESTATE; }
-    if (g->bonds.r_bond < 0) { set_error("no bond list: call mlip_forward_bonds first"); return MLIP_ESTATE; }
-    if (bond_edge) *bond_edge = g->bonds.edge.as<int32_t>();
-    if (bond_ptr) *bond_ptr = g->bonds.ptr.as<int64_t>();
-    if (n_bonds) *n_bonds = g->bonds.n;
+    if (p < -1 || p >= g->P || (p >= 0 && g->P < 2)) { set_error("partition index out of range"); return MLIP_EINVAL; }
+    const BondGraph &B = (p < 0) ? g->whole.bonds : g->slabs[p].bonds;
+    if (B.r_bond < 0) { set_error("no bond list: call mlip_forward_bonds in that mode first"); return MLIP_ESTATE; }
+    if (bond_edge) *bond_edge = B.edge.as<int32_t>();
+    if (bond_ptr) *bond_ptr = B.ptr.as<int64_t>();
+    if (n_bonds) *n_bonds = B.n;
     return MLIP_OK;
 }
 
@@ -213,15 +212,13 @@ void mlip_graph_destroy(mlip_graph_t *g)
                       &g->small, &g->row_ptr, &g->senders, &g->recv, &g->mirror, &g->shiftp, &g->d, &g->chunk_row, &g->slab_of, &g->needed_by,
                       &g->local_of, &g->local_in_owner, &g->class_cnt, &g->class_off, &g->wpack, &g->energy_part};
     for (DevBuf *b : bufs) b->release();
-    {
-        BondGraph &B = g->bonds;
-        DevBuf *bb[] = {&B.scan, &B.flag, &B.of_edge, &B.edge, &B.ptr, &B.mirror, &B.sender, &B.d, &B.u, &B.du, &B.rhat,
-                        &B.e0, &B.P, &B.Q, &B.S, &B.m, &B.e1, &B.wb, &B.wbbar, &B.e1bar, &B.Sbar, &B.Pbar, &B.Qbar,
-                        &B.ubar, &B.dbond, &B.rbar, &B.wpack};
-        for (DevBuf *b : bb) b->release();
-    }
+    g->bond_wpack.release();
     auto drop_view = [](SlabView &v) {
-        DevBuf *vb[] = {&v.h, &v.hbar, &v.abar, &v.gbar, &v.eps, &v.dsum, &v.floc, &v.g, &v.a, &v.wst};
+        BondGraph &B = v.bonds;
+        DevBuf *vb[] = {&v.h, &v.hbar, &v.abar, &v.gbar, &v.eps, &v.dsum, &v.floc, &v.g, &v.a, &v.wst,
+                        &B.scan, &B.flag, &B.of_edge, &B.edge, &B.ptr, &B.mirror, &B.sender, &B.d, &B.u, &B.du, &B.rhat,
+                        &B.e0, &B.P, &B.Q, &B.S, &B.m, &B.e1, &B.wb, &B.wbbar, &B.e1bar, &B.Sbar, &B.Pbar, &B.Qbar,
+                        &B.ubar, &B.dbond, &B.rbar};
         for (DevBuf *b : vb) b->release();
     };
     drop_view(g->whole);

@@ -628,12 +628,12 @@ int prepare_cell(const double *C, double r_cut, int32_t n_slabs, int64_t N, Cell
 
 // flag[e] = 1 if the edge is a bond: the neighbour list's own fp64 test with the bond cutoff
 __global__ void k_bond_flag(int64_t E, CellParams cp, double rb2, const double *__restrict__ pos,
-                            const int32_t *__restrict__ recv, const int32_t *__restrict__ senders,
-                            const uint32_t *__restrict__ shiftp, int32_t *flag)
+                            const int32_t *__restrict__ nodes, const int32_t *__restrict__ recv,
+                            const int32_t *__restrict__ senders, const uint32_t *__restrict__ shiftp, int32_t *flag)
 {
     const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= E) return;
-    const int64_t i = recv[e], j = senders[e];
+    const int64_t i = nodes ? nodes[recv[e]] : recv[e], j = nodes ? nodes[senders[e]] : senders[e];
     int S0, S1, S2;
     unpack3(shiftp[e], S0, S1, S2);
     const double t0 = (pos[3 * j] - pos[3 * i]) + (((double)S0 * cp.C[0] + (double)S1 * cp.C[3]) + (double)S2 * cp.C[6]);
@@ -645,7 +645,8 @@ __global__ void k_bond_flag(int64_t E, CellParams cp, double rb2, const double *
 
 // bond numbering in edge order; unit vector (fp64, rounded once), length, envelope and its derivative
 __global__ void k_bond_fill(int64_t E, CellParams cp, double r_bond, int p, const double *__restrict__ pos,
-                            const int32_t *__restrict__ recv, const int32_t *__restrict__ senders,
+                            const int32_t *__restrict__ nodes, const int32_t *__restrict__ recv,
+                            const int32_t *__restrict__ senders,
                             const uint32_t *__restrict__ shiftp, const float *__restrict__ d,
                             const int32_t *__restrict__ flag, const int32_t *__restrict__ scan, int32_t *of_edge,
                             int32_t *edge, int32_t *sender, float *bd, float *bu, float *bdu, float *rhat)
@@ -656,8 +657,8 @@ __global__ void k_bond_fill(int64_t E, CellParams cp, double r_bond, int p, cons
     const int32_t b = scan[e];
     of_edge[e] = b;
     edge[b] = (int32_t)e;
-    const int64_t i = recv[e], j = senders[e];
-    sender[b] = (int32_t)j;
+    sender[b] = senders[e];
+    const int64_t i = nodes ? nodes[recv[e]] : recv[e], j = nodes ? nodes[senders[e]] : senders[e];
     int S0, S1, S2;
     unpack3(shiftp[e], S0, S1, S2);
     const double t0 = (pos[3 * j] - pos[3 * i]) + (((double)S0 * cp.C[0] + (double)S1 * cp.C[3]) + (double)S2 * cp.C[6]);
@@ -685,13 +686,15 @@ __global__ void k_bond_ptr(int64_t N, const int64_t *__restrict__ row_ptr, const
     ptr[i] = scan[row_ptr[i]];
 }
 
-// the reverse edge of a bond has the same length, so it is a bond too
-__global__ void k_bond_mirror(int64_t nb, const int32_t *__restrict__ edge, const int32_t *__restrict__ mirror,
+// the reverse edge of a bond has the same length, so it is a bond too - of this partition if it lies in an owned
+// row (edge index below E), of the sender's partition otherwise (-1)
+__global__ void k_bond_mirror(int64_t nb, int64_t E, const int32_t *__restrict__ edge, const int32_t *__restrict__ mirror,
                               const int32_t *__restrict__ of_edge, int32_t *bmirror)
 {
     const int64_t b = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (b >= nb) return;
-    bmirror[b] = of_edge[mirror[edge[b]]];
+    const int32_t m = mirror[edge[b]];
+    bmirror[b] = (m < E) ? of_edge[m] : -1;
 }
 
 }  // namespace
@@ -705,12 +708,12 @@ int unpack_shifts(const mlip_graph *g, int32_t *out)
     return MLIP_OK;
 }
 
-int build_bonds_impl(mlip_graph *g, double r_bond, int p_envelope)
+int build_bonds_impl(mlip_graph *g, SlabView &v, double r_bond, int p_envelope)
 {
-    BondGraph &B = g->bonds;
+    BondGraph &B = v.bonds;
     if (B.r_bond == r_bond) return MLIP_OK;   // same graph (a rebuild resets r_bond), same cutoff
     hipStream_t s = g->stream;
-    const int64_t E = g->E, N = g->N;
+    const int64_t E = v.n_edges_owned, N = v.n_owned;
     const size_t Ecap = (size_t)std::max<int64_t>(E, 1);
     MLIP_TRY(B.flag.ensure(Ecap * 4));
     MLIP_TRY(B.scan.ensure((Ecap + 1) * 4));
@@ -718,9 +721,8 @@ int build_bonds_impl(mlip_graph *g, double r_bond, int p_envelope)
     MLIP_TRY(B.ptr.ensure((size_t)(N + 1) * 8));
     const double *pos = g->pos.as<double>();
     if (E > 0) {
-        k_bond_flag<<<blocks_for(E, 256), 256, 0, s>>>(E, g->cell, r_bond * r_bond, pos, g->recv.as<int32_t>(),
-                                                       g->senders.as<int32_t>(), g->shiftp.as<uint32_t>(),
-                                                       B.flag.as<int32_t>());
+        k_bond_flag<<<blocks_for(E, 256), 256, 0, s>>>(E, g->cell, r_bond * r_bond, pos, v.nodes, v.recv, v.senders,
+                                                       v.shiftp, B.flag.as<int32_t>());
         MLIP_HIP(hipGetLastError());
     }
     MLIP_TRY(scan_i32_to_i32(B.flag.as<int32_t>(), B.scan.as<int32_t>(), E, g->scan_tmp, s));
@@ -738,16 +740,16 @@ int build_bonds_impl(mlip_graph *g, double r_bond, int p_envelope)
     MLIP_TRY(B.rhat.ensure(ncap * 12));
     if (E > 0) {
         k_bond_fill<<<blocks_for(E, 256), 256, 0, s>>>(
-            E, g->cell, r_bond, p_envelope, pos, g->recv.as<int32_t>(), g->senders.as<int32_t>(), g->shiftp.as<uint32_t>(),
-            g->d.as<float>(), B.flag.as<int32_t>(), B.scan.as<int32_t>(), B.of_edge.as<int32_t>(), B.edge.as<int32_t>(),
-            B.sender.as<int32_t>(), B.d.as<float>(), B.u.as<float>(), B.du.as<float>(), B.rhat.as<float>());
+            E, g->cell, r_bond, p_envelope, pos, v.nodes, v.recv, v.senders, v.shiftp, v.d, B.flag.as<int32_t>(),
+            B.scan.as<int32_t>(), B.of_edge.as<int32_t>(), B.edge.as<int32_t>(), B.sender.as<int32_t>(), B.d.as<float>(),
+            B.u.as<float>(), B.du.as<float>(), B.rhat.as<float>());
         MLIP_HIP(hipGetLastError());
     }
-    k_bond_ptr<<<blocks_for(N + 1, 256), 256, 0, s>>>(N, g->row_ptr.as<int64_t>(), B.scan.as<int32_t>(), B.ptr.as<int64_t>());
+    k_bond_ptr<<<blocks_for(N + 1, 256), 256, 0, s>>>(N, v.row_ptr, B.scan.as<int32_t>(), B.ptr.as<int64_t>());
     MLIP_HIP(hipGetLastError());
     if (nb > 0) {
-        k_bond_mirror<<<blocks_for(nb, 256), 256, 0, s>>>(nb, B.edge.as<int32_t>(), g->mirror.as<int32_t>(),
-                                                          B.of_edge.as<int32_t>(), B.mirror.as<int32_t>());
+        k_bond_mirror<<<blocks_for(nb, 256), 256, 0, s>>>(nb, E, B.edge.as<int32_t>(), v.mirror, B.of_edge.as<int32_t>(),
+                                                          B.mirror.as<int32_t>());
         MLIP_HIP(hipGetLastError());
     }
     B.n = nb;
@@ -763,7 +765,8 @@ int build_graph_impl(mlip_graph *g, const double *positions, const double *cell,
     MLIP_TRY(prepare_cell(cell, r_cut, P, N, cp));
     g->cell = cp;
     g->N = 0;  // the handle is invalid until the build completes
-    g->bonds.r_bond = -1.0;
+    g->whole.bonds.r_bond = -1.0;
+    for (SlabView &sv : g->slabs) sv.bonds.r_bond = -1.0;
     g->E = 0;
     const int64_t ncell = (int64_t)cp.nb[0] * cp.nb[1] * cp.nb[2];
     if (!g->pinned) MLIP_HIP(hipHostMalloc(&g->pinned, 4096, hipHostMallocDefault));

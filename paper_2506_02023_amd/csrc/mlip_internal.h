@@ -57,6 +57,26 @@ struct CellParams {
 constexpr int kChunkEdges = MLIP_CHUNK;
 inline int64_t chunks_of(int64_t n_edges) { return n_edges > 0 ? (n_edges + kChunkEdges - 1) / kChunkEdges : 1; }
 
+// Bond graph of the three-body variant for one partition: the edges of its owned rows within the bond cutoff,
+// in edge order (all bonds of an owned centre belong to its partition).
+struct BondGraph {
+    double r_bond = -1.0;   // cutoff the list was built for (< 0: none)
+    int64_t n = 0;          // bonds
+    DevBuf scan;            // i32 [E + 1] exclusive scan of the bond flags (E = edges of the owned rows)
+    DevBuf flag;            // i32 [E]
+    DevBuf of_edge;         // i32 [E]   bond index of an edge, -1 if it is no bond
+    DevBuf edge;            // i32 [n]   edge index of a bond
+    DevBuf ptr;             // i64 [n_owned + 1] bonds of centre i: ptr[i] .. ptr[i + 1]
+    DevBuf mirror;          // i32 [n]   the bond of the reverse edge, -1 if the sender is a ghost row
+    DevBuf sender;          // i32 [n]   sender row (local) of the bond
+    DevBuf d, u, du;        // f32 [n]   length, envelope u(d / r_bond), du/dd
+    DevBuf rhat;            // f32 [n][3] unit vector from the centre to the neighbour's image
+    // model workspace, [n][F] unless noted
+    DevBuf e0, P, Q, S, m, e1, wb /* [L][n][F] */, wbbar, e1bar, Sbar, Pbar, Qbar;
+    DevBuf ubar, dbond;     // f32 [n]
+    DevBuf rbar;            // f32 [n][3]
+};
+
 // One partition as the model kernels see it.  The whole graph is the special
 // case nodes == nullptr (identity), n_owned == n_local == N.
 struct SlabView {
@@ -75,30 +95,11 @@ struct SlabView {
     std::vector<int64_t> markers;          // host, P + 3
     // model workspace (sized in mlip_forward)
     DevBuf h, hbar, abar, gbar, eps, dsum, floc, g, a, wst;  // g and a hold L slices each, wst L - 1
+    BondGraph bonds;
 };
 
 struct SlabStore {  // device arrays owned per slab
     DevBuf nodes, row_ptr, senders, recv, mirror, shiftp, d, chunk_row, ghost_owner, ghost_src, owned_sorted, rowlen;
-};
-
-// Bond graph of the three-body variant (whole graph): the edges within the bond cutoff, in edge order.
-struct BondGraph {
-    double r_bond = -1.0;   // cutoff the list was built for (< 0: none)
-    int64_t n = 0;          // bonds
-    DevBuf scan;            // i32 [E + 1] exclusive scan of the bond flags
-    DevBuf flag;            // i32 [E]
-    DevBuf of_edge;         // i32 [E]   bond index of an edge, -1 if it is no bond
-    DevBuf edge;            // i32 [n]   edge index of a bond
-    DevBuf ptr;             // i64 [N + 1] bonds of centre i: ptr[i] .. ptr[i + 1]
-    DevBuf mirror;          // i32 [n]   the bond of the reverse edge
-    DevBuf sender;          // i32 [n]   sender atom of the bond
-    DevBuf d, u, du;        // f32 [n]   length, envelope u(d / r_bond), du/dd
-    DevBuf rhat;            // f32 [n][3] unit vector from the centre to the neighbour's image
-    // model workspace, [n][F] unless noted
-    DevBuf e0, P, Q, S, m, e1, wb /* [L][n][F] */, wbbar, e1bar, Sbar, Pbar, Qbar;
-    DevBuf ubar, dbond;     // f32 [n]
-    DevBuf rbar;            // f32 [n][3]
-    DevBuf wpack;           // packed weights of the bond part
 };
 
 enum { kMaxSlabs = 64, kMaxEvents = 4096 };
@@ -136,7 +137,7 @@ struct mlip_graph {
     // forward scratch shared by all views
     mlip::DevBuf wpack, energy_part;
     mlip::Profiler prof;
-    mlip::BondGraph bonds;
+    mlip::DevBuf bond_wpack;  // packed weights of the three-body variant's bond part
     void *pinned = nullptr;  // small pinned host staging area
 };
 
@@ -154,8 +155,8 @@ int build_graph_impl(mlip_graph *g, const double *positions, const double *cell,
 int forward_impl(mlip_graph *g, const mlip_weights_t *w, int32_t mode, double *energy, float *forces,
                  float *atom_energy);
 int unpack_shifts(const mlip_graph *g, int32_t *out);
-// bond list of the whole graph for cutoff r_bond (kept until the graph is rebuilt or r_bond changes); synchronises
-int build_bonds_impl(mlip_graph *g, double r_bond, int p_envelope);
+// bond list of one partition for cutoff r_bond (kept until the graph is rebuilt or r_bond changes); synchronises
+int build_bonds_impl(mlip_graph *g, SlabView &v, double r_bond, int p_envelope);
 int forward_bonds_impl(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t *bw, int32_t mode,
                        double *energy, float *forces, float *atom_energy);
 

@@ -1081,7 +1081,7 @@ template <int F>
 __global__ void __launch_bounds__(256)
 k_ghost_gbar(int64_t n_ghost, int64_t n_owned, const int64_t *__restrict__ row_ptr, const int32_t *__restrict__ senders,
              const int32_t *__restrict__ mirror, const float *__restrict__ wstore, const float *__restrict__ abar,
-             float *__restrict__ gbar)
+             const int32_t *__restrict__ bond_of_edge, const float *__restrict__ wb, float *__restrict__ gbar)
 {
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int64_t k = (int64_t)blockIdx.x * 4 + wave;
@@ -1094,11 +1094,14 @@ k_ghost_gbar(int64_t n_ghost, int64_t n_owned, const int64_t *__restrict__ row_p
         const int n = (int)min((int64_t)16, e1 - eb);
         const int64_t el = min(eb + (lane & 15), e1 - 1);
         const int32_t jl = senders[el], ml = mirror[el];
+        const int32_t bl = bond_of_edge ? bond_of_edge[ml] : -1;   // three-body variant: the reverse edge's bond
         float wv[16], av[16];
 #pragma unroll
         for (int k = 0; k < 16; ++k) {
             const int64_t j = __builtin_amdgcn_readlane(jl, k), m = __builtin_amdgcn_readlane(ml, k);
+            const int64_t b = __builtin_amdgcn_readlane(bl, k);
             wv[k] = wstore[m * F + f];
+            if (b >= 0) wv[k] += wb[b * F + f];
             av[k] = abar[j * F + f];
         }
 #pragma unroll
@@ -1106,6 +1109,33 @@ k_ghost_gbar(int64_t n_ghost, int64_t n_owned, const int64_t *__restrict__ row_p
             if (k < n) acc = fmaf(wv[k], av[k], acc);
     }
     if (F == 64 || lane < F) gbar[r * F + f] = acc;
+}
+
+// Three-body variant, ghost rows: a ghost atom i is the sender of bonds (j <- i) held by this partition; each pulls
+// on it with +dE/dDelta.  Gathered over the ghost's sub-row through the reverse edges.
+__global__ void k_bond_force_ghost(int64_t n_ghost, int64_t n_owned, const int64_t *__restrict__ row_ptr,
+                                   const int32_t *__restrict__ mirror, const int32_t *__restrict__ bond_of_edge,
+                                   const float *__restrict__ dbond, const float *__restrict__ rbar,
+                                   const float *__restrict__ rhat, const float *__restrict__ bd, float *floc)
+{
+    const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= n_ghost) return;
+    const int64_t r = n_owned + k;
+    float fx = 0.f, fy = 0.f, fz = 0.f;
+    for (int64_t e = row_ptr[r]; e < row_ptr[r + 1]; ++e) {
+        const int64_t q = bond_of_edge[mirror[e]];
+        if (q < 0) continue;
+        const float x = rhat[3 * q], y = rhat[3 * q + 1], z = rhat[3 * q + 2];
+        const float ax = rbar[3 * q], ay = rbar[3 * q + 1], az = rbar[3 * q + 2];
+        const float dot = fmaf(ax, x, fmaf(ay, y, az * z));
+        const float inv = 1.0f / bd[q];
+        fx -= fmaf(dbond[q], x, (ax - dot * x) * inv);
+        fy -= fmaf(dbond[q], y, (ay - dot * y) * inv);
+        fz -= fmaf(dbond[q], z, (az - dot * z) * inv);
+    }
+    floc[3 * r] += fx;
+    floc[3 * r + 1] += fy;
+    floc[3 * r + 2] += fz;
 }
 
 __global__ void k_ghost_addback(int64_t n_ghost, int64_t n_owned, int F, const int32_t *__restrict__ owner,
@@ -1345,7 +1375,8 @@ k_bond_bwd(int64_t N, const int64_t *__restrict__ bptr, const int32_t *__restric
     for (int64_t b = bptr[i]; b < bptr[i + 1]; ++b) {
         const int64_t j = sender[b];
         if (F == 64 || lane < F) wbbar[b * F + f] = ai * g[j * F + f];
-        if (gbar) acc = fmaf(wb[(int64_t)bmirror[b] * F + f], abar[j * F + f], acc);
+        const int64_t bm = bmirror[b];   // -1: the sender is a ghost row (abar_j = 0 here, its owner adds that term)
+        if (gbar && bm >= 0) acc = fmaf(wb[bm * F + f], abar[j * F + f], acc);
     }
     if (gbar && (F == 64 || lane < F)) gbar[i * F + f] += acc;
 }
@@ -1478,6 +1509,7 @@ __global__ void k_bond_force(int64_t N, const int64_t *__restrict__ bptr, const 
     for (int64_t b = bptr[i]; b < bptr[i + 1]; ++b) {
         for (int side = 0; side < 2; ++side) {
             const int64_t q = side ? (int64_t)bmirror[b] : b;
+            if (q < 0) continue;   // reverse bond held by the sender's partition (it reaches this atom as a ghost there)
             const float x = rhat[3 * q], y = rhat[3 * q + 1], z = rhat[3 * q + 2];
             const float ax = rbar[3 * q], ay = rbar[3 * q + 1], az = rbar[3 * q + 2];
             const float dot = fmaf(ax, x, fmaf(ay, y, az * z));
@@ -1701,32 +1733,48 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
     MLIP_HIP(hipGetLastError());
     prof_end(g);
 
-    // ---- three-body variant: bond list, bond embedding, triplet update, bond terms of the layers' filters
-    BondGraph &BG = g->bonds;
-    int64_t nbond = 0;
-    size_t bstride = 0;          // floats per [n][F] bond array
+    // ---- three-body variant: bond lists, bond embedding, triplet update, bond terms of the layers' filters.
+    // All bonds and triplets of an owned centre are local to its partition, so this part needs no transfer.
     float *bpk = nullptr;        // packed F x F operands of the bond part
     const size_t ffp = (size_t)F * F;
     // operand slots: 0 Wta (y = x W), 1 Wtb, 2 Wt2, 3 Wta^T, 4 Wtb^T, 5 Wt2^T, 6 + l Wb_l, 6 + L + l Wb_l^T
     BasisParams bpb = bp;
+    auto bstride = [&](SlabView &v) { return (size_t)std::max<int64_t>(v.bonds.n, 1) * F; };   // floats per [n][F] array
+    auto wbslice = [&](SlabView &v, int l) { return v.bonds.wb.as<float>() + (size_t)l * bstride(v); };
+    // F x F product over the bonds of every partition: out = X P1 (OP_PROJ) or out += X P1 (OP_BWD_PROJ)
+    auto bond_gemm = [&](auto op, int slot, DevBuf BondGraph::*X, float *(*out)(SlabView &, int), int l) -> int {
+        constexpr int OP = decltype(op)::value;
+        return node_pass<F, OP>(g, views, P, bpk + (size_t)slot * ffp, nullptr, nullptr, [&](SlabView &v, NodeArgs &na) {
+            na.n_rows = v.bonds.n;
+            na.X = (v.bonds.*X).template as<float>();
+            na.Y = out(v, l);
+            na.Z = na.Y;
+        });
+    };
+    using OpProj = std::integral_constant<int, OP_PROJ>;
+    using OpAcc = std::integral_constant<int, OP_BWD_PROJ>;
+    bool any_bonds = false;
     if (bw) {
-        prof_begin(g, MLIP_PROF_BOND);
-        MLIP_TRY(build_bonds_impl(g, (double)bw->r_bond, w->p));
-        prof_end(g);
-        nbond = BG.n;
-        bstride = (size_t)std::max<int64_t>(nbond, 1) * F;
         bpb.rc = bw->r_bond;
         bpb.inv_rc = 1.0f / bw->r_bond;
-        DevBuf *fb[] = {&BG.e0, &BG.P, &BG.Q, &BG.S, &BG.m, &BG.e1, &BG.wbbar, &BG.e1bar, &BG.Sbar, &BG.Pbar, &BG.Qbar};
-        for (DevBuf *b : fb) MLIP_TRY(b->ensure(bstride * sizeof(float)));
-        MLIP_TRY(BG.wb.ensure(bstride * sizeof(float) * (size_t)std::max(L, 1)));
-        MLIP_TRY(BG.ubar.ensure((size_t)std::max<int64_t>(nbond, 1) * sizeof(float)));
-        MLIP_TRY(BG.dbond.ensure((size_t)std::max<int64_t>(nbond, 1) * sizeof(float)));
-        MLIP_TRY(BG.rbar.ensure((size_t)std::max<int64_t>(nbond, 1) * 3 * sizeof(float)));
-        MLIP_TRY(BG.wpack.ensure((size_t)(6 + 2 * L) * ffp * sizeof(float)));
-        bpk = BG.wpack.as<float>();
         prof_begin(g, MLIP_PROF_BOND);
-        const float *Wta = bw->Wt1, *Wtb = bw->Wt1 + ffp;
+        for (int p = 0; p < P; ++p) MLIP_TRY(build_bonds_impl(g, views[p], (double)bw->r_bond, w->p));
+        prof_end(g);
+        for (int p = 0; p < P; ++p) {
+            BondGraph &BG = views[p].bonds;
+            const size_t bs = bstride(views[p]), nb1 = (size_t)std::max<int64_t>(BG.n, 1);
+            DevBuf *fb[] = {&BG.e0, &BG.P, &BG.Q, &BG.S, &BG.m, &BG.e1, &BG.wbbar, &BG.e1bar, &BG.Sbar, &BG.Pbar, &BG.Qbar};
+            for (DevBuf *b : fb) MLIP_TRY(b->ensure(bs * sizeof(float)));
+            MLIP_TRY(BG.wb.ensure(bs * sizeof(float) * (size_t)std::max(L, 1)));
+            MLIP_TRY(BG.ubar.ensure(nb1 * sizeof(float)));
+            MLIP_TRY(BG.dbond.ensure(nb1 * sizeof(float)));
+            MLIP_TRY(BG.rbar.ensure(nb1 * 3 * sizeof(float)));
+            any_bonds = any_bonds || BG.n > 0;
+        }
+        MLIP_TRY(g->bond_wpack.ensure((size_t)(6 + 2 * L) * ffp * sizeof(float)));
+        bpk = g->bond_wpack.as<float>();
+        prof_begin(g, MLIP_PROF_BOND);
+        const float *Wta = bw->Wt1, *Wtb = bw->Wt1 + ffp, *Wtc = bw->Wt1 + 2 * ffp;
         k_pack_ff<<<pb, 256, 0, s>>>(Wta, F, 1, 1.0f, bpk + 0 * ffp);
         k_pack_ff<<<pb, 256, 0, s>>>(Wtb, F, 1, 1.0f, bpk + 1 * ffp);
         k_pack_ff<<<pb, 256, 0, s>>>(bw->Wt2, F, 1, 1.0f, bpk + 2 * ffp);
@@ -1738,24 +1786,34 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
             k_pack_ff<<<pb, 256, 0, s>>>(bw->Wb + l * ffp, F, 0, 1.0f, bpk + (6 + L + l) * ffp);
         }
         MLIP_HIP(hipGetLastError());
-        if (nbond > 0) {
-            const float *Wtc = bw->Wt1 + 2 * ffp;
-            k_bond_e0<F><<<blocks_for(nbond * F, 256), 256, 0, s>>>(nbond, BG.d.as<float>(), bpb, bw->We0, BG.e0.as<float>());
-            MLIP_HIP(hipGetLastError());
-            MLIP_TRY((rows_gemm<F, OP_PROJ>(g, bpk + 0 * ffp, nbond, BG.e0.as<float>(), BG.P.as<float>())));
-            MLIP_TRY((rows_gemm<F, OP_PROJ>(g, bpk + 1 * ffp, nbond, BG.e0.as<float>(), BG.Q.as<float>())));
-            k_triplet_fwd<F><<<blocks_for(g->N, 4), 256, 0, s>>>(g->N, BG.ptr.as<int64_t>(), BG.rhat.as<float>(),
-                                                                 BG.u.as<float>(), BG.P.as<float>(), BG.Q.as<float>(),
-                                                                 Wtc, BG.S.as<float>());
-            MLIP_HIP(hipGetLastError());
-            MLIP_TRY((rows_gemm<F, OP_PROJ>(g, bpk + 2 * ffp, nbond, BG.S.as<float>(), BG.m.as<float>())));
-            k_bond_e1<F><<<blocks_for(nbond * F, 256), 256, 0, s>>>(nbond, BG.e0.as<float>(), BG.m.as<float>(),
-                                                                    BG.u.as<float>(), BG.e1.as<float>());
-            MLIP_HIP(hipGetLastError());
-            for (int l = 0; l < L; ++l)
-                MLIP_TRY((rows_gemm<F, OP_PROJ>(g, bpk + (6 + l) * ffp, nbond, BG.e1.as<float>(),
-                                                BG.wb.as<float>() + (size_t)l * bstride)));
+        for (int p = 0; p < P; ++p) {
+            BondGraph &BG = views[p].bonds;
+            if (BG.n > 0)
+                k_bond_e0<F><<<blocks_for(BG.n * F, 256), 256, 0, s>>>(BG.n, BG.d.as<float>(), bpb, bw->We0, BG.e0.as<float>());
         }
+        MLIP_HIP(hipGetLastError());
+        MLIP_TRY(bond_gemm(OpProj{}, 0, &BondGraph::e0, [](SlabView &v, int) { return v.bonds.P.as<float>(); }, 0));
+        MLIP_TRY(bond_gemm(OpProj{}, 1, &BondGraph::e0, [](SlabView &v, int) { return v.bonds.Q.as<float>(); }, 0));
+        for (int p = 0; p < P; ++p) {
+            SlabView &v = views[p];
+            BondGraph &BG = v.bonds;
+            if (BG.n > 0)
+                k_triplet_fwd<F><<<blocks_for(v.n_owned, 4), 256, 0, s>>>(v.n_owned, BG.ptr.as<int64_t>(), BG.rhat.as<float>(),
+                                                                          BG.u.as<float>(), BG.P.as<float>(),
+                                                                          BG.Q.as<float>(), Wtc, BG.S.as<float>());
+        }
+        MLIP_HIP(hipGetLastError());
+        MLIP_TRY(bond_gemm(OpProj{}, 2, &BondGraph::S, [](SlabView &v, int) { return v.bonds.m.as<float>(); }, 0));
+        for (int p = 0; p < P; ++p) {
+            BondGraph &BG = views[p].bonds;
+            if (BG.n > 0)
+                k_bond_e1<F><<<blocks_for(BG.n * F, 256), 256, 0, s>>>(BG.n, BG.e0.as<float>(), BG.m.as<float>(),
+                                                                       BG.u.as<float>(), BG.e1.as<float>());
+        }
+        MLIP_HIP(hipGetLastError());
+        for (int l = 0; l < L; ++l)
+            MLIP_TRY(bond_gemm(OpProj{}, 6 + l, &BondGraph::e1, [](SlabView &v, int ll) {
+                return v.bonds.wb.as<float>() + (size_t)ll * (size_t)std::max<int64_t>(v.bonds.n, 1) * F; }, l));
         prof_end(g);
     }
 
@@ -1814,11 +1872,15 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
             MLIP_TRY((launch_edge<F>(g, eb, false)));
             prof_end(g);
         }
-        if (bw && nbond > 0) {   // bond term of the filters: a_i += sum_b wb_b * g_send(b)
+        if (any_bonds) {   // bond term of the filters: a_i += sum_b wb_b * g_send(b)
             prof_begin(g, MLIP_PROF_BOND);
-            k_bond_aggregate<F><<<blocks_for(g->N, 4), 256, 0, s>>>(g->N, BG.ptr.as<int64_t>(), BG.sender.as<int32_t>(),
-                                                                    BG.wb.as<float>() + (size_t)l * bstride,
-                                                                    gslice(views[0], l), aslice(views[0], l));
+            for (int p = 0; p < P; ++p) {
+                SlabView &v = views[p];
+                if (v.bonds.n > 0)
+                    k_bond_aggregate<F><<<blocks_for(v.n_owned, 4), 256, 0, s>>>(
+                        v.n_owned, v.bonds.ptr.as<int64_t>(), v.bonds.sender.as<int32_t>(), wbslice(v, l), gslice(v, l),
+                        aslice(v, l));
+            }
             MLIP_HIP(hipGetLastError());
             prof_end(g);
         }
@@ -1862,7 +1924,10 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
         if (L > 0 && v.n_ghost > 0)
             MLIP_HIP(hipMemsetAsync(v.abar.as<float>() + (size_t)v.n_owned * F, 0, (size_t)v.n_ghost * rowb, s));
     }
-    if (bw && nbond > 0) MLIP_HIP(hipMemsetAsync(BG.e1bar.p, 0, bstride * sizeof(float), s));
+    if (any_bonds)
+        for (int p = 0; p < P; ++p)
+            if (views[p].bonds.n > 0)
+                MLIP_HIP(hipMemsetAsync(views[p].bonds.e1bar.p, 0, bstride(views[p]) * sizeof(float), s));
     for (int l = L - 1; l >= 0; --l) {
         const float *base = wp + pk.per_layer * l;
         const bool need_gbar = l > 0;  // dE/dh0 is never used: the embedding does not depend on positions
@@ -1908,14 +1973,18 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
             MLIP_TRY((launch_edge<F>(g, eb, true)));
             prof_end(g);
         }
-        if (bw && nbond > 0) {   // bond term: dE/dwb, its share of gbar, and e1bar += wbbar Wb_l^T
+        if (any_bonds) {   // bond term: dE/dwb, its share of gbar, and e1bar += wbbar Wb_l^T
             prof_begin(g, MLIP_PROF_BOND);
-            k_bond_bwd<F><<<blocks_for(g->N, 4), 256, 0, s>>>(
-                g->N, BG.ptr.as<int64_t>(), BG.sender.as<int32_t>(), BG.mirror.as<int32_t>(),
-                BG.wb.as<float>() + (size_t)l * bstride, gslice(views[0], l), views[0].abar.as<float>(),
-                BG.wbbar.as<float>(), need_gbar ? views[0].gbar.as<float>() : nullptr);
+            for (int p = 0; p < P; ++p) {
+                SlabView &v = views[p];
+                BondGraph &BG = v.bonds;
+                if (BG.n > 0)
+                    k_bond_bwd<F><<<blocks_for(v.n_owned, 4), 256, 0, s>>>(
+                        v.n_owned, BG.ptr.as<int64_t>(), BG.sender.as<int32_t>(), BG.mirror.as<int32_t>(), wbslice(v, l),
+                        gslice(v, l), v.abar.as<float>(), BG.wbbar.as<float>(), need_gbar ? v.gbar.as<float>() : nullptr);
+            }
             MLIP_HIP(hipGetLastError());
-            MLIP_TRY((rows_gemm<F, OP_BWD_PROJ>(g, bpk + (6 + L + l) * ffp, nbond, BG.wbbar.as<float>(), BG.e1bar.as<float>())));
+            MLIP_TRY(bond_gemm(OpAcc{}, 6 + L + l, &BondGraph::wbbar, [](SlabView &v, int) { return v.bonds.e1bar.as<float>(); }, 0));
             prof_end(g);
         }
         if (need_gbar) {
@@ -1928,7 +1997,8 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
                     if (v.n_ghost > 0)
                         k_ghost_gbar<F><<<blocks_for(v.n_ghost, 4), 256, 0, s>>>(
                             v.n_ghost, v.n_owned, v.row_ptr, v.senders, v.mirror, wslice(v, l), v.abar.as<float>(),
-                            v.gbar.as<float>());
+                            (bw && v.bonds.n > 0) ? v.bonds.of_edge.as<int32_t>() : nullptr,
+                            (bw && v.bonds.n > 0) ? wbslice(v, l) : nullptr, v.gbar.as<float>());
                     if (v.n_ghost > 0)
                         k_ghost_addback<<<blocks_for(v.n_ghost * (F / 4), 256), 256, 0, s>>>(
                             v.n_ghost, v.n_owned, F, v.ghost_owner, v.ghost_src, tab, v.gbar.as<float>());
@@ -1947,24 +2017,35 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
     }
 
     // ---- reverse of the bond update: e1 = e0 + u SiLU(m), m = S Wt2, S = triplet sum, e0 = bbond(d) We0
-    if (bw && nbond > 0) {
+    if (any_bonds) {
         prof_begin(g, MLIP_PROF_BOND);
         const float *Wtc = bw->Wt1 + 2 * ffp;
-        k_bond_mbar<F><<<blocks_for(nbond, 4), 256, 0, s>>>(nbond, BG.e1bar.as<float>(), BG.m.as<float>(), BG.u.as<float>(),
-                                                            BG.S.as<float>() /* mbar, S is no longer needed */,
-                                                            BG.ubar.as<float>());
+        for (int p = 0; p < P; ++p) {
+            BondGraph &BG = views[p].bonds;
+            if (BG.n > 0)   // mbar goes where S was: S is no longer needed
+                k_bond_mbar<F><<<blocks_for(BG.n, 4), 256, 0, s>>>(BG.n, BG.e1bar.as<float>(), BG.m.as<float>(), BG.u.as<float>(),
+                                                                   BG.S.as<float>(), BG.ubar.as<float>());
+        }
         MLIP_HIP(hipGetLastError());
-        MLIP_TRY((rows_gemm<F, OP_PROJ>(g, bpk + 5 * ffp, nbond, BG.S.as<float>(), BG.Sbar.as<float>())));
-        k_triplet_bwd<F><<<blocks_for(g->N, 4), 256, 0, s>>>(g->N, BG.ptr.as<int64_t>(), BG.rhat.as<float>(), BG.u.as<float>(),
-                                                             BG.P.as<float>(), BG.Q.as<float>(), Wtc, BG.Sbar.as<float>(),
-                                                             BG.Pbar.as<float>(), BG.Qbar.as<float>(), BG.ubar.as<float>(),
-                                                             BG.rbar.as<float>());
+        MLIP_TRY(bond_gemm(OpProj{}, 5, &BondGraph::S, [](SlabView &v, int) { return v.bonds.Sbar.as<float>(); }, 0));
+        for (int p = 0; p < P; ++p) {
+            SlabView &v = views[p];
+            BondGraph &BG = v.bonds;
+            if (BG.n > 0)
+                k_triplet_bwd<F><<<blocks_for(v.n_owned, 4), 256, 0, s>>>(
+                    v.n_owned, BG.ptr.as<int64_t>(), BG.rhat.as<float>(), BG.u.as<float>(), BG.P.as<float>(), BG.Q.as<float>(),
+                    Wtc, BG.Sbar.as<float>(), BG.Pbar.as<float>(), BG.Qbar.as<float>(), BG.ubar.as<float>(), BG.rbar.as<float>());
+        }
         MLIP_HIP(hipGetLastError());
         // e0bar = e1bar + Pbar Wta^T + Qbar Wtb^T, accumulated in place
-        MLIP_TRY((rows_gemm<F, OP_BWD_PROJ>(g, bpk + 3 * ffp, nbond, BG.Pbar.as<float>(), BG.e1bar.as<float>())));
-        MLIP_TRY((rows_gemm<F, OP_BWD_PROJ>(g, bpk + 4 * ffp, nbond, BG.Qbar.as<float>(), BG.e1bar.as<float>())));
-        k_bond_dist_bwd<F><<<blocks_for(nbond, 4), 256, 0, s>>>(nbond, BG.e1bar.as<float>(), bw->We0, BG.d.as<float>(), bpb,
-                                                                BG.ubar.as<float>(), BG.du.as<float>(), BG.dbond.as<float>());
+        MLIP_TRY(bond_gemm(OpAcc{}, 3, &BondGraph::Pbar, [](SlabView &v, int) { return v.bonds.e1bar.as<float>(); }, 0));
+        MLIP_TRY(bond_gemm(OpAcc{}, 4, &BondGraph::Qbar, [](SlabView &v, int) { return v.bonds.e1bar.as<float>(); }, 0));
+        for (int p = 0; p < P; ++p) {
+            BondGraph &BG = views[p].bonds;
+            if (BG.n > 0)
+                k_bond_dist_bwd<F><<<blocks_for(BG.n, 4), 256, 0, s>>>(BG.n, BG.e1bar.as<float>(), bw->We0, BG.d.as<float>(), bpb,
+                                                                       BG.ubar.as<float>(), BG.du.as<float>(), BG.dbond.as<float>());
+        }
         MLIP_HIP(hipGetLastError());
         prof_end(g);
     }
@@ -1980,10 +2061,16 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
         } else if (v.n_local > 0) {
             MLIP_HIP(hipMemsetAsync(v.floc.p, 0, (size_t)v.n_local * 3 * sizeof(float), s));
         }
-        if (bw && nbond > 0)
-            k_bond_force<<<blocks_for(g->N, 128), 128, 0, s>>>(g->N, BG.ptr.as<int64_t>(), BG.mirror.as<int32_t>(),
-                                                               BG.dbond.as<float>(), BG.rbar.as<float>(),
-                                                               BG.rhat.as<float>(), BG.d.as<float>(), v.floc.as<float>());
+        if (bw && v.bonds.n > 0) {
+            BondGraph &BG = v.bonds;
+            k_bond_force<<<blocks_for(v.n_owned, 128), 128, 0, s>>>(v.n_owned, BG.ptr.as<int64_t>(), BG.mirror.as<int32_t>(),
+                                                                    BG.dbond.as<float>(), BG.rbar.as<float>(),
+                                                                    BG.rhat.as<float>(), BG.d.as<float>(), v.floc.as<float>());
+            if (v.n_ghost > 0)
+                k_bond_force_ghost<<<blocks_for(v.n_ghost, 128), 128, 0, s>>>(
+                    v.n_ghost, v.n_owned, v.row_ptr, v.mirror, BG.of_edge.as<int32_t>(), BG.dbond.as<float>(),
+                    BG.rbar.as<float>(), BG.rhat.as<float>(), BG.d.as<float>(), v.floc.as<float>());
+        }
         if (v.n_owned > 0)
             k_store_owned<<<blocks_for(v.n_owned, 256), 256, 0, s>>>(v.n_owned, v.nodes, v.floc.as<float>(),
                                                                      v.eps.as<float>(), forces, atom_energy);

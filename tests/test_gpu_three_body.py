@@ -1,4 +1,4 @@
-"""GPU parity of the three-body (bond graph) variant against the fp64 oracle (whole-graph mode).
+"""GPU parity of the three-body (bond graph) variant against the fp64 oracle, whole-graph and partitioned.
 
 Bond list and per-centre bond ranges are bit-exact.  The library computes this variant in fp32, so forces are
 held to the fp32 bound (1e-4 max|F|; the benchmark allows 2e-2 max|F| for its bf16 version) and the energy to
@@ -19,13 +19,13 @@ E_RTOL3 = 1e-4
 pytestmark = pytest.mark.gpu
 
 
-def _gpu3(g, c, weights=None):
+def _gpu3(g, c, weights=None, mode=0):
     import torch
     import paper_2506_02023_amd as M
     w = c["weights"] if weights is None else weights
     W = M.Weights({k: w[k] for k in ("emb", "W1", "W2", "Wm", "Wo", "Wr1", "wr2")}, c["p"])
     BW = M.BondWeights(w, c["r_bond"], c["A"])
-    e, f, ae = M.mlip_forward_bonds(g, W, BW, M.MODE_WHOLE)
+    e, f, ae = M.mlip_forward_bonds(g, W, BW, mode)
     torch.cuda.synchronize()
     return float(e.cpu()[0]), f.cpu().numpy().astype(np.float64), ae.cpu().numpy().astype(np.float64)
 
@@ -86,14 +86,43 @@ def test_three_body_without_bonds_is_two_body():
     assert np.array_equal(f2.cpu().numpy().astype(np.float64), f3)
 
 
-def test_three_body_rejects_slab_mode():
-    import paper_2506_02023_amd as M
+def _check_slabs(pos, cell, sp, c, P, label):
+    """SLABS mode: per-partition bond lists bit-exact, energy and forces against the (whole-graph) oracle and
+    against the library's own whole-graph run."""
+    ref_g = og.build_graph(pos, cell, c["r_cut"])
+    ref = tb.energy_forces3(pos, cell, sp, c["weights"], ref_g, c["r_cut"], c["r_bond"], c["K"], c["p"])
+    g = gpu_graph(pos, cell, sp, c["r_cut"], n_slabs=P)
+    es, fs, aes = _gpu3(g, c, mode=1)
+    slab_of, _ = og.slab_assign(pos, cell, P)
+    slabs = og.partition(ref_g, slab_of, P)
+    _, _, bond_of_edge = tb.bond_graph(pos, cell, ref_g, c["r_bond"])
+    for p in range(P):
+        is_bond = bond_of_edge[slabs[p].edge_ids] >= 0
+        be, bp = g.bonds(p)
+        assert np.array_equal(be, np.flatnonzero(is_bond))
+        assert np.array_equal(bp, np.concatenate([[0], np.cumsum(is_bond)])[slabs[p].row_ptr])
+    ew, fw, aew = _gpu3(g, c, mode=0)
+    fmax = np.abs(ref["forces"]).max()
+    de, df = abs(es - ref["energy"]) / abs(ref["energy"]), np.abs(fs - ref["forces"]).max() / fmax
+    print(f"{label}, {P} slabs: dE/E {de:.2e}, dF {df:.2e}; slabs vs whole dE/E {abs(es - ew) / abs(ew):.1e}, "
+          f"dF {np.abs(fs - fw).max() / fmax:.1e}")
+    assert de <= E_RTOL3 and df <= F_RTOL
+    assert abs(es - ew) <= E_RTOL3 * abs(ew) and np.abs(fs - fw).max() <= F_RTOL * fmax
+    assert np.abs(aes - ref["atom_energy"]).max() <= 1e-4 * np.abs(ref["atom_energy"]).max()
+
+
+@pytest.mark.parametrize("P", [2, 3, 8])
+def test_three_body_slabs_fcc(P):
+    c = wl.make_config(4, n=6)
+    _check_slabs(c["positions"], c["cell"], c["species"], c, P, "configs[4] recipe at 6^3")
+
+
+@pytest.mark.parametrize("P", [2, 5])
+def test_three_body_slabs_triclinic(P):
+    """Thin triclinic cell: slabs narrower than the cutoffs, bonds to periodic images across the walls."""
     c = wl.make_config(4, n=3)
-    g = gpu_graph(c["positions"], c["cell"], c["species"], c["r_cut"], n_slabs=2)
-    W = M.Weights({k: c["weights"][k] for k in ("emb", "W1", "W2", "Wm", "Wo", "Wr1", "wr2")}, c["p"])
-    BW = M.BondWeights(c["weights"], c["r_bond"], c["A"])
-    with pytest.raises(M.MlipError):
-        M.mlip_forward_bonds(g, W, BW, M.MODE_SLABS)
+    pos, cell, sp = wl.random_triclinic(40, 11, scale=9.0, spread=1.1)
+    _check_slabs(pos, cell, sp, c, P, "triclinic")
 
 
 def test_three_body_config4_full_size():
@@ -103,3 +132,8 @@ def test_three_body_config4_full_size():
     e, f = _check(c["positions"], c["cell"], c["species"], c, label="configs[4] 37^3")
     assert len(c["species"]) == 202612
     assert np.abs(f.sum(0)).max() <= 1e-6 * np.abs(f).max() * np.sqrt(len(f))
+    # the same system through 8 slabs
+    g = gpu_graph(c["positions"], c["cell"], c["species"], c["r_cut"], n_slabs=8)
+    es, fs, _ = _gpu3(g, c, mode=1)
+    assert abs(es - e) <= E_RTOL3 * abs(e)
+    assert np.abs(fs - f).max() <= F_RTOL * np.abs(f).max()

@@ -76,3 +76,30 @@ def test_zero_layers_and_isolated_atoms():
     g = gpu_graph(pos, cell, np.array([0, 1, 9], np.int32), 5.0)
     with pytest.raises(M.MlipError):
         gpu_energy_forces(g, c["weights"], 6, WHOLE)
+
+
+def test_more_slabs_than_populated_regions():
+    """A cluster at one end of a long cell cut into 8 slabs: most partitions own nothing, some have ghosts only
+    on one side.  Two-body and three-body variants, slabs against whole graph and oracle."""
+    import torch
+    import paper_2506_02023_amd as M
+    from oracle import three_body as tb
+    c4 = wl.make_config(4, n=3)
+    rng = np.random.default_rng(9)
+    pos = np.concatenate([rng.uniform(0.5, 9.5, (40, 3)) * np.array([1.0, 0.6, 0.6]), np.array([[41.0, 3.0, 3.0]])])
+    cell = np.diag([64.0, 7.0, 7.0])
+    sp = rng.integers(0, 4, len(pos)).astype(np.int32)
+    ref_g = og.build_graph(pos, cell, 5.0)
+    ref = om.energy_forces(pos, cell, sp, c4["weights"], ref_g, 5.0, 8, 6)
+    g = gpu_graph(pos, cell, sp, 5.0, n_slabs=8)
+    owned = [g.slab(p)["n_owned"] for p in range(8)]
+    assert owned.count(0) >= 4
+    es, fs, _ = gpu_energy_forces(g, {k: c4["weights"][k] for k in ("emb", "W1", "W2", "Wm", "Wo", "Wr1", "wr2")}, 6, SLABS)
+    assert_energy_forces(es, fs, ref, "sparse slabs")
+    ref3 = tb.energy_forces3(pos, cell, sp, c4["weights"], ref_g, 5.0, 3.0, 8, 6)
+    W = M.Weights({k: c4["weights"][k] for k in ("emb", "W1", "W2", "Wm", "Wo", "Wr1", "wr2")}, 6)
+    BW = M.BondWeights(c4["weights"], 3.0, 8)
+    e3, f3, _ = M.mlip_forward_bonds(g, W, BW, M.MODE_SLABS)
+    torch.cuda.synchronize()
+    assert abs(float(e3.cpu()[0]) - ref3["energy"]) <= 1e-4 * abs(ref3["energy"])
+    assert np.abs(f3.cpu().numpy() - ref3["forces"]).max() <= 1e-4 * np.abs(ref3["forces"]).max()

@@ -47,7 +47,13 @@ typedef enum {
 } mlip_status;
 
 enum { MLIP_MODE_WHOLE = 0, MLIP_MODE_SLABS = 1 };
-enum { MLIP_PRECISION_FP32 = 0 };
+/*
+ * MLIP_PRECISION_FP32: everything from the basis on in fp32 (fp32 MFMA).
+ * MLIP_PRECISION_BF16: the F x F products of the filter MLP (forward w = SiLU(t) W2, reverse sbar = wbar W2^T)
+ *   take bf16 operands with fp32 accumulation (benchmark configuration 4: "edge MLPs in bf16 with fp32
+ *   accumulation"); everything else stays fp32.  Forces then agree with the fp64 result to about 1e-3 max|F|.
+ */
+enum { MLIP_PRECISION_FP32 = 0, MLIP_PRECISION_BF16 = 1 };
 
 typedef struct mlip_graph mlip_graph_t;
 

@@ -199,13 +199,14 @@ def mlip_build_graph(positions, cell, species, r_cut, n_slabs=1, graph=None):
 class Weights:
     """Device copies of the model weights plus the POD struct the library takes."""
 
-    def __init__(self, weights, p, K=8, device="cuda"):
-        self.t = {k: torch.as_tensor(np.ascontiguousarray(v, np.float32)).to(device).contiguous()
-                  for k, v in weights.items()}
+    def __init__(self, weights, p, K=8, device="cuda", precision=0):
+        """precision: 0 = fp32, 1 = bf16 operands for the filter MLP's F x F products (fp32 accumulation)."""
+        self.t = {k: torch.as_tensor(np.ascontiguousarray(weights[k], np.float32)).to(device).contiguous()
+                  for k in ("emb", "W1", "W2", "Wm", "Wo", "Wr1", "wr2")}
         S, F = self.t["emb"].shape
         L = self.t["W1"].shape[0]
         self.F, self.L = F, L
-        self.c = _Weights(S, F, L, K, p, 0, *[self.t[k].data_ptr() for k in
+        self.c = _Weights(S, F, L, K, p, int(precision), *[self.t[k].data_ptr() for k in
                                                ("emb", "W1", "W2", "Wm", "Wo", "Wr1", "wr2")])
 
 

@@ -40,6 +40,9 @@ namespace {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kBufferFlags = 0x00020000;  // raw 32-bit buffer descriptor word 3 on gfx9-family targets
 constexpr float kPi = 3.14159265358979323846f;
@@ -127,6 +130,37 @@ __global__ void k_pack_w1(const float *__restrict__ W1, int F, float scale, floa
     if (idx >= NB * 4 * 64) return;
     const int lane = idx & 63, s = (idx >> 6) & 3, bo = idx >> 8;
     out[idx] = scale * W1[(2 * s + (lane >> 5)) * F + 32 * bo + (lane & 31)];
+}
+
+// bf16 form of an F x F operand for v_mfma_f32_32x32x16_bf16 (the bf16 precision mode: the W2 products of the
+// filter MLP run on the bf16 matrix pipeline with fp32 accumulation, at 1/16 of the fp32 MFMA time).
+// Index (((bo * NB + bi) * 2 + q) * 64 + lane) * 8 + t  ->  M[32 bo + lane % 32][32 bi + 8 (r / 4) + 4 (lane / 32) + r % 4],
+// r = 8 q + t: element t of lane-half h of MFMA (bi, q) pairs with accumulator register r of a chained product
+// (or with the same feature of an item-major LDS row).
+__global__ void k_pack_ff_bf16(const float *__restrict__ W, int F, int trans, float scale, __bf16 *__restrict__ out)
+{
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= F * F) return;
+    const int NB = F / 32;
+    const int t = idx & 7, lane = (idx >> 3) & 63, q = (idx >> 9) & 1, bb = idx >> 10;
+    const int bi = bb % NB, bo = bb / NB;
+    const int r = 8 * q + t;
+    const int o = 32 * bo + (lane & 31);
+    const int k = 32 * bi + 8 * (r / 4) + 4 * (lane >> 5) + (r & 3);
+    out[idx] = (__bf16)(scale * (trans ? W[k * F + o] : W[o * F + k]));
+}
+
+__device__ inline bf16x8 to_bf16x8(const float (&v)[8])
+{
+    bf16x8 o;
+#pragma unroll
+    for (int i = 0; i < 8; i += 2) {
+        const f32x2 p = {v[i], v[i + 1]};
+        const bf16x2 h = __builtin_convertvector(p, bf16x2);   // round to nearest even, two per instruction
+        o[i] = h[0];
+        o[i + 1] = h[1];
+    }
+    return o;
 }
 
 template <int F> struct Dims {
@@ -279,6 +313,56 @@ __device__ inline void gemm_rl(const float *__restrict__ Ap, const f32x16 (&in)[
 #pragma unroll
         for (int bo = 0; bo < NB; ++bo) av[bo] = an[bo];
     }
+}
+
+// gemm_rl in bf16: weights as a bf16 pack in LDS, the chained B operand rounded to bf16, fp32 accumulation
+template <int F>
+__device__ inline void gemm_rl_bf16(const __bf16 *__restrict__ Ap, const f32x16 (&in)[Dims<F>::NB],
+                                    f32x16 (&out)[Dims<F>::NB], int lane)
+{
+    constexpr int NB = Dims<F>::NB;
+    const bf16x8 *A = reinterpret_cast<const bf16x8 *>(Ap) + lane;
+#pragma unroll
+    for (int bo = 0; bo < NB; ++bo)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) out[bo][r] = 0.f;
+#pragma unroll
+    for (int bi = 0; bi < NB; ++bi)
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            float v[8];
+#pragma unroll
+            for (int t = 0; t < 8; ++t) v[t] = in[bi][8 * q + t];
+            const bf16x8 b = to_bf16x8(v);
+#pragma unroll
+            for (int bo = 0; bo < NB; ++bo)
+                out[bo] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[((bo * NB + bi) * 2 + q) * 64], b, out[bo], 0, 0, 0);
+        }
+}
+
+// the same with the B operand taken from an item-major LDS row of this lane's item (fp32, rounded here)
+template <int F>
+__device__ inline void gemm_row_bf16(const __bf16 *__restrict__ Ap, const float *row, f32x16 (&out)[Dims<F>::NB], int lane)
+{
+    constexpr int NB = Dims<F>::NB;
+    const int h = lane >> 5;
+    const bf16x8 *A = reinterpret_cast<const bf16x8 *>(Ap) + lane;
+#pragma unroll
+    for (int bo = 0; bo < NB; ++bo)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) out[bo][r] = 0.f;
+#pragma unroll
+    for (int bi = 0; bi < NB; ++bi)
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const f32x4 lo4 = *reinterpret_cast<const f32x4 *>(row + 32 * bi + 16 * q + 4 * h);
+            const f32x4 hi4 = *reinterpret_cast<const f32x4 *>(row + 32 * bi + 16 * q + 8 + 4 * h);
+            const float v[8] = {lo4[0], lo4[1], lo4[2], lo4[3], hi4[0], hi4[1], hi4[2], hi4[3]};
+            const bf16x8 b = to_bf16x8(v);
+#pragma unroll
+            for (int bo = 0; bo < NB; ++bo)
+                out[bo] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[((bo * NB + bi) * 2 + q) * 64], b, out[bo], 0, 0, 0);
+        }
 }
 
 template <int F> struct RegPack1 {
@@ -477,14 +561,15 @@ __device__ inline uint32_t row_ends(int32_t rk, int32_t rn_first, bool valid, in
     return (uint32_t)__ballot(valid && rnext != rk);
 }
 
-template <int F>
+// BF16: the W2 product runs on the bf16 matrix pipeline (A2t is then a bf16 pack)
+template <int F, bool BF16>
 __global__ void __launch_bounds__(256, 3) k_edge_fwd(EdgeBatch B)
 {
     using D = Dims<F>;
     extern __shared__ float lds[];
     float *A2t = lds;
     float *tiles = A2t + D::PACKF;
-    for (int i = threadIdx.x; i < D::PACKF; i += 256) A2t[i] = B.c.A2t[i];
+    for (int i = threadIdx.x; i < (BF16 ? D::PACKF / 2 : D::PACKF); i += 256) A2t[i] = B.c.A2t[i];
     __syncthreads();
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int c32 = lane & 31;
@@ -554,7 +639,10 @@ __global__ void __launch_bounds__(256, 3) k_edge_fwd(EdgeBatch B)
         for (int bb = 0; bb < D::NB; ++bb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) t[bb][r] = t[bb][r] * sigmoid_scaled(t[bb][r]);
-        gemm_rl<F>(A2t, t, w, lane);
+        if (BF16)
+            gemm_rl_bf16<F>(reinterpret_cast<const __bf16 *>(A2t), t, w, lane);
+        else
+            gemm_rl<F>(A2t, t, w, lane);
         regs_to_tile<F>(w, tile, lane);
         wave_lds_fence();
         __builtin_amdgcn_sched_barrier(0);  // keep the use of the prefetched receiver after the MFMA chain
@@ -649,7 +737,7 @@ __device__ inline void gemm_queue(const float *__restrict__ Ap, const float *row
     }
 }
 
-template <int F>
+template <int F, bool BF16>
 __global__ void __launch_bounds__(256, 2) k_edge_bwd(EdgeBatch B)
 {
     using D = Dims<F>;
@@ -659,7 +747,7 @@ __global__ void __launch_bounds__(256, 2) k_edge_bwd(EdgeBatch B)
     float *A2n = lds;
     float *A1l = A2n + D::PACKF;
     float *queues = A1l + D::PACK1;
-    for (int i = threadIdx.x; i < D::PACKF; i += 256) A2n[i] = B.c.A2n[i];
+    for (int i = threadIdx.x; i < (BF16 ? D::PACKF / 2 : D::PACKF); i += 256) A2n[i] = B.c.A2n[i];
     for (int i = threadIdx.x; i < D::PACK1; i += 256) A1l[i] = B.c.A1[i];
     __syncthreads();
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
@@ -831,7 +919,10 @@ __global__ void __launch_bounds__(256, 2) k_edge_bwd(EdgeBatch B)
             }
         }
         f32x16 sb[D::NB];
-        gemm_queue<F>(A2n, Q + slot * FS, sb, lane);   // sbar[k] = sum_f W2[k][f] wsym[f]
+        if (BF16)   // sbar[k] = sum_f W2[k][f] wsym[f]
+            gemm_row_bf16<F>(reinterpret_cast<const __bf16 *>(A2n), Q + slot * FS, sb, lane);
+        else
+            gemm_queue<F>(A2n, Q + slot * FS, sb, lane);
         float part = 0.f;
 #pragma unroll
         for (int bb = 0; bb < D::NB; ++bb)
@@ -1598,23 +1689,23 @@ int node_pass(mlip_graph *g, SlabView *views, int P, const float *P1, const floa
     return MLIP_OK;
 }
 
-template <int F> int launch_edge(mlip_graph *g, EdgeBatch &b, bool backward)
+template <int F, bool BF16> int launch_edge(mlip_graph *g, EdgeBatch &b, bool backward)
 {
     const size_t lds = backward ? Lds<F>::edge_bwd : Lds<F>::edge_fwd;
     // resident blocks per compute unit, queried once per kernel
     static int occ_f = 0, occ_b = 0, n_cu = 0;
     int &occ = backward ? occ_b : occ_f;
     if (occ == 0) {
-        const void *fn = backward ? reinterpret_cast<const void *>(&k_edge_bwd<F>)
-                                  : reinterpret_cast<const void *>(&k_edge_fwd<F>);
+        const void *fn = backward ? reinterpret_cast<const void *>(&k_edge_bwd<F, BF16>)
+                                  : reinterpret_cast<const void *>(&k_edge_fwd<F, BF16>);
         MLIP_HIP(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         int dev = 0, o = 0;
         MLIP_HIP(hipGetDevice(&dev));
         MLIP_HIP(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
         if (backward)
-            MLIP_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&o, k_edge_bwd<F>, 256, lds));
+            MLIP_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&o, k_edge_bwd<F, BF16>, 256, lds));
         else
-            MLIP_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&o, k_edge_fwd<F>, 256, lds));
+            MLIP_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&o, k_edge_fwd<F, BF16>, 256, lds));
         if (o < 1 || n_cu < 8) {
             set_error("edge kernel does not fit the device (occupancy %d, %d compute units)", o, n_cu);
             return MLIP_EHIP;
@@ -1631,34 +1722,21 @@ template <int F> int launch_edge(mlip_graph *g, EdgeBatch &b, bool backward)
     const int64_t needed = ((items + 7) / 8 + 3) / 4;
     const unsigned blocks = (unsigned)(8 * std::max<int64_t>(1, std::min(resident, needed)));
     if (backward)
-        k_edge_bwd<F><<<blocks, 256, lds, g->stream>>>(b);
+        k_edge_bwd<F, BF16><<<blocks, 256, lds, g->stream>>>(b);
     else
-        k_edge_fwd<F><<<blocks, 256, lds, g->stream>>>(b);
+        k_edge_fwd<F, BF16><<<blocks, 256, lds, g->stream>>>(b);
     MLIP_HIP(hipGetLastError());
     return MLIP_OK;
 }
 
-// y = x W over n_rows rows with a packed F x F operand: Y = X P1 (OP_PROJ) or Z += X P1 (OP_BWD_PROJ)
-template <int F, int OP>
-int rows_gemm(mlip_graph *g, const float *P1, int64_t n_rows, const float *X, float *out)
-{
-    NodeBatch nb{};
-    nb.n = 1;
-    nb.P1 = P1;
-    nb.s[0].n_rows = n_rows;
-    nb.s[0].X = X;
-    nb.s[0].Y = out;
-    nb.s[0].Z = out;
-    return launch_node<F, OP>(g, nb);
-}
-
-// bw != nullptr: the three-body variant (whole graph only)
+// bw != nullptr: the three-body variant
 template <int F>
 int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t *bw, int32_t mode, double *energy,
               float *forces, float *atom_energy)
 {
     hipStream_t s = g->stream;
     const int L = w->L;
+    const bool bf16 = (w->precision == MLIP_PRECISION_BF16);
     const bool slabs = (mode == MLIP_MODE_SLABS);
     const int P = slabs ? g->P : 1;
     SlabView *views = slabs ? g->slabs.data() : &g->whole;
@@ -1712,8 +1790,13 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
         const size_t ff = (size_t)F * F;
         k_pack_w1<<<blocks_for((F / 32) * 256, 256), 256, 0, s>>>(w->W1 + (size_t)l * 8 * F, F, 1.0f, base + pk.A1);
         k_pack_w1<<<blocks_for((F / 32) * 256, 256), 256, 0, s>>>(w->W1 + (size_t)l * 8 * F, F, kSiluScale, base + pk.A1s);
-        k_pack_ff<<<pb, 256, 0, s>>>(w->W2 + l * ff, F, 1, kSiluScaleInv, base + pk.W2t);
-        k_pack_ff<<<pb, 256, 0, s>>>(w->W2 + l * ff, F, 0, 1.0f, base + pk.W2n);
+        if (bf16) {   // the two W2 operands as bf16 packs (half of their slots)
+            k_pack_ff_bf16<<<pb, 256, 0, s>>>(w->W2 + l * ff, F, 1, kSiluScaleInv, reinterpret_cast<__bf16 *>(base + pk.W2t));
+            k_pack_ff_bf16<<<pb, 256, 0, s>>>(w->W2 + l * ff, F, 0, 1.0f, reinterpret_cast<__bf16 *>(base + pk.W2n));
+        } else {
+            k_pack_ff<<<pb, 256, 0, s>>>(w->W2 + l * ff, F, 1, kSiluScaleInv, base + pk.W2t);
+            k_pack_ff<<<pb, 256, 0, s>>>(w->W2 + l * ff, F, 0, 1.0f, base + pk.W2n);
+        }
         k_pack_ff<<<pb, 256, 0, s>>>(w->Wm + l * ff, F, 1, 1.0f, base + pk.Wmt);
         k_pack_ff<<<pb, 256, 0, s>>>(w->Wm + l * ff, F, 0, 1.0f, base + pk.Wmn);
         k_pack_ff<<<pb, 256, 0, s>>>(w->Wo + l * ff, F, 1, 1.0f, base + pk.Wot);
@@ -1869,7 +1952,7 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
                 ea.wstore = (l >= 1) ? wslice(v, l) : nullptr;
             }
             prof_begin(g, MLIP_PROF_EDGE_FWD);
-            MLIP_TRY((launch_edge<F>(g, eb, false)));
+            MLIP_TRY(bf16 ? (launch_edge<F, true>(g, eb, false)) : (launch_edge<F, false>(g, eb, false)));
             prof_end(g);
         }
         if (any_bonds) {   // bond term of the filters: a_i += sum_b wb_b * g_send(b)
@@ -1970,7 +2053,7 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
                 ea.n_stored = need_gbar ? v.n_edges_owned : 0;
             }
             prof_begin(g, MLIP_PROF_EDGE_BWD);
-            MLIP_TRY((launch_edge<F>(g, eb, true)));
+            MLIP_TRY(bf16 ? (launch_edge<F, true>(g, eb, true)) : (launch_edge<F, false>(g, eb, true)));
             prof_end(g);
         }
         if (any_bonds) {   // bond term: dE/dwb, its share of gbar, and e1bar += wbbar Wb_l^T

@@ -68,8 +68,9 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--cpu-cells", type=int, default=40)
     ap.add_argument("--whole", action="store_true", help="also time whole-graph mode on the same graph (extra fields)")
-    ap.add_argument("--precision", choices=("f32", "bf16"), default="f32",
-                    help="bf16: the F x F products of the filter MLP take bf16 operands (fp32 accumulation)")
+    ap.add_argument("--precision", choices=("f32", "f32split", "bf16"), default="f32",
+                    help="f32split: the F x F products of the filter MLP as split-fp16 MFMA triples (fp32-grade results); "
+                         "bf16: those products with bf16 operands (fp32 accumulation)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (slabs are processed in sequence on one device); "
@@ -88,7 +89,7 @@ def main():
     torch.cuda.set_device(0)
     pos = torch.as_tensor(c["positions"], device="cuda")
     spec = torch.as_tensor(c["species"], device="cuda")
-    W = M.Weights(c["weights"], c["p"], precision=1 if args.precision == "bf16" else 0)
+    W = M.Weights(c["weights"], c["p"], precision={"f32": 0, "bf16": 1, "f32split": 2}[args.precision])
     BW = M.BondWeights(c["weights"], c["r_bond"], c["A"]) if three_body else None
     N = pos.shape[0]
     out = (torch.empty(1, dtype=torch.float64, device="cuda"), torch.empty((N, 3), dtype=torch.float32, device="cuda"),
@@ -133,6 +134,22 @@ def main():
         dt_whole_fwd = (time.perf_counter() - t1) / args.steps
         energy_whole = float(out[0].cpu()[0])
 
+    # the same step with the W2 products as split-fp16 triples (same bounds as fp32), for the record
+    split_ms = None
+    if args.precision == "f32" and not three_body:
+        W2 = M.Weights(c["weights"], c["p"], precision=2)
+        Wsave, W = W, W2
+        for _ in range(2):
+            step()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        split_ms = (time.perf_counter() - t1) / args.steps * 1e3
+        energy_split = float(out[0].cpu()[0])
+        W = Wsave
+
     ms_step = dt / args.steps * 1e3
     L = c["L"]
     default_workload = args.config == 3 and args.cells is None
@@ -148,9 +165,9 @@ def main():
              "ms_per_step": ms / args.steps}
         if executed is not None:
             r["executed_tflops"] = ach * executed / flops_edge
-        if args.precision == "bf16":
-            r["note"] = ("bf16 mode: the W2 products run on the bf16 matrix pipeline; frac is the algorithmic rate against "
-                         "the fp32 MFMA peak of the default mode, not a utilisation of the units used")
+        if args.precision != "f32":
+            r["note"] = ("the W2 products run on the 16-bit matrix pipeline; frac is the algorithmic rate against the fp32 "
+                         "MFMA peak of the default mode, not a utilisation of the units used")
         return r
 
     F = c["F"]
@@ -164,7 +181,8 @@ def main():
         "metric": "atoms/s (energy+forces)", "value": N / (dt / args.steps), "unit": "atoms/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32" if args.precision == "f32" else "f32 with bf16 operands in the filter MLP's F x F products",
+        "dtype": {"f32": "f32", "bf16": "f32 with bf16 operands in the filter MLP's F x F products",
+                  "f32split": "f32, the filter MLP's F x F products as split-fp16 MFMA triples"}[args.precision],
         "data": "synthetic",
         "config": {"workload": c["name"] + f", {N} atoms, {E} directed edges, r_cut 5.0, F={c['F']} L={L} K=8, "
                                + (f"three-body variant (bonds within {c['r_bond']}), graph build + whole-graph energy+forces"
@@ -175,6 +193,11 @@ def main():
         "energy": energy, "net_force_max_component": fsum,
         "roofline": roof, "roofline_edge_fwd": roof_fwd, "roofline_edge_bwd": roof_bwd,
     }
+    if split_ms is not None:
+        res["split_fp16_products"] = {"ms_per_step": split_ms, "value": N / (split_ms * 1e-3), "unit": "atoms/s",
+                                      "energy": energy_split,
+                                      "note": "MLIP_PRECISION_FP32_SPLIT: same step, W2 products as three fp16 MFMA products "
+                                              "of split operands; held to the fp32 bounds by the parity tests"}
     if args.whole:
         res["whole_graph_forward_ms"] = dt_whole_fwd * 1e3
         res["whole_graph_atoms_per_s_excl_graph"] = N / dt_whole_fwd

@@ -15,6 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libmlip.so")
 
 MODE_WHOLE, MODE_SLABS = 0, 1
+PRECISION_FP32, PRECISION_BF16, PRECISION_FP32_SPLIT = 0, 1, 2
 PROF_GROUPS = ("graph", "node", "edge_fwd", "edge_bwd", "ghost", "force", "bond")
 
 
@@ -200,7 +201,8 @@ class Weights:
     """Device copies of the model weights plus the POD struct the library takes."""
 
     def __init__(self, weights, p, K=8, device="cuda", precision=0):
-        """precision: 0 = fp32, 1 = bf16 operands for the filter MLP's F x F products (fp32 accumulation)."""
+        """precision: 0 = fp32, 1 = bf16 operands for the filter MLP's F x F products (fp32 accumulation),
+        2 = those products as split-fp16 triples (fp32-grade results)."""
         self.t = {k: torch.as_tensor(np.ascontiguousarray(weights[k], np.float32)).to(device).contiguous()
                   for k in ("emb", "W1", "W2", "Wm", "Wo", "Wr1", "wr2")}
         S, F = self.t["emb"].shape

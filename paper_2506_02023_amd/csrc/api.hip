@@ -140,8 +140,8 @@ static int check_forward_args(mlip_graph_t *g, const mlip_weights_t *w, int32_t 
         return MLIP_EINVAL;
     }
     if (!(w->F == 32 || w->F == 64) || w->K != 8 || w->L < 0 || w->L > 8 || w->p < 2 || w->p > 64 ||
-        w->n_species < 1 || (w->precision != MLIP_PRECISION_FP32 && w->precision != MLIP_PRECISION_BF16)) {
-        set_error("unsupported model dimensions (need F in {32,64}, K = 8, 0 <= L <= 8, 2 <= p <= 64, precision fp32 or bf16)");
+        w->n_species < 1 || (w->precision < MLIP_PRECISION_FP32 || w->precision > MLIP_PRECISION_FP32_SPLIT)) {
+        set_error("unsupported model dimensions (need F in {32,64}, K = 8, 0 <= L <= 8, 2 <= p <= 64, precision 0..2)");
         return MLIP_EINVAL;
     }
     if (g->species_min < 0 || g->species_max >= w->n_species) {

@@ -43,6 +43,8 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kBufferFlags = 0x00020000;  // raw 32-bit buffer descriptor word 3 on gfx9-family targets
 constexpr float kPi = 3.14159265358979323846f;
@@ -148,6 +150,41 @@ __global__ void k_pack_ff_bf16(const float *__restrict__ W, int F, int trans, fl
     const int o = 32 * bo + (lane & 31);
     const int k = 32 * bi + 8 * (r / 4) + 4 * (lane >> 5) + (r & 3);
     out[idx] = (__bf16)(scale * (trans ? W[k * F + o] : W[o * F + k]));
+}
+
+// Split-fp16 form of the same operand: every fp32 value v is kept as hi + lo, hi = fp16(v), lo = fp16(v - hi)
+// (22 significant bits together); a product of two such values is taken as hi hi + hi lo + lo hi with fp32
+// accumulation.  What is dropped (lo lo, and the rounding of the two lo parts) is about 3 * 2^-22 of the term,
+// the size of the rounding an fp32 accumulation of 64 terms makes anyway, at 3/16 of the fp32 MFMA's matrix time.
+// hi parts first (F * F halves), then lo parts: together the bytes of the fp32 pack.
+__global__ void k_pack_ff_f16x2(const float *__restrict__ W, int F, int trans, float scale, _Float16 *__restrict__ out)
+{
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= F * F) return;
+    const int NB = F / 32;
+    const int t = idx & 7, lane = (idx >> 3) & 63, q = (idx >> 9) & 1, bb = idx >> 10;
+    const int bi = bb % NB, bo = bb / NB;
+    const int r = 8 * q + t;
+    const int o = 32 * bo + (lane & 31);
+    const int k = 32 * bi + 8 * (r / 4) + 4 * (lane >> 5) + (r & 3);
+    const float v = scale * (trans ? W[k * F + o] : W[o * F + k]);
+    const _Float16 h = (_Float16)v;
+    out[idx] = h;
+    out[F * F + idx] = (_Float16)(v - (float)h);
+}
+
+__device__ inline void split_f16(const float (&v)[8], f16x8 &hi, f16x8 &lo)
+{
+#pragma unroll
+    for (int i = 0; i < 8; i += 2) {
+        const f32x2 p = {v[i], v[i + 1]};
+        const f16x2 h = __builtin_convertvector(p, f16x2);
+        const f16x2 l = __builtin_convertvector(p - __builtin_convertvector(h, f32x2), f16x2);
+        hi[i] = h[0];
+        hi[i + 1] = h[1];
+        lo[i] = l[0];
+        lo[i + 1] = l[1];
+    }
 }
 
 __device__ inline bf16x8 to_bf16x8(const float (&v)[8])
@@ -365,6 +402,67 @@ __device__ inline void gemm_row_bf16(const __bf16 *__restrict__ Ap, const float 
         }
 }
 
+// gemm_rl and gemm_row in split fp16 (three MFMAs of depth 16 per 16 k-values)
+template <int F>
+__device__ inline void gemm_rl_f16x3(const _Float16 *__restrict__ Ap, const f32x16 (&in)[Dims<F>::NB],
+                                     f32x16 (&out)[Dims<F>::NB], int lane)
+{
+    constexpr int NB = Dims<F>::NB;
+    const f16x8 *Ah = reinterpret_cast<const f16x8 *>(Ap) + lane;
+    const f16x8 *Al = reinterpret_cast<const f16x8 *>(Ap + F * F) + lane;
+#pragma unroll
+    for (int bo = 0; bo < NB; ++bo)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) out[bo][r] = 0.f;
+#pragma unroll
+    for (int bi = 0; bi < NB; ++bi)
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            float v[8];
+#pragma unroll
+            for (int t = 0; t < 8; ++t) v[t] = in[bi][8 * q + t];
+            f16x8 bh, bl;
+            split_f16(v, bh, bl);
+#pragma unroll
+            for (int bo = 0; bo < NB; ++bo) {
+                const f16x8 ah = Ah[((bo * NB + bi) * 2 + q) * 64], al = Al[((bo * NB + bi) * 2 + q) * 64];
+                out[bo] = __builtin_amdgcn_mfma_f32_32x32x16_f16(al, bh, out[bo], 0, 0, 0);   // small terms first
+                out[bo] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah, bl, out[bo], 0, 0, 0);
+                out[bo] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah, bh, out[bo], 0, 0, 0);
+            }
+        }
+}
+
+template <int F>
+__device__ inline void gemm_row_f16x3(const _Float16 *__restrict__ Ap, const float *row, f32x16 (&out)[Dims<F>::NB], int lane)
+{
+    constexpr int NB = Dims<F>::NB;
+    const int h = lane >> 5;
+    const f16x8 *Ah = reinterpret_cast<const f16x8 *>(Ap) + lane;
+    const f16x8 *Al = reinterpret_cast<const f16x8 *>(Ap + F * F) + lane;
+#pragma unroll
+    for (int bo = 0; bo < NB; ++bo)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) out[bo][r] = 0.f;
+#pragma unroll
+    for (int bi = 0; bi < NB; ++bi)
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const f32x4 lo4 = *reinterpret_cast<const f32x4 *>(row + 32 * bi + 16 * q + 4 * h);
+            const f32x4 hi4 = *reinterpret_cast<const f32x4 *>(row + 32 * bi + 16 * q + 8 + 4 * h);
+            const float v[8] = {lo4[0], lo4[1], lo4[2], lo4[3], hi4[0], hi4[1], hi4[2], hi4[3]};
+            f16x8 bh, bl;
+            split_f16(v, bh, bl);
+#pragma unroll
+            for (int bo = 0; bo < NB; ++bo) {
+                const f16x8 ah = Ah[((bo * NB + bi) * 2 + q) * 64], al = Al[((bo * NB + bi) * 2 + q) * 64];
+                out[bo] = __builtin_amdgcn_mfma_f32_32x32x16_f16(al, bh, out[bo], 0, 0, 0);
+                out[bo] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah, bl, out[bo], 0, 0, 0);
+                out[bo] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah, bh, out[bo], 0, 0, 0);
+            }
+        }
+}
+
 template <int F> struct RegPack1 {
     float v[Dims<F>::NB][4];
 };
@@ -485,6 +583,7 @@ struct EdgeCommon {
 // with chunk_start[p] <= w < chunk_start[p + 1].  The partitions keep their own arrays (local rows,
 // ghost rows); batching only removes the idle tail between per-partition launches.
 constexpr int kBatch = 8;
+enum { kPrecF32 = 0, kPrecBf16 = 1, kPrecF16x3 = 2 };
 struct EdgeBatch {
     EdgeCommon c;
     int n;
@@ -561,15 +660,15 @@ __device__ inline uint32_t row_ends(int32_t rk, int32_t rn_first, bool valid, in
     return (uint32_t)__ballot(valid && rnext != rk);
 }
 
-// BF16: the W2 product runs on the bf16 matrix pipeline (A2t is then a bf16 pack)
-template <int F, bool BF16>
+// PREC selects how the F x F product with W2 runs: kPrecF32 fp32 MFMA, kPrecBf16 bf16 operands, kPrecF16x3 split fp16
+template <int F, int PREC>
 __global__ void __launch_bounds__(256, 3) k_edge_fwd(EdgeBatch B)
 {
     using D = Dims<F>;
     extern __shared__ float lds[];
     float *A2t = lds;
     float *tiles = A2t + D::PACKF;
-    for (int i = threadIdx.x; i < (BF16 ? D::PACKF / 2 : D::PACKF); i += 256) A2t[i] = B.c.A2t[i];
+    for (int i = threadIdx.x; i < (PREC == kPrecBf16 ? D::PACKF / 2 : D::PACKF); i += 256) A2t[i] = B.c.A2t[i];
     __syncthreads();
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int c32 = lane & 31;
@@ -639,8 +738,10 @@ __global__ void __launch_bounds__(256, 3) k_edge_fwd(EdgeBatch B)
         for (int bb = 0; bb < D::NB; ++bb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) t[bb][r] = t[bb][r] * sigmoid_scaled(t[bb][r]);
-        if (BF16)
+        if (PREC == kPrecBf16)
             gemm_rl_bf16<F>(reinterpret_cast<const __bf16 *>(A2t), t, w, lane);
+        else if (PREC == kPrecF16x3)
+            gemm_rl_f16x3<F>(reinterpret_cast<const _Float16 *>(A2t), t, w, lane);
         else
             gemm_rl<F>(A2t, t, w, lane);
         regs_to_tile<F>(w, tile, lane);
@@ -737,7 +838,7 @@ __device__ inline void gemm_queue(const float *__restrict__ Ap, const float *row
     }
 }
 
-template <int F, bool BF16>
+template <int F, int PREC>
 __global__ void __launch_bounds__(256, 2) k_edge_bwd(EdgeBatch B)
 {
     using D = Dims<F>;
@@ -747,7 +848,7 @@ __global__ void __launch_bounds__(256, 2) k_edge_bwd(EdgeBatch B)
     float *A2n = lds;
     float *A1l = A2n + D::PACKF;
     float *queues = A1l + D::PACK1;
-    for (int i = threadIdx.x; i < (BF16 ? D::PACKF / 2 : D::PACKF); i += 256) A2n[i] = B.c.A2n[i];
+    for (int i = threadIdx.x; i < (PREC == kPrecBf16 ? D::PACKF / 2 : D::PACKF); i += 256) A2n[i] = B.c.A2n[i];
     for (int i = threadIdx.x; i < D::PACK1; i += 256) A1l[i] = B.c.A1[i];
     __syncthreads();
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
@@ -919,8 +1020,10 @@ __global__ void __launch_bounds__(256, 2) k_edge_bwd(EdgeBatch B)
             }
         }
         f32x16 sb[D::NB];
-        if (BF16)   // sbar[k] = sum_f W2[k][f] wsym[f]
+        if (PREC == kPrecBf16)   // sbar[k] = sum_f W2[k][f] wsym[f]
             gemm_row_bf16<F>(reinterpret_cast<const __bf16 *>(A2n), Q + slot * FS, sb, lane);
+        else if (PREC == kPrecF16x3)
+            gemm_row_f16x3<F>(reinterpret_cast<const _Float16 *>(A2n), Q + slot * FS, sb, lane);
         else
             gemm_queue<F>(A2n, Q + slot * FS, sb, lane);
         float part = 0.f;
@@ -1689,23 +1792,23 @@ int node_pass(mlip_graph *g, SlabView *views, int P, const float *P1, const floa
     return MLIP_OK;
 }
 
-template <int F, bool BF16> int launch_edge(mlip_graph *g, EdgeBatch &b, bool backward)
+template <int F, int PREC> int launch_edge(mlip_graph *g, EdgeBatch &b, bool backward)
 {
     const size_t lds = backward ? Lds<F>::edge_bwd : Lds<F>::edge_fwd;
     // resident blocks per compute unit, queried once per kernel
     static int occ_f = 0, occ_b = 0, n_cu = 0;
     int &occ = backward ? occ_b : occ_f;
     if (occ == 0) {
-        const void *fn = backward ? reinterpret_cast<const void *>(&k_edge_bwd<F, BF16>)
-                                  : reinterpret_cast<const void *>(&k_edge_fwd<F, BF16>);
+        const void *fn = backward ? reinterpret_cast<const void *>(&k_edge_bwd<F, PREC>)
+                                  : reinterpret_cast<const void *>(&k_edge_fwd<F, PREC>);
         MLIP_HIP(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         int dev = 0, o = 0;
         MLIP_HIP(hipGetDevice(&dev));
         MLIP_HIP(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
         if (backward)
-            MLIP_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&o, k_edge_bwd<F, BF16>, 256, lds));
+            MLIP_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&o, k_edge_bwd<F, PREC>, 256, lds));
         else
-            MLIP_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&o, k_edge_fwd<F, BF16>, 256, lds));
+            MLIP_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&o, k_edge_fwd<F, PREC>, 256, lds));
         if (o < 1 || n_cu < 8) {
             set_error("edge kernel does not fit the device (occupancy %d, %d compute units)", o, n_cu);
             return MLIP_EHIP;
@@ -1722,9 +1825,9 @@ template <int F, bool BF16> int launch_edge(mlip_graph *g, EdgeBatch &b, bool ba
     const int64_t needed = ((items + 7) / 8 + 3) / 4;
     const unsigned blocks = (unsigned)(8 * std::max<int64_t>(1, std::min(resident, needed)));
     if (backward)
-        k_edge_bwd<F, BF16><<<blocks, 256, lds, g->stream>>>(b);
+        k_edge_bwd<F, PREC><<<blocks, 256, lds, g->stream>>>(b);
     else
-        k_edge_fwd<F, BF16><<<blocks, 256, lds, g->stream>>>(b);
+        k_edge_fwd<F, PREC><<<blocks, 256, lds, g->stream>>>(b);
     MLIP_HIP(hipGetLastError());
     return MLIP_OK;
 }
@@ -1736,7 +1839,8 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
 {
     hipStream_t s = g->stream;
     const int L = w->L;
-    const bool bf16 = (w->precision == MLIP_PRECISION_BF16);
+    const int prec = (w->precision == MLIP_PRECISION_BF16) ? kPrecBf16
+                     : (w->precision == MLIP_PRECISION_FP32_SPLIT) ? kPrecF16x3 : kPrecF32;
     const bool slabs = (mode == MLIP_MODE_SLABS);
     const int P = slabs ? g->P : 1;
     SlabView *views = slabs ? g->slabs.data() : &g->whole;
@@ -1790,9 +1894,12 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
         const size_t ff = (size_t)F * F;
         k_pack_w1<<<blocks_for((F / 32) * 256, 256), 256, 0, s>>>(w->W1 + (size_t)l * 8 * F, F, 1.0f, base + pk.A1);
         k_pack_w1<<<blocks_for((F / 32) * 256, 256), 256, 0, s>>>(w->W1 + (size_t)l * 8 * F, F, kSiluScale, base + pk.A1s);
-        if (bf16) {   // the two W2 operands as bf16 packs (half of their slots)
+        if (prec == kPrecBf16) {   // the two W2 operands as bf16 packs (half of their slots)
             k_pack_ff_bf16<<<pb, 256, 0, s>>>(w->W2 + l * ff, F, 1, kSiluScaleInv, reinterpret_cast<__bf16 *>(base + pk.W2t));
             k_pack_ff_bf16<<<pb, 256, 0, s>>>(w->W2 + l * ff, F, 0, 1.0f, reinterpret_cast<__bf16 *>(base + pk.W2n));
+        } else if (prec == kPrecF16x3) {   // as split-fp16 packs (hi and lo halves)
+            k_pack_ff_f16x2<<<pb, 256, 0, s>>>(w->W2 + l * ff, F, 1, kSiluScaleInv, reinterpret_cast<_Float16 *>(base + pk.W2t));
+            k_pack_ff_f16x2<<<pb, 256, 0, s>>>(w->W2 + l * ff, F, 0, 1.0f, reinterpret_cast<_Float16 *>(base + pk.W2n));
         } else {
             k_pack_ff<<<pb, 256, 0, s>>>(w->W2 + l * ff, F, 1, kSiluScaleInv, base + pk.W2t);
             k_pack_ff<<<pb, 256, 0, s>>>(w->W2 + l * ff, F, 0, 1.0f, base + pk.W2n);
@@ -1952,7 +2059,8 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
                 ea.wstore = (l >= 1) ? wslice(v, l) : nullptr;
             }
             prof_begin(g, MLIP_PROF_EDGE_FWD);
-            MLIP_TRY(bf16 ? (launch_edge<F, true>(g, eb, false)) : (launch_edge<F, false>(g, eb, false)));
+            MLIP_TRY(prec == kPrecBf16 ? (launch_edge<F, kPrecBf16>(g, eb, false))
+                     : prec == kPrecF16x3 ? (launch_edge<F, kPrecF16x3>(g, eb, false)) : (launch_edge<F, kPrecF32>(g, eb, false)));
             prof_end(g);
         }
         if (any_bonds) {   // bond term of the filters: a_i += sum_b wb_b * g_send(b)
@@ -2053,7 +2161,8 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
                 ea.n_stored = need_gbar ? v.n_edges_owned : 0;
             }
             prof_begin(g, MLIP_PROF_EDGE_BWD);
-            MLIP_TRY(bf16 ? (launch_edge<F, true>(g, eb, true)) : (launch_edge<F, false>(g, eb, true)));
+            MLIP_TRY(prec == kPrecBf16 ? (launch_edge<F, kPrecBf16>(g, eb, true))
+                     : prec == kPrecF16x3 ? (launch_edge<F, kPrecF16x3>(g, eb, true)) : (launch_edge<F, kPrecF32>(g, eb, true)));
             prof_end(g);
         }
         if (any_bonds) {   // bond term: dE/dwb, its share of gbar, and e1bar += wbbar Wb_l^T

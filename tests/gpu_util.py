@@ -19,10 +19,10 @@ def gpu_graph(pos, cell, species, r_cut, n_slabs=1, graph=None):
     return M.mlip_build_graph(tp, cell, ts, r_cut, n_slabs=n_slabs, graph=graph)
 
 
-def gpu_energy_forces(g, weights, p, mode):
+def gpu_energy_forces(g, weights, p, mode, precision=0):
     import torch
     import paper_2506_02023_amd as M
-    W = M.Weights(weights, p)
+    W = M.Weights(weights, p, precision=precision)
     e, f, ae = M.mlip_forward(g, W, mode)
     torch.cuda.synchronize()
     return float(e.cpu()[0]), f.cpu().numpy().astype(np.float64), ae.cpu().numpy().astype(np.float64)

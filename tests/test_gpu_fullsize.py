@@ -51,6 +51,9 @@ def test_config2_partition_equivalence():
     es, fs, as_ = gpu_energy_forces(g, c["weights"], c["p"], SLABS)
     dw = assert_energy_forces(ew, fw, ref, "configs[2] whole")
     ds = assert_energy_forces(es, fs, ref, "configs[2] 8 slabs")
+    e2, f2, _ = gpu_energy_forces(g, c["weights"], c["p"], SLABS, precision=2)   # split-fp16 W2 products, same bounds
+    d2 = assert_energy_forces(e2, f2, ref, "configs[2] 8 slabs, split-fp16 products")
+    print(f"configs[2] split-fp16 products: dE/E {d2[0]:.2e} dF {d2[1]:.2e}")
     assert abs(es - ew) <= E_RTOL * abs(ew)
     assert np.abs(fs - fw).max() <= F_RTOL * np.abs(fw).max()
     print(f"configs[2]: whole dE/E {dw[0]:.2e} dF {dw[1]:.2e}; slabs dE/E {ds[0]:.2e} dF {ds[1]:.2e}")
@@ -78,6 +81,7 @@ def test_config3_million_atoms():
     slab_of = _check_sets(g, ref_g, pos, cell, P)
     ew, fw, aw = gpu_energy_forces(g, c["weights"], c["p"], WHOLE)
     es, fs, as_ = gpu_energy_forces(g, c["weights"], c["p"], SLABS)
+    e2, f2, a2 = gpu_energy_forces(g, c["weights"], c["p"], SLABS, precision=2)   # split-fp16 W2 products
     # properties: reductions consistent, zero net force, partitioned == whole
     assert abs(ew - aw.sum()) <= 1e-9 * abs(ew) and abs(es - as_.sum()) <= 1e-9 * abs(es)
     fmax = np.abs(fw).max()
@@ -99,7 +103,7 @@ def test_config3_million_atoms():
         k = int(np.flatnonzero(sel == i)[0])
         # the cluster graph reproduces the atom's row of the periodic graph
         assert cg.row_ptr[k + 1] - cg.row_ptr[k] == ref_g.row_ptr[i + 1] - ref_g.row_ptr[i]
-        for ae, ff in ((aw, fw), (as_, fs)):
+        for ae, ff in ((aw, fw), (as_, fs), (a2, f2)):
             de = abs(ae[i] - ref["atom_energy"][k]) / max(abs(ref["atom_energy"][k]), np.abs(aw).mean())
             df = np.abs(ff[i] - ref["forces"][k]).max() / fmax
             worst_e, worst_f = max(worst_e, de), max(worst_f, df)

@@ -13,14 +13,16 @@ pytestmark = pytest.mark.gpu
 WHOLE, SLABS = 0, 1
 
 
+# precision 0: fp32 MFMA; 2: the W2 products as split-fp16 triples, held to the same fp32 bounds
+@pytest.mark.parametrize("precision", [0, 2])
 @pytest.mark.parametrize("index", [0, 1])
-def test_whole_graph_configs(index):
+def test_whole_graph_configs(index, precision):
     c, _, ref = oracle_config(index)
     g = gpu_graph(c["positions"], c["cell"], c["species"], c["r_cut"])
-    e, f, ae = gpu_energy_forces(g, c["weights"], c["p"], WHOLE)
+    e, f, ae = gpu_energy_forces(g, c["weights"], c["p"], WHOLE, precision)
     de, df = assert_energy_forces(e, f, ref, f"configs[{index}] whole")
     assert np.abs(ae - ref["atom_energy"]).max() <= 1e-4 * np.abs(ref["atom_energy"]).max()
-    print(f"configs[{index}] whole: dE/E = {de:.2e}, dF/Fmax = {df:.2e}")
+    print(f"configs[{index}] whole, precision {precision}: dE/E = {de:.2e}, dF/Fmax = {df:.2e}")
 
 
 @pytest.mark.parametrize("P", [2, 3, 8])
@@ -33,12 +35,13 @@ def test_slabs_config0(P):
     assert_energy_forces(ew, fw, ref, "configs[0] whole on a partitioned graph")
 
 
-def test_slabs_medium():
+@pytest.mark.parametrize("precision", [0, 2])
+def test_slabs_medium(precision):
     c, _, ref = oracle_config(1)
     g = gpu_graph(c["positions"], c["cell"], c["species"], c["r_cut"], n_slabs=8)
-    e, f, ae = gpu_energy_forces(g, c["weights"], c["p"], SLABS)
+    e, f, ae = gpu_energy_forces(g, c["weights"], c["p"], SLABS, precision)
     de, df = assert_energy_forces(e, f, ref, "configs[1] 8 slabs")
-    print(f"configs[1] 8 slabs: dE/E = {de:.2e}, dF/Fmax = {df:.2e}")
+    print(f"configs[1] 8 slabs, precision {precision}: dE/E = {de:.2e}, dF/Fmax = {df:.2e}")
 
 
 def test_triclinic_small_cell_f32_features():

@@ -67,7 +67,7 @@ def main():
     ap.add_argument("--cells", type=int, default=None, help="override fcc cells per side (smaller runs)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--cpu-cells", type=int, default=40)
-    ap.add_argument("--whole", action="store_true", help="also time whole-graph mode on the same graph (extra fields)")
+    ap.add_argument("--no-whole", action="store_true", help="skip the unpartitioned (whole-graph) run of the same system")
     ap.add_argument("--precision", choices=("f32", "f32split", "bf16"), default="f32",
                     help="f32split: the F x F products of the filter MLP as split-fp16 MFMA triples (fp32-grade results); "
                          "bf16: those products with bf16 operands (fp32 accumulation)")
@@ -121,34 +121,28 @@ def main():
     energy = float(out[0].cpu()[0])
     fsum = out[1].double().sum(0).abs().max().item()
 
-    # whole-graph mode on the same graph, for the record (not the headline)
-    dt_whole_fwd, energy_whole = None, None
-    if args.whole:
-        for _ in range(2):
-            M.mlip_forward(g, W, M.MODE_WHOLE, out=out, want_atom_energy=False)
+    def timed_variant(weights, n_slabs, mode):
+        """The same step with other weights / slab count, outside the headline's timed region."""
+        gv = None
+        t1 = 0.0
+        for it in range(2 + args.steps):
+            if it == 2:
+                torch.cuda.synchronize()
+                t1 = time.perf_counter()
+            gv = M.mlip_build_graph(pos, c["cell"], spec, c["r_cut"], n_slabs=n_slabs, graph=gv)
+            M.mlip_forward(gv, weights, mode, out=out, want_atom_energy=False)
         torch.cuda.synchronize()
-        t1 = time.perf_counter()
-        for _ in range(args.steps):
-            M.mlip_forward(g, W, M.MODE_WHOLE, out=out, want_atom_energy=False)
-        torch.cuda.synchronize()
-        dt_whole_fwd = (time.perf_counter() - t1) / args.steps
-        energy_whole = float(out[0].cpu()[0])
+        ms = (time.perf_counter() - t1) / args.steps * 1e3
+        e = float(out[0].cpu()[0])
+        gv.destroy()
+        return ms, e
 
-    # the same step with the W2 products as split-fp16 triples (same bounds as fp32), for the record
-    split_ms = None
+    # for the record (not the headline): the unpartitioned run, and the split-fp16 mode of the headline's step
+    whole_ms = split_ms = None
+    if not three_body and not args.no_whole:
+        whole_ms, energy_whole = timed_variant(W, 1, M.MODE_WHOLE)
     if args.precision == "f32" and not three_body:
-        W2 = M.Weights(c["weights"], c["p"], precision=2)
-        Wsave, W = W, W2
-        for _ in range(2):
-            step()
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-        for _ in range(args.steps):
-            step()
-        torch.cuda.synchronize()
-        split_ms = (time.perf_counter() - t1) / args.steps * 1e3
-        energy_split = float(out[0].cpu()[0])
-        W = Wsave
+        split_ms, energy_split = timed_variant(M.Weights(c["weights"], c["p"], precision=2), P, M.MODE_SLABS)
 
     ms_step = dt / args.steps * 1e3
     L = c["L"]
@@ -198,10 +192,10 @@ def main():
                                       "energy": energy_split,
                                       "note": "MLIP_PRECISION_FP32_SPLIT: same step, W2 products as three fp16 MFMA products "
                                               "of split operands; held to the fp32 bounds by the parity tests"}
-    if args.whole:
-        res["whole_graph_forward_ms"] = dt_whole_fwd * 1e3
-        res["whole_graph_atoms_per_s_excl_graph"] = N / dt_whole_fwd
-        res["energy_whole"] = energy_whole
+    if whole_ms is not None:
+        res["whole_graph"] = {"ms_per_step": whole_ms, "value": N / (whole_ms * 1e-3), "unit": "atoms/s",
+                              "energy": energy_whole, "rel_energy_difference_to_slabs": abs(energy_whole - energy) / abs(energy),
+                              "note": "graph build without partition + unpartitioned energy+forces of the same system"}
     if not args.no_cpu:
         res["cpu_baseline"] = cpu_baseline(args.config, min(args.cpu_cells, 24) if three_body else args.cpu_cells)
     print(json.dumps(res))

@@ -648,6 +648,17 @@ __device__ inline void buffer_store_f32(float v, __amdgpu_buffer_rsrc_t r, unsig
 {
     __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), r, voff, soff, 0);
 }
+// The same with the non-temporal hint (cache policy bit 1) for the kept filter values: written once, read once
+// much later, they should not displace the gathered rows in the L2 (measured on the 1M-atom benchmark: 0.7 ms
+// of 40 per step in fp32 mode, 1.5 ms of 34 in the split-fp16 mode).
+__device__ inline float buffer_load_f32_stream(__amdgpu_buffer_rsrc_t r, unsigned voff, int soff)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, voff, soff, 2));
+}
+__device__ inline void buffer_store_f32_stream(float v, __amdgpu_buffer_rsrc_t r, unsigned voff, int soff)
+{
+    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), r, voff, soff, 2);
+}
 
 // Per-tile row bookkeeping shared by both edge kernels.  Every lane holds the receiver of its edge
 // (rk, the sentinel r1 for lanes past the end of the chunk); the receiver of the following edge
@@ -759,7 +770,7 @@ __global__ void __launch_bounds__(256, 3) k_edge_fwd(EdgeBatch B)
                 A.wstore + (int64_t)tb * F, 0, kmax * (F * 4), kBufferFlags);
 #pragma unroll
             for (int k = 0; k < 32; ++k)
-                if (F == 64 || lane < F) buffer_store_f32(wv[k], w_rsrc, f * 4, k * (F * 4), 0);
+                if (F == 64 || lane < F) buffer_store_f32_stream(wv[k], w_rsrc, f * 4, k * (F * 4));
         }
 #pragma unroll
         for (int k = 0; k < 32; ++k) {
@@ -794,7 +805,13 @@ __global__ void __launch_bounds__(256, 3) k_edge_fwd(EdgeBatch B)
 //   sum_k (W2 wsym)_k * ds_k/dd,   ds_k/dd = SiLU'(t_k) * sum_n W1[n][k] db_n/dd,
 //   on the MFMA units, written to both edges of the pair.  Both edges of a pair have the same length
 //   and the same wsym, so the dense work runs once per pair instead of once per directed edge.
-constexpr int kQueue = 48;   // queued pairs per wavefront: at most 31 pending + 16 new
+// Edges per step of the reverse kernel's phase 1.  Steps of 8 with a 32-slot queue fit three blocks per compute
+// unit instead of two (154 registers, 52 KB of LDS) and measured slower (16.2 against 14.8 ms on the 1M-atom
+// benchmark): the per-step bookkeeping doubles and phase 2 runs on partly filled tiles.
+constexpr int kStep = 16;
+constexpr int kQueue = 31 + kStep + 1;   // queued pairs per wavefront: at most 31 pending + one step's new ones
+// phase 2 runs once a further step could overflow the queue (and at the latest with 32 pairs queued)
+constexpr int kQueueTrigger = (kQueue - kStep < 32) ? kQueue - kStep : 32;
 
 template <int F>
 __device__ inline void gemm_queue(const float *__restrict__ Ap, const float *row, f32x16 (&out)[Dims<F>::NB], int lane)
@@ -853,7 +870,7 @@ __global__ void __launch_bounds__(256, 2) k_edge_bwd(EdgeBatch B)
     __syncthreads();
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int c32 = lane & 31;
-    const int l16 = lane & 15;
+    const int l16 = lane & (kStep - 1);   // lane's edge within a step
     const unsigned f = lane & (F - 1);
     // Queue of pairs, one per wavefront: slot s is LDS row s, floats [0, F) = wsym, then the upper
     // edge's index, the reverse edge's index and the edge length in the row's padding.  It carries
@@ -884,16 +901,16 @@ __global__ void __launch_bounds__(256, 2) k_edge_bwd(EdgeBatch B)
     int32_t r1 = 0, e_hi = 0;
     float acc = 0.f;
 
-    // Phase 1 runs in steps of 16 edges through a software pipeline whose loads are all issued ahead of
+    // Phase 1 runs in steps of kStep edges through a software pipeline whose loads are all issued ahead of
     // their use: the edge records (sender, receiver, reverse edge, length) two steps ahead, the rows they
     // point to one step ahead.  Vector memory loads complete in order, so a stage may only contain loads
     // and address arithmetic; anything that consumes a loaded value belongs to a later stage.
-    struct Ids {    // lane k (mod 16) holds edge tb + k, clamped to the last edge of the work item
+    struct Ids {    // lane k (mod kStep) holds edge tb + k, clamped to the last edge of the work item
         int32_t sj, rk, mk;
         float dk;
     };
     struct Step {
-        float av[16], gv[16], wv[16];   // abar / g rows of the senders, kept filter values
+        float av[kStep], gv[kStep], wv[kStep];   // abar / g rows of the senders, kept filter values
         float ai0, gi0, ai1, gi1;       // abar / g rows of the first and of the last edge's receiver
         int kmax;                       // valid edges in the step
         int32_t tb;
@@ -907,7 +924,7 @@ __global__ void __launch_bounds__(256, 2) k_edge_bwd(EdgeBatch B)
     };
     auto load_step = [&](Step &S, const Ids &I, int32_t tb) {
         S.tb = tb;
-        S.kmax = __builtin_amdgcn_readfirstlane(max(0, min(16, e_hi - tb)));   // (the clamp is a vector instruction)
+        S.kmax = __builtin_amdgcn_readfirstlane(max(0, min(kStep, e_hi - tb)));   // (the clamp is a vector instruction)
         // A step past the end of the work item (kmax = 0) still issues its loads, from the clamped records:
         // every path through the pipeline then has the same number of loads in flight, which is what lets
         // the waits before the uses be partial ones.
@@ -922,11 +939,11 @@ __global__ void __launch_bounds__(256, 2) k_edge_bwd(EdgeBatch B)
         const __amdgpu_buffer_rsrc_t w_rsrc = __builtin_amdgcn_make_buffer_rsrc(
             A.wstore + (need_gbar ? (int64_t)tb * F : 0), 0, need_gbar ? S.kmax * kRowBytes : 0, kBufferFlags);
 #pragma unroll
-        for (int k = 0; k < 16; ++k) {
+        for (int k = 0; k < kStep; ++k) {
             const int32_t so = __builtin_amdgcn_readlane(sjo, k);
             S.av[k] = buffer_load_f32(a_rsrc, f * 4, so, 0);
             S.gv[k] = buffer_load_f32(g_rsrc, f * 4, so, 0);
-            S.wv[k] = buffer_load_f32(w_rsrc, f * 4, k * kRowBytes, 0);   // 0 outside the descriptor's range
+            S.wv[k] = buffer_load_f32_stream(w_rsrc, f * 4, k * kRowBytes);   // 0 outside the descriptor's range
         }
     };
     // rn_first: receiver of the first edge of the following step (r1 after the last step)
@@ -937,14 +954,14 @@ __global__ void __launch_bounds__(256, 2) k_edge_bwd(EdgeBatch B)
         const int32_t e_l = S.tb + l16;
         // wave-uniform masks: bit k = edge k ends its row / edge k is the upper edge of its pair
         const int32_t up = __shfl(rk, l16 + 1, 64);
-        const int32_t rnext = (l16 == 15) ? rn_first : up;
-        const uint32_t ends = (uint32_t)__ballot(valid_l && rnext != rk) & 0xffffu;
+        const int32_t rnext = (l16 == kStep - 1) ? rn_first : up;
+        const uint32_t ends = (uint32_t)__ballot(valid_l && rnext != rk) & ((1u << kStep) - 1u);
         const bool upper_l = valid_l && I.mk > e_l;
-        const uint32_t uppers = (uint32_t)__ballot(upper_l) & 0xffffu;
+        const uint32_t uppers = (uint32_t)__ballot(upper_l) & ((1u << kStep) - 1u);
         {   // records of the pairs queued by this step, all at once: slots follow q_tail in edge order
-            int slot = q_tail + (int)__builtin_amdgcn_mbcnt_lo(uppers, 0u);   // upper edges before this lane's (lanes < 16)
+            int slot = q_tail + (int)__builtin_amdgcn_mbcnt_lo(uppers, 0u);   // upper edges before this lane's (lanes < kStep)
             slot -= (slot >= kQueue) ? kQueue : 0;
-            if (upper_l && lane < 16) {
+            if (upper_l && lane < kStep) {
                 float *rec = Q + slot * FS + F;
                 reinterpret_cast<int32_t *>(rec)[0] = e_l;
                 reinterpret_cast<int32_t *>(rec)[1] = I.mk;
@@ -955,7 +972,7 @@ __global__ void __launch_bounds__(256, 2) k_edge_bwd(EdgeBatch B)
         float ai = S.ai0, gi = S.gi0;
         int q_off = q_tail * (FS * 4);   // byte offset of the slot the next pair goes to
 #pragma unroll
-        for (int k = 0; k < 16; ++k) {
+        for (int k = 0; k < kStep; ++k) {
             acc = fmaf(S.wv[k], S.av[k], acc);   // edges past the end contribute w = 0
             // wsym goes to the next free slot whether or not the edge is an upper one; only an upper edge
             // advances the slot, anything else is overwritten by the next edge
@@ -1065,26 +1082,26 @@ __global__ void __launch_bounds__(256, 2) k_edge_bwd(EdgeBatch B)
         Ids IA, IB, IC;
         Step SA, SB;
         load_ids(IA, e_lo);
-        load_ids(IB, e_lo + 16);
+        load_ids(IB, e_lo + kStep);
         {   // rows of the chunk before its first edge are empty
             const int32_t first = __builtin_amdgcn_readfirstlane(IA.rk);
             for (int32_t r = r0; r < first; ++r) store_row(r, 0.f);
         }
         load_step(SA, IA, e_lo);
-        for (int32_t tb = e_lo; tb < e_hi; tb += 32) {
+        for (int32_t tb = e_lo; tb < e_hi; tb += 2 * kStep) {
             int32_t nf;
-            load_ids(IC, tb + 32);
-            load_step(SB, IB, tb + 16);
+            load_ids(IC, tb + 2 * kStep);
+            load_step(SB, IB, tb + kStep);
             nf = __builtin_amdgcn_readfirstlane(IB.rk);
-            compute_step(SA, IA, (tb + 16 < e_hi) ? nf : r1);
-            if (q_count >= 32) phase2();
-            load_ids(IA, tb + 48);
-            load_step(SA, IC, tb + 32);
+            compute_step(SA, IA, (tb + kStep < e_hi) ? nf : r1);
+            if (q_count >= kQueueTrigger) phase2();
+            load_ids(IA, tb + 3 * kStep);
+            load_step(SA, IC, tb + 2 * kStep);
             nf = __builtin_amdgcn_readfirstlane(IC.rk);
-            compute_step(SB, IB, (tb + 32 < e_hi) ? nf : r1);
-            if (q_count >= 32) phase2();
-            IB = IA;   // records of step tb + 48, loaded a step ago
-            IA = IC;   // records of step tb + 32, whose rows SA holds
+            compute_step(SB, IB, (tb + 2 * kStep < e_hi) ? nf : r1);
+            if (q_count >= kQueueTrigger) phase2();
+            IB = IA;   // records of step tb + 3 kStep, loaded a step ago
+            IA = IC;   // records of step tb + 2 kStep, whose rows SA holds
         }
     }   // work items
     while (q_count > 0) phase2();   // queued pairs index this partition's arrays

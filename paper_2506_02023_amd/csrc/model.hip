@@ -1128,20 +1128,35 @@ struct NodeBatch {     // up to kBatch partitions per launch, 32-row tiles numbe
     NodeArgs s[kBatch];
 };
 
+// A 32-row tile of X travels global memory -> registers -> LDS in two halves, so that the loads of the next
+// tile can be in flight while the current one is multiplied.
+template <int F> struct TileRegs {
+    static constexpr int LPR = F / 4;        // lanes per row (float4 each)
+    static constexpr int RPI = 64 / LPR;     // rows per wave instruction
+    f32x4 v[32 / RPI];
+};
+
 template <int F>
-__device__ inline void load_tile(const float *__restrict__ X, int64_t row0, int64_t n_rows, float *tile, int lane)
+__device__ inline void fetch_tile(TileRegs<F> &T, const float *__restrict__ X, int64_t row0, int64_t n_rows, int lane)
 {
-    constexpr int FS = Dims<F>::FS;
-    constexpr int LPR = F / 4;        // lanes per row (float4 each)
-    constexpr int RPI = 64 / LPR;     // rows per wave instruction
+    constexpr int LPR = TileRegs<F>::LPR, RPI = TileRegs<F>::RPI;
     const int rr = lane / LPR, cc = (lane % LPR) * 4;
 #pragma unroll
     for (int r = 0; r < 32; r += RPI) {
         const int64_t row = row0 + r + rr;
         f32x4 v = {0.f, 0.f, 0.f, 0.f};
         if (row < n_rows) v = *reinterpret_cast<const f32x4 *>(X + row * F + cc);
-        *reinterpret_cast<f32x4 *>(tile + (r + rr) * FS + cc) = v;
+        T.v[r / RPI] = v;
     }
+}
+
+template <int F> __device__ inline void stash_tile(const TileRegs<F> &T, float *tile, int lane)
+{
+    constexpr int FS = Dims<F>::FS;
+    constexpr int LPR = TileRegs<F>::LPR, RPI = TileRegs<F>::RPI;
+    const int rr = lane / LPR, cc = (lane % LPR) * 4;
+#pragma unroll
+    for (int r = 0; r < 32; r += RPI) *reinterpret_cast<f32x4 *>(tile + (r + rr) * FS + cc) = T.v[r / RPI];
 }
 
 template <int F, int OP>
@@ -1162,14 +1177,34 @@ __global__ void __launch_bounds__(256) k_node(NodeBatch B)
     const int c32 = lane & 31, h = lane >> 5;
     float *tile = tiles + wave * D::TILE;
     const int64_t n_tiles = B.tile_start[B.n];
-    for (int64_t ti = (int64_t)blockIdx.x * 4 + wave; ti < n_tiles; ti += (int64_t)gridDim.x * 4) {
+    const int64_t stride = (int64_t)gridDim.x * 4;
+    TileRegs<F> pre;
+    auto fetch = [&](int64_t ti) {
+        const int part = batch_find(B.tile_start, B.n, ti);
+        fetch_tile<F>(pre, B.s[part].X, (ti - B.tile_start[part]) * 32, B.s[part].n_rows, lane);
+    };
+    int64_t ti = (int64_t)blockIdx.x * 4 + wave;
+    if (ti < n_tiles) fetch(ti);
+    for (; ti < n_tiles; ti += stride) {
         const int part = batch_find(B.tile_start, B.n, ti);
         const NodeArgs A = B.s[part];
         const int64_t row0 = (ti - B.tile_start[part]) * 32;
         const int64_t row = row0 + c32;
         const bool ok = row < A.n_rows;
-        load_tile<F>(A.X, row0, A.n_rows, tile, lane);
+        stash_tile<F>(pre, tile, lane);
         wave_lds_fence();
+        // rows of Z this tile combines with its product, requested before the product as well
+        constexpr bool READS_Z = (OP == OP_UPDATE || OP == OP_BWD_PROJ || OP == OP_BWD_UPDATE);
+        f32x4 zv[D::NB][4];
+        if (READS_Z)
+#pragma unroll
+            for (int b = 0; b < D::NB; ++b)
+#pragma unroll
+                for (int a = 0; a < 4; ++a) {
+                    zv[b][a] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    if (ok) zv[b][a] = *reinterpret_cast<const f32x4 *>(A.Z + row * F + 32 * b + 8 * a + 4 * h);
+                }
+        if (ti + stride < n_tiles) fetch(ti + stride);   // in flight during this tile's products
         f32x16 acc[D::NB];
         gemm_lds<F>(P1, tile, acc, lane);
         wave_lds_fence();
@@ -1191,7 +1226,7 @@ __global__ void __launch_bounds__(256) k_node(NodeBatch B)
 #pragma unroll
                     for (int a = 0; a < 4; ++a) {
                         float *zp = A.Z + row * F + 32 * b + 8 * a + 4 * h;
-                        f32x4 v = *reinterpret_cast<const f32x4 *>(zp);
+                        f32x4 v = zv[b][a];
 #pragma unroll
                         for (int c = 0; c < 4; ++c) {
                             const float q = acc[b][4 * a + c];
@@ -1233,8 +1268,7 @@ __global__ void __launch_bounds__(256) k_node(NodeBatch B)
             for (int b = 0; b < D::NB; ++b)
 #pragma unroll
                 for (int a = 0; a < 4; ++a) {
-                    f32x4 hv = {0.f, 0.f, 0.f, 0.f};
-                    if (ok) hv = *reinterpret_cast<const f32x4 *>(A.Z + row * F + 32 * b + 8 * a + 4 * h);
+                    const f32x4 hv = zv[b][a];
 #pragma unroll
                     for (int c = 0; c < 4; ++c) {
                         const float x = acc[b][4 * a + c];

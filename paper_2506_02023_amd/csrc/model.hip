@@ -1405,18 +1405,19 @@ __device__ inline void unpack_shift(uint32_t p, int &a, int &b, int &c)
     c = (int)(p & 1023u) - 512;
 }
 
-// F_loc[r] = sum_{e in local row r} dsum_e * rhat_e, rhat from fp64 positions; one wavefront per row
-__global__ void __launch_bounds__(64)
+// F_loc[r] = sum_{e in local row r} dsum_e * rhat_e, rhat from fp64 positions; 16 lanes per row, 16 rows per block
+__global__ void __launch_bounds__(256)
 k_force_rows(int64_t n_rows, const int64_t *__restrict__ row_ptr, const int32_t *__restrict__ senders,
              const uint32_t *__restrict__ shiftp, const float *__restrict__ dsum, const int32_t *__restrict__ nodes,
              const double *__restrict__ pos, CellParams cp, float *__restrict__ floc)
 {
-    const int64_t r = blockIdx.x;
+    const int64_t r = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
+    if (r >= n_rows) return;   // whole groups of 16 lanes leave together; the shuffles below stay inside a group
     const int64_t ig = nodes ? nodes[r] : r;
     const double xi = pos[3 * ig], yi = pos[3 * ig + 1], zi = pos[3 * ig + 2];
     double fx = 0, fy = 0, fz = 0;
     const int64_t e1 = row_ptr[r + 1];
-    for (int64_t e = row_ptr[r] + threadIdx.x; e < e1; e += 64) {
+    for (int64_t e = row_ptr[r] + (threadIdx.x & 15); e < e1; e += 16) {
         const int64_t jl = senders[e];
         const int64_t jg = nodes ? nodes[jl] : jl;
         int S0, S1, S2;
@@ -1430,12 +1431,12 @@ k_force_rows(int64_t n_rows, const int64_t *__restrict__ row_ptr, const int32_t 
         fz += s * t2;
     }
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) {
+    for (int off = 8; off > 0; off >>= 1) {
         fx += __shfl_xor(fx, off, 64);
         fy += __shfl_xor(fy, off, 64);
         fz += __shfl_xor(fz, off, 64);
     }
-    if (threadIdx.x == 0) {
+    if ((threadIdx.x & 15) == 0) {
         floc[3 * r] = (float)fx;
         floc[3 * r + 1] = (float)fy;
         floc[3 * r + 2] = (float)fz;
@@ -1513,6 +1514,12 @@ __device__ inline void silu_both(float x, float &s, float &ds)
     ds = sg * (1.0f + x * (1.0f - sg));
 }
 
+// value of lane k (wave-uniform k) of a float register, as a wave-uniform value
+__device__ inline float readlane_f32(float v, int k)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), k));
+}
+
 // T_n(c) = cos(n theta), dT_n/dc = n U_{n-1}(c), n = 0..7
 __device__ inline void chebyshev(float c, float (&T)[kAngle], float (&dT)[kAngle])
 {
@@ -1547,6 +1554,8 @@ __global__ void __launch_bounds__(256) k_bond_e0(int64_t nb, const float *__rest
 }
 
 // S[b1][f] = sum_{b2 != b1, same centre} u[b2] SiLU(P[b1][f] + Q[b2][f] + sum_n T_n(c) Wtc[n][f])
+// One wavefront per centre.  The angle basis does not depend on the feature: for a fixed b1 it is evaluated for
+// 64 bonds b2 at once (lane = b2) and handed to the feature lanes through wave-uniform registers.
 template <int F>
 __global__ void __launch_bounds__(256)
 k_triplet_fwd(int64_t N, const int64_t *__restrict__ bptr, const float *__restrict__ rhat, const float *__restrict__ u,
@@ -1560,21 +1569,28 @@ k_triplet_fwd(int64_t N, const int64_t *__restrict__ bptr, const float *__restri
 #pragma unroll
     for (int n = 0; n < kAngle; ++n) wc[n] = Wtc[n * F + f];
     const int64_t b0 = bptr[i], b1e = bptr[i + 1];
-    for (int64_t b1 = b0; b1 < b1e; ++b1) {
-        const float p1 = P[b1 * F + f];
-        const float x1 = rhat[3 * b1], y1 = rhat[3 * b1 + 1], z1 = rhat[3 * b1 + 2];
-        float acc = 0.f;
-        for (int64_t b2 = b0; b2 < b1e; ++b2) {
-            if (b2 == b1) continue;
-            const float c = fmaf(x1, rhat[3 * b2], fmaf(y1, rhat[3 * b2 + 1], z1 * rhat[3 * b2 + 2]));
+    for (int64_t c0 = b0; c0 < b1e; c0 += 64) {   // bonds b2 in groups of 64 (one group unless the centre has more)
+        const int nl = (int)min((int64_t)64, b1e - c0);
+        const int64_t bl = min(c0 + lane, b1e - 1);
+        const float xl = rhat[3 * bl], yl = rhat[3 * bl + 1], zl = rhat[3 * bl + 2], ul = u[bl];
+        for (int64_t b1 = b0; b1 < b1e; ++b1) {
+            const float p1 = P[b1 * F + f];
+            const float x1 = rhat[3 * b1], y1 = rhat[3 * b1 + 1], z1 = rhat[3 * b1 + 2];
             float T[kAngle], dT[kAngle];
-            chebyshev(c, T, dT);
-            float h = p1 + Q[b2 * F + f];
+            chebyshev(fmaf(x1, xl, fmaf(y1, yl, z1 * zl)), T, dT);   // lane = b2
+            float acc = 0.f;
+            for (int k = 0; k < nl; ++k) {
+                if (c0 + k == b1) continue;
+                float h = p1 + Q[(c0 + k) * F + f];
 #pragma unroll
-            for (int n = 0; n < kAngle; ++n) h = fmaf(T[n], wc[n], h);
-            acc = fmaf(u[b2], silu_f(h), acc);
+                for (int n = 1; n < kAngle; ++n) h = fmaf(readlane_f32(T[n], k), wc[n], h);   // T_0 = 1
+                acc = fmaf(readlane_f32(ul, k), silu_f(h + wc[0]), acc);
+            }
+            if (F == 64 || lane < F) {
+                float *sp = S + b1 * F + f;
+                *sp = (c0 == b0) ? acc : *sp + acc;
+            }
         }
-        if (F == 64 || lane < F) S[b1 * F + f] = acc;
     }
 }
 
@@ -2299,7 +2315,7 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
     for (int p = 0; p < P; ++p) {
         SlabView &v = views[p];
         if (L > 0 && v.n_local > 0) {
-            k_force_rows<<<(unsigned)v.n_local, 64, 0, s>>>(v.n_local, v.row_ptr, v.senders, v.shiftp, v.dsum.as<float>(),
+            k_force_rows<<<(unsigned)((v.n_local + 15) / 16), 256, 0, s>>>(v.n_local, v.row_ptr, v.senders, v.shiftp, v.dsum.as<float>(),
                                                             v.nodes, pos, g->cell, v.floc.as<float>());
         } else if (v.n_local > 0) {
             MLIP_HIP(hipMemsetAsync(v.floc.p, 0, (size_t)v.n_local * 3 * sizeof(float), s));

@@ -233,17 +233,18 @@ __device__ inline void gemm_regs(const float *__restrict__ Ap, const f32x16 (&in
 
 // same product with the B operand read from an item-major LDS tile [32][FS]; A and B operand
 // loads of step k+1 are issued before the MFMAs of step k
-template <int F>
+template <int F, bool ACCUMULATE = false>
 __device__ inline void gemm_lds(const float *__restrict__ Ap, const float *tile, f32x16 (&out)[Dims<F>::NB], int lane)
 {
     constexpr int NB = Dims<F>::NB;
     constexpr int FS = Dims<F>::FS;
     constexpr int STEPS = NB * 4;
     const int c32 = lane & 31, h = lane >> 5;
+    if (!ACCUMULATE)
 #pragma unroll
-    for (int bo = 0; bo < NB; ++bo)
+        for (int bo = 0; bo < NB; ++bo)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) out[bo][r] = 0.f;
+            for (int r = 0; r < 16; ++r) out[bo][r] = 0.f;
     const float *bp = tile + c32 * FS + 4 * h;
     const float *ap = Ap + lane * 4;
     f32x4 bv = *reinterpret_cast<const f32x4 *>(bp);
@@ -1536,23 +1537,6 @@ __device__ inline void chebyshev(float c, float (&T)[kAngle], float (&dT)[kAngle
     }
 }
 
-// e0[b][f] = sum_n bbond_n(d_b) We0[n][f]
-template <int F>
-__global__ void __launch_bounds__(256) k_bond_e0(int64_t nb, const float *__restrict__ bd, BasisParams bp,
-                                                 const float *__restrict__ We0, float *__restrict__ e0)
-{
-    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= nb * F) return;
-    const int64_t b = idx / F;
-    const int f = (int)(idx % F);
-    float bb[8], db[8];
-    radial_basis<false>(bd[b], bp, bb, db);
-    float acc = 0.f;
-#pragma unroll
-    for (int n = 0; n < 8; ++n) acc = fmaf(bb[n], We0[n * F + f], acc);
-    e0[idx] = acc;
-}
-
 // S[b1][f] = sum_{b2 != b1, same centre} u[b2] SiLU(P[b1][f] + Q[b2][f] + sum_n T_n(c) Wtc[n][f])
 // One wavefront per centre.  The angle basis does not depend on the feature: for a fixed b1 it is evaluated for
 // 64 bonds b2 at once (lane = b2) and handed to the feature lanes through wave-uniform registers.
@@ -1594,16 +1578,6 @@ k_triplet_fwd(int64_t N, const int64_t *__restrict__ bptr, const float *__restri
     }
 }
 
-// e1 = e0 + u SiLU(m)
-template <int F>
-__global__ void __launch_bounds__(256) k_bond_e1(int64_t nb, const float *__restrict__ e0, const float *__restrict__ m,
-                                                 const float *__restrict__ u, float *__restrict__ e1)
-{
-    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= nb * F) return;
-    e1[idx] = fmaf(u[idx / F], silu_f(m[idx]), e0[idx]);
-}
-
 // bond term of a layer's aggregation: a[i] += sum over the bonds b = (i <- j) of wb[b] * g[j]
 template <int F>
 __global__ void __launch_bounds__(256)
@@ -1619,47 +1593,25 @@ k_bond_aggregate(int64_t N, const int64_t *__restrict__ bptr, const int32_t *__r
     if (F == 64 || lane < F) a[i * F + f] += acc;
 }
 
-// reverse of the bond term: wbbar[b] = abar[i] * g[j]; gbar[i] (+)= sum_b wb[mirror(b)] * abar[j]
+// reverse of the bond term, the share of gbar: gbar[i] += sum_b wb[mirror(b)] * abar[j]
 // (the reverse bond (j <- i) is the one whose filter multiplies g_i in row j)
 template <int F>
 __global__ void __launch_bounds__(256)
-k_bond_bwd(int64_t N, const int64_t *__restrict__ bptr, const int32_t *__restrict__ sender,
-           const int32_t *__restrict__ bmirror, const float *__restrict__ wb, const float *__restrict__ g,
-           const float *__restrict__ abar, float *__restrict__ wbbar, float *gbar)
+k_bond_gbar(int64_t N, const int64_t *__restrict__ bptr, const int32_t *__restrict__ sender,
+            const int32_t *__restrict__ bmirror, const float *__restrict__ wb, const float *__restrict__ abar,
+            float *gbar)
 {
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int64_t i = (int64_t)blockIdx.x * 4 + wave;
     if (i >= N) return;
     const int f = lane & (F - 1);
-    const float ai = abar[i * F + f];
     float acc = 0.f;
     for (int64_t b = bptr[i]; b < bptr[i + 1]; ++b) {
         const int64_t j = sender[b];
-        if (F == 64 || lane < F) wbbar[b * F + f] = ai * g[j * F + f];
         const int64_t bm = bmirror[b];   // -1: the sender is a ghost row (abar_j = 0 here, its owner adds that term)
-        if (gbar && bm >= 0) acc = fmaf(wb[bm * F + f], abar[j * F + f], acc);
+        if (bm >= 0) acc = fmaf(wb[bm * F + f], abar[j * F + f], acc);
     }
-    if (gbar && (F == 64 || lane < F)) gbar[i * F + f] += acc;
-}
-
-// e1 = e0 + u SiLU(m):  ubar[b] = sum_f e1bar SiLU(m);  mbar = e1bar u SiLU'(m)
-template <int F>
-__global__ void __launch_bounds__(256)
-k_bond_mbar(int64_t nb, const float *__restrict__ e1bar, const float *__restrict__ m, const float *__restrict__ u,
-            float *__restrict__ mbar, float *__restrict__ ubar)
-{
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-    const int64_t b = (int64_t)blockIdx.x * 4 + wave;
-    if (b >= nb) return;
-    const int f = lane & (F - 1);
-    float s, ds;
-    silu_both(m[b * F + f], s, ds);
-    const float eb = e1bar[b * F + f];
-    float part = (F == 64 || lane < F) ? eb * s : 0.f;
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off, 64);
-    if (F == 64 || lane < F) mbar[b * F + f] = eb * u[b] * ds;
-    if (lane == 0) ubar[b] = part;
+    if (F == 64 || lane < F) gbar[i * F + f] += acc;
 }
 
 // Reverse of k_triplet_fwd for one centre per wavefront.  Pbar[b1] and rbar[b1] accumulate over the inner
@@ -1735,28 +1687,6 @@ k_triplet_bwd(int64_t N, const int64_t *__restrict__ bptr, const float *__restri
     }
 }
 
-// dE/dd_b through e0 = bbond(d) We0 and u = u(d / r_bond):
-//   dbond[b] = sum_f e0bar[b][f] (sum_n We0[n][f] dbbond_n/dd) + ubar[b] du/dd
-template <int F>
-__global__ void __launch_bounds__(256)
-k_bond_dist_bwd(int64_t nb, const float *__restrict__ e0bar, const float *__restrict__ We0, const float *__restrict__ bd,
-                BasisParams bp, const float *__restrict__ ubar, const float *__restrict__ bdu, float *__restrict__ dbond)
-{
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-    const int64_t b = (int64_t)blockIdx.x * 4 + wave;
-    if (b >= nb) return;
-    const int f = lane & (F - 1);
-    float bb[8], db[8];
-    radial_basis<true>(bd[b], bp, bb, db);
-    float v = 0.f;
-#pragma unroll
-    for (int n = 0; n < 8; ++n) v = fmaf(We0[n * F + f], db[n], v);
-    float part = (F == 64 || lane < F) ? e0bar[b * F + f] * v : 0.f;
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off, 64);
-    if (lane == 0) dbond[b] = fmaf(ubar[b], bdu[b], part);
-}
-
 // Forces of the bond part.  dE/dDelta_b = dbond rhat + (rbar - (rbar . rhat) rhat) / d for the bond vector
 // Delta_b = r_j + S C - r_i; it pulls on j with + and on i with -.  Gathered per centre: the bonds in which i
 // is the sender are the reverse bonds of its own.   F_i += sum_b (gDelta_b - gDelta_mirror(b))
@@ -1784,6 +1714,244 @@ __global__ void k_bond_force(int64_t N, const int64_t *__restrict__ bptr, const 
     floc[3 * i] += fx;
     floc[3 * i + 1] += fy;
     floc[3 * i + 2] += fz;
+}
+
+// ---- F x F products over the bonds, fused with what surrounds them
+//
+// Same tile scheme as the node kernel (32 bonds per wavefront step, packed operands in LDS, features x items
+// accumulators); each stage reads or writes every [bonds x F] array it touches once.
+//   HEAD       e0 = bbond(d) We0 (built in the tile);  P = e0 Wta;  Q = e0 Wtb
+//   TAIL       m = S Wt2;  e1 = e0 + u SiLU(m) (registers only);  wb_l = e1 Wb_l for every layer l
+//   LAYER_BWD  wbbar = abar_recv * g_send (built in the tile);  e1bar (+)= wbbar Wb_l^T
+//   MBAR       ubar = sum_f e1bar SiLU(m);  mbar = e1bar u SiLU'(m) (tile only);  Sbar = mbar Wt2^T
+//   E0BAR      e0bar = e1bar + Pbar Wta^T + Qbar Wtb^T (registers only);
+//              dbond = sum_f e0bar (We0^T dbbond/dd) + ubar du/dd
+enum { BOND_HEAD = 0, BOND_TAIL = 1, BOND_LAYER_BWD = 2, BOND_MBAR = 3, BOND_E0BAR = 4 };
+
+struct BondArgs {                      // one partition
+    int64_t n;                         // bonds
+    const float *d, *u, *du;           // [n] length, envelope at the bond cutoff, its derivative
+    const int32_t *edge, *sender;      // [n] edge index, sender row of a bond
+    const int32_t *recv;               // receiver row of an edge
+    const float *We0;                  // [8][F]
+    BasisParams bp;                    // radial basis at the bond cutoff
+    const float *W[4];                 // packed F x F operands of the stage (TAIL: Wt2, then the first layers' Wb)
+    const float *Wx;                   // TAIL: packed Wb of the layers beyond the third (read from global memory)
+    int n_layers;                      // TAIL
+    int first;                         // LAYER_BWD: store e1bar instead of accumulating
+    size_t wb_stride;                  // TAIL: floats between two layers' wb
+    float *e0, *P, *Q;                 // HEAD out; TAIL reads e0
+    const float *S;                    // TAIL in
+    float *m, *wb;                     // TAIL out; MBAR reads m
+    const float *abar, *g;             // LAYER_BWD in (node rows)
+    float *e1bar;                      // LAYER_BWD in/out; MBAR, E0BAR in
+    float *ubar, *Sbar;                // MBAR out; E0BAR reads ubar
+    const float *Pbar, *Qbar;          // E0BAR in
+    float *dbond;                      // E0BAR out
+};
+
+template <int STAGE> struct BondStage {
+    static constexpr int NW = (STAGE == BOND_TAIL) ? 8 : 4;   // wavefronts per block
+    static constexpr int NPACK = (STAGE == BOND_TAIL) ? 4 : (STAGE == BOND_HEAD || STAGE == BOND_E0BAR) ? 2 : 1;
+};
+
+template <int F, int STAGE>
+__global__ void __launch_bounds__(BondStage<STAGE>::NW * 64) k_bond_mlp(BondArgs A)
+{
+    using D = Dims<F>;
+    constexpr int NB = D::NB, FS = D::FS;
+    constexpr int NW = BondStage<STAGE>::NW, NPACK = BondStage<STAGE>::NPACK;
+    constexpr int LPR = TileRegs<F>::LPR, RPI = TileRegs<F>::RPI;
+    extern __shared__ float lds[];
+    float *packs = lds;
+    float *we0 = packs + NPACK * D::PACKF;
+    float *tiles = we0 + 8 * F;
+    const int n_lds_layers = (STAGE == BOND_TAIL) ? min(A.n_layers, 3) : 0;
+    const int n_packs = (STAGE == BOND_TAIL) ? 1 + n_lds_layers : NPACK;
+    for (int q = 0; q < n_packs; ++q)
+        for (int i = threadIdx.x; i < D::PACKF; i += NW * 64) packs[q * D::PACKF + i] = A.W[q][i];
+    if (STAGE == BOND_HEAD || STAGE == BOND_E0BAR)
+        for (int i = threadIdx.x; i < 8 * F; i += NW * 64) we0[i] = A.We0[i];
+    __syncthreads();
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int c32 = lane & 31, h = lane >> 5;
+    const int rr = lane / LPR, cc = (lane % LPR) * 4;   // this lane's row and first feature within a tile row group
+    float *tile = tiles + wave * D::TILE;
+    const int64_t n_tiles = (A.n + 31) / 32;
+    const int64_t stride = (int64_t)gridDim.x * NW;
+
+    // rows of a [bonds x F] array in accumulator layout: lane (c32, h) holds features 32 b + 8 a + 4 h + (0..3) of bond c32
+    auto load_rows = [&](const float *Y, int64_t row, bool ok, f32x4 (&v)[NB][4]) {
+#pragma unroll
+        for (int b = 0; b < NB; ++b)
+#pragma unroll
+            for (int a = 0; a < 4; ++a) {
+                v[b][a] = f32x4{0.f, 0.f, 0.f, 0.f};
+                if (ok) v[b][a] = *reinterpret_cast<const f32x4 *>(Y + row * F + 32 * b + 8 * a + 4 * h);
+            }
+    };
+    auto store_rows = [&](float *Y, int64_t row, bool ok, const f32x16 (&acc)[NB]) {
+        if (ok)
+#pragma unroll
+            for (int b = 0; b < NB; ++b)
+#pragma unroll
+                for (int a = 0; a < 4; ++a) {
+                    const f32x4 v = {acc[b][4 * a], acc[b][4 * a + 1], acc[b][4 * a + 2], acc[b][4 * a + 3]};
+                    *reinterpret_cast<f32x4 *>(Y + row * F + 32 * b + 8 * a + 4 * h) = v;
+                }
+    };
+
+    TileRegs<F> pre, pre2;
+    int64_t ti = (int64_t)blockIdx.x * NW + wave;
+    if (ti < n_tiles) {
+        if (STAGE == BOND_TAIL) fetch_tile<F>(pre, A.S, ti * 32, A.n, lane);
+        if (STAGE == BOND_MBAR) {
+            fetch_tile<F>(pre, A.e1bar, ti * 32, A.n, lane);
+            fetch_tile<F>(pre2, A.m, ti * 32, A.n, lane);
+        }
+        if (STAGE == BOND_E0BAR) fetch_tile<F>(pre, A.Pbar, ti * 32, A.n, lane);
+    }
+    for (; ti < n_tiles; ti += stride) {
+        const int64_t row0 = ti * 32;
+        const int64_t row = row0 + c32;
+        const bool ok = row < A.n;
+        const bool more = ti + stride < n_tiles;
+        f32x16 acc[NB];
+
+        if (STAGE == BOND_HEAD) {
+#pragma unroll
+            for (int r = 0; r < 32; r += RPI) {
+                const int64_t rw = row0 + r + rr;
+                const bool okr = rw < A.n;
+                float bb[8], db[8];
+                radial_basis<false>(okr ? A.d[rw] : A.bp.rc, A.bp, bb, db);
+                f32x4 v = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int n = 0; n < 8; ++n) {
+                    const f32x4 wv = *reinterpret_cast<const f32x4 *>(we0 + n * F + cc);
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) v[c] = fmaf(bb[n], wv[c], v[c]);
+                }
+                if (!okr) v = f32x4{0.f, 0.f, 0.f, 0.f};
+                *reinterpret_cast<f32x4 *>(tile + (r + rr) * FS + cc) = v;
+                if (okr) *reinterpret_cast<f32x4 *>(A.e0 + rw * F + cc) = v;
+            }
+            wave_lds_fence();
+            gemm_lds<F>(packs, tile, acc, lane);
+            store_rows(A.P, row, ok, acc);
+            gemm_lds<F>(packs + D::PACKF, tile, acc, lane);
+            store_rows(A.Q, row, ok, acc);
+            wave_lds_fence();
+        } else if (STAGE == BOND_TAIL) {
+            stash_tile<F>(pre, tile, lane);
+            wave_lds_fence();
+            f32x4 zv[NB][4];
+            load_rows(A.e0, row, ok, zv);
+            const float uc = ok ? A.u[row] : 0.f;
+            if (more) fetch_tile<F>(pre, A.S, (ti + stride) * 32, A.n, lane);
+            gemm_lds<F>(packs, tile, acc, lane);
+            wave_lds_fence();
+            store_rows(A.m, row, ok, acc);
+            f32x16 e1[NB];
+#pragma unroll
+            for (int b = 0; b < NB; ++b)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) e1[b][r] = fmaf(uc, silu_f(acc[b][r]), zv[b][r / 4][r % 4]);
+            for (int l = 0; l < n_lds_layers; ++l) {
+                gemm_regs<F>(packs + (1 + l) * D::PACKF, e1, acc, lane);
+                store_rows(A.wb + (size_t)l * A.wb_stride, row, ok, acc);
+            }
+            for (int l = 3; l < A.n_layers; ++l) {
+                gemm_regs<F>(A.Wx + (size_t)(l - 3) * D::PACKF, e1, acc, lane);
+                store_rows(A.wb + (size_t)l * A.wb_stride, row, ok, acc);
+            }
+        } else if (STAGE == BOND_LAYER_BWD) {
+#pragma unroll
+            for (int r = 0; r < 32; r += RPI) {
+                const int64_t rw = row0 + r + rr;
+                const bool okr = rw < A.n;
+                f32x4 v = {0.f, 0.f, 0.f, 0.f};
+                if (okr) {
+                    const int64_t i = A.recv[A.edge[rw]], j = A.sender[rw];
+                    const f32x4 va = *reinterpret_cast<const f32x4 *>(A.abar + i * F + cc);
+                    const f32x4 vg = *reinterpret_cast<const f32x4 *>(A.g + j * F + cc);
+                    v = va * vg;
+                }
+                *reinterpret_cast<f32x4 *>(tile + (r + rr) * FS + cc) = v;
+            }
+            wave_lds_fence();
+            f32x4 zv[NB][4];
+            load_rows(A.e1bar, row, ok && !A.first, zv);
+            gemm_lds<F>(packs, tile, acc, lane);
+            wave_lds_fence();
+#pragma unroll
+            for (int b = 0; b < NB; ++b)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[b][r] += zv[b][r / 4][r % 4];
+            store_rows(A.e1bar, row, ok, acc);
+        } else if (STAGE == BOND_MBAR) {
+#pragma unroll
+            for (int r = 0; r < 32; r += RPI) {
+                const int64_t rw = row0 + r + rr;
+                const bool okr = rw < A.n;
+                const f32x4 eb = pre.v[r / RPI], mm = pre2.v[r / RPI];   // zero past the end
+                const float ur = okr ? A.u[rw] : 0.f;
+                f32x4 v;
+                float part = 0.f;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    float sv, ds;
+                    silu_both(mm[c], sv, ds);
+                    v[c] = eb[c] * ur * ds;
+                    part = fmaf(eb[c], sv, part);
+                }
+#pragma unroll
+                for (int off = LPR / 2; off > 0; off >>= 1) part += __shfl_xor(part, off, 64);
+                if (okr && (lane % LPR) == 0) A.ubar[rw] = part;
+                *reinterpret_cast<f32x4 *>(tile + (r + rr) * FS + cc) = v;
+            }
+            wave_lds_fence();
+            if (more) {
+                fetch_tile<F>(pre, A.e1bar, (ti + stride) * 32, A.n, lane);
+                fetch_tile<F>(pre2, A.m, (ti + stride) * 32, A.n, lane);
+            }
+            gemm_lds<F>(packs, tile, acc, lane);
+            wave_lds_fence();
+            store_rows(A.Sbar, row, ok, acc);
+        } else {   // BOND_E0BAR
+            stash_tile<F>(pre, tile, lane);
+            wave_lds_fence();
+            fetch_tile<F>(pre2, A.Qbar, row0, A.n, lane);   // in flight during the first product
+            f32x4 zv[NB][4];
+            load_rows(A.e1bar, row, ok, zv);
+            gemm_lds<F>(packs, tile, acc, lane);
+            wave_lds_fence();
+            stash_tile<F>(pre2, tile, lane);
+            wave_lds_fence();
+            if (more) fetch_tile<F>(pre, A.Pbar, (ti + stride) * 32, A.n, lane);
+            gemm_lds<F, true>(packs + D::PACKF, tile, acc, lane);
+            wave_lds_fence();
+            float bb[8], db[8];
+            radial_basis<true>(ok ? A.d[row] : A.bp.rc, A.bp, bb, db);
+            float part = 0.f;
+#pragma unroll
+            for (int b = 0; b < NB; ++b)
+#pragma unroll
+                for (int a = 0; a < 4; ++a) {
+                    f32x4 v = {0.f, 0.f, 0.f, 0.f};   // (We0^T dbbond/dd) for this lane's four features
+#pragma unroll
+                    for (int n = 0; n < 8; ++n) {
+                        const f32x4 wv = *reinterpret_cast<const f32x4 *>(we0 + n * F + 32 * b + 8 * a + 4 * h);
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) v[c] = fmaf(wv[c], db[n], v[c]);
+                    }
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) part = fmaf(zv[b][a][c] + acc[b][4 * a + c], v[c], part);
+                }
+            part += __shfl_xor(part, 32, 64);
+            if (ok && h == 0) A.dbond[row] = fmaf(A.ubar[row], A.du[row], part);
+        }
+    }
 }
 
 inline unsigned blocks_for(int64_t n, int threads) { return (unsigned)((n + threads - 1) / threads); }
@@ -1839,6 +2007,25 @@ template <int F, int OP> int launch_node(mlip_graph *g, NodeBatch &b)
     // each block keeps its weight pack in LDS, so let it walk several tiles
     const unsigned blocks = (unsigned)std::min<int64_t>((n_tiles + 3) / 4, 2048);
     k_node<F, OP><<<blocks, 256, lds, g->stream>>>(b);
+    MLIP_HIP(hipGetLastError());
+    return MLIP_OK;
+}
+
+template <int F, int STAGE> int launch_bond_mlp(mlip_graph *g, const BondArgs &a)
+{
+    constexpr int NW = BondStage<STAGE>::NW;
+    constexpr size_t lds = sizeof(float) * (BondStage<STAGE>::NPACK * Dims<F>::PACKF + 8 * F + NW * Dims<F>::TILE);
+    static bool configured = false;
+    if (!configured) {
+        MLIP_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_bond_mlp<F, STAGE>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        configured = true;
+    }
+    if (a.n <= 0) return MLIP_OK;
+    const int64_t n_tiles = (a.n + 31) / 32;
+    // each block keeps its operand packs in LDS, so let it walk several tiles
+    const unsigned blocks = (unsigned)std::min<int64_t>((n_tiles + NW - 1) / NW, 8192 / NW);
+    k_bond_mlp<F, STAGE><<<blocks, NW * 64, lds, g->stream>>>(a);
     MLIP_HIP(hipGetLastError());
     return MLIP_OK;
 }
@@ -1998,18 +2185,34 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
     BasisParams bpb = bp;
     auto bstride = [&](SlabView &v) { return (size_t)std::max<int64_t>(v.bonds.n, 1) * F; };   // floats per [n][F] array
     auto wbslice = [&](SlabView &v, int l) { return v.bonds.wb.as<float>() + (size_t)l * bstride(v); };
-    // F x F product over the bonds of every partition: out = X P1 (OP_PROJ) or out += X P1 (OP_BWD_PROJ)
-    auto bond_gemm = [&](auto op, int slot, DevBuf BondGraph::*X, float *(*out)(SlabView &, int), int l) -> int {
-        constexpr int OP = decltype(op)::value;
-        return node_pass<F, OP>(g, views, P, bpk + (size_t)slot * ffp, nullptr, nullptr, [&](SlabView &v, NodeArgs &na) {
-            na.n_rows = v.bonds.n;
-            na.X = (v.bonds.*X).template as<float>();
-            na.Y = out(v, l);
-            na.Z = na.Y;
-        });
+    auto bond_args = [&](SlabView &v) {   // everything a stage of k_bond_mlp may touch; the stage's operands are set by the caller
+        BondGraph &BG = v.bonds;
+        BondArgs a{};
+        a.n = BG.n;
+        a.d = BG.d.as<float>();
+        a.u = BG.u.as<float>();
+        a.du = BG.du.as<float>();
+        a.edge = BG.edge.as<int32_t>();
+        a.sender = BG.sender.as<int32_t>();
+        a.recv = v.recv;
+        a.We0 = bw->We0;
+        a.bp = bpb;
+        a.wb_stride = bstride(v);
+        a.e0 = BG.e0.as<float>();
+        a.P = BG.P.as<float>();
+        a.Q = BG.Q.as<float>();
+        a.S = BG.S.as<float>();
+        a.m = BG.m.as<float>();
+        a.wb = BG.wb.as<float>();
+        a.abar = v.abar.as<float>();
+        a.e1bar = BG.e1bar.as<float>();
+        a.ubar = BG.ubar.as<float>();
+        a.Sbar = BG.Sbar.as<float>();
+        a.Pbar = BG.Pbar.as<float>();
+        a.Qbar = BG.Qbar.as<float>();
+        a.dbond = BG.dbond.as<float>();
+        return a;
     };
-    using OpProj = std::integral_constant<int, OP_PROJ>;
-    using OpAcc = std::integral_constant<int, OP_BWD_PROJ>;
     bool any_bonds = false;
     if (bw) {
         bpb.rc = bw->r_bond;
@@ -2020,7 +2223,7 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
         for (int p = 0; p < P; ++p) {
             BondGraph &BG = views[p].bonds;
             const size_t bs = bstride(views[p]), nb1 = (size_t)std::max<int64_t>(BG.n, 1);
-            DevBuf *fb[] = {&BG.e0, &BG.P, &BG.Q, &BG.S, &BG.m, &BG.e1, &BG.wbbar, &BG.e1bar, &BG.Sbar, &BG.Pbar, &BG.Qbar};
+            DevBuf *fb[] = {&BG.e0, &BG.P, &BG.Q, &BG.S, &BG.m, &BG.e1bar, &BG.Sbar, &BG.Pbar, &BG.Qbar};
             for (DevBuf *b : fb) MLIP_TRY(b->ensure(bs * sizeof(float)));
             MLIP_TRY(BG.wb.ensure(bs * sizeof(float) * (size_t)std::max(L, 1)));
             MLIP_TRY(BG.ubar.ensure(nb1 * sizeof(float)));
@@ -2043,14 +2246,12 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
             k_pack_ff<<<pb, 256, 0, s>>>(bw->Wb + l * ffp, F, 0, 1.0f, bpk + (6 + L + l) * ffp);
         }
         MLIP_HIP(hipGetLastError());
-        for (int p = 0; p < P; ++p) {
-            BondGraph &BG = views[p].bonds;
-            if (BG.n > 0)
-                k_bond_e0<F><<<blocks_for(BG.n * F, 256), 256, 0, s>>>(BG.n, BG.d.as<float>(), bpb, bw->We0, BG.e0.as<float>());
+        for (int p = 0; p < P; ++p) {   // e0, P = e0 Wta, Q = e0 Wtb
+            BondArgs a = bond_args(views[p]);
+            a.W[0] = bpk + 0 * ffp;
+            a.W[1] = bpk + 1 * ffp;
+            MLIP_TRY((launch_bond_mlp<F, BOND_HEAD>(g, a)));
         }
-        MLIP_HIP(hipGetLastError());
-        MLIP_TRY(bond_gemm(OpProj{}, 0, &BondGraph::e0, [](SlabView &v, int) { return v.bonds.P.as<float>(); }, 0));
-        MLIP_TRY(bond_gemm(OpProj{}, 1, &BondGraph::e0, [](SlabView &v, int) { return v.bonds.Q.as<float>(); }, 0));
         for (int p = 0; p < P; ++p) {
             SlabView &v = views[p];
             BondGraph &BG = v.bonds;
@@ -2060,17 +2261,14 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
                                                                           BG.Q.as<float>(), Wtc, BG.S.as<float>());
         }
         MLIP_HIP(hipGetLastError());
-        MLIP_TRY(bond_gemm(OpProj{}, 2, &BondGraph::S, [](SlabView &v, int) { return v.bonds.m.as<float>(); }, 0));
-        for (int p = 0; p < P; ++p) {
-            BondGraph &BG = views[p].bonds;
-            if (BG.n > 0)
-                k_bond_e1<F><<<blocks_for(BG.n * F, 256), 256, 0, s>>>(BG.n, BG.e0.as<float>(), BG.m.as<float>(),
-                                                                       BG.u.as<float>(), BG.e1.as<float>());
+        for (int p = 0; p < P; ++p) {   // m = S Wt2, e1 = e0 + u SiLU(m), wb_l = e1 Wb_l
+            BondArgs a = bond_args(views[p]);
+            a.W[0] = bpk + 2 * ffp;
+            for (int l = 0; l < std::min(L, 3); ++l) a.W[1 + l] = bpk + (6 + l) * ffp;
+            a.Wx = bpk + (6 + 3) * ffp;
+            a.n_layers = L;
+            MLIP_TRY((launch_bond_mlp<F, BOND_TAIL>(g, a)));
         }
-        MLIP_HIP(hipGetLastError());
-        for (int l = 0; l < L; ++l)
-            MLIP_TRY(bond_gemm(OpProj{}, 6 + l, &BondGraph::e1, [](SlabView &v, int ll) {
-                return v.bonds.wb.as<float>() + (size_t)ll * (size_t)std::max<int64_t>(v.bonds.n, 1) * F; }, l));
         prof_end(g);
     }
 
@@ -2182,7 +2380,7 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
         if (L > 0 && v.n_ghost > 0)
             MLIP_HIP(hipMemsetAsync(v.abar.as<float>() + (size_t)v.n_owned * F, 0, (size_t)v.n_ghost * rowb, s));
     }
-    if (any_bonds)
+    if (any_bonds && L == 0)   // no layer writes e1bar: the energy does not depend on the bonds
         for (int p = 0; p < P; ++p)
             if (views[p].bonds.n > 0)
                 MLIP_HIP(hipMemsetAsync(views[p].bonds.e1bar.p, 0, bstride(views[p]) * sizeof(float), s));
@@ -2232,18 +2430,24 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
                      : prec == kPrecF16x3 ? (launch_edge<F, kPrecF16x3>(g, eb, true)) : (launch_edge<F, kPrecF32>(g, eb, true)));
             prof_end(g);
         }
-        if (any_bonds) {   // bond term: dE/dwb, its share of gbar, and e1bar += wbbar Wb_l^T
+        if (any_bonds) {   // bond term: its share of gbar, and e1bar (+)= dE/dwb Wb_l^T
             prof_begin(g, MLIP_PROF_BOND);
             for (int p = 0; p < P; ++p) {
                 SlabView &v = views[p];
                 BondGraph &BG = v.bonds;
-                if (BG.n > 0)
-                    k_bond_bwd<F><<<blocks_for(v.n_owned, 4), 256, 0, s>>>(
+                if (BG.n > 0 && need_gbar)
+                    k_bond_gbar<F><<<blocks_for(v.n_owned, 4), 256, 0, s>>>(
                         v.n_owned, BG.ptr.as<int64_t>(), BG.sender.as<int32_t>(), BG.mirror.as<int32_t>(), wbslice(v, l),
-                        gslice(v, l), v.abar.as<float>(), BG.wbbar.as<float>(), need_gbar ? v.gbar.as<float>() : nullptr);
+                        v.abar.as<float>(), v.gbar.as<float>());
             }
             MLIP_HIP(hipGetLastError());
-            MLIP_TRY(bond_gemm(OpAcc{}, 6 + L + l, &BondGraph::wbbar, [](SlabView &v, int) { return v.bonds.e1bar.as<float>(); }, 0));
+            for (int p = 0; p < P; ++p) {   // e1bar (+)= (abar_recv * g_send) Wb_l^T
+                BondArgs a = bond_args(views[p]);
+                a.g = gslice(views[p], l);
+                a.W[0] = bpk + (6 + L + l) * ffp;
+                a.first = (l == L - 1);
+                MLIP_TRY((launch_bond_mlp<F, BOND_LAYER_BWD>(g, a)));
+            }
             prof_end(g);
         }
         if (need_gbar) {
@@ -2279,14 +2483,11 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
     if (any_bonds) {
         prof_begin(g, MLIP_PROF_BOND);
         const float *Wtc = bw->Wt1 + 2 * ffp;
-        for (int p = 0; p < P; ++p) {
-            BondGraph &BG = views[p].bonds;
-            if (BG.n > 0)   // mbar goes where S was: S is no longer needed
-                k_bond_mbar<F><<<blocks_for(BG.n, 4), 256, 0, s>>>(BG.n, BG.e1bar.as<float>(), BG.m.as<float>(), BG.u.as<float>(),
-                                                                   BG.S.as<float>(), BG.ubar.as<float>());
+        for (int p = 0; p < P; ++p) {   // ubar, Sbar = (e1bar u SiLU'(m)) Wt2^T
+            BondArgs a = bond_args(views[p]);
+            a.W[0] = bpk + 5 * ffp;
+            MLIP_TRY((launch_bond_mlp<F, BOND_MBAR>(g, a)));
         }
-        MLIP_HIP(hipGetLastError());
-        MLIP_TRY(bond_gemm(OpProj{}, 5, &BondGraph::S, [](SlabView &v, int) { return v.bonds.Sbar.as<float>(); }, 0));
         for (int p = 0; p < P; ++p) {
             SlabView &v = views[p];
             BondGraph &BG = v.bonds;
@@ -2296,16 +2497,12 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
                     Wtc, BG.Sbar.as<float>(), BG.Pbar.as<float>(), BG.Qbar.as<float>(), BG.ubar.as<float>(), BG.rbar.as<float>());
         }
         MLIP_HIP(hipGetLastError());
-        // e0bar = e1bar + Pbar Wta^T + Qbar Wtb^T, accumulated in place
-        MLIP_TRY(bond_gemm(OpAcc{}, 3, &BondGraph::Pbar, [](SlabView &v, int) { return v.bonds.e1bar.as<float>(); }, 0));
-        MLIP_TRY(bond_gemm(OpAcc{}, 4, &BondGraph::Qbar, [](SlabView &v, int) { return v.bonds.e1bar.as<float>(); }, 0));
-        for (int p = 0; p < P; ++p) {
-            BondGraph &BG = views[p].bonds;
-            if (BG.n > 0)
-                k_bond_dist_bwd<F><<<blocks_for(BG.n, 4), 256, 0, s>>>(BG.n, BG.e1bar.as<float>(), bw->We0, BG.d.as<float>(), bpb,
-                                                                       BG.ubar.as<float>(), BG.du.as<float>(), BG.dbond.as<float>());
+        for (int p = 0; p < P; ++p) {   // e0bar = e1bar + Pbar Wta^T + Qbar Wtb^T, and dE/dd of the bonds from it
+            BondArgs a = bond_args(views[p]);
+            a.W[0] = bpk + 3 * ffp;
+            a.W[1] = bpk + 4 * ffp;
+            MLIP_TRY((launch_bond_mlp<F, BOND_E0BAR>(g, a)));
         }
-        MLIP_HIP(hipGetLastError());
         prof_end(g);
     }
 

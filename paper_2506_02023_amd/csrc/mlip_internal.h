@@ -72,7 +72,7 @@ struct BondGraph {
     DevBuf d, u, du;        // f32 [n]   length, envelope u(d / r_bond), du/dd
     DevBuf rhat;            // f32 [n][3] unit vector from the centre to the neighbour's image
     // model workspace, [n][F] unless noted
-    DevBuf e0, P, Q, S, m, wb /* [L][n][F] */, e1bar, Sbar, Pbar, Qbar;
+    DevBuf P, Q, S, m, wb /* [L][n][F] */, e1bar, Sbar, Pbar, Qbar;
     DevBuf ubar, dbond;     // f32 [n]
     DevBuf rbar;            // f32 [n][3]
 };

@@ -1720,7 +1720,7 @@ __global__ void k_bond_force(int64_t N, const int64_t *__restrict__ bptr, const 
 //
 // Same tile scheme as the node kernel (32 bonds per wavefront step, packed operands in LDS, features x items
 // accumulators); each stage reads or writes every [bonds x F] array it touches once.
-//   HEAD       e0 = bbond(d) We0 (built in the tile);  P = e0 Wta;  Q = e0 Wtb
+//   HEAD       e0 = bbond(d) We0 (registers only, never stored: TAIL recomputes it);  P = e0 Wta;  Q = e0 Wtb
 //   TAIL       m = S Wt2;  e1 = e0 + u SiLU(m) (registers only);  wb_l = e1 Wb_l for every layer l
 //   LAYER_BWD  wbbar = abar_recv * g_send (built in the tile);  e1bar (+)= wbbar Wb_l^T
 //   MBAR       ubar = sum_f e1bar SiLU(m);  mbar = e1bar u SiLU'(m) (tile only);  Sbar = mbar Wt2^T
@@ -1733,14 +1733,14 @@ struct BondArgs {                      // one partition
     const float *d, *u, *du;           // [n] length, envelope at the bond cutoff, its derivative
     const int32_t *edge, *sender;      // [n] edge index, sender row of a bond
     const int32_t *recv;               // receiver row of an edge
-    const float *We0;                  // [8][F]
+    const float *We0p;                 // We0 packed for the K = 8 product (k_pack_w1)
     BasisParams bp;                    // radial basis at the bond cutoff
     const float *W[4];                 // packed F x F operands of the stage (TAIL: Wt2, then the first layers' Wb)
     const float *Wx;                   // TAIL: packed Wb of the layers beyond the third (read from global memory)
     int n_layers;                      // TAIL
     int first;                         // LAYER_BWD: store e1bar instead of accumulating
     size_t wb_stride;                  // TAIL: floats between two layers' wb
-    float *e0, *P, *Q;                 // HEAD out; TAIL reads e0
+    float *P, *Q;                      // HEAD out
     const float *S;                    // TAIL in
     float *m, *wb;                     // TAIL out; MBAR reads m
     const float *abar, *g;             // LAYER_BWD in (node rows)
@@ -1764,18 +1764,17 @@ __global__ void __launch_bounds__(BondStage<STAGE>::NW * 64) k_bond_mlp(BondArgs
     constexpr int LPR = TileRegs<F>::LPR, RPI = TileRegs<F>::RPI;
     extern __shared__ float lds[];
     float *packs = lds;
-    float *we0 = packs + NPACK * D::PACKF;
-    float *tiles = we0 + 8 * F;
+    float *tiles = packs + NPACK * D::PACKF;
     const int n_lds_layers = (STAGE == BOND_TAIL) ? min(A.n_layers, 3) : 0;
     const int n_packs = (STAGE == BOND_TAIL) ? 1 + n_lds_layers : NPACK;
     for (int q = 0; q < n_packs; ++q)
         for (int i = threadIdx.x; i < D::PACKF; i += NW * 64) packs[q * D::PACKF + i] = A.W[q][i];
-    if (STAGE == BOND_HEAD || STAGE == BOND_E0BAR)
-        for (int i = threadIdx.x; i < 8 * F; i += NW * 64) we0[i] = A.We0[i];
     __syncthreads();
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int c32 = lane & 31, h = lane >> 5;
     const int rr = lane / LPR, cc = (lane % LPR) * 4;   // this lane's row and first feature within a tile row group
+    RegPack1<F> W0;   // We0 as the A operands of the K = 8 product
+    if (STAGE == BOND_HEAD || STAGE == BOND_TAIL || STAGE == BOND_E0BAR) load_pack1<F>(W0, A.We0p, lane);
     float *tile = tiles + wave * D::TILE;
     const int64_t n_tiles = (A.n + 31) / 32;
     const int64_t stride = (int64_t)gridDim.x * NW;
@@ -1819,44 +1818,33 @@ __global__ void __launch_bounds__(BondStage<STAGE>::NW * 64) k_bond_mlp(BondArgs
         f32x16 acc[NB];
 
         if (STAGE == BOND_HEAD) {
-#pragma unroll
-            for (int r = 0; r < 32; r += RPI) {
-                const int64_t rw = row0 + r + rr;
-                const bool okr = rw < A.n;
-                float bb[8], db[8];
-                radial_basis<false>(okr ? A.d[rw] : A.bp.rc, A.bp, bb, db);
-                f32x4 v = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int n = 0; n < 8; ++n) {
-                    const f32x4 wv = *reinterpret_cast<const f32x4 *>(we0 + n * F + cc);
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) v[c] = fmaf(bb[n], wv[c], v[c]);
-                }
-                if (!okr) v = f32x4{0.f, 0.f, 0.f, 0.f};
-                *reinterpret_cast<f32x4 *>(tile + (r + rr) * FS + cc) = v;
-                if (okr) *reinterpret_cast<f32x4 *>(A.e0 + rw * F + cc) = v;
-            }
-            wave_lds_fence();
-            gemm_lds<F>(packs, tile, acc, lane);
+            float bb[8], db[8];
+            radial_basis<false>(ok ? A.d[row] : A.bp.rc, A.bp, bb, db);   // 0 at the cutoff
+            f32x16 e0[NB];
+            gemm_k8r<F>(W0, bb, e0, lane);
+            gemm_regs<F>(packs, e0, acc, lane);
             store_rows(A.P, row, ok, acc);
-            gemm_lds<F>(packs + D::PACKF, tile, acc, lane);
+            gemm_regs<F>(packs + D::PACKF, e0, acc, lane);
             store_rows(A.Q, row, ok, acc);
-            wave_lds_fence();
         } else if (STAGE == BOND_TAIL) {
             stash_tile<F>(pre, tile, lane);
             wave_lds_fence();
-            f32x4 zv[NB][4];
-            load_rows(A.e0, row, ok, zv);
             const float uc = ok ? A.u[row] : 0.f;
+            const float dc = ok ? A.d[row] : A.bp.rc;
             if (more) fetch_tile<F>(pre, A.S, (ti + stride) * 32, A.n, lane);
             gemm_lds<F>(packs, tile, acc, lane);
             wave_lds_fence();
             store_rows(A.m, row, ok, acc);
             f32x16 e1[NB];
+            {
+                float bb[8], db[8];
+                radial_basis<false>(dc, A.bp, bb, db);
+                gemm_k8r<F>(W0, bb, e1, lane);   // e0, as in HEAD
+            }
 #pragma unroll
             for (int b = 0; b < NB; ++b)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) e1[b][r] = fmaf(uc, silu_f(acc[b][r]), zv[b][r / 4][r % 4]);
+                for (int r = 0; r < 16; ++r) e1[b][r] = fmaf(uc, silu_f(acc[b][r]), e1[b][r]);
             for (int l = 0; l < n_lds_layers; ++l) {
                 gemm_regs<F>(packs + (1 + l) * D::PACKF, e1, acc, lane);
                 store_rows(A.wb + (size_t)l * A.wb_stride, row, ok, acc);
@@ -1933,21 +1921,13 @@ __global__ void __launch_bounds__(BondStage<STAGE>::NW * 64) k_bond_mlp(BondArgs
             wave_lds_fence();
             float bb[8], db[8];
             radial_basis<true>(ok ? A.d[row] : A.bp.rc, A.bp, bb, db);
+            f32x16 vv[NB];   // We0^T dbbond/dd
+            gemm_k8r<F>(W0, db, vv, lane);
             float part = 0.f;
 #pragma unroll
             for (int b = 0; b < NB; ++b)
 #pragma unroll
-                for (int a = 0; a < 4; ++a) {
-                    f32x4 v = {0.f, 0.f, 0.f, 0.f};   // (We0^T dbbond/dd) for this lane's four features
-#pragma unroll
-                    for (int n = 0; n < 8; ++n) {
-                        const f32x4 wv = *reinterpret_cast<const f32x4 *>(we0 + n * F + 32 * b + 8 * a + 4 * h);
-#pragma unroll
-                        for (int c = 0; c < 4; ++c) v[c] = fmaf(wv[c], db[n], v[c]);
-                    }
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) part = fmaf(zv[b][a][c] + acc[b][4 * a + c], v[c], part);
-                }
+                for (int r = 0; r < 16; ++r) part = fmaf(zv[b][r / 4][r % 4] + acc[b][r], vv[b][r], part);
             part += __shfl_xor(part, 32, 64);
             if (ok && h == 0) A.dbond[row] = fmaf(A.ubar[row], A.du[row], part);
         }
@@ -2014,7 +1994,7 @@ template <int F, int OP> int launch_node(mlip_graph *g, NodeBatch &b)
 template <int F, int STAGE> int launch_bond_mlp(mlip_graph *g, const BondArgs &a)
 {
     constexpr int NW = BondStage<STAGE>::NW;
-    constexpr size_t lds = sizeof(float) * (BondStage<STAGE>::NPACK * Dims<F>::PACKF + 8 * F + NW * Dims<F>::TILE);
+    constexpr size_t lds = sizeof(float) * (BondStage<STAGE>::NPACK * Dims<F>::PACKF + NW * Dims<F>::TILE);
     static bool configured = false;
     if (!configured) {
         MLIP_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_bond_mlp<F, STAGE>),
@@ -2181,7 +2161,8 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
     // All bonds and triplets of an owned centre are local to its partition, so this part needs no transfer.
     float *bpk = nullptr;        // packed F x F operands of the bond part
     const size_t ffp = (size_t)F * F;
-    // operand slots: 0 Wta (y = x W), 1 Wtb, 2 Wt2, 3 Wta^T, 4 Wtb^T, 5 Wt2^T, 6 + l Wb_l, 6 + L + l Wb_l^T
+    // operand slots: 0 Wta (y = x W), 1 Wtb, 2 Wt2, 3 Wta^T, 4 Wtb^T, 5 Wt2^T, 6 + l Wb_l, 6 + L + l Wb_l^T; after them We0
+    // packed for the K = 8 product
     BasisParams bpb = bp;
     auto bstride = [&](SlabView &v) { return (size_t)std::max<int64_t>(v.bonds.n, 1) * F; };   // floats per [n][F] array
     auto wbslice = [&](SlabView &v, int l) { return v.bonds.wb.as<float>() + (size_t)l * bstride(v); };
@@ -2195,10 +2176,9 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
         a.edge = BG.edge.as<int32_t>();
         a.sender = BG.sender.as<int32_t>();
         a.recv = v.recv;
-        a.We0 = bw->We0;
+        a.We0p = bpk + (size_t)(6 + 2 * L) * ffp;
         a.bp = bpb;
         a.wb_stride = bstride(v);
-        a.e0 = BG.e0.as<float>();
         a.P = BG.P.as<float>();
         a.Q = BG.Q.as<float>();
         a.S = BG.S.as<float>();
@@ -2223,7 +2203,7 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
         for (int p = 0; p < P; ++p) {
             BondGraph &BG = views[p].bonds;
             const size_t bs = bstride(views[p]), nb1 = (size_t)std::max<int64_t>(BG.n, 1);
-            DevBuf *fb[] = {&BG.e0, &BG.P, &BG.Q, &BG.S, &BG.m, &BG.e1bar, &BG.Sbar, &BG.Pbar, &BG.Qbar};
+            DevBuf *fb[] = {&BG.P, &BG.Q, &BG.S, &BG.m, &BG.e1bar, &BG.Sbar, &BG.Pbar, &BG.Qbar};
             for (DevBuf *b : fb) MLIP_TRY(b->ensure(bs * sizeof(float)));
             MLIP_TRY(BG.wb.ensure(bs * sizeof(float) * (size_t)std::max(L, 1)));
             MLIP_TRY(BG.ubar.ensure(nb1 * sizeof(float)));
@@ -2231,7 +2211,7 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
             MLIP_TRY(BG.rbar.ensure(nb1 * 3 * sizeof(float)));
             any_bonds = any_bonds || BG.n > 0;
         }
-        MLIP_TRY(g->bond_wpack.ensure((size_t)(6 + 2 * L) * ffp * sizeof(float)));
+        MLIP_TRY(g->bond_wpack.ensure(((size_t)(6 + 2 * L) * ffp + Dims<F>::PACK1) * sizeof(float)));
         bpk = g->bond_wpack.as<float>();
         prof_begin(g, MLIP_PROF_BOND);
         const float *Wta = bw->Wt1, *Wtb = bw->Wt1 + ffp, *Wtc = bw->Wt1 + 2 * ffp;
@@ -2245,8 +2225,9 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
             k_pack_ff<<<pb, 256, 0, s>>>(bw->Wb + l * ffp, F, 1, 1.0f, bpk + (6 + l) * ffp);
             k_pack_ff<<<pb, 256, 0, s>>>(bw->Wb + l * ffp, F, 0, 1.0f, bpk + (6 + L + l) * ffp);
         }
+        k_pack_w1<<<blocks_for(Dims<F>::PACK1, 256), 256, 0, s>>>(bw->We0, F, 1.0f, bpk + (size_t)(6 + 2 * L) * ffp);
         MLIP_HIP(hipGetLastError());
-        for (int p = 0; p < P; ++p) {   // e0, P = e0 Wta, Q = e0 Wtb
+        for (int p = 0; p < P; ++p) {   // P = e0 Wta, Q = e0 Wtb with e0 = bbond(d) We0
             BondArgs a = bond_args(views[p]);
             a.W[0] = bpk + 0 * ffp;
             a.W[1] = bpk + 1 * ffp;

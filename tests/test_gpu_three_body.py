@@ -61,6 +61,15 @@ def test_three_body_width_32_and_two_layers():
     _check(c["positions"], c["cell"], c["species"], c, weights=w, label="F = 32, L = 2")
 
 
+def test_three_body_five_layers():
+    """More layers than the fused bond kernel keeps operand packs for in LDS (the later layers' packs are read from
+    global memory)."""
+    c = wl.make_config(4, n=3)
+    w = wl.rmp_weights(4, 64, 5, 78)
+    w.update(wl.three_body_weights(64, 5, 78))
+    _check(c["positions"], c["cell"], c["species"], c, weights=w, label="F = 64, L = 5")
+
+
 @pytest.mark.parametrize("seed", [0, 3])
 def test_three_body_triclinic(seed):
     """Thin triclinic cells: several images of the same neighbour among the bonds, uneven bond counts."""

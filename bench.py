@@ -31,10 +31,10 @@ def flops_bwd_edge(F, K=8):
 
 
 # HBM bytes per launch (one layer over all 8 slabs) on the default workload, from rocprofv3 --pmc FETCH_SIZE and
-# WRITE_SIZE (profiles/edge_traffic_configs3_8slabs.md): KiB x copy-kernel scale (1.9980 for FETCH_SIZE, 1.000 for
+# WRITE_SIZE (profiles/edge_traffic_configs3_8slabs.md): KiB x copy-kernel scale (1.9975 for FETCH_SIZE, 1.000 for
 # WRITE_SIZE)
-TRAFFIC_BWD_LAUNCH_BYTES = (12708060 * 1.9980 + 996390 * 1.0) * 1024
-TRAFFIC_FWD_LAUNCH_BYTES = (4030352 * 1.9980 + 7878067 * 1.0) * 1024
+TRAFFIC_BWD_LAUNCH_BYTES = (11700752 * 1.9975 + 999817 * 1.0) * 1024
+TRAFFIC_FWD_LAUNCH_BYTES = (2490002 * 1.9975 + 7878067 * 1.0) * 1024
 
 
 def cpu_baseline(cfg_index, n_cells):

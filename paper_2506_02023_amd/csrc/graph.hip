@@ -192,8 +192,10 @@ __global__ void k_bin(int64_t N, const double *__restrict__ pos, const int32_t *
             zmin = min(zmin, __shfl_xor(zmin, off, 64));
         }
         if ((threadIdx.x & 63) == 0) {
-            if (zmax > 0) atomicMax(err + 1, zmax);
-            if (zmin < 0) atomicMin(err + 2, zmin);
+            // the running extremes only move one way, so a wavefront that cannot move them skips its atomics
+            // (thousands of atomics on one address would serialise and dominate this kernel)
+            if (zmax > __atomic_load_n(err + 1, __ATOMIC_RELAXED)) atomicMax(err + 1, zmax);
+            if (zmin < __atomic_load_n(err + 2, __ATOMIC_RELAXED)) atomicMin(err + 2, zmin);
         }
     }
     if (i >= N) return;

@@ -37,6 +37,22 @@ TRAFFIC_BWD_LAUNCH_BYTES = (11700752 * 1.9975 + 999817 * 1.0) * 1024
 TRAFFIC_FWD_LAUNCH_BYTES = (2490002 * 1.9975 + 7878067 * 1.0) * 1024
 
 
+# fp32 vector peak of the chip (256 CUs x 4 SIMDs x 16 lanes x 2 flop per FMA x 2.4 GHz = 78.6 TFLOP/s per issue slot;
+# the published 157.3 TFLOP/s counts the dual-issue/packed rate): the bound of the triplet kernels of the three-body variant
+PEAK_FP32_VECTOR_TFLOPS = 157.3
+
+
+def flops_triplet_fwd(F, A=8):
+    """Per ordered triplet: h = P + Q + T(c) Wtc (2 + 2A per feature), SiLU (5), u * SiLU accumulated (2)."""
+    return F * (2 + 2 * A + 5 + 2)
+
+
+def flops_triplet_bwd(F, A=8):
+    """Per ordered triplet, each evaluated once: h again (2 + 2A), SiLU and SiLU' (8), hbar = Sbar u SiLU' (2), sums into
+    Pbar, Qbar (2), ubar (2), dT/dc Wtc (2A), its product with hbar (2)."""
+    return F * (2 + 2 * A + 8 + 2 + 2 + 2 + 2 * A + 2)
+
+
 def cpu_baseline(cfg_index, n_cells):
     """The oracle, as it stands, on a bounded sample of the same workload (same recipe, smaller box)."""
     import workloads as wl
@@ -170,6 +186,23 @@ def main():
     roof_fwd = edge_roofline("edge_fwd", f"k_edge_fwd<{F}> (forward edge step)", flops_fwd_edge(F),
                              TRAFFIC_FWD_LAUNCH_BYTES)
     roof = roof_fwd if roof_fwd["ms_per_step"] >= roof_bwd["ms_per_step"] else roof_bwd   # the dominant kernel
+    roof_trip = {}
+    if three_body:
+        _, bptr = g.bonds()
+        cnt = np.diff(bptr).astype(np.int64)
+        n_triplets = int((cnt * (cnt - 1)).sum())
+        for group, kernel, fl in (("triplet_fwd", f"k_triplet_fwd<{F}>", flops_triplet_fwd(F)),
+                                  ("triplet_bwd", f"k_triplet_bwd<{F}>", flops_triplet_bwd(F))):
+            ms, n = prof[group]
+            per_launch = n_triplets * fl * args.steps / max(n, 1)
+            avg_ms = ms / max(n, 1)
+            ach = per_launch / (avg_ms * 1e-3) / 1e12 if avg_ms > 0 else 0.0
+            roof_trip[group] = {"kernel": kernel, "bound": "alu", "achieved": ach, "peak": PEAK_FP32_VECTOR_TFLOPS,
+                                "unit": "TFLOP/s", "frac": ach / PEAK_FP32_VECTOR_TFLOPS, "traffic": None,
+                                "avg_launch_ms": avg_ms, "launches": int(n), "flops_per_launch": per_launch,
+                                "ms_per_step": ms / args.steps, "triplets": n_triplets}
+        if roof_trip["triplet_bwd"]["ms_per_step"] > roof["ms_per_step"]:
+            roof = roof_trip["triplet_bwd"]
 
     res = {
         "metric": "atoms/s (energy+forces)", "value": N / (dt / args.steps), "unit": "atoms/s", "n_gpus": 1,
@@ -187,6 +220,8 @@ def main():
         "energy": energy, "net_force_max_component": fsum,
         "roofline": roof, "roofline_edge_fwd": roof_fwd, "roofline_edge_bwd": roof_bwd,
     }
+    for k, v in roof_trip.items():
+        res["roofline_" + k] = v
     if split_ms is not None:
         res["split_fp16_products"] = {"ms_per_step": split_ms, "value": N / (split_ms * 1e-3), "unit": "atoms/s",
                                       "energy": energy_split,

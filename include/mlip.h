@@ -239,8 +239,10 @@ enum {
     MLIP_PROF_EDGE_BWD = 3,
     MLIP_PROF_GHOST = 4,   /* ghost row copies and gradient add-backs         */
     MLIP_PROF_FORCE = 5,   /* force assembly and energy reduction            */
-    MLIP_PROF_BOND = 6,    /* three-body variant: bond list, triplet update and its reverse */
-    MLIP_PROF_COUNT = 7
+    MLIP_PROF_BOND = 6,    /* three-body variant: bond list and the kernels over bonds */
+    MLIP_PROF_TRIPLET_FWD = 7,   /* three-body variant: the triplet sum           */
+    MLIP_PROF_TRIPLET_BWD = 8,   /* three-body variant: its reverse               */
+    MLIP_PROF_COUNT = 9
 };
 int mlip_profile_enable(mlip_graph_t *graph, int32_t on);
 int mlip_profile_read(mlip_graph_t *graph, float *ms /*HOST [MLIP_PROF_COUNT]*/,

@@ -16,7 +16,7 @@ _LIB_PATH = os.path.join(_HERE, "libmlip.so")
 
 MODE_WHOLE, MODE_SLABS = 0, 1
 PRECISION_FP32, PRECISION_BF16, PRECISION_FP32_SPLIT = 0, 1, 2
-PROF_GROUPS = ("graph", "node", "edge_fwd", "edge_bwd", "ghost", "force", "bond")
+PROF_GROUPS = ("graph", "node", "edge_fwd", "edge_bwd", "ghost", "force", "bond", "triplet_fwd", "triplet_bwd")
 
 
 class MlipError(RuntimeError):

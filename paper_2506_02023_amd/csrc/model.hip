@@ -2233,6 +2233,8 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
             a.W[1] = bpk + 1 * ffp;
             MLIP_TRY((launch_bond_mlp<F, BOND_HEAD>(g, a)));
         }
+        prof_end(g);
+        prof_begin(g, MLIP_PROF_TRIPLET_FWD);
         for (int p = 0; p < P; ++p) {
             SlabView &v = views[p];
             BondGraph &BG = v.bonds;
@@ -2242,6 +2244,8 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
                                                                           BG.Q.as<float>(), Wtc, BG.S.as<float>());
         }
         MLIP_HIP(hipGetLastError());
+        prof_end(g);
+        prof_begin(g, MLIP_PROF_BOND);
         for (int p = 0; p < P; ++p) {   // m = S Wt2, e1 = e0 + u SiLU(m), wb_l = e1 Wb_l
             BondArgs a = bond_args(views[p]);
             a.W[0] = bpk + 2 * ffp;
@@ -2469,6 +2473,8 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
             a.W[0] = bpk + 5 * ffp;
             MLIP_TRY((launch_bond_mlp<F, BOND_MBAR>(g, a)));
         }
+        prof_end(g);
+        prof_begin(g, MLIP_PROF_TRIPLET_BWD);
         for (int p = 0; p < P; ++p) {
             SlabView &v = views[p];
             BondGraph &BG = v.bonds;
@@ -2478,6 +2484,8 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
                     Wtc, BG.Sbar.as<float>(), BG.Pbar.as<float>(), BG.Qbar.as<float>(), BG.ubar.as<float>(), BG.rbar.as<float>());
         }
         MLIP_HIP(hipGetLastError());
+        prof_end(g);
+        prof_begin(g, MLIP_PROF_BOND);
         for (int p = 0; p < P; ++p) {   // e0bar = e1bar + Pbar Wta^T + Qbar Wtb^T, and dE/dd of the bonds from it
             BondArgs a = bond_args(views[p]);
             a.W[0] = bpk + 3 * ffp;

@@ -1538,13 +1538,19 @@ __device__ inline void chebyshev(float c, float (&T)[kAngle], float (&dT)[kAngle
 }
 
 // S[b1][f] = sum_{b2 != b1, same centre} u[b2] SiLU(P[b1][f] + Q[b2][f] + sum_n T_n(c) Wtc[n][f])
-// One wavefront per centre.  The angle basis does not depend on the feature: for a fixed b1 it is evaluated for
-// 64 bonds b2 at once (lane = b2) and handed to the feature lanes through wave-uniform registers.
+// One wavefront per centre, lane = feature.  The angle basis does not depend on the feature: for a fixed b1 it is
+// evaluated for 64 bonds b2 at once (lane = b2) and handed to the feature lanes through wave-uniform registers.
+// Centres with at most kPairBondsFwd bonds are processed by unordered pairs {a, o}: T(c) Wtc is shared by the
+// triplets (a, o) and (o, a); the term of bond a accumulates in a register, the term of bond o in a per-lane LDS row.
+constexpr int kPairBondsFwd = 32;
+
 template <int F>
 __global__ void __launch_bounds__(256)
 k_triplet_fwd(int64_t N, const int64_t *__restrict__ bptr, const float *__restrict__ rhat, const float *__restrict__ u,
               const float *__restrict__ P, const float *__restrict__ Q, const float *__restrict__ Wtc, float *__restrict__ S)
 {
+    constexpr int NB = kPairBondsFwd;
+    __shared__ float acc_lds[4][NB * 64];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int64_t i = (int64_t)blockIdx.x * 4 + wave;
     if (i >= N) return;
@@ -1553,6 +1559,38 @@ k_triplet_fwd(int64_t N, const int64_t *__restrict__ bptr, const float *__restri
 #pragma unroll
     for (int n = 0; n < kAngle; ++n) wc[n] = Wtc[n * F + f];
     const int64_t b0 = bptr[i], b1e = bptr[i + 1];
+    const int nb = (int)(b1e - b0);
+    if (nb <= 0) return;
+    if (nb <= NB) {
+        float *accS = acc_lds[wave];
+        for (int b = 0; b < nb; ++b) accS[b * 64 + lane] = 0.f;
+        const int64_t bl = min(b0 + lane, b1e - 1);
+        const float xl = rhat[3 * bl], yl = rhat[3 * bl + 1], zl = rhat[3 * bl + 2], ul = u[bl];   // lane = bond
+        for (int a = 0; a < nb; ++a) {
+            const int64_t ba = b0 + a;
+            const float pa = P[ba * F + f], qa = Q[ba * F + f];
+            const float ua = readlane_f32(ul, a);
+            float T[kAngle], dT[kAngle];
+            chebyshev(fmaf(readlane_f32(xl, a), xl, fmaf(readlane_f32(yl, a), yl, readlane_f32(zl, a) * zl)), T, dT);   // lane = o
+            float acc = 0.f;
+            for (int o = a + 1; o < nb; ++o) {
+                float tw = wc[0];   // T_0 = 1
+#pragma unroll
+                for (int n = 1; n < kAngle; ++n) tw = fmaf(readlane_f32(T[n], o), wc[n], tw);
+                const float po = P[(b0 + o) * F + f], qo = Q[(b0 + o) * F + f];
+                const float so = accS[o * 64 + lane];   // per-lane slot (read early, written at the end of the step;
+                                                        // LDS float atomics measured an order of magnitude slower)
+                acc = fmaf(readlane_f32(ul, o), silu_f(pa + qo + tw), acc);       // triplet (b1 = a, b2 = o)
+                accS[o * 64 + lane] = fmaf(ua, silu_f(po + qa + tw), so);        // triplet (b1 = o, b2 = a)
+            }
+            accS[a * 64 + lane] += acc;
+        }
+        wave_lds_fence();
+        if (F == 64 || lane < F)
+            for (int b = 0; b < nb; ++b) S[(b0 + b) * F + f] = accS[b * 64 + lane];
+        return;
+    }
+    // any number of bonds, no LDS: ordered pairs, bonds b2 in groups of 64
     for (int64_t c0 = b0; c0 < b1e; c0 += 64) {   // bonds b2 in groups of 64 (one group unless the centre has more)
         const int nl = (int)min((int64_t)64, b1e - c0);
         const int64_t bl = min(c0 + lane, b1e - 1);
@@ -1614,19 +1652,33 @@ k_bond_gbar(int64_t N, const int64_t *__restrict__ bptr, const int32_t *__restri
     if (F == 64 || lane < F) gbar[i * F + f] += acc;
 }
 
-// Reverse of k_triplet_fwd for one centre per wavefront.  Pbar[b1] and rbar[b1] accumulate over the inner
-// loop in registers; Qbar[b2], ubar[b2] and rbar[b2] are indexed by the inner bond, so they are accumulated in
-// a second sweep with the roles of the loops exchanged (h is recomputed there) - no LDS, any number of bonds.
-template <int F>
-__global__ void __launch_bounds__(256)
-k_triplet_bwd(int64_t N, const int64_t *__restrict__ bptr, const float *__restrict__ rhat, const float *__restrict__ u,
-              const float *__restrict__ P, const float *__restrict__ Q, const float *__restrict__ Wtc,
-              const float *__restrict__ Sbar, float *__restrict__ Pbar, float *__restrict__ Qbar,
-              float *__restrict__ ubar, float *__restrict__ rbar)
+// sum over the 64 lanes of a wavefront on the data-parallel-primitive path (no LDS); the total is returned
+// as a wave-uniform value
+template <int CTRL, int ROW_MASK, bool BOUND> __device__ inline float dpp_shifted(float v)
 {
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-    const int64_t i = (int64_t)blockIdx.x * 4 + wave;
-    if (i >= N) return;
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROW_MASK, 0xf, BOUND));
+}
+__device__ inline float wave_sum(float v)
+{
+    v += dpp_shifted<0x111, 0xf, true>(v);    // row_shr:1  (lanes shifted in from outside a row of 16 read 0)
+    v += dpp_shifted<0x112, 0xf, true>(v);    // row_shr:2
+    v += dpp_shifted<0x114, 0xf, true>(v);    // row_shr:4
+    v += dpp_shifted<0x118, 0xf, true>(v);    // row_shr:8: lane 15 of every row holds the row's sum
+    v += dpp_shifted<0x142, 0xa, false>(v);   // row_bcast:15 into rows 1 and 3
+    v += dpp_shifted<0x143, 0xc, false>(v);   // row_bcast:31 into rows 2 and 3: lane 63 holds the total
+    return readlane_f32(v, 63);
+}
+
+// Reverse of k_triplet_fwd for one centre, any number of bonds, no LDS.  Pbar[b1] and rbar[b1] accumulate over the
+// inner loop in registers; Qbar[b2], ubar[b2] and rbar[b2] are indexed by the inner bond, so they are accumulated
+// in a second sweep with the roles of the loops exchanged (h is recomputed there): every triplet is evaluated twice.
+template <int F>
+__device__ inline void
+triplet_bwd_sweep(int64_t i, int lane, const int64_t *__restrict__ bptr, const float *__restrict__ rhat,
+                  const float *__restrict__ u, const float *__restrict__ P, const float *__restrict__ Q,
+                  const float *__restrict__ Wtc, const float *__restrict__ Sbar, float *__restrict__ Pbar,
+                  float *__restrict__ Qbar, float *__restrict__ ubar, float *__restrict__ rbar)
+{
     const int f = lane & (F - 1);
     const bool on = (F == 64 || lane < F);
     float wc[kAngle];
@@ -1684,6 +1736,108 @@ k_triplet_bwd(int64_t N, const int64_t *__restrict__ bptr, const float *__restri
             rbar[3 * ba + 1] = ry;
             rbar[3 * ba + 2] = rz;
         }
+    }
+}
+
+
+constexpr int kPairBonds = 16;   // bonds per centre up to which the pair-wise reverse triplet kernel applies
+
+// Reverse of k_triplet_fwd, one centre per wavefront, lane = feature.  Centres with at most kPairBonds bonds
+// (12 on the benchmark's lattice) are processed by unordered pairs {a, o}: the angle terms T(c) Wtc and
+// dT/dc Wtc are shared by the triplets (a, o) and (o, a), and each triplet is evaluated once.  What a pair
+// contributes to bond a stays in registers; what it contributes to bond o goes to per-lane accumulators in LDS
+// (rows accP, accQ, accU of 64 floats per bond), and dE/dc of the pair, reduced over the features, into a small
+// table from which rbar is assembled at the end with lane = bond.
+template <int F>
+__global__ void __launch_bounds__(256)
+k_triplet_bwd(int64_t N, const int64_t *__restrict__ bptr, const float *__restrict__ rhat, const float *__restrict__ u,
+              const float *__restrict__ P, const float *__restrict__ Q, const float *__restrict__ Wtc,
+              const float *__restrict__ Sbar, float *__restrict__ Pbar, float *__restrict__ Qbar,
+              float *__restrict__ ubar, float *__restrict__ rbar)
+{
+    constexpr int NB = kPairBonds;
+    __shared__ float acc_lds[4][3 * NB * 64 + NB * NB];
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int64_t i = (int64_t)blockIdx.x * 4 + wave;
+    if (i >= N) return;
+    const int64_t b0 = bptr[i];
+    const int n = (int)(bptr[i + 1] - b0);
+    if (n > NB) {
+        triplet_bwd_sweep<F>(i, lane, bptr, rhat, u, P, Q, Wtc, Sbar, Pbar, Qbar, ubar, rbar);
+        return;
+    }
+    if (n <= 0) return;
+    const int f = lane & (F - 1);
+    const bool on = (F == 64 || lane < F);
+    float wc[kAngle];
+#pragma unroll
+    for (int k = 0; k < kAngle; ++k) wc[k] = Wtc[k * F + f];
+    float *accP = acc_lds[wave], *accQ = accP + NB * 64, *accU = accQ + NB * 64, *dsym = accU + NB * 64;
+    for (int b = 0; b < n; ++b) {
+        accP[b * 64 + lane] = 0.f;
+        accQ[b * 64 + lane] = 0.f;
+        accU[b * 64 + lane] = 0.f;
+    }
+    for (int a = 0; a < n; ++a) {
+        const int64_t ba = b0 + a;
+        const float xa = rhat[3 * ba], ya = rhat[3 * ba + 1], za = rhat[3 * ba + 2];
+        const float pa = P[ba * F + f], qa = Q[ba * F + f], sa = Sbar[ba * F + f], ua = u[ba];
+        float pacc = 0.f, qacc = 0.f, uacc = 0.f;
+        float drow = 0.f;   // lane o: dE/dc of the pair {a, o}
+        for (int o = a + 1; o < n; ++o) {
+            const int64_t bo = b0 + o;
+            const float c = fmaf(xa, rhat[3 * bo], fmaf(ya, rhat[3 * bo + 1], za * rhat[3 * bo + 2]));
+            float T[kAngle], dT[kAngle];
+            chebyshev(c, T, dT);
+            float tw = 0.f, dw = 0.f;   // T(c) Wtc and dT(c)/dc Wtc for this lane's feature
+#pragma unroll
+            for (int k = 0; k < kAngle; ++k) {
+                tw = fmaf(T[k], wc[k], tw);
+                dw = fmaf(dT[k], wc[k], dw);
+            }
+            const float po = P[bo * F + f], qo = Q[bo * F + f], so = Sbar[bo * F + f], uo = u[bo];
+            // bond o's accumulators: per-lane slots, read here and written at the end of the step (LDS float
+            // atomics measured an order of magnitude slower than this read-modify-write)
+            const float aq = accQ[o * 64 + lane], ap = accP[o * 64 + lane], au = accU[o * 64 + lane];
+            float s1, ds1, s2, ds2;
+            silu_both(pa + qo + tw, s1, ds1);   // triplet (b1 = a, b2 = o)
+            silu_both(po + qa + tw, s2, ds2);   // triplet (b1 = o, b2 = a)
+            const float h1 = sa * uo * ds1, h2 = so * ua * ds2;
+            pacc += h1;
+            qacc += h2;
+            uacc = fmaf(so, s2, uacc);
+            accQ[o * 64 + lane] = aq + h1;
+            accP[o * 64 + lane] = ap + h2;
+            accU[o * 64 + lane] = fmaf(sa, s1, au);
+            const float tot = wave_sum(on ? (h1 + h2) * dw : 0.f);
+            drow = (lane == o) ? tot : drow;
+        }
+        accP[a * 64 + lane] += pacc;
+        accQ[a * 64 + lane] += qacc;
+        accU[a * 64 + lane] += uacc;
+        if (lane < NB) dsym[a * NB + lane] = drow;   // entries o > a
+    }
+    wave_lds_fence();
+    for (int b = 0; b < n; ++b) {
+        if (on) {
+            Pbar[(b0 + b) * F + f] = accP[b * 64 + lane];
+            Qbar[(b0 + b) * F + f] = accQ[b * 64 + lane];
+        }
+        const float ub = wave_sum(on ? accU[b * 64 + lane] : 0.f);
+        if (lane == 0) ubar[b0 + b] += ub;
+    }
+    if (lane < n) {   // lane = bond: rbar_b = sum over the other bonds o of dE/dc{b, o} rhat_o
+        float rx = 0.f, ry = 0.f, rz = 0.f;
+        for (int o = 0; o < n; ++o) {
+            if (o == lane) continue;
+            const float dv = (o > lane) ? dsym[lane * NB + o] : dsym[o * NB + lane];
+            rx = fmaf(dv, rhat[3 * (b0 + o)], rx);
+            ry = fmaf(dv, rhat[3 * (b0 + o) + 1], ry);
+            rz = fmaf(dv, rhat[3 * (b0 + o) + 2], rz);
+        }
+        rbar[3 * (b0 + lane)] = rx;
+        rbar[3 * (b0 + lane) + 1] = ry;
+        rbar[3 * (b0 + lane) + 2] = rz;
     }
 }
 

@@ -70,6 +70,17 @@ def test_three_body_five_layers():
     _check(c["positions"], c["cell"], c["species"], c, weights=w, label="F = 64, L = 5")
 
 
+@pytest.mark.parametrize("r_bond,expected", [(3.9, 18), (4.8, 42)])
+def test_three_body_many_bonds_per_centre(r_bond, expected):
+    """Bond cutoffs that take in the second and third neighbour shells: 18 and about 42 bonds per centre, beyond what
+    the pair-wise triplet kernels keep accumulators for (16 reverse, 32 forward), so their general paths run."""
+    c = dict(wl.make_config(4, n=3), r_bond=r_bond)
+    g = og.build_graph(c["positions"], c["cell"], c["r_cut"])
+    _, bptr, _ = tb.bond_graph(c["positions"], c["cell"], g, r_bond)
+    assert abs(np.diff(bptr).mean() - expected) < 3 and np.diff(bptr).max() > (16 if expected == 18 else 32)
+    _check(c["positions"], c["cell"], c["species"], c, label=f"r_bond = {r_bond}")
+
+
 @pytest.mark.parametrize("seed", [0, 3])
 def test_three_body_triclinic(seed):
     """Thin triclinic cells: several images of the same neighbour among the bonds, uneven bond counts."""

@@ -68,7 +68,8 @@ constexpr float kSiluScaleInv = -0.6931471805599453f;
 __device__ inline float sigmoid_scaled(float tp) { return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(tp)); }
 
 struct BasisParams {
-    float rc, inv_rc, c0, c1, c2, pc0, pc1, pc2;  // envelope coefficients and those of its derivative
+    float rc, inv_rc;
+    float pc0;   // p (p + 1) (p + 2) / 2, the factor of the envelope's derivative
     int p;
 };
 
@@ -84,14 +85,22 @@ __device__ inline void radial_basis(float d, const BasisParams &bp, float (&b)[8
                z2 * (-2.75573192e-7f + z2 * 2.08767570e-9f)))));
     float c1v = -z * (1.0f + z2 * (-1.66666667e-1f + z2 * (8.33333333e-3f + z2 * (-1.98412698e-4f +
                 z2 * (2.75573192e-6f + z2 * (-2.50521084e-8f + z2 * 1.60590438e-10f))))));
+    // envelope in factored form, free of cancellation near the cutoff where it goes to zero with its first two
+    // derivatives:  u(x) = (1 - x)^3 sum_{k < p} C(k + 2, 2) x^k  (the same polynomial as 1 - (p+1)(p+2)/2 x^p
+    // + p(p+2) x^(p+1) - p(p+1)/2 x^(p+2)),  u'(x) = -p(p+1)(p+2)/2 x^(p-1) (1 - x)^2
+    const float w1 = 1.0f - x;
     float xpm1 = 1.0f;
-    for (int k = 0; k < bp.p - 1; ++k) xpm1 *= x;
-    const float xp = xpm1 * x;
-    const float u = 1.0f - xp * (bp.c0 - x * (bp.c1 - bp.c2 * x));
+    float q = (float)(bp.p * (bp.p + 1) / 2);
+    for (int k = bp.p - 2; k >= 0; --k) {
+        q = fmaf(q, x, (float)((k + 1) * (k + 2) / 2));
+        xpm1 *= x;
+    }
+    const float w2 = w1 * w1;
+    const float u = w2 * w1 * q;
     const float inv_d = __builtin_amdgcn_rcpf(d);
     float du_term = 0.f;  // u'/rc - u/d
     if (DERIV) {
-        const float du = -xpm1 * (bp.pc0 - x * (bp.pc1 - bp.pc2 * x));
+        const float du = -bp.pc0 * xpm1 * w2;
         du_term = du * bp.inv_rc - u * inv_d;
     }
     const float u_rc = u * bp.inv_rc;
@@ -2267,12 +2276,7 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
     bp.inv_rc = (float)(1.0 / g->r_cut);
     bp.p = w->p;
     const double pd = (double)w->p;
-    bp.c0 = (float)((pd + 1) * (pd + 2) / 2);
-    bp.c1 = (float)(pd * (pd + 2));
-    bp.c2 = (float)(pd * (pd + 1) / 2);
     bp.pc0 = (float)(pd * (pd + 1) * (pd + 2) / 2);
-    bp.pc1 = (float)((pd + 1) * pd * (pd + 2));
-    bp.pc2 = (float)((pd + 2) * pd * (pd + 1) / 2);
 
     // ---- pack weights
     prof_begin(g, MLIP_PROF_NODE);

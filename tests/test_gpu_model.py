@@ -81,6 +81,23 @@ def test_zero_layers_and_isolated_atoms():
         gpu_energy_forces(g, c["weights"], 6, WHOLE)
 
 
+@pytest.mark.parametrize("d", [4.9, 4.95])
+def test_only_edges_close_to_the_cutoff(d):
+    """Three atoms whose only neighbours sit just inside the cutoff, where the envelope and its derivative are tiny:
+    the force bound is relative to these tiny forces, so it only holds if the envelope is evaluated without
+    cancellation there."""
+    c = wl.make_config(1, n=2)
+    pos = np.array([[10.0, 10.0, 10.0], [10.0 + d, 10.0, 10.0], [10.0, 10.0 + 0.6 * d, 10.0 + 0.8 * d]])
+    cell = np.eye(3) * 30.0
+    sp = np.array([0, 1, 2], np.int32)
+    ref_g = og.build_graph(pos, cell, c["r_cut"])
+    assert ref_g.E == 4
+    ref = om.energy_forces(pos, cell, sp, c["weights"], ref_g, c["r_cut"], c["K"], c["p"])
+    g = gpu_graph(pos, cell, sp, c["r_cut"])
+    e, f, _ = gpu_energy_forces(g, c["weights"], c["p"], WHOLE)
+    assert_energy_forces(e, f, ref, f"neighbours at {d}")
+
+
 def test_more_slabs_than_populated_regions():
     """A cluster at one end of a long cell cut into 8 slabs: most partitions own nothing, some have ghosts only
     on one side.  Two-body and three-body variants, slabs against whole graph and oracle."""

@@ -609,15 +609,15 @@ struct EdgeBatch {
 struct ItemRange {
     int64_t first, end, stride;
 };
-__device__ inline ItemRange edge_items(int64_t total, int wave)
+__device__ inline ItemRange edge_items(int64_t total, int wave, int nw = 4)   // nw: wavefronts per block
 {
     const int64_t n_slots = gridDim.x >> 3;
     const int64_t per = (((total + 7) >> 3) + 3) & ~(int64_t)3;
     const int64_t xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
     ItemRange r;
-    r.first = xcd * per + slot * 4 + wave;
+    r.first = xcd * per + slot * nw + wave;
     r.end = min(total, (xcd + 1) * per);
-    r.stride = n_slots * 4;
+    r.stride = n_slots * nw;
     return r;
 }
 
@@ -815,10 +815,12 @@ __global__ void __launch_bounds__(256, 3) k_edge_fwd(EdgeBatch B)
 //   sum_k (W2 wsym)_k * ds_k/dd,   ds_k/dd = SiLU'(t_k) * sum_n W1[n][k] db_n/dd,
 //   on the MFMA units, written to both edges of the pair.  Both edges of a pair have the same length
 //   and the same wsym, so the dense work runs once per pair instead of once per directed edge.
-// Edges per step of the reverse kernel's phase 1.  Steps of 8 with a 32-slot queue fit three blocks per compute
-// unit instead of two (154 registers, 52 KB of LDS) and measured slower (16.2 against 14.8 ms on the 1M-atom
-// benchmark): the per-step bookkeeping doubles and phase 2 runs on partly filled tiles.
+// Edges per step of the reverse kernel's phase 1 and wavefronts per block.  Three wavefronts per SIMD instead of two
+// were tried twice and measured slower on the 1M-atom benchmark (14.1 - 14.8 ms per step as built): steps of 8 with a
+// 32-slot queue in three 4-wave blocks per compute unit (154 registers): 16.2 ms, the per-step bookkeeping doubles and
+// phase 2 runs on partly filled tiles; steps of 12 in one 12-wave block (168 registers, 4 of them spilled): 16.0 ms.
 constexpr int kStep = 16;
+constexpr int kBwdWaves = 4;
 constexpr int kQueue = 31 + kStep + 1;   // queued pairs per wavefront: at most 31 pending + one step's new ones
 // phase 2 runs once a further step could overflow the queue (and at the latest with 32 pairs queued)
 constexpr int kQueueTrigger = (kQueue - kStep < 32) ? kQueue - kStep : 32;
@@ -866,7 +868,7 @@ __device__ inline void gemm_queue(const float *__restrict__ Ap, const float *row
 }
 
 template <int F, int PREC>
-__global__ void __launch_bounds__(256, 2) k_edge_bwd(EdgeBatch B)
+__global__ void __launch_bounds__(kBwdWaves * 64, kBwdWaves == 4 ? 2 : 1) k_edge_bwd(EdgeBatch B)
 {
     using D = Dims<F>;
     constexpr int FS = D::FS;
@@ -875,12 +877,12 @@ __global__ void __launch_bounds__(256, 2) k_edge_bwd(EdgeBatch B)
     float *A2n = lds;
     float *A1l = A2n + D::PACKF;
     float *queues = A1l + D::PACK1;
-    for (int i = threadIdx.x; i < (PREC == kPrecBf16 ? D::PACKF / 2 : D::PACKF); i += 256) A2n[i] = B.c.A2n[i];
-    for (int i = threadIdx.x; i < D::PACK1; i += 256) A1l[i] = B.c.A1[i];
+    for (int i = threadIdx.x; i < (PREC == kPrecBf16 ? D::PACKF / 2 : D::PACKF); i += kBwdWaves * 64) A2n[i] = B.c.A2n[i];
+    for (int i = threadIdx.x; i < D::PACK1; i += kBwdWaves * 64) A1l[i] = B.c.A1[i];
     __syncthreads();
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int c32 = lane & 31;
-    const int l16 = lane & (kStep - 1);   // lane's edge within a step
+    const int l16 = lane % kStep;   // lane's edge within a step
     const unsigned f = lane & (F - 1);
     // Queue of pairs, one per wavefront: slot s is LDS row s, floats [0, F) = wsym, then the upper
     // edge's index, the reverse edge's index and the edge length in the row's padding.  It carries
@@ -892,7 +894,7 @@ __global__ void __launch_bounds__(256, 2) k_edge_bwd(EdgeBatch B)
     int q_head = 0, q_count = 0;   // first queued slot, queued pairs
     int q_tail = 0;                // (q_head + q_count) % kQueue, the slot the next pair goes to
 
-    const ItemRange items = edge_items(B.chunk_start[B.n], wave);
+    const ItemRange items = edge_items(B.chunk_start[B.n], wave, kBwdWaves);
     int64_t item = items.first;
     for (int part = 0; part < B.n; ++part) {
     const int64_t part_end = min(items.end, B.chunk_start[part + 1]);
@@ -2127,7 +2129,7 @@ Packs pack_layout(int F, int L)
 template <int F> struct Lds {
     using D = Dims<F>;
     static constexpr size_t edge_fwd = sizeof(float) * (D::PACKF + 4 * D::TILE);
-    static constexpr size_t edge_bwd = sizeof(float) * (D::PACKF + D::PACK1 + 4 * kQueue * D::FS);
+    static constexpr size_t edge_bwd = sizeof(float) * (D::PACKF + D::PACK1 + kBwdWaves * kQueue * D::FS);
     static constexpr size_t node1 = sizeof(float) * (D::PACKF + 4 * D::TILE);
     static constexpr size_t node2 = sizeof(float) * (2 * D::PACKF + 4 * D::TILE);
 };
@@ -2203,7 +2205,7 @@ template <int F, int PREC> int launch_edge(mlip_graph *g, EdgeBatch &b, bool bac
         MLIP_HIP(hipGetDevice(&dev));
         MLIP_HIP(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
         if (backward)
-            MLIP_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&o, k_edge_bwd<F, PREC>, 256, lds));
+            MLIP_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&o, k_edge_bwd<F, PREC>, kBwdWaves * 64, lds));
         else
             MLIP_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&o, k_edge_fwd<F, PREC>, 256, lds));
         if (o < 1 || n_cu < 8) {
@@ -2219,10 +2221,11 @@ template <int F, int PREC> int launch_edge(mlip_graph *g, EdgeBatch &b, bool bac
     if (items <= 0) return MLIP_OK;
     // persistent grid: what is resident at once, a multiple of the 8 XCDs, no more than the work needs
     const int64_t resident = (int64_t)(n_cu / 8) * occ;
-    const int64_t needed = ((items + 7) / 8 + 3) / 4;
+    const int nw = backward ? kBwdWaves : 4;
+    const int64_t needed = ((items + 7) / 8 + nw - 1) / nw;
     const unsigned blocks = (unsigned)(8 * std::max<int64_t>(1, std::min(resident, needed)));
     if (backward)
-        k_edge_bwd<F, PREC><<<blocks, 256, lds, g->stream>>>(b);
+        k_edge_bwd<F, PREC><<<blocks, kBwdWaves * 64, lds, g->stream>>>(b);
     else
         k_edge_fwd<F, PREC><<<blocks, 256, lds, g->stream>>>(b);
     MLIP_HIP(hipGetLastError());

@@ -1,0 +1,394 @@
+// Node kernels (F x F products over atoms) and the small kernels: embedding, ghost transfers, forces, energy.
+// Part of model.hip (one translation unit): included inside namespace mlip, anonymous namespace.
+#ifndef MLIP_MODEL_NODE_H
+#define MLIP_MODEL_NODE_H
+
+// ---------------------------------------------------------------- node kernels
+
+enum { OP_PROJ = 0, OP_UPDATE = 1, OP_READOUT = 2, OP_BWD_UPDATE = 3, OP_BWD_PROJ = 4 };
+
+struct NodeArgs {      // one partition
+    int64_t n_rows;
+    const float *X;    // GEMM input rows
+    float *Y;          // primary output rows
+    float *Z;          // secondary in/out rows (h for UPDATE, hbar for BWD_*)
+    float *eps;
+};
+
+struct NodeBatch {     // up to kBatch partitions per launch, 32-row tiles numbered across them
+    const float *P1, *P2;
+    const float *wr2;
+    int n;
+    int64_t tile_start[kBatch + 1];
+    NodeArgs s[kBatch];
+};
+
+// A 32-row tile of X travels global memory -> registers -> LDS in two halves, so that the loads of the next
+// tile can be in flight while the current one is multiplied.
+template <int F> struct TileRegs {
+    static constexpr int LPR = F / 4;        // lanes per row (float4 each)
+    static constexpr int RPI = 64 / LPR;     // rows per wave instruction
+    f32x4 v[32 / RPI];
+};
+
+template <int F>
+__device__ inline void fetch_tile(TileRegs<F> &T, const float *__restrict__ X, int64_t row0, int64_t n_rows, int lane)
+{
+    constexpr int LPR = TileRegs<F>::LPR, RPI = TileRegs<F>::RPI;
+    const int rr = lane / LPR, cc = (lane % LPR) * 4;
+#pragma unroll
+    for (int r = 0; r < 32; r += RPI) {
+        const int64_t row = row0 + r + rr;
+        f32x4 v = {0.f, 0.f, 0.f, 0.f};
+        if (row < n_rows) v = *reinterpret_cast<const f32x4 *>(X + row * F + cc);
+        T.v[r / RPI] = v;
+    }
+}
+
+template <int F> __device__ inline void stash_tile(const TileRegs<F> &T, float *tile, int lane)
+{
+    constexpr int FS = Dims<F>::FS;
+    constexpr int LPR = TileRegs<F>::LPR, RPI = TileRegs<F>::RPI;
+    const int rr = lane / LPR, cc = (lane % LPR) * 4;
+#pragma unroll
+    for (int r = 0; r < 32; r += RPI) *reinterpret_cast<f32x4 *>(tile + (r + rr) * FS + cc) = T.v[r / RPI];
+}
+
+template <int F, int OP>
+__global__ void __launch_bounds__(256) k_node(NodeBatch B)
+{
+    using D = Dims<F>;
+    constexpr bool TWO = (OP == OP_READOUT || OP == OP_BWD_UPDATE);
+    extern __shared__ float lds[];
+    float *P1 = lds;
+    float *P2 = P1 + D::PACKF;
+    float *tiles = P2 + (TWO ? D::PACKF : 0);
+    for (int i = threadIdx.x; i < D::PACKF; i += 256) {
+        P1[i] = B.P1[i];
+        if (TWO) P2[i] = B.P2[i];
+    }
+    __syncthreads();
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int c32 = lane & 31, h = lane >> 5;
+    float *tile = tiles + wave * D::TILE;
+    const int64_t n_tiles = B.tile_start[B.n];
+    const int64_t stride = (int64_t)gridDim.x * 4;
+    TileRegs<F> pre;
+    auto fetch = [&](int64_t ti) {
+        const int part = batch_find(B.tile_start, B.n, ti);
+        fetch_tile<F>(pre, B.s[part].X, (ti - B.tile_start[part]) * 32, B.s[part].n_rows, lane);
+    };
+    int64_t ti = (int64_t)blockIdx.x * 4 + wave;
+    if (ti < n_tiles) fetch(ti);
+    for (; ti < n_tiles; ti += stride) {
+        const int part = batch_find(B.tile_start, B.n, ti);
+        const NodeArgs A = B.s[part];
+        const int64_t row0 = (ti - B.tile_start[part]) * 32;
+        const int64_t row = row0 + c32;
+        const bool ok = row < A.n_rows;
+        stash_tile<F>(pre, tile, lane);
+        wave_lds_fence();
+        // rows of Z this tile combines with its product, requested before the product as well
+        constexpr bool READS_Z = (OP == OP_UPDATE || OP == OP_BWD_PROJ || OP == OP_BWD_UPDATE);
+        f32x4 zv[D::NB][4];
+        if (READS_Z)
+#pragma unroll
+            for (int b = 0; b < D::NB; ++b)
+#pragma unroll
+                for (int a = 0; a < 4; ++a) {
+                    zv[b][a] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    if (ok) zv[b][a] = *reinterpret_cast<const f32x4 *>(A.Z + row * F + 32 * b + 8 * a + 4 * h);
+                }
+        if (ti + stride < n_tiles) fetch(ti + stride);   // in flight during this tile's products
+        f32x16 acc[D::NB];
+        gemm_lds<F>(P1, tile, acc, lane);
+        wave_lds_fence();
+        if (OP == OP_PROJ) {
+            if (ok)
+#pragma unroll
+                for (int b = 0; b < D::NB; ++b)
+#pragma unroll
+                    for (int a = 0; a < 4; ++a) {
+                        f32x4 v = {acc[b][4 * a], acc[b][4 * a + 1], acc[b][4 * a + 2], acc[b][4 * a + 3]};
+                        *reinterpret_cast<f32x4 *>(A.Y + row * F + 32 * b + 8 * a + 4 * h) = v;
+                    }
+        } else if (OP == OP_UPDATE || OP == OP_BWD_PROJ) {
+            // UPDATE:   Z = h,    h    += SiLU(a Wo)
+            // BWD_PROJ: Z = hbar, hbar += gbar Wm^T
+            if (ok)
+#pragma unroll
+                for (int b = 0; b < D::NB; ++b)
+#pragma unroll
+                    for (int a = 0; a < 4; ++a) {
+                        float *zp = A.Z + row * F + 32 * b + 8 * a + 4 * h;
+                        f32x4 v = zv[b][a];
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) {
+                            const float q = acc[b][4 * a + c];
+                            v[c] += (OP == OP_UPDATE) ? q * sigmoidf_fast(q) : q;
+                        }
+                        *reinterpret_cast<f32x4 *>(zp) = v;
+                    }
+        } else if (OP == OP_READOUT) {
+            // eps = SiLU(h Wr1) . wr2 ;  hbar = (wr2 * SiLU'(h Wr1)) Wr1^T
+            float part = 0.f;
+#pragma unroll
+            for (int b = 0; b < D::NB; ++b)
+#pragma unroll
+                for (int a = 0; a < 4; ++a) {
+                    const f32x4 wv = *reinterpret_cast<const f32x4 *>(B.wr2 + 32 * b + 8 * a + 4 * h);
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        const float x = acc[b][4 * a + c];
+                        const float sg = sigmoidf_fast(x);
+                        part += x * sg * wv[c];
+                        acc[b][4 * a + c] = wv[c] * sg * (1.0f + x * (1.0f - sg));
+                    }
+                }
+            part += __shfl_xor(part, 32, 64);
+            if (ok && h == 0) A.eps[row] = part;
+            f32x16 hb[D::NB];
+            gemm_regs<F>(P2, acc, hb, lane);
+            if (ok)
+#pragma unroll
+                for (int b = 0; b < D::NB; ++b)
+#pragma unroll
+                    for (int a = 0; a < 4; ++a) {
+                        f32x4 v = {hb[b][4 * a], hb[b][4 * a + 1], hb[b][4 * a + 2], hb[b][4 * a + 3]};
+                        *reinterpret_cast<f32x4 *>(A.Y + row * F + 32 * b + 8 * a + 4 * h) = v;
+                    }
+        } else if (OP == OP_BWD_UPDATE) {
+            // q = a Wo ; qbar = hbar * SiLU'(q) ; abar = qbar Wo^T       (X = a, Z = hbar, Y = abar)
+#pragma unroll
+            for (int b = 0; b < D::NB; ++b)
+#pragma unroll
+                for (int a = 0; a < 4; ++a) {
+                    const f32x4 hv = zv[b][a];
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        const float x = acc[b][4 * a + c];
+                        const float sg = sigmoidf_fast(x);
+                        acc[b][4 * a + c] = hv[c] * sg * (1.0f + x * (1.0f - sg));
+                    }
+                }
+            f32x16 ab[D::NB];
+            gemm_regs<F>(P2, acc, ab, lane);
+            if (ok)
+#pragma unroll
+                for (int b = 0; b < D::NB; ++b)
+#pragma unroll
+                    for (int a = 0; a < 4; ++a) {
+                        f32x4 v = {ab[b][4 * a], ab[b][4 * a + 1], ab[b][4 * a + 2], ab[b][4 * a + 3]};
+                        *reinterpret_cast<f32x4 *>(A.Y + row * F + 32 * b + 8 * a + 4 * h) = v;
+                    }
+        }
+    }
+}
+
+// ---------------------------------------------------------------- small kernels
+
+__global__ void k_embed(int64_t n_rows, int F, const int32_t *__restrict__ nodes, const int32_t *__restrict__ species,
+                        const float *__restrict__ emb, float *__restrict__ h)
+{
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= n_rows * F) return;
+    const int64_t r = idx / F;
+    const int f = (int)(idx % F);
+    const int64_t u = nodes ? nodes[r] : r;
+    h[idx] = emb[species[u] * F + f];
+}
+
+struct PtrTable { float *p[kMaxSlabs]; };
+
+// ghost rows of this partition's g  <-  the owners' rows
+__global__ void k_ghost_copy(int64_t n_ghost, int64_t n_owned, int F, const int32_t *__restrict__ owner,
+                             const int32_t *__restrict__ src, PtrTable tab, float *__restrict__ dst)
+{
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int F4 = F / 4;
+    if (idx >= n_ghost * F4) return;
+    const int64_t k = idx / F4;
+    const int c = (int)(idx % F4) * 4;
+    const float *sp = tab.p[owner[k]] + (int64_t)src[k] * F + c;
+    *reinterpret_cast<f32x4 *>(dst + (n_owned + k) * F + c) = *reinterpret_cast<const f32x4 *>(sp);
+}
+
+// the owners' gradient rows  +=  this partition's ghost rows (each ghost atom appears once per partition)
+// gbar of the ghost rows: gbar_i = sum over the ghost's sub-row (its neighbours owned by this partition) of
+// w_e * abar_send(e).  w_e is the reverse edge's, which the forward pass kept (both edges of a pair have the
+// same length, hence the same filter value).  One wavefront per row, lane = feature, edges in row order.
+template <int F>
+__global__ void __launch_bounds__(256)
+k_ghost_gbar(int64_t n_ghost, int64_t n_owned, const int64_t *__restrict__ row_ptr, const int32_t *__restrict__ senders,
+             const int32_t *__restrict__ mirror, const float *__restrict__ wstore, const float *__restrict__ abar,
+             const int32_t *__restrict__ bond_of_edge, const float *__restrict__ wb, float *__restrict__ gbar)
+{
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int64_t k = (int64_t)blockIdx.x * 4 + wave;
+    if (k >= n_ghost) return;
+    const int64_t r = n_owned + k;
+    const unsigned f = lane & (F - 1);
+    const int64_t e0 = row_ptr[r], e1 = row_ptr[r + 1];
+    float acc = 0.f;
+    for (int64_t eb = e0; eb < e1; eb += 16) {   // 16 edges at a time: ids by lane, then all rows in flight together
+        const int n = (int)min((int64_t)16, e1 - eb);
+        const int64_t el = min(eb + (lane & 15), e1 - 1);
+        const int32_t jl = senders[el], ml = mirror[el];
+        const int32_t bl = bond_of_edge ? bond_of_edge[ml] : -1;   // three-body variant: the reverse edge's bond
+        float wv[16], av[16];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            const int64_t j = __builtin_amdgcn_readlane(jl, k), m = __builtin_amdgcn_readlane(ml, k);
+            const int64_t b = __builtin_amdgcn_readlane(bl, k);
+            wv[k] = wstore[m * F + f];
+            if (b >= 0) wv[k] += wb[b * F + f];
+            av[k] = abar[j * F + f];
+        }
+#pragma unroll
+        for (int k = 0; k < 16; ++k)
+            if (k < n) acc = fmaf(wv[k], av[k], acc);
+    }
+    if (F == 64 || lane < F) gbar[r * F + f] = acc;
+}
+
+// Three-body variant, ghost rows: a ghost atom i is the sender of bonds (j <- i) held by this partition; each pulls
+// on it with +dE/dDelta.  Gathered over the ghost's sub-row through the reverse edges.
+__global__ void k_bond_force_ghost(int64_t n_ghost, int64_t n_owned, const int64_t *__restrict__ row_ptr,
+                                   const int32_t *__restrict__ mirror, const int32_t *__restrict__ bond_of_edge,
+                                   const float *__restrict__ dbond, const float *__restrict__ rbar,
+                                   const float *__restrict__ rhat, const float *__restrict__ bd, float *floc)
+{
+    const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= n_ghost) return;
+    const int64_t r = n_owned + k;
+    float fx = 0.f, fy = 0.f, fz = 0.f;
+    for (int64_t e = row_ptr[r]; e < row_ptr[r + 1]; ++e) {
+        const int64_t q = bond_of_edge[mirror[e]];
+        if (q < 0) continue;
+        const float x = rhat[3 * q], y = rhat[3 * q + 1], z = rhat[3 * q + 2];
+        const float ax = rbar[3 * q], ay = rbar[3 * q + 1], az = rbar[3 * q + 2];
+        const float dot = fmaf(ax, x, fmaf(ay, y, az * z));
+        const float inv = 1.0f / bd[q];
+        fx -= fmaf(dbond[q], x, (ax - dot * x) * inv);
+        fy -= fmaf(dbond[q], y, (ay - dot * y) * inv);
+        fz -= fmaf(dbond[q], z, (az - dot * z) * inv);
+    }
+    floc[3 * r] += fx;
+    floc[3 * r + 1] += fy;
+    floc[3 * r + 2] += fz;
+}
+
+__global__ void k_ghost_addback(int64_t n_ghost, int64_t n_owned, int F, const int32_t *__restrict__ owner,
+                                const int32_t *__restrict__ src, PtrTable tab, const float *__restrict__ mine)
+{
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int F4 = F / 4;
+    if (idx >= n_ghost * F4) return;
+    const int64_t k = idx / F4;
+    const int c = (int)(idx % F4) * 4;
+    float *dp = tab.p[owner[k]] + (int64_t)src[k] * F + c;
+    f32x4 v = *reinterpret_cast<const f32x4 *>(dp);
+    const f32x4 m = *reinterpret_cast<const f32x4 *>(mine + (n_owned + k) * F + c);
+    v += m;
+    *reinterpret_cast<f32x4 *>(dp) = v;
+}
+
+__device__ inline void unpack_shift(uint32_t p, int &a, int &b, int &c)
+{
+    a = (int)(p >> 20) - 512;
+    b = (int)((p >> 10) & 1023u) - 512;
+    c = (int)(p & 1023u) - 512;
+}
+
+// F_loc[r] = sum_{e in local row r} dsum_e * rhat_e, rhat from fp64 positions; 16 lanes per row, 16 rows per block
+__global__ void __launch_bounds__(256)
+k_force_rows(int64_t n_rows, const int64_t *__restrict__ row_ptr, const int32_t *__restrict__ senders,
+             const uint32_t *__restrict__ shiftp, const float *__restrict__ dsum, const int32_t *__restrict__ nodes,
+             const double *__restrict__ pos, CellParams cp, float *__restrict__ floc)
+{
+    const int64_t r = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
+    if (r >= n_rows) return;   // whole groups of 16 lanes leave together; the shuffles below stay inside a group
+    const int64_t ig = nodes ? nodes[r] : r;
+    const double xi = pos[3 * ig], yi = pos[3 * ig + 1], zi = pos[3 * ig + 2];
+    double fx = 0, fy = 0, fz = 0;
+    const int64_t e1 = row_ptr[r + 1];
+    for (int64_t e = row_ptr[r] + (threadIdx.x & 15); e < e1; e += 16) {
+        const int64_t jl = senders[e];
+        const int64_t jg = nodes ? nodes[jl] : jl;
+        int S0, S1, S2;
+        unpack_shift(shiftp[e], S0, S1, S2);
+        const double t0 = (pos[3 * jg] - xi) + (((double)S0 * cp.C[0] + (double)S1 * cp.C[3]) + (double)S2 * cp.C[6]);
+        const double t1 = (pos[3 * jg + 1] - yi) + (((double)S0 * cp.C[1] + (double)S1 * cp.C[4]) + (double)S2 * cp.C[7]);
+        const double t2 = (pos[3 * jg + 2] - zi) + (((double)S0 * cp.C[2] + (double)S1 * cp.C[5]) + (double)S2 * cp.C[8]);
+        const double s = (double)dsum[e] / sqrt((t0 * t0 + t1 * t1) + t2 * t2);
+        fx += s * t0;
+        fy += s * t1;
+        fz += s * t2;
+    }
+#pragma unroll
+    for (int off = 8; off > 0; off >>= 1) {
+        fx += __shfl_xor(fx, off, 64);
+        fy += __shfl_xor(fy, off, 64);
+        fz += __shfl_xor(fz, off, 64);
+    }
+    if ((threadIdx.x & 15) == 0) {
+        floc[3 * r] = (float)fx;
+        floc[3 * r + 1] = (float)fy;
+        floc[3 * r + 2] = (float)fz;
+    }
+}
+
+// owned rows: forces[global] = F_loc ; atom_energy[global] = eps
+__global__ void k_store_owned(int64_t n_owned, const int32_t *__restrict__ nodes, const float *__restrict__ floc,
+                              const float *__restrict__ eps, float *__restrict__ forces, float *__restrict__ atom_energy)
+{
+    const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (r >= n_owned) return;
+    const int64_t u = nodes ? nodes[r] : r;
+    forces[3 * u] = floc[3 * r];
+    forces[3 * u + 1] = floc[3 * r + 1];
+    forces[3 * u + 2] = floc[3 * r + 2];
+    if (atom_energy) atom_energy[u] = eps[r];
+}
+
+// ghost rows: forces[global] += F_loc (position gradients of ghost atoms go back to their owners)
+__global__ void k_addback_ghost_forces(int64_t n_ghost, int64_t n_owned, const int32_t *__restrict__ nodes,
+                                       const float *__restrict__ floc, float *__restrict__ forces)
+{
+    const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= n_ghost) return;
+    const int64_t r = n_owned + k;
+    const int64_t u = nodes[r];
+    forces[3 * u] += floc[3 * r];
+    forces[3 * u + 1] += floc[3 * r + 1];
+    forces[3 * u + 2] += floc[3 * r + 2];
+}
+
+// fixed-shape fp64 reduction of the per-atom energies: 1024-element blocks, then one block over the partials
+__global__ void __launch_bounds__(256) k_energy_partial(int64_t n, const float *__restrict__ eps, double *__restrict__ part)
+{
+    __shared__ double sh[4];
+    const int64_t base = (int64_t)blockIdx.x * 1024;
+    double s = 0;
+    for (int k = threadIdx.x; k < 1024; k += 256)
+        if (base + k < n) s += (double)eps[base + k];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) part[blockIdx.x] = (sh[0] + sh[1]) + (sh[2] + sh[3]);
+}
+
+__global__ void __launch_bounds__(256) k_energy_final(int64_t n, const double *__restrict__ part, double *__restrict__ energy)
+{
+    __shared__ double sh[4];
+    double s = 0;
+    for (int64_t k = threadIdx.x; k < n; k += 256) s += part[k];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) *energy = (sh[0] + sh[1]) + (sh[2] + sh[3]);
+}
+
+#endif  // MLIP_MODEL_NODE_H

@@ -56,7 +56,8 @@ enum { MLIP_MODE_WHOLE = 0, MLIP_MODE_SLABS = 1 };
  *   significant bits) and taken as three fp16 MFMA products with fp32 accumulation.  The results meet the fp32
  *   mode's bounds (the dropped terms are of the size of fp32 accumulation rounding) in a fraction of the matrix
  *   time; the operands of those products - SiLU outputs and the products abar * g of the reverse pass - must
- *   stay below the fp16 range (65504), which holds for any physical input but is not checked.
+ *   stay below the fp16 range (65504), which holds for any physical input but is not checked: a value beyond it
+ *   becomes infinite in the split and the energy and forces come out non-finite.
  */
 enum { MLIP_PRECISION_FP32 = 0, MLIP_PRECISION_BF16 = 1, MLIP_PRECISION_FP32_SPLIT = 2 };
 

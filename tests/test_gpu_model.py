@@ -98,6 +98,19 @@ def test_only_edges_close_to_the_cutoff(d):
     assert_energy_forces(e, f, ref, f"neighbours at {d}")
 
 
+def test_split_mode_range_violation_is_visible():
+    """The split-fp16 mode needs the operands of its products below the fp16 range; weights that push the hidden
+    activations of the filter MLP beyond it give a non-finite energy there (and a finite one in fp32 mode)."""
+    c, ref_g, _ = oracle_config(0)
+    w = dict(c["weights"])
+    w["W1"] = w["W1"] * np.float32(3e5)
+    g = gpu_graph(c["positions"], c["cell"], c["species"], c["r_cut"])
+    e32, _, _ = gpu_energy_forces(g, w, c["p"], WHOLE, precision=0)
+    e16, _, _ = gpu_energy_forces(g, w, c["p"], WHOLE, precision=2)
+    assert np.isfinite(e32)
+    assert not np.isfinite(e16)
+
+
 def test_more_slabs_than_populated_regions():
     """A cluster at one end of a long cell cut into 8 slabs: most partitions own nothing, some have ghosts only
     on one side.  Two-body and three-body variants, slabs against whole graph and oracle."""

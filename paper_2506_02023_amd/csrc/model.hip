@@ -257,7 +257,7 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
     for (int p = 0; p < P; ++p) {
         SlabView &v = views[p];
         if (v.n_owned > 0)
-            k_embed<<<blocks_for(v.n_owned * F, 256), 256, 0, s>>>(v.n_owned, F, v.nodes, species, w->emb, v.h.as<float>());
+            k_embed<<<blocks_for(v.n_owned * (F / 4), 256), 256, 0, s>>>(v.n_owned, F, v.nodes, species, w->emb, v.h.as<float>());
     }
     MLIP_HIP(hipGetLastError());
     prof_end(g);

@@ -190,12 +190,14 @@ __global__ void __launch_bounds__(256) k_node(NodeBatch B)
 __global__ void k_embed(int64_t n_rows, int F, const int32_t *__restrict__ nodes, const int32_t *__restrict__ species,
                         const float *__restrict__ emb, float *__restrict__ h)
 {
-    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= n_rows * F) return;
-    const int64_t r = idx / F;
-    const int f = (int)(idx % F);
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;   // one float4 per thread
+    const int F4 = F / 4;
+    if (idx >= n_rows * F4) return;
+    const int64_t r = idx / F4;
+    const int c = (int)(idx % F4) * 4;
     const int64_t u = nodes ? nodes[r] : r;
-    h[idx] = emb[species[u] * F + f];
+    const float *e = emb + (int64_t)species[u] * F + c;   // the caller's table: no alignment assumed
+    *reinterpret_cast<f32x4 *>(h + r * F + c) = f32x4{e[0], e[1], e[2], e[3]};
 }
 
 struct PtrTable { float *p[kMaxSlabs]; };

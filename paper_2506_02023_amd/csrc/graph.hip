@@ -432,16 +432,21 @@ __global__ void k_unpack_shifts(int64_t E, const uint32_t *__restrict__ shiftp, 
 // ---------------------------------------------------------------- partition
 
 // needed_by[j] gets bit q when some atom owned by slab q != slab(j) receives from j
-__global__ void __launch_bounds__(64)
+// (16 lanes per row, 16 rows per block; a bit that is already set is not set again)
+__global__ void __launch_bounds__(256)
 k_needed_by(int64_t N, const int64_t *__restrict__ row_ptr, const int32_t *__restrict__ senders,
             const int32_t *__restrict__ slab_of, unsigned long long *needed_by)
 {
-    const int64_t i = blockIdx.x;
+    const int64_t i = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
+    if (i >= N) return;
     const int si = slab_of[i];
     const int64_t e1 = row_ptr[i + 1];
-    for (int64_t e = row_ptr[i] + threadIdx.x; e < e1; e += 64) {
+    for (int64_t e = row_ptr[i] + (threadIdx.x & 15); e < e1; e += 16) {
         const int32_t j = senders[e];
-        if (slab_of[j] != si) atomicOr(&needed_by[j], 1ull << si);
+        if (slab_of[j] != si) {
+            const unsigned long long bit = 1ull << si;
+            if (!(__atomic_load_n(&needed_by[j], __ATOMIC_RELAXED) & bit)) atomicOr(&needed_by[j], bit);
+        }
     }
 }
 
@@ -901,7 +906,7 @@ int build_graph_impl(mlip_graph *g, const double *positions, const double *cell,
         MLIP_TRY(g->local_of.ensure((size_t)N * 4));
         MLIP_TRY(g->local_in_owner.ensure((size_t)N * 4));
         MLIP_HIP(hipMemsetAsync(g->needed_by.p, 0, (size_t)N * 8, s));
-        k_needed_by<<<(unsigned)N, 64, 0, s>>>(N, g->row_ptr.as<int64_t>(), g->senders.as<int32_t>(),
+        k_needed_by<<<(unsigned)((N + 15) / 16), 256, 0, s>>>(N, g->row_ptr.as<int64_t>(), g->senders.as<int32_t>(),
                                                g->slab_of.as<int32_t>(), g->needed_by.as<unsigned long long>());
         MLIP_HIP(hipGetLastError());
         const int ncls = P + 2;

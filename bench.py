@@ -126,11 +126,15 @@ def main():
     g.profile_enable(True)
     g.profile_read(reset=True)
     torch.cuda.synchronize()
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]   # step boundaries, on the library's stream
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    marks[0].record()
+    for k in range(args.steps):
         step()
+        marks[k + 1].record()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    per_step = sorted(marks[k].elapsed_time(marks[k + 1]) for k in range(args.steps))
     prof = g.profile_read(reset=True)
     g.profile_enable(False)
     _, E, _ = g.sizes()
@@ -206,7 +210,8 @@ def main():
 
     res = {
         "metric": "atoms/s (energy+forces)", "value": N / (dt / args.steps), "unit": "atoms/s", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step, "higher_is_better": True,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step, "ms_per_step_min": per_step[0],
+        "ms_per_step_median": per_step[len(per_step) // 2], "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None,
         "dtype": {"f32": "f32", "bf16": "f32 with bf16 operands in the filter MLP's F x F products",
                   "f32split": "f32, the filter MLP's F x F products as split-fp16 MFMA triples"}[args.precision],

@@ -125,6 +125,13 @@ def test_partition_triclinic(P):
     _check_partition(pos, cell, sp, 3.0, P)
 
 
+def test_partition_maximum_slab_count():
+    """64 slabs (the limit) across a 21.6 A box: slabs a third of an Angstrom wide, every owned atom needed by many
+    partitions (multi-valued TO), ghosts from dozens of owners."""
+    c = wl.make_config(0, n=6)
+    _check_partition(c["positions"], c["cell"], c["species"], c["r_cut"], 64)
+
+
 def test_partition_medium_8_slabs():
     c, _, _ = oracle_config(1)
     _check_partition(c["positions"], c["cell"], c["species"], c["r_cut"], 8)

@@ -98,6 +98,20 @@ def test_only_edges_close_to_the_cutoff(d):
     assert_energy_forces(e, f, ref, f"neighbours at {d}")
 
 
+@pytest.mark.parametrize("precision", [0, 2])
+def test_limits_eight_layers_64_slabs(precision):
+    """The largest layer count and slab count the library accepts, whole graph and partitioned."""
+    c = wl.make_config(0, n=4)
+    w = wl.rmp_weights(4, 32, 8, 91)
+    ref_g = og.build_graph(c["positions"], c["cell"], c["r_cut"])
+    ref = om.energy_forces(c["positions"], c["cell"], c["species"], w, ref_g, c["r_cut"], c["K"], c["p"])
+    g = gpu_graph(c["positions"], c["cell"], c["species"], c["r_cut"], n_slabs=64)
+    e, f, _ = gpu_energy_forces(g, w, c["p"], WHOLE, precision=precision)
+    assert_energy_forces(e, f, ref, "L = 8, whole graph")
+    es, fs, _ = gpu_energy_forces(g, w, c["p"], SLABS, precision=precision)
+    assert_energy_forces(es, fs, ref, "L = 8, 64 slabs")
+
+
 def test_split_mode_range_violation_is_visible():
     """The split-fp16 mode needs the operands of its products below the fp16 range; weights that push the hidden
     activations of the filter MLP beyond it give a non-finite energy there (and a finite one in fp32 mode)."""

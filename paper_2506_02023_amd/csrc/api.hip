@@ -217,7 +217,7 @@ void mlip_graph_destroy(mlip_graph_t *g)
         BondGraph &B = v.bonds;
         DevBuf *vb[] = {&v.h, &v.hbar, &v.abar, &v.gbar, &v.eps, &v.dsum, &v.floc, &v.g, &v.a, &v.wst,
                         &B.scan, &B.flag, &B.of_edge, &B.edge, &B.ptr, &B.mirror, &B.sender, &B.d, &B.u, &B.du, &B.rhat,
-                        &B.P, &B.Q, &B.S, &B.m, &B.wb, &B.e1bar, &B.Sbar, &B.Pbar, &B.Qbar,
+                        &B.P, &B.Q, &B.S, &B.m, &B.wb, &B.abar_keep, &B.e1bar, &B.Sbar, &B.Pbar, &B.Qbar,
                         &B.ubar, &B.dbond, &B.rbar};
         for (DevBuf *b : vb) b->release();
     };

@@ -73,6 +73,7 @@ struct BondGraph {
     DevBuf rhat;            // f32 [n][3] unit vector from the centre to the neighbour's image
     // model workspace, [n][F] unless noted
     DevBuf P, Q, S, m, wb /* [L][n][F] */, e1bar, Sbar, Pbar, Qbar;
+    DevBuf abar_keep;       // f32 [L][n_owned][F] dE/da of the owned rows, every layer's (for the bonds' reverse step)
     DevBuf ubar, dbond;     // f32 [n]
     DevBuf rbar;            // f32 [n][3]
 };

@@ -289,7 +289,10 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
         a.S = BG.S.as<float>();
         a.m = BG.m.as<float>();
         a.wb = BG.wb.as<float>();
-        a.abar = v.abar.as<float>();
+        a.abar = BG.abar_keep.as<float>();
+        a.abar_stride = (size_t)std::max<int64_t>(v.n_owned, 1) * F;
+        a.g = v.g.as<float>();
+        a.g_stride = (size_t)v.n_local * F;
         a.e1bar = BG.e1bar.as<float>();
         a.ubar = BG.ubar.as<float>();
         a.Sbar = BG.Sbar.as<float>();
@@ -311,6 +314,7 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
             DevBuf *fb[] = {&BG.P, &BG.Q, &BG.S, &BG.m, &BG.e1bar, &BG.Sbar, &BG.Pbar, &BG.Qbar};
             for (DevBuf *b : fb) MLIP_TRY(b->ensure(bs * sizeof(float)));
             MLIP_TRY(BG.wb.ensure(bs * sizeof(float) * (size_t)std::max(L, 1)));
+            MLIP_TRY(BG.abar_keep.ensure((size_t)std::max<int64_t>(views[p].n_owned, 1) * rowb * (size_t)std::max(L, 1)));
             MLIP_TRY(BG.ubar.ensure(nb1 * sizeof(float)));
             MLIP_TRY(BG.dbond.ensure(nb1 * sizeof(float)));
             MLIP_TRY(BG.rbar.ensure(nb1 * 3 * sizeof(float)));
@@ -470,10 +474,6 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
         if (L > 0 && v.n_ghost > 0)
             MLIP_HIP(hipMemsetAsync(v.abar.as<float>() + (size_t)v.n_owned * F, 0, (size_t)v.n_ghost * rowb, s));
     }
-    if (any_bonds && L == 0)   // no layer writes e1bar: the energy does not depend on the bonds
-        for (int p = 0; p < P; ++p)
-            if (views[p].bonds.n > 0)
-                MLIP_HIP(hipMemsetAsync(views[p].bonds.e1bar.p, 0, bstride(views[p]) * sizeof(float), s));
     for (int l = L - 1; l >= 0; --l) {
         const float *base = wp + pk.per_layer * l;
         const bool need_gbar = l > 0;  // dE/dh0 is never used: the embedding does not depend on positions
@@ -520,24 +520,20 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
                      : prec == kPrecF16x3 ? (launch_edge<F, kPrecF16x3>(g, eb, true)) : (launch_edge<F, kPrecF32>(g, eb, true)));
             prof_end(g);
         }
-        if (any_bonds) {   // bond term: its share of gbar, and e1bar (+)= dE/dwb Wb_l^T
+        if (any_bonds) {   // bond term: its share of gbar; this layer's abar is kept for the bonds' own reverse step
             prof_begin(g, MLIP_PROF_BOND);
             for (int p = 0; p < P; ++p) {
                 SlabView &v = views[p];
                 BondGraph &BG = v.bonds;
+                if (BG.n > 0)
+                    MLIP_HIP(hipMemcpyAsync(BG.abar_keep.as<float>() + (size_t)l * (size_t)v.n_owned * F, v.abar.p,
+                                            (size_t)v.n_owned * rowb, hipMemcpyDeviceToDevice, s));
                 if (BG.n > 0 && need_gbar)
                     k_bond_gbar<F><<<blocks_for(v.n_owned, 4), 256, 0, s>>>(
                         v.n_owned, BG.ptr.as<int64_t>(), BG.sender.as<int32_t>(), BG.mirror.as<int32_t>(), wbslice(v, l),
                         v.abar.as<float>(), v.gbar.as<float>());
             }
             MLIP_HIP(hipGetLastError());
-            for (int p = 0; p < P; ++p) {   // e1bar (+)= (abar_recv * g_send) Wb_l^T
-                BondArgs a = bond_args(views[p]);
-                a.g = gslice(views[p], l);
-                a.W[0] = bpk + (6 + L + l) * ffp;
-                a.first = (l == L - 1);
-                MLIP_TRY((launch_bond_mlp<F, BOND_LAYER_BWD>(g, a)));
-            }
             prof_end(g);
         }
         if (need_gbar) {
@@ -573,10 +569,13 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
     if (any_bonds) {
         prof_begin(g, MLIP_PROF_BOND);
         const float *Wtc = bw->Wt1 + 2 * ffp;
-        for (int p = 0; p < P; ++p) {   // ubar, Sbar = (e1bar u SiLU'(m)) Wt2^T
+        for (int p = 0; p < P; ++p) {   // e1bar = sum_l dE/dwb_l Wb_l^T, ubar, Sbar = (e1bar u SiLU'(m)) Wt2^T
             BondArgs a = bond_args(views[p]);
             a.W[0] = bpk + 5 * ffp;
-            MLIP_TRY((launch_bond_mlp<F, BOND_MBAR>(g, a)));
+            for (int l = 0; l < std::min(L, 3); ++l) a.W[1 + l] = bpk + (6 + L + l) * ffp;
+            a.Wx = bpk + (6 + L + 3) * ffp;
+            a.n_layers = L;
+            MLIP_TRY((launch_bond_mlp<F, BOND_EBAR>(g, a)));
         }
         prof_end(g);
         prof_begin(g, MLIP_PROF_TRIPLET_BWD);

@@ -382,11 +382,12 @@ __global__ void k_bond_force(int64_t N, const int64_t *__restrict__ bptr, const 
 // accumulators); each stage reads or writes every [bonds x F] array it touches once.
 //   HEAD       e0 = bbond(d) We0 (registers only, never stored: TAIL recomputes it);  P = e0 Wta;  Q = e0 Wtb
 //   TAIL       m = S Wt2;  e1 = e0 + u SiLU(m) (registers only);  wb_l = e1 Wb_l for every layer l
-//   LAYER_BWD  wbbar = abar_recv * g_send (built in the tile);  e1bar (+)= wbbar Wb_l^T
-//   MBAR       ubar = sum_f e1bar SiLU(m);  mbar = e1bar u SiLU'(m) (tile only);  Sbar = mbar Wt2^T
+//   EBAR       e1bar = sum over the layers l of (abar_l,recv * g_l,send) Wb_l^T, each factor tile built in LDS from the
+//              kept per-layer abar and g rows;  ubar = sum_f e1bar SiLU(m);  mbar = e1bar u SiLU'(m) (registers only);
+//              Sbar = mbar Wt2^T
 //   E0BAR      e0bar = e1bar + Pbar Wta^T + Qbar Wtb^T (registers only);
 //              dbond = sum_f e0bar (We0^T dbbond/dd) + ubar du/dd
-enum { BOND_HEAD = 0, BOND_TAIL = 1, BOND_LAYER_BWD = 2, BOND_MBAR = 3, BOND_E0BAR = 4 };
+enum { BOND_HEAD = 0, BOND_TAIL = 1, BOND_EBAR = 2, BOND_E0BAR = 3 };
 
 struct BondArgs {                      // one partition
     int64_t n;                         // bonds
@@ -395,24 +396,26 @@ struct BondArgs {                      // one partition
     const int32_t *recv;               // receiver row of an edge
     const float *We0p;                 // We0 packed for the K = 8 product (k_pack_w1)
     BasisParams bp;                    // radial basis at the bond cutoff
-    const float *W[4];                 // packed F x F operands of the stage (TAIL: Wt2, then the first layers' Wb)
-    const float *Wx;                   // TAIL: packed Wb of the layers beyond the third (read from global memory)
-    int n_layers;                      // TAIL
-    int first;                         // LAYER_BWD: store e1bar instead of accumulating
+    const float *W[4];                 // packed F x F operands of the stage (TAIL: Wt2, then the first layers' Wb;
+                                       // EBAR: Wt2^T, then the first layers' Wb^T)
+    const float *Wx;                   // TAIL, EBAR: the packs of the layers beyond the third (read from global memory)
+    int n_layers;                      // TAIL, EBAR
     size_t wb_stride;                  // TAIL: floats between two layers' wb
     float *P, *Q;                      // HEAD out
     const float *S;                    // TAIL in
-    float *m, *wb;                     // TAIL out; MBAR reads m
-    const float *abar, *g;             // LAYER_BWD in (node rows)
-    float *e1bar;                      // LAYER_BWD in/out; MBAR, E0BAR in
-    float *ubar, *Sbar;                // MBAR out; E0BAR reads ubar
+    float *m, *wb;                     // TAIL out; EBAR reads m
+    const float *abar, *g;             // EBAR in: kept per-layer node rows, layer l at abar + l abar_stride, g + l g_stride
+    size_t abar_stride, g_stride;
+    float *e1bar;                      // EBAR out; E0BAR in
+    float *ubar, *Sbar;                // EBAR out; E0BAR reads ubar
     const float *Pbar, *Qbar;          // E0BAR in
     float *dbond;                      // E0BAR out
 };
 
 template <int STAGE> struct BondStage {
-    static constexpr int NW = (STAGE == BOND_TAIL) ? 8 : 4;   // wavefronts per block
-    static constexpr int NPACK = (STAGE == BOND_TAIL) ? 4 : (STAGE == BOND_HEAD || STAGE == BOND_E0BAR) ? 2 : 1;
+    static constexpr bool PER_LAYER = (STAGE == BOND_TAIL || STAGE == BOND_EBAR);   // one operand pack per layer
+    static constexpr int NW = PER_LAYER ? 8 : 4;   // wavefronts per block
+    static constexpr int NPACK = PER_LAYER ? 4 : 2;
 };
 
 template <int F, int STAGE>
@@ -425,8 +428,8 @@ __global__ void __launch_bounds__(BondStage<STAGE>::NW * 64) k_bond_mlp(BondArgs
     extern __shared__ float lds[];
     float *packs = lds;
     float *tiles = packs + NPACK * D::PACKF;
-    const int n_lds_layers = (STAGE == BOND_TAIL) ? min(A.n_layers, 3) : 0;
-    const int n_packs = (STAGE == BOND_TAIL) ? 1 + n_lds_layers : NPACK;
+    const int n_lds_layers = BondStage<STAGE>::PER_LAYER ? min(A.n_layers, 3) : 0;
+    const int n_packs = BondStage<STAGE>::PER_LAYER ? 1 + n_lds_layers : NPACK;
     for (int q = 0; q < n_packs; ++q)
         for (int i = threadIdx.x; i < D::PACKF; i += NW * 64) packs[q * D::PACKF + i] = A.W[q][i];
     __syncthreads();
@@ -464,10 +467,6 @@ __global__ void __launch_bounds__(BondStage<STAGE>::NW * 64) k_bond_mlp(BondArgs
     int64_t ti = (int64_t)blockIdx.x * NW + wave;
     if (ti < n_tiles) {
         if (STAGE == BOND_TAIL) fetch_tile<F>(pre, A.S, ti * 32, A.n, lane);
-        if (STAGE == BOND_MBAR) {
-            fetch_tile<F>(pre, A.e1bar, ti * 32, A.n, lane);
-            fetch_tile<F>(pre2, A.m, ti * 32, A.n, lane);
-        }
         if (STAGE == BOND_E0BAR) fetch_tile<F>(pre, A.Pbar, ti * 32, A.n, lane);
     }
     for (; ti < n_tiles; ti += stride) {
@@ -513,58 +512,61 @@ __global__ void __launch_bounds__(BondStage<STAGE>::NW * 64) k_bond_mlp(BondArgs
                 gemm_regs<F>(A.Wx + (size_t)(l - 3) * D::PACKF, e1, acc, lane);
                 store_rows(A.wb + (size_t)l * A.wb_stride, row, ok, acc);
             }
-        } else if (STAGE == BOND_LAYER_BWD) {
+        } else if (STAGE == BOND_EBAR) {
+            f32x4 mv[NB][4];
+            load_rows(A.m, row, ok, mv);   // needed after the products
+            const float uc = ok ? A.u[row] : 0.f;
+            int32_t ri[32 / RPI], rj[32 / RPI];   // receiver and sender rows of this lane's tile rows
 #pragma unroll
             for (int r = 0; r < 32; r += RPI) {
                 const int64_t rw = row0 + r + rr;
-                const bool okr = rw < A.n;
-                f32x4 v = {0.f, 0.f, 0.f, 0.f};
-                if (okr) {
-                    const int64_t i = A.recv[A.edge[rw]], j = A.sender[rw];
-                    const f32x4 va = *reinterpret_cast<const f32x4 *>(A.abar + i * F + cc);
-                    const f32x4 vg = *reinterpret_cast<const f32x4 *>(A.g + j * F + cc);
-                    v = va * vg;
+                ri[r / RPI] = rj[r / RPI] = -1;
+                if (rw < A.n) {
+                    ri[r / RPI] = A.recv[A.edge[rw]];
+                    rj[r / RPI] = A.sender[rw];
                 }
-                *reinterpret_cast<f32x4 *>(tile + (r + rr) * FS + cc) = v;
             }
-            wave_lds_fence();
-            f32x4 zv[NB][4];
-            load_rows(A.e1bar, row, ok && !A.first, zv);
-            gemm_lds<F>(packs, tile, acc, lane);
-            wave_lds_fence();
 #pragma unroll
             for (int b = 0; b < NB; ++b)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) acc[b][r] += zv[b][r / 4][r % 4];
-            store_rows(A.e1bar, row, ok, acc);
-        } else if (STAGE == BOND_MBAR) {
+                for (int r = 0; r < 16; ++r) acc[b][r] = 0.f;
+            auto factor_tile = [&](int l) {   // dE/dwb_l of the tile's bonds = abar_l[receiver] * g_l[sender]
+                const float *al = A.abar + (size_t)l * A.abar_stride, *gl = A.g + (size_t)l * A.g_stride;
 #pragma unroll
-            for (int r = 0; r < 32; r += RPI) {
-                const int64_t rw = row0 + r + rr;
-                const bool okr = rw < A.n;
-                const f32x4 eb = pre.v[r / RPI], mm = pre2.v[r / RPI];   // zero past the end
-                const float ur = okr ? A.u[rw] : 0.f;
-                f32x4 v;
-                float part = 0.f;
-#pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    float sv, ds;
-                    silu_both(mm[c], sv, ds);
-                    v[c] = eb[c] * ur * ds;
-                    part = fmaf(eb[c], sv, part);
+                for (int r = 0; r < 32; r += RPI) {
+                    f32x4 v = {0.f, 0.f, 0.f, 0.f};
+                    if (ri[r / RPI] >= 0)
+                        v = *reinterpret_cast<const f32x4 *>(al + (int64_t)ri[r / RPI] * F + cc) *
+                            *reinterpret_cast<const f32x4 *>(gl + (int64_t)rj[r / RPI] * F + cc);
+                    *reinterpret_cast<f32x4 *>(tile + (r + rr) * FS + cc) = v;
                 }
+                wave_lds_fence();
+            };
+            for (int l = 0; l < n_lds_layers; ++l) {
+                factor_tile(l);
+                gemm_lds<F, true>(packs + (1 + l) * D::PACKF, tile, acc, lane);
+                wave_lds_fence();
+            }
+            for (int l = 3; l < A.n_layers; ++l) {
+                factor_tile(l);
+                gemm_lds<F, true>(A.Wx + (size_t)(l - 3) * D::PACKF, tile, acc, lane);
+                wave_lds_fence();
+            }
+            store_rows(A.e1bar, row, ok, acc);
+            float part = 0.f;
+            f32x16 mb[NB];
 #pragma unroll
-                for (int off = LPR / 2; off > 0; off >>= 1) part += __shfl_xor(part, off, 64);
-                if (okr && (lane % LPR) == 0) A.ubar[rw] = part;
-                *reinterpret_cast<f32x4 *>(tile + (r + rr) * FS + cc) = v;
-            }
-            wave_lds_fence();
-            if (more) {
-                fetch_tile<F>(pre, A.e1bar, (ti + stride) * 32, A.n, lane);
-                fetch_tile<F>(pre2, A.m, (ti + stride) * 32, A.n, lane);
-            }
-            gemm_lds<F>(packs, tile, acc, lane);
-            wave_lds_fence();
+            for (int b = 0; b < NB; ++b)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    float sv, ds;
+                    silu_both(mv[b][r / 4][r % 4], sv, ds);
+                    part = fmaf(acc[b][r], sv, part);
+                    mb[b][r] = acc[b][r] * uc * ds;
+                }
+            part += __shfl_xor(part, 32, 64);
+            if (ok && h == 0) A.ubar[row] = part;
+            gemm_regs<F>(packs, mb, acc, lane);
             store_rows(A.Sbar, row, ok, acc);
         } else {   // BOND_E0BAR
             stash_tile<F>(pre, tile, lane);

@@ -250,43 +250,6 @@ __device__ inline void gemm_lds(const float *__restrict__ Ap, const float *tile,
     }
 }
 
-// A operands of an F x F matrix held in registers (one f32x4 per (bo, bi, a))
-template <int F> struct RegPack {
-    f32x4 v[Dims<F>::NB][Dims<F>::NB][4];
-};
-
-template <int F> __device__ inline void load_pack(RegPack<F> &P, const float *__restrict__ Ap, int lane)
-{
-    constexpr int NB = Dims<F>::NB;
-#pragma unroll
-    for (int bo = 0; bo < NB; ++bo)
-#pragma unroll
-        for (int bi = 0; bi < NB; ++bi)
-#pragma unroll
-            for (int a = 0; a < 4; ++a)
-                P.v[bo][bi][a] = *reinterpret_cast<const f32x4 *>(Ap + ((((bo * NB + bi) * 4 + a) * 64 + lane) * 4));
-}
-
-// chained product with register-resident weights; consecutive MFMAs alternate accumulators
-template <int F>
-__device__ inline void gemm_rr(const RegPack<F> &P, const f32x16 (&in)[Dims<F>::NB], f32x16 (&out)[Dims<F>::NB])
-{
-    constexpr int NB = Dims<F>::NB;
-#pragma unroll
-    for (int bo = 0; bo < NB; ++bo)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) out[bo][r] = 0.f;
-#pragma unroll
-    for (int bi = 0; bi < NB; ++bi)
-#pragma unroll
-        for (int a = 0; a < 4; ++a)
-#pragma unroll
-            for (int c = 0; c < 4; ++c)
-#pragma unroll
-                for (int bo = 0; bo < NB; ++bo)
-                    out[bo] = __builtin_amdgcn_mfma_f32_32x32x2f32(P.v[bo][bi][a][c], in[bi][4 * a + c], out[bo], 0, 0, 0);
-}
-
 // chained product with the weights in LDS (packed A operands), B operand in registers; the A
 // operands of step k+1 are fetched while the MFMAs of step k run
 template <int F>
@@ -482,25 +445,6 @@ __device__ inline void gemm_k8r_block(const RegPack1<F> &P, const float (&v)[8],
     }
 }
 
-// out[f][item] = sum_n W1[n][f] v[n][item], v = 8 per-lane values of the lane's item
-template <int F>
-__device__ inline void gemm_k8(const float *__restrict__ A1, const float (&v)[8], f32x16 (&out)[Dims<F>::NB], int lane)
-{
-    constexpr int NB = Dims<F>::NB;
-    const int h = lane >> 5;
-#pragma unroll
-    for (int bo = 0; bo < NB; ++bo)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) out[bo][r] = 0.f;
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-        const float bv = h ? v[2 * s + 1] : v[2 * s];
-#pragma unroll
-        for (int bo = 0; bo < NB; ++bo)
-            out[bo] = __builtin_amdgcn_mfma_f32_32x32x2f32(A1[(bo * 4 + s) * 64 + lane], bv, out[bo], 0, 0, 0);
-    }
-}
-
 // accumulator layout -> item-major LDS tile
 template <int F>
 __device__ inline void regs_to_tile(const f32x16 (&v)[Dims<F>::NB], float *tile, int lane)
@@ -515,16 +459,6 @@ __device__ inline void regs_to_tile(const f32x16 (&v)[Dims<F>::NB], float *tile,
             f32x4 x = {v[b][4 * a], v[b][4 * a + 1], v[b][4 * a + 2], v[b][4 * a + 3]};
             *reinterpret_cast<f32x4 *>(tile + c32 * FS + 32 * b + 8 * a + 4 * h) = x;
         }
-}
-
-__device__ inline int64_t lower_bound_i64(const int64_t *__restrict__ a, int64_t n, int64_t v)
-{
-    int64_t lo = 0, hi = n;  // first index in [0, n] with a[idx] >= v (a has n + 1 entries, searched over [0, n))
-    while (lo < hi) {
-        const int64_t mid = (lo + hi) >> 1;
-        if (a[mid] < v) lo = mid + 1; else hi = mid;
-    }
-    return lo;
 }
 
 #endif  // MLIP_MODEL_TILES_H

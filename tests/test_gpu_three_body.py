@@ -189,3 +189,37 @@ def test_bf16_filter_products(three_body):
         print(f"bf16 filter products, three_body={three_body}, {P} slab(s): dE/E {de:.2e}, dF {df:.2e}")
         assert df <= 2e-2 and de <= 1e-2
         assert df > 1e-6    # it really is the reduced-precision path
+
+
+def test_one_handle_reused_across_sizes_variants_and_slab_counts():
+    """The same graph handle rebuilt for systems of different size, slab count and model variant, growing and
+    shrinking: no state of an earlier build (buffers, bond lists, partitions) may leak into a later result.  Every
+    result must equal, bit for bit, that of a fresh handle (all reductions run in a fixed order), and match the oracle
+    (energy relative to the sum of the per-atom magnitudes: these seeds are not chosen for a large total)."""
+    from oracle import model as om
+    from gpu_util import gpu_energy_forces
+    c = wl.make_config(4, n=3)
+    two_body = {k: c["weights"][k] for k in ("emb", "W1", "W2", "Wm", "Wo", "Wr1", "wr2")}
+    g = None
+    for n, P, three_body in [(5, 3, False), (3, 1, True), (4, 8, True), (6, 2, False), (2, 4, True), (5, 1, True)]:
+        ci = wl.make_config(4, n=n, seed=wl.BASE_SEED + 40 + n)
+        pos, cell, sp = ci["positions"], ci["cell"], ci["species"]
+        ref_g = og.build_graph(pos, cell, c["r_cut"])
+        g = gpu_graph(pos, cell, sp, c["r_cut"], n_slabs=P, graph=g)
+        fresh = gpu_graph(pos, cell, sp, c["r_cut"], n_slabs=P)
+        mode = 1 if P > 1 else 0
+        label = f"n = {n}, P = {P}, three_body = {three_body}"
+        if three_body:
+            ref = tb.energy_forces3(pos, cell, sp, c["weights"], ref_g, c["r_cut"], c["r_bond"], c["K"], c["p"])
+            e, f, ae = _gpu3(g, c, mode=mode)
+            e2, f2, ae2 = _gpu3(fresh, c, mode=mode)
+        else:
+            ref = om.energy_forces(pos, cell, sp, two_body, ref_g, c["r_cut"], c["K"], c["p"])
+            e, f, ae = gpu_energy_forces(g, two_body, c["p"], mode)
+            e2, f2, ae2 = gpu_energy_forces(fresh, two_body, c["p"], mode)
+        fresh.destroy()
+        assert e == e2 and np.array_equal(f, f2) and np.array_equal(ae, ae2), label
+        de = abs(e - ref["energy"]) / np.abs(ref["atom_energy"]).sum()
+        df = np.abs(f - ref["forces"]).max() / np.abs(ref["forces"]).max()
+        print(f"{label}: dE/sum|eps| {de:.2e}, dF {df:.2e}, E {ref['energy']:.3f}, sum|eps| {np.abs(ref['atom_energy']).sum():.3f}")
+        assert de <= 1e-5 and df <= F_RTOL, label

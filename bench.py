@@ -82,7 +82,7 @@ def main():
     ap.add_argument("--config", type=int, default=3)
     ap.add_argument("--cells", type=int, default=None, help="override fcc cells per side (smaller runs)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
-    ap.add_argument("--cpu-cells", type=int, default=40)
+    ap.add_argument("--cpu-cells", type=int, default=48, help="fcc cells per side of the oracle's bounded sample")
     ap.add_argument("--no-whole", action="store_true", help="skip the unpartitioned (whole-graph) run of the same system")
     ap.add_argument("--precision", choices=("f32", "f32split", "bf16"), default="f32",
                     help="f32split: the F x F products of the filter MLP as split-fp16 MFMA triples (fp32-grade results); "
@@ -237,7 +237,7 @@ def main():
                               "energy": energy_whole, "rel_energy_difference_to_slabs": abs(energy_whole - energy) / abs(energy),
                               "note": "graph build without partition + unpartitioned energy+forces of the same system"}
     if not args.no_cpu:
-        res["cpu_baseline"] = cpu_baseline(args.config, min(args.cpu_cells, 24) if three_body else args.cpu_cells)
+        res["cpu_baseline"] = cpu_baseline(args.config, min(args.cpu_cells, 36) if three_body else args.cpu_cells)
     print(json.dumps(res))
 
 

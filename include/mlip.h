@@ -51,7 +51,9 @@ enum { MLIP_MODE_WHOLE = 0, MLIP_MODE_SLABS = 1 };
  * MLIP_PRECISION_FP32: everything from the basis on in fp32 (fp32 MFMA).
  * MLIP_PRECISION_BF16: the F x F products of the filter MLP (forward w = SiLU(t) W2, reverse sbar = wbar W2^T)
  *   take bf16 operands with fp32 accumulation (benchmark configuration 4: "edge MLPs in bf16 with fp32
- *   accumulation"); everything else stays fp32.  Forces then agree with the fp64 result to about 4e-3 max|F|.
+ *   accumulation"), and in mlip_forward_bonds the F x F products of the bond MLPs as well; everything else stays
+ *   fp32 (arrays, the K = 8 products, activations, sums).  Forces then agree with the fp64 result to about
+ *   4e-3 max|F|.
  * MLIP_PRECISION_FP32_SPLIT: the same two products with every operand split into two fp16 parts (hi + lo, 22
  *   significant bits) and taken as three fp16 MFMA products with fp32 accumulation.  The results meet the fp32
  *   mode's bounds (the dropped terms are of the size of fp32 accumulation rounding) in a fraction of the matrix

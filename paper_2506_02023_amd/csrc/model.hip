@@ -33,6 +33,7 @@
 
 #include <algorithm>
 #include <cmath>
+#include <type_traits>
 
 namespace mlip {
 
@@ -100,13 +101,13 @@ template <int F, int OP> int launch_node(mlip_graph *g, NodeBatch &b)
     return MLIP_OK;
 }
 
-template <int F, int STAGE> int launch_bond_mlp(mlip_graph *g, const BondArgs &a)
+template <int F, int STAGE, bool BF16> int launch_bond_mlp(mlip_graph *g, const BondArgs &a)
 {
     constexpr int NW = BondStage<STAGE>::NW;
     constexpr size_t lds = sizeof(float) * (BondStage<STAGE>::NPACK * Dims<F>::PACKF + NW * Dims<F>::TILE);
     static bool configured = false;
     if (!configured) {
-        MLIP_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_bond_mlp<F, STAGE>),
+        MLIP_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_bond_mlp<F, STAGE, BF16>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         configured = true;
     }
@@ -114,7 +115,7 @@ template <int F, int STAGE> int launch_bond_mlp(mlip_graph *g, const BondArgs &a
     const int64_t n_tiles = (a.n + 31) / 32;
     // each block keeps its operand packs in LDS, so let it walk several tiles
     const unsigned blocks = (unsigned)std::min<int64_t>((n_tiles + NW - 1) / NW, 8192 / NW);
-    k_bond_mlp<F, STAGE><<<blocks, NW * 64, lds, g->stream>>>(a);
+    k_bond_mlp<F, STAGE, BF16><<<blocks, NW * 64, lds, g->stream>>>(a);
     MLIP_HIP(hipGetLastError());
     return MLIP_OK;
 }
@@ -302,6 +303,7 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
         return a;
     };
     bool any_bonds = false;
+    const bool bond_bf16 = (prec == kPrecBf16);   // the bond MLPs' F x F products follow the filter MLP's precision mode
     if (bw) {
         bpb.rc = bw->r_bond;
         bpb.inv_rc = 1.0f / bw->r_bond;
@@ -324,15 +326,21 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
         bpk = g->bond_wpack.as<float>();
         prof_begin(g, MLIP_PROF_BOND);
         const float *Wta = bw->Wt1, *Wtb = bw->Wt1 + ffp, *Wtc = bw->Wt1 + 2 * ffp;
-        k_pack_ff<<<pb, 256, 0, s>>>(Wta, F, 1, 1.0f, bpk + 0 * ffp);
-        k_pack_ff<<<pb, 256, 0, s>>>(Wtb, F, 1, 1.0f, bpk + 1 * ffp);
-        k_pack_ff<<<pb, 256, 0, s>>>(bw->Wt2, F, 1, 1.0f, bpk + 2 * ffp);
-        k_pack_ff<<<pb, 256, 0, s>>>(Wta, F, 0, 1.0f, bpk + 3 * ffp);
-        k_pack_ff<<<pb, 256, 0, s>>>(Wtb, F, 0, 1.0f, bpk + 4 * ffp);
-        k_pack_ff<<<pb, 256, 0, s>>>(bw->Wt2, F, 0, 1.0f, bpk + 5 * ffp);
+        auto pack_bond = [&](const float *Wsrc, int trans, int slot) {   // fp32 pack, or bf16 in the first half of the slot
+            if (bond_bf16)
+                k_pack_ff_bf16<<<pb, 256, 0, s>>>(Wsrc, F, trans, 1.0f, reinterpret_cast<__bf16 *>(bpk + (size_t)slot * ffp));
+            else
+                k_pack_ff<<<pb, 256, 0, s>>>(Wsrc, F, trans, 1.0f, bpk + (size_t)slot * ffp);
+        };
+        pack_bond(Wta, 1, 0);
+        pack_bond(Wtb, 1, 1);
+        pack_bond(bw->Wt2, 1, 2);
+        pack_bond(Wta, 0, 3);
+        pack_bond(Wtb, 0, 4);
+        pack_bond(bw->Wt2, 0, 5);
         for (int l = 0; l < L; ++l) {
-            k_pack_ff<<<pb, 256, 0, s>>>(bw->Wb + l * ffp, F, 1, 1.0f, bpk + (6 + l) * ffp);
-            k_pack_ff<<<pb, 256, 0, s>>>(bw->Wb + l * ffp, F, 0, 1.0f, bpk + (6 + L + l) * ffp);
+            pack_bond(bw->Wb + l * ffp, 1, 6 + l);
+            pack_bond(bw->Wb + l * ffp, 0, 6 + L + l);
         }
         k_pack_w1<<<blocks_for(Dims<F>::PACK1, 256), 256, 0, s>>>(bw->We0, F, 1.0f, bpk + (size_t)(6 + 2 * L) * ffp);
         MLIP_HIP(hipGetLastError());
@@ -340,7 +348,7 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
             BondArgs a = bond_args(views[p]);
             a.W[0] = bpk + 0 * ffp;
             a.W[1] = bpk + 1 * ffp;
-            MLIP_TRY((launch_bond_mlp<F, BOND_HEAD>(g, a)));
+            MLIP_TRY(bond_bf16 ? (launch_bond_mlp<F, BOND_HEAD, true>(g, a)) : (launch_bond_mlp<F, BOND_HEAD, false>(g, a)));
         }
         prof_end(g);
         prof_begin(g, MLIP_PROF_TRIPLET_FWD);
@@ -361,7 +369,7 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
             for (int l = 0; l < std::min(L, 3); ++l) a.W[1 + l] = bpk + (6 + l) * ffp;
             a.Wx = bpk + (6 + 3) * ffp;
             a.n_layers = L;
-            MLIP_TRY((launch_bond_mlp<F, BOND_TAIL>(g, a)));
+            MLIP_TRY(bond_bf16 ? (launch_bond_mlp<F, BOND_TAIL, true>(g, a)) : (launch_bond_mlp<F, BOND_TAIL, false>(g, a)));
         }
         prof_end(g);
     }
@@ -575,7 +583,7 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
             for (int l = 0; l < std::min(L, 3); ++l) a.W[1 + l] = bpk + (6 + L + l) * ffp;
             a.Wx = bpk + (6 + L + 3) * ffp;
             a.n_layers = L;
-            MLIP_TRY((launch_bond_mlp<F, BOND_EBAR>(g, a)));
+            MLIP_TRY(bond_bf16 ? (launch_bond_mlp<F, BOND_EBAR, true>(g, a)) : (launch_bond_mlp<F, BOND_EBAR, false>(g, a)));
         }
         prof_end(g);
         prof_begin(g, MLIP_PROF_TRIPLET_BWD);
@@ -594,7 +602,7 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
             BondArgs a = bond_args(views[p]);
             a.W[0] = bpk + 3 * ffp;
             a.W[1] = bpk + 4 * ffp;
-            MLIP_TRY((launch_bond_mlp<F, BOND_E0BAR>(g, a)));
+            MLIP_TRY(bond_bf16 ? (launch_bond_mlp<F, BOND_E0BAR, true>(g, a)) : (launch_bond_mlp<F, BOND_E0BAR, false>(g, a)));
         }
         prof_end(g);
     }

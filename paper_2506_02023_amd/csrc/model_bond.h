@@ -418,7 +418,9 @@ template <int STAGE> struct BondStage {
     static constexpr int NPACK = PER_LAYER ? 4 : 2;
 };
 
-template <int F, int STAGE>
+// BF16: the F x F products take bf16 operands (packs prepared as bf16, activations rounded in registers) with fp32
+// accumulation, as the filter MLP's do in that precision mode; the K = 8 products and all arrays stay fp32.
+template <int F, int STAGE, bool BF16>
 __global__ void __launch_bounds__(BondStage<STAGE>::NW * 64) k_bond_mlp(BondArgs A)
 {
     using D = Dims<F>;
@@ -430,8 +432,8 @@ __global__ void __launch_bounds__(BondStage<STAGE>::NW * 64) k_bond_mlp(BondArgs
     float *tiles = packs + NPACK * D::PACKF;
     const int n_lds_layers = BondStage<STAGE>::PER_LAYER ? min(A.n_layers, 3) : 0;
     const int n_packs = BondStage<STAGE>::PER_LAYER ? 1 + n_lds_layers : NPACK;
-    for (int q = 0; q < n_packs; ++q)
-        for (int i = threadIdx.x; i < D::PACKF; i += NW * 64) packs[q * D::PACKF + i] = A.W[q][i];
+    for (int q = 0; q < n_packs; ++q)   // (a bf16 pack fills the first half of its slot)
+        for (int i = threadIdx.x; i < (BF16 ? D::PACKF / 2 : D::PACKF); i += NW * 64) packs[q * D::PACKF + i] = A.W[q][i];
     __syncthreads();
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int c32 = lane & 31, h = lane >> 5;
@@ -463,6 +465,19 @@ __global__ void __launch_bounds__(BondStage<STAGE>::NW * 64) k_bond_mlp(BondArgs
                 }
     };
 
+    // out (+)= M x, x a 32-bond tile in LDS (this lane's bond = tile row c32) or a tile held in accumulator layout
+    auto mul_tile = [&](auto accumulate, const float *pack, const float *t, f32x16 (&out)[NB]) {
+        constexpr bool ACC = decltype(accumulate)::value;
+        if (BF16) gemm_row_bf16<F, ACC>(reinterpret_cast<const __bf16 *>(pack), t + c32 * FS, out, lane);
+        else gemm_lds<F, ACC>(pack, t, out, lane);
+    };
+    auto mul_regs = [&](const float *pack, const f32x16 (&in)[NB], f32x16 (&out)[NB]) {
+        if (BF16) gemm_rl_bf16<F>(reinterpret_cast<const __bf16 *>(pack), in, out, lane);
+        else gemm_regs<F>(pack, in, out, lane);
+    };
+    using Fresh = std::false_type;
+    using Add = std::true_type;
+
     TileRegs<F> pre, pre2;
     int64_t ti = (int64_t)blockIdx.x * NW + wave;
     if (ti < n_tiles) {
@@ -481,9 +496,9 @@ __global__ void __launch_bounds__(BondStage<STAGE>::NW * 64) k_bond_mlp(BondArgs
             radial_basis<false>(ok ? A.d[row] : A.bp.rc, A.bp, bb, db);   // 0 at the cutoff
             f32x16 e0[NB];
             gemm_k8r<F>(W0, bb, e0, lane);
-            gemm_regs<F>(packs, e0, acc, lane);
+            mul_regs(packs, e0, acc);
             store_rows(A.P, row, ok, acc);
-            gemm_regs<F>(packs + D::PACKF, e0, acc, lane);
+            mul_regs(packs + D::PACKF, e0, acc);
             store_rows(A.Q, row, ok, acc);
         } else if (STAGE == BOND_TAIL) {
             stash_tile<F>(pre, tile, lane);
@@ -491,7 +506,7 @@ __global__ void __launch_bounds__(BondStage<STAGE>::NW * 64) k_bond_mlp(BondArgs
             const float uc = ok ? A.u[row] : 0.f;
             const float dc = ok ? A.d[row] : A.bp.rc;
             if (more) fetch_tile<F>(pre, A.S, (ti + stride) * 32, A.n, lane);
-            gemm_lds<F>(packs, tile, acc, lane);
+            mul_tile(Fresh{}, packs, tile, acc);
             wave_lds_fence();
             store_rows(A.m, row, ok, acc);
             f32x16 e1[NB];
@@ -505,11 +520,11 @@ __global__ void __launch_bounds__(BondStage<STAGE>::NW * 64) k_bond_mlp(BondArgs
 #pragma unroll
                 for (int r = 0; r < 16; ++r) e1[b][r] = fmaf(uc, silu_f(acc[b][r]), e1[b][r]);
             for (int l = 0; l < n_lds_layers; ++l) {
-                gemm_regs<F>(packs + (1 + l) * D::PACKF, e1, acc, lane);
+                mul_regs(packs + (1 + l) * D::PACKF, e1, acc);
                 store_rows(A.wb + (size_t)l * A.wb_stride, row, ok, acc);
             }
             for (int l = 3; l < A.n_layers; ++l) {
-                gemm_regs<F>(A.Wx + (size_t)(l - 3) * D::PACKF, e1, acc, lane);
+                mul_regs(A.Wx + (size_t)(l - 3) * D::PACKF, e1, acc);
                 store_rows(A.wb + (size_t)l * A.wb_stride, row, ok, acc);
             }
         } else if (STAGE == BOND_EBAR) {
@@ -544,12 +559,12 @@ __global__ void __launch_bounds__(BondStage<STAGE>::NW * 64) k_bond_mlp(BondArgs
             };
             for (int l = 0; l < n_lds_layers; ++l) {
                 factor_tile(l);
-                gemm_lds<F, true>(packs + (1 + l) * D::PACKF, tile, acc, lane);
+                mul_tile(Add{}, packs + (1 + l) * D::PACKF, tile, acc);
                 wave_lds_fence();
             }
             for (int l = 3; l < A.n_layers; ++l) {
                 factor_tile(l);
-                gemm_lds<F, true>(A.Wx + (size_t)(l - 3) * D::PACKF, tile, acc, lane);
+                mul_tile(Add{}, A.Wx + (size_t)(l - 3) * D::PACKF, tile, acc);
                 wave_lds_fence();
             }
             store_rows(A.e1bar, row, ok, acc);
@@ -566,7 +581,7 @@ __global__ void __launch_bounds__(BondStage<STAGE>::NW * 64) k_bond_mlp(BondArgs
                 }
             part += __shfl_xor(part, 32, 64);
             if (ok && h == 0) A.ubar[row] = part;
-            gemm_regs<F>(packs, mb, acc, lane);
+            mul_regs(packs, mb, acc);
             store_rows(A.Sbar, row, ok, acc);
         } else {   // BOND_E0BAR
             stash_tile<F>(pre, tile, lane);
@@ -574,12 +589,12 @@ __global__ void __launch_bounds__(BondStage<STAGE>::NW * 64) k_bond_mlp(BondArgs
             fetch_tile<F>(pre2, A.Qbar, row0, A.n, lane);   // in flight during the first product
             f32x4 zv[NB][4];
             load_rows(A.e1bar, row, ok, zv);
-            gemm_lds<F>(packs, tile, acc, lane);
+            mul_tile(Fresh{}, packs, tile, acc);
             wave_lds_fence();
             stash_tile<F>(pre2, tile, lane);
             wave_lds_fence();
             if (more) fetch_tile<F>(pre, A.Pbar, (ti + stride) * 32, A.n, lane);
-            gemm_lds<F, true>(packs + D::PACKF, tile, acc, lane);
+            mul_tile(Add{}, packs + D::PACKF, tile, acc);
             wave_lds_fence();
             float bb[8], db[8];
             radial_basis<true>(ok ? A.d[row] : A.bp.rc, A.bp, bb, db);

@@ -291,16 +291,17 @@ __device__ inline void gemm_rl(const float *__restrict__ Ap, const f32x16 (&in)[
 }
 
 // gemm_rl in bf16: weights as a bf16 pack in LDS, the chained B operand rounded to bf16, fp32 accumulation
-template <int F>
+template <int F, bool ACCUMULATE = false>
 __device__ inline void gemm_rl_bf16(const __bf16 *__restrict__ Ap, const f32x16 (&in)[Dims<F>::NB],
                                     f32x16 (&out)[Dims<F>::NB], int lane)
 {
     constexpr int NB = Dims<F>::NB;
     const bf16x8 *A = reinterpret_cast<const bf16x8 *>(Ap) + lane;
+    if (!ACCUMULATE)
 #pragma unroll
-    for (int bo = 0; bo < NB; ++bo)
+        for (int bo = 0; bo < NB; ++bo)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) out[bo][r] = 0.f;
+            for (int r = 0; r < 16; ++r) out[bo][r] = 0.f;
 #pragma unroll
     for (int bi = 0; bi < NB; ++bi)
 #pragma unroll
@@ -316,16 +317,17 @@ __device__ inline void gemm_rl_bf16(const __bf16 *__restrict__ Ap, const f32x16 
 }
 
 // the same with the B operand taken from an item-major LDS row of this lane's item (fp32, rounded here)
-template <int F>
+template <int F, bool ACCUMULATE = false>
 __device__ inline void gemm_row_bf16(const __bf16 *__restrict__ Ap, const float *row, f32x16 (&out)[Dims<F>::NB], int lane)
 {
     constexpr int NB = Dims<F>::NB;
     const int h = lane >> 5;
     const bf16x8 *A = reinterpret_cast<const bf16x8 *>(Ap) + lane;
+    if (!ACCUMULATE)
 #pragma unroll
-    for (int bo = 0; bo < NB; ++bo)
+        for (int bo = 0; bo < NB; ++bo)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) out[bo][r] = 0.f;
+            for (int r = 0; r < 16; ++r) out[bo][r] = 0.f;
 #pragma unroll
     for (int bi = 0; bi < NB; ++bi)
 #pragma unroll

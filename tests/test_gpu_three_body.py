@@ -161,10 +161,12 @@ def test_three_body_config4_full_size():
 
 @pytest.mark.parametrize("three_body", [False, True])
 def test_bf16_filter_products(three_body):
-    """MLIP_PRECISION_BF16: the F x F products of the filter MLP in bf16 with fp32 accumulation (what benchmark
-    configuration 4 asks for).  Bound from the benchmark: forces within 2e-2 max|F| of the fp64 oracle; the energy
-    (no bound stated) is held to 1e-2 relative: bf16 carries 8 significant bits and the rounding of the weights is
-    the same for every edge, so it does not average out (measured 4e-3 on both)."""
+    """MLIP_PRECISION_BF16: the F x F products of the filter MLP, and in the three-body variant those of the bond MLPs,
+    in bf16 with fp32 accumulation (what benchmark configuration 4 asks for).  Bound from the benchmark: forces within
+    2e-2 max|F| of the fp64 oracle (measured 2e-3 .. 4e-3).  No energy bound is stated; the energy is held to 2e-3 of
+    the sum of the per-atom magnitudes: bf16 carries 8 significant bits and the rounding of the weights is the same
+    for every edge and bond, so it does not average out (measured 4e-4 and 6e-4 of that sum, i.e. 4e-3 of E two-body and 1.1e-2 of E
+    three-body, where the total is a small fraction of the sum)."""
     import torch
     import paper_2506_02023_amd as M
     c = wl.make_config(4, n=6)
@@ -186,8 +188,9 @@ def test_bf16_filter_products(three_body):
         torch.cuda.synchronize()
         e, f = float(e.cpu()[0]), f.cpu().numpy().astype(np.float64)
         de, df = abs(e - ref["energy"]) / abs(ref["energy"]), np.abs(f - ref["forces"]).max() / fmax
-        print(f"bf16 filter products, three_body={three_body}, {P} slab(s): dE/E {de:.2e}, dF {df:.2e}")
-        assert df <= 2e-2 and de <= 1e-2
+        des = abs(e - ref["energy"]) / np.abs(ref["atom_energy"]).sum()
+        print(f"bf16 products, three_body={three_body}, {P} slab(s): dE/E {de:.2e}, dE/sum|eps| {des:.2e}, dF {df:.2e}")
+        assert df <= 2e-2 and des <= 2e-3
         assert df > 1e-6    # it really is the reduced-precision path
 
 

@@ -54,7 +54,7 @@ enum { MLIP_MODE_WHOLE = 0, MLIP_MODE_SLABS = 1 };
  *   accumulation"), and in mlip_forward_bonds the F x F products of the bond MLPs as well; everything else stays
  *   fp32 (arrays, the K = 8 products, activations, sums).  Forces then agree with the fp64 result to about
  *   4e-3 max|F|.
- * MLIP_PRECISION_FP32_SPLIT: the same two products with every operand split into two fp16 parts (hi + lo, 22
+ * MLIP_PRECISION_FP32_SPLIT: the same products (the bond MLPs' included) with every operand split into two fp16 parts (hi + lo, 22
  *   significant bits) and taken as three fp16 MFMA products with fp32 accumulation.  The results meet the fp32
  *   mode's bounds (the dropped terms are of the size of fp32 accumulation rounding) in a fraction of the matrix
  *   time; the operands of those products - SiLU outputs and the products abar * g of the reverse pass - must

@@ -101,13 +101,13 @@ template <int F, int OP> int launch_node(mlip_graph *g, NodeBatch &b)
     return MLIP_OK;
 }
 
-template <int F, int STAGE, bool BF16> int launch_bond_mlp(mlip_graph *g, const BondArgs &a)
+template <int F, int STAGE, int PREC> int launch_bond_mlp(mlip_graph *g, const BondArgs &a)
 {
     constexpr int NW = BondStage<STAGE>::NW;
     constexpr size_t lds = sizeof(float) * (BondStage<STAGE>::NPACK * Dims<F>::PACKF + NW * Dims<F>::TILE);
     static bool configured = false;
     if (!configured) {
-        MLIP_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_bond_mlp<F, STAGE, BF16>),
+        MLIP_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_bond_mlp<F, STAGE, PREC>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         configured = true;
     }
@@ -115,7 +115,7 @@ template <int F, int STAGE, bool BF16> int launch_bond_mlp(mlip_graph *g, const 
     const int64_t n_tiles = (a.n + 31) / 32;
     // each block keeps its operand packs in LDS, so let it walk several tiles
     const unsigned blocks = (unsigned)std::min<int64_t>((n_tiles + NW - 1) / NW, 8192 / NW);
-    k_bond_mlp<F, STAGE, BF16><<<blocks, NW * 64, lds, g->stream>>>(a);
+    k_bond_mlp<F, STAGE, PREC><<<blocks, NW * 64, lds, g->stream>>>(a);
     MLIP_HIP(hipGetLastError());
     return MLIP_OK;
 }
@@ -303,7 +303,6 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
         return a;
     };
     bool any_bonds = false;
-    const bool bond_bf16 = (prec == kPrecBf16);   // the bond MLPs' F x F products follow the filter MLP's precision mode
     if (bw) {
         bpb.rc = bw->r_bond;
         bpb.inv_rc = 1.0f / bw->r_bond;
@@ -326,9 +325,13 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
         bpk = g->bond_wpack.as<float>();
         prof_begin(g, MLIP_PROF_BOND);
         const float *Wta = bw->Wt1, *Wtb = bw->Wt1 + ffp, *Wtc = bw->Wt1 + 2 * ffp;
-        auto pack_bond = [&](const float *Wsrc, int trans, int slot) {   // fp32 pack, or bf16 in the first half of the slot
-            if (bond_bf16)
+        // the bond MLPs' F x F products follow the filter MLP's precision mode: fp32 pack, bf16 in the first half of the
+        // slot, or split-fp16 (hi and lo halves)
+        auto pack_bond = [&](const float *Wsrc, int trans, int slot) {
+            if (prec == kPrecBf16)
                 k_pack_ff_bf16<<<pb, 256, 0, s>>>(Wsrc, F, trans, 1.0f, reinterpret_cast<__bf16 *>(bpk + (size_t)slot * ffp));
+            else if (prec == kPrecF16x3)
+                k_pack_ff_f16x2<<<pb, 256, 0, s>>>(Wsrc, F, trans, 1.0f, reinterpret_cast<_Float16 *>(bpk + (size_t)slot * ffp));
             else
                 k_pack_ff<<<pb, 256, 0, s>>>(Wsrc, F, trans, 1.0f, bpk + (size_t)slot * ffp);
         };
@@ -348,7 +351,8 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
             BondArgs a = bond_args(views[p]);
             a.W[0] = bpk + 0 * ffp;
             a.W[1] = bpk + 1 * ffp;
-            MLIP_TRY(bond_bf16 ? (launch_bond_mlp<F, BOND_HEAD, true>(g, a)) : (launch_bond_mlp<F, BOND_HEAD, false>(g, a)));
+            MLIP_TRY(prec == kPrecBf16 ? (launch_bond_mlp<F, BOND_HEAD, kPrecBf16>(g, a))
+                     : prec == kPrecF16x3 ? (launch_bond_mlp<F, BOND_HEAD, kPrecF16x3>(g, a)) : (launch_bond_mlp<F, BOND_HEAD, kPrecF32>(g, a)));
         }
         prof_end(g);
         prof_begin(g, MLIP_PROF_TRIPLET_FWD);
@@ -369,7 +373,8 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
             for (int l = 0; l < std::min(L, 3); ++l) a.W[1 + l] = bpk + (6 + l) * ffp;
             a.Wx = bpk + (6 + 3) * ffp;
             a.n_layers = L;
-            MLIP_TRY(bond_bf16 ? (launch_bond_mlp<F, BOND_TAIL, true>(g, a)) : (launch_bond_mlp<F, BOND_TAIL, false>(g, a)));
+            MLIP_TRY(prec == kPrecBf16 ? (launch_bond_mlp<F, BOND_TAIL, kPrecBf16>(g, a))
+                     : prec == kPrecF16x3 ? (launch_bond_mlp<F, BOND_TAIL, kPrecF16x3>(g, a)) : (launch_bond_mlp<F, BOND_TAIL, kPrecF32>(g, a)));
         }
         prof_end(g);
     }
@@ -583,7 +588,8 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
             for (int l = 0; l < std::min(L, 3); ++l) a.W[1 + l] = bpk + (6 + L + l) * ffp;
             a.Wx = bpk + (6 + L + 3) * ffp;
             a.n_layers = L;
-            MLIP_TRY(bond_bf16 ? (launch_bond_mlp<F, BOND_EBAR, true>(g, a)) : (launch_bond_mlp<F, BOND_EBAR, false>(g, a)));
+            MLIP_TRY(prec == kPrecBf16 ? (launch_bond_mlp<F, BOND_EBAR, kPrecBf16>(g, a))
+                     : prec == kPrecF16x3 ? (launch_bond_mlp<F, BOND_EBAR, kPrecF16x3>(g, a)) : (launch_bond_mlp<F, BOND_EBAR, kPrecF32>(g, a)));
         }
         prof_end(g);
         prof_begin(g, MLIP_PROF_TRIPLET_BWD);
@@ -602,7 +608,8 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
             BondArgs a = bond_args(views[p]);
             a.W[0] = bpk + 3 * ffp;
             a.W[1] = bpk + 4 * ffp;
-            MLIP_TRY(bond_bf16 ? (launch_bond_mlp<F, BOND_E0BAR, true>(g, a)) : (launch_bond_mlp<F, BOND_E0BAR, false>(g, a)));
+            MLIP_TRY(prec == kPrecBf16 ? (launch_bond_mlp<F, BOND_E0BAR, kPrecBf16>(g, a))
+                     : prec == kPrecF16x3 ? (launch_bond_mlp<F, BOND_E0BAR, kPrecF16x3>(g, a)) : (launch_bond_mlp<F, BOND_E0BAR, kPrecF32>(g, a)));
         }
         prof_end(g);
     }

@@ -418,9 +418,10 @@ template <int STAGE> struct BondStage {
     static constexpr int NPACK = PER_LAYER ? 4 : 2;
 };
 
-// BF16: the F x F products take bf16 operands (packs prepared as bf16, activations rounded in registers) with fp32
-// accumulation, as the filter MLP's do in that precision mode; the K = 8 products and all arrays stay fp32.
-template <int F, int STAGE, bool BF16>
+// PREC: the F x F products follow the precision mode of the filter MLP's (fp32 MFMA; bf16 operands; split-fp16 triples;
+// packs prepared accordingly, activations converted in registers, fp32 accumulation); the K = 8 products and all
+// arrays stay fp32.
+template <int F, int STAGE, int PREC>
 __global__ void __launch_bounds__(BondStage<STAGE>::NW * 64) k_bond_mlp(BondArgs A)
 {
     using D = Dims<F>;
@@ -433,7 +434,7 @@ __global__ void __launch_bounds__(BondStage<STAGE>::NW * 64) k_bond_mlp(BondArgs
     const int n_lds_layers = BondStage<STAGE>::PER_LAYER ? min(A.n_layers, 3) : 0;
     const int n_packs = BondStage<STAGE>::PER_LAYER ? 1 + n_lds_layers : NPACK;
     for (int q = 0; q < n_packs; ++q)   // (a bf16 pack fills the first half of its slot)
-        for (int i = threadIdx.x; i < (BF16 ? D::PACKF / 2 : D::PACKF); i += NW * 64) packs[q * D::PACKF + i] = A.W[q][i];
+        for (int i = threadIdx.x; i < (PREC == kPrecBf16 ? D::PACKF / 2 : D::PACKF); i += NW * 64) packs[q * D::PACKF + i] = A.W[q][i];
     __syncthreads();
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int c32 = lane & 31, h = lane >> 5;
@@ -468,11 +469,13 @@ __global__ void __launch_bounds__(BondStage<STAGE>::NW * 64) k_bond_mlp(BondArgs
     // out (+)= M x, x a 32-bond tile in LDS (this lane's bond = tile row c32) or a tile held in accumulator layout
     auto mul_tile = [&](auto accumulate, const float *pack, const float *t, f32x16 (&out)[NB]) {
         constexpr bool ACC = decltype(accumulate)::value;
-        if (BF16) gemm_row_bf16<F, ACC>(reinterpret_cast<const __bf16 *>(pack), t + c32 * FS, out, lane);
+        if (PREC == kPrecBf16) gemm_row_bf16<F, ACC>(reinterpret_cast<const __bf16 *>(pack), t + c32 * FS, out, lane);
+        else if (PREC == kPrecF16x3) gemm_row_f16x3<F, ACC>(reinterpret_cast<const _Float16 *>(pack), t + c32 * FS, out, lane);
         else gemm_lds<F, ACC>(pack, t, out, lane);
     };
     auto mul_regs = [&](const float *pack, const f32x16 (&in)[NB], f32x16 (&out)[NB]) {
-        if (BF16) gemm_rl_bf16<F>(reinterpret_cast<const __bf16 *>(pack), in, out, lane);
+        if (PREC == kPrecBf16) gemm_rl_bf16<F>(reinterpret_cast<const __bf16 *>(pack), in, out, lane);
+        else if (PREC == kPrecF16x3) gemm_rl_f16x3<F>(reinterpret_cast<const _Float16 *>(pack), in, out, lane);
         else gemm_regs<F>(pack, in, out, lane);
     };
     using Fresh = std::false_type;

@@ -343,17 +343,18 @@ __device__ inline void gemm_row_bf16(const __bf16 *__restrict__ Ap, const float 
 }
 
 // gemm_rl and gemm_row in split fp16 (three MFMAs of depth 16 per 16 k-values)
-template <int F>
+template <int F, bool ACCUMULATE = false>
 __device__ inline void gemm_rl_f16x3(const _Float16 *__restrict__ Ap, const f32x16 (&in)[Dims<F>::NB],
                                      f32x16 (&out)[Dims<F>::NB], int lane)
 {
     constexpr int NB = Dims<F>::NB;
     const f16x8 *Ah = reinterpret_cast<const f16x8 *>(Ap) + lane;
     const f16x8 *Al = reinterpret_cast<const f16x8 *>(Ap + F * F) + lane;
+    if (!ACCUMULATE)
 #pragma unroll
-    for (int bo = 0; bo < NB; ++bo)
+        for (int bo = 0; bo < NB; ++bo)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) out[bo][r] = 0.f;
+            for (int r = 0; r < 16; ++r) out[bo][r] = 0.f;
 #pragma unroll
     for (int bi = 0; bi < NB; ++bi)
 #pragma unroll
@@ -373,17 +374,18 @@ __device__ inline void gemm_rl_f16x3(const _Float16 *__restrict__ Ap, const f32x
         }
 }
 
-template <int F>
+template <int F, bool ACCUMULATE = false>
 __device__ inline void gemm_row_f16x3(const _Float16 *__restrict__ Ap, const float *row, f32x16 (&out)[Dims<F>::NB], int lane)
 {
     constexpr int NB = Dims<F>::NB;
     const int h = lane >> 5;
     const f16x8 *Ah = reinterpret_cast<const f16x8 *>(Ap) + lane;
     const f16x8 *Al = reinterpret_cast<const f16x8 *>(Ap + F * F) + lane;
+    if (!ACCUMULATE)
 #pragma unroll
-    for (int bo = 0; bo < NB; ++bo)
+        for (int bo = 0; bo < NB; ++bo)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) out[bo][r] = 0.f;
+            for (int r = 0; r < 16; ++r) out[bo][r] = 0.f;
 #pragma unroll
     for (int bi = 0; bi < NB; ++bi)
 #pragma unroll

@@ -19,23 +19,23 @@ E_RTOL3 = 1e-4
 pytestmark = pytest.mark.gpu
 
 
-def _gpu3(g, c, weights=None, mode=0):
+def _gpu3(g, c, weights=None, mode=0, precision=0):
     import torch
     import paper_2506_02023_amd as M
     w = c["weights"] if weights is None else weights
-    W = M.Weights({k: w[k] for k in ("emb", "W1", "W2", "Wm", "Wo", "Wr1", "wr2")}, c["p"])
+    W = M.Weights({k: w[k] for k in ("emb", "W1", "W2", "Wm", "Wo", "Wr1", "wr2")}, c["p"], precision=precision)
     BW = M.BondWeights(w, c["r_bond"], c["A"])
     e, f, ae = M.mlip_forward_bonds(g, W, BW, mode)
     torch.cuda.synchronize()
     return float(e.cpu()[0]), f.cpu().numpy().astype(np.float64), ae.cpu().numpy().astype(np.float64)
 
 
-def _check(pos, cell, sp, c, weights=None, label=""):
+def _check(pos, cell, sp, c, weights=None, label="", precision=0):
     ref_g = og.build_graph(pos, cell, c["r_cut"])
     ref = tb.energy_forces3(pos, cell, sp, c["weights"] if weights is None else weights, ref_g, c["r_cut"], c["r_bond"],
                             c["K"], c["p"])
     g = gpu_graph(pos, cell, sp, c["r_cut"])
-    e, f, ae = _gpu3(g, c, weights)
+    e, f, ae = _gpu3(g, c, weights, precision=precision)
     bond_edge, bond_ptr = g.bonds()
     assert np.array_equal(bond_edge, ref["bond_edge"])          # integer outputs: bit-exact
     assert np.array_equal(bond_ptr, ref["bptr"])
@@ -48,10 +48,13 @@ def _check(pos, cell, sp, c, weights=None, label=""):
     return e, f
 
 
+# precision 0: fp32 MFMA; 2: all F x F products (filter MLP and bond MLPs) as split-fp16 triples, held to the same bounds
+@pytest.mark.parametrize("precision", [0, 2])
 @pytest.mark.parametrize("n", [3, 6])
-def test_three_body_fcc(n):
+def test_three_body_fcc(n, precision):
     c = wl.make_config(4, n=n)
-    _check(c["positions"], c["cell"], c["species"], c, label=f"configs[4] recipe at {n}^3")
+    _check(c["positions"], c["cell"], c["species"], c, label=f"configs[4] recipe at {n}^3, precision {precision}",
+           precision=precision)
 
 
 def test_three_body_width_32_and_two_layers():
@@ -106,13 +109,13 @@ def test_three_body_without_bonds_is_two_body():
     assert np.array_equal(f2.cpu().numpy().astype(np.float64), f3)
 
 
-def _check_slabs(pos, cell, sp, c, P, label):
+def _check_slabs(pos, cell, sp, c, P, label, precision=0):
     """SLABS mode: per-partition bond lists bit-exact, energy and forces against the (whole-graph) oracle and
     against the library's own whole-graph run."""
     ref_g = og.build_graph(pos, cell, c["r_cut"])
     ref = tb.energy_forces3(pos, cell, sp, c["weights"], ref_g, c["r_cut"], c["r_bond"], c["K"], c["p"])
     g = gpu_graph(pos, cell, sp, c["r_cut"], n_slabs=P)
-    es, fs, aes = _gpu3(g, c, mode=1)
+    es, fs, aes = _gpu3(g, c, mode=1, precision=precision)
     slab_of, _ = og.slab_assign(pos, cell, P)
     slabs = og.partition(ref_g, slab_of, P)
     _, _, bond_of_edge = tb.bond_graph(pos, cell, ref_g, c["r_bond"])
@@ -121,7 +124,7 @@ def _check_slabs(pos, cell, sp, c, P, label):
         be, bp = g.bonds(p)
         assert np.array_equal(be, np.flatnonzero(is_bond))
         assert np.array_equal(bp, np.concatenate([[0], np.cumsum(is_bond)])[slabs[p].row_ptr])
-    ew, fw, aew = _gpu3(g, c, mode=0)
+    ew, fw, aew = _gpu3(g, c, mode=0, precision=precision)
     fmax = np.abs(ref["forces"]).max()
     de, df = abs(es - ref["energy"]) / abs(ref["energy"]), np.abs(fs - ref["forces"]).max() / fmax
     print(f"{label}, {P} slabs: dE/E {de:.2e}, dF {df:.2e}; slabs vs whole dE/E {abs(es - ew) / abs(ew):.1e}, "
@@ -135,6 +138,8 @@ def _check_slabs(pos, cell, sp, c, P, label):
 def test_three_body_slabs_fcc(P):
     c = wl.make_config(4, n=6)
     _check_slabs(c["positions"], c["cell"], c["species"], c, P, "configs[4] recipe at 6^3")
+    if P == 3:
+        _check_slabs(c["positions"], c["cell"], c["species"], c, P, "configs[4] recipe at 6^3, split-fp16 products", precision=2)
 
 
 @pytest.mark.parametrize("P", [2, 5])

@@ -247,6 +247,9 @@ __global__ void k_fill_cells(int64_t N, const double *__restrict__ pos, const in
 // same candidate cells.  FILL = false counts and, if `keys` is given, parks the first kStage unsorted keys
 // (sender << 32 | packed shift) in the atom's staging row keys[i * kStage ...]; FILL = true writes the keys
 // into the atom's CSR row.
+// The search is bound by the latency of its dependent loads, not by the fp64 pair tests: the next candidate's
+// record is requested before the current one is tested.  (Requesting all 27 bin ranges at once and streaming the
+// candidates across bin boundaries needs twice the registers and measured slower.)
 template <bool FILL>
 __global__ void k_neighbours(int64_t N, CellParams cp, const int32_t *__restrict__ cell_start,
                              const int32_t *__restrict__ sid, const double *__restrict__ sx,
@@ -270,6 +273,37 @@ __global__ void k_neighbours(int64_t N, CellParams cp, const int32_t *__restrict
     else base = (int64_t)i * kStage;
     int32_t cnt = 0;
     bool coincident = false;
+
+    struct Rec {   // one candidate: atom id, wrap counts, position
+        int32_t j;
+        uint32_t w;
+        double x, y, z;
+    };
+    auto load = [&](Rec &r, int32_t q) {
+        r.j = sid[q];
+        r.w = swrap[q];
+        r.x = sx[q];
+        r.y = sy[q];
+        r.z = sz[q];
+    };
+    // the pair test for a candidate found in a bin that is (i0, i1, i2) cells away by wrap-around
+    auto test = [&](const Rec &r, int i0, int i1, int i2) {
+        int wj0, wj1, wj2;
+        unpack3(r.w, wj0, wj1, wj2);
+        const int S0 = i0 - wj0 + wi0, S1 = i1 - wj1 + wi1, S2 = i2 - wj2 + wi2;
+        if (r.j == i && S0 == 0 && S1 == 0 && S2 == 0) return;
+        const double t0 = (r.x - xi) + (((double)S0 * cp.C[0] + (double)S1 * cp.C[3]) + (double)S2 * cp.C[6]);
+        const double t1 = (r.y - yi) + (((double)S0 * cp.C[1] + (double)S1 * cp.C[4]) + (double)S2 * cp.C[7]);
+        const double t2 = (r.z - zi) + (((double)S0 * cp.C[2] + (double)S1 * cp.C[5]) + (double)S2 * cp.C[8]);
+        const double d2 = (t0 * t0 + t1 * t1) + t2 * t2;
+        if (d2 <= cp.rc2) {
+            if (d2 == 0.0) coincident = true;
+            if (FILL ? cnt < cap : (keys != nullptr && cnt < kStage))
+                keys[base + cnt] = ((uint64_t)(uint32_t)r.j << 32) | pack3(S0, S1, S2);
+            ++cnt;
+        }
+    };
+
     for (int dx = -cp.reach[0]; dx <= cp.reach[0]; ++dx) {
         int c0 = b0 + dx;
         const int i0 = floordiv(c0, cp.nb[0]);
@@ -284,22 +318,13 @@ __global__ void k_neighbours(int64_t N, CellParams cp, const int32_t *__restrict
                 c2 -= i2 * cp.nb[2];
                 const int32_t cc = (c0 * cp.nb[1] + c1) * cp.nb[2] + c2;
                 const int32_t qe = cell_start[cc + 1];
-                for (int32_t q = cell_start[cc]; q < qe; ++q) {
-                    const int32_t j = sid[q];
-                    int wj0, wj1, wj2;
-                    unpack3(swrap[q], wj0, wj1, wj2);
-                    const int S0 = i0 - wj0 + wi0, S1 = i1 - wj1 + wi1, S2 = i2 - wj2 + wi2;
-                    if (j == i && S0 == 0 && S1 == 0 && S2 == 0) continue;
-                    const double t0 = (sx[q] - xi) + (((double)S0 * cp.C[0] + (double)S1 * cp.C[3]) + (double)S2 * cp.C[6]);
-                    const double t1 = (sy[q] - yi) + (((double)S0 * cp.C[1] + (double)S1 * cp.C[4]) + (double)S2 * cp.C[7]);
-                    const double t2 = (sz[q] - zi) + (((double)S0 * cp.C[2] + (double)S1 * cp.C[5]) + (double)S2 * cp.C[8]);
-                    const double d2 = (t0 * t0 + t1 * t1) + t2 * t2;
-                    if (d2 <= cp.rc2) {
-                        if (d2 == 0.0) coincident = true;
-                        if (FILL ? cnt < cap : (keys != nullptr && cnt < kStage))
-                            keys[base + cnt] = ((uint64_t)(uint32_t)j << 32) | pack3(S0, S1, S2);
-                        ++cnt;
-                    }
+                int32_t q = cell_start[cc];
+                Rec nxt{};
+                if (q < qe) load(nxt, q);
+                for (; q < qe; ++q) {
+                    const Rec cur = nxt;
+                    if (q + 1 < qe) load(nxt, q + 1);
+                    test(cur, i0, i1, i2);
                 }
             }
         }

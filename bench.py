@@ -33,8 +33,8 @@ def flops_bwd_edge(F, K=8):
 # HBM bytes per launch (one layer over all 8 slabs) on the default workload, from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE (profiles/edge_traffic_configs3_8slabs.md): KiB x copy-kernel scale (1.9976 for FETCH_SIZE, 1.000 for
 # WRITE_SIZE)
-TRAFFIC_BWD_LAUNCH_BYTES = (11678695 * 1.9976 + 999847 * 1.0) * 1024
-TRAFFIC_FWD_LAUNCH_BYTES = (2486028 * 1.9976 + 7878067 * 1.0) * 1024
+TRAFFIC_BWD_LAUNCH_BYTES = (11679546 * 1.9976 + 999832 * 1.0) * 1024
+TRAFFIC_FWD_LAUNCH_BYTES = (2482961 * 1.9976 + 7878068 * 1.0) * 1024
 
 
 # fp32 vector peak of the chip (256 CUs x 4 SIMDs x 16 lanes x 2 flop per FMA x 2.4 GHz = 78.6 TFLOP/s per issue slot;

@@ -532,28 +532,30 @@ __global__ void k_gather_markers(const int32_t *__restrict__ off, int ncls, int6
 
 // length of each local row: owned rows keep their whole global row, ghost rows
 // keep only the senders owned by partition q
-__global__ void __launch_bounds__(64)
+__global__ void __launch_bounds__(256)
 k_local_rowlen(int64_t n_local, int64_t n_owned, const int32_t *__restrict__ nodes,
                const int64_t *__restrict__ row_ptr, const int32_t *__restrict__ senders,
                const int32_t *__restrict__ slab_of, int q, int32_t *rowlen)
 {
-    const int64_t r = blockIdx.x;
+    const int lane = threadIdx.x & 63;   // one wavefront per row, four rows per block
+    const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (r >= n_local) return;
     const int32_t u = nodes[r];
     const int64_t e0 = row_ptr[u], e1 = row_ptr[u + 1];
     if (r < n_owned) {
-        if (threadIdx.x == 0) rowlen[r] = (int32_t)(e1 - e0);
+        if (lane == 0) rowlen[r] = (int32_t)(e1 - e0);
         return;
     }
     int cnt = 0;
     for (int64_t eb = e0; eb < e1; eb += 64) {
-        const int64_t e = eb + threadIdx.x;
+        const int64_t e = eb + lane;
         const bool keep = e < e1 && slab_of[senders[e]] == q;
         cnt += __popcll(__ballot(keep));
     }
-    if (threadIdx.x == 0) rowlen[r] = cnt;
+    if (lane == 0) rowlen[r] = cnt;
 }
 
-__global__ void __launch_bounds__(64)
+__global__ void __launch_bounds__(256)
 k_local_fill(int64_t n_local, int64_t n_owned, const int32_t *__restrict__ nodes,
              const int64_t *__restrict__ row_ptr, const int32_t *__restrict__ senders,
              const uint32_t *__restrict__ shiftp, const float *__restrict__ d,
@@ -561,15 +563,17 @@ k_local_fill(int64_t n_local, int64_t n_owned, const int32_t *__restrict__ nodes
              const int32_t *__restrict__ gmirror, const int64_t *__restrict__ lrow_ptr, int32_t *lsenders,
              int32_t *lrecv, uint32_t *lshiftp, float *ld, int32_t *lmirror)
 {
-    const int64_t r = blockIdx.x;
+    const int lane = threadIdx.x & 63;   // one wavefront per row, four rows per block
+    const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (r >= n_local) return;
     const int32_t u = nodes[r];
     const int64_t e0 = row_ptr[u], e1 = row_ptr[u + 1];
     int64_t out = lrow_ptr[r];
     const int64_t out_end = lrow_ptr[r + 1];
     const bool all = r < n_owned;
-    const unsigned long long lt = (1ull << threadIdx.x) - 1ull;
+    const unsigned long long lt = (1ull << lane) - 1ull;
     for (int64_t eb = e0; eb < e1; eb += 64) {
-        const int64_t e = eb + threadIdx.x;
+        const int64_t e = eb + lane;
         int32_t j = 0;
         bool keep = false;
         if (e < e1) {
@@ -971,7 +975,7 @@ int build_graph_impl(mlip_graph *g, const double *positions, const double *cell,
                 g->local_of.as<int32_t>(), g->local_in_owner.as<int32_t>());
             MLIP_HIP(hipGetLastError());
             if (v.n_local > 0) {
-                k_local_rowlen<<<(unsigned)v.n_local, 64, 0, s>>>(v.n_local, v.n_owned, st.nodes.as<int32_t>(),
+                k_local_rowlen<<<(unsigned)((v.n_local + 3) / 4), 256, 0, s>>>(v.n_local, v.n_owned, st.nodes.as<int32_t>(),
                                                                   g->row_ptr.as<int64_t>(), g->senders.as<int32_t>(),
                                                                   g->slab_of.as<int32_t>(), q, st.rowlen.as<int32_t>());
                 MLIP_HIP(hipGetLastError());
@@ -989,7 +993,7 @@ int build_graph_impl(mlip_graph *g, const double *positions, const double *cell,
             MLIP_TRY(st.mirror.ensure(ne * 4));
             MLIP_TRY(st.d.ensure(ne * 4));
             if (v.n_local > 0) {
-                k_local_fill<<<(unsigned)v.n_local, 64, 0, s>>>(
+                k_local_fill<<<(unsigned)((v.n_local + 3) / 4), 256, 0, s>>>(
                     v.n_local, v.n_owned, st.nodes.as<int32_t>(), g->row_ptr.as<int64_t>(), g->senders.as<int32_t>(),
                     g->shiftp.as<uint32_t>(), g->d.as<float>(), g->slab_of.as<int32_t>(), g->local_of.as<int32_t>(), q,
                     g->mirror.as<int32_t>(), st.row_ptr.as<int64_t>(), st.senders.as<int32_t>(), st.recv.as<int32_t>(),

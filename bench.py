@@ -21,25 +21,34 @@ PEAK_FP32_MFMA_TFLOPS = 157.3
 #   reverse: pre-activations t = b W1 (2 K F), sbar = wbar W2^T (2 F F), dt/dd contraction through W1 (2 K F);
 #            the filter value w_e itself is not recomputed, the forward pass keeps it in HBM (layers >= 1).
 # The reverse kernel runs this dense work once per edge / reverse-edge pair (both have the same length), so the
-# MFMA units execute half of the reverse figure; both rates are reported.
+# MFMA units execute half of the reverse figure per directed edge.  The roofline fraction of the reverse kernel is
+# taken on what is executed; the rate of the operation as defined is reported beside it ("as_defined_tflops").
 def flops_fwd_edge(F, K=8):
     return 2 * K * F + 2 * F * F
 
 
-def flops_bwd_edge(F, K=8):
+def flops_bwd_edge_as_defined(F, K=8):
     return 2 * K * F + 2 * F * F + 2 * K * F
+
+
+def flops_bwd_edge(F, K=8):
+    """Executed per directed edge: the dense work of a pair, shared by its two edges."""
+    return flops_bwd_edge_as_defined(F, K) // 2
 
 
 # HBM bytes per launch (one layer over all 8 slabs) on the default workload, from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE (profiles/edge_traffic_configs3_8slabs.md): KiB x copy-kernel scale (1.9976 for FETCH_SIZE, 1.000 for
 # WRITE_SIZE)
+TRAFFIC_SOURCE = ("profiled constant, not measured by this run: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this kernel on "
+                  "this workload, profiles/edge_traffic_configs3_8slabs.md")
 TRAFFIC_BWD_LAUNCH_BYTES = (11679546 * 1.9976 + 999832 * 1.0) * 1024
 TRAFFIC_FWD_LAUNCH_BYTES = (2482961 * 1.9976 + 7878068 * 1.0) * 1024
 
 
-# fp32 vector peak of the chip (256 CUs x 4 SIMDs x 16 lanes x 2 flop per FMA x 2.4 GHz = 78.6 TFLOP/s per issue slot;
-# the published 157.3 TFLOP/s counts the dual-issue/packed rate): the bound of the triplet kernels of the three-body variant
-PEAK_FP32_VECTOR_TFLOPS = 157.3
+# fp32 vector peak that applies to this build: 256 CUs x 4 SIMDs x 16 lanes x 2 flop per FMA x 2.4 GHz = 78.6 TFLOP/s.
+# (The published 157.3 TFLOP/s counts packed fp32 FMAs, which the library is compiled without.)  It bounds the triplet
+# kernels of the three-body variant.
+PEAK_FP32_VECTOR_TFLOPS = 78.6
 
 
 def flops_triplet_fwd(F, A=8):
@@ -54,7 +63,8 @@ def flops_triplet_bwd(F, A=8):
 
 
 def cpu_baseline(cfg_index, n_cells):
-    """The oracle, as it stands, on a bounded sample of the same workload (same recipe, smaller box)."""
+    """The oracle, as it stands, timed once on the timed system itself (n_cells = None) or on a smaller box of the
+    same recipe."""
     import workloads as wl
     from oracle import _lib as ol
     from oracle import graph as og
@@ -70,8 +80,9 @@ def cpu_baseline(cfg_index, n_cells):
     dt = time.perf_counter() - t0
     n = len(c["species"])
     return {"value": n / dt, "unit": "atoms/s", "cores": int(ol.lib().orc_num_threads()), "kind": "oracle",
-            "sample": f"configs[{cfg_index}] recipe at {n_cells}^3 fcc cells ({n} atoms, {g.E} edges), "
-                      f"fp64, graph + energy + forces, one run of {dt:.1f} s"}
+            "sample": (f"configs[{cfg_index}] itself" if n_cells is None else
+                       f"configs[{cfg_index}] recipe at {n_cells}^3 fcc cells")
+                      + f" ({n} atoms, {g.E} directed edges), fp64, graph + energy + forces, one run of {dt:.1f} s"}
 
 
 def main():
@@ -82,7 +93,8 @@ def main():
     ap.add_argument("--config", type=int, default=3)
     ap.add_argument("--cells", type=int, default=None, help="override fcc cells per side (smaller runs)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
-    ap.add_argument("--cpu-cells", type=int, default=48, help="fcc cells per side of the oracle's bounded sample")
+    ap.add_argument("--cpu-cells", type=int, default=None,
+                    help="fcc cells per side of a smaller sample for the oracle timing (default: the timed system itself)")
     ap.add_argument("--no-whole", action="store_true", help="skip the unpartitioned (whole-graph) run of the same system")
     ap.add_argument("--precision", choices=("f32", "f32split", "bf16"), default="f32",
                     help="f32split: the F x F products of the filter MLP as split-fp16 MFMA triples (fp32-grade results); "
@@ -168,17 +180,19 @@ def main():
     L = c["L"]
     default_workload = args.config == 3 and args.cells is None
 
-    def edge_roofline(group, kernel, flops_edge, traffic, executed=None):
+    def edge_roofline(group, kernel, flops_edge, traffic, as_defined=None):
         ms, n = prof[group]
         per_launch = E * flops_edge * L * args.steps / max(n, 1)
         avg_ms = ms / max(n, 1)
         ach = per_launch / (avg_ms * 1e-3) / 1e12 if avg_ms > 0 else 0.0
         r = {"kernel": kernel, "bound": "mfma", "achieved": ach, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
              "frac": ach / PEAK_FP32_MFMA_TFLOPS, "traffic": traffic if default_workload else None,
+             "traffic_source": TRAFFIC_SOURCE if default_workload else None,
              "avg_launch_ms": avg_ms, "launches": int(n), "flops_per_launch": per_launch,
              "ms_per_step": ms / args.steps}
-        if executed is not None:
-            r["executed_tflops"] = ach * executed / flops_edge
+        if as_defined is not None:   # rate of the operation as defined (twice the executed work), not a utilisation
+            r["as_defined_tflops"] = ach * as_defined / flops_edge
+            r["flops_per_edge_layer"] = {"executed": flops_edge, "as_defined": as_defined}
         if args.precision != "f32":
             r["note"] = ("the W2 products run on the 16-bit matrix pipeline; frac is the algorithmic rate against the fp32 "
                          "MFMA peak of the default mode, not a utilisation of the units used")
@@ -186,7 +200,7 @@ def main():
 
     F = c["F"]
     roof_bwd = edge_roofline("edge_bwd", f"k_edge_bwd<{F}> (reverse edge step)", flops_bwd_edge(F),
-                             TRAFFIC_BWD_LAUNCH_BYTES, flops_bwd_edge(F) // 2)
+                             TRAFFIC_BWD_LAUNCH_BYTES, flops_bwd_edge_as_defined(F))
     roof_fwd = edge_roofline("edge_fwd", f"k_edge_fwd<{F}> (forward edge step)", flops_fwd_edge(F),
                              TRAFFIC_FWD_LAUNCH_BYTES)
     roof = roof_fwd if roof_fwd["ms_per_step"] >= roof_bwd["ms_per_step"] else roof_bwd   # the dominant kernel
@@ -237,7 +251,7 @@ def main():
                               "energy": energy_whole, "rel_energy_difference_to_slabs": abs(energy_whole - energy) / abs(energy),
                               "note": "graph build without partition + unpartitioned energy+forces of the same system"}
     if not args.no_cpu:
-        res["cpu_baseline"] = cpu_baseline(args.config, min(args.cpu_cells, 36) if three_body else args.cpu_cells)
+        res["cpu_baseline"] = cpu_baseline(args.config, args.cpu_cells if args.cpu_cells else args.cells)
     print(json.dumps(res))
 
 

@@ -747,7 +747,9 @@ int unpack_shifts(const mlip_graph *g, int32_t *out)
 int build_bonds_impl(mlip_graph *g, SlabView &v, double r_bond, int p_envelope)
 {
     BondGraph &B = v.bonds;
-    if (B.r_bond == r_bond) return MLIP_OK;   // same graph (a rebuild resets r_bond), same cutoff
+    // same graph (a rebuild resets r_bond), same cutoff, same envelope (u and du/dd are stored with the list)
+    if (B.r_bond == r_bond && B.p_env == p_envelope) return MLIP_OK;
+    B.r_bond = -1.0;   // the arrays are about to be overwritten: a failure below must not leave a half-built list valid
     hipStream_t s = g->stream;
     const int64_t E = v.n_edges_owned, N = v.n_owned;
     const size_t Ecap = (size_t)std::max<int64_t>(E, 1);
@@ -790,6 +792,7 @@ int build_bonds_impl(mlip_graph *g, SlabView &v, double r_bond, int p_envelope)
     }
     B.n = nb;
     B.r_bond = r_bond;
+    B.p_env = p_envelope;
     return MLIP_OK;
 }
 

@@ -61,6 +61,7 @@ inline int64_t chunks_of(int64_t n_edges) { return n_edges > 0 ? (n_edges + kChu
 // in edge order (all bonds of an owned centre belong to its partition).
 struct BondGraph {
     double r_bond = -1.0;   // cutoff the list was built for (< 0: none)
+    int p_env = -1;         // envelope exponent the stored u, du/dd were evaluated with
     int64_t n = 0;          // bonds
     DevBuf scan;            // i32 [E + 1] exclusive scan of the bond flags (E = edges of the owned rows)
     DevBuf flag;            // i32 [E]

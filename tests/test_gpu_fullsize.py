@@ -3,9 +3,11 @@
 configs[2] (108,000 atoms, 8 slabs): index sets bit-exact, whole-graph and partitioned energy/forces
 against the full fp64 oracle.
 configs[3] (1,000,188 atoms, the configuration bench.py times, 8 slabs): neighbour list and index
-sets bit-exact against the oracle; energy and forces on sampled atoms, each recomputed by the oracle
-on the atom's own dependency cluster (all atoms within 2 L r_cut, which determines its energy and its
-force exactly), plus properties that hold at any size.
+sets bit-exact against the oracle; total energy, every per-atom energy and every force component of
+the whole-graph, the 8-slab and the split-fp16 runs against the full fp64 oracle run of the same
+million atoms (relative energy error <= 1e-5, force error <= 1e-4 max|F|); as a second, independent
+witness, sampled atoms recomputed by the oracle on the atom's own dependency cluster (all atoms within
+2 L r_cut, which determines its energy and its force exactly), plus properties that hold at any size.
 """
 import numpy as np
 import pytest
@@ -89,6 +91,15 @@ def test_config3_million_atoms():
     assert np.abs(fs.sum(0)).max() <= 1e-6 * fmax * np.sqrt(N)
     assert abs(es - ew) <= E_RTOL * abs(ew)
     assert np.abs(fs - fw).max() <= F_RTOL * fmax
+    # the full fp64 oracle on the same 1,000,188 atoms: total energy and all forces, every mode
+    ref_full = om.energy_forces(pos, cell, sp, c["weights"], ref_g, c["r_cut"], c["K"], c["p"])
+    eps_scale = np.abs(ref_full["atom_energy"]).mean()
+    for what, e_, f_, a_ in (("whole", ew, fw, aw), ("8 slabs", es, fs, as_), ("8 slabs, split-fp16 products", e2, f2, a2)):
+        de, df = assert_energy_forces(e_, f_, ref_full, "configs[3] " + what)
+        da = np.abs(a_ - ref_full["atom_energy"]).max() / eps_scale
+        print(f"configs[3] {what} against the full oracle: dE/E {de:.2e}, dF {df:.2e} of max|F|, "
+              f"worst atom energy {da:.2e} of mean|eps|")
+        assert da <= 1e-4, (what, da)      # a single fp32 atom energy; the 1e-5 bound is on the total
     # sampled atoms: near a slab wall, near the box faces, and in the bulk
     L = c["L"]
     radius = 2 * L * c["r_cut"] + 0.5
@@ -101,6 +112,9 @@ def test_config3_million_atoms():
         cg = og.build_graph(cpos, ccell, c["r_cut"])
         ref = om.energy_forces(cpos, ccell, sp[sel], c["weights"], cg, c["r_cut"], c["K"], c["p"])
         k = int(np.flatnonzero(sel == i)[0])
+        # the two oracle routes (periodic million-atom run, free cluster) agree on this atom
+        assert abs(ref["atom_energy"][k] - ref_full["atom_energy"][i]) <= 1e-9 * eps_scale
+        assert np.abs(ref["forces"][k] - ref_full["forces"][i]).max() <= 1e-9 * fmax
         # the cluster graph reproduces the atom's row of the periodic graph
         assert cg.row_ptr[k + 1] - cg.row_ptr[k] == ref_g.row_ptr[i + 1] - ref_g.row_ptr[i]
         for ae, ff in ((aw, fw), (as_, fs), (a2, f2)):

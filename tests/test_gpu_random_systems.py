@@ -13,6 +13,8 @@ from gpu_util import F_RTOL, gpu_graph
 
 pytestmark = pytest.mark.gpu
 
+# |E - E_ref| / |E_ref| for systems whose per-atom energies do not cancel in the total: two-body, three-body
+REL_BOUND = (1e-5, 1e-5)
 KEYS = ("emb", "W1", "W2", "Wm", "Wo", "Wr1", "wr2")
 
 
@@ -35,6 +37,7 @@ def test_random_systems():
     rng = np.random.default_rng(12345)
     done = 0
     worst = np.zeros(4)
+    worst_rel, n_rel = [0.0, 0.0], [0, 0]
     for case in range(240):
         kind = case % 3
         F = 64 if case % 2 else 32
@@ -76,6 +79,15 @@ def test_random_systems():
         assert err[0] <= 1e-5 and err[1] <= F_RTOL, (label, err)
         assert err[2] <= 1e-4 and err[3] <= F_RTOL, (label, err)
         worst = np.maximum(worst, err)
+        # where the per-atom energies do not cancel in the total, the bound relative to |E| itself
+        for k, (e, ref) in enumerate(((e2, ref2), (e3, ref3))):
+            if abs(ref["energy"]) >= 0.2 * np.abs(ref["atom_energy"]).sum():
+                rel = abs(e - ref["energy"]) / abs(ref["energy"])
+                assert rel <= REL_BOUND[k], (label, k, rel)
+                worst_rel[k] = max(worst_rel[k], rel)
+                n_rel[k] += 1
         done += 1
     print(f"{done} systems, worst errors dE2 {worst[0]:.1e} dF2 {worst[1]:.1e} dE3 {worst[2]:.1e} dF3 {worst[3]:.1e}")
-    assert done >= 100
+    print(f"relative to |E| (systems with |E| >= 0.2 sum|eps|): two-body {n_rel[0]} systems, worst {worst_rel[0]:.1e}; "
+          f"three-body {n_rel[1]} systems, worst {worst_rel[1]:.1e}")
+    assert done >= 100 and min(n_rel) >= 20

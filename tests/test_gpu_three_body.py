@@ -1,9 +1,10 @@
 """GPU parity of the three-body (bond graph) variant against the fp64 oracle, whole-graph and partitioned.
 
-Bond list and per-centre bond ranges are bit-exact.  The library computes this variant in fp32, so forces are
-held to the fp32 bound (1e-4 max|F|; the benchmark allows 2e-2 max|F| for its bf16 version) and the energy to
-1e-4 relative (the benchmark states no energy bound for this configuration; measured 2e-8 .. 8e-6, the larger
-values on the 108-atom case whose total energy is only a few units).
+Bond list and per-centre bond ranges are bit-exact.  In the fp32 modes forces are held to the fp32 bound
+(1e-4 max|F|) and the energy to the fp32 bound of 1e-5 relative wherever the system has a few hundred atoms or
+more (6^3 cells and the full 37^3 configuration).  The 108-atom and triclinic cases, whose total energy is only a
+few units (a handful of per-atom energies of either sign), keep 1e-4; each such test says so.  The bf16 mode the
+benchmark names for this configuration is run at full size against its bound, 2e-2 max|F|.
 """
 import numpy as np
 import pytest
@@ -14,7 +15,8 @@ from oracle import three_body as tb
 
 from gpu_util import F_RTOL, gpu_graph
 
-E_RTOL3 = 1e-4
+E_RTOL3 = 1e-5        # systems of 864 atoms and more
+E_RTOL3_TINY = 1e-4   # 108 atoms and fewer: |E| is a few units, a sum of a few terms of either sign
 
 pytestmark = pytest.mark.gpu
 
@@ -30,7 +32,7 @@ def _gpu3(g, c, weights=None, mode=0, precision=0):
     return float(e.cpu()[0]), f.cpu().numpy().astype(np.float64), ae.cpu().numpy().astype(np.float64)
 
 
-def _check(pos, cell, sp, c, weights=None, label="", precision=0):
+def _check(pos, cell, sp, c, weights=None, label="", precision=0, e_rtol=E_RTOL3):
     ref_g = og.build_graph(pos, cell, c["r_cut"])
     ref = tb.energy_forces3(pos, cell, sp, c["weights"] if weights is None else weights, ref_g, c["r_cut"], c["r_bond"],
                             c["K"], c["p"])
@@ -42,7 +44,7 @@ def _check(pos, cell, sp, c, weights=None, label="", precision=0):
     de = abs(e - ref["energy"]) / abs(ref["energy"])
     df = np.abs(f - ref["forces"]).max() / np.abs(ref["forces"]).max()
     print(f"{label}: {ref_g.N} atoms, {ref['n_bonds']} bonds, {ref['n_triplets']} triplets, dE/E {de:.2e}, dF {df:.2e}")
-    assert de <= E_RTOL3, (label, de)
+    assert de <= e_rtol, (label, de)
     assert df <= F_RTOL, (label, df)
     assert np.abs(ae - ref["atom_energy"]).max() <= 1e-4 * np.abs(ref["atom_energy"]).max()
     return e, f
@@ -54,14 +56,14 @@ def _check(pos, cell, sp, c, weights=None, label="", precision=0):
 def test_three_body_fcc(n, precision):
     c = wl.make_config(4, n=n)
     _check(c["positions"], c["cell"], c["species"], c, label=f"configs[4] recipe at {n}^3, precision {precision}",
-           precision=precision)
+           precision=precision, e_rtol=E_RTOL3_TINY if n == 3 else E_RTOL3)   # n = 3: 108 atoms
 
 
 def test_three_body_width_32_and_two_layers():
     c = wl.make_config(4, n=3)
     w = wl.rmp_weights(4, 32, 2, 77)
     w.update(wl.three_body_weights(32, 2, 77))
-    _check(c["positions"], c["cell"], c["species"], c, weights=w, label="F = 32, L = 2")
+    _check(c["positions"], c["cell"], c["species"], c, weights=w, label="F = 32, L = 2", e_rtol=E_RTOL3_TINY)   # 108 atoms
 
 
 def test_three_body_five_layers():
@@ -70,7 +72,7 @@ def test_three_body_five_layers():
     c = wl.make_config(4, n=3)
     w = wl.rmp_weights(4, 64, 5, 78)
     w.update(wl.three_body_weights(64, 5, 78))
-    _check(c["positions"], c["cell"], c["species"], c, weights=w, label="F = 64, L = 5")
+    _check(c["positions"], c["cell"], c["species"], c, weights=w, label="F = 64, L = 5", e_rtol=E_RTOL3_TINY)   # 108 atoms
 
 
 @pytest.mark.parametrize("r_bond,expected", [(3.9, 18), (4.8, 42)])
@@ -81,7 +83,7 @@ def test_three_body_many_bonds_per_centre(r_bond, expected):
     g = og.build_graph(c["positions"], c["cell"], c["r_cut"])
     _, bptr, _ = tb.bond_graph(c["positions"], c["cell"], g, r_bond)
     assert abs(np.diff(bptr).mean() - expected) < 3 and np.diff(bptr).max() > (16 if expected == 18 else 32)
-    _check(c["positions"], c["cell"], c["species"], c, label=f"r_bond = {r_bond}")
+    _check(c["positions"], c["cell"], c["species"], c, label=f"r_bond = {r_bond}", e_rtol=E_RTOL3_TINY)   # 108 atoms
 
 
 @pytest.mark.parametrize("seed", [0, 3])
@@ -89,7 +91,7 @@ def test_three_body_triclinic(seed):
     """Thin triclinic cells: several images of the same neighbour among the bonds, uneven bond counts."""
     c = wl.make_config(4, n=3)
     pos, cell, sp = wl.random_triclinic(14 + 5 * seed, seed, scale=[4.0, 7.0, 0, 9.0][seed], spread=1.2)
-    _check(pos, cell, sp, c, label=f"triclinic seed {seed}")
+    _check(pos, cell, sp, c, label=f"triclinic seed {seed}", e_rtol=E_RTOL3_TINY)   # 14 and 29 atoms
 
 
 def test_three_body_without_bonds_is_two_body():
@@ -109,7 +111,24 @@ def test_three_body_without_bonds_is_two_body():
     assert np.array_equal(f2.cpu().numpy().astype(np.float64), f3)
 
 
-def _check_slabs(pos, cell, sp, c, P, label, precision=0):
+def test_three_body_envelope_exponent_changes_on_one_handle():
+    """Two calls on one graph handle with the same bond cutoff and different envelope exponents: the bond list's stored
+    envelope values belong to one exponent and must be rebuilt for the other (whole graph and slabs)."""
+    c = wl.make_config(4, n=6)
+    pos, cell, sp = c["positions"], c["cell"], c["species"]
+    ref_g = og.build_graph(pos, cell, c["r_cut"])
+    g = gpu_graph(pos, cell, sp, c["r_cut"], n_slabs=3)
+    for p_env in (6, 4, 6):
+        ci = dict(c, p=p_env)
+        ref = tb.energy_forces3(pos, cell, sp, c["weights"], ref_g, c["r_cut"], c["r_bond"], c["K"], p_env)
+        for mode in (0, 1):
+            e, f, _ = _gpu3(g, ci, mode=mode)
+            de = abs(e - ref["energy"]) / abs(ref["energy"])
+            df = np.abs(f - ref["forces"]).max() / np.abs(ref["forces"]).max()
+            assert de <= E_RTOL3 and df <= F_RTOL, (p_env, mode, de, df)
+
+
+def _check_slabs(pos, cell, sp, c, P, label, precision=0, e_rtol=E_RTOL3):
     """SLABS mode: per-partition bond lists bit-exact, energy and forces against the (whole-graph) oracle and
     against the library's own whole-graph run."""
     ref_g = og.build_graph(pos, cell, c["r_cut"])
@@ -129,8 +148,8 @@ def _check_slabs(pos, cell, sp, c, P, label, precision=0):
     de, df = abs(es - ref["energy"]) / abs(ref["energy"]), np.abs(fs - ref["forces"]).max() / fmax
     print(f"{label}, {P} slabs: dE/E {de:.2e}, dF {df:.2e}; slabs vs whole dE/E {abs(es - ew) / abs(ew):.1e}, "
           f"dF {np.abs(fs - fw).max() / fmax:.1e}")
-    assert de <= E_RTOL3 and df <= F_RTOL
-    assert abs(es - ew) <= E_RTOL3 * abs(ew) and np.abs(fs - fw).max() <= F_RTOL * fmax
+    assert de <= e_rtol and df <= F_RTOL
+    assert abs(es - ew) <= e_rtol * abs(ew) and np.abs(fs - fw).max() <= F_RTOL * fmax
     assert np.abs(aes - ref["atom_energy"]).max() <= 1e-4 * np.abs(ref["atom_energy"]).max()
 
 
@@ -147,7 +166,7 @@ def test_three_body_slabs_triclinic(P):
     """Thin triclinic cell: slabs narrower than the cutoffs, bonds to periodic images across the walls."""
     c = wl.make_config(4, n=3)
     pos, cell, sp = wl.random_triclinic(40, 11, scale=9.0, spread=1.1)
-    _check_slabs(pos, cell, sp, c, P, "triclinic")
+    _check_slabs(pos, cell, sp, c, P, "triclinic", e_rtol=E_RTOL3_TINY)   # 40 atoms
 
 
 def test_three_body_config4_full_size():
@@ -162,6 +181,27 @@ def test_three_body_config4_full_size():
     es, fs, _ = _gpu3(g, c, mode=1)
     assert abs(es - e) <= E_RTOL3 * abs(e)
     assert np.abs(fs - f).max() <= F_RTOL * np.abs(f).max()
+
+
+def test_three_body_config4_full_size_bf16():
+    """configs[4] in the precision the benchmark names for it: bf16 operands with fp32 accumulation in the edge
+    and bond MLPs' F x F products, 202,612 atoms, whole graph and 8 slabs, against the full fp64 oracle.  Bound from
+    the benchmark: forces within 2e-2 max|F|; the energy (no bound stated) within 2e-3 of the sum of the per-atom
+    magnitudes, as in the small bf16 cases."""
+    c = wl.make_config(4)
+    pos, cell, sp = c["positions"], c["cell"], c["species"]
+    ref_g = og.build_graph(pos, cell, c["r_cut"])
+    ref = tb.energy_forces3(pos, cell, sp, c["weights"], ref_g, c["r_cut"], c["r_bond"], c["K"], c["p"])
+    fmax = np.abs(ref["forces"]).max()
+    g = gpu_graph(pos, cell, sp, c["r_cut"], n_slabs=8)
+    for mode, what in ((0, "whole"), (1, "8 slabs")):
+        e, f, _ = _gpu3(g, c, mode=mode, precision=1)
+        df = np.abs(f - ref["forces"]).max() / fmax
+        des = abs(e - ref["energy"]) / np.abs(ref["atom_energy"]).sum()
+        print(f"configs[4] 37^3 bf16, {what}: dF {df:.2e} of max|F|, dE/sum|eps| {des:.2e}, "
+              f"dE/E {abs(e - ref['energy']) / abs(ref['energy']):.2e}")
+        assert df <= 2e-2 and des <= 2e-3
+        assert df > 1e-6    # it really is the reduced-precision path
 
 
 @pytest.mark.parametrize("three_body", [False, True])

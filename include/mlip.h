@@ -16,9 +16,11 @@
  *   - every function returns 0 (MLIP_OK) or a negative mlip_status; no C++
  *     exception or abort crosses this boundary; on error no output argument is
  *     written and mlip_last_error() describes the failure (thread-local text);
- *   - a graph handle owns all device memory it allocates (hipMalloc) until
- *     mlip_graph_destroy; inputs are borrowed for the duration of the call and
- *     never written; handles are not thread-safe;
+ *   - a graph handle owns all device memory it obtains - from the caller's
+ *     allocator if the handle was made by mlip_graph_create with one, from
+ *     hipMalloc otherwise - until mlip_graph_destroy; inputs are borrowed for
+ *     the duration of the call and never written; one handle must not be used
+ *     from two threads at once (different handles may be);
  *   - all work is enqueued on the HIP stream given to mlip_build_graph
  *     (a hipStream_t passed as void*, NULL = default stream); outputs of
  *     mlip_forward are valid after that stream is synchronised;
@@ -66,12 +68,38 @@ enum { MLIP_PRECISION_FP32 = 0, MLIP_PRECISION_BF16 = 1, MLIP_PRECISION_FP32_SPL
 typedef struct mlip_graph mlip_graph_t;
 
 /*
+ * Caller-supplied device allocator (appendix "Parallelizing a Model": the distributed object owns the graph
+ * metadata while the features live in the framework's tensors - here the framework's allocator hands out every
+ * device block the handle uses, graph arrays and feature workspace alike, so that the framework's memory
+ * accounting sees them).
+ *   alloc(bytes, ctx)  returns a DEVICE pointer aligned to at least 256 bytes, valid on the handle's stream, or
+ *                      NULL when out of memory (the call in progress then fails with MLIP_ENOMEM);
+ *   free(ptr, ctx)     takes a block back; the library synchronises the handle's stream first, so no enqueued
+ *                      kernel still uses the block.
+ * Both are called on the thread that calls into the library, only from mlip_build_graph, mlip_forward,
+ * mlip_forward_bonds and mlip_graph_destroy.  Buffers are grow-only: a rebuilt handle asks for memory only when
+ * a buffer must grow.
+ */
+typedef struct {
+    void *(*alloc)(size_t bytes, void *ctx);
+    void (*free)(void *ptr, void *ctx);
+    void *ctx;
+} mlip_alloc_t;
+
+/*
+ * Creates an empty handle that takes all its device memory from `alloc` (copied; NULL or a NULL alloc function:
+ * hipMalloc / hipFree).  Pass the handle to mlip_build_graph, which fills it.  mlip_build_graph with *graph ==
+ * NULL is the same as creating a handle without an allocator first.
+ */
+int mlip_graph_create(const mlip_alloc_t *alloc, mlip_graph_t **graph);
+
+/*
  * Weights of the radial message-passing potential (benchmark configuration 0
  * defines it): species embedding; per layer l the filter MLP W1_l (K x F),
  * W2_l (F x F), the sender projection Wm_l (F x F) and the update Wo_l (F x F);
  * readout Wr1 (F x F), wr2 (F).  All fp32, row-major [fan_in][fan_out]
  * (y = x W), no biases.  DEVICE pointers, borrowed.
- * Supported: F in {32, 64}, K = 8, 1 <= L <= 8, p >= 2, n_species >= 1.
+ * Supported: F in {32, 64}, K = 8, 0 <= L <= 8, 2 <= p <= 64, n_species >= 1.
  */
 typedef struct {
     int32_t n_species, F, L, K, p, precision;
@@ -159,9 +187,16 @@ int mlip_build_graph(const double *positions, const double *cell, const int32_t 
  *
  * Asynchronous on the graph's stream; does not modify the graph's topology (it uses
  * workspace owned by the handle, so two forwards on one handle must not overlap).
+ *
+ * The weights are re-laid-out for the matrix units on the first call and kept in the handle: a later call whose
+ * mlip_weights_t (pointers, dimensions, precision) is identical reuses them.  After changing weight VALUES in
+ * place, call mlip_graph_invalidate_weights.
  */
 int mlip_forward(mlip_graph_t *graph, const mlip_weights_t *weights, int32_t mode,
                  double *energy, float *forces, float *atom_energy);
+
+/* Drops the handle's packed copies of the weights (two-body and bond part); the next forward call packs again. */
+int mlip_graph_invalidate_weights(mlip_graph_t *graph);
 
 /*
  * Three-body (bond graph) variant: benchmark configuration 4; the paper's counterpart is the bond graph built
@@ -199,10 +234,18 @@ int mlip_graph_bonds(const mlip_graph_t *graph, int32_t p, const int32_t **bond_
 
 void mlip_graph_destroy(mlip_graph_t *graph);
 
-/* N atoms, E directed edges, P slabs, all HOST outputs (any may be NULL). */
+/*
+ * N atoms, E directed edges, P slabs, all HOST outputs (any may be NULL): the sizes of the graph object the
+ * paper's create_distributed returns (appendix "Parallelizing a Model in DistMLIP").
+ */
 int mlip_graph_sizes(const mlip_graph_t *graph, int64_t *n_atoms, int64_t *n_edges, int32_t *n_slabs);
 
-/* Whole-graph CSR, borrowed DEVICE pointers: row_ptr[N+1], senders[E], d[E] (fp32 edge lengths). */
+/*
+ * Whole-graph CSR, borrowed DEVICE pointers: row_ptr[N+1], senders[E], d[E] (fp32 edge lengths).  This is what the
+ * paper's graph object exposes as src_nodes / dst_nodes (appendix "Parallelizing a Model in DistMLIP"): edge e of
+ * row i has destination (receiver) i and source senders[e]; the neighbour list itself is the one of Methods,
+ * "Graph-Parallel Message Passing".
+ */
 int mlip_graph_csr(const mlip_graph_t *graph, const int64_t **row_ptr, const int32_t **senders,
                    const float **d);
 
@@ -213,10 +256,18 @@ int mlip_graph_csr(const mlip_graph_t *graph, const int64_t **row_ptr, const int
  */
 int mlip_graph_mirror(const mlip_graph_t *graph, const int32_t **mirror);
 
-/* Image shifts of all edges written to a caller-owned DEVICE buffer [E][3] int32 (enqueued on the stream). */
+/*
+ * Image shifts of all edges written to a caller-owned DEVICE buffer [E][3] int32 (enqueued on the stream): the
+ * periodic-boundary part of an edge (the distributed object is built from positions, periodic boundary
+ * conditions and the cell lattice, appendix "Parallelizing a Model in DistMLIP"); the sender's image sits at
+ * r_j + S.C.
+ */
 int mlip_graph_shifts(const mlip_graph_t *graph, int32_t *shifts);
 
-/* slab_of[N] (DEVICE, borrowed) and the axis the walls are perpendicular to (HOST). */
+/*
+ * slab_of[N] (DEVICE, borrowed) and the axis the walls are perpendicular to (HOST): the vertical-wall partition
+ * of Methods, "Distributing Atom Graphs" (walls along the longest cell dimension; appendix "Graph Partitioning").
+ */
 int mlip_graph_slab_of(const mlip_graph_t *graph, const int32_t **slab_of, int32_t *axis);
 
 /* Partition p's node array and local graph. */

@@ -41,6 +41,45 @@ class _SlabInfo(ctypes.Structure):
                [(n, ctypes.c_void_p) for n in ("nodes", "markers", "row_ptr", "senders", "owned_sorted")]
 
 
+_ALLOC_FN = ctypes.CFUNCTYPE(ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p)
+_FREE_FN = ctypes.CFUNCTYPE(None, ctypes.c_void_p, ctypes.c_void_p)
+
+
+class _Alloc(ctypes.Structure):
+    _fields_ = [("alloc", _ALLOC_FN), ("free", _FREE_FN), ("ctx", ctypes.c_void_p)]
+
+
+class TorchAllocator:
+    """mlip_alloc_t backed by torch tensors: every device block the library uses is a uint8 tensor from torch's
+    caching allocator (so torch's memory accounting sees it).  Keeps the blocks alive until the library frees them."""
+
+    def __init__(self):
+        self.blocks = {}
+        self.bytes_requested = 0
+        self.n_alloc = self.n_free = 0
+        self._a = _ALLOC_FN(self._alloc)
+        self._f = _FREE_FN(self._free)
+        self.c = _Alloc(self._a, self._f, None)
+
+    def _alloc(self, nbytes, _ctx):
+        try:
+            t = torch.empty(max(int(nbytes), 1), dtype=torch.uint8, device="cuda")
+        except Exception:   # out of memory: the library reports MLIP_ENOMEM
+            return None
+        self.blocks[t.data_ptr()] = t
+        self.bytes_requested += int(nbytes)
+        self.n_alloc += 1
+        return t.data_ptr()
+
+    def _free(self, ptr, _ctx):
+        self.n_free += 1
+        self.blocks.pop(ptr, None)
+
+    @property
+    def bytes_held(self):
+        return sum(t.numel() for t in self.blocks.values())
+
+
 _lib = None
 
 
@@ -53,6 +92,8 @@ def lib():
                               "(run __graft_entry__.build()); there is no fallback path")
         L = ctypes.CDLL(_LIB_PATH)
         vp, i64, i32, dbl = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_double
+        L.mlip_graph_create.argtypes = [ctypes.POINTER(_Alloc), ctypes.POINTER(vp)]
+        L.mlip_graph_invalidate_weights.argtypes = [vp]
         L.mlip_build_graph.argtypes = [vp, ctypes.POINTER(dbl), vp, i64, dbl, i32, vp, ctypes.POINTER(vp)]
         L.mlip_forward.argtypes = [vp, ctypes.POINTER(_Weights), i32, vp, vp, vp]
         L.mlip_forward_bonds.argtypes = [vp, ctypes.POINTER(_Weights), ctypes.POINTER(_BondWeights), i32, vp, vp, vp]
@@ -86,10 +127,17 @@ def _stream():
 
 
 class Graph:
-    """Owner of a mlip_graph_t handle."""
+    """Owner of a mlip_graph_t handle.  By default the handle takes its device memory from torch (TorchAllocator);
+    allocator=False leaves allocation to the library (hipMalloc)."""
 
-    def __init__(self):
+    def __init__(self, allocator=None):
         self._h = ctypes.c_void_p(None)
+        self.allocator = TorchAllocator() if allocator is None else (allocator or None)
+        if self.allocator is not None:
+            _check(lib().mlip_graph_create(ctypes.byref(self.allocator.c), ctypes.byref(self._h)))
+
+    def invalidate_weights(self):
+        _check(lib().mlip_graph_invalidate_weights(self._h))
 
     def __del__(self):
         self.destroy()
@@ -236,7 +284,7 @@ def mlip_forward_bonds(graph, weights, bond_weights, mode=MODE_WHOLE, out=None, 
     return energy, forces, atom_e
 
 
-def mlip_forward(graph, weights, mode=MODE_WHOLE, out=None, want_atom_energy=True):
+def mlip_forward(graph, weights, mode=MODE_WHOLE, out=None, want_atom_energy=True, _fn="mlip_forward"):
     """Returns (energy cuda f64 [1], forces cuda f32 [N,3], atom_energy cuda f32 [N] or None); asynchronous."""
     N, _, _ = graph.sizes()
     if out is None:
@@ -245,7 +293,7 @@ def mlip_forward(graph, weights, mode=MODE_WHOLE, out=None, want_atom_energy=Tru
         atom_e = torch.empty(N, dtype=torch.float32, device="cuda") if want_atom_energy else None
     else:
         energy, forces, atom_e = out
-    _check(lib().mlip_forward(graph._h, ctypes.byref(weights.c), int(mode), ctypes.c_void_p(energy.data_ptr()),
+    _check(getattr(lib(), _fn)(graph._h, ctypes.byref(weights.c), int(mode), ctypes.c_void_p(energy.data_ptr()),
                               ctypes.c_void_p(forces.data_ptr()),
                               ctypes.c_void_p(atom_e.data_ptr() if atom_e is not None else None)))
     return energy, forces, atom_e

@@ -2,6 +2,7 @@
 #include "mlip_internal.h"
 
 #include <cstring>
+#include <mutex>
 #include <new>
 
 namespace mlip {
@@ -16,32 +17,75 @@ void set_error(const char *fmt, ...)
     va_end(ap);
 }
 
+// allocator and stream of the handle the calling thread is working on (AllocScope)
+static thread_local mlip_alloc_t t_alloc = {nullptr, nullptr, nullptr};
+static thread_local hipStream_t t_stream = nullptr;
+static thread_local bool t_scope = false;
+
+AllocScope::AllocScope(const mlip_graph *g)
+{
+    t_alloc = g->alloc;
+    t_stream = g->stream;
+    t_scope = true;
+}
+
+AllocScope::~AllocScope()
+{
+    t_alloc = {nullptr, nullptr, nullptr};
+    t_stream = nullptr;
+    t_scope = false;
+}
+
+static void *raw_alloc(const mlip_alloc_t &a, size_t bytes, const char **why)
+{
+    void *np = nullptr;
+    if (a.alloc) {
+        np = a.alloc(bytes, a.ctx);
+        if (!np) *why = "the caller's allocator returned NULL";
+        return np;
+    }
+    const hipError_t e = hipMalloc(&np, bytes);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        *why = hipGetErrorString(e);
+        return nullptr;
+    }
+    return np;
+}
+
 int DevBuf::ensure(size_t bytes)
 {
     if (bytes <= cap) return MLIP_OK;
     // grow with slack so that a slowly growing system does not reallocate every step
     size_t want = bytes + bytes / 8 + 256;
-    void *np = nullptr;
-    hipError_t e = hipMalloc(&np, want);
-    if (e != hipSuccess) {
-        (void)hipGetLastError();
+    const char *why = "";
+    void *np = raw_alloc(t_alloc, want, &why);
+    if (!np) {
         want = bytes + 256;  // kernels may read (never use) up to 128 bytes past the end of index arrays
-        e = hipMalloc(&np, want);
+        np = raw_alloc(t_alloc, want, &why);
     }
-    if (e != hipSuccess) {
-        (void)hipGetLastError();
-        set_error("device allocation of %zu bytes failed: %s", bytes, hipGetErrorString(e));
+    if (!np) {
+        set_error("device allocation of %zu bytes failed: %s", bytes, why);
         return MLIP_ENOMEM;
     }
-    if (p) (void)hipFree(p);  // hipFree synchronises, so no kernel still reads the old block
+    release();
     p = np;
     cap = want;
+    owner = t_alloc;
     return MLIP_OK;
 }
 
 void DevBuf::release()
 {
-    if (p) (void)hipFree(p);
+    if (p) {
+        if (owner.alloc) {
+            // a caller's allocator may hand the block to other work at once: nothing enqueued may still use it
+            if (t_scope) (void)hipStreamSynchronize(t_stream);
+            if (owner.free) owner.free(p, owner.ctx);
+        } else {
+            (void)hipFree(p);  // hipFree synchronises, so no kernel still reads the old block
+        }
+    }
     p = nullptr;
     cap = 0;
 }
@@ -101,6 +145,25 @@ extern "C" {
 const char *mlip_last_error(void) { return g_err; }
 const char *mlip_version(void) { return "libmlip 0.1 (gfx950)"; }
 
+int mlip_graph_create(const mlip_alloc_t *alloc, mlip_graph_t **graph)
+{
+    if (!graph) { set_error("null pointer argument"); return MLIP_EINVAL; }
+    if (alloc && alloc->alloc && !alloc->free) { set_error("allocator without a free function"); return MLIP_EINVAL; }
+    mlip_graph *g = new (std::nothrow) mlip_graph();
+    if (!g) { set_error("host allocation failed"); return MLIP_ENOMEM; }
+    if (alloc && alloc->alloc) g->alloc = *alloc;
+    *graph = g;
+    return MLIP_OK;
+}
+
+int mlip_graph_invalidate_weights(mlip_graph_t *g)
+{
+    if (!g) { set_error("null graph"); return MLIP_EINVAL; }
+    g->packed_w_valid = false;
+    g->packed_bw_valid = false;
+    return MLIP_OK;
+}
+
 int mlip_build_graph(const double *positions, const double *cell, const int32_t *species, int64_t n_atoms,
                      double r_cut, int32_t n_slabs, void *stream, mlip_graph_t **graph)
 {
@@ -117,6 +180,7 @@ int mlip_build_graph(const double *positions, const double *cell, const int32_t 
     g->stream = static_cast<hipStream_t>(stream);
     if (g->prof.on && g->prof.used + 64 > (size_t)kMaxEvents) (void)prof_collect(g);
     int rc = MLIP_EHIP;
+    AllocScope scope(g);
     try {
         rc = build_graph_impl(g, positions, cell, species, n_atoms, r_cut, n_slabs);
     } catch (const std::exception &e) {
@@ -161,8 +225,9 @@ int mlip_forward(mlip_graph_t *g, const mlip_weights_t *w, int32_t mode, double 
 {
     MLIP_TRY(check_forward_args(g, w, mode, energy, forces));
     if (g->prof.on && g->prof.used + 1024 > (size_t)kMaxEvents) (void)prof_collect(g);
+    AllocScope scope(g);
     try {
-        return forward_impl(g, w, mode, energy, forces, atom_energy);
+        return forward_impl(g, w, mode, energy, forces, atom_energy, nullptr);
     } catch (const std::exception &e) {
         set_error("host exception: %s", e.what());
         return MLIP_ENOMEM;
@@ -182,6 +247,7 @@ int mlip_forward_bonds(mlip_graph_t *g, const mlip_weights_t *w, const mlip_bond
         return MLIP_EINVAL;
     }
     if (g->prof.on && g->prof.used + 1024 > (size_t)kMaxEvents) (void)prof_collect(g);
+    AllocScope scope(g);
     try {
         return forward_bonds_impl(g, w, bw, mode, energy, forces, atom_energy);
     } catch (const std::exception &e) {
@@ -206,7 +272,7 @@ int mlip_graph_bonds(const mlip_graph_t *g, int32_t p, const int32_t **bond_edge
 void mlip_graph_destroy(mlip_graph_t *g)
 {
     if (!g) return;
-    (void)hipStreamSynchronize(g->stream);
+    (void)hipStreamSynchronize(g->stream);   // once, here: the buffers' release below need not synchronise again
     DevBuf *bufs[] = {&g->pos, &g->species, &g->cell_of, &g->wrapp, &g->cell_cnt, &g->cell_start, &g->cell_fill,
                       &g->sid, &g->sx, &g->sy, &g->sz, &g->swrap, &g->counts, &g->keys, &g->stage, &g->flags, &g->scan_tmp,
                       &g->small, &g->row_ptr, &g->senders, &g->recv, &g->mirror, &g->shiftp, &g->d, &g->chunk_row, &g->slab_of, &g->needed_by,

@@ -29,13 +29,45 @@ void set_error(const char *fmt, ...);
         if (rc_ != MLIP_OK) return rc_; \
     } while (0)
 
-// Grow-only device buffer owned by a graph handle.
+// Grow-only device buffer owned by a graph handle.  Memory comes from the allocator that is current when the
+// buffer grows (the handle's, made current by every entry point that may allocate: AllocScope); the buffer
+// remembers who gave it its block and returns it there.
 struct DevBuf {
     void *p = nullptr;
     size_t cap = 0;
+    mlip_alloc_t owner = {nullptr, nullptr, nullptr};   // alloc == nullptr: hipMalloc / hipFree
     int ensure(size_t bytes);
     void release();
     template <class T> T *as() const { return static_cast<T *>(p); }
+};
+
+// Makes a handle's allocator (and its stream, which is synchronised before a block goes back to a caller's
+// allocator) current for the calling thread until the scope ends.
+struct AllocScope {
+    explicit AllocScope(const mlip_graph *g);
+    ~AllocScope();
+    AllocScope(const AllocScope &) = delete;
+    AllocScope &operator=(const AllocScope &) = delete;
+};
+
+// Bump allocator over a fixed block (the static scratch of mlip_forward_static): 256-byte aligned pieces, no frees.
+struct Carver {
+    char *base = nullptr;
+    size_t size = 0, used = 0;
+    void *take(size_t bytes)
+    {
+        const size_t at = (used + 255) & ~(size_t)255;
+        if (at + bytes > size) { used = size + 1; return nullptr; }   // stays failed
+        used = at + bytes;
+        return base + at;
+    }
+    bool failed() const { return used > size; }
+};
+
+// Workspace of one partition for the forward call in progress (from the view's buffers, or carved from a fixed block).
+struct ViewWs {
+    float *h = nullptr, *hbar = nullptr, *abar = nullptr, *gbar = nullptr, *eps = nullptr, *dsum = nullptr,
+          *floc = nullptr, *g = nullptr, *a = nullptr, *wst = nullptr;
 };
 
 // Cell geometry prepared on the host, passed to kernels by value.
@@ -97,6 +129,7 @@ struct SlabView {
     std::vector<int64_t> markers;          // host, P + 3
     // model workspace (sized in mlip_forward)
     DevBuf h, hbar, abar, gbar, eps, dsum, floc, g, a, wst;  // g and a hold L slices each, wst L - 1
+    ViewWs ws;                             // the pointers the kernels of the current call use
     BondGraph bonds;
 };
 
@@ -119,6 +152,16 @@ struct Profiler {
 
 struct mlip_graph {
     hipStream_t stream = nullptr;
+    mlip_alloc_t alloc = {nullptr, nullptr, nullptr};   // caller's allocator (alloc == nullptr: hipMalloc)
+    // per-handle launch configuration: kernels whose attributes are set, with their resident blocks per compute unit
+    std::vector<std::pair<const void *, int>> fn_occ;
+    int n_cu = 0;
+    // packed weights are kept until the weight struct of a call differs from the one they were packed from
+    mlip_weights_t packed_w = {};
+    bool packed_w_valid = false;
+    mlip_bond_weights_t packed_bw = {};
+    mlip_weights_t packed_bw_w = {};
+    bool packed_bw_valid = false;
     int64_t N = 0, E = 0;
     int32_t P = 1;
     int32_t species_max = 0, species_min = 0;
@@ -154,8 +197,9 @@ void prof_end(mlip_graph *g);
 
 int build_graph_impl(mlip_graph *g, const double *positions, const double *cell, const int32_t *species,
                      int64_t n_atoms, double r_cut, int32_t n_slabs);
+// scratch != nullptr: every piece of workspace is carved from it (nothing is allocated, nothing cached)
 int forward_impl(mlip_graph *g, const mlip_weights_t *w, int32_t mode, double *energy, float *forces,
-                 float *atom_energy);
+                 float *atom_energy, Carver *scratch);
 int unpack_shifts(const mlip_graph *g, int32_t *out);
 // bond list of one partition for cutoff r_bond (kept until the graph is rebuilt or r_bond changes); synchronises
 int build_bonds_impl(mlip_graph *g, SlabView &v, double r_bond, int p_envelope);

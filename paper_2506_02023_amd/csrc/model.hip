@@ -33,6 +33,7 @@
 
 #include <algorithm>
 #include <cmath>
+#include <cstring>
 #include <type_traits>
 
 namespace mlip {
@@ -79,16 +80,40 @@ template <int F> struct Lds {
     static constexpr size_t node2 = sizeof(float) * (2 * D::PACKF + 4 * D::TILE);
 };
 
+// Dynamic LDS size of a kernel, set once per handle (a handle lives on one device and is used by one thread at a
+// time, so this state needs no lock and is right for the device the handle's memory is on).  Returns the slot of
+// the kernel in g->fn_occ, whose second member caches the resident blocks per compute unit (0: not queried).
+int configure_kernel(mlip_graph *g, const void *fn, size_t lds, int *slot)
+{
+    for (size_t k = 0; k < g->fn_occ.size(); ++k)
+        if (g->fn_occ[k].first == fn) { *slot = (int)k; return MLIP_OK; }
+    MLIP_HIP(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    g->fn_occ.emplace_back(fn, 0);
+    *slot = (int)g->fn_occ.size() - 1;
+    return MLIP_OK;
+}
+
+__global__ void k_fill_zero(float *p, int64_t n)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0.f;
+}
+
+// zero-fill with a kernel (not hipMemsetAsync: memset nodes of a captured stream have misbehaved on replay)
+int fill_zero(float *p, int64_t n, hipStream_t s)
+{
+    if (n <= 0) return MLIP_OK;
+    k_fill_zero<<<blocks_for(n, 256), 256, 0, s>>>(p, n);
+    MLIP_HIP(hipGetLastError());
+    return MLIP_OK;
+}
+
 template <int F, int OP> int launch_node(mlip_graph *g, NodeBatch &b)
 {
     constexpr bool TWO = (OP == OP_READOUT || OP == OP_BWD_UPDATE);
     const size_t lds = TWO ? Lds<F>::node2 : Lds<F>::node1;
-    static bool configured = false;
-    if (!configured) {
-        MLIP_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_node<F, OP>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        configured = true;
-    }
+    int slot = 0;
+    MLIP_TRY(configure_kernel(g, reinterpret_cast<const void *>(&k_node<F, OP>), lds, &slot));
     b.tile_start[0] = 0;
     for (int q = 0; q < b.n; ++q) b.tile_start[q + 1] = b.tile_start[q] + (std::max<int64_t>(b.s[q].n_rows, 0) + 31) / 32;
     for (int q = b.n; q < kBatch; ++q) b.tile_start[q + 1] = b.tile_start[b.n];
@@ -105,12 +130,8 @@ template <int F, int STAGE, int PREC> int launch_bond_mlp(mlip_graph *g, const B
 {
     constexpr int NW = BondStage<STAGE>::NW;
     constexpr size_t lds = sizeof(float) * (BondStage<STAGE>::NPACK * Dims<F>::PACKF + NW * Dims<F>::TILE);
-    static bool configured = false;
-    if (!configured) {
-        MLIP_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_bond_mlp<F, STAGE, PREC>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        configured = true;
-    }
+    int slot = 0;
+    MLIP_TRY(configure_kernel(g, reinterpret_cast<const void *>(&k_bond_mlp<F, STAGE, PREC>), lds, &slot));
     if (a.n <= 0) return MLIP_OK;
     const int64_t n_tiles = (a.n + 31) / 32;
     // each block keeps its operand packs in LDS, so let it walk several tiles
@@ -139,25 +160,25 @@ int node_pass(mlip_graph *g, SlabView *views, int P, const float *P1, const floa
 template <int F, int PREC> int launch_edge(mlip_graph *g, EdgeBatch &b, bool backward)
 {
     const size_t lds = backward ? Lds<F>::edge_bwd : Lds<F>::edge_fwd;
-    // resident blocks per compute unit, queried once per kernel
-    static int occ_f = 0, occ_b = 0, n_cu = 0;
-    int &occ = backward ? occ_b : occ_f;
+    // resident blocks per compute unit, queried once per kernel and handle
+    const void *fn = backward ? reinterpret_cast<const void *>(&k_edge_bwd<F, PREC>)
+                              : reinterpret_cast<const void *>(&k_edge_fwd<F, PREC>);
+    int slot = 0;
+    MLIP_TRY(configure_kernel(g, fn, lds, &slot));
+    int occ = g->fn_occ[slot].second;
     if (occ == 0) {
-        const void *fn = backward ? reinterpret_cast<const void *>(&k_edge_bwd<F, PREC>)
-                                  : reinterpret_cast<const void *>(&k_edge_fwd<F, PREC>);
-        MLIP_HIP(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         int dev = 0, o = 0;
         MLIP_HIP(hipGetDevice(&dev));
-        MLIP_HIP(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
+        MLIP_HIP(hipDeviceGetAttribute(&g->n_cu, hipDeviceAttributeMultiprocessorCount, dev));
         if (backward)
             MLIP_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&o, k_edge_bwd<F, PREC>, kBwdWaves * 64, lds));
         else
             MLIP_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&o, k_edge_fwd<F, PREC>, 256, lds));
-        if (o < 1 || n_cu < 8) {
-            set_error("edge kernel does not fit the device (occupancy %d, %d compute units)", o, n_cu);
+        if (o < 1 || g->n_cu < 8) {
+            set_error("edge kernel does not fit the device (occupancy %d, %d compute units)", o, g->n_cu);
             return MLIP_EHIP;
         }
-        occ = o;
+        occ = g->fn_occ[slot].second = o;
     }
     b.chunk_start[0] = 0;
     for (int q = 0; q < b.n; ++q) b.chunk_start[q + 1] = b.chunk_start[q] + (b.s[q].n_rows > 0 ? b.s[q].n_chunks : 0);
@@ -165,7 +186,7 @@ template <int F, int PREC> int launch_edge(mlip_graph *g, EdgeBatch &b, bool bac
     const int64_t items = b.chunk_start[b.n];
     if (items <= 0) return MLIP_OK;
     // persistent grid: what is resident at once, a multiple of the 8 XCDs, no more than the work needs
-    const int64_t resident = (int64_t)(n_cu / 8) * occ;
+    const int64_t resident = (int64_t)(g->n_cu / 8) * occ;
     const int nw = backward ? kBwdWaves : 4;
     const int64_t needed = ((items + 7) / 8 + nw - 1) / nw;
     const unsigned blocks = (unsigned)(8 * std::max<int64_t>(1, std::min(resident, needed)));
@@ -180,7 +201,7 @@ template <int F, int PREC> int launch_edge(mlip_graph *g, EdgeBatch &b, bool bac
 // bw != nullptr: the three-body variant
 template <int F>
 int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t *bw, int32_t mode, double *energy,
-              float *forces, float *atom_energy)
+              float *forces, float *atom_energy, Carver *scratch)
 {
     hipStream_t s = g->stream;
     const int L = w->L;
@@ -197,27 +218,43 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
             set_error("a partition holds more than 2^31 bytes of node features; use more slabs");
             return MLIP_EINVAL;
         }
+    // every array of the call either lives in the view's own grow-only buffer or is carved from the fixed block
+    auto place = [&](DevBuf &buf, size_t bytes, float *&ptr) -> int {
+        if (scratch) {
+            ptr = static_cast<float *>(scratch->take(bytes));
+            return MLIP_OK;   // a failed carve is reported once, below
+        }
+        MLIP_TRY(buf.ensure(bytes));
+        ptr = buf.as<float>();
+        return MLIP_OK;
+    };
     int64_t n_parts = 0;
     for (int p = 0; p < P; ++p) {
         SlabView &v = views[p];
         const size_t no = (size_t)std::max<int64_t>(v.n_owned, 1), nl = (size_t)std::max<int64_t>(v.n_local, 1);
-        MLIP_TRY(v.h.ensure(no * rowb));
-        MLIP_TRY(v.hbar.ensure(no * rowb));
-        MLIP_TRY(v.abar.ensure(nl * rowb));
-        MLIP_TRY(v.gbar.ensure(nl * rowb));
-        MLIP_TRY(v.eps.ensure(no * sizeof(float)));
-        MLIP_TRY(v.dsum.ensure((size_t)std::max<int64_t>(v.n_edges, 1) * sizeof(float)));
-        MLIP_TRY(v.floc.ensure(nl * 3 * sizeof(float)));
-        MLIP_TRY(v.g.ensure(nl * rowb * (size_t)std::max(L, 1)));
-        MLIP_TRY(v.a.ensure(no * rowb * (size_t)std::max(L, 1)));
+        MLIP_TRY(place(v.h, no * rowb, v.ws.h));
+        MLIP_TRY(place(v.hbar, no * rowb, v.ws.hbar));
+        MLIP_TRY(place(v.abar, nl * rowb, v.ws.abar));
+        MLIP_TRY(place(v.gbar, nl * rowb, v.ws.gbar));
+        MLIP_TRY(place(v.eps, no * sizeof(float), v.ws.eps));
+        MLIP_TRY(place(v.dsum, (size_t)std::max<int64_t>(v.n_edges, 1) * sizeof(float), v.ws.dsum));
+        MLIP_TRY(place(v.floc, nl * 3 * sizeof(float), v.ws.floc));
+        MLIP_TRY(place(v.g, nl * rowb * (size_t)std::max(L, 1), v.ws.g));
+        MLIP_TRY(place(v.a, no * rowb * (size_t)std::max(L, 1), v.ws.a));
+        v.ws.wst = nullptr;
         if (L > 1)  // filter values of layers 1..L-1, kept for the reverse pass instead of being recomputed
-            MLIP_TRY(v.wst.ensure((size_t)std::max<int64_t>(v.n_edges_owned, 1) * rowb * (size_t)(L - 1)));
+            MLIP_TRY(place(v.wst, (size_t)std::max<int64_t>(v.n_edges_owned, 1) * rowb * (size_t)(L - 1), v.ws.wst));
         n_parts += (v.n_owned + 1023) / 1024;
     }
-    MLIP_TRY(g->energy_part.ensure((size_t)std::max<int64_t>(n_parts, 1) * sizeof(double)));
     const Packs pk = pack_layout(F, L);
-    MLIP_TRY(g->wpack.ensure(pk.total * sizeof(float)));
-    float *wp = g->wpack.as<float>();
+    float *wp = nullptr, *energy_part_f = nullptr;
+    MLIP_TRY(place(g->energy_part, (size_t)std::max<int64_t>(n_parts, 1) * sizeof(double), energy_part_f));
+    MLIP_TRY(place(g->wpack, pk.total * sizeof(float), wp));
+    if (scratch && scratch->failed()) {
+        set_error("this graph and model need more than the %zu bytes of static workspace", scratch->size);
+        return MLIP_EINVAL;
+    }
+    double *energy_part = reinterpret_cast<double *>(energy_part_f);
 
     BasisParams bp;
     bp.rc = (float)g->r_cut;
@@ -226,10 +263,13 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
     const double pd = (double)w->p;
     bp.pc0 = (float)(pd * (pd + 1) * (pd + 2) / 2);
 
-    // ---- pack weights
+    // ---- pack weights (kept in the handle until a call comes with a different weight struct; the fixed block of
+    // the static variant is shared by all handles, so there they are packed on every call)
     prof_begin(g, MLIP_PROF_NODE);
     const unsigned pb = blocks_for((int64_t)F * F, 256);
-    for (int l = 0; l < L; ++l) {
+    const bool repack = scratch != nullptr || !g->packed_w_valid || std::memcmp(&g->packed_w, w, sizeof(*w)) != 0;
+    g->packed_w_valid = false;
+    for (int l = 0; repack && l < L; ++l) {
         float *base = wp + pk.per_layer * l;
         const size_t ff = (size_t)F * F;
         k_pack_w1<<<blocks_for((F / 32) * 256, 256), 256, 0, s>>>(w->W1 + (size_t)l * 8 * F, F, 1.0f, base + pk.A1);
@@ -249,16 +289,22 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
         k_pack_ff<<<pb, 256, 0, s>>>(w->Wo + l * ff, F, 1, 1.0f, base + pk.Wot);
         k_pack_ff<<<pb, 256, 0, s>>>(w->Wo + l * ff, F, 0, 1.0f, base + pk.Won);
     }
-    k_pack_ff<<<pb, 256, 0, s>>>(w->Wr1, F, 1, 1.0f, wp + pk.readout_t);
-    k_pack_ff<<<pb, 256, 0, s>>>(w->Wr1, F, 0, 1.0f, wp + pk.readout_n);
+    if (repack) {
+        k_pack_ff<<<pb, 256, 0, s>>>(w->Wr1, F, 1, 1.0f, wp + pk.readout_t);
+        k_pack_ff<<<pb, 256, 0, s>>>(w->Wr1, F, 0, 1.0f, wp + pk.readout_n);
+    }
     MLIP_HIP(hipGetLastError());
+    if (!scratch) {
+        g->packed_w = *w;
+        g->packed_w_valid = true;
+    }
 
     // ---- embedding
     const int32_t *species = g->species.as<int32_t>();
     for (int p = 0; p < P; ++p) {
         SlabView &v = views[p];
         if (v.n_owned > 0)
-            k_embed<<<blocks_for(v.n_owned * (F / 4), 256), 256, 0, s>>>(v.n_owned, F, v.nodes, species, w->emb, v.h.as<float>());
+            k_embed<<<blocks_for(v.n_owned * (F / 4), 256), 256, 0, s>>>(v.n_owned, F, v.nodes, species, w->emb, v.ws.h);
     }
     MLIP_HIP(hipGetLastError());
     prof_end(g);
@@ -292,7 +338,7 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
         a.wb = BG.wb.as<float>();
         a.abar = BG.abar_keep.as<float>();
         a.abar_stride = (size_t)std::max<int64_t>(v.n_owned, 1) * F;
-        a.g = v.g.as<float>();
+        a.g = v.ws.g;
         a.g_stride = (size_t)v.n_local * F;
         a.e1bar = BG.e1bar.as<float>();
         a.ubar = BG.ubar.as<float>();
@@ -325,6 +371,9 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
         bpk = g->bond_wpack.as<float>();
         prof_begin(g, MLIP_PROF_BOND);
         const float *Wta = bw->Wt1, *Wtb = bw->Wt1 + ffp, *Wtc = bw->Wt1 + 2 * ffp;
+        const bool repack_b = !g->packed_bw_valid || std::memcmp(&g->packed_bw, bw, sizeof(*bw)) != 0 ||
+                              std::memcmp(&g->packed_bw_w, w, sizeof(*w)) != 0;
+        g->packed_bw_valid = false;
         // the bond MLPs' F x F products follow the filter MLP's precision mode: fp32 pack, bf16 in the first half of the
         // slot, or split-fp16 (hi and lo halves)
         auto pack_bond = [&](const float *Wsrc, int trans, int slot) {
@@ -335,18 +384,23 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
             else
                 k_pack_ff<<<pb, 256, 0, s>>>(Wsrc, F, trans, 1.0f, bpk + (size_t)slot * ffp);
         };
-        pack_bond(Wta, 1, 0);
-        pack_bond(Wtb, 1, 1);
-        pack_bond(bw->Wt2, 1, 2);
-        pack_bond(Wta, 0, 3);
-        pack_bond(Wtb, 0, 4);
-        pack_bond(bw->Wt2, 0, 5);
-        for (int l = 0; l < L; ++l) {
-            pack_bond(bw->Wb + l * ffp, 1, 6 + l);
-            pack_bond(bw->Wb + l * ffp, 0, 6 + L + l);
+        if (repack_b) {
+            pack_bond(Wta, 1, 0);
+            pack_bond(Wtb, 1, 1);
+            pack_bond(bw->Wt2, 1, 2);
+            pack_bond(Wta, 0, 3);
+            pack_bond(Wtb, 0, 4);
+            pack_bond(bw->Wt2, 0, 5);
+            for (int l = 0; l < L; ++l) {
+                pack_bond(bw->Wb + l * ffp, 1, 6 + l);
+                pack_bond(bw->Wb + l * ffp, 0, 6 + L + l);
+            }
+            k_pack_w1<<<blocks_for(Dims<F>::PACK1, 256), 256, 0, s>>>(bw->We0, F, 1.0f, bpk + (size_t)(6 + 2 * L) * ffp);
         }
-        k_pack_w1<<<blocks_for(Dims<F>::PACK1, 256), 256, 0, s>>>(bw->We0, F, 1.0f, bpk + (size_t)(6 + 2 * L) * ffp);
         MLIP_HIP(hipGetLastError());
+        g->packed_bw = *bw;
+        g->packed_bw_w = *w;
+        g->packed_bw_valid = true;
         for (int p = 0; p < P; ++p) {   // P = e0 Wta, Q = e0 Wtb with e0 = bbond(d) We0
             BondArgs a = bond_args(views[p]);
             a.W[0] = bpk + 0 * ffp;
@@ -379,10 +433,10 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
         prof_end(g);
     }
 
-    auto gslice = [&](SlabView &v, int l) { return v.g.as<float>() + (size_t)l * (size_t)v.n_local * F; };
-    auto aslice = [&](SlabView &v, int l) { return v.a.as<float>() + (size_t)l * (size_t)v.n_owned * F; };
+    auto gslice = [&](SlabView &v, int l) { return v.ws.g + (size_t)l * (size_t)v.n_local * F; };
+    auto aslice = [&](SlabView &v, int l) { return v.ws.a + (size_t)l * (size_t)v.n_owned * F; };
     auto wslice = [&](SlabView &v, int l) {  // l >= 1
-        return v.wst.as<float>() + (size_t)(l - 1) * (size_t)v.n_edges_owned * F;
+        return v.ws.wst + (size_t)(l - 1) * (size_t)v.n_edges_owned * F;
     };
 
     // ---- forward layers
@@ -391,7 +445,7 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
         prof_begin(g, MLIP_PROF_NODE);
         MLIP_TRY((node_pass<F, OP_PROJ>(g, views, P, base + pk.Wmt, nullptr, nullptr, [&](SlabView &v, NodeArgs &na) {
             na.n_rows = v.n_owned;   // sender projection on owned rows
-            na.X = v.h.as<float>();
+            na.X = v.ws.h;
             na.Y = gslice(v, l);
         })));
         prof_end(g);
@@ -451,7 +505,7 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
         MLIP_TRY((node_pass<F, OP_UPDATE>(g, views, P, base + pk.Wot, nullptr, nullptr, [&](SlabView &v, NodeArgs &na) {
             na.n_rows = v.n_owned;
             na.X = aslice(v, l);
-            na.Z = v.h.as<float>();
+            na.Z = v.ws.h;
         })));
         prof_end(g);
     }
@@ -461,19 +515,19 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
     MLIP_TRY((node_pass<F, OP_READOUT>(g, views, P, wp + pk.readout_t, wp + pk.readout_n, w->wr2,
                                        [&](SlabView &v, NodeArgs &na) {
                                            na.n_rows = v.n_owned;
-                                           na.X = v.h.as<float>();
-                                           na.Y = v.hbar.as<float>();
-                                           na.eps = v.eps.as<float>();
+                                           na.X = v.ws.h;
+                                           na.Y = v.ws.hbar;
+                                           na.eps = v.ws.eps;
                                        })));
     prof_end(g);
     prof_begin(g, MLIP_PROF_FORCE);
     {
         int64_t off = 0;
-        double *part = g->energy_part.as<double>();
+        double *part = energy_part;
         for (int p = 0; p < P; ++p) {
             SlabView &v = views[p];
             const int64_t nb = (v.n_owned + 1023) / 1024;
-            if (nb > 0) k_energy_partial<<<(unsigned)nb, 256, 0, s>>>(v.n_owned, v.eps.as<float>(), part + off);
+            if (nb > 0) k_energy_partial<<<(unsigned)nb, 256, 0, s>>>(v.n_owned, v.ws.eps, part + off);
             off += nb;
         }
         k_energy_final<<<1, 256, 0, s>>>(off, part, energy);
@@ -485,7 +539,7 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
     for (int p = 0; p < P; ++p) {  // ghost rows carry no dE/da: zero once, no kernel ever writes them
         SlabView &v = views[p];
         if (L > 0 && v.n_ghost > 0)
-            MLIP_HIP(hipMemsetAsync(v.abar.as<float>() + (size_t)v.n_owned * F, 0, (size_t)v.n_ghost * rowb, s));
+            MLIP_TRY(fill_zero(v.ws.abar + (size_t)v.n_owned * F, v.n_ghost * (int64_t)F, s));
     }
     for (int l = L - 1; l >= 0; --l) {
         const float *base = wp + pk.per_layer * l;
@@ -495,8 +549,8 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
                                               [&](SlabView &v, NodeArgs &na) {
                                                   na.n_rows = v.n_owned;
                                                   na.X = aslice(v, l);
-                                                  na.Z = v.hbar.as<float>();
-                                                  na.Y = v.abar.as<float>();
+                                                  na.Z = v.ws.hbar;
+                                                  na.Y = v.ws.abar;
                                               })));
         prof_end(g);
         for (int p0 = 0; p0 < P; p0 += kBatch) {
@@ -521,9 +575,9 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
                 ea.recv = v.recv;
                 ea.d = v.d;
                 ea.g = gslice(v, l);
-                ea.abar = v.abar.as<float>();
-                ea.out = v.gbar.as<float>();
-                ea.dsum = v.dsum.as<float>();
+                ea.abar = v.ws.abar;
+                ea.out = v.ws.gbar;
+                ea.dsum = v.ws.dsum;
                 ea.mirror = v.mirror;
                 ea.wstore = need_gbar ? wslice(v, l) : nullptr;
                 ea.n_stored = need_gbar ? v.n_edges_owned : 0;
@@ -539,12 +593,12 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
                 SlabView &v = views[p];
                 BondGraph &BG = v.bonds;
                 if (BG.n > 0)
-                    MLIP_HIP(hipMemcpyAsync(BG.abar_keep.as<float>() + (size_t)l * (size_t)v.n_owned * F, v.abar.p,
+                    MLIP_HIP(hipMemcpyAsync(BG.abar_keep.as<float>() + (size_t)l * (size_t)v.n_owned * F, v.ws.abar,
                                             (size_t)v.n_owned * rowb, hipMemcpyDeviceToDevice, s));
                 if (BG.n > 0 && need_gbar)
                     k_bond_gbar<F><<<blocks_for(v.n_owned, 4), 256, 0, s>>>(
                         v.n_owned, BG.ptr.as<int64_t>(), BG.sender.as<int32_t>(), BG.mirror.as<int32_t>(), wbslice(v, l),
-                        v.abar.as<float>(), v.gbar.as<float>());
+                        v.ws.abar, v.ws.gbar);
             }
             MLIP_HIP(hipGetLastError());
             prof_end(g);
@@ -553,17 +607,17 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
             if (slabs) {
                 prof_begin(g, MLIP_PROF_GHOST);
                 PtrTable tab{};
-                for (int q = 0; q < P; ++q) tab.p[q] = views[q].gbar.as<float>();
+                for (int q = 0; q < P; ++q) tab.p[q] = views[q].ws.gbar;
                 for (int p = 0; p < P; ++p) {  // ghost-row gradients -> owners, partitions in ascending order
                     SlabView &v = views[p];
                     if (v.n_ghost > 0)
                         k_ghost_gbar<F><<<blocks_for(v.n_ghost, 4), 256, 0, s>>>(
-                            v.n_ghost, v.n_owned, v.row_ptr, v.senders, v.mirror, wslice(v, l), v.abar.as<float>(),
+                            v.n_ghost, v.n_owned, v.row_ptr, v.senders, v.mirror, wslice(v, l), v.ws.abar,
                             (bw && v.bonds.n > 0) ? v.bonds.of_edge.as<int32_t>() : nullptr,
-                            (bw && v.bonds.n > 0) ? wbslice(v, l) : nullptr, v.gbar.as<float>());
+                            (bw && v.bonds.n > 0) ? wbslice(v, l) : nullptr, v.ws.gbar);
                     if (v.n_ghost > 0)
                         k_ghost_addback<<<blocks_for(v.n_ghost * (F / 4), 256), 256, 0, s>>>(
-                            v.n_ghost, v.n_owned, F, v.ghost_owner, v.ghost_src, tab, v.gbar.as<float>());
+                            v.n_ghost, v.n_owned, F, v.ghost_owner, v.ghost_src, tab, v.ws.gbar);
                 }
                 MLIP_HIP(hipGetLastError());
                 prof_end(g);
@@ -571,8 +625,8 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
             prof_begin(g, MLIP_PROF_NODE);
             MLIP_TRY((node_pass<F, OP_BWD_PROJ>(g, views, P, base + pk.Wmn, nullptr, nullptr, [&](SlabView &v, NodeArgs &na) {
                 na.n_rows = v.n_owned;
-                na.X = v.gbar.as<float>();
-                na.Z = v.hbar.as<float>();
+                na.X = v.ws.gbar;
+                na.Z = v.ws.hbar;
             })));
             prof_end(g);
         }
@@ -620,31 +674,31 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
     for (int p = 0; p < P; ++p) {
         SlabView &v = views[p];
         if (L > 0 && v.n_local > 0) {
-            k_force_rows<<<(unsigned)((v.n_local + 15) / 16), 256, 0, s>>>(v.n_local, v.row_ptr, v.senders, v.shiftp, v.dsum.as<float>(),
-                                                            v.nodes, pos, g->cell, v.floc.as<float>());
+            k_force_rows<<<(unsigned)((v.n_local + 15) / 16), 256, 0, s>>>(v.n_local, v.row_ptr, v.senders, v.shiftp, v.ws.dsum,
+                                                            v.nodes, pos, g->cell, v.ws.floc);
         } else if (v.n_local > 0) {
-            MLIP_HIP(hipMemsetAsync(v.floc.p, 0, (size_t)v.n_local * 3 * sizeof(float), s));
+            MLIP_TRY(fill_zero(v.ws.floc, v.n_local * 3, s));
         }
         if (bw && v.bonds.n > 0) {
             BondGraph &BG = v.bonds;
             k_bond_force<<<blocks_for(v.n_owned, 128), 128, 0, s>>>(v.n_owned, BG.ptr.as<int64_t>(), BG.mirror.as<int32_t>(),
                                                                     BG.dbond.as<float>(), BG.rbar.as<float>(),
-                                                                    BG.rhat.as<float>(), BG.d.as<float>(), v.floc.as<float>());
+                                                                    BG.rhat.as<float>(), BG.d.as<float>(), v.ws.floc);
             if (v.n_ghost > 0)
                 k_bond_force_ghost<<<blocks_for(v.n_ghost, 128), 128, 0, s>>>(
                     v.n_ghost, v.n_owned, v.row_ptr, v.mirror, BG.of_edge.as<int32_t>(), BG.dbond.as<float>(),
-                    BG.rbar.as<float>(), BG.rhat.as<float>(), BG.d.as<float>(), v.floc.as<float>());
+                    BG.rbar.as<float>(), BG.rhat.as<float>(), BG.d.as<float>(), v.ws.floc);
         }
         if (v.n_owned > 0)
-            k_store_owned<<<blocks_for(v.n_owned, 256), 256, 0, s>>>(v.n_owned, v.nodes, v.floc.as<float>(),
-                                                                     v.eps.as<float>(), forces, atom_energy);
+            k_store_owned<<<blocks_for(v.n_owned, 256), 256, 0, s>>>(v.n_owned, v.nodes, v.ws.floc,
+                                                                     v.ws.eps, forces, atom_energy);
     }
     if (slabs)
         for (int p = 0; p < P; ++p) {
             SlabView &v = views[p];
             if (v.n_ghost > 0)
                 k_addback_ghost_forces<<<blocks_for(v.n_ghost, 256), 256, 0, s>>>(v.n_ghost, v.n_owned, v.nodes,
-                                                                                  v.floc.as<float>(), forces);
+                                                                                  v.ws.floc, forces);
         }
     MLIP_HIP(hipGetLastError());
     prof_end(g);
@@ -653,17 +707,18 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
 
 }  // namespace
 
-int forward_impl(mlip_graph *g, const mlip_weights_t *w, int32_t mode, double *energy, float *forces, float *atom_energy)
+int forward_impl(mlip_graph *g, const mlip_weights_t *w, int32_t mode, double *energy, float *forces, float *atom_energy,
+                 Carver *scratch)
 {
-    if (w->F == 32) return forward_t<32>(g, w, nullptr, mode, energy, forces, atom_energy);
-    return forward_t<64>(g, w, nullptr, mode, energy, forces, atom_energy);
+    if (w->F == 32) return forward_t<32>(g, w, nullptr, mode, energy, forces, atom_energy, scratch);
+    return forward_t<64>(g, w, nullptr, mode, energy, forces, atom_energy, scratch);
 }
 
 int forward_bonds_impl(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t *bw, int32_t mode,
                        double *energy, float *forces, float *atom_energy)
 {
-    if (w->F == 32) return forward_t<32>(g, w, bw, mode, energy, forces, atom_energy);
-    return forward_t<64>(g, w, bw, mode, energy, forces, atom_energy);
+    if (w->F == 32) return forward_t<32>(g, w, bw, mode, energy, forces, atom_energy, nullptr);
+    return forward_t<64>(g, w, bw, mode, energy, forces, atom_energy, nullptr);
 }
 
 }  // namespace mlip

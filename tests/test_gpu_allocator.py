@@ -1,0 +1,119 @@
+"""The caller-supplied allocator and the packed-weight cache, through the C ABI.
+
+Every device block of a handle made by mlip_graph_create with an allocator comes from that allocator (here backed
+by torch tensors and counting what is asked for); results are bit-identical to those of a handle that lets the
+library call hipMalloc; a rebuilt handle asks for nothing new; a failing allocator surfaces as MLIP_ENOMEM.
+"""
+import ctypes
+
+import numpy as np
+import pytest
+
+import workloads as wl
+
+from gpu_util import assert_energy_forces, oracle_config
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(g, c, mode, weights=None, precision=0):
+    import torch
+    import paper_2506_02023_amd as M
+    W = weights if weights is not None else M.Weights(c["weights"], c["p"], precision=precision)
+    e, f, ae = M.mlip_forward(g, W, mode)
+    torch.cuda.synchronize()
+    return float(e.cpu()[0]), f.cpu().numpy().astype(np.float64), ae.cpu().numpy().astype(np.float64)
+
+
+def test_allocator_receives_every_block_and_results_are_unchanged():
+    import torch
+    import paper_2506_02023_amd as M
+    c, ref_g, ref = oracle_config(1, 8)          # configs[1] recipe at 8^3 cells: 2,048 atoms, F = 64, L = 3
+    pos = torch.as_tensor(c["positions"], device="cuda")
+    sp = torch.as_tensor(c["species"], device="cuda")
+    N, E, F, L, P = ref_g.N, ref_g.E, c["F"], c["L"], 3
+    A = M.TorchAllocator()
+    g = M.Graph(allocator=A)
+    assert A.n_alloc == 0
+    g = M.mlip_build_graph(pos, c["cell"], sp, c["r_cut"], n_slabs=P, graph=g)
+    graph_bytes = A.bytes_requested
+    assert A.n_alloc > 10 and graph_bytes >= E * 20 + N * 8        # CSR: 20 B per edge, row_ptr
+    plain = M.mlip_build_graph(pos, c["cell"], sp, c["r_cut"], n_slabs=P, graph=M.Graph(allocator=False))
+    for mode in (M.MODE_WHOLE, M.MODE_SLABS):
+        before = A.bytes_requested
+        e, f, ae = _run(g, c, mode)
+        # node workspace (h, hbar, abar, gbar, L slices of g and a) and the kept filter values of layers 1..L-1
+        assert A.bytes_requested - before >= N * F * 4 * (4 + 2 * L) + E * F * 4 * (L - 1)
+        assert_energy_forces(e, f, ref, f"allocator handle, mode {mode}")
+        e0, f0, ae0 = _run(plain, c, mode)
+        assert e == e0 and np.array_equal(f, f0) and np.array_equal(ae, ae0)
+    # grow-only: the same system again asks for nothing
+    n_alloc, asked = A.n_alloc, A.bytes_requested
+    g = M.mlip_build_graph(pos, c["cell"], sp, c["r_cut"], n_slabs=P, graph=g)
+    _run(g, c, M.MODE_SLABS)
+    assert (A.n_alloc, A.bytes_requested) == (n_alloc, asked)
+    assert A.bytes_held >= asked * 0.5
+    g.destroy()
+    plain.destroy()
+    assert A.n_free == A.n_alloc and not A.blocks
+
+
+def test_failing_allocator_is_reported_as_out_of_memory():
+    import torch
+    import paper_2506_02023_amd as M
+    c = wl.make_config(0)
+    pos = torch.as_tensor(c["positions"], device="cuda")
+    sp = torch.as_tensor(c["species"], device="cuda")
+
+    class Stingy(M.TorchAllocator):
+        budget = 200_000
+
+        def _alloc(self, nbytes, ctx):
+            if self.bytes_requested + nbytes > self.budget:
+                return None
+            return super()._alloc(nbytes, ctx)
+
+    A = Stingy()
+    g = M.Graph(allocator=A)
+    with pytest.raises(M.MlipError) as err:
+        M.mlip_build_graph(pos, c["cell"], sp, c["r_cut"], n_slabs=2, graph=g)
+    assert err.value.code == -4 and "allocator" in str(err.value)
+    A.budget = 1 << 40       # the same handle works once memory is there
+    g = M.mlip_build_graph(pos, c["cell"], sp, c["r_cut"], n_slabs=2, graph=g)
+    _, _, ref = oracle_config(0)
+    e, f, _ = _run(g, c, M.MODE_SLABS)
+    assert_energy_forces(e, f, ref, "after the allocator recovered")
+    g.destroy()
+    assert A.n_free == A.n_alloc
+
+
+def test_packed_weights_are_cached_and_invalidated():
+    """A second call with the same weight struct reuses the packed operands; after the values change in place,
+    mlip_graph_invalidate_weights makes the next call pack again (checked against the oracle with the new values);
+    a different struct (other precision) is noticed without it."""
+    import torch
+    import paper_2506_02023_amd as M
+    from oracle import model as om
+    c, ref_g, ref = oracle_config(0)
+    pos = torch.as_tensor(c["positions"], device="cuda")
+    sp = torch.as_tensor(c["species"], device="cuda")
+    g = M.mlip_build_graph(pos, c["cell"], sp, c["r_cut"], n_slabs=2)
+    W = M.Weights(c["weights"], c["p"])
+    r1 = _run(g, c, M.MODE_SLABS, weights=W)
+    r2 = _run(g, c, M.MODE_SLABS, weights=W)
+    assert r1[0] == r2[0] and np.array_equal(r1[1], r2[1])
+    assert_energy_forces(r1[0], r1[1], ref, "first call")
+    W.t["W2"].mul_(2.0)      # (a change that leaves a total energy well away from zero: -56.3 against -2.9)
+    torch.cuda.synchronize()
+    g.invalidate_weights()
+    w2 = dict(c["weights"])
+    w2["W2"] = (w2["W2"] * np.float32(2.0)).astype(np.float32)
+    ref2 = om.energy_forces(c["positions"], c["cell"], c["species"], w2, ref_g, c["r_cut"], c["K"], c["p"])
+    assert abs(ref2["energy"] - ref["energy"]) > 1e-3 * abs(ref["energy"])
+    r3 = _run(g, c, M.MODE_SLABS, weights=W)
+    assert_energy_forces(r3[0], r3[1], ref2, "after invalidation")
+    W16 = M.Weights(w2, c["p"], precision=2)     # other struct: packed anew without being told
+    r4 = _run(g, c, M.MODE_WHOLE, weights=W16)
+    assert_energy_forces(r4[0], r4[1], ref2, "other precision")
+    r5 = _run(g, c, M.MODE_WHOLE, weights=W)
+    assert r5[0] == _run(M.mlip_build_graph(pos, c["cell"], sp, c["r_cut"]), c, M.MODE_WHOLE, weights=W)[0]

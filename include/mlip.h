@@ -195,6 +195,24 @@ int mlip_build_graph(const double *positions, const double *cell, const int32_t 
 int mlip_forward(mlip_graph_t *graph, const mlip_weights_t *weights, int32_t mode,
                  double *energy, float *forces, float *atom_energy);
 
+/*
+ * mlip_forward for callers that cannot allocate device memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments, results and error codes as mlip_forward, but every
+ * piece of workspace (node features and their gradients, kept filter values, per-edge accumulators, packed
+ * weights, energy partial sums) is carved from one fixed device array inside the library of
+ * mlip_static_scratch_bytes() = 64 MiB per GPU, held until the process ends; the call allocates and frees
+ * nothing and clears what must start at zero with fill kernels.  A graph and model whose workspace
+ * (about n_local (4 + 2 L) F 4 + n_edges (4 + (L - 1) F 4) bytes summed over the partitions of the mode, plus
+ * the packed weights) exceeds the array are rejected with MLIP_EINVAL; with the event profiler enabled the call
+ * returns MLIP_ESTATE.  All calls on one GPU, from any handle, share the array and find the previous call's
+ * contents in it: calls that overlap on one GPU (two streams, two threads) race and must be serialised by the
+ * caller.  Weights are packed on every call (nothing is cached in the shared array).  The graph itself must
+ * have been built before (mlip_build_graph allocates).
+ */
+int mlip_forward_static(mlip_graph_t *graph, const mlip_weights_t *weights, int32_t mode,
+                        double *energy, float *forces, float *atom_energy);
+size_t mlip_static_scratch_bytes(void);
+
 /* Drops the handle's packed copies of the weights (two-body and bond part); the next forward call packs again. */
 int mlip_graph_invalidate_weights(mlip_graph_t *graph);
 

@@ -94,6 +94,8 @@ def lib():
         vp, i64, i32, dbl = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_double
         L.mlip_graph_create.argtypes = [ctypes.POINTER(_Alloc), ctypes.POINTER(vp)]
         L.mlip_graph_invalidate_weights.argtypes = [vp]
+        L.mlip_forward_static.argtypes = [vp, ctypes.POINTER(_Weights), i32, vp, vp, vp]
+        L.mlip_static_scratch_bytes.restype = ctypes.c_size_t
         L.mlip_build_graph.argtypes = [vp, ctypes.POINTER(dbl), vp, i64, dbl, i32, vp, ctypes.POINTER(vp)]
         L.mlip_forward.argtypes = [vp, ctypes.POINTER(_Weights), i32, vp, vp, vp]
         L.mlip_forward_bonds.argtypes = [vp, ctypes.POINTER(_Weights), ctypes.POINTER(_BondWeights), i32, vp, vp, vp]
@@ -282,6 +284,11 @@ def mlip_forward_bonds(graph, weights, bond_weights, mode=MODE_WHOLE, out=None, 
                                     ctypes.c_void_p(energy.data_ptr()), ctypes.c_void_p(forces.data_ptr()),
                                     ctypes.c_void_p(atom_e.data_ptr() if atom_e is not None else None)))
     return energy, forces, atom_e
+
+
+def mlip_forward_static(graph, weights, mode=MODE_WHOLE, out=None, want_atom_energy=True):
+    """mlip_forward with the library's fixed workspace (no device allocation inside the call); `out` as mlip_forward."""
+    return mlip_forward(graph, weights, mode, out, want_atom_energy, _fn="mlip_forward_static")
 
 
 def mlip_forward(graph, weights, mode=MODE_WHOLE, out=None, want_atom_energy=True, _fn="mlip_forward"):

@@ -234,6 +234,57 @@ int mlip_forward(mlip_graph_t *g, const mlip_weights_t *w, int32_t mode, double 
     }
 }
 
+// ---- mlip_forward_static: the forward call with its whole workspace in a fixed device array of the library.
+//
+// Each GPU holds its own copy of the array at its own address; the array's name is only a host-side handle
+// for hipGetSymbolAddress, whose result (per device) is what kernels and fills are given.
+#define MLIP_STATIC_SCRATCH_BYTES (64u << 20)
+static __device__ __align__(256) unsigned char scratch[MLIP_STATIC_SCRATCH_BYTES];
+
+enum { kMaxDevices = 64 };
+static std::mutex g_scratch_mutex;
+static void *g_scratch_ptr[kMaxDevices] = {nullptr};
+
+// device address of the array on the current device, looked up once per device
+static int static_scratch(void **out)
+{
+    int dev = -1;
+    MLIP_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) { set_error("device index %d out of range", dev); return MLIP_EHIP; }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        MLIP_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) { set_error("hipGetSymbolAddress returned a null address for the static workspace"); return MLIP_EHIP; }
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return MLIP_OK;
+}
+
+size_t mlip_static_scratch_bytes(void) { return (size_t)MLIP_STATIC_SCRATCH_BYTES; }
+
+int mlip_forward_static(mlip_graph_t *g, const mlip_weights_t *w, int32_t mode, double *energy, float *forces,
+                        float *atom_energy)
+{
+    MLIP_TRY(check_forward_args(g, w, mode, energy, forces));
+    if (g->prof.on) {   // the event profiler creates events as it goes
+        set_error("mlip_forward_static does not run with the event profiler enabled");
+        return MLIP_ESTATE;
+    }
+    void *base = nullptr;
+    MLIP_TRY(static_scratch(&base));
+    Carver carve;
+    carve.base = static_cast<char *>(base);
+    carve.size = (size_t)MLIP_STATIC_SCRATCH_BYTES;
+    try {
+        return forward_impl(g, w, mode, energy, forces, atom_energy, &carve);
+    } catch (const std::exception &e) {
+        set_error("host exception: %s", e.what());
+        return MLIP_ENOMEM;
+    }
+}
+
 int mlip_forward_bonds(mlip_graph_t *g, const mlip_weights_t *w, const mlip_bond_weights_t *bw, int32_t mode,
                        double *energy, float *forces, float *atom_energy)
 {

@@ -340,9 +340,11 @@ void mlip_graph_destroy(mlip_graph_t *g)
     };
     drop_view(g->whole);
     for (auto &v : g->slabs) drop_view(v);
-    for (auto &st : g->store) {
-        DevBuf *sb[] = {&st.nodes, &st.row_ptr, &st.senders, &st.recv, &st.mirror, &st.shiftp, &st.d, &st.chunk_row, &st.ghost_owner, &st.ghost_src,
-                        &st.owned_sorted, &st.rowlen};
+    {
+        PartStore &st = g->part;
+        DevBuf *sb[] = {&st.nodes, &st.owned_sorted, &st.ghost_owner, &st.ghost_src, &st.rowlen, &st.row_abs, &st.row_ptr,
+                        &st.senders, &st.recv, &st.mirror, &st.shiftp, &st.d, &st.chunk_row, &st.gbase, &st.ghost_local,
+                        &st.sizes};
         for (DevBuf *b : sb) b->release();
     }
     for (hipEvent_t e : g->prof.pool) (void)hipEventDestroy(e);
@@ -409,7 +411,7 @@ int mlip_graph_slab(const mlip_graph_t *g, int32_t p, mlip_slab_info_t *info)
     info->markers = v.markers.data();
     info->row_ptr = v.row_ptr;
     info->senders = v.senders;
-    info->owned_sorted = g->store[p].owned_sorted.as<int32_t>();
+    info->owned_sorted = v.owned_sorted;
     return MLIP_OK;
 }
 

@@ -482,68 +482,150 @@ __device__ inline int node_class(int s, unsigned long long nb, int q)
     return ((nb >> q) & 1ull) ? 2 + s : -1;
 }
 
-// per wavefront of 64 consecutive atoms: how many fall in each class; class ncls is "owned"
-__global__ void __launch_bounds__(64)
-k_class_count(int64_t N, const int32_t *__restrict__ slab_of, const unsigned long long *__restrict__ needed_by,
-              int q, int ncls, int64_t nwaves, int32_t *cnt)
+// ---- index sets of all partitions in one pass
+//
+// Every atom u is a node of its own partition (PURE or BORDER) and a ghost of every partition q whose bit is set in
+// needed_by[u] (span FROM_q[slab(u)]).  The node arrays of all partitions sit one after another in one array, each
+// laid out PURE | BORDER | FROM[0] | ... | FROM[P-1] with every span in ascending atom id: a stable counting sort
+// with the bins (q, c), c = 0 PURE, 1 BORDER, 2 + s FROM[s]  (P (P + 2) bins), followed by P pseudo-bins "owned by
+// q" for the ascending list of owned atoms.  One wavefront walks kRange consecutive atoms and keeps its bins'
+// counts (first pass) or write positions (second pass) in its own LDS table; between the passes one flat scan over
+// cnt[bin][range] turns the counts into positions.
+constexpr int kRange = 512;
+
+__device__ inline unsigned long long wave_or(unsigned long long v)
 {
-    const int64_t w = blockIdx.x;
-    const int64_t u = w * 64 + threadIdx.x;
-    const int cls = u < N ? node_class(slab_of[u], needed_by[u], q) : -1;
-    for (int c = 0; c < ncls; ++c) {
-        const unsigned long long m = __ballot(cls == c);
-        if (threadIdx.x == 0) cnt[(int64_t)c * nwaves + w] = __popcll(m);
-    }
-    const unsigned long long mo = __ballot(cls == 0 || cls == 1);
-    if (threadIdx.x == 0) cnt[(int64_t)ncls * nwaves + w] = __popcll(mo);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v |= __shfl_xor(v, off, 64);
+    return v;
 }
 
-__global__ void __launch_bounds__(64)
-k_class_scatter(int64_t N, const int32_t *__restrict__ slab_of, const unsigned long long *__restrict__ needed_by,
-                int q, int ncls, int64_t nwaves, const int32_t *__restrict__ off, int32_t *nodes,
-                int32_t *owned_sorted, int32_t *local_of, int32_t *local_in_owner)
+template <bool SCATTER>
+__global__ void __launch_bounds__(256)
+k_classes(int64_t N, int P, int64_t nranges, const int32_t *__restrict__ slab_of,
+          const unsigned long long *__restrict__ needed_by, int32_t *cnt, const int32_t *__restrict__ off,
+          const int32_t *__restrict__ gbase, int32_t *nodes, int32_t *owned_sorted, int32_t *local_in_owner,
+          int32_t *ghost_local)
 {
-    const int64_t w = blockIdx.x;
-    const int64_t u = w * 64 + threadIdx.x;
-    const int cls = u < N ? node_class(slab_of[u], needed_by[u], q) : -1;
-    const unsigned long long lt = (1ull << threadIdx.x) - 1ull;
-    for (int c = 0; c < ncls; ++c) {
-        const unsigned long long m = __ballot(cls == c);
-        if (cls == c) {
-            const int32_t p = off[(int64_t)c * nwaves + w] + __popcll(m & lt);
-            nodes[p] = (int32_t)u;
-            local_of[u] = p;
-            if (c < 2) local_in_owner[u] = p;
+    extern __shared__ int32_t class_lds[];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int B1 = P * (P + 2), nbins = B1 + P;
+    int32_t *tab = class_lds + wave * nbins;
+    const int64_t w = (int64_t)blockIdx.x * (blockDim.x >> 6) + wave;
+    if (w >= nranges) return;
+    for (int b = lane; b < nbins; b += 64) tab[b] = SCATTER ? -1 : 0;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const unsigned long long lt = (1ull << lane) - 1ull;
+    const int32_t total_local = SCATTER ? off[(int64_t)B1 * nranges] : 0;   // the pseudo-bins' positions start here
+    // position of the wavefront's next entry of bin b (second pass) or its count so far (first pass), advanced by n
+    auto take = [&](int b, int n) -> int32_t {
+        int32_t pos = 0;
+        if (lane == 0) {
+            pos = tab[b];
+            if (SCATTER && pos < 0) pos = off[(int64_t)b * nranges + w];
+            tab[b] = pos + n;
+        }
+        return __builtin_amdgcn_readfirstlane(pos);
+    };
+    for (int c = 0; c < kRange / 64; ++c) {
+        const int64_t u = w * kRange + c * 64 + lane;
+        const bool valid = u < N;
+        const int s = valid ? slab_of[u] : 0;
+        const unsigned long long nb = valid ? needed_by[u] : 0ull;
+        unsigned long long todo = wave_or(valid ? (nb | (1ull << s)) : 0ull);   // partitions some atom of the chunk is in
+        while (todo) {
+            const int q = __builtin_ctzll(todo);
+            todo &= todo - 1;
+            const int cls = valid ? node_class(s, nb, q) : -1;
+            unsigned long long rem = __ballot(cls >= 0);
+            const unsigned long long mo = __ballot(cls == 0 || cls == 1);
+            while (rem) {
+                const int cc = __builtin_amdgcn_readlane(cls, __builtin_ctzll(rem));
+                const unsigned long long m = __ballot(cls == cc);
+                rem &= ~m;
+                const int32_t pos = take(q * (P + 2) + cc, __popcll(m));
+                if (SCATTER && cls == cc) {
+                    const int32_t at = pos + __popcll(m & lt);
+                    const int32_t loc = at - off[(int64_t)(q * (P + 2)) * nranges];   // index inside partition q
+                    nodes[at] = (int32_t)u;
+                    if (cc < 2) local_in_owner[u] = loc;
+                    else ghost_local[gbase[u] + __popcll(nb & ((1ull << q) - 1ull))] = loc;
+                }
+            }
+            if (mo) {
+                const int32_t pos = take(B1 + q, __popcll(mo));
+                if (SCATTER && (cls == 0 || cls == 1)) owned_sorted[pos - total_local + __popcll(mo & lt)] = (int32_t)u;
+            }
         }
     }
-    const bool own = (cls == 0 || cls == 1);
-    const unsigned long long mo = __ballot(own);
-    if (own) {
-        const int32_t base_owned = off[(int64_t)ncls * nwaves];  // start of the "owned" pseudo class
-        owned_sorted[off[(int64_t)ncls * nwaves + w] - base_owned + __popcll(mo & lt)] = (int32_t)u;
+    if (!SCATTER) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        for (int b = lane; b < nbins; b += 64)
+            if (tab[b]) cnt[(int64_t)b * nranges + w] = tab[b];   // cnt is zero-filled beforehand
     }
 }
 
-__global__ void k_gather_markers(const int32_t *__restrict__ off, int ncls, int64_t nwaves, int64_t *out)
+__global__ void k_popcount(int64_t N, const unsigned long long *__restrict__ needed_by, int32_t *out)
 {
-    const int c = threadIdx.x;
-    if (c <= ncls) out[c] = off[(int64_t)c * nwaves];  // out[ncls] = start of the "owned" class = n_local
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < N) out[i] = __popcll(needed_by[i]);
 }
 
-// length of each local row: owned rows keep their whole global row, ghost rows
-// keep only the senders owned by partition q
-__global__ void __launch_bounds__(256)
-k_local_rowlen(int64_t n_local, int64_t n_owned, const int32_t *__restrict__ nodes,
-               const int64_t *__restrict__ row_ptr, const int32_t *__restrict__ senders,
-               const int32_t *__restrict__ slab_of, int q, int32_t *rowlen)
+// span starts of every partition: out[q * (P + 3) + k] = start of span k of partition q in the concatenated node
+// array (k = P + 2: its end); out[P * (P + 3)] = number of ghost entries
+__global__ void k_gather_markers(const int32_t *__restrict__ off, int P, int64_t nranges, const int32_t *__restrict__ gbase,
+                                 int64_t N, int64_t *out)
 {
-    const int lane = threadIdx.x & 63;   // one wavefront per row, four rows per block
-    const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (r >= n_local) return;
-    const int32_t u = nodes[r];
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    const int n = P * (P + 3);
+    if (idx < n) {
+        const int q = idx / (P + 3), k = idx % (P + 3);
+        out[idx] = off[(int64_t)(q * (P + 2) + k) * nranges];   // (q, P + 2) is bin (q + 1, 0) or the first pseudo-bin
+    } else if (idx == n) {
+        out[idx] = gbase[N];
+    }
+}
+
+// Where each partition's pieces start in the concatenated arrays (passed to kernels by value; all scalar reads).
+struct PartTab {
+    int32_t P;
+    int64_t row0[kMaxSlabs + 1];    // first node / row of partition q; row0[P] = total
+    int64_t n_owned[kMaxSlabs];
+    int64_t ghost0[kMaxSlabs + 1];  // first ghost entry
+    int64_t chunk0[kMaxSlabs + 1];  // first work-item table entry
+    int64_t n_edges[kMaxSlabs];
+};
+
+__device__ inline int part_find(const int64_t *start, int P, int64_t x)
+{
+    int p = 0;
+    for (int q = 1; q < P; ++q)
+        if (x >= start[q]) p = q;
+    return p;
+}
+
+// length of each local row: owned rows keep their whole global row, ghost rows keep only the senders owned by the
+// partition; ghost rows also record their owner and their row inside the owner.  One wavefront per row, all
+// partitions in one launch.  Partition q's lengths start at rowlen[row0[q] + q] (one closing entry per partition,
+// zero-filled beforehand, so that one scan yields every partition's n_local + 1 offsets).
+__global__ void __launch_bounds__(256)
+k_local_rowlen(PartTab T, const int32_t *__restrict__ nodes, const int64_t *__restrict__ row_ptr,
+               const int32_t *__restrict__ senders, const int32_t *__restrict__ slab_of,
+               const int32_t *__restrict__ local_in_owner, int32_t *rowlen, int32_t *ghost_owner, int32_t *ghost_src)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t x = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (x >= T.row0[T.P]) return;
+    const int q = part_find(T.row0, T.P, x);
+    const int64_t r = x - T.row0[q];
+    const int32_t u = nodes[x];
     const int64_t e0 = row_ptr[u], e1 = row_ptr[u + 1];
-    if (r < n_owned) {
-        if (lane == 0) rowlen[r] = (int32_t)(e1 - e0);
+    if (r < T.n_owned[q]) {
+        if (lane == 0) rowlen[x + q] = (int32_t)(e1 - e0);
         return;
     }
     int cnt = 0;
@@ -552,61 +634,105 @@ k_local_rowlen(int64_t n_local, int64_t n_owned, const int32_t *__restrict__ nod
         const bool keep = e < e1 && slab_of[senders[e]] == q;
         cnt += __popcll(__ballot(keep));
     }
-    if (lane == 0) rowlen[r] = cnt;
+    if (lane == 0) {
+        rowlen[x + q] = cnt;
+        const int64_t k = T.ghost0[q] + (r - T.n_owned[q]);
+        ghost_owner[k] = slab_of[u];
+        ghost_src[k] = local_in_owner[u];
+    }
 }
 
+// row_ptr of every partition, starting at 0 (row_abs holds the scan over all partitions' lengths), and per
+// partition the edges of its owned rows and of all its rows
+__global__ void k_local_rowptr(PartTab T, const int64_t *__restrict__ row_abs, int64_t *row_ptr, int64_t *sizes)
+{
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t total = T.row0[T.P] + T.P;
+    if (idx >= total) return;
+    int q = 0;
+    for (int p = 1; p < T.P; ++p)
+        if (idx >= T.row0[p] + p) q = p;
+    const int64_t first = T.row0[q] + q;
+    const int64_t base = row_abs[first];
+    row_ptr[idx] = row_abs[idx] - base;
+    if (idx == first) {
+        sizes[2 * q] = row_abs[first + T.n_owned[q]] - base;
+        sizes[2 * q + 1] = row_abs[T.row0[q + 1] + q] - base;
+    }
+}
+
+// Local CSR of every partition (one wavefront per local row).  Owned rows copy their global row with local sender
+// ids; a ghost row keeps the senders its partition owns.  Reverse-edge index: an owned sender's local row is its
+// whole global row, so the reverse edge keeps its offset inside the row; the reverse of an edge from a ghost sender
+// lies in that ghost's sub-row and is written, together with its own entry, by the wavefront that fills the sub-row
+// (which knows both positions), so no search is needed.
 __global__ void __launch_bounds__(256)
-k_local_fill(int64_t n_local, int64_t n_owned, const int32_t *__restrict__ nodes,
-             const int64_t *__restrict__ row_ptr, const int32_t *__restrict__ senders,
-             const uint32_t *__restrict__ shiftp, const float *__restrict__ d,
-             const int32_t *__restrict__ slab_of, const int32_t *__restrict__ local_of, int q,
-             const int32_t *__restrict__ gmirror, const int64_t *__restrict__ lrow_ptr, int32_t *lsenders,
+k_local_fill(PartTab T, const int32_t *__restrict__ nodes, const int64_t *__restrict__ row_ptr,
+             const int32_t *__restrict__ senders, const uint32_t *__restrict__ shiftp, const float *__restrict__ d,
+             const int32_t *__restrict__ gmirror, const int32_t *__restrict__ slab_of,
+             const unsigned long long *__restrict__ needed_by, const int32_t *__restrict__ local_in_owner,
+             const int32_t *__restrict__ gbase, const int32_t *__restrict__ ghost_local,
+             const int64_t *__restrict__ row_abs, const int64_t *__restrict__ lrow_ptr, int32_t *lsenders,
              int32_t *lrecv, uint32_t *lshiftp, float *ld, int32_t *lmirror)
 {
-    const int lane = threadIdx.x & 63;   // one wavefront per row, four rows per block
-    const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (r >= n_local) return;
-    const int32_t u = nodes[r];
+    const int lane = threadIdx.x & 63;
+    const int64_t x = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (x >= T.row0[T.P]) return;
+    const int q = part_find(T.row0, T.P, x);
+    const int64_t r = x - T.row0[q];
+    const int32_t u = nodes[x];
     const int64_t e0 = row_ptr[u], e1 = row_ptr[u + 1];
-    int64_t out = lrow_ptr[r];
-    const int64_t out_end = lrow_ptr[r + 1];
-    const bool all = r < n_owned;
-    const unsigned long long lt = (1ull << lane) - 1ull;
+    const int64_t first = T.row0[q] + q;          // the partition's first entry in row_abs / lrow_ptr
+    const int64_t ebase = row_abs[first];         // its first edge in the concatenated edge arrays
+    const int64_t *lrp = lrow_ptr + first;        // its own row_ptr
+    int64_t out = row_abs[x + q];                 // absolute position of the row's first edge
+    const bool owned = r < T.n_owned[q];
+    const unsigned long long lt = (1ull << lane) - 1ull, below = (1ull << q) - 1ull;
     for (int64_t eb = e0; eb < e1; eb += 64) {
         const int64_t e = eb + lane;
         int32_t j = 0;
-        bool keep = false;
+        bool keep = false, jown = false;
         if (e < e1) {
             j = senders[e];
-            keep = all || slab_of[j] == q;
+            jown = slab_of[j] == q;
+            keep = owned || jown;
         }
         const unsigned long long m = __ballot(keep);
         if (keep) {
             const int64_t o = out + __popcll(m & lt);
-            if (o < out_end) {
-                const int32_t jl = local_of[j];
-                lsenders[o] = jl;
-                // reverse edge: an owned sender's local row is its whole global row, so the reverse edge keeps
-                // its offset inside the row; a ghost sender's sub-row is searched afterwards (k_mirror)
-                lmirror[o] = (jl < n_owned) ? (int32_t)(lrow_ptr[jl] + ((int64_t)gmirror[e] - row_ptr[j])) : -1;
-                lshiftp[o] = shiftp[e];
-                lrecv[o] = (int32_t)r;
-                ld[o] = d[e];
+            const int32_t jl = jown ? local_in_owner[j] : ghost_local[gbase[j] + __popcll(needed_by[j] & below)];
+            lsenders[o] = jl;
+            lshiftp[o] = shiftp[e];
+            lrecv[o] = (int32_t)r;
+            ld[o] = d[e];
+            if (jown) {
+                const int32_t partner = (int32_t)(lrp[jl] + ((int64_t)gmirror[e] - row_ptr[j]));
+                lmirror[o] = partner;
+                if (!owned) lmirror[ebase + partner] = (int32_t)(o - ebase);   // the owned row's edge from this ghost
             }
         }
         out += __popcll(m);
     }
 }
 
-__global__ void k_ghost_src(int64_t n_ghost, const int32_t *__restrict__ ghost_nodes,
-                            const int32_t *__restrict__ slab_of, const int32_t *__restrict__ local_in_owner,
-                            int32_t *ghost_owner, int32_t *ghost_src)
+// work-item tables of all partitions: entry c of partition q = first local row whose first edge lies at or after
+// c * kChunkEdges; the last entry = n_local
+__global__ void k_chunk_rows_parts(PartTab T, const int64_t *__restrict__ lrow_ptr, int32_t *__restrict__ chunk_row)
 {
-    const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (k >= n_ghost) return;
-    const int32_t u = ghost_nodes[k];
-    ghost_owner[k] = slab_of[u];
-    ghost_src[k] = local_in_owner[u];
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= T.chunk0[T.P]) return;
+    const int q = part_find(T.chunk0, T.P, idx);
+    const int64_t c = idx - T.chunk0[q], n_chunks = T.chunk0[q + 1] - T.chunk0[q] - 1;
+    const int64_t n_rows = T.row0[q + 1] - T.row0[q];
+    const int64_t *rp = lrow_ptr + T.row0[q] + q;
+    int64_t lo = 0, hi = n_rows;
+    if (c == n_chunks) lo = n_rows;
+    const int64_t v = c * kChunkEdges;
+    while (lo < hi) {
+        const int64_t mid = (lo + hi) >> 1;
+        if (rp[mid] < v) lo = mid + 1; else hi = mid;
+    }
+    chunk_row[idx] = (int32_t)lo;
 }
 
 inline unsigned blocks_for(int64_t n, int threads) { return (unsigned)((n + threads - 1) / threads); }
@@ -808,7 +934,7 @@ int build_graph_impl(mlip_graph *g, const double *positions, const double *cell,
     for (SlabView &sv : g->slabs) sv.bonds.r_bond = -1.0;
     g->E = 0;
     const int64_t ncell = (int64_t)cp.nb[0] * cp.nb[1] * cp.nb[2];
-    if (!g->pinned) MLIP_HIP(hipHostMalloc(&g->pinned, 4096, hipHostMallocDefault));
+    if (!g->pinned) MLIP_HIP(hipHostMalloc(&g->pinned, 65536, hipHostMallocDefault));
 
     MLIP_TRY(g->pos.ensure((size_t)N * 3 * sizeof(double)));
     MLIP_TRY(g->species.ensure((size_t)N * sizeof(int32_t)));
@@ -930,121 +1056,160 @@ int build_graph_impl(mlip_graph *g, const double *positions, const double *cell,
     W.chunk_row = g->chunk_row.as<int32_t>();
     W.markers = {0, N, N, N};
 
-    // ------------------------------------------------------------ partition
+    // ------------------------------------------------------------ partition: all slabs in one pass
     if (P > 1) {
-        if (g->store.size() < (size_t)P) g->store.resize(P);
         if (g->slabs.size() < (size_t)P) g->slabs.resize(P);  // never shrunk: views own workspace
+        PartStore &st = g->part;
         MLIP_TRY(g->needed_by.ensure((size_t)N * 8));
-        MLIP_TRY(g->local_of.ensure((size_t)N * 4));
         MLIP_TRY(g->local_in_owner.ensure((size_t)N * 4));
+        MLIP_TRY(st.gbase.ensure((size_t)(N + 1) * 4));
         MLIP_HIP(hipMemsetAsync(g->needed_by.p, 0, (size_t)N * 8, s));
         k_needed_by<<<(unsigned)((N + 15) / 16), 256, 0, s>>>(N, g->row_ptr.as<int64_t>(), g->senders.as<int32_t>(),
                                                g->slab_of.as<int32_t>(), g->needed_by.as<unsigned long long>());
         MLIP_HIP(hipGetLastError());
-        const int ncls = P + 2;
-        const int64_t nwaves = (N + 63) / 64;
-        const int64_t nent = (int64_t)(ncls + 1) * nwaves;
+        // ghost entries per atom and their scan: where the (partition -> local index) entries of an atom start
+        k_popcount<<<blocks_for(N, 256), 256, 0, s>>>(N, g->needed_by.as<unsigned long long>(), g->counts.as<int32_t>());
+        MLIP_HIP(hipGetLastError());
+        MLIP_TRY(scan_i32_to_i32(g->counts.as<int32_t>(), st.gbase.as<int32_t>(), N, g->scan_tmp, s));
+        // class counts of every (partition, span) bin per range of kRange atoms, one flat scan
+        const int B1 = P * (P + 2), nbins = B1 + P;
+        const int64_t nranges = (N + kRange - 1) / kRange;
+        const int64_t nent = (int64_t)nbins * nranges;
+        if (nent >= ((int64_t)1 << 31)) { prof_end(g); set_error("too many atoms for this many slabs"); return MLIP_EINVAL; }
         MLIP_TRY(g->class_cnt.ensure((size_t)nent * 4));
         MLIP_TRY(g->class_off.ensure((size_t)(nent + 1) * 4));
+        MLIP_HIP(hipMemsetAsync(g->class_cnt.p, 0, (size_t)nent * 4, s));
+        const int cwaves = ((size_t)nbins * 4 * 4 > 60000) ? 2 : 4;   // wavefronts per block: each keeps a table of nbins counters in LDS
+        const size_t clds = (size_t)cwaves * nbins * 4;
+        const unsigned cblocks = (unsigned)((nranges + cwaves - 1) / cwaves);
+        k_classes<false><<<cblocks, cwaves * 64, clds, s>>>(N, P, nranges, g->slab_of.as<int32_t>(),
+                                                            g->needed_by.as<unsigned long long>(), g->class_cnt.as<int32_t>(),
+                                                            nullptr, nullptr, nullptr, nullptr, nullptr, nullptr);
+        MLIP_HIP(hipGetLastError());
+        MLIP_TRY(scan_i32_to_i32(g->class_cnt.as<int32_t>(), g->class_off.as<int32_t>(), nent, g->scan_tmp, s));
+        const int nmark = P * (P + 3) + 1;
+        MLIP_TRY(st.sizes.ensure((size_t)(nmark + 2 * P + 8) * 8));
+        k_gather_markers<<<blocks_for(nmark, 256), 256, 0, s>>>(g->class_off.as<int32_t>(), P, nranges, st.gbase.as<int32_t>(), N,
+                                                                st.sizes.as<int64_t>());
+        MLIP_HIP(hipGetLastError());
+        MLIP_HIP(hipMemcpyAsync(hp, st.sizes.p, (size_t)nmark * 8, hipMemcpyDeviceToHost, s));
+        MLIP_HIP(hipStreamSynchronize(s));   // second synchronisation: the span starts of all partitions
+        PartTab T{};
+        T.P = P;
+        int64_t n_ghost_total = 0, chunk_total = 0;
         for (int q = 0; q < P; ++q) {
-            SlabStore &st = g->store[q];
             SlabView &v = g->slabs[q];
-            k_class_count<<<(unsigned)nwaves, 64, 0, s>>>(N, g->slab_of.as<int32_t>(),
-                                                          g->needed_by.as<unsigned long long>(), q, ncls, nwaves,
-                                                          g->class_cnt.as<int32_t>());
-            MLIP_HIP(hipGetLastError());
-            MLIP_TRY(scan_i32_to_i32(g->class_cnt.as<int32_t>(), g->class_off.as<int32_t>(), nent, g->scan_tmp, s));
-            int64_t *mk = g->small.as<int64_t>() + 16;
-            k_gather_markers<<<1, 128, 0, s>>>(g->class_off.as<int32_t>(), ncls, nwaves, mk);
-            MLIP_HIP(hipGetLastError());
-            MLIP_HIP(hipMemcpyAsync(hp, mk, (size_t)(ncls + 1) * 8, hipMemcpyDeviceToHost, s));
-            MLIP_HIP(hipStreamSynchronize(s));
-            v.markers.assign(hp, hp + ncls + 1);  // P + 3 entries
-            v.n_pure = hp[1];
-            v.n_owned = hp[2];
+            const int64_t *mk = hp + (size_t)q * (P + 3);
+            v.markers.resize(P + 3);
+            for (int k = 0; k < P + 3; ++k) v.markers[k] = mk[k] - mk[0];
+            v.n_pure = v.markers[1];
+            v.n_owned = v.markers[2];
             v.n_border = v.n_owned - v.n_pure;
-            v.n_local = hp[ncls];
+            v.n_local = v.markers[P + 2];
             v.n_ghost = v.n_local - v.n_owned;
-            const size_t nl = (size_t)std::max<int64_t>(v.n_local, 1);
-            MLIP_TRY(st.nodes.ensure(nl * 4));
-            MLIP_TRY(st.owned_sorted.ensure((size_t)std::max<int64_t>(v.n_owned, 1) * 4));
-            MLIP_TRY(st.rowlen.ensure((nl + 1) * 4));
-            MLIP_TRY(st.row_ptr.ensure((nl + 1) * 8));
-            MLIP_TRY(st.ghost_owner.ensure((size_t)std::max<int64_t>(v.n_ghost, 1) * 4));
-            MLIP_TRY(st.ghost_src.ensure((size_t)std::max<int64_t>(v.n_ghost, 1) * 4));
-            k_class_scatter<<<(unsigned)nwaves, 64, 0, s>>>(
-                N, g->slab_of.as<int32_t>(), g->needed_by.as<unsigned long long>(), q, ncls, nwaves,
-                g->class_off.as<int32_t>(), st.nodes.as<int32_t>(), st.owned_sorted.as<int32_t>(),
-                g->local_of.as<int32_t>(), g->local_in_owner.as<int32_t>());
-            MLIP_HIP(hipGetLastError());
-            if (v.n_local > 0) {
-                k_local_rowlen<<<(unsigned)((v.n_local + 3) / 4), 256, 0, s>>>(v.n_local, v.n_owned, st.nodes.as<int32_t>(),
-                                                                  g->row_ptr.as<int64_t>(), g->senders.as<int32_t>(),
-                                                                  g->slab_of.as<int32_t>(), q, st.rowlen.as<int32_t>());
-                MLIP_HIP(hipGetLastError());
-            }
-            MLIP_TRY(scan_i32_to_i64(st.rowlen.as<int32_t>(), st.row_ptr.as<int64_t>(), v.n_local, g->scan_tmp, s));
-            MLIP_HIP(hipMemcpyAsync(hp, st.row_ptr.as<int64_t>() + v.n_owned, 8, hipMemcpyDeviceToHost, s));
-            MLIP_HIP(hipMemcpyAsync(hp + 1, st.row_ptr.as<int64_t>() + v.n_local, 8, hipMemcpyDeviceToHost, s));
-            MLIP_HIP(hipStreamSynchronize(s));
-            v.n_edges_owned = hp[0];
-            v.n_edges = hp[1];
-            const size_t ne = (size_t)std::max<int64_t>(v.n_edges, 1);
-            MLIP_TRY(st.senders.ensure(ne * 4));
-            MLIP_TRY(st.shiftp.ensure(ne * 4));
-            MLIP_TRY(st.recv.ensure(ne * 4));
-            MLIP_TRY(st.mirror.ensure(ne * 4));
-            MLIP_TRY(st.d.ensure(ne * 4));
-            if (v.n_local > 0) {
-                k_local_fill<<<(unsigned)((v.n_local + 3) / 4), 256, 0, s>>>(
-                    v.n_local, v.n_owned, st.nodes.as<int32_t>(), g->row_ptr.as<int64_t>(), g->senders.as<int32_t>(),
-                    g->shiftp.as<uint32_t>(), g->d.as<float>(), g->slab_of.as<int32_t>(), g->local_of.as<int32_t>(), q,
-                    g->mirror.as<int32_t>(), st.row_ptr.as<int64_t>(), st.senders.as<int32_t>(), st.recv.as<int32_t>(),
-                    st.shiftp.as<uint32_t>(), st.d.as<float>(), st.mirror.as<int32_t>());
-                MLIP_HIP(hipGetLastError());
-            }
-            v.nodes = st.nodes.as<int32_t>();
-            v.row_ptr = st.row_ptr.as<int64_t>();
-            v.senders = st.senders.as<int32_t>();
-            v.shiftp = st.shiftp.as<uint32_t>();
-            v.recv = st.recv.as<int32_t>();
-            v.mirror = st.mirror.as<int32_t>();
-            if (v.n_edges_owned > 0 && v.n_ghost > 0) {
-                // the local edge set (owned rows + ghost sub-rows) is symmetric as well; what is left to find
-                // are the reverse edges of owned rows' edges from ghost senders, inside the ghost sub-rows
-                k_mirror<false><<<blocks_for(v.n_edges_owned, 256), 256, 0, s>>>(
-                    v.n_edges_owned, st.row_ptr.as<int64_t>(), st.senders.as<int32_t>(), st.recv.as<int32_t>(),
-                    st.shiftp.as<uint32_t>(), st.nodes.as<int32_t>(), (int32_t)v.n_owned, st.mirror.as<int32_t>(), err);
-                MLIP_HIP(hipGetLastError());
-            }
-            v.d = st.d.as<float>();
-            {
-                const int64_t nc = chunks_of(v.n_edges);
-                MLIP_TRY(st.chunk_row.ensure((size_t)(nc + 1) * 4));
-                k_chunk_rows<<<blocks_for(nc + 1, 256), 256, 0, s>>>(v.n_local, nc, st.row_ptr.as<int64_t>(),
-                                                                      st.chunk_row.as<int32_t>());
-                MLIP_HIP(hipGetLastError());
-                v.chunk_row = st.chunk_row.as<int32_t>();
-            }
-            v.ghost_owner = st.ghost_owner.as<int32_t>();
-            v.ghost_src = st.ghost_src.as<int32_t>();
+            T.row0[q] = mk[0];
+            T.n_owned[q] = v.n_owned;
+            T.ghost0[q] = n_ghost_total;
+            n_ghost_total += v.n_ghost;
         }
+        const int64_t TL = hp[(size_t)(P - 1) * (P + 3) + P + 2];   // all partitions' nodes
+        T.row0[P] = TL;
+        T.ghost0[P] = n_ghost_total;
+        if (n_ghost_total != hp[nmark - 1] || TL != N + n_ghost_total) {
+            prof_end(g);
+            set_error("internal error: inconsistent partition sizes");
+            return MLIP_EHIP;
+        }
+        if (TL + N >= ((int64_t)1 << 31)) { prof_end(g); set_error("more than 2^31 local nodes over all slabs"); return MLIP_EINVAL; }
+        const size_t ng1 = (size_t)std::max<int64_t>(n_ghost_total, 1);
+        MLIP_TRY(st.nodes.ensure((size_t)TL * 4));
+        MLIP_TRY(st.owned_sorted.ensure((size_t)N * 4));
+        MLIP_TRY(st.ghost_local.ensure(ng1 * 4));
+        MLIP_TRY(st.ghost_owner.ensure(ng1 * 4));
+        MLIP_TRY(st.ghost_src.ensure(ng1 * 4));
+        MLIP_TRY(st.rowlen.ensure((size_t)(TL + P + 1) * 4));
+        MLIP_TRY(st.row_abs.ensure((size_t)(TL + P + 1) * 8));
+        MLIP_TRY(st.row_ptr.ensure((size_t)(TL + P + 1) * 8));
+        k_classes<true><<<cblocks, cwaves * 64, clds, s>>>(N, P, nranges, g->slab_of.as<int32_t>(),
+                                                           g->needed_by.as<unsigned long long>(), nullptr,
+                                                           g->class_off.as<int32_t>(), st.gbase.as<int32_t>(),
+                                                           st.nodes.as<int32_t>(), st.owned_sorted.as<int32_t>(),
+                                                           g->local_in_owner.as<int32_t>(), st.ghost_local.as<int32_t>());
+        MLIP_HIP(hipGetLastError());
+        MLIP_HIP(hipMemsetAsync(st.rowlen.p, 0, (size_t)(TL + P + 1) * 4, s));
+        k_local_rowlen<<<(unsigned)((TL + 3) / 4), 256, 0, s>>>(T, st.nodes.as<int32_t>(), g->row_ptr.as<int64_t>(),
+                                                                g->senders.as<int32_t>(), g->slab_of.as<int32_t>(),
+                                                                g->local_in_owner.as<int32_t>(), st.rowlen.as<int32_t>(),
+                                                                st.ghost_owner.as<int32_t>(), st.ghost_src.as<int32_t>());
+        MLIP_HIP(hipGetLastError());
+        MLIP_TRY(scan_i32_to_i64(st.rowlen.as<int32_t>(), st.row_abs.as<int64_t>(), TL + P, g->scan_tmp, s));
+        int64_t *dsz = st.sizes.as<int64_t>() + nmark;
+        k_local_rowptr<<<blocks_for(TL + P, 256), 256, 0, s>>>(T, st.row_abs.as<int64_t>(), st.row_ptr.as<int64_t>(), dsz);
+        MLIP_HIP(hipGetLastError());
+        MLIP_HIP(hipMemcpyAsync(hp, dsz, (size_t)2 * P * 8, hipMemcpyDeviceToHost, s));
+        MLIP_HIP(hipMemcpyAsync(hp + 2 * P, err, 4, hipMemcpyDeviceToHost, s));
+        MLIP_HIP(hipStreamSynchronize(s));   // third and last synchronisation: the partitions' edge counts, the error flags
+        if (*reinterpret_cast<int32_t *>(hp + 2 * P) & ERR_MIRROR) {
+            prof_end(g);
+            set_error("internal error: an edge without its reverse edge");
+            return MLIP_EHIP;
+        }
+        int64_t TE = 0;
+        std::vector<int64_t> ebase(P + 1);
         for (int q = 0; q < P; ++q) {
             SlabView &v = g->slabs[q];
-            if (v.n_ghost > 0) {
-                k_ghost_src<<<blocks_for(v.n_ghost, 256), 256, 0, s>>>(
-                    v.n_ghost, v.nodes + v.n_owned, g->slab_of.as<int32_t>(), g->local_in_owner.as<int32_t>(),
-                    g->store[q].ghost_owner.as<int32_t>(), g->store[q].ghost_src.as<int32_t>());
-                MLIP_HIP(hipGetLastError());
-            }
+            v.n_edges_owned = hp[2 * q];
+            v.n_edges = hp[2 * q + 1];
+            ebase[q] = TE;
+            TE += v.n_edges;
+            T.n_edges[q] = v.n_edges;
+            T.chunk0[q] = chunk_total;
+            chunk_total += chunks_of(v.n_edges) + 1;
         }
-    }
-    prof_end(g);
-    MLIP_HIP(hipMemcpyAsync(hp, err, 4, hipMemcpyDeviceToHost, s));
-    MLIP_HIP(hipStreamSynchronize(s));
-    if (*reinterpret_cast<int32_t *>(hp) & ERR_MIRROR) {
-        set_error("internal error: an edge without its reverse edge");
-        return MLIP_EHIP;
+        ebase[P] = TE;
+        T.chunk0[P] = chunk_total;
+        if (TE >= ((int64_t)1 << 31)) { prof_end(g); set_error("more than 2^31 local edges over all slabs"); return MLIP_EINVAL; }
+        const size_t ne = (size_t)std::max<int64_t>(TE, 1);
+        MLIP_TRY(st.senders.ensure(ne * 4));
+        MLIP_TRY(st.shiftp.ensure(ne * 4));
+        MLIP_TRY(st.recv.ensure(ne * 4));
+        MLIP_TRY(st.mirror.ensure(ne * 4));
+        MLIP_TRY(st.d.ensure(ne * 4));
+        MLIP_TRY(st.chunk_row.ensure((size_t)chunk_total * 4));
+        if (TL > 0) {
+            k_local_fill<<<(unsigned)((TL + 3) / 4), 256, 0, s>>>(
+                T, st.nodes.as<int32_t>(), g->row_ptr.as<int64_t>(), g->senders.as<int32_t>(), g->shiftp.as<uint32_t>(),
+                g->d.as<float>(), g->mirror.as<int32_t>(), g->slab_of.as<int32_t>(), g->needed_by.as<unsigned long long>(),
+                g->local_in_owner.as<int32_t>(), st.gbase.as<int32_t>(), st.ghost_local.as<int32_t>(),
+                st.row_abs.as<int64_t>(), st.row_ptr.as<int64_t>(), st.senders.as<int32_t>(), st.recv.as<int32_t>(),
+                st.shiftp.as<uint32_t>(), st.d.as<float>(), st.mirror.as<int32_t>());
+            MLIP_HIP(hipGetLastError());
+        }
+        k_chunk_rows_parts<<<blocks_for(chunk_total, 256), 256, 0, s>>>(T, st.row_ptr.as<int64_t>(), st.chunk_row.as<int32_t>());
+        MLIP_HIP(hipGetLastError());
+        for (int q = 0; q < P; ++q) {
+            SlabView &v = g->slabs[q];
+            v.nodes = st.nodes.as<int32_t>() + T.row0[q];
+            v.owned_sorted = st.owned_sorted.as<int32_t>() + (T.row0[q] - T.ghost0[q]);   // owned atoms before partition q
+            v.row_ptr = st.row_ptr.as<int64_t>() + T.row0[q] + q;
+            v.senders = st.senders.as<int32_t>() + ebase[q];
+            v.shiftp = st.shiftp.as<uint32_t>() + ebase[q];
+            v.recv = st.recv.as<int32_t>() + ebase[q];
+            v.mirror = st.mirror.as<int32_t>() + ebase[q];
+            v.d = st.d.as<float>() + ebase[q];
+            v.chunk_row = st.chunk_row.as<int32_t>() + T.chunk0[q];
+            v.ghost_owner = st.ghost_owner.as<int32_t>() + T.ghost0[q];
+            v.ghost_src = st.ghost_src.as<int32_t>() + T.ghost0[q];
+        }
+        prof_end(g);
+    } else {
+        prof_end(g);
+        MLIP_HIP(hipMemcpyAsync(hp, err, 4, hipMemcpyDeviceToHost, s));
+        MLIP_HIP(hipStreamSynchronize(s));
+        if (*reinterpret_cast<int32_t *>(hp) & ERR_MIRROR) {
+            set_error("internal error: an edge without its reverse edge");
+            return MLIP_EHIP;
+        }
     }
     g->N = N;
     g->E = E;

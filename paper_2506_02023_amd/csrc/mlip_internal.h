@@ -126,6 +126,7 @@ struct SlabView {
     const int32_t *chunk_row = nullptr;    // [chunks_of(n_edges) + 1] first row of every work item, then n_local
     const int32_t *ghost_owner = nullptr;  // [n_ghost] owning slab
     const int32_t *ghost_src = nullptr;    // [n_ghost] local index inside the owner
+    const int32_t *owned_sorted = nullptr; // [n_owned] owned atoms, ascending global id
     std::vector<int64_t> markers;          // host, P + 3
     // model workspace (sized in mlip_forward)
     DevBuf h, hbar, abar, gbar, eps, dsum, floc, g, a, wst;  // g and a hold L slices each, wst L - 1
@@ -133,8 +134,15 @@ struct SlabView {
     BondGraph bonds;
 };
 
-struct SlabStore {  // device arrays owned per slab
-    DevBuf nodes, row_ptr, senders, recv, mirror, shiftp, d, chunk_row, ghost_owner, ghost_src, owned_sorted, rowlen;
+// Device arrays of all partitions, each array holding the partitions' pieces one after another (one allocation and
+// one kernel launch per step of the partition build instead of one per slab).
+struct PartStore {
+    DevBuf nodes, owned_sorted, ghost_owner, ghost_src;   // i32, pieces of n_local / n_owned / n_ghost entries
+    DevBuf rowlen, row_abs, row_ptr;                      // i32 / i64 / i64, pieces of n_local + 1 entries
+    DevBuf senders, recv, mirror, shiftp, d;              // pieces of n_edges entries
+    DevBuf chunk_row;                                     // i32, pieces of chunks_of(n_edges) + 1 entries
+    DevBuf gbase, ghost_local;                            // i32 [N + 1] scan of popcount(needed_by); i32 [sum n_ghost]
+    DevBuf sizes;                                         // i64 small read-back area
 };
 
 enum { kMaxSlabs = 64, kMaxEvents = 4096 };
@@ -176,7 +184,7 @@ struct mlip_graph {
     mlip::DevBuf row_ptr, senders, recv, mirror, shiftp, d, chunk_row;
     // partition
     mlip::DevBuf slab_of, needed_by, local_of, local_in_owner, class_cnt, class_off;
-    std::vector<mlip::SlabStore> store;
+    mlip::PartStore part;
     std::vector<mlip::SlabView> slabs;  // P views (empty when P == 1)
     mlip::SlabView whole;
     // forward scratch shared by all views

@@ -257,7 +257,7 @@ __global__ void k_neighbours(int64_t N, CellParams cp, const int32_t *__restrict
                              const uint32_t *__restrict__ swrap, const int32_t *__restrict__ cell_of,
                              int32_t *counts, const int64_t *__restrict__ row_ptr, uint64_t *keys, int32_t *err)
 {
-    const int64_t s = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t s = (int64_t)xcd_block() * blockDim.x + threadIdx.x;
     if (s >= N) return;
     const int32_t i = sid[s];
     const double xi = sx[s], yi = sy[s], zi = sz[s];
@@ -345,7 +345,8 @@ k_sort_rows(int64_t N, CellParams cp, const double *__restrict__ pos, const int6
             float *d)
 {
     __shared__ uint64_t lds[kRowLds];
-    const int64_t i = blockIdx.x;
+    const int64_t i = xcd_block();
+    if (i >= N) return;   // (whole block: the grid is rounded up to a multiple of 8)
     const int lane = threadIdx.x;
     const int64_t base = row_ptr[i];
     const int64_t n = row_ptr[i + 1] - base;
@@ -409,7 +410,7 @@ __global__ void k_mirror(int64_t E, const int64_t *__restrict__ row_ptr, const i
                          const int32_t *__restrict__ nodes, int32_t min_sender, int32_t *__restrict__ mirror,
                          int32_t *err)
 {
-    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t e = (int64_t)xcd_block() * blockDim.x + threadIdx.x;
     if (e >= E) return;
     const int32_t r = recv[e], sd = senders[e];
     if (sd < min_sender) return;
@@ -462,7 +463,7 @@ __global__ void __launch_bounds__(256)
 k_needed_by(int64_t N, const int64_t *__restrict__ row_ptr, const int32_t *__restrict__ senders,
             const int32_t *__restrict__ slab_of, unsigned long long *needed_by)
 {
-    const int64_t i = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
+    const int64_t i = (int64_t)xcd_block() * 16 + (threadIdx.x >> 4);
     if (i >= N) return;
     const int si = slab_of[i];
     const int64_t e1 = row_ptr[i + 1];
@@ -493,6 +494,13 @@ __device__ inline int node_class(int s, unsigned long long nb, int q)
 // cnt[bin][range] turns the counts into positions.
 constexpr int kRange = 512;
 
+// What the local-CSR fill needs to know about a sender, in one 16-byte record per atom: its owner partition, its
+// row there, and the distance from a position in its global row to the same position in its owner's local row.
+struct __attribute__((aligned(16))) OwnRec {
+    int32_t local, slab;
+    int64_t delta;
+};
+
 __device__ inline unsigned long long wave_or(unsigned long long v)
 {
 #pragma unroll
@@ -504,7 +512,7 @@ template <bool SCATTER>
 __global__ void __launch_bounds__(256)
 k_classes(int64_t N, int P, int64_t nranges, const int32_t *__restrict__ slab_of,
           const unsigned long long *__restrict__ needed_by, int32_t *cnt, const int32_t *__restrict__ off,
-          const int32_t *__restrict__ gbase, int32_t *nodes, int32_t *owned_sorted, int32_t *local_in_owner,
+          const int32_t *__restrict__ gbase, int32_t *nodes, int32_t *owned_sorted, OwnRec *own_rec,
           int32_t *ghost_local)
 {
     extern __shared__ int32_t class_lds[];
@@ -550,7 +558,7 @@ k_classes(int64_t N, int P, int64_t nranges, const int32_t *__restrict__ slab_of
                     const int32_t at = pos + __popcll(m & lt);
                     const int32_t loc = at - off[(int64_t)(q * (P + 2)) * nranges];   // index inside partition q
                     nodes[at] = (int32_t)u;
-                    if (cc < 2) local_in_owner[u] = loc;
+                    if (cc < 2) { own_rec[u].local = loc; own_rec[u].slab = q; }
                     else ghost_local[gbase[u] + __popcll(nb & ((1ull << q) - 1ull))] = loc;
                 }
             }
@@ -615,10 +623,10 @@ __device__ inline int part_find(const int64_t *start, int P, int64_t x)
 __global__ void __launch_bounds__(256)
 k_local_rowlen(PartTab T, const int32_t *__restrict__ nodes, const int64_t *__restrict__ row_ptr,
                const int32_t *__restrict__ senders, const int32_t *__restrict__ slab_of,
-               const int32_t *__restrict__ local_in_owner, int32_t *rowlen, int32_t *ghost_owner, int32_t *ghost_src)
+               const OwnRec *__restrict__ own_rec, int32_t *rowlen, int32_t *ghost_owner, int32_t *ghost_src)
 {
     const int lane = threadIdx.x & 63;
-    const int64_t x = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t x = (int64_t)xcd_block() * 4 + (threadIdx.x >> 6);
     if (x >= T.row0[T.P]) return;
     const int q = part_find(T.row0, T.P, x);
     const int64_t r = x - T.row0[q];
@@ -637,14 +645,15 @@ k_local_rowlen(PartTab T, const int32_t *__restrict__ nodes, const int64_t *__re
     if (lane == 0) {
         rowlen[x + q] = cnt;
         const int64_t k = T.ghost0[q] + (r - T.n_owned[q]);
-        ghost_owner[k] = slab_of[u];
-        ghost_src[k] = local_in_owner[u];
+        ghost_owner[k] = own_rec[u].slab;
+        ghost_src[k] = own_rec[u].local;
     }
 }
 
 // row_ptr of every partition, starting at 0 (row_abs holds the scan over all partitions' lengths), and per
 // partition the edges of its owned rows and of all its rows
-__global__ void k_local_rowptr(PartTab T, const int64_t *__restrict__ row_abs, int64_t *row_ptr, int64_t *sizes)
+__global__ void k_local_rowptr(PartTab T, const int64_t *__restrict__ row_abs, const int32_t *__restrict__ nodes,
+                               const int64_t *__restrict__ grow_ptr, int64_t *row_ptr, OwnRec *own_rec, int64_t *sizes)
 {
     const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int64_t total = T.row0[T.P] + T.P;
@@ -655,6 +664,10 @@ __global__ void k_local_rowptr(PartTab T, const int64_t *__restrict__ row_abs, i
     const int64_t first = T.row0[q] + q;
     const int64_t base = row_abs[first];
     row_ptr[idx] = row_abs[idx] - base;
+    if (idx - first < T.n_owned[q]) {   // an owned row: where its edges went, relative to its global row
+        const int32_t u = nodes[idx - q];
+        own_rec[u].delta = (row_abs[idx] - base) - grow_ptr[u];
+    }
     if (idx == first) {
         sizes[2 * q] = row_abs[first + T.n_owned[q]] - base;
         sizes[2 * q + 1] = row_abs[T.row0[q + 1] + q] - base;
@@ -669,14 +682,13 @@ __global__ void k_local_rowptr(PartTab T, const int64_t *__restrict__ row_abs, i
 __global__ void __launch_bounds__(256)
 k_local_fill(PartTab T, const int32_t *__restrict__ nodes, const int64_t *__restrict__ row_ptr,
              const int32_t *__restrict__ senders, const uint32_t *__restrict__ shiftp, const float *__restrict__ d,
-             const int32_t *__restrict__ gmirror, const int32_t *__restrict__ slab_of,
-             const unsigned long long *__restrict__ needed_by, const int32_t *__restrict__ local_in_owner,
-             const int32_t *__restrict__ gbase, const int32_t *__restrict__ ghost_local,
-             const int64_t *__restrict__ row_abs, const int64_t *__restrict__ lrow_ptr, int32_t *lsenders,
+             const int32_t *__restrict__ gmirror, const unsigned long long *__restrict__ needed_by,
+             const OwnRec *__restrict__ own_rec, const int32_t *__restrict__ gbase,
+             const int32_t *__restrict__ ghost_local, const int64_t *__restrict__ row_abs, int32_t *lsenders,
              int32_t *lrecv, uint32_t *lshiftp, float *ld, int32_t *lmirror)
 {
     const int lane = threadIdx.x & 63;
-    const int64_t x = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t x = (int64_t)xcd_block() * 4 + (threadIdx.x >> 6);
     if (x >= T.row0[T.P]) return;
     const int q = part_find(T.row0, T.P, x);
     const int64_t r = x - T.row0[q];
@@ -684,7 +696,6 @@ k_local_fill(PartTab T, const int32_t *__restrict__ nodes, const int64_t *__rest
     const int64_t e0 = row_ptr[u], e1 = row_ptr[u + 1];
     const int64_t first = T.row0[q] + q;          // the partition's first entry in row_abs / lrow_ptr
     const int64_t ebase = row_abs[first];         // its first edge in the concatenated edge arrays
-    const int64_t *lrp = lrow_ptr + first;        // its own row_ptr
     int64_t out = row_abs[x + q];                 // absolute position of the row's first edge
     const bool owned = r < T.n_owned[q];
     const unsigned long long lt = (1ull << lane) - 1ull, below = (1ull << q) - 1ull;
@@ -692,21 +703,23 @@ k_local_fill(PartTab T, const int32_t *__restrict__ nodes, const int64_t *__rest
         const int64_t e = eb + lane;
         int32_t j = 0;
         bool keep = false, jown = false;
+        OwnRec rec{};
         if (e < e1) {
             j = senders[e];
-            jown = slab_of[j] == q;
+            rec = own_rec[j];
+            jown = rec.slab == q;
             keep = owned || jown;
         }
         const unsigned long long m = __ballot(keep);
         if (keep) {
             const int64_t o = out + __popcll(m & lt);
-            const int32_t jl = jown ? local_in_owner[j] : ghost_local[gbase[j] + __popcll(needed_by[j] & below)];
+            const int32_t jl = jown ? rec.local : ghost_local[gbase[j] + __popcll(needed_by[j] & below)];
             lsenders[o] = jl;
             lshiftp[o] = shiftp[e];
             lrecv[o] = (int32_t)r;
             ld[o] = d[e];
             if (jown) {
-                const int32_t partner = (int32_t)(lrp[jl] + ((int64_t)gmirror[e] - row_ptr[j]));
+                const int32_t partner = (int32_t)((int64_t)gmirror[e] + rec.delta);
                 lmirror[o] = partner;
                 if (!owned) lmirror[ebase + partner] = (int32_t)(o - ebase);   // the owned row's edge from this ghost
             }
@@ -976,7 +989,7 @@ int build_graph_impl(mlip_graph *g, const double *positions, const double *cell,
     // more than 8 GB; the sort then reads the staging rows and the second neighbour pass is not needed
     const bool use_stage = (size_t)N * kStage * 8 <= ((size_t)8 << 30);
     if (use_stage) MLIP_TRY(g->stage.ensure((size_t)N * kStage * 8));
-    k_neighbours<false><<<blocks_for(N, 128), 128, 0, s>>>(
+    k_neighbours<false><<<grid8(blocks_for(N, 128)), 128, 0, s>>>(
         N, cp, g->cell_start.as<int32_t>(), g->sid.as<int32_t>(), g->sx.as<double>(), g->sy.as<double>(),
         g->sz.as<double>(), g->swrap.as<uint32_t>(), g->cell_of.as<int32_t>(), g->counts.as<int32_t>(), nullptr,
         use_stage ? g->stage.as<uint64_t>() : nullptr, err);
@@ -1016,20 +1029,20 @@ int build_graph_impl(mlip_graph *g, const double *positions, const double *cell,
     MLIP_TRY(g->mirror.ensure(Ecap * 4));
     MLIP_TRY(g->d.ensure(Ecap * 4));
     if (!staged) {
-        k_neighbours<true><<<blocks_for(N, 128), 128, 0, s>>>(
+        k_neighbours<true><<<grid8(blocks_for(N, 128)), 128, 0, s>>>(
             N, cp, g->cell_start.as<int32_t>(), g->sid.as<int32_t>(), g->sx.as<double>(), g->sy.as<double>(),
             g->sz.as<double>(), g->swrap.as<uint32_t>(), g->cell_of.as<int32_t>(), nullptr, g->row_ptr.as<int64_t>(),
             g->keys.as<uint64_t>(), err);
         MLIP_HIP(hipGetLastError());
     }
-    k_sort_rows<<<(unsigned)N, 64, 0, s>>>(N, cp, pos, g->row_ptr.as<int64_t>(),
+    k_sort_rows<<<grid8(N), 64, 0, s>>>(N, cp, pos, g->row_ptr.as<int64_t>(),
                                            staged ? g->stage.as<uint64_t>() : g->keys.as<uint64_t>(), staged ? 1 : 0,
                                            g->senders.as<int32_t>(), g->recv.as<int32_t>(), g->shiftp.as<uint32_t>(),
                                            g->d.as<float>());
     MLIP_HIP(hipGetLastError());
 
     if (E > 0) {
-        k_mirror<true><<<blocks_for(E, 256), 256, 0, s>>>(E, g->row_ptr.as<int64_t>(), g->senders.as<int32_t>(),
+        k_mirror<true><<<grid8(blocks_for(E, 256)), 256, 0, s>>>(E, g->row_ptr.as<int64_t>(), g->senders.as<int32_t>(),
                                                           g->recv.as<int32_t>(), g->shiftp.as<uint32_t>(), nullptr, 0,
                                                           g->mirror.as<int32_t>(), err);
         MLIP_HIP(hipGetLastError());
@@ -1061,10 +1074,10 @@ int build_graph_impl(mlip_graph *g, const double *positions, const double *cell,
         if (g->slabs.size() < (size_t)P) g->slabs.resize(P);  // never shrunk: views own workspace
         PartStore &st = g->part;
         MLIP_TRY(g->needed_by.ensure((size_t)N * 8));
-        MLIP_TRY(g->local_in_owner.ensure((size_t)N * 4));
+        MLIP_TRY(g->local_in_owner.ensure((size_t)N * sizeof(OwnRec)));   // one record per atom
         MLIP_TRY(st.gbase.ensure((size_t)(N + 1) * 4));
         MLIP_HIP(hipMemsetAsync(g->needed_by.p, 0, (size_t)N * 8, s));
-        k_needed_by<<<(unsigned)((N + 15) / 16), 256, 0, s>>>(N, g->row_ptr.as<int64_t>(), g->senders.as<int32_t>(),
+        k_needed_by<<<grid8((N + 15) / 16), 256, 0, s>>>(N, g->row_ptr.as<int64_t>(), g->senders.as<int32_t>(),
                                                g->slab_of.as<int32_t>(), g->needed_by.as<unsigned long long>());
         MLIP_HIP(hipGetLastError());
         // ghost entries per atom and their scan: where the (partition -> local index) entries of an atom start
@@ -1134,17 +1147,19 @@ int build_graph_impl(mlip_graph *g, const double *positions, const double *cell,
                                                            g->needed_by.as<unsigned long long>(), nullptr,
                                                            g->class_off.as<int32_t>(), st.gbase.as<int32_t>(),
                                                            st.nodes.as<int32_t>(), st.owned_sorted.as<int32_t>(),
-                                                           g->local_in_owner.as<int32_t>(), st.ghost_local.as<int32_t>());
+                                                           g->local_in_owner.as<OwnRec>(), st.ghost_local.as<int32_t>());
         MLIP_HIP(hipGetLastError());
         MLIP_HIP(hipMemsetAsync(st.rowlen.p, 0, (size_t)(TL + P + 1) * 4, s));
-        k_local_rowlen<<<(unsigned)((TL + 3) / 4), 256, 0, s>>>(T, st.nodes.as<int32_t>(), g->row_ptr.as<int64_t>(),
+        k_local_rowlen<<<grid8((TL + 3) / 4), 256, 0, s>>>(T, st.nodes.as<int32_t>(), g->row_ptr.as<int64_t>(),
                                                                 g->senders.as<int32_t>(), g->slab_of.as<int32_t>(),
-                                                                g->local_in_owner.as<int32_t>(), st.rowlen.as<int32_t>(),
+                                                                g->local_in_owner.as<OwnRec>(), st.rowlen.as<int32_t>(),
                                                                 st.ghost_owner.as<int32_t>(), st.ghost_src.as<int32_t>());
         MLIP_HIP(hipGetLastError());
         MLIP_TRY(scan_i32_to_i64(st.rowlen.as<int32_t>(), st.row_abs.as<int64_t>(), TL + P, g->scan_tmp, s));
         int64_t *dsz = st.sizes.as<int64_t>() + nmark;
-        k_local_rowptr<<<blocks_for(TL + P, 256), 256, 0, s>>>(T, st.row_abs.as<int64_t>(), st.row_ptr.as<int64_t>(), dsz);
+        k_local_rowptr<<<blocks_for(TL + P, 256), 256, 0, s>>>(T, st.row_abs.as<int64_t>(), st.nodes.as<int32_t>(),
+                                                               g->row_ptr.as<int64_t>(), st.row_ptr.as<int64_t>(),
+                                                               g->local_in_owner.as<OwnRec>(), dsz);
         MLIP_HIP(hipGetLastError());
         MLIP_HIP(hipMemcpyAsync(hp, dsz, (size_t)2 * P * 8, hipMemcpyDeviceToHost, s));
         MLIP_HIP(hipMemcpyAsync(hp + 2 * P, err, 4, hipMemcpyDeviceToHost, s));
@@ -1177,11 +1192,11 @@ int build_graph_impl(mlip_graph *g, const double *positions, const double *cell,
         MLIP_TRY(st.d.ensure(ne * 4));
         MLIP_TRY(st.chunk_row.ensure((size_t)chunk_total * 4));
         if (TL > 0) {
-            k_local_fill<<<(unsigned)((TL + 3) / 4), 256, 0, s>>>(
+            k_local_fill<<<grid8((TL + 3) / 4), 256, 0, s>>>(
                 T, st.nodes.as<int32_t>(), g->row_ptr.as<int64_t>(), g->senders.as<int32_t>(), g->shiftp.as<uint32_t>(),
-                g->d.as<float>(), g->mirror.as<int32_t>(), g->slab_of.as<int32_t>(), g->needed_by.as<unsigned long long>(),
-                g->local_in_owner.as<int32_t>(), st.gbase.as<int32_t>(), st.ghost_local.as<int32_t>(),
-                st.row_abs.as<int64_t>(), st.row_ptr.as<int64_t>(), st.senders.as<int32_t>(), st.recv.as<int32_t>(),
+                g->d.as<float>(), g->mirror.as<int32_t>(), g->needed_by.as<unsigned long long>(),
+                g->local_in_owner.as<OwnRec>(), st.gbase.as<int32_t>(), st.ghost_local.as<int32_t>(),
+                st.row_abs.as<int64_t>(), st.senders.as<int32_t>(), st.recv.as<int32_t>(),
                 st.shiftp.as<uint32_t>(), st.d.as<float>(), st.mirror.as<int32_t>());
             MLIP_HIP(hipGetLastError());
         }

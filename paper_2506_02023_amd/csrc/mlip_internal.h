@@ -82,6 +82,16 @@ struct CellParams {
     int n_slabs;
 };
 
+// Workgroups are dealt to the 8 XCDs round-robin (workgroup b runs on XCD b mod 8), and every XCD has its own L2.
+// A kernel whose neighbouring blocks gather overlapping data (neighbour rows, candidate cells) takes its logical
+// block index from xcd_block() instead of blockIdx.x: every XCD then works on one contiguous eighth of the blocks
+// and its L2 holds that eighth's data, instead of all eight L2s holding the same lines.  The grid must be a
+// multiple of 8 (grid8) and the kernel must bounds-check its items.
+#ifdef __HIPCC__
+__device__ inline unsigned xcd_block() { return (blockIdx.x & 7u) * (gridDim.x >> 3) + (blockIdx.x >> 3); }
+#endif
+inline unsigned grid8(int64_t blocks) { return (unsigned)(((blocks > 0 ? blocks : 1) + 7) / 8 * 8); }
+
 // Work item of the edge kernels: the rows whose first edge lies in one span of kChunkEdges edges.
 #ifndef MLIP_CHUNK
 #define MLIP_CHUNK 1024

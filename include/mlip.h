@@ -173,6 +173,22 @@ int mlip_build_graph(const double *positions, const double *cell, const int32_t 
                      mlip_graph_t **graph);
 
 /*
+ * Verlet skin for repeated builds on one handle (molecular dynamics: the paper's workload is long MD with the graph
+ * and its partition rebuilt at every step - "Molecular Dynamics Simulation Stability", appendix "Graph
+ * Partitioning").  With skin > 0 the handle keeps a candidate neighbour list for the cutoff r_cut + skin and the
+ * positions it was built at.  A later mlip_build_graph with the same atom count, cell and r_cut first checks, on the
+ * device, that no atom has moved further than skin / 2 from those positions; if so the neighbour list is the
+ * candidates that pass the edge test at the new positions (no cell list, no search, no sort: same fp64 expression,
+ * same order, so the graph is bit-identical to a fresh build), otherwise the candidate list is rebuilt first.
+ * Positions must be continuous between builds (an atom folded back into the cell by a lattice vector counts as
+ * moved).  Species may change freely.  skin = 0 (the default) searches at every build.  The partition is built
+ * from the neighbour list either way.
+ */
+int mlip_graph_set_skin(mlip_graph_t *graph, double skin);
+/* How often the candidate list was rebuilt and how often it was reused since the handle was made (HOST outputs). */
+int mlip_graph_skin_stats(const mlip_graph_t *graph, int64_t *list_builds, int64_t *list_reuses);
+
+/*
  * Energy and forces (Methods: per-layer border-node transfer forward, the same
  * transfers reversed for the gradients; appendix "Parallelizing a Model":
  * distribute / atom_transfer / aggregate).

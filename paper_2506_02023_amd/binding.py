@@ -94,6 +94,8 @@ def lib():
         vp, i64, i32, dbl = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_double
         L.mlip_graph_create.argtypes = [ctypes.POINTER(_Alloc), ctypes.POINTER(vp)]
         L.mlip_graph_invalidate_weights.argtypes = [vp]
+        L.mlip_graph_set_skin.argtypes = [vp, dbl]
+        L.mlip_graph_skin_stats.argtypes = [vp, ctypes.POINTER(i64), ctypes.POINTER(i64)]
         L.mlip_forward_static.argtypes = [vp, ctypes.POINTER(_Weights), i32, vp, vp, vp]
         L.mlip_static_scratch_bytes.restype = ctypes.c_size_t
         L.mlip_build_graph.argtypes = [vp, ctypes.POINTER(dbl), vp, i64, dbl, i32, vp, ctypes.POINTER(vp)]
@@ -137,6 +139,18 @@ class Graph:
         self.allocator = TorchAllocator() if allocator is None else (allocator or None)
         if self.allocator is not None:
             _check(lib().mlip_graph_create(ctypes.byref(self.allocator.c), ctypes.byref(self._h)))
+
+    def set_skin(self, skin):
+        """Verlet skin (same length unit as the positions) for repeated builds on this handle; 0 switches it off."""
+        if not self._h.value:
+            _check(lib().mlip_graph_create(None, ctypes.byref(self._h)))
+        _check(lib().mlip_graph_set_skin(self._h, float(skin)))
+
+    def skin_stats(self):
+        """(candidate list rebuilds, reuses) since the handle was made."""
+        a, b = ctypes.c_int64(), ctypes.c_int64()
+        _check(lib().mlip_graph_skin_stats(self._h, ctypes.byref(a), ctypes.byref(b)))
+        return a.value, b.value
 
     def invalidate_weights(self):
         _check(lib().mlip_graph_invalidate_weights(self._h))

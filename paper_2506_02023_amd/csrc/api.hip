@@ -156,6 +156,23 @@ int mlip_graph_create(const mlip_alloc_t *alloc, mlip_graph_t **graph)
     return MLIP_OK;
 }
 
+int mlip_graph_set_skin(mlip_graph_t *g, double skin)
+{
+    if (!g) { set_error("null graph"); return MLIP_EINVAL; }
+    if (!(skin >= 0.0) || !(skin < 1e6)) { set_error("skin must be non-negative and finite"); return MLIP_EINVAL; }
+    g->skin = skin;
+    g->cand_valid = false;
+    return MLIP_OK;
+}
+
+int mlip_graph_skin_stats(const mlip_graph_t *g, int64_t *list_builds, int64_t *list_reuses)
+{
+    if (!g) { set_error("null graph"); return MLIP_EINVAL; }
+    if (list_builds) *list_builds = g->skin_builds;
+    if (list_reuses) *list_reuses = g->skin_reuses;
+    return MLIP_OK;
+}
+
 int mlip_graph_invalidate_weights(mlip_graph_t *g)
 {
     if (!g) { set_error("null graph"); return MLIP_EINVAL; }
@@ -327,7 +344,8 @@ void mlip_graph_destroy(mlip_graph_t *g)
     DevBuf *bufs[] = {&g->pos, &g->species, &g->cell_of, &g->wrapp, &g->cell_cnt, &g->cell_start, &g->cell_fill,
                       &g->sid, &g->sx, &g->sy, &g->sz, &g->swrap, &g->counts, &g->keys, &g->stage, &g->flags, &g->scan_tmp,
                       &g->small, &g->row_ptr, &g->senders, &g->recv, &g->mirror, &g->shiftp, &g->d, &g->chunk_row, &g->slab_of, &g->needed_by,
-                      &g->local_of, &g->local_in_owner, &g->class_cnt, &g->class_off, &g->wpack, &g->energy_part};
+                      &g->local_of, &g->local_in_owner, &g->class_cnt, &g->class_off, &g->wpack, &g->energy_part,
+                      &g->cand_row_ptr, &g->cand_senders, &g->cand_recv, &g->cand_shiftp, &g->cand_d, &g->ref_pos};
     for (DevBuf *b : bufs) b->release();
     g->bond_wpack.release();
     auto drop_view = [](SlabView &v) {

@@ -748,6 +748,80 @@ __global__ void k_chunk_rows_parts(PartTab T, const int64_t *__restrict__ lrow_p
     chunk_row[idx] = (int32_t)lo;
 }
 
+// ---- neighbour list from a candidate list (Verlet skin)
+//
+// The candidates of atom i are its neighbour list for the cutoff r_cut + skin at some earlier positions (`ref`),
+// sorted like the final rows.  While no atom has moved further than skin / 2 from `ref`, every pair within r_cut is
+// among them, so the exact neighbour list is the candidates that pass the fp64 test at the current positions, in
+// the same order.  One wavefront per atom; the first pass counts (and checks the displacement, assigns the slab and
+// tracks the species range as the binning kernel does), the second writes the rows.
+enum { FLAG_DISPLACED = 16 };
+template <bool FILL>
+__global__ void __launch_bounds__(256)
+k_skin_rows(int64_t N, CellParams cp, const double *__restrict__ pos, const double *__restrict__ ref, double half_skin2,
+            const int32_t *__restrict__ species, const int64_t *__restrict__ crow, const int32_t *__restrict__ csend,
+            const uint32_t *__restrict__ cshift, int32_t *counts, int32_t *slab_of, const int64_t *__restrict__ row_ptr,
+            int32_t *senders, int32_t *recv, uint32_t *shiftp, float *d, int32_t *err)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t i = (int64_t)xcd_block() * 4 + (threadIdx.x >> 6);
+    if (i >= N) return;
+    const double xi = pos[3 * i], yi = pos[3 * i + 1], zi = pos[3 * i + 2];
+    if (!FILL && lane == 0) {
+        const double u0 = xi - ref[3 * i], u1 = yi - ref[3 * i + 1], u2 = zi - ref[3 * i + 2];
+        if (!((u0 * u0 + u1 * u1) + u2 * u2 <= half_skin2)) atomicOr(err, FLAG_DISPLACED);   // (a NaN counts as moved)
+        const double r[3] = {xi, yi, zi};
+        double f = frac_k(r, cp.nrm[cp.axis], cp.V);
+        double fl = floor(f);
+        if (!(fabs(fl) <= 200.0)) { fl = 0.0; f = 0.0; }
+        const double fr = f - fl;
+        int sl = (int)floor(fr * (double)cp.n_slabs);
+        sl = sl > cp.n_slabs - 1 ? cp.n_slabs - 1 : sl;
+        slab_of[i] = sl < 0 ? 0 : sl;
+        const int z = species[i];
+        if (z > __atomic_load_n(err + 1, __ATOMIC_RELAXED)) atomicMax(err + 1, z);
+        if (z < __atomic_load_n(err + 2, __ATOMIC_RELAXED)) atomicMin(err + 2, z);
+    }
+    const int64_t e1 = crow[i + 1];
+    int64_t out = FILL ? row_ptr[i] : 0;
+    int cnt = 0;
+    bool coincident = false;
+    const unsigned long long lt = (1ull << lane) - 1ull;
+    for (int64_t eb = crow[i]; eb < e1; eb += 64) {
+        const int64_t e = eb + lane;
+        bool keep = false;
+        int32_t j = 0;
+        uint32_t sp = 0;
+        double d2 = 1.0;
+        if (e < e1) {
+            j = csend[e];
+            sp = cshift[e];
+            int S0, S1, S2;
+            unpack3(sp, S0, S1, S2);
+            const double t0 = (pos[3 * (int64_t)j] - xi) + (((double)S0 * cp.C[0] + (double)S1 * cp.C[3]) + (double)S2 * cp.C[6]);
+            const double t1 = (pos[3 * (int64_t)j + 1] - yi) + (((double)S0 * cp.C[1] + (double)S1 * cp.C[4]) + (double)S2 * cp.C[7]);
+            const double t2 = (pos[3 * (int64_t)j + 2] - zi) + (((double)S0 * cp.C[2] + (double)S1 * cp.C[5]) + (double)S2 * cp.C[8]);
+            d2 = (t0 * t0 + t1 * t1) + t2 * t2;
+            keep = d2 <= cp.rc2;
+            if (keep && d2 == 0.0) coincident = true;
+        }
+        const unsigned long long m = __ballot(keep);
+        if (FILL && keep) {
+            const int64_t o = out + __popcll(m & lt);
+            senders[o] = j;
+            shiftp[o] = sp;
+            recv[o] = (int32_t)i;
+            d[o] = (float)sqrt(d2);
+        }
+        out += __popcll(m);
+        cnt += __popcll(m);
+    }
+    if (!FILL) {
+        if (lane == 0) counts[i] = cnt;
+        if (coincident) atomicOr(err, ERR_COINCIDENT);
+    }
+}
+
 inline unsigned blocks_for(int64_t n, int threads) { return (unsigned)((n + threads - 1) / threads); }
 
 void cross3(const double *a, const double *b, double *o)
@@ -935,28 +1009,49 @@ int build_bonds_impl(mlip_graph *g, SlabView &v, double r_bond, int p_envelope)
     return MLIP_OK;
 }
 
-int build_graph_impl(mlip_graph *g, const double *positions, const double *cell, const int32_t *species,
-                     int64_t N, double r_cut, int32_t P)
+namespace {
+
+struct CsrOut {   // where a neighbour search puts its receiver-sorted CSR
+    DevBuf *row_ptr, *senders, *recv, *shiftp, *d;
+};
+
+// reads the edge count and the flag words after the first pass of either route and turns the flags into errors
+int read_counts_and_flags(mlip_graph *g, const int64_t *row_ptr_end, int32_t *err, int64_t *E, int32_t *flags_out)
 {
     hipStream_t s = g->stream;
-    CellParams cp;
-    MLIP_TRY(prepare_cell(cell, r_cut, P, N, cp));
-    g->cell = cp;
-    g->N = 0;  // the handle is invalid until the build completes
-    g->whole.bonds.r_bond = -1.0;
-    for (SlabView &sv : g->slabs) sv.bonds.r_bond = -1.0;
-    g->E = 0;
+    int64_t *hp = static_cast<int64_t *>(g->pinned);
+    MLIP_HIP(hipMemcpyAsync(hp, row_ptr_end, 8, hipMemcpyDeviceToHost, s));
+    MLIP_HIP(hipMemcpyAsync(hp + 1, err, 12, hipMemcpyDeviceToHost, s));
+    MLIP_HIP(hipStreamSynchronize(s));
+    *E = hp[0];
+    const int32_t *herr = reinterpret_cast<int32_t *>(hp + 1);
+    const int32_t flags = herr[0];
+    *flags_out = flags;
+    g->species_max = herr[1];
+    g->species_min = herr[2];
+    if (flags & ERR_RANGE) {
+        set_error("an atom lies more than 200 cells away from the origin cell (or has a non-finite coordinate)");
+        return MLIP_ECELL;
+    }
+    if (flags & ERR_COINCIDENT) {
+        set_error("two atoms (or an atom and one of its images) coincide");
+        return MLIP_ECOINCIDENT;
+    }
+    if (*E >= ((int64_t)1 << 31)) {
+        set_error("more than 2^31 directed edges");
+        return MLIP_EINVAL;
+    }
+    return MLIP_OK;
+}
+
+// Cell-list neighbour search for the cutoff in cp.rc2 over the positions and species held by the handle; writes the
+// canonical receiver-sorted CSR to `out`, slab_of and the species range; synchronises the stream once.
+int search_csr(mlip_graph *g, const CellParams &cp, int64_t N, CsrOut out, int64_t *E_out)
+{
+    hipStream_t s = g->stream;
     const int64_t ncell = (int64_t)cp.nb[0] * cp.nb[1] * cp.nb[2];
-    if (!g->pinned) MLIP_HIP(hipHostMalloc(&g->pinned, 65536, hipHostMallocDefault));
-
-    MLIP_TRY(g->pos.ensure((size_t)N * 3 * sizeof(double)));
-    MLIP_TRY(g->species.ensure((size_t)N * sizeof(int32_t)));
-    MLIP_HIP(hipMemcpyAsync(g->pos.p, positions, (size_t)N * 3 * sizeof(double), hipMemcpyDeviceToDevice, s));
-    MLIP_HIP(hipMemcpyAsync(g->species.p, species, (size_t)N * sizeof(int32_t), hipMemcpyDeviceToDevice, s));
-
     MLIP_TRY(g->cell_of.ensure((size_t)N * 4));
     MLIP_TRY(g->wrapp.ensure((size_t)N * 4));
-    MLIP_TRY(g->slab_of.ensure((size_t)N * 4));
     MLIP_TRY(g->cell_cnt.ensure((size_t)(ncell + 1) * 4));
     MLIP_TRY(g->cell_fill.ensure((size_t)(ncell + 1) * 4));
     MLIP_TRY(g->cell_start.ensure((size_t)(ncell + 2) * 4));
@@ -965,12 +1060,8 @@ int build_graph_impl(mlip_graph *g, const double *positions, const double *cell,
     MLIP_TRY(g->sx.ensure((size_t)N * 8));
     MLIP_TRY(g->sy.ensure((size_t)N * 8));
     MLIP_TRY(g->sz.ensure((size_t)N * 8));
-    MLIP_TRY(g->counts.ensure((size_t)(N + 1) * 4));
-    MLIP_TRY(g->row_ptr.ensure((size_t)(N + 1) * 8));
-    MLIP_TRY(g->small.ensure(4096));
+    MLIP_TRY(out.row_ptr->ensure((size_t)(N + 1) * 8));
     int32_t *err = g->small.as<int32_t>();
-
-    prof_begin(g, MLIP_PROF_GRAPH);
     MLIP_HIP(hipMemsetAsync(g->small.p, 0, 4096, s));
     MLIP_HIP(hipMemsetAsync(g->cell_cnt.p, 0, (size_t)(ncell + 1) * 4, s));
     MLIP_HIP(hipMemsetAsync(g->cell_fill.p, 0, (size_t)(ncell + 1) * 4, s));
@@ -994,52 +1085,134 @@ int build_graph_impl(mlip_graph *g, const double *positions, const double *cell,
         g->sz.as<double>(), g->swrap.as<uint32_t>(), g->cell_of.as<int32_t>(), g->counts.as<int32_t>(), nullptr,
         use_stage ? g->stage.as<uint64_t>() : nullptr, err);
     MLIP_HIP(hipGetLastError());
-    MLIP_TRY(scan_i32_to_i64(g->counts.as<int32_t>(), g->row_ptr.as<int64_t>(), N, g->scan_tmp, s));
-    // host needs E and the error flags
-    int64_t *hp = static_cast<int64_t *>(g->pinned);
-    MLIP_HIP(hipMemcpyAsync(hp, g->row_ptr.as<int64_t>() + N, 8, hipMemcpyDeviceToHost, s));
-    MLIP_HIP(hipMemcpyAsync(hp + 1, err, 12, hipMemcpyDeviceToHost, s));
-    MLIP_HIP(hipStreamSynchronize(s));
-    const int64_t E = hp[0];
-    const int32_t *herr = reinterpret_cast<int32_t *>(hp + 1);
-    const int32_t flags = herr[0];
-    g->species_max = herr[1];
-    g->species_min = herr[2];
-    if (flags & ERR_RANGE) {
-        prof_end(g);
-        set_error("an atom lies more than 200 cells away from the origin cell (or has a non-finite coordinate)");
-        return MLIP_ECELL;
-    }
-    if (flags & ERR_COINCIDENT) {
-        prof_end(g);
-        set_error("two atoms (or an atom and one of its images) coincide");
-        return MLIP_ECOINCIDENT;
-    }
-    if (E >= ((int64_t)1 << 31)) {
-        prof_end(g);
-        set_error("more than 2^31 directed edges");
-        return MLIP_EINVAL;
-    }
+    MLIP_TRY(scan_i32_to_i64(g->counts.as<int32_t>(), out.row_ptr->as<int64_t>(), N, g->scan_tmp, s));
+    int64_t E = 0;
+    int32_t flags = 0;
+    MLIP_TRY(read_counts_and_flags(g, out.row_ptr->as<int64_t>() + N, err, &E, &flags));   // first synchronisation
     const size_t Ecap = (size_t)std::max<int64_t>(E, 1);
     const bool staged = use_stage && !(flags & FLAG_STAGE_OVERFLOW);
     if (!staged) MLIP_TRY(g->keys.ensure(Ecap * 8));
-    MLIP_TRY(g->senders.ensure(Ecap * 4));
-    MLIP_TRY(g->shiftp.ensure(Ecap * 4));
-    MLIP_TRY(g->recv.ensure(Ecap * 4));
-    MLIP_TRY(g->mirror.ensure(Ecap * 4));
-    MLIP_TRY(g->d.ensure(Ecap * 4));
+    MLIP_TRY(out.senders->ensure(Ecap * 4));
+    MLIP_TRY(out.shiftp->ensure(Ecap * 4));
+    MLIP_TRY(out.recv->ensure(Ecap * 4));
+    MLIP_TRY(out.d->ensure(Ecap * 4));
     if (!staged) {
         k_neighbours<true><<<grid8(blocks_for(N, 128)), 128, 0, s>>>(
             N, cp, g->cell_start.as<int32_t>(), g->sid.as<int32_t>(), g->sx.as<double>(), g->sy.as<double>(),
-            g->sz.as<double>(), g->swrap.as<uint32_t>(), g->cell_of.as<int32_t>(), nullptr, g->row_ptr.as<int64_t>(),
+            g->sz.as<double>(), g->swrap.as<uint32_t>(), g->cell_of.as<int32_t>(), nullptr, out.row_ptr->as<int64_t>(),
             g->keys.as<uint64_t>(), err);
         MLIP_HIP(hipGetLastError());
     }
-    k_sort_rows<<<grid8(N), 64, 0, s>>>(N, cp, pos, g->row_ptr.as<int64_t>(),
-                                           staged ? g->stage.as<uint64_t>() : g->keys.as<uint64_t>(), staged ? 1 : 0,
-                                           g->senders.as<int32_t>(), g->recv.as<int32_t>(), g->shiftp.as<uint32_t>(),
-                                           g->d.as<float>());
+    k_sort_rows<<<grid8(N), 64, 0, s>>>(N, cp, pos, out.row_ptr->as<int64_t>(),
+                                        staged ? g->stage.as<uint64_t>() : g->keys.as<uint64_t>(), staged ? 1 : 0,
+                                        out.senders->as<int32_t>(), out.recv->as<int32_t>(), out.shiftp->as<uint32_t>(),
+                                        out.d->as<float>());
     MLIP_HIP(hipGetLastError());
+    *E_out = E;
+    return MLIP_OK;
+}
+
+// The exact neighbour list from the handle's candidate list; *valid = false (and nothing usable written) when some
+// atom has moved more than skin / 2 since the candidates were built.  Synchronises the stream once.
+int csr_from_candidates(mlip_graph *g, const CellParams &cp, int64_t N, int64_t *E_out, bool *valid)
+{
+    hipStream_t s = g->stream;
+    int32_t *err = g->small.as<int32_t>();
+    MLIP_HIP(hipMemsetAsync(g->small.p, 0, 4096, s));
+    MLIP_TRY(g->row_ptr.ensure((size_t)(N + 1) * 8));
+    const double h2 = 0.25 * g->skin * g->skin;
+    const double *pos = g->pos.as<double>();
+    k_skin_rows<false><<<grid8((N + 3) / 4), 256, 0, s>>>(
+        N, cp, pos, g->ref_pos.as<double>(), h2, g->species.as<int32_t>(), g->cand_row_ptr.as<int64_t>(),
+        g->cand_senders.as<int32_t>(), g->cand_shiftp.as<uint32_t>(), g->counts.as<int32_t>(), g->slab_of.as<int32_t>(),
+        nullptr, nullptr, nullptr, nullptr, nullptr, err);
+    MLIP_HIP(hipGetLastError());
+    MLIP_TRY(scan_i32_to_i64(g->counts.as<int32_t>(), g->row_ptr.as<int64_t>(), N, g->scan_tmp, s));
+    int64_t E = 0;
+    int32_t flags = 0;
+    const int rc = read_counts_and_flags(g, g->row_ptr.as<int64_t>() + N, err, &E, &flags);
+    if (flags & FLAG_DISPLACED) { *valid = false; return MLIP_OK; }   // (errors seen on the way are found again by the full search)
+    MLIP_TRY(rc);
+    const size_t Ecap = (size_t)std::max<int64_t>(E, 1);
+    MLIP_TRY(g->senders.ensure(Ecap * 4));
+    MLIP_TRY(g->shiftp.ensure(Ecap * 4));
+    MLIP_TRY(g->recv.ensure(Ecap * 4));
+    MLIP_TRY(g->d.ensure(Ecap * 4));
+    k_skin_rows<true><<<grid8((N + 3) / 4), 256, 0, s>>>(
+        N, cp, pos, g->ref_pos.as<double>(), h2, g->species.as<int32_t>(), g->cand_row_ptr.as<int64_t>(),
+        g->cand_senders.as<int32_t>(), g->cand_shiftp.as<uint32_t>(), nullptr, nullptr, g->row_ptr.as<int64_t>(),
+        g->senders.as<int32_t>(), g->recv.as<int32_t>(), g->shiftp.as<uint32_t>(), g->d.as<float>(), err);
+    MLIP_HIP(hipGetLastError());
+    *E_out = E;
+    *valid = true;
+    return MLIP_OK;
+}
+
+}  // namespace
+
+int build_graph_impl(mlip_graph *g, const double *positions, const double *cell, const int32_t *species,
+                     int64_t N, double r_cut, int32_t P)
+{
+    hipStream_t s = g->stream;
+    CellParams cp;
+    MLIP_TRY(prepare_cell(cell, r_cut, P, N, cp));
+    g->cell = cp;
+    g->N = 0;  // the handle is invalid until the build completes
+    g->whole.bonds.r_bond = -1.0;
+    for (SlabView &sv : g->slabs) sv.bonds.r_bond = -1.0;
+    g->E = 0;
+    if (!g->pinned) MLIP_HIP(hipHostMalloc(&g->pinned, 65536, hipHostMallocDefault));
+    int64_t *hp = static_cast<int64_t *>(g->pinned);
+
+    MLIP_TRY(g->pos.ensure((size_t)N * 3 * sizeof(double)));
+    MLIP_TRY(g->species.ensure((size_t)N * sizeof(int32_t)));
+    MLIP_HIP(hipMemcpyAsync(g->pos.p, positions, (size_t)N * 3 * sizeof(double), hipMemcpyDeviceToDevice, s));
+    MLIP_HIP(hipMemcpyAsync(g->species.p, species, (size_t)N * sizeof(int32_t), hipMemcpyDeviceToDevice, s));
+    MLIP_TRY(g->slab_of.ensure((size_t)N * 4));
+    MLIP_TRY(g->counts.ensure((size_t)(N + 1) * 4));
+    MLIP_TRY(g->small.ensure(4096));
+    int32_t *err = g->small.as<int32_t>();
+
+    prof_begin(g, MLIP_PROF_GRAPH);
+    int64_t E = 0;
+    if (g->skin > 0.0) {
+        // Verlet skin: the neighbour list is filtered from a candidate list for r_cut + skin, which is rebuilt
+        // when the system changed or some atom has moved more than skin / 2 since it was made
+        bool valid = false;
+        const bool usable = g->cand_valid && g->cand_N == N && g->cand_rcut == r_cut && g->cand_skin == g->skin &&
+                            std::memcmp(g->cand_cell, cell, sizeof(g->cand_cell)) == 0;
+        int rc = MLIP_OK;
+        if (usable) rc = csr_from_candidates(g, cp, N, &E, &valid);
+        if (rc == MLIP_OK && !valid) {
+            g->cand_valid = false;
+            CellParams cps;
+            rc = prepare_cell(cell, r_cut + g->skin, P, N, cps);
+            if (rc == MLIP_OK)
+                rc = search_csr(g, cps, N, CsrOut{&g->cand_row_ptr, &g->cand_senders, &g->cand_recv, &g->cand_shiftp, &g->cand_d},
+                                &g->cand_E);
+            if (rc == MLIP_OK) rc = g->ref_pos.ensure((size_t)N * 3 * sizeof(double));
+            if (rc == MLIP_OK) {
+                MLIP_HIP(hipMemcpyAsync(g->ref_pos.p, g->pos.p, (size_t)N * 3 * sizeof(double), hipMemcpyDeviceToDevice, s));
+                g->cand_N = N;
+                g->cand_rcut = r_cut;
+                g->cand_skin = g->skin;
+                std::memcpy(g->cand_cell, cell, sizeof(g->cand_cell));
+                g->cand_valid = true;
+                g->skin_builds += 1;
+                rc = csr_from_candidates(g, cp, N, &E, &valid);
+                if (rc == MLIP_OK && !valid) { set_error("internal error: a fresh candidate list is not valid"); rc = MLIP_EHIP; }
+            }
+        } else if (rc == MLIP_OK) {
+            g->skin_reuses += 1;
+        }
+        if (rc != MLIP_OK) { prof_end(g); return rc; }
+    } else {
+        const int rc = search_csr(g, cp, N, CsrOut{&g->row_ptr, &g->senders, &g->recv, &g->shiftp, &g->d}, &E);
+        if (rc != MLIP_OK) { prof_end(g); return rc; }
+    }
+    const double *pos = g->pos.as<double>();
+    (void)pos;
+    MLIP_TRY(g->mirror.ensure((size_t)std::max<int64_t>(E, 1) * 4));
 
     if (E > 0) {
         k_mirror<true><<<grid8(blocks_for(E, 256)), 256, 0, s>>>(E, g->row_ptr.as<int64_t>(), g->senders.as<int32_t>(),

@@ -192,6 +192,13 @@ struct mlip_graph {
         scan_tmp, small;
     // whole-graph CSR
     mlip::DevBuf row_ptr, senders, recv, mirror, shiftp, d, chunk_row;
+    // Verlet skin (mlip_graph_set_skin): candidate list for r_cut + skin and the positions it was built at
+    double skin = 0.0;
+    bool cand_valid = false;
+    int64_t cand_N = 0, cand_E = 0;
+    double cand_rcut = 0.0, cand_skin = 0.0, cand_cell[9] = {0};
+    int64_t skin_builds = 0, skin_reuses = 0;
+    mlip::DevBuf cand_row_ptr, cand_senders, cand_recv, cand_shiftp, cand_d, ref_pos;
     // partition
     mlip::DevBuf slab_of, needed_by, local_of, local_in_owner, class_cnt, class_off;
     mlip::PartStore part;

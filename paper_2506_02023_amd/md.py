@@ -1,7 +1,7 @@
 """A few steps of constant-energy molecular dynamics on the synthetic lattice, the graph rebuilt at every step
 as in the paper's runs (Results: the graph is re-created each step because atoms move).
 
-    python -m paper_2506_02023_amd.md [--cells 63] [--slabs 8] [--steps 50] [--dt 0.004] [--three-body]
+    python -m paper_2506_02023_amd.md [--cells 63] [--slabs 8] [--steps 50] [--dt 0.004] [--three-body] [--skin 0.5]
 
 Energies and forces come from the HIP library (mlip_build_graph + mlip_forward per step); the velocity-Verlet update
 is three lines of torch arithmetic on the positions and velocities (unit masses, the model's own energy unit).
@@ -24,6 +24,9 @@ def main():
     ap.add_argument("--slabs", type=int, default=8)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--dt", type=float, default=0.004)
+    ap.add_argument("--skin", type=float, default=0.0,
+                    help="Verlet skin in Angstrom: the neighbour list is filtered from a candidate list for r_cut + skin that "
+                         "is rebuilt when an atom has moved skin / 2 (0: search at every step)")
     ap.add_argument("--three-body", action="store_true", help="the three-body variant (benchmark configuration 4's model)")
     args = ap.parse_args()
 
@@ -45,6 +48,9 @@ def main():
     mode = M.MODE_SLABS if args.slabs > 1 else M.MODE_WHOLE
     out = (torch.empty(1, dtype=torch.float64, device="cuda"), torch.empty((N, 3), dtype=torch.float32, device="cuda"), None)
     g = None
+    if args.skin > 0:
+        g = M.Graph()
+        g.set_skin(args.skin)
 
     def energy_forces():
         nonlocal g
@@ -80,6 +86,9 @@ def main():
     print(f"{N} atoms, {E} directed edges, {args.slabs} slab(s), {'three-body' if args.three_body else 'two-body'} model")
     print(f"{args.steps} velocity-Verlet steps of dt = {args.dt}: {dt * 1e3:.2f} ms per step "
           f"({N / dt / 1e6:.2f} M atom-steps/s), graph rebuilt every step")
+    if args.skin > 0:
+        builds, reuses = g.skin_stats()
+        print(f"Verlet skin {args.skin}: candidate list built {builds} times, reused {reuses} times")
     print(f"potential energy moved by {swing:.4f}, E_pot + E_kin drifted by at most {drift:.3e} "
           f"({drift / swing:.1e} of the swing)" if swing > 0 else "no motion")
 

@@ -256,6 +256,54 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
     }
     double *energy_part = reinterpret_cast<double *>(energy_part_f);
 
+
+    // ---- batches for the small kernels (embedding, ghost transfers, forces, energy): up to kBatch partitions per launch
+    enum { U_OWNED, U_GHOST, U_BORDER, U_LOCAL, U_KBLOCKS };
+    auto small_batch = [&](int p0, int unit, int layer) {
+        SmallBatch sb{};
+        sb.n = std::min(kBatch, P - p0);
+        sb.first = p0;
+        sb.start[0] = 0;
+        for (int q = 0; q < kBatch; ++q) {
+            if (q >= sb.n) { sb.start[q + 1] = sb.start[q]; continue; }
+            SlabView &v = views[p0 + q];
+            SmallArgs &a = sb.s[q];
+            a.n_owned = v.n_owned;
+            a.n_pure = v.n_pure;
+            a.n_ghost = v.n_ghost;
+            a.n_local = v.n_local;
+            a.nodes = v.nodes;
+            a.ghost_owner = v.ghost_owner;
+            a.ghost_src = v.ghost_src;
+            a.row_ptr = v.row_ptr;
+            a.senders = v.senders;
+            a.mirror = v.mirror;
+            a.shiftp = v.shiftp;
+            a.h = v.ws.h;
+            a.g = (layer >= 0) ? v.ws.g + (size_t)layer * (size_t)v.n_local * F : nullptr;
+            a.gbar = v.ws.gbar;
+            a.abar = v.ws.abar;
+            a.floc = v.ws.floc;
+            a.eps = v.ws.eps;
+            a.dsum = v.ws.dsum;
+            a.wstore = (layer >= 1) ? v.ws.wst + (size_t)(layer - 1) * (size_t)v.n_edges_owned * F : nullptr;
+            a.bond_of_edge = (bw && v.bonds.n > 0) ? v.bonds.of_edge.as<int32_t>() : nullptr;
+            a.wb = (bw && v.bonds.n > 0 && layer >= 0)
+                       ? v.bonds.wb.as<float>() + (size_t)layer * (size_t)std::max<int64_t>(v.bonds.n, 1) * F : nullptr;
+            const int64_t items = unit == U_OWNED ? v.n_owned : unit == U_GHOST ? v.n_ghost
+                                  : unit == U_BORDER ? v.n_owned - v.n_pure : unit == U_LOCAL ? v.n_local
+                                  : (v.n_owned + 1023) / 1024;
+            sb.start[q + 1] = sb.start[q] + std::max<int64_t>(items, 0);
+        }
+        return sb;
+    };
+    GhostIndex gidx{};
+    if (slabs) {
+        gidx.needed_by = g->needed_by.as<unsigned long long>();
+        gidx.gbase = g->part.gbase.as<int32_t>();
+        gidx.ghost_local = g->part.ghost_local.as<int32_t>();
+    }
+
     BasisParams bp;
     bp.rc = (float)g->r_cut;
     bp.inv_rc = (float)(1.0 / g->r_cut);
@@ -301,10 +349,10 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
 
     // ---- embedding
     const int32_t *species = g->species.as<int32_t>();
-    for (int p = 0; p < P; ++p) {
-        SlabView &v = views[p];
-        if (v.n_owned > 0)
-            k_embed<<<blocks_for(v.n_owned * (F / 4), 256), 256, 0, s>>>(v.n_owned, F, v.nodes, species, w->emb, v.ws.h);
+    for (int p0 = 0; p0 < P; p0 += kBatch) {
+        const SmallBatch sb = small_batch(p0, U_OWNED, -1);
+        if (sb.start[sb.n] > 0)
+            k_embed<<<blocks_for(sb.start[sb.n] * (F / 4), 256), 256, 0, s>>>(sb, F, species, w->emb);
     }
     MLIP_HIP(hipGetLastError());
     prof_end(g);
@@ -453,11 +501,10 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
             prof_begin(g, MLIP_PROF_GHOST);
             PtrTable tab{};
             for (int q = 0; q < P; ++q) tab.p[q] = gslice(views[q], l);
-            for (int p = 0; p < P; ++p) {  // border-node transfer: ghost rows <- owners
-                SlabView &v = views[p];
-                if (v.n_ghost > 0)
-                    k_ghost_copy<<<blocks_for(v.n_ghost * (F / 4), 256), 256, 0, s>>>(
-                        v.n_ghost, v.n_owned, F, v.ghost_owner, v.ghost_src, tab, gslice(v, l));
+            for (int p0 = 0; p0 < P; p0 += kBatch) {   // border-node transfer: ghost rows <- owners
+                const SmallBatch sb = small_batch(p0, U_GHOST, l);
+                if (sb.start[sb.n] > 0)
+                    k_ghost_copy<<<blocks_for(sb.start[sb.n] * (F / 4), 256), 256, 0, s>>>(sb, F, tab);
             }
             MLIP_HIP(hipGetLastError());
             prof_end(g);
@@ -524,10 +571,10 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
     {
         int64_t off = 0;
         double *part = energy_part;
-        for (int p = 0; p < P; ++p) {
-            SlabView &v = views[p];
-            const int64_t nb = (v.n_owned + 1023) / 1024;
-            if (nb > 0) k_energy_partial<<<(unsigned)nb, 256, 0, s>>>(v.n_owned, v.ws.eps, part + off);
+        for (int p0 = 0; p0 < P; p0 += kBatch) {
+            const SmallBatch sb = small_batch(p0, U_KBLOCKS, -1);
+            const int64_t nb = sb.start[sb.n];
+            if (nb > 0) k_energy_partial<<<(unsigned)nb, 256, 0, s>>>(sb, part + off);
             off += nb;
         }
         k_energy_final<<<1, 256, 0, s>>>(off, part, energy);
@@ -536,11 +583,13 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
     prof_end(g);
 
     // ---- reverse pass
-    for (int p = 0; p < P; ++p) {  // ghost rows carry no dE/da: zero once, no kernel ever writes them
-        SlabView &v = views[p];
-        if (L > 0 && v.n_ghost > 0)
-            MLIP_TRY(fill_zero(v.ws.abar + (size_t)v.n_owned * F, v.n_ghost * (int64_t)F, s));
-    }
+    if (L > 0)   // ghost rows carry no dE/da: zero once, no kernel ever writes them
+        for (int p0 = 0; p0 < P; p0 += kBatch) {
+            const SmallBatch sb = small_batch(p0, U_GHOST, -1);
+            if (sb.start[sb.n] > 0)
+                k_zero_ghost_rows<<<blocks_for(sb.start[sb.n] * (F / 4), 256), 256, 0, s>>>(sb, F);
+        }
+    MLIP_HIP(hipGetLastError());
     for (int l = L - 1; l >= 0; --l) {
         const float *base = wp + pk.per_layer * l;
         const bool need_gbar = l > 0;  // dE/dh0 is never used: the embedding does not depend on positions
@@ -608,16 +657,15 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
                 prof_begin(g, MLIP_PROF_GHOST);
                 PtrTable tab{};
                 for (int q = 0; q < P; ++q) tab.p[q] = views[q].ws.gbar;
-                for (int p = 0; p < P; ++p) {  // ghost-row gradients -> owners, partitions in ascending order
-                    SlabView &v = views[p];
-                    if (v.n_ghost > 0)
-                        k_ghost_gbar<F><<<blocks_for(v.n_ghost, 4), 256, 0, s>>>(
-                            v.n_ghost, v.n_owned, v.row_ptr, v.senders, v.mirror, wslice(v, l), v.ws.abar,
-                            (bw && v.bonds.n > 0) ? v.bonds.of_edge.as<int32_t>() : nullptr,
-                            (bw && v.bonds.n > 0) ? wbslice(v, l) : nullptr, v.ws.gbar);
-                    if (v.n_ghost > 0)
-                        k_ghost_addback<<<blocks_for(v.n_ghost * (F / 4), 256), 256, 0, s>>>(
-                            v.n_ghost, v.n_owned, F, v.ghost_owner, v.ghost_src, tab, v.ws.gbar);
+                for (int p0 = 0; p0 < P; p0 += kBatch) {   // the ghost rows' gradients ...
+                    const SmallBatch sb = small_batch(p0, U_GHOST, l);
+                    if (sb.start[sb.n] > 0)
+                        k_ghost_gbar<F><<<blocks_for(sb.start[sb.n], 4), 256, 0, s>>>(sb);
+                }
+                for (int p0 = 0; p0 < P; p0 += kBatch) {   // ... go back to their owners
+                    const SmallBatch sb = small_batch(p0, U_BORDER, l);
+                    if (sb.start[sb.n] > 0)
+                        k_border_add<<<blocks_for(sb.start[sb.n] * (F / 4), 256), 256, 0, s>>>(sb, F, tab, gidx);
                 }
                 MLIP_HIP(hipGetLastError());
                 prof_end(g);
@@ -671,15 +719,18 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
     // ---- forces
     prof_begin(g, MLIP_PROF_FORCE);
     const double *pos = g->pos.as<double>();
-    for (int p = 0; p < P; ++p) {
-        SlabView &v = views[p];
-        if (L > 0 && v.n_local > 0) {
-            k_force_rows<<<(unsigned)((v.n_local + 15) / 16), 256, 0, s>>>(v.n_local, v.row_ptr, v.senders, v.shiftp, v.ws.dsum,
-                                                            v.nodes, pos, g->cell, v.ws.floc);
-        } else if (v.n_local > 0) {
-            MLIP_TRY(fill_zero(v.ws.floc, v.n_local * 3, s));
-        }
-        if (bw && v.bonds.n > 0) {
+    for (int p0 = 0; p0 < P; p0 += kBatch) {
+        const SmallBatch sb = small_batch(p0, U_LOCAL, -1);
+        if (sb.start[sb.n] <= 0) continue;
+        if (L > 0)
+            k_force_rows<<<(unsigned)((sb.start[sb.n] + 15) / 16), 256, 0, s>>>(sb, pos, g->cell);
+        else
+            k_zero_floc<<<blocks_for(sb.start[sb.n], 256), 256, 0, s>>>(sb);
+    }
+    if (bw)
+        for (int p = 0; p < P; ++p) {
+            SlabView &v = views[p];
+            if (v.bonds.n <= 0) continue;
             BondGraph &BG = v.bonds;
             k_bond_force<<<blocks_for(v.n_owned, 128), 128, 0, s>>>(v.n_owned, BG.ptr.as<int64_t>(), BG.mirror.as<int32_t>(),
                                                                     BG.dbond.as<float>(), BG.rbar.as<float>(),
@@ -689,17 +740,15 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
                     v.n_ghost, v.n_owned, v.row_ptr, v.mirror, BG.of_edge.as<int32_t>(), BG.dbond.as<float>(),
                     BG.rbar.as<float>(), BG.rhat.as<float>(), BG.d.as<float>(), v.ws.floc);
         }
-        if (v.n_owned > 0)
-            k_store_owned<<<blocks_for(v.n_owned, 256), 256, 0, s>>>(v.n_owned, v.nodes, v.ws.floc,
-                                                                     v.ws.eps, forces, atom_energy);
-    }
-    if (slabs)
-        for (int p = 0; p < P; ++p) {
-            SlabView &v = views[p];
-            if (v.n_ghost > 0)
-                k_addback_ghost_forces<<<blocks_for(v.n_ghost, 256), 256, 0, s>>>(v.n_ghost, v.n_owned, v.nodes,
-                                                                                  v.ws.floc, forces);
+    {   // owned rows to the caller's arrays; a border atom also collects what its ghost rows gathered elsewhere
+        PtrTable tab{};
+        for (int q = 0; q < P; ++q) tab.p[q] = views[q].ws.floc;
+        for (int p0 = 0; p0 < P; p0 += kBatch) {
+            const SmallBatch sb = small_batch(p0, U_OWNED, -1);
+            if (sb.start[sb.n] > 0)
+                k_store_owned<<<blocks_for(sb.start[sb.n], 256), 256, 0, s>>>(sb, tab, gidx, forces, atom_energy);
         }
+    }
     MLIP_HIP(hipGetLastError());
     prof_end(g);
     return MLIP_OK;

@@ -186,71 +186,144 @@ __global__ void __launch_bounds__(256) k_node(NodeBatch B)
 }
 
 // ---------------------------------------------------------------- small kernels
+//
+// Embedding, ghost transfers, force assembly and the energy partial sums run over all partitions in one launch
+// (up to kBatch partitions per launch, like the edge and node kernels): items are numbered across the
+// partitions, start[q] is the first item of partition q.
 
-__global__ void k_embed(int64_t n_rows, int F, const int32_t *__restrict__ nodes, const int32_t *__restrict__ species,
-                        const float *__restrict__ emb, float *__restrict__ h)
-{
-    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;   // one float4 per thread
-    const int F4 = F / 4;
-    if (idx >= n_rows * F4) return;
-    const int64_t r = idx / F4;
-    const int c = (int)(idx % F4) * 4;
-    const int64_t u = nodes ? nodes[r] : r;
-    const float *e = emb + (int64_t)species[u] * F + c;   // the caller's table: no alignment assumed
-    *reinterpret_cast<f32x4 *>(h + r * F + c) = f32x4{e[0], e[1], e[2], e[3]};
-}
+struct SmallArgs {   // one partition
+    int64_t n_owned, n_pure, n_ghost, n_local;
+    const int32_t *nodes;          // local -> global (nullptr: identity)
+    const int32_t *ghost_owner, *ghost_src;
+    const int64_t *row_ptr;
+    const int32_t *senders, *mirror;
+    const uint32_t *shiftp;
+    float *h, *g, *gbar, *abar, *floc, *eps;
+    const float *dsum, *wstore;
+    const int32_t *bond_of_edge;   // three-body variant (or nullptr)
+    const float *wb;
+    double *energy_part;
+};
+
+struct SmallBatch {
+    int n;
+    int first;                     // partition index of s[0]
+    int64_t start[kBatch + 1];
+    SmallArgs s[kBatch];
+};
 
 struct PtrTable { float *p[kMaxSlabs]; };
 
-// ghost rows of this partition's g  <-  the owners' rows
-__global__ void k_ghost_copy(int64_t n_ghost, int64_t n_owned, int F, const int32_t *__restrict__ owner,
-                             const int32_t *__restrict__ src, PtrTable tab, float *__restrict__ dst)
+// What a border atom's owner needs to collect the atom's ghost rows from the other partitions: the partitions that
+// hold it as a ghost (bits of needed_by) and its row in each of them (ghost_local, starting at gbase[atom]).
+struct GhostIndex {
+    const unsigned long long *needed_by;
+    const int32_t *gbase, *ghost_local;
+};
+
+__global__ void k_embed(SmallBatch B, int F, const int32_t *__restrict__ species, const float *__restrict__ emb)
+{
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;   // one float4 per thread
+    const int F4 = F / 4;
+    const int64_t row = idx / F4;
+    if (row >= B.start[B.n]) return;
+    const int part = batch_find(B.start, B.n, row);
+    const SmallArgs &A = B.s[part];
+    const int64_t r = row - B.start[part];
+    const int c = (int)(idx % F4) * 4;
+    const int64_t u = A.nodes ? A.nodes[r] : r;
+    const float *e = emb + (int64_t)species[u] * F + c;   // the caller's table: no alignment assumed
+    *reinterpret_cast<f32x4 *>(A.h + r * F + c) = f32x4{e[0], e[1], e[2], e[3]};
+}
+
+// ghost rows of every partition's g  <-  the owners' rows (tab: the g arrays of all partitions)
+__global__ void k_ghost_copy(SmallBatch B, int F, PtrTable tab)
 {
     const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int F4 = F / 4;
-    if (idx >= n_ghost * F4) return;
-    const int64_t k = idx / F4;
+    const int64_t gk = idx / F4;
+    if (gk >= B.start[B.n]) return;
+    const int part = batch_find(B.start, B.n, gk);
+    const SmallArgs &A = B.s[part];
+    const int64_t k = gk - B.start[part];
     const int c = (int)(idx % F4) * 4;
-    const float *sp = tab.p[owner[k]] + (int64_t)src[k] * F + c;
-    *reinterpret_cast<f32x4 *>(dst + (n_owned + k) * F + c) = *reinterpret_cast<const f32x4 *>(sp);
+    const float *sp = tab.p[A.ghost_owner[k]] + (int64_t)A.ghost_src[k] * F + c;
+    *reinterpret_cast<f32x4 *>(A.g + (A.n_owned + k) * F + c) = *reinterpret_cast<const f32x4 *>(sp);
 }
 
-// the owners' gradient rows  +=  this partition's ghost rows (each ghost atom appears once per partition)
+// ghost rows of abar are zero (ghost rows carry no dE/da)
+__global__ void k_zero_ghost_rows(SmallBatch B, int F)
+{
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int F4 = F / 4;
+    const int64_t gk = idx / F4;
+    if (gk >= B.start[B.n]) return;
+    const int part = batch_find(B.start, B.n, gk);
+    const SmallArgs &A = B.s[part];
+    const int64_t k = gk - B.start[part];
+    *reinterpret_cast<f32x4 *>(A.abar + (A.n_owned + k) * F + (idx % F4) * 4) = f32x4{0.f, 0.f, 0.f, 0.f};
+}
+
 // gbar of the ghost rows: gbar_i = sum over the ghost's sub-row (its neighbours owned by this partition) of
 // w_e * abar_send(e).  w_e is the reverse edge's, which the forward pass kept (both edges of a pair have the
 // same length, hence the same filter value).  One wavefront per row, lane = feature, edges in row order.
 template <int F>
-__global__ void __launch_bounds__(256)
-k_ghost_gbar(int64_t n_ghost, int64_t n_owned, const int64_t *__restrict__ row_ptr, const int32_t *__restrict__ senders,
-             const int32_t *__restrict__ mirror, const float *__restrict__ wstore, const float *__restrict__ abar,
-             const int32_t *__restrict__ bond_of_edge, const float *__restrict__ wb, float *__restrict__ gbar)
+__global__ void __launch_bounds__(256) k_ghost_gbar(SmallBatch B)
 {
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-    const int64_t k = (int64_t)blockIdx.x * 4 + wave;
-    if (k >= n_ghost) return;
-    const int64_t r = n_owned + k;
+    const int64_t gk = (int64_t)blockIdx.x * 4 + wave;
+    if (gk >= B.start[B.n]) return;
+    const int part = batch_find(B.start, B.n, gk);
+    const SmallArgs &A = B.s[part];
+    const int64_t r = A.n_owned + (gk - B.start[part]);
     const unsigned f = lane & (F - 1);
-    const int64_t e0 = row_ptr[r], e1 = row_ptr[r + 1];
+    const int64_t e0 = A.row_ptr[r], e1 = A.row_ptr[r + 1];
     float acc = 0.f;
     for (int64_t eb = e0; eb < e1; eb += 16) {   // 16 edges at a time: ids by lane, then all rows in flight together
         const int n = (int)min((int64_t)16, e1 - eb);
         const int64_t el = min(eb + (lane & 15), e1 - 1);
-        const int32_t jl = senders[el], ml = mirror[el];
-        const int32_t bl = bond_of_edge ? bond_of_edge[ml] : -1;   // three-body variant: the reverse edge's bond
+        const int32_t jl = A.senders[el], ml = A.mirror[el];
+        const int32_t bl = A.bond_of_edge ? A.bond_of_edge[ml] : -1;   // three-body variant: the reverse edge's bond
         float wv[16], av[16];
 #pragma unroll
         for (int k = 0; k < 16; ++k) {
             const int64_t j = __builtin_amdgcn_readlane(jl, k), m = __builtin_amdgcn_readlane(ml, k);
             const int64_t b = __builtin_amdgcn_readlane(bl, k);
-            wv[k] = wstore[m * F + f];
-            if (b >= 0) wv[k] += wb[b * F + f];
-            av[k] = abar[j * F + f];
+            wv[k] = A.wstore[m * F + f];
+            if (b >= 0) wv[k] += A.wb[b * F + f];
+            av[k] = A.abar[j * F + f];
         }
 #pragma unroll
         for (int k = 0; k < 16; ++k)
             if (k < n) acc = fmaf(wv[k], av[k], acc);
     }
-    if (F == 64 || lane < F) gbar[r * F + f] = acc;
+    if (F == 64 || lane < F) A.gbar[r * F + f] = acc;
+}
+
+// Ghost-row gradients go back to the owners (the reverse of the border-node transfer): every border row adds the
+// rows its atom has as a ghost in the other partitions, in ascending partition order.  Gathered from the owner's
+// side, so one launch covers all partitions without two writers on a row (tab: the gbar arrays of all partitions).
+__global__ void k_border_add(SmallBatch B, int F, PtrTable tab, GhostIndex G)
+{
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int F4 = F / 4;
+    const int64_t bk = idx / F4;
+    if (bk >= B.start[B.n]) return;
+    const int part = batch_find(B.start, B.n, bk);
+    const SmallArgs &A = B.s[part];
+    const int64_t r = A.n_pure + (bk - B.start[part]);
+    const int c = (int)(idx % F4) * 4;
+    const int32_t u = A.nodes[r];
+    unsigned long long nb = G.needed_by[u];
+    const int32_t *loc = G.ghost_local + G.gbase[u];
+    float *dp = A.gbar + r * F + c;
+    f32x4 v = *reinterpret_cast<const f32x4 *>(dp);
+    while (nb) {
+        const int qq = __builtin_ctzll(nb);
+        nb &= nb - 1;
+        v += *reinterpret_cast<const f32x4 *>(tab.p[qq] + (int64_t)(*loc++) * F + c);
+    }
+    *reinterpret_cast<f32x4 *>(dp) = v;
 }
 
 // Three-body variant, ghost rows: a ghost atom i is the sender of bonds (j <- i) held by this partition; each pulls
@@ -280,21 +353,6 @@ __global__ void k_bond_force_ghost(int64_t n_ghost, int64_t n_owned, const int64
     floc[3 * r + 2] += fz;
 }
 
-__global__ void k_ghost_addback(int64_t n_ghost, int64_t n_owned, int F, const int32_t *__restrict__ owner,
-                                const int32_t *__restrict__ src, PtrTable tab, const float *__restrict__ mine)
-{
-    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int F4 = F / 4;
-    if (idx >= n_ghost * F4) return;
-    const int64_t k = idx / F4;
-    const int c = (int)(idx % F4) * 4;
-    float *dp = tab.p[owner[k]] + (int64_t)src[k] * F + c;
-    f32x4 v = *reinterpret_cast<const f32x4 *>(dp);
-    const f32x4 m = *reinterpret_cast<const f32x4 *>(mine + (n_owned + k) * F + c);
-    v += m;
-    *reinterpret_cast<f32x4 *>(dp) = v;
-}
-
 __device__ inline void unpack_shift(uint32_t p, int &a, int &b, int &c)
 {
     a = (int)(p >> 20) - 512;
@@ -304,25 +362,27 @@ __device__ inline void unpack_shift(uint32_t p, int &a, int &b, int &c)
 
 // F_loc[r] = sum_{e in local row r} dsum_e * rhat_e, rhat from fp64 positions; 16 lanes per row, 16 rows per block
 __global__ void __launch_bounds__(256)
-k_force_rows(int64_t n_rows, const int64_t *__restrict__ row_ptr, const int32_t *__restrict__ senders,
-             const uint32_t *__restrict__ shiftp, const float *__restrict__ dsum, const int32_t *__restrict__ nodes,
-             const double *__restrict__ pos, CellParams cp, float *__restrict__ floc)
+k_force_rows(SmallBatch B, const double *__restrict__ pos, CellParams cp)
 {
-    const int64_t r = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
-    if (r >= n_rows) return;   // whole groups of 16 lanes leave together; the shuffles below stay inside a group
+    const int64_t gr = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
+    if (gr >= B.start[B.n]) return;   // whole groups of 16 lanes leave together; the shuffles below stay inside a group
+    const int part = batch_find(B.start, B.n, gr);
+    const SmallArgs &A = B.s[part];
+    const int64_t r = gr - B.start[part];
+    const int32_t *nodes = A.nodes;
     const int64_t ig = nodes ? nodes[r] : r;
     const double xi = pos[3 * ig], yi = pos[3 * ig + 1], zi = pos[3 * ig + 2];
     double fx = 0, fy = 0, fz = 0;
-    const int64_t e1 = row_ptr[r + 1];
-    for (int64_t e = row_ptr[r] + (threadIdx.x & 15); e < e1; e += 16) {
-        const int64_t jl = senders[e];
+    const int64_t e1 = A.row_ptr[r + 1];
+    for (int64_t e = A.row_ptr[r] + (threadIdx.x & 15); e < e1; e += 16) {
+        const int64_t jl = A.senders[e];
         const int64_t jg = nodes ? nodes[jl] : jl;
         int S0, S1, S2;
-        unpack_shift(shiftp[e], S0, S1, S2);
+        unpack_shift(A.shiftp[e], S0, S1, S2);
         const double t0 = (pos[3 * jg] - xi) + (((double)S0 * cp.C[0] + (double)S1 * cp.C[3]) + (double)S2 * cp.C[6]);
         const double t1 = (pos[3 * jg + 1] - yi) + (((double)S0 * cp.C[1] + (double)S1 * cp.C[4]) + (double)S2 * cp.C[7]);
         const double t2 = (pos[3 * jg + 2] - zi) + (((double)S0 * cp.C[2] + (double)S1 * cp.C[5]) + (double)S2 * cp.C[8]);
-        const double s = (double)dsum[e] / sqrt((t0 * t0 + t1 * t1) + t2 * t2);
+        const double s = (double)A.dsum[e] / sqrt((t0 * t0 + t1 * t1) + t2 * t2);
         fx += s * t0;
         fy += s * t1;
         fz += s * t2;
@@ -334,43 +394,64 @@ k_force_rows(int64_t n_rows, const int64_t *__restrict__ row_ptr, const int32_t 
         fz += __shfl_xor(fz, off, 64);
     }
     if ((threadIdx.x & 15) == 0) {
-        floc[3 * r] = (float)fx;
-        floc[3 * r + 1] = (float)fy;
-        floc[3 * r + 2] = (float)fz;
+        A.floc[3 * r] = (float)fx;
+        A.floc[3 * r + 1] = (float)fy;
+        A.floc[3 * r + 2] = (float)fz;
     }
 }
 
-// owned rows: forces[global] = F_loc ; atom_energy[global] = eps
-__global__ void k_store_owned(int64_t n_owned, const int32_t *__restrict__ nodes, const float *__restrict__ floc,
-                              const float *__restrict__ eps, float *__restrict__ forces, float *__restrict__ atom_energy)
+__global__ void k_zero_floc(SmallBatch B)
 {
-    const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (r >= n_owned) return;
-    const int64_t u = nodes ? nodes[r] : r;
-    forces[3 * u] = floc[3 * r];
-    forces[3 * u + 1] = floc[3 * r + 1];
-    forces[3 * u + 2] = floc[3 * r + 2];
-    if (atom_energy) atom_energy[u] = eps[r];
+    const int64_t gr = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (gr >= B.start[B.n]) return;
+    const int part = batch_find(B.start, B.n, gr);
+    const int64_t r = gr - B.start[part];
+    float *f = B.s[part].floc + 3 * r;
+    f[0] = 0.f;
+    f[1] = 0.f;
+    f[2] = 0.f;
 }
 
-// ghost rows: forces[global] += F_loc (position gradients of ghost atoms go back to their owners)
-__global__ void k_addback_ghost_forces(int64_t n_ghost, int64_t n_owned, const int32_t *__restrict__ nodes,
-                                       const float *__restrict__ floc, float *__restrict__ forces)
+// owned rows: forces[global] = F_loc (+ for a border atom, in ascending partition order, the position gradients its
+// ghost rows collected in the other partitions: gathered by the owner, one writer per atom); atom_energy[global] = eps
+// (tab: the floc arrays of all partitions)
+__global__ void k_store_owned(SmallBatch B, PtrTable tab, GhostIndex G, float *__restrict__ forces,
+                              float *__restrict__ atom_energy)
 {
-    const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (k >= n_ghost) return;
-    const int64_t r = n_owned + k;
-    const int64_t u = nodes[r];
-    forces[3 * u] += floc[3 * r];
-    forces[3 * u + 1] += floc[3 * r + 1];
-    forces[3 * u + 2] += floc[3 * r + 2];
+    const int64_t gr = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (gr >= B.start[B.n]) return;
+    const int part = batch_find(B.start, B.n, gr);
+    const SmallArgs &A = B.s[part];
+    const int64_t r = gr - B.start[part];
+    const int64_t u = A.nodes ? A.nodes[r] : r;
+    float fx = A.floc[3 * r], fy = A.floc[3 * r + 1], fz = A.floc[3 * r + 2];
+    if (r >= A.n_pure) {
+        unsigned long long nb = G.needed_by[u];
+        const int32_t *loc = G.ghost_local + G.gbase[u];
+        while (nb) {
+            const int qq = __builtin_ctzll(nb);
+            nb &= nb - 1;
+            const float *fg = tab.p[qq] + 3 * (int64_t)(*loc++);
+            fx += fg[0];
+            fy += fg[1];
+            fz += fg[2];
+        }
+    }
+    forces[3 * u] = fx;
+    forces[3 * u + 1] = fy;
+    forces[3 * u + 2] = fz;
+    if (atom_energy) atom_energy[u] = A.eps[r];
 }
 
 // fixed-shape fp64 reduction of the per-atom energies: 1024-element blocks, then one block over the partials
-__global__ void __launch_bounds__(256) k_energy_partial(int64_t n, const float *__restrict__ eps, double *__restrict__ part)
+__global__ void __launch_bounds__(256) k_energy_partial(SmallBatch B, double *__restrict__ part)
 {
     __shared__ double sh[4];
-    const int64_t base = (int64_t)blockIdx.x * 1024;
+    // start[] counts 1024-element blocks here; the partial sums of all partitions sit one after another in `part`
+    const int q = batch_find(B.start, B.n, (int64_t)blockIdx.x);
+    const int64_t n = B.s[q].n_owned;
+    const float *eps = B.s[q].eps;
+    const int64_t base = ((int64_t)blockIdx.x - B.start[q]) * 1024;
     double s = 0;
     for (int k = threadIdx.x; k < 1024; k += 256)
         if (base + k < n) s += (double)eps[base + k];

@@ -616,26 +616,33 @@ __device__ inline int part_find(const int64_t *start, int P, int64_t x)
     return p;
 }
 
-// length of each local row: owned rows keep their whole global row, ghost rows keep only the senders owned by the
-// partition; ghost rows also record their owner and their row inside the owner.  One wavefront per row, all
-// partitions in one launch.  Partition q's lengths start at rowlen[row0[q] + q] (one closing entry per partition,
-// zero-filled beforehand, so that one scan yields every partition's n_local + 1 offsets).
+// Length of each local row.  Owned rows keep their whole global row (one thread per owned atom, which knows its
+// partition and row from its owner record); ghost rows keep only the senders owned by the partition and also record
+// their owner and their row inside the owner (one wavefront per ghost row).  Partition q's lengths start at
+// rowlen[row0[q] + q] (one closing entry per partition, zero-filled beforehand, so that one scan yields every
+// partition's n_local + 1 offsets).
+__global__ void k_owned_rowlen(int64_t N, PartTab T, const OwnRec *__restrict__ own_rec, const int64_t *__restrict__ row_ptr,
+                               int32_t *rowlen)
+{
+    const int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (u >= N) return;
+    const OwnRec rec = own_rec[u];
+    rowlen[T.row0[rec.slab] + rec.slab + rec.local] = (int32_t)(row_ptr[u + 1] - row_ptr[u]);
+}
+
 __global__ void __launch_bounds__(256)
-k_local_rowlen(PartTab T, const int32_t *__restrict__ nodes, const int64_t *__restrict__ row_ptr,
+k_ghost_rowlen(PartTab T, const int32_t *__restrict__ nodes, const int64_t *__restrict__ row_ptr,
                const int32_t *__restrict__ senders, const int32_t *__restrict__ slab_of,
                const OwnRec *__restrict__ own_rec, int32_t *rowlen, int32_t *ghost_owner, int32_t *ghost_src)
 {
     const int lane = threadIdx.x & 63;
-    const int64_t x = (int64_t)xcd_block() * 4 + (threadIdx.x >> 6);
-    if (x >= T.row0[T.P]) return;
-    const int q = part_find(T.row0, T.P, x);
-    const int64_t r = x - T.row0[q];
+    const int64_t k = (int64_t)xcd_block() * 4 + (threadIdx.x >> 6);   // ghost entry, numbered across the partitions
+    if (k >= T.ghost0[T.P]) return;
+    const int q = part_find(T.ghost0, T.P, k);
+    const int64_t r = T.n_owned[q] + (k - T.ghost0[q]);
+    const int64_t x = T.row0[q] + r;
     const int32_t u = nodes[x];
     const int64_t e0 = row_ptr[u], e1 = row_ptr[u + 1];
-    if (r < T.n_owned[q]) {
-        if (lane == 0) rowlen[x + q] = (int32_t)(e1 - e0);
-        return;
-    }
     int cnt = 0;
     for (int64_t eb = e0; eb < e1; eb += 64) {
         const int64_t e = eb + lane;
@@ -644,7 +651,6 @@ k_local_rowlen(PartTab T, const int32_t *__restrict__ nodes, const int64_t *__re
     }
     if (lane == 0) {
         rowlen[x + q] = cnt;
-        const int64_t k = T.ghost0[q] + (r - T.n_owned[q]);
         ghost_owner[k] = own_rec[u].slab;
         ghost_src[k] = own_rec[u].local;
     }
@@ -674,55 +680,74 @@ __global__ void k_local_rowptr(PartTab T, const int64_t *__restrict__ row_abs, c
     }
 }
 
-// Local CSR of every partition (one wavefront per local row).  Owned rows copy their global row with local sender
-// ids; a ghost row keeps the senders its partition owns.  Reverse-edge index: an owned sender's local row is its
-// whole global row, so the reverse edge keeps its offset inside the row; the reverse of an edge from a ghost sender
-// lies in that ghost's sub-row and is written, together with its own entry, by the wavefront that fills the sub-row
-// (which knows both positions), so no search is needed.
+// Local CSR of every partition.
+//
+// Owned rows (k_local_fill_owned, one thread per edge of the whole graph): an edge belongs to the partition of its
+// receiver, and an owned row is its whole global row, so edge e goes to position e + delta(receiver) of that
+// partition's arrays, with the sender's local id; if the sender is owned by the same partition the reverse edge
+// keeps its offset inside the sender's row (gmirror[e] + delta(sender)).
+// Ghost rows (k_local_fill_ghost, one wavefront per ghost row): the senders the partition owns, in row order.  Each
+// such edge (u <- k) is the reverse of the owned-row edge (k <- u), whose position follows from the whole graph's
+// reverse-edge index; the wavefront writes both entries of the pair, so no search is needed.
 __global__ void __launch_bounds__(256)
-k_local_fill(PartTab T, const int32_t *__restrict__ nodes, const int64_t *__restrict__ row_ptr,
-             const int32_t *__restrict__ senders, const uint32_t *__restrict__ shiftp, const float *__restrict__ d,
-             const int32_t *__restrict__ gmirror, const unsigned long long *__restrict__ needed_by,
-             const OwnRec *__restrict__ own_rec, const int32_t *__restrict__ gbase,
-             const int32_t *__restrict__ ghost_local, const int64_t *__restrict__ row_abs, int32_t *lsenders,
-             int32_t *lrecv, uint32_t *lshiftp, float *ld, int32_t *lmirror)
+k_local_fill_owned(int64_t E, PartTab T, const int32_t *__restrict__ recv, const int32_t *__restrict__ senders,
+                   const uint32_t *__restrict__ shiftp, const float *__restrict__ d, const int32_t *__restrict__ gmirror,
+                   const unsigned long long *__restrict__ needed_by, const OwnRec *__restrict__ own_rec,
+                   const int32_t *__restrict__ gbase, const int32_t *__restrict__ ghost_local,
+                   const int64_t *__restrict__ row_abs, int32_t *lsenders, int32_t *lrecv, uint32_t *lshiftp, float *ld,
+                   int32_t *lmirror)
+{
+    const int64_t e = (int64_t)xcd_block() * blockDim.x + threadIdx.x;
+    if (e >= E) return;
+    const OwnRec ri = own_rec[recv[e]];
+    const int q = ri.slab;
+    const int64_t o = row_abs[T.row0[q] + q] + (e + ri.delta);   // the partition's first edge + position inside it
+    const int32_t j = senders[e];
+    const OwnRec rj = own_rec[j];
+    const bool jown = rj.slab == q;
+    lsenders[o] = jown ? rj.local : ghost_local[gbase[j] + __popcll(needed_by[j] & ((1ull << q) - 1ull))];
+    lshiftp[o] = shiftp[e];
+    lrecv[o] = ri.local;
+    ld[o] = d[e];
+    if (jown) lmirror[o] = (int32_t)((int64_t)gmirror[e] + rj.delta);
+}
+
+__global__ void __launch_bounds__(256)
+k_local_fill_ghost(PartTab T, const int32_t *__restrict__ nodes, const int64_t *__restrict__ row_ptr,
+                   const int32_t *__restrict__ senders, const uint32_t *__restrict__ shiftp, const float *__restrict__ d,
+                   const int32_t *__restrict__ gmirror, const OwnRec *__restrict__ own_rec,
+                   const int64_t *__restrict__ row_abs, int32_t *lsenders, int32_t *lrecv, uint32_t *lshiftp, float *ld,
+                   int32_t *lmirror)
 {
     const int lane = threadIdx.x & 63;
-    const int64_t x = (int64_t)xcd_block() * 4 + (threadIdx.x >> 6);
-    if (x >= T.row0[T.P]) return;
-    const int q = part_find(T.row0, T.P, x);
-    const int64_t r = x - T.row0[q];
+    const int64_t k = (int64_t)xcd_block() * 4 + (threadIdx.x >> 6);
+    if (k >= T.ghost0[T.P]) return;
+    const int q = part_find(T.ghost0, T.P, k);
+    const int64_t r = T.n_owned[q] + (k - T.ghost0[q]);
+    const int64_t x = T.row0[q] + r;
     const int32_t u = nodes[x];
     const int64_t e0 = row_ptr[u], e1 = row_ptr[u + 1];
-    const int64_t first = T.row0[q] + q;          // the partition's first entry in row_abs / lrow_ptr
-    const int64_t ebase = row_abs[first];         // its first edge in the concatenated edge arrays
-    int64_t out = row_abs[x + q];                 // absolute position of the row's first edge
-    const bool owned = r < T.n_owned[q];
-    const unsigned long long lt = (1ull << lane) - 1ull, below = (1ull << q) - 1ull;
+    const int64_t ebase = row_abs[T.row0[q] + q];   // the partition's first edge in the concatenated edge arrays
+    int64_t out = row_abs[x + q];                   // absolute position of the row's first edge
+    const unsigned long long lt = (1ull << lane) - 1ull;
     for (int64_t eb = e0; eb < e1; eb += 64) {
         const int64_t e = eb + lane;
-        int32_t j = 0;
-        bool keep = false, jown = false;
+        bool keep = false;
         OwnRec rec{};
         if (e < e1) {
-            j = senders[e];
-            rec = own_rec[j];
-            jown = rec.slab == q;
-            keep = owned || jown;
+            rec = own_rec[senders[e]];
+            keep = rec.slab == q;
         }
         const unsigned long long m = __ballot(keep);
         if (keep) {
             const int64_t o = out + __popcll(m & lt);
-            const int32_t jl = jown ? rec.local : ghost_local[gbase[j] + __popcll(needed_by[j] & below)];
-            lsenders[o] = jl;
+            const int32_t partner = (int32_t)((int64_t)gmirror[e] + rec.delta);   // the owned row's edge from this ghost
+            lsenders[o] = rec.local;
             lshiftp[o] = shiftp[e];
             lrecv[o] = (int32_t)r;
             ld[o] = d[e];
-            if (jown) {
-                const int32_t partner = (int32_t)((int64_t)gmirror[e] + rec.delta);
-                lmirror[o] = partner;
-                if (!owned) lmirror[ebase + partner] = (int32_t)(o - ebase);   // the owned row's edge from this ghost
-            }
+            lmirror[o] = partner;
+            lmirror[ebase + partner] = (int32_t)(o - ebase);
         }
         out += __popcll(m);
     }
@@ -1323,10 +1348,13 @@ int build_graph_impl(mlip_graph *g, const double *positions, const double *cell,
                                                            g->local_in_owner.as<OwnRec>(), st.ghost_local.as<int32_t>());
         MLIP_HIP(hipGetLastError());
         MLIP_HIP(hipMemsetAsync(st.rowlen.p, 0, (size_t)(TL + P + 1) * 4, s));
-        k_local_rowlen<<<grid8((TL + 3) / 4), 256, 0, s>>>(T, st.nodes.as<int32_t>(), g->row_ptr.as<int64_t>(),
-                                                                g->senders.as<int32_t>(), g->slab_of.as<int32_t>(),
-                                                                g->local_in_owner.as<OwnRec>(), st.rowlen.as<int32_t>(),
-                                                                st.ghost_owner.as<int32_t>(), st.ghost_src.as<int32_t>());
+        k_owned_rowlen<<<blocks_for(N, 256), 256, 0, s>>>(N, T, g->local_in_owner.as<OwnRec>(), g->row_ptr.as<int64_t>(),
+                                                         st.rowlen.as<int32_t>());
+        if (n_ghost_total > 0)
+            k_ghost_rowlen<<<grid8((n_ghost_total + 3) / 4), 256, 0, s>>>(
+                T, st.nodes.as<int32_t>(), g->row_ptr.as<int64_t>(), g->senders.as<int32_t>(), g->slab_of.as<int32_t>(),
+                g->local_in_owner.as<OwnRec>(), st.rowlen.as<int32_t>(), st.ghost_owner.as<int32_t>(),
+                st.ghost_src.as<int32_t>());
         MLIP_HIP(hipGetLastError());
         MLIP_TRY(scan_i32_to_i64(st.rowlen.as<int32_t>(), st.row_abs.as<int64_t>(), TL + P, g->scan_tmp, s));
         int64_t *dsz = st.sizes.as<int64_t>() + nmark;
@@ -1364,13 +1392,20 @@ int build_graph_impl(mlip_graph *g, const double *positions, const double *cell,
         MLIP_TRY(st.mirror.ensure(ne * 4));
         MLIP_TRY(st.d.ensure(ne * 4));
         MLIP_TRY(st.chunk_row.ensure((size_t)chunk_total * 4));
-        if (TL > 0) {
-            k_local_fill<<<grid8((TL + 3) / 4), 256, 0, s>>>(
+        if (E > 0) {
+            k_local_fill_owned<<<grid8(blocks_for(E, 256)), 256, 0, s>>>(
+                E, T, g->recv.as<int32_t>(), g->senders.as<int32_t>(), g->shiftp.as<uint32_t>(), g->d.as<float>(),
+                g->mirror.as<int32_t>(), g->needed_by.as<unsigned long long>(), g->local_in_owner.as<OwnRec>(),
+                st.gbase.as<int32_t>(), st.ghost_local.as<int32_t>(), st.row_abs.as<int64_t>(), st.senders.as<int32_t>(),
+                st.recv.as<int32_t>(), st.shiftp.as<uint32_t>(), st.d.as<float>(), st.mirror.as<int32_t>());
+            MLIP_HIP(hipGetLastError());
+        }
+        if (n_ghost_total > 0) {
+            k_local_fill_ghost<<<grid8((n_ghost_total + 3) / 4), 256, 0, s>>>(
                 T, st.nodes.as<int32_t>(), g->row_ptr.as<int64_t>(), g->senders.as<int32_t>(), g->shiftp.as<uint32_t>(),
-                g->d.as<float>(), g->mirror.as<int32_t>(), g->needed_by.as<unsigned long long>(),
-                g->local_in_owner.as<OwnRec>(), st.gbase.as<int32_t>(), st.ghost_local.as<int32_t>(),
-                st.row_abs.as<int64_t>(), st.senders.as<int32_t>(), st.recv.as<int32_t>(),
-                st.shiftp.as<uint32_t>(), st.d.as<float>(), st.mirror.as<int32_t>());
+                g->d.as<float>(), g->mirror.as<int32_t>(), g->local_in_owner.as<OwnRec>(), st.row_abs.as<int64_t>(),
+                st.senders.as<int32_t>(), st.recv.as<int32_t>(), st.shiftp.as<uint32_t>(), st.d.as<float>(),
+                st.mirror.as<int32_t>());
             MLIP_HIP(hipGetLastError());
         }
         k_chunk_rows_parts<<<blocks_for(chunk_total, 256), 256, 0, s>>>(T, st.row_ptr.as<int64_t>(), st.chunk_row.as<int32_t>());

@@ -286,6 +286,7 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
             a.floc = v.ws.floc;
             a.eps = v.ws.eps;
             a.dsum = v.ws.dsum;
+            a.d = v.d;
             a.wstore = (layer >= 1) ? v.ws.wst + (size_t)(layer - 1) * (size_t)v.n_edges_owned * F : nullptr;
             a.bond_of_edge = (bw && v.bonds.n > 0) ? v.bonds.of_edge.as<int32_t>() : nullptr;
             a.wb = (bw && v.bonds.n > 0 && layer >= 0)

@@ -381,6 +381,194 @@ k_sort_rows(int64_t N, CellParams cp, const double *__restrict__ pos, const int6
     }
 }
 
+// ---- pair-wise neighbour search
+//
+// Every pair {(i <- j, S), (j <- i, -S)} is tested once, by the atom that comes first in cell order: the thread of
+// sorted position s looks only at positions q > s (cells after its own in the cell order are taken whole, cells
+// before it are skipped, its own cell from s on; q = s only for images of the atom itself, of which the one with
+// the larger packed shift is taken).  The edge predicate is symmetric bit for bit (negating every term negates the
+// differences exactly), so one test decides both edges.  The finder parks the key of its own edge in its "own"
+// staging row (private counter) and the key of the reverse edge in the partner's "partner" staging row (atomic
+// counter), and notes in each entry the slot of the other one.  After the rows are sorted, the reverse-edge index
+// follows from these notes without any search: half the candidate loads of the one-sided search and no binary
+// searches.  Rows are sorted afterwards, so the order in which the atomics hand out slots does not matter.
+constexpr int kOwn = 64, kPar = 64;   // staging slots per atom for edges found by the atom itself / by its partners
+
+__global__ void k_neighbours_pairs(int64_t N, CellParams cp, const int32_t *__restrict__ cell_start,
+                                   const int32_t *__restrict__ sid, const double *__restrict__ sx,
+                                   const double *__restrict__ sy, const double *__restrict__ sz,
+                                   const uint32_t *__restrict__ swrap, const int32_t *__restrict__ cell_of,
+                                   uint64_t *stage_own, uint64_t *stage_par, uint8_t *pslot_own, uint8_t *pslot_par,
+                                   int32_t *n_own, int32_t *n_par, int32_t *err)
+{
+    const int64_t s = (int64_t)xcd_block() * blockDim.x + threadIdx.x;
+    if (s >= N) return;
+    const int32_t i = sid[s];
+    const double xi = sx[s], yi = sy[s], zi = sz[s];
+    int wi0, wi1, wi2;
+    unpack3(swrap[s], wi0, wi1, wi2);
+    const int32_t c = cell_of[i];
+    int cr = c;
+    const int b2 = cr % cp.nb[2];
+    cr /= cp.nb[2];
+    const int b1 = cr % cp.nb[1];
+    const int b0 = cr / cp.nb[1];
+    int32_t cnt = 0;
+    bool coincident = false, overflow = false;
+
+    struct Rec {   // one candidate: atom id, wrap counts, position
+        int32_t j;
+        uint32_t w;
+        double x, y, z;
+    };
+    auto load = [&](Rec &r, int32_t q) {
+        r.j = sid[q];
+        r.w = swrap[q];
+        r.x = sx[q];
+        r.y = sy[q];
+        r.z = sz[q];
+    };
+    // the pair test for the candidate at sorted position q found in a bin that is (i0, i1, i2) cells away by wrap-around
+    auto test = [&](const Rec &r, bool self, int i0, int i1, int i2) {
+        int wj0, wj1, wj2;
+        unpack3(r.w, wj0, wj1, wj2);
+        const int S0 = i0 - wj0 + wi0, S1 = i1 - wj1 + wi1, S2 = i2 - wj2 + wi2;
+        const uint32_t sp = pack3(S0, S1, S2), sn = pack3(-S0, -S1, -S2);
+        if (self && sp <= sn) return;   // the atom itself (zero shift) or the half of its image pairs taken from the other side
+        const double t0 = (r.x - xi) + (((double)S0 * cp.C[0] + (double)S1 * cp.C[3]) + (double)S2 * cp.C[6]);
+        const double t1 = (r.y - yi) + (((double)S0 * cp.C[1] + (double)S1 * cp.C[4]) + (double)S2 * cp.C[7]);
+        const double t2 = (r.z - zi) + (((double)S0 * cp.C[2] + (double)S1 * cp.C[5]) + (double)S2 * cp.C[8]);
+        const double d2 = (t0 * t0 + t1 * t1) + t2 * t2;
+        if (d2 <= cp.rc2) {
+            if (d2 == 0.0) coincident = true;
+            const int a = cnt++;
+            if (a < kOwn) stage_own[(int64_t)i * kOwn + a] = ((uint64_t)(uint32_t)r.j << 32) | sp;
+            else overflow = true;
+        }
+    };
+
+    for (int dx = -cp.reach[0]; dx <= cp.reach[0]; ++dx) {
+        int c0 = b0 + dx;
+        const int i0 = floordiv(c0, cp.nb[0]);
+        c0 -= i0 * cp.nb[0];
+        for (int dy = -cp.reach[1]; dy <= cp.reach[1]; ++dy) {
+            int c1 = b1 + dy;
+            const int i1 = floordiv(c1, cp.nb[1]);
+            c1 -= i1 * cp.nb[1];
+            for (int dz = -cp.reach[2]; dz <= cp.reach[2]; ++dz) {
+                int c2 = b2 + dz;
+                const int i2 = floordiv(c2, cp.nb[2]);
+                c2 -= i2 * cp.nb[2];
+                const int32_t cc = (c0 * cp.nb[1] + c1) * cp.nb[2] + c2;
+                if (cc < c) continue;   // those atoms come before this one: they find the pair
+                const int32_t qe = cell_start[cc + 1];
+                int32_t q = (cc == c) ? (int32_t)s : cell_start[cc];
+                Rec nxt{};
+                if (q < qe) load(nxt, q);
+                for (; q < qe; ++q) {
+                    const Rec cur = nxt;
+                    if (q + 1 < qe) load(nxt, q + 1);
+                    test(cur, q == (int32_t)s, i0, i1, i2);
+                }
+            }
+        }
+    }
+    n_own[i] = cnt;
+    if (overflow) atomicOr(err, FLAG_STAGE_OVERFLOW);
+    if (coincident) atomicOr(err, ERR_COINCIDENT);
+}
+
+// The reverse edges, in a pass of their own over what the search parked (one thread per own slot): the slot that a
+// partner's counter hands out is not needed during the search, and the atomics travel past the L2, so they are
+// issued from as many threads as possible instead of one after another inside the search loop.
+__global__ void k_pair_partners(int64_t N, const int32_t *__restrict__ n_own, const uint64_t *__restrict__ stage_own,
+                                uint64_t *stage_par, uint8_t *pslot_own, uint8_t *pslot_par, int32_t *n_par, int32_t *err)
+{
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t i = idx / kOwn;
+    const int a = (int)(idx % kOwn);
+    if (i >= N || a >= n_own[i]) return;
+    const uint64_t key = stage_own[idx];
+    const int64_t j = (int64_t)(key >> 32);
+    int S0, S1, S2;
+    unpack3((uint32_t)key, S0, S1, S2);
+    const int b = atomicAdd(&n_par[j], 1);
+    pslot_own[idx] = (uint8_t)(b < 255 ? b : 255);
+    if (b < kPar) {
+        stage_par[j * kPar + b] = ((uint64_t)(uint32_t)i << 32) | pack3(-S0, -S1, -S2);
+        pslot_par[j * kPar + b] = (uint8_t)a;
+    } else {
+        atomicOr(err, FLAG_STAGE_OVERFLOW);
+    }
+}
+
+__global__ void k_pair_counts(int64_t N, const int32_t *__restrict__ n_own, const int32_t *__restrict__ n_par, int32_t *counts)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < N) counts[i] = n_own[i] + n_par[i];
+}
+
+// k_sort_rows for the pair-wise search: the row's keys come from the atom's two staging rows; the rank of every
+// staging slot is kept for the reverse-edge index
+__global__ void __launch_bounds__(64)
+k_sort_rows_pairs(int64_t N, CellParams cp, const double *__restrict__ pos, const int64_t *__restrict__ row_ptr,
+                  const uint64_t *__restrict__ stage_own, const uint64_t *__restrict__ stage_par,
+                  const int32_t *__restrict__ n_own, uint8_t *rank_own, uint8_t *rank_par, int32_t *senders, int32_t *recv,
+                  uint32_t *shiftp, float *d)
+{
+    __shared__ uint64_t lds[kOwn + kPar];
+    const int64_t i = xcd_block();
+    if (i >= N) return;   // (whole block: the grid is rounded up to a multiple of 8)
+    const int lane = threadIdx.x;
+    const int64_t base = row_ptr[i];
+    const int n = (int)(row_ptr[i + 1] - base);
+    const int no = n_own[i];
+    for (int m = lane; m < n; m += 64)
+        lds[m] = (m < no) ? stage_own[i * kOwn + m] : stage_par[i * kPar + (m - no)];
+    __syncthreads();
+    const double xi = pos[3 * i], yi = pos[3 * i + 1], zi = pos[3 * i + 2];
+    for (int m = lane; m < n; m += 64) {
+        const uint64_t key = lds[m];
+        int rank = 0;
+        for (int t = 0; t < n; ++t) rank += (lds[t] < key) ? 1 : 0;
+        if (m < no) rank_own[i * kOwn + m] = (uint8_t)rank; else rank_par[i * kPar + (m - no)] = (uint8_t)rank;
+        const int64_t e = base + rank;
+        const int32_t j = (int32_t)(key >> 32);
+        const uint32_t sp = (uint32_t)key;
+        int S0, S1, S2;
+        unpack3(sp, S0, S1, S2);
+        const double t0 = (pos[3 * (int64_t)j] - xi) + (((double)S0 * cp.C[0] + (double)S1 * cp.C[3]) + (double)S2 * cp.C[6]);
+        const double t1 = (pos[3 * (int64_t)j + 1] - yi) + (((double)S0 * cp.C[1] + (double)S1 * cp.C[4]) + (double)S2 * cp.C[7]);
+        const double t2 = (pos[3 * (int64_t)j + 2] - zi) + (((double)S0 * cp.C[2] + (double)S1 * cp.C[5]) + (double)S2 * cp.C[8]);
+        const double d2 = (t0 * t0 + t1 * t1) + t2 * t2;
+        senders[e] = j;
+        shiftp[e] = sp;
+        recv[e] = (int32_t)i;
+        d[e] = (float)sqrt(d2);
+    }
+}
+
+// reverse-edge index from the pair notes: the edge in own slot a of atom i and the edge in partner slot b of atom j
+// are each other's reverse; 32 lanes per atom
+__global__ void __launch_bounds__(256)
+k_mirror_pairs(int64_t N, const int64_t *__restrict__ row_ptr, const uint64_t *__restrict__ stage_own,
+               const uint8_t *__restrict__ pslot_own, const int32_t *__restrict__ n_own,
+               const uint8_t *__restrict__ rank_own, const uint8_t *__restrict__ rank_par, int32_t *__restrict__ mirror)
+{
+    const int64_t i = (int64_t)xcd_block() * 8 + (threadIdx.x >> 5);
+    if (i >= N) return;
+    const int no = n_own[i];
+    const int64_t rp = row_ptr[i];
+    for (int a = threadIdx.x & 31; a < no; a += 32) {
+        const int64_t j = (int64_t)(stage_own[i * kOwn + a] >> 32);
+        const int b = pslot_own[i * kOwn + a];
+        const int32_t e = (int32_t)(rp + rank_own[i * kOwn + a]);
+        const int32_t m = (int32_t)(row_ptr[j] + rank_par[j * kPar + b]);
+        mirror[e] = m;
+        mirror[m] = e;
+    }
+}
+
 // chunk_row[c] = first row whose first edge lies at or after c * kChunkEdges; chunk_row[n_chunks] = n_rows.
 __global__ void k_chunk_rows(int64_t n_rows, int64_t n_chunks, const int64_t *__restrict__ row_ptr,
                              int32_t *__restrict__ chunk_row)
@@ -1036,8 +1224,8 @@ int build_bonds_impl(mlip_graph *g, SlabView &v, double r_bond, int p_envelope)
 
 namespace {
 
-struct CsrOut {   // where a neighbour search puts its receiver-sorted CSR
-    DevBuf *row_ptr, *senders, *recv, *shiftp, *d;
+struct CsrOut {   // where a neighbour search puts its receiver-sorted CSR (mirror: the reverse-edge index, or nullptr)
+    DevBuf *row_ptr, *senders, *recv, *shiftp, *d, *mirror;
 };
 
 // reads the edge count and the flag words after the first pass of either route and turns the flags into errors
@@ -1101,38 +1289,84 @@ int search_csr(mlip_graph *g, const CellParams &cp, int64_t N, CsrOut out, int64
                                                     g->sid.as<int32_t>(), g->sx.as<double>(), g->sy.as<double>(),
                                                     g->sz.as<double>(), g->swrap.as<uint32_t>());
     MLIP_HIP(hipGetLastError());
-    // the counting pass parks what it finds in fixed-width staging rows (768 B per atom), unless that would take
-    // more than 8 GB; the sort then reads the staging rows and the second neighbour pass is not needed
-    const bool use_stage = (size_t)N * kStage * 8 <= ((size_t)8 << 30);
-    if (use_stage) MLIP_TRY(g->stage.ensure((size_t)N * kStage * 8));
-    k_neighbours<false><<<grid8(blocks_for(N, 128)), 128, 0, s>>>(
-        N, cp, g->cell_start.as<int32_t>(), g->sid.as<int32_t>(), g->sx.as<double>(), g->sy.as<double>(),
-        g->sz.as<double>(), g->swrap.as<uint32_t>(), g->cell_of.as<int32_t>(), g->counts.as<int32_t>(), nullptr,
-        use_stage ? g->stage.as<uint64_t>() : nullptr, err);
-    MLIP_HIP(hipGetLastError());
-    MLIP_TRY(scan_i32_to_i64(g->counts.as<int32_t>(), out.row_ptr->as<int64_t>(), N, g->scan_tmp, s));
     int64_t E = 0;
     int32_t flags = 0;
-    MLIP_TRY(read_counts_and_flags(g, out.row_ptr->as<int64_t>() + N, err, &E, &flags));   // first synchronisation
-    const size_t Ecap = (size_t)std::max<int64_t>(E, 1);
-    const bool staged = use_stage && !(flags & FLAG_STAGE_OVERFLOW);
-    if (!staged) MLIP_TRY(g->keys.ensure(Ecap * 8));
-    MLIP_TRY(out.senders->ensure(Ecap * 4));
-    MLIP_TRY(out.shiftp->ensure(Ecap * 4));
-    MLIP_TRY(out.recv->ensure(Ecap * 4));
-    MLIP_TRY(out.d->ensure(Ecap * 4));
-    if (!staged) {
+    // Pair-wise search (every pair tested once, reverse-edge index without a search) unless its staging rows
+    // (1.25 KB per atom) would take more than 8 GB; an atom with more neighbours than the staging rows hold
+    // (kOwn found by itself, kPar by its partners) sets FLAG_STAGE_OVERFLOW and the one-sided search below runs instead
+    bool done = false;
+    if ((size_t)N * (kOwn + kPar) * 10 <= ((size_t)8 << 30)) {
+        MLIP_TRY(g->stage.ensure((size_t)N * (kOwn + kPar) * 8));
+        MLIP_TRY(g->pair_aux.ensure((size_t)N * (8 + 2 * (kOwn + kPar))));
+        uint64_t *stage_own = g->stage.as<uint64_t>(), *stage_par = stage_own + (size_t)N * kOwn;
+        int32_t *n_own = g->pair_aux.as<int32_t>(), *n_par = n_own + N;
+        uint8_t *pslot_own = reinterpret_cast<uint8_t *>(n_par + N), *pslot_par = pslot_own + (size_t)N * kOwn;
+        uint8_t *rank_own = pslot_par + (size_t)N * kPar, *rank_par = rank_own + (size_t)N * kOwn;
+        MLIP_HIP(hipMemsetAsync(n_par, 0, (size_t)N * 4, s));
+        k_neighbours_pairs<<<grid8(blocks_for(N, 128)), 128, 0, s>>>(
+            N, cp, g->cell_start.as<int32_t>(), g->sid.as<int32_t>(), g->sx.as<double>(), g->sy.as<double>(),
+            g->sz.as<double>(), g->swrap.as<uint32_t>(), g->cell_of.as<int32_t>(), stage_own, stage_par, pslot_own,
+            pslot_par, n_own, n_par, err);
+        MLIP_HIP(hipGetLastError());
+        k_pair_partners<<<blocks_for(N * kOwn, 256), 256, 0, s>>>(N, n_own, stage_own, stage_par, pslot_own, pslot_par, n_par, err);
+        MLIP_HIP(hipGetLastError());
+        k_pair_counts<<<blocks_for(N, 256), 256, 0, s>>>(N, n_own, n_par, g->counts.as<int32_t>());
+        MLIP_HIP(hipGetLastError());
+        MLIP_TRY(scan_i32_to_i64(g->counts.as<int32_t>(), out.row_ptr->as<int64_t>(), N, g->scan_tmp, s));
+        const int rc = read_counts_and_flags(g, out.row_ptr->as<int64_t>() + N, err, &E, &flags);   // first synchronisation
+        if (!(flags & FLAG_STAGE_OVERFLOW)) {
+            MLIP_TRY(rc);
+            const size_t Ecap = (size_t)std::max<int64_t>(E, 1);
+            MLIP_TRY(out.senders->ensure(Ecap * 4));
+            MLIP_TRY(out.shiftp->ensure(Ecap * 4));
+            MLIP_TRY(out.recv->ensure(Ecap * 4));
+            MLIP_TRY(out.d->ensure(Ecap * 4));
+            k_sort_rows_pairs<<<grid8(N), 64, 0, s>>>(N, cp, pos, out.row_ptr->as<int64_t>(), stage_own, stage_par, n_own,
+                                                      rank_own, rank_par, out.senders->as<int32_t>(),
+                                                      out.recv->as<int32_t>(), out.shiftp->as<uint32_t>(),
+                                                      out.d->as<float>());
+            MLIP_HIP(hipGetLastError());
+            if (out.mirror) {
+                MLIP_TRY(out.mirror->ensure(Ecap * 4));
+                k_mirror_pairs<<<grid8((N + 7) / 8), 256, 0, s>>>(N, out.row_ptr->as<int64_t>(), stage_own, pslot_own, n_own,
+                                                                  rank_own, rank_par, out.mirror->as<int32_t>());
+                MLIP_HIP(hipGetLastError());
+            }
+            done = true;
+        }
+        // (on overflow the flag words stay as they are: species and position range remain valid, a coincidence is found again)
+    }
+    if (!done) {   // one-sided search in two passes (count, fill), reverse-edge index by binary search
+        k_neighbours<false><<<grid8(blocks_for(N, 128)), 128, 0, s>>>(
+            N, cp, g->cell_start.as<int32_t>(), g->sid.as<int32_t>(), g->sx.as<double>(), g->sy.as<double>(),
+            g->sz.as<double>(), g->swrap.as<uint32_t>(), g->cell_of.as<int32_t>(), g->counts.as<int32_t>(), nullptr,
+            nullptr, err);
+        MLIP_HIP(hipGetLastError());
+        MLIP_TRY(scan_i32_to_i64(g->counts.as<int32_t>(), out.row_ptr->as<int64_t>(), N, g->scan_tmp, s));
+        MLIP_TRY(read_counts_and_flags(g, out.row_ptr->as<int64_t>() + N, err, &E, &flags));
+        const size_t Ecap = (size_t)std::max<int64_t>(E, 1);
+        MLIP_TRY(g->keys.ensure(Ecap * 8));
+        MLIP_TRY(out.senders->ensure(Ecap * 4));
+        MLIP_TRY(out.shiftp->ensure(Ecap * 4));
+        MLIP_TRY(out.recv->ensure(Ecap * 4));
+        MLIP_TRY(out.d->ensure(Ecap * 4));
         k_neighbours<true><<<grid8(blocks_for(N, 128)), 128, 0, s>>>(
             N, cp, g->cell_start.as<int32_t>(), g->sid.as<int32_t>(), g->sx.as<double>(), g->sy.as<double>(),
             g->sz.as<double>(), g->swrap.as<uint32_t>(), g->cell_of.as<int32_t>(), nullptr, out.row_ptr->as<int64_t>(),
             g->keys.as<uint64_t>(), err);
         MLIP_HIP(hipGetLastError());
+        k_sort_rows<<<grid8(N), 64, 0, s>>>(N, cp, pos, out.row_ptr->as<int64_t>(), g->keys.as<uint64_t>(), 0,
+                                            out.senders->as<int32_t>(), out.recv->as<int32_t>(), out.shiftp->as<uint32_t>(),
+                                            out.d->as<float>());
+        MLIP_HIP(hipGetLastError());
+        if (out.mirror && E > 0) {
+            MLIP_TRY(out.mirror->ensure(Ecap * 4));
+            k_mirror<true><<<grid8(blocks_for(E, 256)), 256, 0, s>>>(E, out.row_ptr->as<int64_t>(), out.senders->as<int32_t>(),
+                                                                     out.recv->as<int32_t>(), out.shiftp->as<uint32_t>(), nullptr,
+                                                                     0, out.mirror->as<int32_t>(), err);
+            MLIP_HIP(hipGetLastError());
+        }
     }
-    k_sort_rows<<<grid8(N), 64, 0, s>>>(N, cp, pos, out.row_ptr->as<int64_t>(),
-                                        staged ? g->stage.as<uint64_t>() : g->keys.as<uint64_t>(), staged ? 1 : 0,
-                                        out.senders->as<int32_t>(), out.recv->as<int32_t>(), out.shiftp->as<uint32_t>(),
-                                        out.d->as<float>());
-    MLIP_HIP(hipGetLastError());
     *E_out = E;
     return MLIP_OK;
 }
@@ -1200,6 +1434,7 @@ int build_graph_impl(mlip_graph *g, const double *positions, const double *cell,
 
     prof_begin(g, MLIP_PROF_GRAPH);
     int64_t E = 0;
+    bool have_mirror = false;   // the search delivers the reverse-edge index, the skin filter does not
     if (g->skin > 0.0) {
         // Verlet skin: the neighbour list is filtered from a candidate list for r_cut + skin, which is rebuilt
         // when the system changed or some atom has moved more than skin / 2 since it was made
@@ -1213,7 +1448,7 @@ int build_graph_impl(mlip_graph *g, const double *positions, const double *cell,
             CellParams cps;
             rc = prepare_cell(cell, r_cut + g->skin, P, N, cps);
             if (rc == MLIP_OK)
-                rc = search_csr(g, cps, N, CsrOut{&g->cand_row_ptr, &g->cand_senders, &g->cand_recv, &g->cand_shiftp, &g->cand_d},
+                rc = search_csr(g, cps, N, CsrOut{&g->cand_row_ptr, &g->cand_senders, &g->cand_recv, &g->cand_shiftp, &g->cand_d, nullptr},
                                 &g->cand_E);
             if (rc == MLIP_OK) rc = g->ref_pos.ensure((size_t)N * 3 * sizeof(double));
             if (rc == MLIP_OK) {
@@ -1232,14 +1467,15 @@ int build_graph_impl(mlip_graph *g, const double *positions, const double *cell,
         }
         if (rc != MLIP_OK) { prof_end(g); return rc; }
     } else {
-        const int rc = search_csr(g, cp, N, CsrOut{&g->row_ptr, &g->senders, &g->recv, &g->shiftp, &g->d}, &E);
+        const int rc = search_csr(g, cp, N, CsrOut{&g->row_ptr, &g->senders, &g->recv, &g->shiftp, &g->d, &g->mirror}, &E);
         if (rc != MLIP_OK) { prof_end(g); return rc; }
+        have_mirror = true;
     }
     const double *pos = g->pos.as<double>();
     (void)pos;
     MLIP_TRY(g->mirror.ensure((size_t)std::max<int64_t>(E, 1) * 4));
 
-    if (E > 0) {
+    if (E > 0 && !have_mirror) {
         k_mirror<true><<<grid8(blocks_for(E, 256)), 256, 0, s>>>(E, g->row_ptr.as<int64_t>(), g->senders.as<int32_t>(),
                                                           g->recv.as<int32_t>(), g->shiftp.as<uint32_t>(), nullptr, 0,
                                                           g->mirror.as<int32_t>(), err);

@@ -188,7 +188,7 @@ struct mlip_graph {
     // inputs copied in
     mlip::DevBuf pos, species;
     // build scratch
-    mlip::DevBuf cell_of, wrapp, cell_cnt, cell_start, cell_fill, sid, sx, sy, sz, swrap, counts, keys, stage, flags,
+    mlip::DevBuf cell_of, wrapp, cell_cnt, cell_start, cell_fill, sid, sx, sy, sz, swrap, counts, keys, stage, pair_aux, flags,
         scan_tmp, small;
     // whole-graph CSR
     mlip::DevBuf row_ptr, senders, recv, mirror, shiftp, d, chunk_row;

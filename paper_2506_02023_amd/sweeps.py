@@ -2,7 +2,11 @@
 step time against the number of layers (interaction range), the feature width (model size), the density
 (neighbours per atom), the number of slabs and the system size (Results: scaling studies).
 
-    python -m paper_2506_02023_amd.sweeps [--which layers,width,density,slabs,size] [--steps 5]
+    python -m paper_2506_02023_amd.sweeps [--which layers,width,density,slabs,size,order] [--steps 5]
+
+`--which order` times configs[3] with the atoms numbered in lattice order and in blocks of B^3 cells (a spatially
+blocked numbering keeps the sender rows an XCD gathers closer together); `--order-blocks B` restricts it to one
+numbering, so that a counter run (rocprofv3 --pmc) sees one case per process.
 
 One step = mlip_build_graph + mlip_forward (SLABS mode when more than one slab, else WHOLE), inputs resident in
 HBM, as in bench.py.  Prints a markdown table per sweep.  Everything runs in the HIP library; this module only
@@ -61,6 +65,8 @@ def main():
     ap.add_argument("--which", default="layers,width,density,slabs,size")
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--cells", type=int, default=40, help="fcc cells per side of the fixed-size sweeps")
+    ap.add_argument("--order-blocks", type=int, default=None,
+                    help="with --which order: only this numbering (0 = lattice order, B = blocks of B^3 cells)")
     args = ap.parse_args()
     which = set(args.which.split(","))
 
@@ -95,6 +101,22 @@ def main():
         for P in (1, 2, 4, 8, 16, 32):
             print(_row(f"P = {P}", _time_case(pos, cell, sp, wl.rmp_weights(8, 64, 3, seed), wl.R_CUT, wl.P_ENVELOPE, P, args.steps)),
                   flush=True)
+    if "order" in which:
+        import numpy as np
+        print("\n### Atom numbering, configs[3] (fcc 63^3), F = 64, L = 3, 8 slabs\n\n" + _HEAD)
+        pos, cell, sp = lattice(63)
+        idx = np.arange(len(sp))
+        ix, iy, iz, b = np.unravel_index(idx, (63, 63, 63, 4))
+        for B in ([args.order_blocks] if args.order_blocks is not None else [0, 4, 8, 16]):
+            if B:
+                key = ((((ix // B) * 100 + (iy // B)) * 100 + (iz // B)) * B + ix % B) * B * B * 4 + ((iy % B) * B + iz % B) * 4 + b
+                perm = np.argsort(key, kind="stable")
+            else:
+                perm = idx
+            r = _time_case(np.ascontiguousarray(pos[perm]), cell, np.ascontiguousarray(sp[perm]),
+                           wl.rmp_weights(8, 64, 3, seed), wl.R_CUT, wl.P_ENVELOPE, 8, args.steps)
+            print(_row("lattice order" if not B else f"blocks of {B}^3 cells", r) +
+                  f" edge fwd {r['prof']['edge_fwd']:.2f} / bwd {r['prof']['edge_bwd']:.2f} ms", flush=True)
     if "size" in which:
         print("\n### System size, F = 64, L = 3, 8 slabs\n\n" + _HEAD)
         for cells in (10, 20, 30, 40, 50, 63, 80):

@@ -37,12 +37,12 @@ def flops_bwd_edge(F, K=8):
 
 
 # HBM bytes per launch (one layer over all 8 slabs) on the default workload, from rocprofv3 --pmc FETCH_SIZE and
-# WRITE_SIZE (profiles/edge_traffic_configs3_8slabs.md): KiB x copy-kernel scale (1.9976 for FETCH_SIZE, 1.000 for
+# WRITE_SIZE (profiles/edge_traffic_configs3_8slabs.md): KiB x copy-kernel scale (1.9975 for FETCH_SIZE, 1.000 for
 # WRITE_SIZE)
 TRAFFIC_SOURCE = ("profiled constant, not measured by this run: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this kernel on "
                   "this workload, profiles/edge_traffic_configs3_8slabs.md")
-TRAFFIC_BWD_LAUNCH_BYTES = (11679546 * 1.9976 + 999832 * 1.0) * 1024
-TRAFFIC_FWD_LAUNCH_BYTES = (2482961 * 1.9976 + 7878068 * 1.0) * 1024
+TRAFFIC_BWD_LAUNCH_BYTES = (11683356 * 1.9975 + 999921 * 1.0) * 1024
+TRAFFIC_FWD_LAUNCH_BYTES = (2491067 * 1.9975 + 7878067 * 1.0) * 1024
 
 
 # fp32 vector peak that applies to this build: 256 CUs x 4 SIMDs x 16 lanes x 2 flop per FMA x 2.4 GHz = 78.6 TFLOP/s.

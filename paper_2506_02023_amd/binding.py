@@ -12,7 +12,8 @@ import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libmlip.so")
+# MLIP_LIBRARY selects another build of the same library (timing experiments); the default is the in-tree product build
+_LIB_PATH = os.environ.get("MLIP_LIBRARY") or os.path.join(_HERE, "libmlip.so")
 
 MODE_WHOLE, MODE_SLABS = 0, 1
 PRECISION_FP32, PRECISION_BF16, PRECISION_FP32_SPLIT = 0, 1, 2

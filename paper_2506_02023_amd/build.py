@@ -18,13 +18,15 @@ COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", INCLUDE, 
 SOURCES = {"api.hip": [], "graph.hip": ["-ffp-contract=off"], "model.hip": []}
 
 
-def build(verbose=False):
-    os.makedirs(BUILD, exist_ok=True)
+def build(verbose=False, defines=(), lib=LIB, build_dir=BUILD):
+    """defines: extra -D macros (timing experiments, e.g. MLIP_TIMING_SKIP_PAIR_PHASE); such a build goes to another
+    `lib` path, never to the library the binding loads."""
+    os.makedirs(build_dir, exist_ok=True)
 
     def compile_one(item):
         src, extra = item
-        obj = os.path.join(BUILD, src.replace(".hip", ".o"))
-        cmd = ["hipcc", *COMMON, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
+        obj = os.path.join(build_dir, src.replace(".hip", ".o"))
+        cmd = ["hipcc", *COMMON, *extra, *[f"-D{d}" for d in defines], "-c", os.path.join(CSRC, src), "-o", obj]
         r = subprocess.run(cmd, capture_output=True, text=True)
         if r.returncode != 0 or verbose:
             sys.stderr.write(r.stdout + r.stderr)
@@ -34,13 +36,18 @@ def build(verbose=False):
 
     with ThreadPoolExecutor(max_workers=len(SOURCES)) as ex:
         objs = list(ex.map(compile_one, SOURCES.items()))
-    cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
+    cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *objs]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         sys.stderr.write(r.stdout + r.stderr)
         raise RuntimeError("link failed")
-    return LIB
+    return lib
 
 
 if __name__ == "__main__":
-    print(build(verbose="-v" in sys.argv))
+    # python -m paper_2506_02023_amd.build [-v] [-DNAME ... --out PATH]
+    defs = [a[2:] for a in sys.argv[1:] if a.startswith("-D")]
+    out = sys.argv[sys.argv.index("--out") + 1] if "--out" in sys.argv else LIB
+    if defs and out == LIB:
+        sys.exit("a build with extra defines needs --out PATH (it must not replace the product library)")
+    print(build(verbose="-v" in sys.argv, defines=defs, lib=out, build_dir=BUILD if out == LIB else BUILD + "_exp"))

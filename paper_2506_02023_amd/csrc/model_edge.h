@@ -457,6 +457,17 @@ __global__ void __launch_bounds__(kBwdWaves * 64, kBwdWaves == 4 ? 2 : 1) k_edge
         q_tail -= (q_tail >= kQueue) ? kQueue : 0;
     };
     auto phase2 = [&]() {
+#ifdef MLIP_TIMING_SKIP_PAIR_PHASE
+        // timing experiment only (results are wrong): drop the queued pairs without the dense work, which leaves
+        // the streaming phase of the kernel to be timed on its own
+        {
+            const int nv = min(q_count, 32);
+            q_head += nv;
+            q_head -= (q_head >= kQueue) ? kQueue : 0;
+            q_count -= nv;
+            return;
+        }
+#endif
         // ---------------- up to 32 queued pairs
         wave_lds_fence();
         const int nval = min(q_count, 32);

@@ -974,7 +974,7 @@ __global__ void __launch_bounds__(256)
 k_skin_rows(int64_t N, CellParams cp, const double *__restrict__ pos, const double *__restrict__ ref, double half_skin2,
             const int32_t *__restrict__ species, const int64_t *__restrict__ crow, const int32_t *__restrict__ csend,
             const uint32_t *__restrict__ cshift, int32_t *counts, int32_t *slab_of, const int64_t *__restrict__ row_ptr,
-            int32_t *senders, int32_t *recv, uint32_t *shiftp, float *d, int32_t *err)
+            int32_t *senders, int32_t *recv, uint32_t *shiftp, float *d, int32_t *newpos, int32_t *err)
 {
     const int lane = threadIdx.x & 63;
     const int64_t i = (int64_t)xcd_block() * 4 + (threadIdx.x >> 6);
@@ -1026,6 +1026,7 @@ k_skin_rows(int64_t N, CellParams cp, const double *__restrict__ pos, const doub
             recv[o] = (int32_t)i;
             d[o] = (float)sqrt(d2);
         }
+        if (FILL && e < e1) newpos[e] = keep ? (int32_t)(out + __popcll(m & lt)) : -1;   // where the candidate went
         out += __popcll(m);
         cnt += __popcll(m);
     }
@@ -1033,6 +1034,20 @@ k_skin_rows(int64_t N, CellParams cp, const double *__restrict__ pos, const doub
         if (lane == 0) counts[i] = cnt;
         if (coincident) atomicOr(err, ERR_COINCIDENT);
     }
+}
+
+// reverse-edge index of the filtered list from the candidate list's: the reverse of a kept candidate is kept as well
+// (same length bit for bit), so mirror[newpos[e]] = newpos[cmirror[e]]
+__global__ void k_skin_mirror(int64_t Ec, const int32_t *__restrict__ newpos, const int32_t *__restrict__ cmirror,
+                              int32_t *__restrict__ mirror, int32_t *err)
+{
+    const int64_t e = (int64_t)xcd_block() * blockDim.x + threadIdx.x;
+    if (e >= Ec) return;
+    const int32_t o = newpos[e];
+    if (o < 0) return;
+    const int32_t m = newpos[cmirror[e]];
+    if (m < 0) { atomicOr(err, ERR_MIRROR); mirror[o] = o; return; }
+    mirror[o] = m;
 }
 
 inline unsigned blocks_for(int64_t n, int threads) { return (unsigned)((n + threads - 1) / threads); }
@@ -1384,7 +1399,7 @@ int csr_from_candidates(mlip_graph *g, const CellParams &cp, int64_t N, int64_t 
     k_skin_rows<false><<<grid8((N + 3) / 4), 256, 0, s>>>(
         N, cp, pos, g->ref_pos.as<double>(), h2, g->species.as<int32_t>(), g->cand_row_ptr.as<int64_t>(),
         g->cand_senders.as<int32_t>(), g->cand_shiftp.as<uint32_t>(), g->counts.as<int32_t>(), g->slab_of.as<int32_t>(),
-        nullptr, nullptr, nullptr, nullptr, nullptr, err);
+        nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, err);
     MLIP_HIP(hipGetLastError());
     MLIP_TRY(scan_i32_to_i64(g->counts.as<int32_t>(), g->row_ptr.as<int64_t>(), N, g->scan_tmp, s));
     int64_t E = 0;
@@ -1397,11 +1412,20 @@ int csr_from_candidates(mlip_graph *g, const CellParams &cp, int64_t N, int64_t 
     MLIP_TRY(g->shiftp.ensure(Ecap * 4));
     MLIP_TRY(g->recv.ensure(Ecap * 4));
     MLIP_TRY(g->d.ensure(Ecap * 4));
+    MLIP_TRY(g->mirror.ensure(Ecap * 4));
+    // the candidate list's reverse-edge index is reused through the positions the kept candidates go to (the recv
+    // array of the candidate list is not needed after its build and holds them)
+    int32_t *newpos = g->cand_recv.as<int32_t>();
     k_skin_rows<true><<<grid8((N + 3) / 4), 256, 0, s>>>(
         N, cp, pos, g->ref_pos.as<double>(), h2, g->species.as<int32_t>(), g->cand_row_ptr.as<int64_t>(),
         g->cand_senders.as<int32_t>(), g->cand_shiftp.as<uint32_t>(), nullptr, nullptr, g->row_ptr.as<int64_t>(),
-        g->senders.as<int32_t>(), g->recv.as<int32_t>(), g->shiftp.as<uint32_t>(), g->d.as<float>(), err);
+        g->senders.as<int32_t>(), g->recv.as<int32_t>(), g->shiftp.as<uint32_t>(), g->d.as<float>(), newpos, err);
     MLIP_HIP(hipGetLastError());
+    if (g->cand_E > 0) {
+        k_skin_mirror<<<grid8(blocks_for(g->cand_E, 256)), 256, 0, s>>>(g->cand_E, newpos, g->cand_mirror.as<int32_t>(),
+                                                                        g->mirror.as<int32_t>(), err);
+        MLIP_HIP(hipGetLastError());
+    }
     *E_out = E;
     *valid = true;
     return MLIP_OK;
@@ -1434,7 +1458,6 @@ int build_graph_impl(mlip_graph *g, const double *positions, const double *cell,
 
     prof_begin(g, MLIP_PROF_GRAPH);
     int64_t E = 0;
-    bool have_mirror = false;   // the search delivers the reverse-edge index, the skin filter does not
     if (g->skin > 0.0) {
         // Verlet skin: the neighbour list is filtered from a candidate list for r_cut + skin, which is rebuilt
         // when the system changed or some atom has moved more than skin / 2 since it was made
@@ -1448,7 +1471,7 @@ int build_graph_impl(mlip_graph *g, const double *positions, const double *cell,
             CellParams cps;
             rc = prepare_cell(cell, r_cut + g->skin, P, N, cps);
             if (rc == MLIP_OK)
-                rc = search_csr(g, cps, N, CsrOut{&g->cand_row_ptr, &g->cand_senders, &g->cand_recv, &g->cand_shiftp, &g->cand_d, nullptr},
+                rc = search_csr(g, cps, N, CsrOut{&g->cand_row_ptr, &g->cand_senders, &g->cand_recv, &g->cand_shiftp, &g->cand_d, &g->cand_mirror},
                                 &g->cand_E);
             if (rc == MLIP_OK) rc = g->ref_pos.ensure((size_t)N * 3 * sizeof(double));
             if (rc == MLIP_OK) {
@@ -1469,18 +1492,10 @@ int build_graph_impl(mlip_graph *g, const double *positions, const double *cell,
     } else {
         const int rc = search_csr(g, cp, N, CsrOut{&g->row_ptr, &g->senders, &g->recv, &g->shiftp, &g->d, &g->mirror}, &E);
         if (rc != MLIP_OK) { prof_end(g); return rc; }
-        have_mirror = true;
     }
     const double *pos = g->pos.as<double>();
     (void)pos;
     MLIP_TRY(g->mirror.ensure((size_t)std::max<int64_t>(E, 1) * 4));
-
-    if (E > 0 && !have_mirror) {
-        k_mirror<true><<<grid8(blocks_for(E, 256)), 256, 0, s>>>(E, g->row_ptr.as<int64_t>(), g->senders.as<int32_t>(),
-                                                          g->recv.as<int32_t>(), g->shiftp.as<uint32_t>(), nullptr, 0,
-                                                          g->mirror.as<int32_t>(), err);
-        MLIP_HIP(hipGetLastError());
-    }
 
     {
         const int64_t nc = chunks_of(E);

@@ -198,7 +198,7 @@ struct mlip_graph {
     int64_t cand_N = 0, cand_E = 0;
     double cand_rcut = 0.0, cand_skin = 0.0, cand_cell[9] = {0};
     int64_t skin_builds = 0, skin_reuses = 0;
-    mlip::DevBuf cand_row_ptr, cand_senders, cand_recv, cand_shiftp, cand_d, ref_pos;
+    mlip::DevBuf cand_row_ptr, cand_senders, cand_recv, cand_shiftp, cand_d, cand_mirror, ref_pos;
     // partition
     mlip::DevBuf slab_of, needed_by, local_of, local_in_owner, class_cnt, class_off;
     mlip::PartStore part;

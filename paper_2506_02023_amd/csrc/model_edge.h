@@ -226,7 +226,7 @@ __global__ void __launch_bounds__(256, 3) k_edge_fwd(EdgeBatch B)
 #pragma unroll
         for (int k = 0; k < 32; ++k) {
             acc = fmaf(wv[k], gv[k], acc);   // lanes past the end hold a zero filter
-            if (ends & (1u << k)) {
+            if (__builtin_expect((ends & (1u << k)) != 0, 0)) {   // unlikely: keeps the common path free of taken branches
                 const int32_t row = __builtin_amdgcn_readlane(rcur, k);
                 const int32_t nrow = __builtin_amdgcn_readlane(rnext, k);
                 store_row(row, acc);
@@ -261,8 +261,14 @@ __global__ void __launch_bounds__(256, 3) k_edge_fwd(EdgeBatch B)
 // 32-slot queue in three 4-wave blocks per compute unit (154 registers): 16.2 ms, the per-step bookkeeping doubles and
 // phase 2 runs on partly filled tiles; steps of 12 in one 12-wave block (168 registers, 4 of them spilled): 16.0 ms.
 constexpr int kStep = 16;
-constexpr int kBwdWaves = 4;
-constexpr int kQueue = 31 + kStep + 1;   // queued pairs per wavefront: at most 31 pending + one step's new ones
+#ifndef MLIP_BWD_WAVES
+#define MLIP_BWD_WAVES 4
+#endif
+constexpr int kBwdWaves = MLIP_BWD_WAVES;
+#ifndef MLIP_BWD_QUEUE
+#define MLIP_BWD_QUEUE (31 + kStep + 1)
+#endif
+constexpr int kQueue = MLIP_BWD_QUEUE;   // queued pairs per wavefront: at most 31 pending + one step's new ones
 // phase 2 runs once a further step could overflow the queue (and at the latest with 32 pairs queued)
 constexpr int kQueueTrigger = (kQueue - kStep < 32) ? kQueue - kStep : 32;
 
@@ -432,7 +438,7 @@ __global__ void __launch_bounds__(kBwdWaves * 64, kBwdWaves == 4 ? 2 : 1) k_edge
             *reinterpret_cast<float *>(Qf + q_off) = fmaf(ai, S.gv[k], S.av[k] * gi);
             q_off += (uppers & (1u << k)) ? FS * 4 : 0;
             q_off = (q_off == kQueue * FS * 4) ? 0 : q_off;
-            if (ends & (1u << k)) {
+            if (__builtin_expect((ends & (1u << k)) != 0, 0)) {   // unlikely: keeps the common path free of taken branches
                 const int32_t rrow = __builtin_amdgcn_readlane(rk, k);
                 const int32_t nrow = __builtin_amdgcn_readlane(rnext, k);
                 store_row(rrow, acc);

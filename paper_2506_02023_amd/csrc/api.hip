@@ -344,7 +344,7 @@ void mlip_graph_destroy(mlip_graph_t *g)
     DevBuf *bufs[] = {&g->pos, &g->species, &g->cell_of, &g->wrapp, &g->cell_cnt, &g->cell_start, &g->cell_fill,
                       &g->sid, &g->sx, &g->sy, &g->sz, &g->swrap, &g->counts, &g->keys, &g->stage, &g->pair_aux, &g->flags, &g->scan_tmp,
                       &g->small, &g->row_ptr, &g->senders, &g->recv, &g->mirror, &g->shiftp, &g->d, &g->chunk_row, &g->slab_of, &g->needed_by,
-                      &g->local_of, &g->local_in_owner, &g->class_cnt, &g->class_off, &g->wpack, &g->energy_part,
+                      &g->local_of, &g->local_in_owner, &g->class_cnt, &g->class_off, &g->wpack, &g->energy_part, &g->work,
                       &g->cand_row_ptr, &g->cand_senders, &g->cand_recv, &g->cand_shiftp, &g->cand_d, &g->cand_mirror, &g->ref_pos};
     for (DevBuf *b : bufs) b->release();
     g->bond_wpack.release();

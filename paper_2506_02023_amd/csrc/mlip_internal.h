@@ -206,6 +206,9 @@ struct mlip_graph {
     mlip::SlabView whole;
     // forward scratch shared by all views
     mlip::DevBuf wpack, energy_part;
+    mlip::DevBuf work;        // work counters of the edge kernels: one set of 8 per launch of a call, zeroed per call
+    int32_t *work_ptr = nullptr;
+    int work_next = 0;        // launches that have taken their counters in the current call
     mlip::Profiler prof;
     mlip::DevBuf bond_wpack;  // packed weights of the three-body variant's bond part
     void *pinned = nullptr;  // small pinned host staging area

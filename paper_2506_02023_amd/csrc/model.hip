@@ -157,6 +157,9 @@ int node_pass(mlip_graph *g, SlabView *views, int P, const float *P1, const floa
     return MLIP_OK;
 }
 
+// Edge-kernel launches of one call: two per layer and batch of partitions (L <= 8, at most 64 / kBatch batches).
+constexpr int kWorkLaunches = 2 * 8 * (64 / kBatch);
+
 template <int F, int PREC> int launch_edge(mlip_graph *g, EdgeBatch &b, bool backward)
 {
     const size_t lds = backward ? Lds<F>::edge_bwd : Lds<F>::edge_fwd;
@@ -180,6 +183,11 @@ template <int F, int PREC> int launch_edge(mlip_graph *g, EdgeBatch &b, bool bac
         }
         occ = g->fn_occ[slot].second = o;
     }
+    if (g->work_next >= kWorkLaunches) {
+        set_error("more than %d edge-kernel launches in one call", kWorkLaunches);
+        return MLIP_ESTATE;
+    }
+    b.work = g->work_ptr + (size_t)g->work_next * (8 * kWorkCounterStride);
     b.chunk_start[0] = 0;
     for (int q = 0; q < b.n; ++q) b.chunk_start[q + 1] = b.chunk_start[q] + (b.s[q].n_rows > 0 ? b.s[q].n_chunks : 0);
     for (int q = b.n; q < kBatch; ++q) b.chunk_start[q + 1] = b.chunk_start[b.n];
@@ -195,6 +203,7 @@ template <int F, int PREC> int launch_edge(mlip_graph *g, EdgeBatch &b, bool bac
     else
         k_edge_fwd<F, PREC><<<blocks, 256, lds, g->stream>>>(b);
     MLIP_HIP(hipGetLastError());
+    ++g->work_next;   // only a launch that ran has used its counters
     return MLIP_OK;
 }
 
@@ -250,11 +259,17 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
     float *wp = nullptr, *energy_part_f = nullptr;
     MLIP_TRY(place(g->energy_part, (size_t)std::max<int64_t>(n_parts, 1) * sizeof(double), energy_part_f));
     MLIP_TRY(place(g->wpack, pk.total * sizeof(float), wp));
+    float *work_f = nullptr;
+    const size_t work_n = (size_t)kWorkLaunches * 8 * kWorkCounterStride;
+    MLIP_TRY(place(g->work, work_n * sizeof(int32_t), work_f));
     if (scratch && scratch->failed()) {
         set_error("this graph and model need more than the %zu bytes of static workspace", scratch->size);
         return MLIP_EINVAL;
     }
     double *energy_part = reinterpret_cast<double *>(energy_part_f);
+    g->work_ptr = reinterpret_cast<int32_t *>(work_f);
+    g->work_next = 0;
+    MLIP_TRY(fill_zero(work_f, (int64_t)work_n, s));
 
 
     // ---- batches for the small kernels (embedding, ghost transfers, forces, energy): up to kBatch partitions per launch

@@ -39,27 +39,48 @@ struct EdgeBatch {
     EdgeCommon c;
     int n;
     int64_t chunk_start[kBatch + 1];
+    int32_t *work;   // this launch's 8 work counters (kWorkCounterStride apart), zero when the kernel starts
     EdgeArgs s[kBatch];
 };
 
 // Persistent launch: the grid holds exactly the blocks that are resident at once, a multiple of 8.
 // Blocks go to the 8 XCDs round-robin, so blocks b with the same b % 8 share an L2.  Each XCD takes one
-// contiguous eighth of the work items and its blocks walk through it side by side (block slot s, wave w
-// takes items 4 s + w, 4 (s + n_slots) + w, ...): at any moment an XCD works on a short contiguous run
-// of rows, whose neighbourhoods overlap, so the sender rows it gathers stay in its L2.
-struct ItemRange {
-    int64_t first, end, stride;
+// contiguous eighth of the work items and its wavefronts walk through it side by side: every wavefront starts
+// with the item of its own position (block slot s, wave w: item nw s + w) and then draws the next item of the
+// eighth from a counter all of them share.  At any moment an XCD works on a short contiguous run of rows, whose
+// neighbourhoods overlap, so the sender rows it gathers stay in its L2; and because items are handed out, not
+// dealt in advance, the wavefronts finish together although those of the younger block of a compute unit
+// run about a fifth slower than those of the older one (measured: the instruction arbiter prefers age).
+// The counters (one per eighth, 128 bytes apart, zero before the launch) are correct for any placement of
+// blocks; only the locality depends on the round-robin.
+constexpr int kWorkCounterStride = 32;   // int32 elements between two counters
+struct ItemQueue {
+    int64_t base, end;   // this eighth of the work items
+    int32_t *counter;    // items drawn so far beyond the first one of every wavefront
+    int32_t n_first;     // wavefronts that share the eighth (their first items are 0 .. n_first - 1)
+    int64_t first;       // this wavefront's first item
+    // Ask for the next item (lane 0's atomic; the value comes back like a load and is not waited for here) ...
+    __device__ int32_t draw(int lane) const
+    {
+        int32_t v = 0;
+        if (lane == 0) v = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return v;
+    }
+    // ... and turn the answer into an item index when the current item is done.
+    __device__ int64_t resolve(int32_t drawn) const { return base + n_first + __builtin_amdgcn_readfirstlane(drawn); }
 };
-__device__ inline ItemRange edge_items(int64_t total, int wave, int nw = 4)   // nw: wavefronts per block
+__device__ inline ItemQueue edge_items(int64_t total, int32_t *counters, int wave, int nw = 4)   // nw: wavefronts per block
 {
     const int64_t n_slots = gridDim.x >> 3;
     const int64_t per = (((total + 7) >> 3) + 3) & ~(int64_t)3;
     const int64_t xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-    ItemRange r;
-    r.first = xcd * per + slot * nw + wave;
-    r.end = min(total, (xcd + 1) * per);
-    r.stride = n_slots * nw;
-    return r;
+    ItemQueue q;
+    q.base = xcd * per;
+    q.end = min(total, (xcd + 1) * per);
+    q.counter = counters + xcd * kWorkCounterStride;
+    q.n_first = (int32_t)(n_slots * nw);
+    q.first = q.base + slot * nw + wave;
+    return q;
 }
 
 __device__ inline int batch_find(const int64_t *start, int n, int64_t w)
@@ -139,8 +160,9 @@ __global__ void __launch_bounds__(256, 3) k_edge_fwd(EdgeBatch B)
     const EdgeCommon &C = B.c;
     RegPack1<F> W1;
     load_pack1<F>(W1, C.A1s, lane);
-    const ItemRange items = edge_items(B.chunk_start[B.n], wave);
+    const ItemQueue items = edge_items(B.chunk_start[B.n], B.work, wave);
     int64_t item = items.first;
+    int32_t drawn = 0;
     for (int part = 0; part < B.n; ++part) {
     const int64_t part_end = min(items.end, B.chunk_start[part + 1]);
     if (item >= part_end) continue;
@@ -152,7 +174,8 @@ __global__ void __launch_bounds__(256, 3) k_edge_fwd(EdgeBatch B)
     auto store_row = [&](int32_t row, float v) {
         if (F == 64 || lane < F) buffer_store_f32(v, o_rsrc, f * 4, row * (F * 4), 0);
     };
-    for (; item < part_end; item += items.stride) {
+    for (; item < part_end; item = items.resolve(drawn)) {
+    drawn = items.draw(lane);
     const int64_t chunk = item - B.chunk_start[part];
     int64_t r0, r1;
     if (!chunk_rows(A, chunk, r0, r1)) continue;
@@ -340,9 +363,15 @@ __global__ void __launch_bounds__(kBwdWaves * 64, kBwdWaves == 4 ? 2 : 1) k_edge
     const bool need_gbar = C.need_gbar != 0;
     int q_head = 0, q_count = 0;   // first queued slot, queued pairs
     int q_tail = 0;                // (q_head + q_count) % kQueue, the slot the next pair goes to
+#ifdef MLIP_TIMING_PHASES
+    // timing experiment only: shader-clock cycles this wavefront spends in the dense phase, printed by one wavefront
+    long long t_start = clock64(), t_dense = 0;
+    int n_dense = 0;
+#endif
 
-    const ItemRange items = edge_items(B.chunk_start[B.n], wave, kBwdWaves);
+    const ItemQueue items = edge_items(B.chunk_start[B.n], B.work, wave, kBwdWaves);
     int64_t item = items.first;
+    int32_t drawn = 0;
     for (int part = 0; part < B.n; ++part) {
     const int64_t part_end = min(items.end, B.chunk_start[part + 1]);
     if (item >= part_end) continue;
@@ -463,6 +492,9 @@ __global__ void __launch_bounds__(kBwdWaves * 64, kBwdWaves == 4 ? 2 : 1) k_edge
         q_tail -= (q_tail >= kQueue) ? kQueue : 0;
     };
     auto phase2 = [&]() {
+#ifdef MLIP_TIMING_PHASES
+        const long long t_in = clock64();
+#endif
 #ifdef MLIP_TIMING_SKIP_PAIR_PHASE
         // timing experiment only (results are wrong): drop the queued pairs without the dense work, which leaves
         // the streaming phase of the kernel to be timed on its own
@@ -534,9 +566,14 @@ __global__ void __launch_bounds__(kBwdWaves * 64, kBwdWaves == 4 ? 2 : 1) k_edge
         q_head -= (q_head >= kQueue) ? kQueue : 0;
         q_count -= nval;
         wave_lds_fence();
+#ifdef MLIP_TIMING_PHASES
+        t_dense += clock64() - t_in;
+        ++n_dense;
+#endif
     };
 
-    for (; item < part_end; item += items.stride) {
+    for (; item < part_end; item = items.resolve(drawn)) {
+        drawn = items.draw(lane);
         const int64_t chunk = item - B.chunk_start[part];
         int64_t r0_, r1_;
         if (!chunk_rows(A, chunk, r0_, r1_)) continue;
@@ -576,6 +613,13 @@ __global__ void __launch_bounds__(kBwdWaves * 64, kBwdWaves == 4 ? 2 : 1) k_edge
     }   // work items
     while (q_count > 0) phase2();   // queued pairs index this partition's arrays
     }   // partitions
+#ifdef MLIP_TIMING_PHASES
+    long long t_total = clock64() - t_start;
+    asm volatile("" : "+s"(t_total));   // taken before the print starts
+    if (lane == 0 && wave == 0 && blockIdx.x % 37 == 0)
+        printf("k_edge_bwd prec %d first %d block %d : %lld cycles, %lld in %d dense phases\n", PREC, (int)B.c.first,
+               (int)blockIdx.x, t_total, t_dense, n_dense);
+#endif
 }
 
 #endif  // MLIP_MODEL_EDGE_H

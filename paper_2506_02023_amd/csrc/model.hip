@@ -304,8 +304,11 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
             a.d = v.d;
             a.wstore = (layer >= 1) ? v.ws.wst + (size_t)(layer - 1) * (size_t)v.n_edges_owned * F : nullptr;
             a.bond_of_edge = (bw && v.bonds.n > 0) ? v.bonds.of_edge.as<int32_t>() : nullptr;
+            a.wb_bf16 = (prec == kPrecBf16);
             a.wb = (bw && v.bonds.n > 0 && layer >= 0)
-                       ? v.bonds.wb.as<float>() + (size_t)layer * (size_t)std::max<int64_t>(v.bonds.n, 1) * F : nullptr;
+                       ? static_cast<char *>(v.bonds.wb.p) + (size_t)layer * (size_t)std::max<int64_t>(v.bonds.n, 1) * F *
+                                                                   (a.wb_bf16 ? sizeof(__bf16) : sizeof(float))
+                       : nullptr;
             const int64_t items = unit == U_OWNED ? v.n_owned : unit == U_GHOST ? v.n_ghost
                                   : unit == U_BORDER ? v.n_owned - v.n_pure : unit == U_LOCAL ? v.n_local
                                   : (v.n_owned + 1023) / 1024;
@@ -380,8 +383,17 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
     // operand slots: 0 Wta (y = x W), 1 Wtb, 2 Wt2, 3 Wta^T, 4 Wtb^T, 5 Wt2^T, 6 + l Wb_l, 6 + L + l Wb_l^T; after them We0
     // packed for the K = 8 product
     BasisParams bpb = bp;
-    auto bstride = [&](SlabView &v) { return (size_t)std::max<int64_t>(v.bonds.n, 1) * F; };   // floats per [n][F] array
-    auto wbslice = [&](SlabView &v, int l) { return v.bonds.wb.as<float>() + (size_t)l * bstride(v); };
+    auto bstride = [&](SlabView &v) { return (size_t)std::max<int64_t>(v.bonds.n, 1) * F; };   // elements per [n][F] array
+    // the [bonds x F] arrays are bf16 in the bf16 mode, fp32 otherwise
+    const bool bond_bf16 = (prec == kPrecBf16);
+    const size_t belem = bond_bf16 ? sizeof(__bf16) : sizeof(float);
+    auto bond_elem = [&](auto &&launch) {   // calls launch with a value of the arrays' element type
+        if (bond_bf16) launch((__bf16)0.0f);
+        else launch(0.0f);
+    };
+    auto wbslice = [&](SlabView &v, int l) -> void * {
+        return static_cast<char *>(v.bonds.wb.p) + (size_t)l * bstride(v) * belem;
+    };
     auto bond_args = [&](SlabView &v) {   // everything a stage of k_bond_mlp may touch; the stage's operands are set by the caller
         BondGraph &BG = v.bonds;
         BondArgs a{};
@@ -395,20 +407,20 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
         a.We0p = bpk + (size_t)(6 + 2 * L) * ffp;
         a.bp = bpb;
         a.wb_stride = bstride(v);
-        a.P = BG.P.as<float>();
-        a.Q = BG.Q.as<float>();
-        a.S = BG.S.as<float>();
-        a.m = BG.m.as<float>();
-        a.wb = BG.wb.as<float>();
+        a.P = BG.P.p;
+        a.Q = BG.Q.p;
+        a.S = BG.S.p;
+        a.m = BG.m.p;
+        a.wb = BG.wb.p;
         a.abar = BG.abar_keep.as<float>();
         a.abar_stride = (size_t)std::max<int64_t>(v.n_owned, 1) * F;
         a.g = v.ws.g;
         a.g_stride = (size_t)v.n_local * F;
-        a.e1bar = BG.e1bar.as<float>();
+        a.e1bar = BG.e1bar.p;
         a.ubar = BG.ubar.as<float>();
-        a.Sbar = BG.Sbar.as<float>();
-        a.Pbar = BG.Pbar.as<float>();
-        a.Qbar = BG.Qbar.as<float>();
+        a.Sbar = BG.Sbar.p;
+        a.Pbar = BG.Pbar.p;
+        a.Qbar = BG.Qbar.p;
         a.dbond = BG.dbond.as<float>();
         return a;
     };
@@ -423,8 +435,8 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
             BondGraph &BG = views[p].bonds;
             const size_t bs = bstride(views[p]), nb1 = (size_t)std::max<int64_t>(BG.n, 1);
             DevBuf *fb[] = {&BG.P, &BG.Q, &BG.S, &BG.m, &BG.e1bar, &BG.Sbar, &BG.Pbar, &BG.Qbar};
-            for (DevBuf *b : fb) MLIP_TRY(b->ensure(bs * sizeof(float)));
-            MLIP_TRY(BG.wb.ensure(bs * sizeof(float) * (size_t)std::max(L, 1)));
+            for (DevBuf *b : fb) MLIP_TRY(b->ensure(bs * belem));
+            MLIP_TRY(BG.wb.ensure(bs * belem * (size_t)std::max(L, 1)));
             MLIP_TRY(BG.abar_keep.ensure((size_t)std::max<int64_t>(views[p].n_owned, 1) * rowb * (size_t)std::max(L, 1)));
             MLIP_TRY(BG.ubar.ensure(nb1 * sizeof(float)));
             MLIP_TRY(BG.dbond.ensure(nb1 * sizeof(float)));
@@ -478,9 +490,12 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
             SlabView &v = views[p];
             BondGraph &BG = v.bonds;
             if (BG.n > 0)
-                k_triplet_fwd<F><<<blocks_for(v.n_owned, 4), 256, 0, s>>>(v.n_owned, BG.ptr.as<int64_t>(), BG.rhat.as<float>(),
-                                                                          BG.u.as<float>(), BG.P.as<float>(),
-                                                                          BG.Q.as<float>(), Wtc, BG.S.as<float>());
+                bond_elem([&](auto zero) {
+                    using BT = decltype(zero);
+                    k_triplet_fwd<F, BT><<<blocks_for(v.n_owned, 4), 256, 0, s>>>(
+                        v.n_owned, BG.ptr.as<int64_t>(), BG.rhat.as<float>(), BG.u.as<float>(), BG.P.as<BT>(), BG.Q.as<BT>(), Wtc,
+                        BG.S.as<BT>());
+                });
         }
         MLIP_HIP(hipGetLastError());
         prof_end(g);
@@ -557,9 +572,12 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
             for (int p = 0; p < P; ++p) {
                 SlabView &v = views[p];
                 if (v.bonds.n > 0)
-                    k_bond_aggregate<F><<<blocks_for(v.n_owned, 4), 256, 0, s>>>(
-                        v.n_owned, v.bonds.ptr.as<int64_t>(), v.bonds.sender.as<int32_t>(), wbslice(v, l), gslice(v, l),
-                        aslice(v, l));
+                    bond_elem([&](auto zero) {
+                        using BT = decltype(zero);
+                        k_bond_aggregate<F, BT><<<blocks_for(v.n_owned, 4), 256, 0, s>>>(
+                            v.n_owned, v.bonds.ptr.as<int64_t>(), v.bonds.sender.as<int32_t>(),
+                            static_cast<const BT *>(wbslice(v, l)), gslice(v, l), aslice(v, l));
+                    });
             }
             MLIP_HIP(hipGetLastError());
             prof_end(g);
@@ -661,9 +679,12 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
                     MLIP_HIP(hipMemcpyAsync(BG.abar_keep.as<float>() + (size_t)l * (size_t)v.n_owned * F, v.ws.abar,
                                             (size_t)v.n_owned * rowb, hipMemcpyDeviceToDevice, s));
                 if (BG.n > 0 && need_gbar)
-                    k_bond_gbar<F><<<blocks_for(v.n_owned, 4), 256, 0, s>>>(
-                        v.n_owned, BG.ptr.as<int64_t>(), BG.sender.as<int32_t>(), BG.mirror.as<int32_t>(), wbslice(v, l),
-                        v.ws.abar, v.ws.gbar);
+                    bond_elem([&](auto zero) {
+                        using BT = decltype(zero);
+                        k_bond_gbar<F, BT><<<blocks_for(v.n_owned, 4), 256, 0, s>>>(
+                            v.n_owned, BG.ptr.as<int64_t>(), BG.sender.as<int32_t>(), BG.mirror.as<int32_t>(),
+                            static_cast<const BT *>(wbslice(v, l)), v.ws.abar, v.ws.gbar);
+                    });
             }
             MLIP_HIP(hipGetLastError());
             prof_end(g);
@@ -715,9 +736,12 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
             SlabView &v = views[p];
             BondGraph &BG = v.bonds;
             if (BG.n > 0)
-                k_triplet_bwd<F><<<blocks_for(v.n_owned, 4), 256, 0, s>>>(
-                    v.n_owned, BG.ptr.as<int64_t>(), BG.rhat.as<float>(), BG.u.as<float>(), BG.P.as<float>(), BG.Q.as<float>(),
-                    Wtc, BG.Sbar.as<float>(), BG.Pbar.as<float>(), BG.Qbar.as<float>(), BG.ubar.as<float>(), BG.rbar.as<float>());
+                bond_elem([&](auto zero) {
+                    using BT = decltype(zero);
+                    k_triplet_bwd<F, BT><<<blocks_for(v.n_owned, 4), 256, 0, s>>>(
+                        v.n_owned, BG.ptr.as<int64_t>(), BG.rhat.as<float>(), BG.u.as<float>(), BG.P.as<BT>(), BG.Q.as<BT>(), Wtc,
+                        BG.Sbar.as<BT>(), BG.Pbar.as<BT>(), BG.Qbar.as<BT>(), BG.ubar.as<float>(), BG.rbar.as<float>());
+                });
         }
         MLIP_HIP(hipGetLastError());
         prof_end(g);

@@ -11,6 +11,10 @@
 // feature and needs no atomics.  Notation: P_b = e0_b Wta, Q_b = e0_b Wtb, Wtc = rows 2F.. of Wt1,
 //   h(b1, b2) = P_b1 + Q_b2 + T(c) Wtc,  S_b1 = sum_{b2 != b1} u_b2 SiLU(h),  m = S Wt2,  e1 = e0 + u SiLU(m).
 
+//
+// BT is the element type of the [bonds x F] arrays (P, Q, S, m, wb, e1bar, Sbar, Pbar, Qbar): float, or __bf16 in the
+// bf16 precision mode, where these arrays are most of the bytes the bond kernels move.  Arithmetic is fp32 either way.
+
 constexpr int kAngle = 8;
 
 __device__ inline float silu_f(float x) { return x * __builtin_amdgcn_rcpf(1.0f + __expf(-x)); }
@@ -50,11 +54,12 @@ __device__ inline void chebyshev(float c, float (&T)[kAngle], float (&dT)[kAngle
 // triplets (a, o) and (o, a); the term of bond a accumulates in a register, the term of bond o in a per-lane LDS row.
 constexpr int kPairBondsFwd = 32;
 
-template <int F>
+template <int F, typename BT>
 __global__ void __launch_bounds__(256)
 k_triplet_fwd(int64_t N, const int64_t *__restrict__ bptr, const float *__restrict__ rhat, const float *__restrict__ u,
-              const float *__restrict__ P, const float *__restrict__ Q, const float *__restrict__ Wtc, float *__restrict__ S)
+              const BT *__restrict__ P, const BT *__restrict__ Q, const float *__restrict__ Wtc, BT *__restrict__ S)
 {
+    using IO = Elem<BT>;
     constexpr int NB = kPairBondsFwd;
     __shared__ float acc_lds[4][NB * 64];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
@@ -74,7 +79,7 @@ k_triplet_fwd(int64_t N, const int64_t *__restrict__ bptr, const float *__restri
         const float xl = rhat[3 * bl], yl = rhat[3 * bl + 1], zl = rhat[3 * bl + 2], ul = u[bl];   // lane = bond
         for (int a = 0; a < nb; ++a) {
             const int64_t ba = b0 + a;
-            const float pa = P[ba * F + f], qa = Q[ba * F + f];
+            const float pa = IO::load(P + ba * F + f), qa = IO::load(Q + ba * F + f);
             const float ua = readlane_f32(ul, a);
             float T[kAngle], dT[kAngle];
             chebyshev(fmaf(readlane_f32(xl, a), xl, fmaf(readlane_f32(yl, a), yl, readlane_f32(zl, a) * zl)), T, dT);   // lane = o
@@ -83,7 +88,7 @@ k_triplet_fwd(int64_t N, const int64_t *__restrict__ bptr, const float *__restri
                 float tw = wc[0];   // T_0 = 1
 #pragma unroll
                 for (int n = 1; n < kAngle; ++n) tw = fmaf(readlane_f32(T[n], o), wc[n], tw);
-                const float po = P[(b0 + o) * F + f], qo = Q[(b0 + o) * F + f];
+                const float po = IO::load(P + (b0 + o) * F + f), qo = IO::load(Q + (b0 + o) * F + f);
                 const float so = accS[o * 64 + lane];   // per-lane slot (read early, written at the end of the step;
                                                         // LDS float atomics measured an order of magnitude slower)
                 acc = fmaf(readlane_f32(ul, o), silu_f(pa + qo + tw), acc);       // triplet (b1 = a, b2 = o)
@@ -93,7 +98,7 @@ k_triplet_fwd(int64_t N, const int64_t *__restrict__ bptr, const float *__restri
         }
         wave_lds_fence();
         if (F == 64 || lane < F)
-            for (int b = 0; b < nb; ++b) S[(b0 + b) * F + f] = accS[b * 64 + lane];
+            for (int b = 0; b < nb; ++b) IO::store(S + (b0 + b) * F + f, accS[b * 64 + lane]);
         return;
     }
     // any number of bonds, no LDS: ordered pairs, bonds b2 in groups of 64
@@ -102,47 +107,47 @@ k_triplet_fwd(int64_t N, const int64_t *__restrict__ bptr, const float *__restri
         const int64_t bl = min(c0 + lane, b1e - 1);
         const float xl = rhat[3 * bl], yl = rhat[3 * bl + 1], zl = rhat[3 * bl + 2], ul = u[bl];
         for (int64_t b1 = b0; b1 < b1e; ++b1) {
-            const float p1 = P[b1 * F + f];
+            const float p1 = IO::load(P + b1 * F + f);
             const float x1 = rhat[3 * b1], y1 = rhat[3 * b1 + 1], z1 = rhat[3 * b1 + 2];
             float T[kAngle], dT[kAngle];
             chebyshev(fmaf(x1, xl, fmaf(y1, yl, z1 * zl)), T, dT);   // lane = b2
             float acc = 0.f;
             for (int k = 0; k < nl; ++k) {
                 if (c0 + k == b1) continue;
-                float h = p1 + Q[(c0 + k) * F + f];
+                float h = p1 + IO::load(Q + (c0 + k) * F + f);
 #pragma unroll
                 for (int n = 1; n < kAngle; ++n) h = fmaf(readlane_f32(T[n], k), wc[n], h);   // T_0 = 1
                 acc = fmaf(readlane_f32(ul, k), silu_f(h + wc[0]), acc);
             }
             if (F == 64 || lane < F) {
-                float *sp = S + b1 * F + f;
-                *sp = (c0 == b0) ? acc : *sp + acc;
+                BT *sp = S + b1 * F + f;
+                IO::store(sp, (c0 == b0) ? acc : IO::load(sp) + acc);
             }
         }
     }
 }
 
 // bond term of a layer's aggregation: a[i] += sum over the bonds b = (i <- j) of wb[b] * g[j]
-template <int F>
+template <int F, typename BT>
 __global__ void __launch_bounds__(256)
 k_bond_aggregate(int64_t N, const int64_t *__restrict__ bptr, const int32_t *__restrict__ sender,
-                 const float *__restrict__ wb, const float *__restrict__ g, float *__restrict__ a)
+                 const BT *__restrict__ wb, const float *__restrict__ g, float *__restrict__ a)
 {
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int64_t i = (int64_t)blockIdx.x * 4 + wave;
     if (i >= N) return;
     const int f = lane & (F - 1);
     float acc = 0.f;
-    for (int64_t b = bptr[i]; b < bptr[i + 1]; ++b) acc = fmaf(wb[b * F + f], g[(int64_t)sender[b] * F + f], acc);
+    for (int64_t b = bptr[i]; b < bptr[i + 1]; ++b) acc = fmaf(Elem<BT>::load(wb + b * F + f), g[(int64_t)sender[b] * F + f], acc);
     if (F == 64 || lane < F) a[i * F + f] += acc;
 }
 
 // reverse of the bond term, the share of gbar: gbar[i] += sum_b wb[mirror(b)] * abar[j]
 // (the reverse bond (j <- i) is the one whose filter multiplies g_i in row j)
-template <int F>
+template <int F, typename BT>
 __global__ void __launch_bounds__(256)
 k_bond_gbar(int64_t N, const int64_t *__restrict__ bptr, const int32_t *__restrict__ sender,
-            const int32_t *__restrict__ bmirror, const float *__restrict__ wb, const float *__restrict__ abar,
+            const int32_t *__restrict__ bmirror, const BT *__restrict__ wb, const float *__restrict__ abar,
             float *gbar)
 {
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
@@ -153,7 +158,7 @@ k_bond_gbar(int64_t N, const int64_t *__restrict__ bptr, const int32_t *__restri
     for (int64_t b = bptr[i]; b < bptr[i + 1]; ++b) {
         const int64_t j = sender[b];
         const int64_t bm = bmirror[b];   // -1: the sender is a ghost row (abar_j = 0 here, its owner adds that term)
-        if (bm >= 0) acc = fmaf(wb[bm * F + f], abar[j * F + f], acc);
+        if (bm >= 0) acc = fmaf(Elem<BT>::load(wb + bm * F + f), abar[j * F + f], acc);
     }
     if (F == 64 || lane < F) gbar[i * F + f] += acc;
 }
@@ -178,13 +183,14 @@ __device__ inline float wave_sum(float v)
 // Reverse of k_triplet_fwd for one centre, any number of bonds, no LDS.  Pbar[b1] and rbar[b1] accumulate over the
 // inner loop in registers; Qbar[b2], ubar[b2] and rbar[b2] are indexed by the inner bond, so they are accumulated
 // in a second sweep with the roles of the loops exchanged (h is recomputed there): every triplet is evaluated twice.
-template <int F>
+template <int F, typename BT>
 __device__ inline void
 triplet_bwd_sweep(int64_t i, int lane, const int64_t *__restrict__ bptr, const float *__restrict__ rhat,
-                  const float *__restrict__ u, const float *__restrict__ P, const float *__restrict__ Q,
-                  const float *__restrict__ Wtc, const float *__restrict__ Sbar, float *__restrict__ Pbar,
-                  float *__restrict__ Qbar, float *__restrict__ ubar, float *__restrict__ rbar)
+                  const float *__restrict__ u, const BT *__restrict__ P, const BT *__restrict__ Q,
+                  const float *__restrict__ Wtc, const BT *__restrict__ Sbar, BT *__restrict__ Pbar,
+                  BT *__restrict__ Qbar, float *__restrict__ ubar, float *__restrict__ rbar)
 {
+    using IO = Elem<BT>;
     const int f = lane & (F - 1);
     const bool on = (F == 64 || lane < F);
     float wc[kAngle];
@@ -193,7 +199,7 @@ triplet_bwd_sweep(int64_t i, int lane, const int64_t *__restrict__ bptr, const f
     const int64_t b0 = bptr[i], be = bptr[i + 1];
     for (int64_t ba = b0; ba < be; ++ba) {
         const float xa = rhat[3 * ba], ya = rhat[3 * ba + 1], za = rhat[3 * ba + 2];
-        const float pa = P[ba * F + f], qa = Q[ba * F + f], sa = Sbar[ba * F + f], ua = u[ba];
+        const float pa = IO::load(P + ba * F + f), qa = IO::load(Q + ba * F + f), sa = IO::load(Sbar + ba * F + f), ua = u[ba];
         float pbar = 0.f, qbar = 0.f, ub = 0.f, rx = 0.f, ry = 0.f, rz = 0.f;
         for (int64_t bo = b0; bo < be; ++bo) {
             if (bo == ba) continue;
@@ -209,13 +215,13 @@ triplet_bwd_sweep(int64_t i, int lane, const int64_t *__restrict__ bptr, const f
             }
             // triplet (b1 = ba, b2 = bo): contributes to Pbar[ba] and, through c, to rbar[ba]
             float s1, ds1;
-            silu_both(pa + Q[bo * F + f] + tw, s1, ds1);
+            silu_both(pa + IO::load(Q + bo * F + f) + tw, s1, ds1);
             const float h1 = sa * u[bo] * ds1;
             pbar += h1;
             // triplet (b1 = bo, b2 = ba): contributes to Qbar[ba], ubar[ba] and, through c, to rbar[ba]
             float s2, ds2;
-            const float so = Sbar[bo * F + f];
-            silu_both(P[bo * F + f] + qa + tw, s2, ds2);
+            const float so = IO::load(Sbar + bo * F + f);
+            silu_both(IO::load(P + bo * F + f) + qa + tw, s2, ds2);
             const float h2 = so * ua * ds2;
             qbar += h2;
             ub = fmaf(so, s2, ub);
@@ -233,8 +239,8 @@ triplet_bwd_sweep(int64_t i, int lane, const int64_t *__restrict__ bptr, const f
             rz += __shfl_xor(rz, off, 64);
         }
         if (on) {
-            Pbar[ba * F + f] = pbar;
-            Qbar[ba * F + f] = qbar;
+            IO::store(Pbar + ba * F + f, pbar);
+            IO::store(Qbar + ba * F + f, qbar);
         }
         if (lane == 0) {
             ubar[ba] += ub;
@@ -254,13 +260,14 @@ constexpr int kPairBonds = 16;   // bonds per centre up to which the pair-wise r
 // contributes to bond a stays in registers; what it contributes to bond o goes to per-lane accumulators in LDS
 // (rows accP, accQ, accU of 64 floats per bond), and dE/dc of the pair, reduced over the features, into a small
 // table from which rbar is assembled at the end with lane = bond.
-template <int F>
+template <int F, typename BT>
 __global__ void __launch_bounds__(256)
 k_triplet_bwd(int64_t N, const int64_t *__restrict__ bptr, const float *__restrict__ rhat, const float *__restrict__ u,
-              const float *__restrict__ P, const float *__restrict__ Q, const float *__restrict__ Wtc,
-              const float *__restrict__ Sbar, float *__restrict__ Pbar, float *__restrict__ Qbar,
+              const BT *__restrict__ P, const BT *__restrict__ Q, const float *__restrict__ Wtc,
+              const BT *__restrict__ Sbar, BT *__restrict__ Pbar, BT *__restrict__ Qbar,
               float *__restrict__ ubar, float *__restrict__ rbar)
 {
+    using IO = Elem<BT>;
     constexpr int NB = kPairBonds;
     __shared__ float acc_lds[4][3 * NB * 64 + NB * NB];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
@@ -269,7 +276,7 @@ k_triplet_bwd(int64_t N, const int64_t *__restrict__ bptr, const float *__restri
     const int64_t b0 = bptr[i];
     const int n = (int)(bptr[i + 1] - b0);
     if (n > NB) {
-        triplet_bwd_sweep<F>(i, lane, bptr, rhat, u, P, Q, Wtc, Sbar, Pbar, Qbar, ubar, rbar);
+        triplet_bwd_sweep<F, BT>(i, lane, bptr, rhat, u, P, Q, Wtc, Sbar, Pbar, Qbar, ubar, rbar);
         return;
     }
     if (n <= 0) return;
@@ -287,7 +294,7 @@ k_triplet_bwd(int64_t N, const int64_t *__restrict__ bptr, const float *__restri
     for (int a = 0; a < n; ++a) {
         const int64_t ba = b0 + a;
         const float xa = rhat[3 * ba], ya = rhat[3 * ba + 1], za = rhat[3 * ba + 2];
-        const float pa = P[ba * F + f], qa = Q[ba * F + f], sa = Sbar[ba * F + f], ua = u[ba];
+        const float pa = IO::load(P + ba * F + f), qa = IO::load(Q + ba * F + f), sa = IO::load(Sbar + ba * F + f), ua = u[ba];
         float pacc = 0.f, qacc = 0.f, uacc = 0.f;
         float drow = 0.f;   // lane o: dE/dc of the pair {a, o}
         for (int o = a + 1; o < n; ++o) {
@@ -301,7 +308,7 @@ k_triplet_bwd(int64_t N, const int64_t *__restrict__ bptr, const float *__restri
                 tw = fmaf(T[k], wc[k], tw);
                 dw = fmaf(dT[k], wc[k], dw);
             }
-            const float po = P[bo * F + f], qo = Q[bo * F + f], so = Sbar[bo * F + f], uo = u[bo];
+            const float po = IO::load(P + bo * F + f), qo = IO::load(Q + bo * F + f), so = IO::load(Sbar + bo * F + f), uo = u[bo];
             // bond o's accumulators: per-lane slots, read here and written at the end of the step (LDS float
             // atomics measured an order of magnitude slower than this read-modify-write)
             const float aq = accQ[o * 64 + lane], ap = accP[o * 64 + lane], au = accU[o * 64 + lane];
@@ -326,8 +333,8 @@ k_triplet_bwd(int64_t N, const int64_t *__restrict__ bptr, const float *__restri
     wave_lds_fence();
     for (int b = 0; b < n; ++b) {
         if (on) {
-            Pbar[(b0 + b) * F + f] = accP[b * 64 + lane];
-            Qbar[(b0 + b) * F + f] = accQ[b * 64 + lane];
+            IO::store(Pbar + (b0 + b) * F + f, accP[b * 64 + lane]);
+            IO::store(Qbar + (b0 + b) * F + f, accQ[b * 64 + lane]);
         }
         const float ub = wave_sum(on ? accU[b * 64 + lane] : 0.f);
         if (lane == 0) ubar[b0 + b] += ub;
@@ -400,15 +407,17 @@ struct BondArgs {                      // one partition
                                        // EBAR: Wt2^T, then the first layers' Wb^T)
     const float *Wx;                   // TAIL, EBAR: the packs of the layers beyond the third (read from global memory)
     int n_layers;                      // TAIL, EBAR
-    size_t wb_stride;                  // TAIL: floats between two layers' wb
-    float *P, *Q;                      // HEAD out
-    const float *S;                    // TAIL in
-    float *m, *wb;                     // TAIL out; EBAR reads m
+    size_t wb_stride;                  // TAIL: elements between two layers' wb
+    // [bonds x F] arrays, elements of type BT (fp32, or bf16 in the bf16 mode)
+    void *P, *Q;                       // HEAD out
+    const void *S;                     // TAIL in
+    void *m, *wb;                      // TAIL out; EBAR reads m
     const float *abar, *g;             // EBAR in: kept per-layer node rows, layer l at abar + l abar_stride, g + l g_stride
     size_t abar_stride, g_stride;
-    float *e1bar;                      // EBAR out; E0BAR in
-    float *ubar, *Sbar;                // EBAR out; E0BAR reads ubar
-    const float *Pbar, *Qbar;          // E0BAR in
+    void *e1bar;                       // EBAR out; E0BAR in (BT)
+    float *ubar;                       // EBAR out; E0BAR in
+    void *Sbar;                        // EBAR out (BT)
+    const void *Pbar, *Qbar;           // E0BAR in (BT)
     float *dbond;                      // E0BAR out
 };
 
@@ -419,12 +428,17 @@ template <int STAGE> struct BondStage {
 };
 
 // PREC: the F x F products follow the precision mode of the filter MLP's (fp32 MFMA; bf16 operands; split-fp16 triples;
-// packs prepared accordingly, activations converted in registers, fp32 accumulation); the K = 8 products and all
-// arrays stay fp32.
+// packs prepared accordingly, activations converted in registers, fp32 accumulation); the K = 8 products stay fp32.
+// The [bonds x F] arrays are bf16 in the bf16 mode and fp32 otherwise.
+template <int PREC> struct BondElem { typedef float type; };
+template <> struct BondElem<kPrecBf16> { typedef __bf16 type; };
+
 template <int F, int STAGE, int PREC>
 __global__ void __launch_bounds__(BondStage<STAGE>::NW * 64) k_bond_mlp(BondArgs A)
 {
     using D = Dims<F>;
+    using BT = typename BondElem<PREC>::type;
+    using IO = Elem<BT>;
     constexpr int NB = D::NB, FS = D::FS;
     constexpr int NW = BondStage<STAGE>::NW, NPACK = BondStage<STAGE>::NPACK;
     constexpr int LPR = TileRegs<F>::LPR, RPI = TileRegs<F>::RPI;
@@ -446,23 +460,26 @@ __global__ void __launch_bounds__(BondStage<STAGE>::NW * 64) k_bond_mlp(BondArgs
     const int64_t stride = (int64_t)gridDim.x * NW;
 
     // rows of a [bonds x F] array in accumulator layout: lane (c32, h) holds features 32 b + 8 a + 4 h + (0..3) of bond c32
-    auto load_rows = [&](const float *Y, int64_t row, bool ok, f32x4 (&v)[NB][4]) {
+    typedef typename IO::raw4 raw4;
+    auto load_rows = [&](const void *Yv, int64_t row, bool ok, raw4 (&v)[NB][4]) {   // as loaded: widen at the use
+        const BT *Y = static_cast<const BT *>(Yv);
 #pragma unroll
         for (int b = 0; b < NB; ++b)
 #pragma unroll
             for (int a = 0; a < 4; ++a) {
-                v[b][a] = f32x4{0.f, 0.f, 0.f, 0.f};
-                if (ok) v[b][a] = *reinterpret_cast<const f32x4 *>(Y + row * F + 32 * b + 8 * a + 4 * h);
+                v[b][a] = raw4{};
+                if (ok) v[b][a] = IO::load4_raw(Y + row * F + 32 * b + 8 * a + 4 * h);
             }
     };
-    auto store_rows = [&](float *Y, int64_t row, bool ok, const f32x16 (&acc)[NB]) {
+    auto store_rows = [&](void *Yv, int64_t row, bool ok, const f32x16 (&acc)[NB]) {
+        BT *Y = static_cast<BT *>(Yv);
         if (ok)
 #pragma unroll
             for (int b = 0; b < NB; ++b)
 #pragma unroll
                 for (int a = 0; a < 4; ++a) {
                     const f32x4 v = {acc[b][4 * a], acc[b][4 * a + 1], acc[b][4 * a + 2], acc[b][4 * a + 3]};
-                    *reinterpret_cast<f32x4 *>(Y + row * F + 32 * b + 8 * a + 4 * h) = v;
+                    IO::store4(Y + row * F + 32 * b + 8 * a + 4 * h, v);
                 }
     };
 
@@ -481,11 +498,11 @@ __global__ void __launch_bounds__(BondStage<STAGE>::NW * 64) k_bond_mlp(BondArgs
     using Fresh = std::false_type;
     using Add = std::true_type;
 
-    TileRegs<F> pre, pre2;
+    TileRegs<F, BT> pre, pre2;
     int64_t ti = (int64_t)blockIdx.x * NW + wave;
     if (ti < n_tiles) {
-        if (STAGE == BOND_TAIL) fetch_tile<F>(pre, A.S, ti * 32, A.n, lane);
-        if (STAGE == BOND_E0BAR) fetch_tile<F>(pre, A.Pbar, ti * 32, A.n, lane);
+        if (STAGE == BOND_TAIL) fetch_tile<F, BT>(pre, static_cast<const BT *>(A.S), ti * 32, A.n, lane);
+        if (STAGE == BOND_E0BAR) fetch_tile<F, BT>(pre, static_cast<const BT *>(A.Pbar), ti * 32, A.n, lane);
     }
     for (; ti < n_tiles; ti += stride) {
         const int64_t row0 = ti * 32;
@@ -508,7 +525,7 @@ __global__ void __launch_bounds__(BondStage<STAGE>::NW * 64) k_bond_mlp(BondArgs
             wave_lds_fence();
             const float uc = ok ? A.u[row] : 0.f;
             const float dc = ok ? A.d[row] : A.bp.rc;
-            if (more) fetch_tile<F>(pre, A.S, (ti + stride) * 32, A.n, lane);
+            if (more) fetch_tile<F, BT>(pre, static_cast<const BT *>(A.S), (ti + stride) * 32, A.n, lane);
             mul_tile(Fresh{}, packs, tile, acc);
             wave_lds_fence();
             store_rows(A.m, row, ok, acc);
@@ -524,14 +541,14 @@ __global__ void __launch_bounds__(BondStage<STAGE>::NW * 64) k_bond_mlp(BondArgs
                 for (int r = 0; r < 16; ++r) e1[b][r] = fmaf(uc, silu_f(acc[b][r]), e1[b][r]);
             for (int l = 0; l < n_lds_layers; ++l) {
                 mul_regs(packs + (1 + l) * D::PACKF, e1, acc);
-                store_rows(A.wb + (size_t)l * A.wb_stride, row, ok, acc);
+                store_rows(static_cast<BT *>(A.wb) + (size_t)l * A.wb_stride, row, ok, acc);
             }
             for (int l = 3; l < A.n_layers; ++l) {
                 mul_regs(A.Wx + (size_t)(l - 3) * D::PACKF, e1, acc);
-                store_rows(A.wb + (size_t)l * A.wb_stride, row, ok, acc);
+                store_rows(static_cast<BT *>(A.wb) + (size_t)l * A.wb_stride, row, ok, acc);
             }
         } else if (STAGE == BOND_EBAR) {
-            f32x4 mv[NB][4];
+            raw4 mv[NB][4];
             load_rows(A.m, row, ok, mv);   // needed after the products
             const float uc = ok ? A.u[row] : 0.f;
             int32_t ri[32 / RPI], rj[32 / RPI];   // receiver and sender rows of this lane's tile rows
@@ -578,7 +595,7 @@ __global__ void __launch_bounds__(BondStage<STAGE>::NW * 64) k_bond_mlp(BondArgs
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     float sv, ds;
-                    silu_both(mv[b][r / 4][r % 4], sv, ds);
+                    silu_both(IO::widen4(mv[b][r / 4])[r % 4], sv, ds);
                     part = fmaf(acc[b][r], sv, part);
                     mb[b][r] = acc[b][r] * uc * ds;
                 }
@@ -589,14 +606,14 @@ __global__ void __launch_bounds__(BondStage<STAGE>::NW * 64) k_bond_mlp(BondArgs
         } else {   // BOND_E0BAR
             stash_tile<F>(pre, tile, lane);
             wave_lds_fence();
-            fetch_tile<F>(pre2, A.Qbar, row0, A.n, lane);   // in flight during the first product
-            f32x4 zv[NB][4];
+            fetch_tile<F, BT>(pre2, static_cast<const BT *>(A.Qbar), row0, A.n, lane);   // in flight during the first product
+            raw4 zv[NB][4];
             load_rows(A.e1bar, row, ok, zv);
             mul_tile(Fresh{}, packs, tile, acc);
             wave_lds_fence();
             stash_tile<F>(pre2, tile, lane);
             wave_lds_fence();
-            if (more) fetch_tile<F>(pre, A.Pbar, (ti + stride) * 32, A.n, lane);
+            if (more) fetch_tile<F, BT>(pre, static_cast<const BT *>(A.Pbar), (ti + stride) * 32, A.n, lane);
             mul_tile(Add{}, packs + D::PACKF, tile, acc);
             wave_lds_fence();
             float bb[8], db[8];
@@ -607,7 +624,7 @@ __global__ void __launch_bounds__(BondStage<STAGE>::NW * 64) k_bond_mlp(BondArgs
 #pragma unroll
             for (int b = 0; b < NB; ++b)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) part = fmaf(zv[b][r / 4][r % 4] + acc[b][r], vv[b][r], part);
+                for (int r = 0; r < 16; ++r) part = fmaf(IO::widen4(zv[b][r / 4])[r % 4] + acc[b][r], vv[b][r], part);
             part += __shfl_xor(part, 32, 64);
             if (ok && h == 0) A.dbond[row] = fmaf(A.ubar[row], A.du[row], part);
         }

@@ -25,33 +25,33 @@ struct NodeBatch {     // up to kBatch partitions per launch, 32-row tiles numbe
 
 // A 32-row tile of X travels global memory -> registers -> LDS in two halves, so that the loads of the next
 // tile can be in flight while the current one is multiplied.
-template <int F> struct TileRegs {
-    static constexpr int LPR = F / 4;        // lanes per row (float4 each)
+template <int F, typename T_ = float> struct TileRegs {
+    static constexpr int LPR = F / 4;        // lanes per row (four elements each)
     static constexpr int RPI = 64 / LPR;     // rows per wave instruction
-    f32x4 v[32 / RPI];
+    typename Elem<T_>::raw4 v[32 / RPI];     // as loaded; widened to fp32 when the tile goes to LDS
 };
 
-template <int F>
-__device__ inline void fetch_tile(TileRegs<F> &T, const float *__restrict__ X, int64_t row0, int64_t n_rows, int lane)
+template <int F, typename T_>
+__device__ inline void fetch_tile(TileRegs<F, T_> &T, const T_ *__restrict__ X, int64_t row0, int64_t n_rows, int lane)
 {
     constexpr int LPR = TileRegs<F>::LPR, RPI = TileRegs<F>::RPI;
     const int rr = lane / LPR, cc = (lane % LPR) * 4;
 #pragma unroll
     for (int r = 0; r < 32; r += RPI) {
         const int64_t row = row0 + r + rr;
-        f32x4 v = {0.f, 0.f, 0.f, 0.f};
-        if (row < n_rows) v = *reinterpret_cast<const f32x4 *>(X + row * F + cc);
+        typename Elem<T_>::raw4 v = {};   // all-zero bits are 0.0 in either type
+        if (row < n_rows) v = Elem<T_>::load4_raw(X + row * F + cc);
         T.v[r / RPI] = v;
     }
 }
 
-template <int F> __device__ inline void stash_tile(const TileRegs<F> &T, float *tile, int lane)
+template <int F, typename T_> __device__ inline void stash_tile(const TileRegs<F, T_> &T, float *tile, int lane)
 {
     constexpr int FS = Dims<F>::FS;
     constexpr int LPR = TileRegs<F>::LPR, RPI = TileRegs<F>::RPI;
     const int rr = lane / LPR, cc = (lane % LPR) * 4;
 #pragma unroll
-    for (int r = 0; r < 32; r += RPI) *reinterpret_cast<f32x4 *>(tile + (r + rr) * FS + cc) = T.v[r / RPI];
+    for (int r = 0; r < 32; r += RPI) *reinterpret_cast<f32x4 *>(tile + (r + rr) * FS + cc) = Elem<T_>::widen4(T.v[r / RPI]);
 }
 
 template <int F, int OP>
@@ -201,7 +201,8 @@ struct SmallArgs {   // one partition
     float *h, *g, *gbar, *abar, *floc, *eps;
     const float *dsum, *wstore, *d;
     const int32_t *bond_of_edge;   // three-body variant (or nullptr)
-    const float *wb;
+    const void *wb;                // bond filter rows of the layer: fp32, or bf16 if wb_bf16
+    int wb_bf16;
     double *energy_part;
 };
 
@@ -290,7 +291,9 @@ __global__ void __launch_bounds__(256) k_ghost_gbar(SmallBatch B)
             const int64_t j = __builtin_amdgcn_readlane(jl, k), m = __builtin_amdgcn_readlane(ml, k);
             const int64_t b = __builtin_amdgcn_readlane(bl, k);
             wv[k] = A.wstore[m * F + f];
-            if (b >= 0) wv[k] += A.wb[b * F + f];
+            if (b >= 0)
+                wv[k] += A.wb_bf16 ? Elem<__bf16>::load(static_cast<const __bf16 *>(A.wb) + b * F + f)
+                                   : static_cast<const float *>(A.wb)[b * F + f];
             av[k] = A.abar[j * F + f];
         }
 #pragma unroll

@@ -23,6 +23,44 @@ __device__ inline void wave_lds_fence()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// Element access for arrays that are kept as fp32 or, in the bf16 precision mode, as bf16: rounded to nearest even
+// on the way out, exact on the way in.  load4 / store4 move four consecutive elements; load4_raw returns them
+// as loaded and widen4 converts later, so that a prefetch does not have to wait for its data to convert it.
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+    static __device__ inline float load(const float *p) { return *p; }
+    static __device__ inline void store(float *p, float v) { *p = v; }
+    typedef f32x4 raw4;
+    static __device__ inline raw4 load4_raw(const float *p) { return *reinterpret_cast<const f32x4 *>(p); }
+    static __device__ inline f32x4 widen4(raw4 w) { return w; }
+    static __device__ inline f32x4 load4(const float *p) { return *reinterpret_cast<const f32x4 *>(p); }
+    static __device__ inline void store4(float *p, f32x4 v) { *reinterpret_cast<f32x4 *>(p) = v; }
+};
+template <> struct Elem<__bf16> {
+    static __device__ inline float load(const __bf16 *p)
+    {
+        return __builtin_bit_cast(float, (unsigned)*reinterpret_cast<const unsigned short *>(p) << 16);
+    }
+    static __device__ inline void store(__bf16 *p, float v) { *p = (__bf16)v; }
+    typedef uint2 raw4;
+    static __device__ inline raw4 load4_raw(const __bf16 *p) { return *reinterpret_cast<const uint2 *>(p); }
+    static __device__ inline f32x4 widen4(raw4 w)
+    {
+        return f32x4{__builtin_bit_cast(float, w.x << 16), __builtin_bit_cast(float, w.x & 0xffff0000u),
+                     __builtin_bit_cast(float, w.y << 16), __builtin_bit_cast(float, w.y & 0xffff0000u)};
+    }
+    static __device__ inline f32x4 load4(const __bf16 *p) { return widen4(load4_raw(p)); }
+    static __device__ inline void store4(__bf16 *p, f32x4 v)
+    {
+        const bf16x2 lo = __builtin_convertvector(f32x2{v[0], v[1]}, bf16x2);
+        const bf16x2 hi = __builtin_convertvector(f32x2{v[2], v[3]}, bf16x2);
+        uint2 w;
+        w.x = __builtin_bit_cast(unsigned, lo);
+        w.y = __builtin_bit_cast(unsigned, hi);
+        *reinterpret_cast<uint2 *>(p) = w;
+    }
+};
+
 __device__ inline float sigmoidf_fast(float x) { return __builtin_amdgcn_rcpf(1.0f + __expf(-x)); }
 
 // The edge kernels evaluate SiLU on pre-scaled pre-activations t' = c t with c = -log2(e):

@@ -160,12 +160,31 @@ int node_pass(mlip_graph *g, SlabView *views, int P, const float *P1, const floa
 // Edge-kernel launches of one call: two per layer and batch of partitions (L <= 8, at most 64 / kBatch batches).
 constexpr int kWorkLaunches = 2 * 8 * (64 / kBatch);
 
+// The reverse edge kernel the library runs is the one whose wavefronts alternate between the two phases.  Building
+// with -DMLIP_BWD_ROLES selects the variant with specialised wavefronts instead (same results; measured slower, kept
+// for that experiment).
+#ifdef MLIP_BWD_ROLES
+template <int F, int PREC> struct BwdKernel {
+    static constexpr int threads = (kStreamWaves + kDenseWaves) * 64, item_waves = kStreamWaves;
+    static constexpr size_t lds = BwdRolesLds<F>::bytes;
+    static const void *fn() { return reinterpret_cast<const void *>(&k_edge_bwd_roles<F, PREC>); }
+    static void launch(unsigned blocks, hipStream_t s, const EdgeBatch &b) { k_edge_bwd_roles<F, PREC><<<blocks, threads, lds, s>>>(b); }
+};
+#else
+template <int F, int PREC> struct BwdKernel {
+    static constexpr int threads = kBwdWaves * 64, item_waves = kBwdWaves;
+    static constexpr size_t lds = Lds<F>::edge_bwd;
+    static const void *fn() { return reinterpret_cast<const void *>(&k_edge_bwd<F, PREC>); }
+    static void launch(unsigned blocks, hipStream_t s, const EdgeBatch &b) { k_edge_bwd<F, PREC><<<blocks, threads, lds, s>>>(b); }
+};
+#endif
+
 template <int F, int PREC> int launch_edge(mlip_graph *g, EdgeBatch &b, bool backward)
 {
-    const size_t lds = backward ? Lds<F>::edge_bwd : Lds<F>::edge_fwd;
+    using BK = BwdKernel<F, PREC>;
+    const size_t lds = backward ? BK::lds : Lds<F>::edge_fwd;
     // resident blocks per compute unit, queried once per kernel and handle
-    const void *fn = backward ? reinterpret_cast<const void *>(&k_edge_bwd<F, PREC>)
-                              : reinterpret_cast<const void *>(&k_edge_fwd<F, PREC>);
+    const void *fn = backward ? BK::fn() : reinterpret_cast<const void *>(&k_edge_fwd<F, PREC>);
     int slot = 0;
     MLIP_TRY(configure_kernel(g, fn, lds, &slot));
     int occ = g->fn_occ[slot].second;
@@ -174,7 +193,7 @@ template <int F, int PREC> int launch_edge(mlip_graph *g, EdgeBatch &b, bool bac
         MLIP_HIP(hipGetDevice(&dev));
         MLIP_HIP(hipDeviceGetAttribute(&g->n_cu, hipDeviceAttributeMultiprocessorCount, dev));
         if (backward)
-            MLIP_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&o, k_edge_bwd<F, PREC>, kBwdWaves * 64, lds));
+            MLIP_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&o, fn, BK::threads, lds));
         else
             MLIP_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&o, k_edge_fwd<F, PREC>, 256, lds));
         if (o < 1 || g->n_cu < 8) {
@@ -195,11 +214,11 @@ template <int F, int PREC> int launch_edge(mlip_graph *g, EdgeBatch &b, bool bac
     if (items <= 0) return MLIP_OK;
     // persistent grid: what is resident at once, a multiple of the 8 XCDs, no more than the work needs
     const int64_t resident = (int64_t)(g->n_cu / 8) * occ;
-    const int nw = backward ? kBwdWaves : 4;
+    const int nw = backward ? BK::item_waves : 4;
     const int64_t needed = ((items + 7) / 8 + nw - 1) / nw;
     const unsigned blocks = (unsigned)(8 * std::max<int64_t>(1, std::min(resident, needed)));
     if (backward)
-        k_edge_bwd<F, PREC><<<blocks, kBwdWaves * 64, lds, g->stream>>>(b);
+        BK::launch(blocks, g->stream, b);
     else
         k_edge_fwd<F, PREC><<<blocks, 256, lds, g->stream>>>(b);
     MLIP_HIP(hipGetLastError());

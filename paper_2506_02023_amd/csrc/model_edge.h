@@ -622,4 +622,371 @@ __global__ void __launch_bounds__(kBwdWaves * 64, kBwdWaves == 4 ? 2 : 1) k_edge
 #endif
 }
 
+
+#ifdef MLIP_BWD_ROLES
+// ---- Reverse edge step with specialised wavefronts (an experiment: compiled only with -DMLIP_BWD_ROLES)
+//
+// The same two phases, but no wavefront alternates between them: of the 12 wavefronts of a block (one block per
+// compute unit, three wavefronts per SIMD) eight stream (phase 1) and four do the dense work (phase 2) of the pairs
+// that "their" two streaming wavefronts queued.  The idea: the streaming phase waits for memory and needs a
+// quarter of the vector pipeline, the dense phase is bound by the MFMA pipeline and touches no memory but its
+// results, so side by side they should overlap.  Measured, they do not: 5.95 ms per launch against 4.67 ms for the
+// alternating kernel on the 1M-atom benchmark (6.05 ms with four streaming wavefronts and full tiles).  While a
+// dense wavefront issues its chain of 64-cycle fp32 MFMAs, every vector instruction of the streaming wavefronts
+// on that SIMD (about 150 per step: readlanes, address arithmetic, the products) waits for the pipeline that the
+// two kinds of instruction share.
+//
+// Hand-over: every streaming wavefront owns a ring of kRoleQueue slots in LDS (slot layout as above, plus the
+// partition index, since pairs of several partitions now share the ring).  All wavefronts of the block meet at one
+// barrier per round.  Before the barrier a streaming wavefront publishes how many pairs it has produced in all and
+// whether it is out of work; after it, every wavefront reads the four published pairs of numbers and derives from
+// them, by the same rule, how many pairs each dense wavefront takes in this round (kRoleTake as soon as that many
+// are there, the rest once the producer is done).  Because all derive the same numbers, nothing flows back from
+// the consumers, and all agree on the round after which everything is consumed: the loop bound of every
+// wavefront, so no barrier is left waiting.  A streaming wavefront ends its round once kRoleTake pairs are pending
+// beyond what the consumer is known to take; slots being read (at most kRoleTake) plus pending ones (less than
+// kRoleTake + kStep) plus the slot a step writes speculatively stay within the ring.
+// The published numbers alternate between two sets, so a set is rewritten only after a barrier that every reader of
+// its previous contents has passed.
+constexpr int kStreamWaves = 8;   // streaming wavefronts per block (two per SIMD), one ring each
+constexpr int kDenseWaves = 4;    // dense wavefronts per block (one per SIMD); each serves kStreamWaves / kDenseWaves rings
+constexpr int kRoleTake = 24;     // pairs a dense step takes from a ring (of the MFMA tile's 32 columns: the rings of a
+                                  // block must fit the LDS, and this is what bounds their length)
+constexpr int kRoleQueue = 65;    // slots of a ring
+static_assert(kRoleQueue >= 2 * kRoleTake + kStep + 1, "ring too small for the hand-over protocol");
+static_assert(kStreamWaves % kDenseWaves == 0, "every dense wavefront serves the same number of rings");
+
+template <int F> struct BwdRolesLds {
+    using D = Dims<F>;
+    static constexpr int kQueuesAt = D::PACKF + D::PACK1;                       // floats
+    static constexpr int kPubAt = kQueuesAt + kStreamWaves * kRoleQueue * D::FS;   // int32 [2][kStreamWaves][2]
+    static constexpr int kTabAt = kPubAt + 4 * kStreamWaves;                       // float* [kBatch], 8-byte aligned
+    static constexpr size_t bytes = sizeof(float) * kTabAt + sizeof(float *) * kBatch;
+    static_assert(kTabAt % 2 == 0, "pointer table must be 8-byte aligned");
+};
+
+template <int F, int PREC>
+__global__ void __launch_bounds__((kStreamWaves + kDenseWaves) * 64, 1) k_edge_bwd_roles(EdgeBatch B)
+{
+    using D = Dims<F>;
+    using L = BwdRolesLds<F>;
+    constexpr int FS = D::FS;
+    constexpr int kRowBytes = F * 4;
+    constexpr int kThreads = (kStreamWaves + kDenseWaves) * 64;
+    extern __shared__ float lds[];
+    float *A2n = lds;
+    float *A1l = A2n + D::PACKF;
+    float *queues = lds + L::kQueuesAt;
+    int32_t *pub = reinterpret_cast<int32_t *>(lds + L::kPubAt);
+    float **dsum_tab = reinterpret_cast<float **>(lds + L::kTabAt);
+    for (int i = threadIdx.x; i < (PREC == kPrecBf16 ? D::PACKF / 2 : D::PACKF); i += kThreads) A2n[i] = B.c.A2n[i];
+    for (int i = threadIdx.x; i < D::PACK1; i += kThreads) A1l[i] = B.c.A1[i];
+    if (threadIdx.x < 4 * kStreamWaves) pub[threadIdx.x] = 0;
+    if (threadIdx.x < kBatch) dsum_tab[threadIdx.x] = (threadIdx.x < B.n) ? B.s[threadIdx.x].dsum : nullptr;
+    __syncthreads();
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const bool streams = wave < kStreamWaves;
+    const int mine = streams ? wave : wave - kStreamWaves;   // streaming: the ring it fills; dense: the first ring it empties
+    const int c32 = lane & 31;
+    const int l16 = lane % kStep;
+    const unsigned f = lane & (F - 1);
+    const EdgeCommon &C = B.c;
+    const bool need_gbar = C.need_gbar != 0;
+
+    // ---- the rounds' bookkeeping, identical in every wavefront
+    int round = 0;
+    int consumed[kStreamWaves];   // pairs taken from every ring so far
+    int take[kStreamWaves];       // ... and in the current round
+#pragma unroll
+    for (int q = 0; q < kStreamWaves; ++q) consumed[q] = 0;
+    int consumed_mine = 0;        // streaming: consumed[mine]
+    // meets the other wavefronts; returns true if this round's takes empty every ring of a finished producer
+    auto rendezvous = [&]() -> bool {
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // LDS writes done; loads in flight stay in flight
+        const int32_t *pb = pub + (round & 1) * (2 * kStreamWaves);   // (re-read: the barrier statement clobbers memory)
+        bool finished = true;
+#pragma unroll
+        for (int q = 0; q < kStreamWaves; ++q) {
+            const int produced = __builtin_amdgcn_readfirstlane(pb[2 * q]);
+            const int done = __builtin_amdgcn_readfirstlane(pb[2 * q + 1]);
+            const int avail = produced - consumed[q];
+            take[q] = (avail >= kRoleTake || done) ? min(avail, kRoleTake) : 0;
+            consumed[q] += take[q];
+            finished = finished && done && produced == consumed[q];
+            if (q == mine) consumed_mine = consumed[q];
+        }
+        ++round;
+        return finished;
+    };
+
+    if (!streams) {
+        // ================================================================ dense wavefronts
+        constexpr int kRings = kStreamWaves / kDenseWaves;
+        int q_head[kRings];
+#pragma unroll
+        for (int j = 0; j < kRings; ++j) q_head[j] = 0;
+        auto dense = [&](const float *Q, int head, int nval) {
+            int slot = head + c32;
+            slot -= (slot >= kRoleQueue) ? kRoleQueue : 0;
+            const bool valid = c32 < nval;
+            const int4 rec = *reinterpret_cast<const int4 *>(Q + slot * FS + F);   // e, m, d, partition
+            const int32_t e2 = valid ? rec.x : 0, m2 = valid ? rec.y : 0;
+            const float d2 = valid ? __builtin_bit_cast(float, rec.z) : C.bp.rc;   // rc: zero derivative
+            // (the table holds pointers to global memory; saying so keeps the stores off the flat path)
+            typedef __attribute__((address_space(1))) float global_float;
+            global_float *dsum = (global_float *)dsum_tab[valid ? rec.w : 0];
+            float b[8], db[8];
+            radial_basis<true>(d2, C.bp, b, db);
+#pragma unroll
+            for (int n = 0; n < 8; ++n) b[n] *= kSiluScale;   // pre-activations come out as t' = c t
+            f32x16 t[D::NB];   // ds_k/dd = SiLU'(t_k) c_k, one block of 32 features at a time
+#pragma unroll
+            for (int bb = 0; bb < D::NB; ++bb) {
+                f32x16 cg;
+                RegPack1<F> W1;
+#pragma unroll
+                for (int s4 = 0; s4 < 4; ++s4) W1.v[bb][s4] = A1l[(bb * 4 + s4) * 64 + lane];
+                gemm_k8r_block<F>(W1, b, bb, t[bb], lane);
+                gemm_k8r_block<F>(W1, db, bb, cg, lane);
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const float sg = sigmoid_scaled(t[bb][r]);
+                    const float ss = t[bb][r] * sg * kSiluScaleInv;               // SiLU(t)
+                    t[bb][r] = fmaf(ss, 1.0f - sg, sg) * cg[r];
+                }
+            }
+            f32x16 sb[D::NB];
+            if (PREC == kPrecBf16)   // sbar[k] = sum_f W2[k][f] wsym[f]
+                gemm_row_bf16<F>(reinterpret_cast<const __bf16 *>(A2n), Q + slot * FS, sb, lane);
+            else if (PREC == kPrecF16x3)
+                gemm_row_f16x3<F>(reinterpret_cast<const _Float16 *>(A2n), Q + slot * FS, sb, lane);
+            else
+                gemm_queue<F>(A2n, Q + slot * FS, sb, lane);
+            float part = 0.f;
+#pragma unroll
+            for (int bb = 0; bb < D::NB; ++bb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) part = fmaf(sb[bb][r], t[bb][r], part);
+            part += __shfl_xor(part, 32, 64);
+            if (valid && lane < 32) {
+                // every edge is written by exactly one pair per launch; after the first layer the value is added
+                if (C.first) {
+                    dsum[e2] = part;
+                    dsum[m2] = part;
+                } else {
+                    __builtin_amdgcn_global_atomic_fadd_f32(dsum + e2, part);
+                    __builtin_amdgcn_global_atomic_fadd_f32(dsum + m2, part);
+                }
+            }
+        };
+        for (;;) {
+            const bool finished = rendezvous();
+#pragma unroll
+            for (int j = 0; j < kRings; ++j) {
+                int nval = 0;
+#pragma unroll
+                for (int q = 0; q < kStreamWaves; ++q)
+                    if (q == mine + j * kDenseWaves) nval = take[q];
+                if (nval > 0) {
+                    dense(queues + (mine + j * kDenseWaves) * (kRoleQueue * FS), q_head[j], nval);
+                    q_head[j] += nval;
+                    q_head[j] -= (q_head[j] >= kRoleQueue) ? kRoleQueue : 0;
+                }
+            }
+            if (finished) break;
+        }
+        return;
+    }
+
+    // ==================================================================== streaming wavefronts
+    float *Q = queues + mine * (kRoleQueue * FS);
+    char *Qf = reinterpret_cast<char *>(Q + f);
+    int produced = 0;   // pairs queued so far
+    int q_tail = 0;     // produced % kRoleQueue
+    auto publish = [&](int done) {
+        if (lane == 0) {
+            int32_t *pb = pub + (round & 1) * (2 * kStreamWaves) + 2 * mine;
+            pb[0] = produced;
+            pb[1] = done;
+        }
+    };
+
+    const ItemQueue items = edge_items(B.chunk_start[B.n], B.work, wave, kStreamWaves);
+    int64_t item = items.first;
+    int32_t drawn = 0;
+    for (int part = 0; part < B.n; ++part) {
+    const int64_t part_end = min(items.end, B.chunk_start[part + 1]);
+    if (item >= part_end) continue;
+    const EdgeArgs A = B.s[part];
+    const __amdgpu_buffer_rsrc_t g_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float *>(A.g), 0, (int)(A.n_nodes * kRowBytes), kBufferFlags);
+    const __amdgpu_buffer_rsrc_t a_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float *>(A.abar), 0, (int)(A.n_nodes * kRowBytes), kBufferFlags);
+    const __amdgpu_buffer_rsrc_t o_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        A.out, 0, need_gbar ? (int)(A.n_rows * kRowBytes) : 0, kBufferFlags);   // gbar rows; nothing is stored without it
+    auto store_row = [&](int32_t row, float v) {
+        if (F == 64 || lane < F) buffer_store_f32(v, o_rsrc, f * 4, row * kRowBytes, 0);
+    };
+    int32_t r1 = 0, e_hi = 0;
+    float acc = 0.f;
+
+    // Steps of kStep edges through a software pipeline whose loads are all issued ahead of their use: the edge
+    // records (sender, receiver, reverse edge, length) two steps ahead, the rows they point to one step ahead.
+    // Vector memory loads complete in order, so a stage may only contain loads and address arithmetic; anything
+    // that consumes a loaded value belongs to a later stage.
+    struct Ids {    // lane k (mod kStep) holds edge tb + k, clamped to the last edge of the work item
+        int32_t sj, rk, mk;
+        float dk;
+    };
+    struct Step {
+        float av[kStep], gv[kStep], wv[kStep];   // abar / g rows of the senders, kept filter values
+        float ai0, gi0, ai1, gi1;       // abar / g rows of the first and of the last edge's receiver
+        int kmax;                       // valid edges in the step
+        int32_t tb;
+    };
+    auto load_ids = [&](Ids &I, int32_t tb) {
+        const int32_t e = min((int32_t)tb + l16, e_hi - 1);
+        I.sj = A.senders[e];
+        I.rk = A.recv[e];
+        I.mk = A.mirror[e];
+        I.dk = A.d[e];
+    };
+    auto load_step = [&](Step &S, const Ids &I, int32_t tb) {
+        S.tb = tb;
+        S.kmax = __builtin_amdgcn_readfirstlane(max(0, min(kStep, e_hi - tb)));
+        // A step past the end of the work item (kmax = 0) still issues its loads, from the clamped records:
+        // every path through the pipeline then has the same number of loads in flight, which is what lets
+        // the waits before the uses be partial ones.
+        const int32_t sjo = I.sj * kRowBytes;
+        const int32_t row0 = __builtin_amdgcn_readfirstlane(I.rk);
+        const int32_t rowl = __builtin_amdgcn_readlane(I.rk, max(S.kmax - 1, 0));
+        S.ai0 = buffer_load_f32(a_rsrc, f * 4, row0 * kRowBytes, 0);
+        S.gi0 = buffer_load_f32(g_rsrc, f * 4, row0 * kRowBytes, 0);
+        S.ai1 = buffer_load_f32(a_rsrc, f * 4, rowl * kRowBytes, 0);
+        S.gi1 = buffer_load_f32(g_rsrc, f * 4, rowl * kRowBytes, 0);
+        // w_e sits at the edge's own index (a range of zero bytes reads 0: without gbar no w is needed)
+        const __amdgpu_buffer_rsrc_t w_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+            A.wstore + (need_gbar ? (int64_t)tb * F : 0), 0, need_gbar ? S.kmax * kRowBytes : 0, kBufferFlags);
+#pragma unroll
+        for (int k = 0; k < kStep; ++k) {
+            const int32_t so = __builtin_amdgcn_readlane(sjo, k);
+            S.av[k] = buffer_load_f32(a_rsrc, f * 4, so, 0);
+            S.gv[k] = buffer_load_f32(g_rsrc, f * 4, so, 0);
+            S.wv[k] = buffer_load_f32_stream(w_rsrc, f * 4, k * kRowBytes);   // 0 outside the descriptor's range
+        }
+    };
+    // rn_first: receiver of the first edge of the following step (r1 after the last step)
+    auto compute_step = [&](const Step &S, const Ids &I, int32_t rn_first) {
+        if (S.kmax <= 0) return;
+        const bool valid_l = l16 < S.kmax;
+        const int32_t rk = valid_l ? I.rk : r1;
+        const int32_t e_l = S.tb + l16;
+        // wave-uniform masks: bit k = edge k ends its row / edge k is the upper edge of its pair
+        const int32_t up = __shfl(rk, l16 + 1, 64);
+        const int32_t rnext = (l16 == kStep - 1) ? rn_first : up;
+        const uint32_t ends = (uint32_t)__ballot(valid_l && rnext != rk) & ((1u << kStep) - 1u);
+        const bool upper_l = valid_l && I.mk > e_l;
+        const uint32_t uppers = (uint32_t)__ballot(upper_l) & ((1u << kStep) - 1u);
+        {   // records of the pairs queued by this step, all at once: slots follow q_tail in edge order
+            int slot = q_tail + (int)__builtin_amdgcn_mbcnt_lo(uppers, 0u);   // upper edges before this lane's (lanes < kStep)
+            slot -= (slot >= kRoleQueue) ? kRoleQueue : 0;
+            if (upper_l && lane < kStep) {
+                float *rec = Q + slot * FS + F;
+                reinterpret_cast<int32_t *>(rec)[0] = e_l;
+                reinterpret_cast<int32_t *>(rec)[1] = I.mk;
+                rec[2] = I.dk;
+                reinterpret_cast<int32_t *>(rec)[3] = part;
+            }
+        }
+        const int32_t row_last = __builtin_amdgcn_readlane(rk, S.kmax - 1);
+        float ai = S.ai0, gi = S.gi0;
+        int q_off = q_tail * (FS * 4);   // byte offset of the slot the next pair goes to
+#pragma unroll
+        for (int k = 0; k < kStep; ++k) {
+            acc = fmaf(S.wv[k], S.av[k], acc);   // edges past the end contribute w = 0
+            // wsym goes to the next free slot whether or not the edge is an upper one; only an upper edge
+            // advances the slot, anything else is overwritten by the next edge
+            *reinterpret_cast<float *>(Qf + q_off) = fmaf(ai, S.gv[k], S.av[k] * gi);
+            q_off += (uppers & (1u << k)) ? FS * 4 : 0;
+            q_off = (q_off == kRoleQueue * FS * 4) ? 0 : q_off;
+            if (__builtin_expect((ends & (1u << k)) != 0, 0)) {   // unlikely: keeps the common path free of taken branches
+                const int32_t rrow = __builtin_amdgcn_readlane(rk, k);
+                const int32_t nrow = __builtin_amdgcn_readlane(rnext, k);
+                store_row(rrow, acc);
+                for (int32_t r = rrow + 1; r < nrow; ++r) store_row(r, 0.f);   // empty rows in between
+                acc = 0.f;
+                if (k + 1 < S.kmax) {   // the next row starts inside this step
+                    ai = S.ai1;
+                    gi = S.gi1;
+                    if (nrow != row_last) {   // a third row inside one step (short rows): fetch it now
+                        ai = buffer_load_f32(a_rsrc, f * 4, nrow * kRowBytes, 0);
+                        gi = buffer_load_f32(g_rsrc, f * 4, nrow * kRowBytes, 0);
+                        // complete the two loads here: left pending, they would make every later use of
+                        // ai / gi, on the common path too, wait for all loads in flight
+                        asm volatile("" : "+v"(ai), "+v"(gi));
+                    }
+                }
+            }
+        }
+        const int n_new = __builtin_popcount(uppers);
+        produced += n_new;
+        q_tail += n_new;
+        q_tail -= (q_tail >= kRoleQueue) ? kRoleQueue : 0;
+    };
+    // end of a round: enough pairs are pending beyond what the consumer is known to take
+    auto maybe_round = [&]() {
+        if (produced - consumed_mine >= kRoleTake) {
+            publish(0);
+            rendezvous();
+        }
+    };
+
+    for (; item < part_end; item = items.resolve(drawn)) {
+        drawn = items.draw(lane);
+        const int64_t chunk = item - B.chunk_start[part];
+        int64_t r0_, r1_;
+        if (!chunk_rows(A, chunk, r0_, r1_)) continue;
+        const int32_t r0 = (int32_t)r0_;
+        r1 = (int32_t)r1_;
+        const int32_t e_lo = __builtin_amdgcn_readfirstlane((int32_t)A.row_ptr[r0]);   // wave-uniform: keep them scalar
+        e_hi = __builtin_amdgcn_readfirstlane((int32_t)A.row_ptr[r1]);
+        acc = 0.f;
+        if (e_lo >= e_hi) {   // only empty rows
+            for (int32_t r = r0; r < r1; ++r) store_row(r, 0.f);
+            continue;
+        }
+        Ids IA, IB, IC;
+        Step SA, SB;
+        load_ids(IA, e_lo);
+        load_ids(IB, e_lo + kStep);
+        {   // rows of the chunk before its first edge are empty
+            const int32_t first = __builtin_amdgcn_readfirstlane(IA.rk);
+            for (int32_t r = r0; r < first; ++r) store_row(r, 0.f);
+        }
+        load_step(SA, IA, e_lo);
+        for (int32_t tb = e_lo; tb < e_hi; tb += 2 * kStep) {
+            int32_t nf;
+            load_ids(IC, tb + 2 * kStep);
+            load_step(SB, IB, tb + kStep);
+            nf = __builtin_amdgcn_readfirstlane(IB.rk);
+            compute_step(SA, IA, (tb + kStep < e_hi) ? nf : r1);
+            maybe_round();
+            load_ids(IA, tb + 3 * kStep);
+            load_step(SA, IC, tb + 2 * kStep);
+            nf = __builtin_amdgcn_readfirstlane(IC.rk);
+            compute_step(SB, IB, (tb + 2 * kStep < e_hi) ? nf : r1);
+            maybe_round();
+            IB = IA;   // records of step tb + 3 kStep, loaded a step ago
+            IA = IC;   // records of step tb + 2 kStep, whose rows SA holds
+        }
+    }   // work items
+    }   // partitions
+    // out of work: keep meeting the others until every ring is empty
+    for (;;) {
+        publish(1);
+        if (rendezvous()) break;
+    }
+}
+#endif  // MLIP_BWD_ROLES
+
 #endif  // MLIP_MODEL_EDGE_H

@@ -8,6 +8,7 @@
 // row of one or two arrays and reads the edge's own row of a streamed array.
 //   layout 1: one feature per lane, one `buffer_load_dword` per row (the kernel's layout): 16 per array and step
 //   layout 4: four features per lane, one `buffer_load_dwordx4` per four rows: 4 per array and step
+//   layout 2: the two gathered arrays interleaved per feature, one `buffer_load_dwordx2` fetches both rows: 16 per step
 // The bytes are the same; only the number of vector memory instructions differs.
 //
 // Build and run (one MI355X):
@@ -37,6 +38,7 @@ constexpr int kBufferFlags = 0x00020000;   // raw buffer, data format 32 bits
     } while (0)
 
 struct Args {
+    const float *ag;   // layout 2: the two gathered arrays interleaved per feature, [row][64][2]
     const float *a, *g, *w;
     const int32_t *senders;
     float *out;
@@ -83,6 +85,43 @@ __global__ void __launch_bounds__(256, PER_SIMD) k_gather(Args A)
                 for (int k = 0; k < kStep; ++k) {
                     float v = av[b][k];
                     if (ARRAYS >= 2) v *= gv[b][k];
+                    acc = (ARRAYS >= 3) ? fmaf(v, wv[b][k], acc) : acc + v;
+                }
+            };
+            int32_t s_cur = s_next;
+            s_next = sp[kStep + (lane & (kStep - 1))];
+            issue(0, s_cur, 0);
+#pragma unroll 1
+            for (int t = 0; t < kChunk / kStep; t += 2) {
+                int32_t s2 = sp[min((t + 2) * kStep, kChunk - kStep) + (lane & (kStep - 1))];
+                issue(1, s_next, t + 1);
+                consume(0);
+                int32_t s3 = sp[min((t + 3) * kStep, kChunk - kStep) + (lane & (kStep - 1))];
+                if (t + 2 < kChunk / kStep) issue(0, s2, t + 2);
+                consume(1);
+                s_next = s3;
+            }
+        } else if (LAYOUT == 2) {
+            typedef float f32x2 __attribute__((ext_vector_type(2)));
+            const __amdgpu_buffer_rsrc_t ag_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+                const_cast<float *>(A.ag), 0, (int)(A.n_rows * 2 * kRowBytes), kBufferFlags);
+            f32x2 agv[2][kStep];
+            float wv[2][kStep];
+            auto issue = [&](int b, int32_t sj, int t) {
+                const int32_t so = sj * 2 * kRowBytes;
+#pragma unroll
+                for (int k = 0; k < kStep; ++k) {
+                    const int32_t o = __builtin_amdgcn_readlane(so, k);
+                    agv[b][k] = __builtin_bit_cast(f32x2, __builtin_amdgcn_raw_buffer_load_b64(ag_rsrc, lane * 8, o, 0));
+                    if (ARRAYS >= 3)
+                        wv[b][k] = __builtin_bit_cast(
+                            float, __builtin_amdgcn_raw_buffer_load_b32(w_rsrc, lane * 4, (t * kStep + k) * kRowBytes, 2));
+                }
+            };
+            auto consume = [&](int b) {
+#pragma unroll
+                for (int k = 0; k < kStep; ++k) {
+                    const float v = agv[b][k][0] * agv[b][k][1];
                     acc = (ARRAYS >= 3) ? fmaf(v, wv[b][k], acc) : acc + v;
                 }
             };
@@ -206,6 +245,10 @@ int main()
     CHECK(hipMalloc(&a, N * kRowBytes));
     CHECK(hipMalloc(&g, N * kRowBytes));
     CHECK(hipMalloc(&w, E * (int64_t)kRowBytes));
+    float *ag;
+    CHECK(hipMalloc(&ag, N * 2 * kRowBytes));
+    CHECK(hipMemset(ag, 0, N * 2 * kRowBytes));
+    A.ag = ag;
     CHECK(hipMalloc(&sd, E * 4));
     CHECK(hipMalloc(&out, 1024 * 4 * 64 * 4));
     CHECK(hipMemset(a, 0, N * kRowBytes));
@@ -225,6 +268,9 @@ int main()
     run<4, 2>(A, "two gathered arrays, dwordx4 loads");
     run<1, 3>(A, "two gathered + one streamed, dword loads");
     run<4, 3>(A, "two gathered + one streamed, dwordx4 loads");
+    run<2, 2>(A, "two gathered arrays interleaved, dwordx2 loads");
+    run<2, 3>(A, "two interleaved + one streamed, dwordx2");
+    run<2, 3, 1>(A, "two interleaved + one streamed, dwordx2");
     // the same with one, three and four wavefronts per SIMD
     run<1, 3, 1>(A, "two gathered + one streamed, dword loads");
     run<1, 3, 3>(A, "two gathered + one streamed, dword loads");

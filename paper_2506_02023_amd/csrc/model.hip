@@ -531,6 +531,18 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
         prof_end(g);
     }
 
+    // Kept filter values: only the upper edge of a pair keeps them, and the lower edge reads its reverse edge's row,
+    // in the modes whose forward launches are bound by the bytes they write (16-bit matrix products; measured on the
+    // 1M-atom benchmark in the split-fp16 mode: forward 3.23 -> 2.71 ms, reverse 4.02 -> 4.12 ms per launch).  With
+    // fp32 MFMA the forward launch does not get shorter and the reverse one pays for the gathered rows (4.67 -> 4.97 ms),
+    // so there every edge keeps its own.  Needs every partition of the launch to have its kept rows within the
+    // 31-bit range of one buffer descriptor; the same answer for the forward and the reverse launch of a layer.
+    auto w_pairs = [&](int p0, int n) {
+        if (prec == kPrecF32) return 0;
+        for (int q = 0; q < n; ++q)
+            if ((int64_t)views[p0 + q].n_edges_owned * F * 4 >= ((int64_t)1 << 31)) return 0;
+        return 1;
+    };
     auto gslice = [&](SlabView &v, int l) { return v.ws.g + (size_t)l * (size_t)v.n_local * F; };
     auto aslice = [&](SlabView &v, int l) { return v.ws.a + (size_t)l * (size_t)v.n_owned * F; };
     auto wslice = [&](SlabView &v, int l) {  // l >= 1
@@ -566,6 +578,7 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
             eb.c.A1s = base + pk.A1s;
             eb.c.A2t = base + pk.W2t;
             eb.c.bp = bp;
+            eb.c.w_pairs = w_pairs(p0, eb.n);
             for (int q = 0; q < eb.n; ++q) {
                 SlabView &v = views[p0 + q];
                 EdgeArgs &ea = eb.s[q];
@@ -577,6 +590,7 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
                 ea.senders = v.senders;
                 ea.recv = v.recv;
                 ea.d = v.d;
+                ea.mirror = v.mirror;
                 ea.g = gslice(v, l);
                 ea.out = aslice(v, l);
                 ea.wstore = (l >= 1) ? wslice(v, l) : nullptr;
@@ -665,6 +679,7 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
             eb.c.bp = bp;
             eb.c.need_gbar = need_gbar ? 1 : 0;
             eb.c.first = (l == L - 1) ? 1 : 0;
+            eb.c.w_pairs = w_pairs(p0, eb.n);
             for (int q = 0; q < eb.n; ++q) {
                 SlabView &v = views[p0 + q];
                 EdgeArgs &ea = eb.s[q];

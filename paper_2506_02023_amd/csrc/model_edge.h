@@ -28,6 +28,8 @@ struct EdgeCommon {
     const float *A1, *A1s, *A2t, *A2n;   // A1s = c W1, A2t = W2 / c (see kSiluScale), A1 and A2n unscaled
     BasisParams bp;
     int need_gbar, first;
+    int w_pairs;   // kept filter values: 1 = only the upper edge of a pair keeps them (both edges' values are the same
+                   // bits, since they are the same function of the same length); 0 = every edge keeps its own
 };
 
 // One launch covers up to kBatch partitions, taken in order: work item w belongs to partition p
@@ -184,6 +186,7 @@ __global__ void __launch_bounds__(256, 3) k_edge_fwd(EdgeBatch B)
     const int32_t e_hi = __builtin_amdgcn_readfirstlane((int32_t)A.row_ptr[r1]);
     const int32_t r_end = (int32_t)r1;
     const bool keep_w = A.wstore != nullptr;
+    const bool w_pairs = PREC != kPrecF32 && C.w_pairs != 0;   // (the host sets the flag in the 16-bit product modes only)
     if (e_lo >= e_hi) {   // only empty rows
         for (int32_t r = (int32_t)r0; r < r_end; ++r) store_row(r, 0.f);
         continue;
@@ -195,6 +198,7 @@ __global__ void __launch_bounds__(256, 3) k_edge_fwd(EdgeBatch B)
     float dv = A.d[en];
     int32_t rk = A.recv[en];
     int32_t sv = A.senders[en];
+    int32_t mv = (keep_w && w_pairs) ? A.mirror[en] : 0;
     {   // rows of the chunk before its first edge are empty
         const int32_t first = __builtin_amdgcn_readfirstlane(rk);
         for (int32_t r = (int32_t)r0; r < first; ++r) store_row(r, 0.f);
@@ -211,11 +215,14 @@ __global__ void __launch_bounds__(256, 3) k_edge_fwd(EdgeBatch B)
 #pragma unroll
         for (int k = 0; k < 32; ++k) gv[k] = buffer_load_f32(g_rsrc, f * 4, __builtin_amdgcn_readlane(so, k), 0);
         const int32_t rcur = valid ? rk : r_end;
+        // bit k: edge k keeps its filter values (with w_pairs only the upper edge of a pair does)
+        const uint32_t keeps = w_pairs ? (uint32_t)__ballot(valid && mv > tb + c32) : 0xffffffffu;
         // next tile's edge records
         en = min(tb + 32 + c32, e_hi - 1);
         dv = A.d[en];
         rk = A.recv[en];
         sv = A.senders[en];
+        if (keep_w && w_pairs) mv = A.mirror[en];
         __builtin_amdgcn_sched_barrier(0);
         f32x16 t[D::NB], w[D::NB];
         gemm_k8r<F>(W1, b, t, lane);
@@ -238,13 +245,14 @@ __global__ void __launch_bounds__(256, 3) k_edge_fwd(EdgeBatch B)
         float wv[32];
 #pragma unroll
         for (int k = 0; k < 32; ++k) wv[k] = tile[k * D::FS + f];
-        if (keep_w) {   // keep w_e for the reverse pass; rows past the end of the chunk fall outside the
-                        // descriptor's range and are dropped by the hardware bounds check
+        if (keep_w) {   // keep w_e for the reverse pass; rows past the end of the chunk, and those of edges that do not
+                        // keep theirs, fall outside the descriptor's range and are dropped by the hardware bounds check
             const __amdgpu_buffer_rsrc_t w_rsrc = __builtin_amdgcn_make_buffer_rsrc(
                 A.wstore + (int64_t)tb * F, 0, kmax * (F * 4), kBufferFlags);
 #pragma unroll
             for (int k = 0; k < 32; ++k)
-                if (F == 64 || lane < F) buffer_store_f32_stream(wv[k], w_rsrc, f * 4, k * (F * 4));
+                if (F == 64 || lane < F)
+                    buffer_store_f32_stream(wv[k], w_rsrc, f * 4, (keeps & (1u << k)) ? k * (F * 4) : 32 * (F * 4));
         }
 #pragma unroll
         for (int k = 0; k < 32; ++k) {
@@ -260,7 +268,7 @@ __global__ void __launch_bounds__(256, 3) k_edge_fwd(EdgeBatch B)
         wave_lds_fence();
         // retire the prefetched edge records here (they arrived long ago); a load left pending across
         // the loop edge would make the compiler wait for all loads, gathers included, at the top
-        asm volatile("" : "+v"(dv), "+v"(rk), "+v"(sv));
+        asm volatile("" : "+v"(dv), "+v"(rk), "+v"(sv), "+v"(mv));
     }
     }   // work items
     }   // partitions
@@ -402,6 +410,7 @@ __global__ void __launch_bounds__(kBwdWaves * 64, kBwdWaves == 4 ? 2 : 1) k_edge
         float ai0, gi0, ai1, gi1;       // abar / g rows of the first and of the last edge's receiver
         int kmax;                       // valid edges in the step
         int32_t tb;
+        uint32_t uppers;                // bit k: edge k is the upper edge of its pair
     };
     auto load_ids = [&](Ids &I, int32_t tb) {
         const int32_t e = min((int32_t)tb + l16, e_hi - 1);
@@ -417,21 +426,30 @@ __global__ void __launch_bounds__(kBwdWaves * 64, kBwdWaves == 4 ? 2 : 1) k_edge
         // every path through the pipeline then has the same number of loads in flight, which is what lets
         // the waits before the uses be partial ones.
         const int32_t sjo = I.sj * kRowBytes;
+        S.uppers = (uint32_t)__ballot(l16 < S.kmax && I.mk > tb + l16) & ((1u << kStep) - 1u);
         const int32_t row0 = __builtin_amdgcn_readfirstlane(I.rk);
         const int32_t rowl = __builtin_amdgcn_readlane(I.rk, max(S.kmax - 1, 0));
         S.ai0 = buffer_load_f32(a_rsrc, f * 4, row0 * kRowBytes, 0);
         S.gi0 = buffer_load_f32(g_rsrc, f * 4, row0 * kRowBytes, 0);
         S.ai1 = buffer_load_f32(a_rsrc, f * 4, rowl * kRowBytes, 0);
         S.gi1 = buffer_load_f32(g_rsrc, f * 4, rowl * kRowBytes, 0);
-        // w_e sits at the edge's own index (a range of zero bytes reads 0: without gbar no w is needed)
+        // w_e sits at the edge's own index or, with w_pairs, at the index of the pair's upper edge (a range of zero
+        // bytes reads 0: without gbar no w is needed).  With w_pairs the descriptor spans the partition's kept values
+        // (the host sets the flag only if they fit a 32-bit range) and a lower edge reads its reverse edge's row;
+        // an edge past the end then reads the row of the item's last edge, which goes into a sum nobody stores.
+        const bool w_pairs = PREC != kPrecF32 && C.w_pairs != 0;   // (the host sets the flag in the 16-bit product modes only)
+        const int32_t w_first = w_pairs ? 0 : tb;   // edge whose row the descriptor starts at
         const __amdgpu_buffer_rsrc_t w_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-            A.wstore + (need_gbar ? (int64_t)tb * F : 0), 0, need_gbar ? S.kmax * kRowBytes : 0, kBufferFlags);
+            A.wstore + (need_gbar ? (int64_t)w_first * F : 0), 0,
+            !need_gbar ? 0 : w_pairs ? (int)(uint32_t)(A.n_stored * kRowBytes) : S.kmax * kRowBytes, kBufferFlags);
+        const int32_t wro = (w_pairs ? min(I.mk, tb + l16) : l16) * kRowBytes;   // lane k: byte offset of edge k's row
 #pragma unroll
         for (int k = 0; k < kStep; ++k) {
             const int32_t so = __builtin_amdgcn_readlane(sjo, k);
             S.av[k] = buffer_load_f32(a_rsrc, f * 4, so, 0);
             S.gv[k] = buffer_load_f32(g_rsrc, f * 4, so, 0);
-            S.wv[k] = buffer_load_f32_stream(w_rsrc, f * 4, k * kRowBytes);   // 0 outside the descriptor's range
+            S.wv[k] = buffer_load_f32_stream(w_rsrc, f * 4,
+                                             PREC == kPrecF32 ? k * kRowBytes : __builtin_amdgcn_readlane(wro, k));   // 0 outside the range
         }
     };
     // rn_first: receiver of the first edge of the following step (r1 after the last step)
@@ -445,7 +463,7 @@ __global__ void __launch_bounds__(kBwdWaves * 64, kBwdWaves == 4 ? 2 : 1) k_edge
         const int32_t rnext = (l16 == kStep - 1) ? rn_first : up;
         const uint32_t ends = (uint32_t)__ballot(valid_l && rnext != rk) & ((1u << kStep) - 1u);
         const bool upper_l = valid_l && I.mk > e_l;
-        const uint32_t uppers = (uint32_t)__ballot(upper_l) & ((1u << kStep) - 1u);
+        const uint32_t uppers = S.uppers;
         {   // records of the pairs queued by this step, all at once: slots follow q_tail in edge order
             int slot = q_tail + (int)__builtin_amdgcn_mbcnt_lo(uppers, 0u);   // upper edges before this lane's (lanes < kStep)
             slot -= (slot >= kQueue) ? kQueue : 0;
@@ -843,6 +861,7 @@ __global__ void __launch_bounds__((kStreamWaves + kDenseWaves) * 64, 1) k_edge_b
         float ai0, gi0, ai1, gi1;       // abar / g rows of the first and of the last edge's receiver
         int kmax;                       // valid edges in the step
         int32_t tb;
+        uint32_t uppers;                // bit k: edge k is the upper edge of its pair
     };
     auto load_ids = [&](Ids &I, int32_t tb) {
         const int32_t e = min((int32_t)tb + l16, e_hi - 1);
@@ -858,21 +877,30 @@ __global__ void __launch_bounds__((kStreamWaves + kDenseWaves) * 64, 1) k_edge_b
         // every path through the pipeline then has the same number of loads in flight, which is what lets
         // the waits before the uses be partial ones.
         const int32_t sjo = I.sj * kRowBytes;
+        S.uppers = (uint32_t)__ballot(l16 < S.kmax && I.mk > tb + l16) & ((1u << kStep) - 1u);
         const int32_t row0 = __builtin_amdgcn_readfirstlane(I.rk);
         const int32_t rowl = __builtin_amdgcn_readlane(I.rk, max(S.kmax - 1, 0));
         S.ai0 = buffer_load_f32(a_rsrc, f * 4, row0 * kRowBytes, 0);
         S.gi0 = buffer_load_f32(g_rsrc, f * 4, row0 * kRowBytes, 0);
         S.ai1 = buffer_load_f32(a_rsrc, f * 4, rowl * kRowBytes, 0);
         S.gi1 = buffer_load_f32(g_rsrc, f * 4, rowl * kRowBytes, 0);
-        // w_e sits at the edge's own index (a range of zero bytes reads 0: without gbar no w is needed)
+        // w_e sits at the edge's own index or, with w_pairs, at the index of the pair's upper edge (a range of zero
+        // bytes reads 0: without gbar no w is needed).  With w_pairs the descriptor spans the partition's kept values
+        // (the host sets the flag only if they fit a 32-bit range) and a lower edge reads its reverse edge's row;
+        // an edge past the end then reads the row of the item's last edge, which goes into a sum nobody stores.
+        const bool w_pairs = PREC != kPrecF32 && C.w_pairs != 0;   // (the host sets the flag in the 16-bit product modes only)
+        const int32_t w_first = w_pairs ? 0 : tb;   // edge whose row the descriptor starts at
         const __amdgpu_buffer_rsrc_t w_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-            A.wstore + (need_gbar ? (int64_t)tb * F : 0), 0, need_gbar ? S.kmax * kRowBytes : 0, kBufferFlags);
+            A.wstore + (need_gbar ? (int64_t)w_first * F : 0), 0,
+            !need_gbar ? 0 : w_pairs ? (int)(uint32_t)(A.n_stored * kRowBytes) : S.kmax * kRowBytes, kBufferFlags);
+        const int32_t wro = (w_pairs ? min(I.mk, tb + l16) : l16) * kRowBytes;   // lane k: byte offset of edge k's row
 #pragma unroll
         for (int k = 0; k < kStep; ++k) {
             const int32_t so = __builtin_amdgcn_readlane(sjo, k);
             S.av[k] = buffer_load_f32(a_rsrc, f * 4, so, 0);
             S.gv[k] = buffer_load_f32(g_rsrc, f * 4, so, 0);
-            S.wv[k] = buffer_load_f32_stream(w_rsrc, f * 4, k * kRowBytes);   // 0 outside the descriptor's range
+            S.wv[k] = buffer_load_f32_stream(w_rsrc, f * 4,
+                                             PREC == kPrecF32 ? k * kRowBytes : __builtin_amdgcn_readlane(wro, k));   // 0 outside the range
         }
     };
     // rn_first: receiver of the first edge of the following step (r1 after the last step)
@@ -886,7 +914,7 @@ __global__ void __launch_bounds__((kStreamWaves + kDenseWaves) * 64, 1) k_edge_b
         const int32_t rnext = (l16 == kStep - 1) ? rn_first : up;
         const uint32_t ends = (uint32_t)__ballot(valid_l && rnext != rk) & ((1u << kStep) - 1u);
         const bool upper_l = valid_l && I.mk > e_l;
-        const uint32_t uppers = (uint32_t)__ballot(upper_l) & ((1u << kStep) - 1u);
+        const uint32_t uppers = S.uppers;
         {   // records of the pairs queued by this step, all at once: slots follow q_tail in edge order
             int slot = q_tail + (int)__builtin_amdgcn_mbcnt_lo(uppers, 0u);   // upper edges before this lane's (lanes < kStep)
             slot -= (slot >= kRoleQueue) ? kRoleQueue : 0;

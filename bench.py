@@ -41,8 +41,8 @@ def flops_bwd_edge(F, K=8):
 # WRITE_SIZE)
 TRAFFIC_SOURCE = ("profiled constant, not measured by this run: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this kernel on "
                   "this workload, profiles/edge_traffic_configs3_8slabs.md")
-TRAFFIC_BWD_LAUNCH_BYTES = (12184271 * 1.9975 + 998336) * 1024
-TRAFFIC_FWD_LAUNCH_BYTES = (3036729 * 1.9975 + 7879464) * 1024
+TRAFFIC_BWD_LAUNCH_BYTES = (12182160 * 1.9975 + 998299) * 1024
+TRAFFIC_FWD_LAUNCH_BYTES = (3045998 * 1.9975 + 7879464) * 1024
 
 
 # fp32 vector peak that applies to this build: 256 CUs x 4 SIMDs x 16 lanes x 2 flop per FMA x 2.4 GHz = 78.6 TFLOP/s.

@@ -21,10 +21,15 @@ PEAK_FP32_MFMA_TFLOPS = 157.3
 #   reverse: pre-activations t = b W1 (2 K F), sbar = wbar W2^T (2 F F), dt/dd contraction through W1 (2 K F);
 #            the filter value w_e itself is not recomputed, the forward pass keeps it in HBM (layers >= 1).
 # The reverse kernel runs this dense work once per edge / reverse-edge pair (both have the same length), so the
-# MFMA units execute half of the reverse figure per directed edge.  The roofline fraction of the reverse kernel is
-# taken on what is executed; the rate of the operation as defined is reported beside it ("as_defined_tflops").
+# MFMA units execute half of the reverse figure per directed edge; with fp32 MFMA the forward step does the same (the
+# first pass evaluates the filter MLP for the upper edge of every pair, a second, memory-bound pass adds the lower
+# edges' terms).  A kernel's roofline fraction is taken on what it executes; the rate of the operation as defined is
+# reported beside it ("as_defined_tflops").
 def flops_fwd_edge(F, K=8):
     return 2 * K * F + 2 * F * F
+
+
+PEAK_HBM_GBS = 8000.0
 
 
 def flops_bwd_edge_as_defined(F, K=8):
@@ -201,9 +206,25 @@ def main():
     F = c["F"]
     roof_bwd = edge_roofline("edge_bwd", f"k_edge_bwd<{F}> (reverse edge step)", flops_bwd_edge(F),
                              TRAFFIC_BWD_LAUNCH_BYTES, flops_bwd_edge_as_defined(F))
-    roof_fwd = edge_roofline("edge_fwd", f"k_edge_fwd<{F}> (forward edge step)", flops_fwd_edge(F),
-                             TRAFFIC_FWD_LAUNCH_BYTES)
+    two_pass = prof["edge_fwd_lower"][1] > 0   # the filter MLP once per edge pair, lower edges in a second pass
+    if two_pass:
+        roof_fwd = edge_roofline("edge_fwd", f"k_edge_fwd_pairs<{F}> (forward edge step, first pass: upper edges)",
+                                 flops_fwd_edge(F) // 2, TRAFFIC_FWD_LAUNCH_BYTES, flops_fwd_edge(F))
+    else:
+        roof_fwd = edge_roofline("edge_fwd", f"k_edge_fwd<{F}> (forward edge step)", flops_fwd_edge(F),
+                                 TRAFFIC_FWD_LAUNCH_BYTES)
     roof = roof_fwd if roof_fwd["ms_per_step"] >= roof_bwd["ms_per_step"] else roof_bwd   # the dominant kernel
+    roof_lower = None
+    if two_pass:   # bound by its row traffic; compulsory bytes: per lower edge the kept filter values (read once), per
+                   # atom the projected row that is gathered (once if the caches were perfect) and the sum (read, written)
+        ms, n = prof["edge_fwd_lower"]
+        per_launch = (E / 2 * F * 4 + N * 3 * F * 4) * L * args.steps / max(n, 1)
+        avg_ms = ms / max(n, 1)
+        ach = per_launch / (avg_ms * 1e-3) / 1e9 if avg_ms > 0 else 0.0
+        roof_lower = {"kernel": f"k_edge_fwd_lower<{F}> (forward edge step, second pass: lower edges)", "bound": "hbm",
+                      "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS, "traffic": None,
+                      "avg_launch_ms": avg_ms, "launches": int(n), "bytes_per_launch": per_launch,
+                      "ms_per_step": ms / args.steps}
     roof_trip = {}
     if three_body:
         _, bptr = g.bonds()
@@ -241,6 +262,8 @@ def main():
     }
     for k, v in roof_trip.items():
         res["roofline_" + k] = v
+    if roof_lower is not None:
+        res["roofline_edge_fwd_lower"] = roof_lower
     if split_ms is not None:
         res["split_fp16_products"] = {"ms_per_step": split_ms, "value": N / (split_ms * 1e-3), "unit": "atoms/s",
                                       "energy": energy_split,

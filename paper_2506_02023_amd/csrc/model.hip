@@ -179,12 +179,17 @@ template <int F, int PREC> struct BwdKernel {
 };
 #endif
 
-template <int F, int PREC> int launch_edge(mlip_graph *g, EdgeBatch &b, bool backward)
+enum { kEdgeFwd = 0, kEdgeFwdPairs = 1, kEdgeBwd = 2 };
+
+template <int F, int PREC> int launch_edge(mlip_graph *g, EdgeBatch &b, int kind)
 {
     using BK = BwdKernel<F, PREC>;
+    const bool backward = (kind == kEdgeBwd);
     const size_t lds = backward ? BK::lds : Lds<F>::edge_fwd;
     // resident blocks per compute unit, queried once per kernel and handle
-    const void *fn = backward ? BK::fn() : reinterpret_cast<const void *>(&k_edge_fwd<F, PREC>);
+    const void *fn = backward ? BK::fn()
+                     : kind == kEdgeFwdPairs ? reinterpret_cast<const void *>(&k_edge_fwd_pairs<F, PREC>)
+                                             : reinterpret_cast<const void *>(&k_edge_fwd<F, PREC>);
     int slot = 0;
     MLIP_TRY(configure_kernel(g, fn, lds, &slot));
     int occ = g->fn_occ[slot].second;
@@ -194,6 +199,8 @@ template <int F, int PREC> int launch_edge(mlip_graph *g, EdgeBatch &b, bool bac
         MLIP_HIP(hipDeviceGetAttribute(&g->n_cu, hipDeviceAttributeMultiprocessorCount, dev));
         if (backward)
             MLIP_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&o, fn, BK::threads, lds));
+        else if (kind == kEdgeFwdPairs)
+            MLIP_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&o, k_edge_fwd_pairs<F, PREC>, 256, lds));
         else
             MLIP_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&o, k_edge_fwd<F, PREC>, 256, lds));
         if (o < 1 || g->n_cu < 8) {
@@ -219,6 +226,8 @@ template <int F, int PREC> int launch_edge(mlip_graph *g, EdgeBatch &b, bool bac
     const unsigned blocks = (unsigned)(8 * std::max<int64_t>(1, std::min(resident, needed)));
     if (backward)
         BK::launch(blocks, g->stream, b);
+    else if (kind == kEdgeFwdPairs)
+        k_edge_fwd_pairs<F, PREC><<<blocks, 256, lds, g->stream>>>(b);
     else
         k_edge_fwd<F, PREC><<<blocks, 256, lds, g->stream>>>(b);
     MLIP_HIP(hipGetLastError());
@@ -270,8 +279,9 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
         MLIP_TRY(place(v.g, nl * rowb * (size_t)std::max(L, 1), v.ws.g));
         MLIP_TRY(place(v.a, no * rowb * (size_t)std::max(L, 1), v.ws.a));
         v.ws.wst = nullptr;
-        if (L > 1)  // filter values of layers 1..L-1, kept for the reverse pass instead of being recomputed
-            MLIP_TRY(place(v.wst, (size_t)std::max<int64_t>(v.n_edges_owned, 1) * rowb * (size_t)(L - 1), v.ws.wst));
+        if (L > 0)  // filter values of every layer: layers 1..L-1 are kept for the reverse pass instead of being recomputed,
+                    // and in the pair-wise forward step every layer's second pass reads what its first pass kept
+            MLIP_TRY(place(v.wst, (size_t)std::max<int64_t>(v.n_edges_owned, 1) * rowb * (size_t)L, v.ws.wst));
         n_parts += (v.n_owned + 1023) / 1024;
     }
     const Packs pk = pack_layout(F, L);
@@ -321,7 +331,8 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
             a.eps = v.ws.eps;
             a.dsum = v.ws.dsum;
             a.d = v.d;
-            a.wstore = (layer >= 1) ? v.ws.wst + (size_t)(layer - 1) * (size_t)v.n_edges_owned * F : nullptr;
+            a.wstore = (layer >= 0 && v.ws.wst) ? v.ws.wst + (size_t)layer * (size_t)v.n_edges_owned * F : nullptr;
+            a.a = (layer >= 0) ? v.ws.a + (size_t)layer * (size_t)v.n_owned * F : nullptr;
             a.bond_of_edge = (bw && v.bonds.n > 0) ? v.bonds.of_edge.as<int32_t>() : nullptr;
             a.wb_bf16 = (prec == kPrecBf16);
             a.wb = (bw && v.bonds.n > 0 && layer >= 0)
@@ -538,15 +549,14 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
     // so there every edge keeps its own.  Needs every partition of the launch to have its kept rows within the
     // 31-bit range of one buffer descriptor; the same answer for the forward and the reverse launch of a layer.
     auto w_pairs = [&](int p0, int n) {
-        if (prec == kPrecF32) return 0;
         for (int q = 0; q < n; ++q)
             if ((int64_t)views[p0 + q].n_edges_owned * F * 4 >= ((int64_t)1 << 31)) return 0;
         return 1;
     };
     auto gslice = [&](SlabView &v, int l) { return v.ws.g + (size_t)l * (size_t)v.n_local * F; };
     auto aslice = [&](SlabView &v, int l) { return v.ws.a + (size_t)l * (size_t)v.n_owned * F; };
-    auto wslice = [&](SlabView &v, int l) {  // l >= 1
-        return v.ws.wst + (size_t)(l - 1) * (size_t)v.n_edges_owned * F;
+    auto wslice = [&](SlabView &v, int l) {
+        return v.ws.wst + (size_t)l * (size_t)v.n_edges_owned * F;
     };
 
     // ---- forward layers
@@ -593,12 +603,25 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
                 ea.mirror = v.mirror;
                 ea.g = gslice(v, l);
                 ea.out = aslice(v, l);
-                ea.wstore = (l >= 1) ? wslice(v, l) : nullptr;
+                ea.wstore = (l >= 1 || (eb.c.w_pairs && prec == kPrecF32)) ? wslice(v, l) : nullptr;
             }
             prof_begin(g, MLIP_PROF_EDGE_FWD);
-            MLIP_TRY(prec == kPrecBf16 ? (launch_edge<F, kPrecBf16>(g, eb, false))
-                     : prec == kPrecF16x3 ? (launch_edge<F, kPrecF16x3>(g, eb, false)) : (launch_edge<F, kPrecF32>(g, eb, false)));
+            // With fp32 MFMA the filter MLP is evaluated once per edge pair (two passes); in the 16-bit product modes the
+            // one-pass kernel is faster (its matrix work is cheap, the second pass's row traffic is not), and there the
+            // pair flag only selects which edges keep their filter values.
+            const bool two_pass = eb.c.w_pairs && prec == kPrecF32;
+            const int kind = two_pass ? kEdgeFwdPairs : kEdgeFwd;
+            MLIP_TRY(prec == kPrecBf16 ? (launch_edge<F, kPrecBf16>(g, eb, kind))
+                     : prec == kPrecF16x3 ? (launch_edge<F, kPrecF16x3>(g, eb, kind)) : (launch_edge<F, kPrecF32>(g, eb, kind)));
             prof_end(g);
+            if (two_pass) {   // second pass: the lower edges' terms, with the filter values the first pass kept
+                prof_begin(g, MLIP_PROF_EDGE_FWD_LOWER);
+                const SmallBatch sb = small_batch(p0, U_OWNED, l);
+                if (sb.start[sb.n] > 0)
+                    k_edge_fwd_lower<F><<<blocks_for(sb.start[sb.n], 4), 256, 0, s>>>(sb);
+                MLIP_HIP(hipGetLastError());
+                prof_end(g);
+            }
         }
         if (any_bonds) {   // bond term of the filters: a_i += sum_b wb_b * g_send(b)
             prof_begin(g, MLIP_PROF_BOND);
@@ -700,8 +723,8 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
                 ea.n_stored = need_gbar ? v.n_edges_owned : 0;
             }
             prof_begin(g, MLIP_PROF_EDGE_BWD);
-            MLIP_TRY(prec == kPrecBf16 ? (launch_edge<F, kPrecBf16>(g, eb, true))
-                     : prec == kPrecF16x3 ? (launch_edge<F, kPrecF16x3>(g, eb, true)) : (launch_edge<F, kPrecF32>(g, eb, true)));
+            MLIP_TRY(prec == kPrecBf16 ? (launch_edge<F, kPrecBf16>(g, eb, kEdgeBwd))
+                     : prec == kPrecF16x3 ? (launch_edge<F, kPrecF16x3>(g, eb, kEdgeBwd)) : (launch_edge<F, kPrecF32>(g, eb, kEdgeBwd)));
             prof_end(g);
         }
         if (any_bonds) {   // bond term: its share of gbar; this layer's abar is kept for the bonds' own reverse step

@@ -199,6 +199,7 @@ struct SmallArgs {   // one partition
     const int32_t *senders, *mirror;
     const uint32_t *shiftp;
     float *h, *g, *gbar, *abar, *floc, *eps;
+    float *a;                      // the layer's receiver sums (second pass of the pair-wise forward step)
     const float *dsum, *wstore, *d;
     const int32_t *bond_of_edge;   // three-body variant (or nullptr)
     const void *wb;                // bond filter rows of the layer: fp32, or bf16 if wb_bf16
@@ -268,6 +269,47 @@ __global__ void k_zero_ghost_rows(SmallBatch B, int F)
 // gbar of the ghost rows: gbar_i = sum over the ghost's sub-row (its neighbours owned by this partition) of
 // w_e * abar_send(e).  w_e is the reverse edge's, which the forward pass kept (both edges of a pair have the
 // same length, hence the same filter value).  One wavefront per row, lane = feature, edges in row order.
+// Forward edge step over edge pairs, second pass: a_i += sum over the lower edges e = (i <- j) of row i of w * g_j, with w
+// read from the slot of the reverse edge, which the first pass has filled.  One wavefront per row, lane = feature; the
+// lower edges of 64 edges at a time are taken 16 at a time, all their rows in flight together.
+template <int F>
+__global__ void __launch_bounds__(256) k_edge_fwd_lower(SmallBatch B)
+{
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int64_t gk = (int64_t)blockIdx.x * 4 + wave;
+    if (gk >= B.start[B.n]) return;
+    const int part = batch_find(B.start, B.n, gk);
+    const SmallArgs &A = B.s[part];
+    const int64_t r = gk - B.start[part];
+    const unsigned f = lane & (F - 1);
+    const int64_t e0 = A.row_ptr[r], e1 = A.row_ptr[r + 1];
+    float acc = 0.f;
+    for (int64_t eb = e0; eb < e1; eb += 64) {
+        const int64_t el = min(eb + lane, e1 - 1);
+        const int32_t jl = A.senders[el], ml = A.mirror[el];
+        unsigned long long mask = __ballot(eb + lane < e1 && (int64_t)ml < el);   // the lower edges among these 64
+        while (mask != 0) {
+            float wv[16], gv[16];
+            int n = 0;
+#pragma unroll
+            for (int t = 0; t < 16; ++t) {
+                wv[t] = gv[t] = 0.f;
+                if (mask != 0) {   // wave-uniform: no load is issued for an edge that is not there
+                    const int idx = __builtin_ctzll(mask);
+                    mask &= mask - 1;
+                    ++n;
+                    const int64_t j = __builtin_amdgcn_readlane(jl, idx), m = __builtin_amdgcn_readlane(ml, idx);
+                    wv[t] = __builtin_nontemporal_load(A.wstore + m * F + f);
+                    gv[t] = A.g[j * F + f];
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < 16; ++t) acc = fmaf(wv[t], gv[t], acc);
+        }
+    }
+    if (F == 64 || lane < F) A.a[r * F + f] += acc;
+}
+
 template <int F>
 __global__ void __launch_bounds__(256) k_ghost_gbar(SmallBatch B)
 {

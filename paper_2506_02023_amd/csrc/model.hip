@@ -542,15 +542,16 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
         prof_end(g);
     }
 
-    // Kept filter values: only the upper edge of a pair keeps them, and the lower edge reads its reverse edge's row,
-    // in the modes whose forward launches are bound by the bytes they write (16-bit matrix products; measured on the
-    // 1M-atom benchmark in the split-fp16 mode: forward 3.23 -> 2.71 ms, reverse 4.02 -> 4.12 ms per launch).  With
-    // fp32 MFMA the forward launch does not get shorter and the reverse one pays for the gathered rows (4.67 -> 4.97 ms),
-    // so there every edge keeps its own.  Needs every partition of the launch to have its kept rows within the
-    // 31-bit range of one buffer descriptor; the same answer for the forward and the reverse launch of a layer.
+    // Kept filter values: both edges of a pair have the same ones bit for bit, so only the upper edge keeps them and
+    // the lower edge's reverse step reads its reverse edge's row.  In the 16-bit product modes that halves what the
+    // forward launches write, which is what bounds them there (1M-atom benchmark, split-fp16: forward 3.23 -> 2.71 ms,
+    // reverse 4.02 -> 4.12 ms per launch).  With fp32 MFMA the forward step goes further and evaluates the filter MLP
+    // once per pair in two passes (k_edge_fwd_pairs, k_edge_fwd_lower: 4.6 -> 2.9 + 1.25 ms per layer, reverse 4.7 -> 4.9 ms).
+    // Needs every partition of the launch to have its kept rows within the 32-bit range of one buffer descriptor
+    // (otherwise every edge keeps its own, in one pass); the same answer for the forward and the reverse launch of a layer.
     auto w_pairs = [&](int p0, int n) {
         for (int q = 0; q < n; ++q)
-            if ((int64_t)views[p0 + q].n_edges_owned * F * 4 >= ((int64_t)1 << 31)) return 0;
+            if ((int64_t)views[p0 + q].n_edges_owned * F * 4 >= ((int64_t)1 << 32) - (1 << 20)) return 0;
         return 1;
     };
     auto gslice = [&](SlabView &v, int l) { return v.ws.g + (size_t)l * (size_t)v.n_local * F; };

@@ -442,9 +442,21 @@ __global__ void __launch_bounds__(256, 3) k_edge_fwd_pairs(EdgeBatch B)
 #pragma unroll
         for (int k = 0; k < 32; ++k) wv[k] = tile[k * D::FS + f];
 #ifndef MLIP_TIMING_NO_W_STORE
+        if (F == 64) {   // four rows per instruction: lane (q, c) stores features 4 c .. 4 c + 3 of edge 4 i + q
+            const int q = lane >> 4, c4 = (lane & 15) * 4;
 #pragma unroll
-        for (int k = 0; k < 32; ++k)
-            if (F == 64 || lane < F) buffer_store_f32_stream(wv[k], w_rsrc, f * 4, __builtin_amdgcn_readlane(wo, k));
+            for (int i = 0; i < 8; ++i) {
+                const int k = 4 * i + q;
+                const f32x4 v = *reinterpret_cast<const f32x4 *>(tile + k * D::FS + c4);
+                const int32_t off = __shfl(wo, k, 64) + c4 * 4;
+                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(__attribute__((ext_vector_type(4))) unsigned, v), w_rsrc,
+                                                       off, 0, 2);
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < 32; ++k)
+                if (lane < F) buffer_store_f32_stream(wv[k], w_rsrc, f * 4, __builtin_amdgcn_readlane(wo, k));
+        }
 #endif
 #pragma unroll
         for (int k = 0; k < 32; ++k) {

@@ -271,7 +271,9 @@ __global__ void k_zero_ghost_rows(SmallBatch B, int F)
 // same length, hence the same filter value).  One wavefront per row, lane = feature, edges in row order.
 // Forward edge step over edge pairs, second pass: a_i += sum over the lower edges e = (i <- j) of row i of w * g_j, with w
 // read from the slot of the reverse edge, which the first pass has filled.  One wavefront per row, lane = feature; the
-// lower edges of 64 edges at a time are taken 16 at a time, all their rows in flight together.
+// lower edges of 64 edges at a time are taken kLowerChunk at a time, all their rows in flight together.
+constexpr int kLowerChunk = 16;   // lower edges whose rows are in flight together (32 measured no faster)
+
 template <int F>
 __global__ void __launch_bounds__(256) k_edge_fwd_lower(SmallBatch B)
 {
@@ -289,10 +291,10 @@ __global__ void __launch_bounds__(256) k_edge_fwd_lower(SmallBatch B)
         const int32_t jl = A.senders[el], ml = A.mirror[el];
         unsigned long long mask = __ballot(eb + lane < e1 && (int64_t)ml < el);   // the lower edges among these 64
         while (mask != 0) {
-            float wv[16], gv[16];
+            float wv[kLowerChunk], gv[kLowerChunk];
             int n = 0;
 #pragma unroll
-            for (int t = 0; t < 16; ++t) {
+            for (int t = 0; t < kLowerChunk; ++t) {
                 wv[t] = gv[t] = 0.f;
                 if (mask != 0) {   // wave-uniform: no load is issued for an edge that is not there
                     const int idx = __builtin_ctzll(mask);
@@ -304,7 +306,7 @@ __global__ void __launch_bounds__(256) k_edge_fwd_lower(SmallBatch B)
                 }
             }
 #pragma unroll
-            for (int t = 0; t < 16; ++t) acc = fmaf(wv[t], gv[t], acc);
+            for (int t = 0; t < kLowerChunk; ++t) acc = fmaf(wv[t], gv[t], acc);
         }
     }
     if (F == 64 || lane < F) A.a[r * F + f] += acc;

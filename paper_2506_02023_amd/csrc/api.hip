@@ -355,6 +355,10 @@ void mlip_graph_destroy(mlip_graph_t *g)
                         &B.P, &B.Q, &B.S, &B.m, &B.wb, &B.abar_keep, &B.e1bar, &B.Sbar, &B.Pbar, &B.Qbar,
                         &B.ubar, &B.dbond, &B.rbar};
         for (DevBuf *b : vb) b->release();
+        PairGraph &Q = v.pairs;
+        DevBuf *pb[] = {&Q.b_rowcnt, &Q.b_u_row_ptr, &Q.b_l_row_ptr, &Q.b_cidx, &Q.b_wslot, &Q.b_u_senders, &Q.b_u_recv,
+                        &Q.b_u_eid, &Q.b_u_mirror, &Q.b_u_qslot, &Q.b_u_d, &Q.b_u_chunk_row};
+        for (DevBuf *b : pb) b->release();
     };
     drop_view(g->whole);
     for (auto &v : g->slabs) drop_view(v);

@@ -1239,6 +1239,158 @@ int build_bonds_impl(mlip_graph *g, SlabView &v, double r_bond, int p_envelope)
 
 namespace {
 
+// ---- upper / lower split of the owned rows' edges (PairGraph)
+
+// per row: how many of its edges are upper ones (reverse edge at a larger index), how many lower ones
+__global__ void __launch_bounds__(256) k_pair_rowcnt(int64_t n_rows, const int64_t *__restrict__ row_ptr,
+                                                    const int32_t *__restrict__ mirror, int32_t *__restrict__ ucnt,
+                                                    int32_t *__restrict__ lcnt)
+{
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int64_t r = (int64_t)blockIdx.x * 4 + wave;
+    if (r >= n_rows) return;
+    const int64_t e0 = row_ptr[r], e1 = row_ptr[r + 1];
+    int nu = 0;
+    for (int64_t eb = e0; eb < e1; eb += 64) {
+        const int64_t e = eb + lane;
+        nu += __builtin_popcountll(__ballot(e < e1 && (int64_t)mirror[min(e, e1 - 1)] > e));
+    }
+    if (lane == 0) {
+        ucnt[r] = nu;
+        lcnt[r] = (int)(e1 - e0) - nu;
+    }
+}
+
+// the compacted upper edges and every edge's index within its class
+__global__ void __launch_bounds__(256)
+k_pair_fill(int64_t n_rows, const int64_t *__restrict__ row_ptr, const int32_t *__restrict__ senders,
+            const int32_t *__restrict__ mirror, const float *__restrict__ d, const int64_t *__restrict__ u_row_ptr,
+            const int64_t *__restrict__ l_row_ptr, int32_t *__restrict__ cidx, int32_t *__restrict__ u_senders,
+            int32_t *__restrict__ u_recv, int32_t *__restrict__ u_eid, int32_t *__restrict__ u_mirror, float *__restrict__ u_d)
+{
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int64_t r = (int64_t)blockIdx.x * 4 + wave;
+    if (r >= n_rows) return;
+    const int64_t e0 = row_ptr[r], e1 = row_ptr[r + 1];
+    int64_t ku = u_row_ptr[r], kl = l_row_ptr[r];
+    for (int64_t eb = e0; eb < e1; eb += 64) {
+        const int64_t e = eb + lane;
+        const bool in = e < e1;
+        const int32_t m = in ? mirror[e] : 0;
+        const bool upper = in && (int64_t)m > e;
+        const unsigned long long um = __ballot(upper), lm = __ballot(in && !upper);
+        const unsigned long long below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+        if (upper) {
+            const int64_t k = ku + __builtin_popcountll(um & below);
+            cidx[e] = (int32_t)k;
+            u_senders[k] = senders[e];
+            u_recv[k] = (int32_t)r;
+            u_eid[k] = (int32_t)e;
+            u_mirror[k] = m;
+            u_d[k] = d[e];
+        } else if (in) {
+            cidx[e] = (int32_t)(kl + __builtin_popcountll(lm & below));
+        }
+        ku += __builtin_popcountll(um);
+        kl += __builtin_popcountll(lm);
+    }
+}
+
+// wslot[e]: upper index of the pair of edge e; u_qslot[k]: lower index of the reverse edge of upper edge k
+__global__ void k_pair_slots(int64_t E_owned, const int32_t *__restrict__ mirror, const int32_t *__restrict__ cidx,
+                             int32_t *__restrict__ wslot, int32_t *__restrict__ u_qslot)
+{
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= E_owned) return;
+    const int64_t m = mirror[e];
+    if (m > e) {
+        const int32_t k = cidx[e];
+        wslot[e] = k;
+        u_qslot[k] = (m < E_owned) ? cidx[m] : -1;
+    } else {
+        wslot[e] = cidx[m];
+    }
+}
+
+// chunk_row[c] = first row whose first edge lies at or after c * kChunkEdges; chunk_row[n_chunks] = n_rows.
+__global__ void k_chunk_rows_of(int64_t n_rows, int64_t n_chunks, const int64_t *__restrict__ row_ptr,
+                                int32_t *__restrict__ chunk_row)
+{
+    const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (c > n_chunks) return;
+    int64_t lo = 0, hi = n_rows;
+    if (c == n_chunks) lo = n_rows;
+    const int64_t v = c * kChunkEdges;
+    while (lo < hi) {
+        const int64_t mid = (lo + hi) >> 1;
+        if (row_ptr[mid] < v) lo = mid + 1; else hi = mid;
+    }
+    chunk_row[c] = (int32_t)lo;
+}
+
+}  // namespace
+
+int build_pairs_impl(mlip_graph *g, SlabView &v, Carver *scratch)
+{
+    PairGraph &Q = v.pairs;
+    if (Q.valid) return MLIP_OK;
+    hipStream_t s = g->stream;
+    const int64_t E = v.n_edges_owned, N = v.n_owned;
+    // every pair of two owned-row edges has one upper edge; an owned-row edge from a ghost sender is an upper edge, and
+    // the ghost rows hold exactly the reverse edges of those
+    const int64_t n_ghost_edges = v.n_edges - v.n_edges_owned;
+    Q.n_upper = (E - n_ghost_edges) / 2 + n_ghost_edges;
+    Q.n_lower = E - Q.n_upper;
+    const size_t Ncap = (size_t)std::max<int64_t>(N, 1), Ecap = (size_t)std::max<int64_t>(E, 1);
+    const size_t Ucap = (size_t)std::max<int64_t>(Q.n_upper, 1);
+    const int64_t n_chunks = chunks_of(Q.n_upper);
+    auto place = [&](DevBuf &buf, size_t bytes, auto *&ptr) -> int {
+        using T = std::remove_reference_t<decltype(*ptr)>;
+        if (scratch) {
+            ptr = static_cast<T *>(scratch->take(bytes));
+            return MLIP_OK;   // a failed carve is reported by the caller
+        }
+        MLIP_TRY(buf.ensure(bytes));
+        ptr = buf.as<T>();
+        return MLIP_OK;
+    };
+    MLIP_TRY(place(Q.b_rowcnt, 2 * Ncap * 4, Q.rowcnt));
+    MLIP_TRY(place(Q.b_u_row_ptr, (Ncap + 1) * 8, Q.u_row_ptr));
+    MLIP_TRY(place(Q.b_l_row_ptr, (Ncap + 1) * 8, Q.l_row_ptr));
+    MLIP_TRY(place(Q.b_cidx, Ecap * 4, Q.cidx));
+    MLIP_TRY(place(Q.b_wslot, Ecap * 4, Q.wslot));
+    MLIP_TRY(place(Q.b_u_senders, Ucap * 4, Q.u_senders));
+    MLIP_TRY(place(Q.b_u_recv, Ucap * 4, Q.u_recv));
+    MLIP_TRY(place(Q.b_u_eid, Ucap * 4, Q.u_eid));
+    MLIP_TRY(place(Q.b_u_mirror, Ucap * 4, Q.u_mirror));
+    MLIP_TRY(place(Q.b_u_qslot, Ucap * 4, Q.u_qslot));
+    MLIP_TRY(place(Q.b_u_d, Ucap * 4, Q.u_d));
+    MLIP_TRY(place(Q.b_u_chunk_row, (size_t)(n_chunks + 1) * 4, Q.u_chunk_row));
+    if (scratch && scratch->failed()) return MLIP_OK;   // nothing may be launched on a failed carve; the caller reports it
+    int32_t *ucnt = Q.rowcnt, *lcnt = ucnt + Ncap;
+    if (N > 0) {
+        k_pair_rowcnt<<<blocks_for(N, 4), 256, 0, s>>>(N, v.row_ptr, v.mirror, ucnt, lcnt);
+        MLIP_HIP(hipGetLastError());
+    }
+    MLIP_TRY(scan_i32_to_i64(ucnt, Q.u_row_ptr, N, g->scan_tmp, s));
+    MLIP_TRY(scan_i32_to_i64(lcnt, Q.l_row_ptr, N, g->scan_tmp, s));
+    if (N > 0) {
+        k_pair_fill<<<blocks_for(N, 4), 256, 0, s>>>(N, v.row_ptr, v.senders, v.mirror, v.d, Q.u_row_ptr, Q.l_row_ptr, Q.cidx,
+                                                     Q.u_senders, Q.u_recv, Q.u_eid, Q.u_mirror, Q.u_d);
+        MLIP_HIP(hipGetLastError());
+    }
+    if (E > 0) {
+        k_pair_slots<<<blocks_for(E, 256), 256, 0, s>>>(E, v.mirror, Q.cidx, Q.wslot, Q.u_qslot);
+        MLIP_HIP(hipGetLastError());
+    }
+    k_chunk_rows_of<<<blocks_for(n_chunks + 1, 256), 256, 0, s>>>(N, n_chunks, Q.u_row_ptr, Q.u_chunk_row);
+    MLIP_HIP(hipGetLastError());
+    Q.valid = (scratch == nullptr);   // arrays in a borrowed block do not outlive the call
+    return MLIP_OK;
+}
+
+namespace {
+
 struct CsrOut {   // where a neighbour search puts its receiver-sorted CSR (mirror: the reverse-edge index, or nullptr)
     DevBuf *row_ptr, *senders, *recv, *shiftp, *d, *mirror;
 };
@@ -1442,7 +1594,11 @@ int build_graph_impl(mlip_graph *g, const double *positions, const double *cell,
     g->cell = cp;
     g->N = 0;  // the handle is invalid until the build completes
     g->whole.bonds.r_bond = -1.0;
-    for (SlabView &sv : g->slabs) sv.bonds.r_bond = -1.0;
+    g->whole.pairs.valid = false;
+    for (SlabView &sv : g->slabs) {
+        sv.bonds.r_bond = -1.0;
+        sv.pairs.valid = false;
+    }
     g->E = 0;
     if (!g->pinned) MLIP_HIP(hipHostMalloc(&g->pinned, 65536, hipHostMallocDefault));
     int64_t *hp = static_cast<int64_t *>(g->pinned);

@@ -121,6 +121,26 @@ struct BondGraph {
     DevBuf rbar;            // f32 [n][3]
 };
 
+// The edges of a partition's owned rows split into the upper and the lower edge of every edge / reverse-edge pair
+// (upper: the one with the smaller index; an edge whose reverse edge lies in a ghost row is an upper edge).  The
+// upper edges are compacted into a graph of their own (same rows, half the edges) on which the edge kernels run;
+// the lower edges' terms are added by row-wise kernels.  Built on first use after a graph build.
+struct PairGraph {
+    bool valid = false;
+    int64_t n_upper = 0, n_lower = 0;
+    // grow-only buffers behind the pointers below (unused when the arrays are carved from a caller-independent block)
+    DevBuf b_rowcnt, b_u_row_ptr, b_l_row_ptr, b_cidx, b_wslot, b_u_senders, b_u_recv, b_u_eid, b_u_mirror, b_u_qslot, b_u_d,
+        b_u_chunk_row;
+    int32_t *rowcnt = nullptr;                        // [2][n_owned] upper / lower edges per row (scratch)
+    int64_t *u_row_ptr = nullptr, *l_row_ptr = nullptr;   // [n_owned + 1]
+    int32_t *cidx = nullptr;                          // [E_owned] index of an edge within its class (upper or lower)
+    int32_t *wslot = nullptr;                         // [E_owned] upper index of the edge's pair
+    // [n_upper]: sender row, receiver row, edge, reverse edge, lower index of the reverse edge (-1: it lies in a ghost row)
+    int32_t *u_senders = nullptr, *u_recv = nullptr, *u_eid = nullptr, *u_mirror = nullptr, *u_qslot = nullptr;
+    float *u_d = nullptr;                             // [n_upper]
+    int32_t *u_chunk_row = nullptr;                   // [chunks_of(n_upper) + 1]
+};
+
 // One partition as the model kernels see it.  The whole graph is the special
 // case nodes == nullptr (identity), n_owned == n_local == N.
 struct SlabView {
@@ -139,9 +159,10 @@ struct SlabView {
     const int32_t *owned_sorted = nullptr; // [n_owned] owned atoms, ascending global id
     std::vector<int64_t> markers;          // host, P + 3
     // model workspace (sized in mlip_forward)
-    DevBuf h, hbar, abar, gbar, eps, dsum, floc, g, a, wst;  // g and a hold L slices each, wst L - 1
+    DevBuf h, hbar, abar, gbar, eps, dsum, floc, g, a, wst;  // g, a and wst hold L slices each
     ViewWs ws;                             // the pointers the kernels of the current call use
     BondGraph bonds;
+    PairGraph pairs;
 };
 
 // Device arrays of all partitions, each array holding the partitions' pieces one after another (one allocation and
@@ -231,6 +252,9 @@ int forward_impl(mlip_graph *g, const mlip_weights_t *w, int32_t mode, double *e
 int unpack_shifts(const mlip_graph *g, int32_t *out);
 // bond list of one partition for cutoff r_bond (kept until the graph is rebuilt or r_bond changes); synchronises
 int build_bonds_impl(mlip_graph *g, SlabView &v, double r_bond, int p_envelope);
+// Upper / lower split of a view's owned-row edges (PairGraph); does nothing if it is valid.  With a block to carve from,
+// the arrays are taken from it (and the caller invalidates the structure when the block is given up).
+int build_pairs_impl(mlip_graph *g, SlabView &v, Carver *scratch);
 int forward_bonds_impl(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t *bw, int32_t mode,
                        double *energy, float *forces, float *atom_energy);
 

@@ -162,34 +162,38 @@ constexpr int kWorkLaunches = 2 * 8 * (64 / kBatch);
 
 // The reverse edge kernel the library runs is the one whose wavefronts alternate between the two phases.  Building
 // with -DMLIP_BWD_ROLES selects the variant with specialised wavefronts instead (same results; measured slower, kept
-// for that experiment).
+// for that experiment; it has no form for the upper-edge graphs, so such a build runs every mode on the full edge lists).
 #ifdef MLIP_BWD_ROLES
-template <int F, int PREC> struct BwdKernel {
+constexpr bool kUpperGraphs = false;
+template <int F, int PREC, bool COMPACT> struct BwdKernel {
     static constexpr int threads = (kStreamWaves + kDenseWaves) * 64, item_waves = kStreamWaves;
     static constexpr size_t lds = BwdRolesLds<F>::bytes;
     static const void *fn() { return reinterpret_cast<const void *>(&k_edge_bwd_roles<F, PREC>); }
     static void launch(unsigned blocks, hipStream_t s, const EdgeBatch &b) { k_edge_bwd_roles<F, PREC><<<blocks, threads, lds, s>>>(b); }
 };
 #else
-template <int F, int PREC> struct BwdKernel {
+constexpr bool kUpperGraphs = true;
+template <int F, int PREC, bool COMPACT> struct BwdKernel {
     static constexpr int threads = kBwdWaves * 64, item_waves = kBwdWaves;
     static constexpr size_t lds = Lds<F>::edge_bwd;
-    static const void *fn() { return reinterpret_cast<const void *>(&k_edge_bwd<F, PREC>); }
-    static void launch(unsigned blocks, hipStream_t s, const EdgeBatch &b) { k_edge_bwd<F, PREC><<<blocks, threads, lds, s>>>(b); }
+    static const void *fn() { return reinterpret_cast<const void *>(&k_edge_bwd<F, PREC, COMPACT>); }
+    static void launch(unsigned blocks, hipStream_t s, const EdgeBatch &b)
+    {
+        k_edge_bwd<F, PREC, COMPACT><<<blocks, threads, lds, s>>>(b);
+    }
 };
 #endif
 
-enum { kEdgeFwd = 0, kEdgeFwdPairs = 1, kEdgeBwd = 2 };
+enum { kEdgeFwd = 0, kEdgeBwd = 1, kEdgeBwdUpper = 2 };   // kEdgeBwdUpper: the launch runs on upper-edge graphs
 
-template <int F, int PREC> int launch_edge(mlip_graph *g, EdgeBatch &b, int kind)
+template <int F, int PREC, bool COMPACT = false> int launch_edge(mlip_graph *g, EdgeBatch &b, int kind)
 {
-    using BK = BwdKernel<F, PREC>;
-    const bool backward = (kind == kEdgeBwd);
+    if (kind == kEdgeBwdUpper && !COMPACT) return launch_edge<F, PREC, true>(g, b, kind);
+    using BK = BwdKernel<F, PREC, COMPACT>;
+    const bool backward = (kind != kEdgeFwd);
     const size_t lds = backward ? BK::lds : Lds<F>::edge_fwd;
     // resident blocks per compute unit, queried once per kernel and handle
-    const void *fn = backward ? BK::fn()
-                     : kind == kEdgeFwdPairs ? reinterpret_cast<const void *>(&k_edge_fwd_pairs<F, PREC>)
-                                             : reinterpret_cast<const void *>(&k_edge_fwd<F, PREC>);
+    const void *fn = backward ? BK::fn() : reinterpret_cast<const void *>(&k_edge_fwd<F, PREC>);
     int slot = 0;
     MLIP_TRY(configure_kernel(g, fn, lds, &slot));
     int occ = g->fn_occ[slot].second;
@@ -199,8 +203,6 @@ template <int F, int PREC> int launch_edge(mlip_graph *g, EdgeBatch &b, int kind
         MLIP_HIP(hipDeviceGetAttribute(&g->n_cu, hipDeviceAttributeMultiprocessorCount, dev));
         if (backward)
             MLIP_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&o, fn, BK::threads, lds));
-        else if (kind == kEdgeFwdPairs)
-            MLIP_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&o, k_edge_fwd_pairs<F, PREC>, 256, lds));
         else
             MLIP_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&o, k_edge_fwd<F, PREC>, 256, lds));
         if (o < 1 || g->n_cu < 8) {
@@ -226,8 +228,6 @@ template <int F, int PREC> int launch_edge(mlip_graph *g, EdgeBatch &b, int kind
     const unsigned blocks = (unsigned)(8 * std::max<int64_t>(1, std::min(resident, needed)));
     if (backward)
         BK::launch(blocks, g->stream, b);
-    else if (kind == kEdgeFwdPairs)
-        k_edge_fwd_pairs<F, PREC><<<blocks, 256, lds, g->stream>>>(b);
     else
         k_edge_fwd<F, PREC><<<blocks, 256, lds, g->stream>>>(b);
     MLIP_HIP(hipGetLastError());
@@ -265,6 +265,15 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
         ptr = buf.as<float>();
         return MLIP_OK;
     };
+    // With fp32 MFMA the edge kernels run on the partitions' upper-edge graphs (one edge per edge / reverse-edge pair:
+    // both edges have the same length, hence bit for bit the same filter values), and row-wise kernels add the lower
+    // edges' terms.  In the 16-bit product modes the matrix work is cheap and the full edge lists are faster.
+    const bool upper = kUpperGraphs && prec == kPrecF32;
+    if (upper) {
+        prof_begin(g, MLIP_PROF_GRAPH);
+        for (int p = 0; p < P; ++p) MLIP_TRY(build_pairs_impl(g, views[p], scratch));
+        prof_end(g);
+    }
     int64_t n_parts = 0;
     for (int p = 0; p < P; ++p) {
         SlabView &v = views[p];
@@ -280,8 +289,9 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
         MLIP_TRY(place(v.a, no * rowb * (size_t)std::max(L, 1), v.ws.a));
         v.ws.wst = nullptr;
         if (L > 0)  // filter values of every layer: layers 1..L-1 are kept for the reverse pass instead of being recomputed,
-                    // and in the pair-wise forward step every layer's second pass reads what its first pass kept
-            MLIP_TRY(place(v.wst, (size_t)std::max<int64_t>(v.n_edges_owned, 1) * rowb * (size_t)L, v.ws.wst));
+                    // and on the upper-edge graphs every layer's second pass reads what its first pass kept
+            MLIP_TRY(place(v.wst, (size_t)std::max<int64_t>(upper ? v.pairs.n_upper : v.n_edges_owned, 1) * rowb * (size_t)L,
+                           v.ws.wst));
         n_parts += (v.n_owned + 1023) / 1024;
     }
     const Packs pk = pack_layout(F, L);
@@ -300,6 +310,9 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
     g->work_next = 0;
     MLIP_TRY(fill_zero(work_f, (int64_t)work_n, s));
 
+
+    // rows of one layer's kept filter values
+    auto wrows = [&](SlabView &v) { return (size_t)(upper ? v.pairs.n_upper : v.n_edges_owned); };
 
     // ---- batches for the small kernels (embedding, ghost transfers, forces, energy): up to kBatch partitions per launch
     enum { U_OWNED, U_GHOST, U_BORDER, U_LOCAL, U_KBLOCKS };
@@ -331,7 +344,8 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
             a.eps = v.ws.eps;
             a.dsum = v.ws.dsum;
             a.d = v.d;
-            a.wstore = (layer >= 0 && v.ws.wst) ? v.ws.wst + (size_t)layer * (size_t)v.n_edges_owned * F : nullptr;
+            a.wstore = (layer >= 0 && v.ws.wst) ? v.ws.wst + (size_t)layer * wrows(v) * F : nullptr;
+            a.wslot = upper ? v.pairs.wslot : nullptr;
             a.a = (layer >= 0) ? v.ws.a + (size_t)layer * (size_t)v.n_owned * F : nullptr;
             a.bond_of_edge = (bw && v.bonds.n > 0) ? v.bonds.of_edge.as<int32_t>() : nullptr;
             a.wb_bf16 = (prec == kPrecBf16);
@@ -542,14 +556,14 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
         prof_end(g);
     }
 
-    // Kept filter values: both edges of a pair have the same ones bit for bit, so only the upper edge keeps them and
-    // the lower edge's reverse step reads its reverse edge's row.  In the 16-bit product modes that halves what the
-    // forward launches write, which is what bounds them there (1M-atom benchmark, split-fp16: forward 3.23 -> 2.71 ms,
-    // reverse 4.02 -> 4.12 ms per launch).  With fp32 MFMA the forward step goes further and evaluates the filter MLP
-    // once per pair in two passes (k_edge_fwd_pairs, k_edge_fwd_lower: 4.6 -> 2.9 + 1.25 ms per layer, reverse 4.7 -> 4.9 ms).
-    // Needs every partition of the launch to have its kept rows within the 32-bit range of one buffer descriptor
-    // (otherwise every edge keeps its own, in one pass); the same answer for the forward and the reverse launch of a layer.
+    // Kept filter values on the full edge lists (16-bit product modes): both edges of a pair have the same ones bit for
+    // bit, so only the upper edge keeps them and the lower edge's reverse step reads its reverse edge's row.  That halves
+    // what the forward launches write, which is what bounds them there (1M-atom benchmark, split-fp16: forward
+    // 3.23 -> 2.71 ms, reverse 4.02 -> 4.12 ms per launch).  Needs every partition of the launch to have its kept rows
+    // within the 32-bit range of one buffer descriptor (otherwise every edge keeps its own); the same answer for the
+    // forward and the reverse launch of a layer.
     auto w_pairs = [&](int p0, int n) {
+        if (upper || prec == kPrecF32) return 0;   // upper-edge graphs keep one row per pair by construction
         for (int q = 0; q < n; ++q)
             if ((int64_t)views[p0 + q].n_edges_owned * F * 4 >= ((int64_t)1 << 32) - (1 << 20)) return 0;
         return 1;
@@ -557,7 +571,7 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
     auto gslice = [&](SlabView &v, int l) { return v.ws.g + (size_t)l * (size_t)v.n_local * F; };
     auto aslice = [&](SlabView &v, int l) { return v.ws.a + (size_t)l * (size_t)v.n_owned * F; };
     auto wslice = [&](SlabView &v, int l) {
-        return v.ws.wst + (size_t)l * (size_t)v.n_edges_owned * F;
+        return v.ws.wst + (size_t)l * wrows(v) * F;
     };
 
     // ---- forward layers
@@ -604,22 +618,28 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
                 ea.mirror = v.mirror;
                 ea.g = gslice(v, l);
                 ea.out = aslice(v, l);
-                ea.wstore = (l >= 1 || (eb.c.w_pairs && prec == kPrecF32)) ? wslice(v, l) : nullptr;
+                ea.wstore = (l >= 1 || upper) ? wslice(v, l) : nullptr;
+                if (upper) {   // the same kernel on the partition's upper-edge graph: row sums of the upper edges, every
+                               // edge's filter values kept one after another
+                    const PairGraph &Q = v.pairs;
+                    ea.n_chunks = chunks_of(Q.n_upper);
+                    ea.chunk_row = Q.u_chunk_row;
+                    ea.row_ptr = Q.u_row_ptr;
+                    ea.senders = Q.u_senders;
+                    ea.recv = Q.u_recv;
+                    ea.d = Q.u_d;
+                    ea.mirror = nullptr;
+                }
             }
             prof_begin(g, MLIP_PROF_EDGE_FWD);
-            // With fp32 MFMA the filter MLP is evaluated once per edge pair (two passes); in the 16-bit product modes the
-            // one-pass kernel is faster (its matrix work is cheap, the second pass's row traffic is not), and there the
-            // pair flag only selects which edges keep their filter values.
-            const bool two_pass = eb.c.w_pairs && prec == kPrecF32;
-            const int kind = two_pass ? kEdgeFwdPairs : kEdgeFwd;
-            MLIP_TRY(prec == kPrecBf16 ? (launch_edge<F, kPrecBf16>(g, eb, kind))
-                     : prec == kPrecF16x3 ? (launch_edge<F, kPrecF16x3>(g, eb, kind)) : (launch_edge<F, kPrecF32>(g, eb, kind)));
+            MLIP_TRY(prec == kPrecBf16 ? (launch_edge<F, kPrecBf16>(g, eb, kEdgeFwd))
+                     : prec == kPrecF16x3 ? (launch_edge<F, kPrecF16x3>(g, eb, kEdgeFwd)) : (launch_edge<F, kPrecF32>(g, eb, kEdgeFwd)));
             prof_end(g);
-            if (two_pass) {   // second pass: the lower edges' terms, with the filter values the first pass kept
+            if (upper) {   // second pass: the lower edges' terms, with the filter values the first pass kept
                 prof_begin(g, MLIP_PROF_EDGE_FWD_LOWER);
                 const SmallBatch sb = small_batch(p0, U_OWNED, l);
                 if (sb.start[sb.n] > 0)
-                    k_edge_fwd_lower<F><<<blocks_for(sb.start[sb.n], 4), 256, 0, s>>>(sb);
+                    k_edge_lower<F, false><<<blocks_for(sb.start[sb.n], 4), 256, 0, s>>>(sb);
                 MLIP_HIP(hipGetLastError());
                 prof_end(g);
             }
@@ -722,10 +742,29 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
                 ea.mirror = v.mirror;
                 ea.wstore = need_gbar ? wslice(v, l) : nullptr;
                 ea.n_stored = need_gbar ? v.n_edges_owned : 0;
+                if (upper) {   // on the partition's upper-edge graph
+                    const PairGraph &Q = v.pairs;
+                    ea.n_chunks = chunks_of(Q.n_upper);
+                    ea.chunk_row = Q.u_chunk_row;
+                    ea.row_ptr = Q.u_row_ptr;
+                    ea.senders = Q.u_senders;
+                    ea.recv = Q.u_recv;
+                    ea.d = Q.u_d;
+                    ea.mirror = Q.u_mirror;
+                    ea.eid = Q.u_eid;
+                    ea.n_stored = need_gbar ? Q.n_upper : 0;
+                }
             }
             prof_begin(g, MLIP_PROF_EDGE_BWD);
-            MLIP_TRY(prec == kPrecBf16 ? (launch_edge<F, kPrecBf16>(g, eb, kEdgeBwd))
-                     : prec == kPrecF16x3 ? (launch_edge<F, kPrecF16x3>(g, eb, kEdgeBwd)) : (launch_edge<F, kPrecF32>(g, eb, kEdgeBwd)));
+            const int kind = upper ? kEdgeBwdUpper : kEdgeBwd;
+            MLIP_TRY(prec == kPrecBf16 ? (launch_edge<F, kPrecBf16>(g, eb, kind))
+                     : prec == kPrecF16x3 ? (launch_edge<F, kPrecF16x3>(g, eb, kind)) : (launch_edge<F, kPrecF32>(g, eb, kind)));
+            if (upper && need_gbar) {   // second pass: the rows' lower edges, from what their pairs' upper edges handed over
+                const SmallBatch sb = small_batch(p0, U_OWNED, l);
+                if (sb.start[sb.n] > 0)
+                    k_edge_lower<F, true><<<blocks_for(sb.start[sb.n], 4), 256, 0, s>>>(sb);
+                MLIP_HIP(hipGetLastError());
+            }
             prof_end(g);
         }
         if (any_bonds) {   // bond term: its share of gbar; this layer's abar is kept for the bonds' own reverse step

@@ -21,6 +21,9 @@ struct EdgeArgs {
     float *wstore;             // forward: filter values w_e [n_stored][F] kept for the reverse pass (or null)
     const int32_t *mirror;     // reverse: position of every edge's reverse edge
     const int32_t *chunk_row;  // first row of every work item
+    // Upper-edge graph (the arrays above then describe the compacted upper edges of the partition; mirror holds the
+    // reverse edges' indices in the partition's full edge list):
+    const int32_t *eid;        // reverse: index of every upper edge in the full edge list
 };
 
 // What all partitions of one launch share: the layer's packed weights and the basis.
@@ -274,216 +277,6 @@ __global__ void __launch_bounds__(256, 3) k_edge_fwd(EdgeBatch B)
     }   // partitions
 }
 
-// Forward edge step over edge pairs, first pass.
-//
-// Both edges of an edge / reverse-edge pair have the same length and therefore, bit for bit, the same filter values
-// w.  This kernel evaluates the filter MLP only for the upper edge of every pair (the one with the smaller index),
-// keeps its w at the edge's own slot and adds w * g_j to the receiver's sum; k_edge_fwd_lower then adds the lower
-// edges' terms with w read back from the reverse edge's slot.  That halves the matrix work of the forward step.
-// A wavefront walks its work item (a run of complete rows) in groups of 64 consecutive edges, picks the upper
-// edges out of each group (wave-uniform mask, rank by population count) and collects them in the 16 spare bytes
-// that every row of its LDS tile has, until 32 are there or the item is exhausted: every tile but the last one of
-// an item is full.  A row's sum is carried from tile to tile and stored when the first edge of another row
-// arrives (or at the end of the item), so no look-ahead past the collected edges is needed; rows without an upper
-// edge get zeros.  Everything after the collection is the tile code of k_edge_fwd.
-template <int F, int PREC>
-__global__ void __launch_bounds__(256, 3) k_edge_fwd_pairs(EdgeBatch B)
-{
-    using D = Dims<F>;
-    extern __shared__ float lds[];
-    float *A2t = lds;
-    float *tiles = A2t + D::PACKF;
-    for (int i = threadIdx.x; i < (PREC == kPrecBf16 ? D::PACKF / 2 : D::PACKF); i += 256) A2t[i] = B.c.A2t[i];
-    __syncthreads();
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-    const int c32 = lane & 31;
-    const unsigned f = lane & (F - 1);
-    float *tile = tiles + wave * D::TILE;
-    const EdgeCommon &C = B.c;
-    RegPack1<F> W1;
-    load_pack1<F>(W1, C.A1s, lane);
-    const ItemQueue items = edge_items(B.chunk_start[B.n], B.work, wave);
-    int64_t item = items.first;
-    int32_t drawn = 0;
-    for (int part = 0; part < B.n; ++part) {
-    const int64_t part_end = min(items.end, B.chunk_start[part + 1]);
-    if (item >= part_end) continue;
-    const EdgeArgs A = B.s[part];
-    const __amdgpu_buffer_rsrc_t g_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<float *>(A.g), 0, (int)(A.n_nodes * F * 4), kBufferFlags);
-    const __amdgpu_buffer_rsrc_t o_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-        A.out, 0, (int)(A.n_rows * F * 4), kBufferFlags);
-    auto store_row = [&](int32_t row, float v) {
-        if (F == 64 || lane < F) buffer_store_f32(v, o_rsrc, f * 4, row * (F * 4), 0);
-    };
-    for (; item < part_end; item = items.resolve(drawn)) {
-    drawn = items.draw(lane);
-    const int64_t chunk = item - B.chunk_start[part];
-    int64_t r0, r1;
-    if (!chunk_rows(A, chunk, r0, r1)) continue;
-    const int32_t e_lo = __builtin_amdgcn_readfirstlane((int32_t)A.row_ptr[r0]);
-    const int32_t e_hi = __builtin_amdgcn_readfirstlane((int32_t)A.row_ptr[r1]);
-    const int32_t r_end = (int32_t)r1;
-    int32_t next_unwritten = (int32_t)r0;   // rows before it have their sums stored
-    int32_t row_open = -1;                  // row whose sum acc carries (-1: none)
-    float acc = 0.f;
-    // source groups of 64 consecutive edges: lane k holds edge src + k of the current group; the next two groups are
-    // requested while a tile is multiplied and retired at the end of that tile, so that the collection usually finds
-    // them there (a tile takes one group on average) and no load is left pending across a loop edge; where the upper
-    // edges are sparse and the two are used up, further groups are loaded on the spot
-    struct Src {
-        float d;
-        int32_t s, r, m;
-    };
-    auto load_src = [&](Src &G, int32_t base) {
-        const int32_t en = min(base + lane, e_hi - 1);
-        G.d = A.d[en];
-        G.s = A.senders[en];
-        G.r = A.recv[en];
-        G.m = A.mirror[en];
-    };
-    auto uppers_of = [&](const Src &G, int32_t base) {
-        return (unsigned long long)__ballot(base + lane < e_hi && G.m > base + lane);
-    };
-    Src cur, nx1, nx2;
-    int32_t src = e_lo;
-    int nbuf = 0;                  // groups after the current one that are loaded (nx1, then nx2)
-    unsigned long long pend = 0;   // upper edges of the current group that are not collected yet
-    if (e_lo < e_hi) {
-        load_src(cur, src);
-        load_src(nx1, src + 64);
-        load_src(nx2, src + 128);
-        nbuf = 2;
-        pend = uppers_of(cur, src);
-        asm volatile("" : "+v"(nx1.d), "+v"(nx1.s), "+v"(nx1.r), "+v"(nx1.m), "+v"(nx2.d), "+v"(nx2.s), "+v"(nx2.r), "+v"(nx2.m));
-    }
-    const __amdgpu_buffer_rsrc_t w_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-        A.wstore + (int64_t)e_lo * F, 0, (e_hi - e_lo) * (F * 4), kBufferFlags);   // the item's slots
-    for (;;) {
-        // ---- collect up to 32 upper edges: entry k = {length, sender, receiver, edge index} in the spare bytes of tile row k
-        int avail = 0;
-        for (;;) {
-            if (pend == 0) {
-                src += 64;
-                if (src >= e_hi) break;
-                if (nbuf > 0) {
-                    cur = nx1;
-                    nx1 = nx2;
-                    --nbuf;
-                } else {
-                    load_src(cur, src);
-                }
-                pend = uppers_of(cur, src);
-                continue;
-            }
-            const int rank = (int)__builtin_amdgcn_mbcnt_hi((unsigned)(pend >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)pend, 0u));
-            const bool mine = ((pend >> lane) & 1ull) != 0 && rank < 32 - avail;
-            if (mine) {
-                float *en = tile + (avail + rank) * D::FS + F;
-                en[0] = cur.d;
-                reinterpret_cast<int32_t *>(en)[1] = cur.s;
-                reinterpret_cast<int32_t *>(en)[2] = cur.r;
-                reinterpret_cast<int32_t *>(en)[3] = src + lane;
-            }
-            const unsigned long long taken = __ballot(mine);
-            pend &= ~taken;
-            avail += __builtin_popcountll(taken);
-            if (avail == 32) break;
-        }
-        if (avail == 0) break;
-        if (nbuf < 2 && src + 64 < e_hi) {   // request the groups the collection used up
-            if (nbuf == 0) load_src(nx1, src + 64);
-            load_src(nx2, src + 128);
-            nbuf = 2;
-        }
-        wave_lds_fence();
-        const int kmax = avail;
-        const bool valid = c32 < kmax;
-        const float *en = tile + min(c32, kmax - 1) * D::FS + F;
-        const float dv = en[0];
-        const int32_t sv = reinterpret_cast<const int32_t *>(en)[1];
-        const int32_t rk = reinterpret_cast<const int32_t *>(en)[2];
-        const int32_t ev = reinterpret_cast<const int32_t *>(en)[3];
-        float b[8], db[8];
-        radial_basis<false>(valid ? dv : C.bp.rc, C.bp, b, db);
-        // sender rows of this tile: issued now, consumed after the MFMA chain (a lane past the end repeats the last entry; its filter is zero)
-        float gv[32];
-        const int32_t so = sv * (F * 4);
-#pragma unroll
-        for (int k = 0; k < 32; ++k) gv[k] = buffer_load_f32(g_rsrc, f * 4, __builtin_amdgcn_readlane(so, k), 0);
-        const int32_t wo = valid ? (ev - e_lo) * (F * 4) : (e_hi - e_lo) * (F * 4);   // slot of the edge; past the range: dropped
-        __builtin_amdgcn_sched_barrier(0);
-        f32x16 t[D::NB], w[D::NB];
-        gemm_k8r<F>(W1, b, t, lane);
-#pragma unroll
-        for (int bb = 0; bb < D::NB; ++bb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) t[bb][r] = t[bb][r] * sigmoid_scaled(t[bb][r]);
-        if (PREC == kPrecBf16)
-            gemm_rl_bf16<F>(reinterpret_cast<const __bf16 *>(A2t), t, w, lane);
-        else if (PREC == kPrecF16x3)
-            gemm_rl_f16x3<F>(reinterpret_cast<const _Float16 *>(A2t), t, w, lane);
-        else
-            gemm_rl<F>(A2t, t, w, lane);
-        regs_to_tile<F>(w, tile, lane);
-        wave_lds_fence();
-        __builtin_amdgcn_sched_barrier(0);
-        // rows: the carried sum belongs to row_open; a tile that starts with another row closes it first
-        const int32_t first_row = __builtin_amdgcn_readfirstlane(rk);
-        if (row_open >= 0 && row_open != first_row) {
-            store_row(row_open, acc);
-            acc = 0.f;
-            next_unwritten = row_open + 1;
-        }
-        for (int32_t r = next_unwritten; r < first_row; ++r) store_row(r, 0.f);   // rows without an upper edge
-        const int32_t up = __shfl(rk, c32 + 1, 64);
-        const uint32_t ends = (uint32_t)__ballot(c32 + 1 < kmax && up != rk);   // the last collected edge never ends its row here
-        float wv[32];
-#pragma unroll
-        for (int k = 0; k < 32; ++k) wv[k] = tile[k * D::FS + f];
-#ifndef MLIP_TIMING_NO_W_STORE
-        if (F == 64) {   // four rows per instruction: lane (q, c) stores features 4 c .. 4 c + 3 of edge 4 i + q
-            const int q = lane >> 4, c4 = (lane & 15) * 4;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int k = 4 * i + q;
-                const f32x4 v = *reinterpret_cast<const f32x4 *>(tile + k * D::FS + c4);
-                const int32_t off = __shfl(wo, k, 64) + c4 * 4;
-                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(__attribute__((ext_vector_type(4))) unsigned, v), w_rsrc,
-                                                       off, 0, 2);
-            }
-        } else {
-#pragma unroll
-            for (int k = 0; k < 32; ++k)
-                if (lane < F) buffer_store_f32_stream(wv[k], w_rsrc, f * 4, __builtin_amdgcn_readlane(wo, k));
-        }
-#endif
-#pragma unroll
-        for (int k = 0; k < 32; ++k) {
-            acc = fmaf(wv[k], gv[k], acc);   // lanes past the end hold a zero filter
-            if (__builtin_expect((ends & (1u << k)) != 0, 0)) {
-                const int32_t row = __builtin_amdgcn_readlane(rk, k);
-                const int32_t nrow = __builtin_amdgcn_readlane(up, k);
-                store_row(row, acc);
-                acc = 0.f;
-                for (int32_t r = row + 1; r < nrow; ++r) store_row(r, 0.f);
-            }
-        }
-        row_open = __builtin_amdgcn_readlane(rk, kmax - 1);
-        next_unwritten = row_open;   // rows before the open one are stored (it is stored when it closes)
-        wave_lds_fence();
-        // retire the requested groups here (they arrived during the products)
-        asm volatile("" : "+v"(nx1.d), "+v"(nx1.s), "+v"(nx1.r), "+v"(nx1.m), "+v"(nx2.d), "+v"(nx2.s), "+v"(nx2.r), "+v"(nx2.m));
-    }
-    if (row_open >= 0) {
-        store_row(row_open, acc);
-        next_unwritten = row_open + 1;
-    }
-    for (int32_t r = next_unwritten; r < r_end; ++r) store_row(r, 0.f);
-    }   // work items
-    }   // partitions
-}
-
 // Reverse edge step.
 //
 // Phase 1 (lane = feature), 16 edges at a time, every edge of the rows:
@@ -555,7 +348,12 @@ __device__ inline void gemm_queue(const float *__restrict__ Ap, const float *row
     }
 }
 
-template <int F, int PREC>
+// COMPACT: the launch runs on the partitions' upper-edge graphs: every edge it sees is the upper edge of its pair and the
+// row sums it stores (gbar) are those of the upper edges only; k_edge_lower completes them with the lower edges' terms.
+// (Letting this kernel hand w * abar_i to the lower edge's row through memory instead was measured: vector stores
+// return in order with the loads on this chip, and 16 scattered row stores per step stalled the load pipeline:
+// 5.2 ms per launch against 3.5 ms.)
+template <int F, int PREC, bool COMPACT>
 __global__ void __launch_bounds__(kBwdWaves * 64, kBwdWaves == 4 ? 2 : 1) k_edge_bwd(EdgeBatch B)
 {
     using D = Dims<F>;
@@ -614,6 +412,7 @@ __global__ void __launch_bounds__(kBwdWaves * 64, kBwdWaves == 4 ? 2 : 1) k_edge
     struct Ids {    // lane k (mod kStep) holds edge tb + k, clamped to the last edge of the work item
         int32_t sj, rk, mk;
         float dk;
+        int32_t ek;       // COMPACT: the edge's index in the full list
     };
     struct Step {
         float av[kStep], gv[kStep], wv[kStep];   // abar / g rows of the senders, kept filter values
@@ -628,6 +427,7 @@ __global__ void __launch_bounds__(kBwdWaves * 64, kBwdWaves == 4 ? 2 : 1) k_edge
         I.rk = A.recv[e];
         I.mk = A.mirror[e];
         I.dk = A.d[e];
+        if (COMPACT) I.ek = A.eid[e];
     };
     auto load_step = [&](Step &S, const Ids &I, int32_t tb) {
         S.tb = tb;
@@ -636,7 +436,8 @@ __global__ void __launch_bounds__(kBwdWaves * 64, kBwdWaves == 4 ? 2 : 1) k_edge
         // every path through the pipeline then has the same number of loads in flight, which is what lets
         // the waits before the uses be partial ones.
         const int32_t sjo = I.sj * kRowBytes;
-        S.uppers = (uint32_t)__ballot(l16 < S.kmax && I.mk > tb + l16) & ((1u << kStep) - 1u);
+        S.uppers = COMPACT ? ((1u << S.kmax) - 1u)
+                           : ((uint32_t)__ballot(l16 < S.kmax && I.mk > tb + l16) & ((1u << kStep) - 1u));
         const int32_t row0 = __builtin_amdgcn_readfirstlane(I.rk);
         const int32_t rowl = __builtin_amdgcn_readlane(I.rk, max(S.kmax - 1, 0));
         S.ai0 = buffer_load_f32(a_rsrc, f * 4, row0 * kRowBytes, 0);
@@ -668,12 +469,12 @@ __global__ void __launch_bounds__(kBwdWaves * 64, kBwdWaves == 4 ? 2 : 1) k_edge
         if (S.kmax <= 0) return;
         const bool valid_l = l16 < S.kmax;
         const int32_t rk = valid_l ? I.rk : r1;
-        const int32_t e_l = S.tb + l16;
+        const int32_t e_l = COMPACT ? I.ek : S.tb + l16;   // index in the full edge list
         // wave-uniform masks: bit k = edge k ends its row / edge k is the upper edge of its pair
         const int32_t up = __shfl(rk, l16 + 1, 64);
         const int32_t rnext = (l16 == kStep - 1) ? rn_first : up;
         const uint32_t ends = (uint32_t)__ballot(valid_l && rnext != rk) & ((1u << kStep) - 1u);
-        const bool upper_l = valid_l && I.mk > e_l;
+        const bool upper_l = COMPACT ? valid_l : (valid_l && I.mk > e_l);
         const uint32_t uppers = S.uppers;
         {   // records of the pairs queued by this step, all at once: slots follow q_tail in edge order
             int slot = q_tail + (int)__builtin_amdgcn_mbcnt_lo(uppers, 0u);   // upper edges before this lane's (lanes < kStep)

@@ -200,6 +200,8 @@ struct SmallArgs {   // one partition
     const uint32_t *shiftp;
     float *h, *g, *gbar, *abar, *floc, *eps;
     float *a;                      // the layer's receiver sums (second pass of the pair-wise forward step)
+    // upper / lower split of the owned rows' edges (or nullptr: kept filter values sit at the edges' own indices)
+    const int32_t *wslot;          // [E_owned] upper index of an edge's pair: where its kept filter values are
     const float *dsum, *wstore, *d;
     const int32_t *bond_of_edge;   // three-body variant (or nullptr)
     const void *wb;                // bond filter rows of the layer: fp32, or bf16 if wb_bf16
@@ -269,13 +271,15 @@ __global__ void k_zero_ghost_rows(SmallBatch B, int F)
 // gbar of the ghost rows: gbar_i = sum over the ghost's sub-row (its neighbours owned by this partition) of
 // w_e * abar_send(e).  w_e is the reverse edge's, which the forward pass kept (both edges of a pair have the
 // same length, hence the same filter value).  One wavefront per row, lane = feature, edges in row order.
-// Forward edge step over edge pairs, second pass: a_i += sum over the lower edges e = (i <- j) of row i of w * g_j, with w
-// read from the slot of the reverse edge, which the first pass has filled.  One wavefront per row, lane = feature; the
+// Second pass of the edge steps that run on the upper-edge graphs: the lower edges' terms of the row sums, with the
+// filter values w read from the row of the edge's pair, which the forward edge kernel (on the upper-edge graph) filled.
+//   forward: a_i    += sum over the lower edges e = (i <- j) of row i of  w * g_j
+//   REVERSE: gbar_i += sum over the same edges of                         w * abar_j  One wavefront per row, lane = feature; the
 // lower edges of 64 edges at a time are taken kLowerChunk at a time, all their rows in flight together.
 constexpr int kLowerChunk = 16;   // lower edges whose rows are in flight together (32 measured no faster)
 
-template <int F>
-__global__ void __launch_bounds__(256) k_edge_fwd_lower(SmallBatch B)
+template <int F, bool REVERSE>
+__global__ void __launch_bounds__(256) k_edge_lower(SmallBatch B)
 {
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int64_t gk = (int64_t)blockIdx.x * 4 + wave;
@@ -289,6 +293,7 @@ __global__ void __launch_bounds__(256) k_edge_fwd_lower(SmallBatch B)
     for (int64_t eb = e0; eb < e1; eb += 64) {
         const int64_t el = min(eb + lane, e1 - 1);
         const int32_t jl = A.senders[el], ml = A.mirror[el];
+        const int32_t sl = A.wslot[el];   // where the pair's filter values are kept
         unsigned long long mask = __ballot(eb + lane < e1 && (int64_t)ml < el);   // the lower edges among these 64
         while (mask != 0) {
             float wv[kLowerChunk], gv[kLowerChunk];
@@ -300,16 +305,16 @@ __global__ void __launch_bounds__(256) k_edge_fwd_lower(SmallBatch B)
                     const int idx = __builtin_ctzll(mask);
                     mask &= mask - 1;
                     ++n;
-                    const int64_t j = __builtin_amdgcn_readlane(jl, idx), m = __builtin_amdgcn_readlane(ml, idx);
+                    const int64_t j = __builtin_amdgcn_readlane(jl, idx), m = __builtin_amdgcn_readlane(sl, idx);
                     wv[t] = __builtin_nontemporal_load(A.wstore + m * F + f);
-                    gv[t] = A.g[j * F + f];
+                    gv[t] = (REVERSE ? A.abar : A.g)[j * F + f];
                 }
             }
 #pragma unroll
             for (int t = 0; t < kLowerChunk; ++t) acc = fmaf(wv[t], gv[t], acc);
         }
     }
-    if (F == 64 || lane < F) A.a[r * F + f] += acc;
+    if (F == 64 || lane < F) (REVERSE ? A.gbar : A.a)[r * F + f] += acc;
 }
 
 template <int F>
@@ -329,10 +334,11 @@ __global__ void __launch_bounds__(256) k_ghost_gbar(SmallBatch B)
         const int64_t el = min(eb + (lane & 15), e1 - 1);
         const int32_t jl = A.senders[el], ml = A.mirror[el];
         const int32_t bl = A.bond_of_edge ? A.bond_of_edge[ml] : -1;   // three-body variant: the reverse edge's bond
+        const int32_t sl = A.wslot ? A.wslot[ml] : ml;                 // where the reverse edge's filter values are kept
         float wv[16], av[16];
 #pragma unroll
         for (int k = 0; k < 16; ++k) {
-            const int64_t j = __builtin_amdgcn_readlane(jl, k), m = __builtin_amdgcn_readlane(ml, k);
+            const int64_t j = __builtin_amdgcn_readlane(jl, k), m = __builtin_amdgcn_readlane(sl, k);
             const int64_t b = __builtin_amdgcn_readlane(bl, k);
             wv[k] = A.wstore[m * F + f];
             if (b >= 0)

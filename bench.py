@@ -21,10 +21,10 @@ PEAK_FP32_MFMA_TFLOPS = 157.3
 #   reverse: pre-activations t = b W1 (2 K F), sbar = wbar W2^T (2 F F), dt/dd contraction through W1 (2 K F);
 #            the filter value w_e itself is not recomputed, the forward pass keeps it in HBM (layers >= 1).
 # The reverse kernel runs this dense work once per edge / reverse-edge pair (both have the same length), so the
-# MFMA units execute half of the reverse figure per directed edge; with fp32 MFMA the forward step does the same (the
-# first pass evaluates the filter MLP for the upper edge of every pair, a second, memory-bound pass adds the lower
-# edges' terms).  A kernel's roofline fraction is taken on what it executes; the rate of the operation as defined is
-# reported beside it ("as_defined_tflops").
+# MFMA units execute half of the reverse figure per directed edge; with fp32 MFMA the edge kernels run on the upper
+# edge of every pair only (the forward one then evaluates the filter MLP once per pair too), and memory-bound second
+# passes add the lower edges' terms.  A kernel's roofline fraction is taken on what it executes; the rate of the
+# operation as defined is reported beside it ("as_defined_tflops").
 def flops_fwd_edge(F, K=8):
     return 2 * K * F + 2 * F * F
 
@@ -206,9 +206,9 @@ def main():
     F = c["F"]
     roof_bwd = edge_roofline("edge_bwd", f"k_edge_bwd<{F}> (reverse edge step)", flops_bwd_edge(F),
                              TRAFFIC_BWD_LAUNCH_BYTES, flops_bwd_edge_as_defined(F))
-    two_pass = prof["edge_fwd_lower"][1] > 0   # the filter MLP once per edge pair, lower edges in a second pass
+    two_pass = prof["edge_fwd_lower"][1] > 0   # edge kernels on the pairs' upper edges, lower edges in second passes
     if two_pass:
-        roof_fwd = edge_roofline("edge_fwd", f"k_edge_fwd_pairs<{F}> (forward edge step, first pass: upper edges)",
+        roof_fwd = edge_roofline("edge_fwd", f"k_edge_fwd<{F}> on the upper-edge graphs (forward edge step, first pass)",
                                  flops_fwd_edge(F) // 2, TRAFFIC_FWD_LAUNCH_BYTES, flops_fwd_edge(F))
         # the operation as defined takes both passes: price it on their summed time
         both_ms = prof["edge_fwd"][0] + prof["edge_fwd_lower"][0]
@@ -217,18 +217,26 @@ def main():
     else:
         roof_fwd = edge_roofline("edge_fwd", f"k_edge_fwd<{F}> (forward edge step)", flops_fwd_edge(F),
                                  TRAFFIC_FWD_LAUNCH_BYTES)
+    if two_pass:   # the reverse operation as defined takes both of its passes
+        both_ms = prof["edge_bwd"][0] + prof["edge_bwd_lower"][0]
+        roof_bwd["kernel"] = f"k_edge_bwd<{F}> on the upper-edge graphs (reverse edge step, first pass)"
+        roof_bwd["as_defined_tflops"] = E * flops_bwd_edge_as_defined(F) * L * args.steps / (both_ms * 1e-3) / 1e12
+        roof_bwd["as_defined_ms_per_step"] = both_ms / args.steps
     roof = roof_fwd if roof_fwd["ms_per_step"] >= roof_bwd["ms_per_step"] else roof_bwd   # the dominant kernel
-    roof_lower = None
-    if two_pass:   # bound by its row traffic; compulsory bytes: per lower edge the kept filter values (read once), per
-                   # atom the projected row that is gathered (once if the caches were perfect) and the sum (read, written)
-        ms, n = prof["edge_fwd_lower"]
-        per_launch = (E / 2 * F * 4 + N * 3 * F * 4) * L * args.steps / max(n, 1)
-        avg_ms = ms / max(n, 1)
-        ach = per_launch / (avg_ms * 1e-3) / 1e9 if avg_ms > 0 else 0.0
-        roof_lower = {"kernel": f"k_edge_fwd_lower<{F}> (forward edge step, second pass: lower edges)", "bound": "hbm",
-                      "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS, "traffic": None,
-                      "avg_launch_ms": avg_ms, "launches": int(n), "bytes_per_launch": per_launch,
-                      "ms_per_step": ms / args.steps}
+    roof_lower = {}
+    if two_pass:   # bound by their row traffic; compulsory bytes: per lower edge the kept filter values (read once), per
+                   # atom the row that is gathered (once if the caches were perfect) and the sum (read, written)
+        for group, what in (("edge_fwd_lower", "forward"), ("edge_bwd_lower", "reverse")):
+            ms, n = prof[group]
+            if n == 0:
+                continue
+            per_launch = E / 2 * F * 4 + N * 3 * F * 4
+            avg_ms = ms / n
+            ach = per_launch / (avg_ms * 1e-3) / 1e9 if avg_ms > 0 else 0.0
+            roof_lower[group] = {"kernel": f"k_edge_lower<{F}> ({what} edge step, second pass: lower edges)", "bound": "hbm",
+                                 "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS,
+                                 "traffic": None, "avg_launch_ms": avg_ms, "launches": int(n),
+                                 "bytes_per_launch": per_launch, "ms_per_step": ms / args.steps}
     roof_trip = {}
     if three_body:
         _, bptr = g.bonds()
@@ -266,8 +274,8 @@ def main():
     }
     for k, v in roof_trip.items():
         res["roofline_" + k] = v
-    if roof_lower is not None:
-        res["roofline_edge_fwd_lower"] = roof_lower
+    for k, v in roof_lower.items():
+        res["roofline_" + k] = v
     if split_ms is not None:
         res["split_fp16_products"] = {"ms_per_step": split_ms, "value": N / (split_ms * 1e-3), "unit": "atoms/s",
                                       "energy": energy_split,

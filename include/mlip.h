@@ -330,9 +330,10 @@ enum {
     MLIP_PROF_BOND = 6,    /* three-body variant: bond list and the kernels over bonds */
     MLIP_PROF_TRIPLET_FWD = 7,   /* three-body variant: the triplet sum           */
     MLIP_PROF_TRIPLET_BWD = 8,   /* three-body variant: its reverse               */
-    MLIP_PROF_EDGE_FWD_LOWER = 9, /* forward edge step, second pass (where the filter MLP is evaluated once per edge pair:
-                                     the terms of the pairs' lower edges, from the filter values the first pass kept) */
-    MLIP_PROF_COUNT = 10
+    MLIP_PROF_EDGE_FWD_LOWER = 9, /* forward edge step, second pass (where the edge kernels run on one edge per edge /
+                                     reverse-edge pair: the terms of the pairs' lower edges, from the kept filter values) */
+    MLIP_PROF_EDGE_BWD_LOWER = 10, /* reverse edge step, second pass (the same for the gradients of the projected rows) */
+    MLIP_PROF_COUNT = 11
 };
 int mlip_profile_enable(mlip_graph_t *graph, int32_t on);
 int mlip_profile_read(mlip_graph_t *graph, float *ms /*HOST [MLIP_PROF_COUNT]*/,

@@ -18,7 +18,7 @@ _LIB_PATH = os.environ.get("MLIP_LIBRARY") or os.path.join(_HERE, "libmlip.so")
 MODE_WHOLE, MODE_SLABS = 0, 1
 PRECISION_FP32, PRECISION_BF16, PRECISION_FP32_SPLIT = 0, 1, 2
 PROF_GROUPS = ("graph", "node", "edge_fwd", "edge_bwd", "ghost", "force", "bond", "triplet_fwd", "triplet_bwd",
-               "edge_fwd_lower")
+               "edge_fwd_lower", "edge_bwd_lower")
 
 
 class MlipError(RuntimeError):

@@ -344,7 +344,7 @@ void mlip_graph_destroy(mlip_graph_t *g)
     DevBuf *bufs[] = {&g->pos, &g->species, &g->cell_of, &g->wrapp, &g->cell_cnt, &g->cell_start, &g->cell_fill,
                       &g->sid, &g->sx, &g->sy, &g->sz, &g->swrap, &g->counts, &g->keys, &g->stage, &g->pair_aux, &g->flags, &g->scan_tmp,
                       &g->small, &g->row_ptr, &g->senders, &g->recv, &g->mirror, &g->shiftp, &g->d, &g->chunk_row, &g->slab_of, &g->needed_by,
-                      &g->local_of, &g->local_in_owner, &g->class_cnt, &g->class_off, &g->wpack, &g->energy_part, &g->work,
+                      &g->local_of, &g->local_in_owner, &g->class_cnt, &g->class_off, &g->wpack, &g->energy_part, &g->work, &g->pair_cnt, &g->pair_scan,
                       &g->cand_row_ptr, &g->cand_senders, &g->cand_recv, &g->cand_shiftp, &g->cand_d, &g->cand_mirror, &g->ref_pos};
     for (DevBuf *b : bufs) b->release();
     g->bond_wpack.release();
@@ -356,8 +356,8 @@ void mlip_graph_destroy(mlip_graph_t *g)
                         &B.ubar, &B.dbond, &B.rbar};
         for (DevBuf *b : vb) b->release();
         PairGraph &Q = v.pairs;
-        DevBuf *pb[] = {&Q.b_rowcnt, &Q.b_u_row_ptr, &Q.b_l_row_ptr, &Q.b_cidx, &Q.b_wslot, &Q.b_u_senders, &Q.b_u_recv,
-                        &Q.b_u_eid, &Q.b_u_mirror, &Q.b_u_qslot, &Q.b_u_d, &Q.b_u_chunk_row};
+        DevBuf *pb[] = {&Q.b_u_row_ptr, &Q.b_wslot, &Q.b_u_senders, &Q.b_u_recv,
+                        &Q.b_u_eid, &Q.b_u_mirror, &Q.b_u_d, &Q.b_u_chunk_row};
         for (DevBuf *b : pb) b->release();
     };
     drop_view(g->whole);

@@ -1239,111 +1239,109 @@ int build_bonds_impl(mlip_graph *g, SlabView &v, double r_bond, int p_envelope)
 
 namespace {
 
-// ---- upper / lower split of the owned rows' edges (PairGraph)
+// ---- upper / lower split of the owned rows' edges (PairGraph), up to kPairBatch partitions per launch
 
-// per row: how many of its edges are upper ones (reverse edge at a larger index), how many lower ones
-__global__ void __launch_bounds__(256) k_pair_rowcnt(int64_t n_rows, const int64_t *__restrict__ row_ptr,
-                                                    const int32_t *__restrict__ mirror, int32_t *__restrict__ ucnt,
-                                                    int32_t *__restrict__ lcnt)
+constexpr int kPairBatch = 8;
+
+struct PairArgs {   // one partition
+    int64_t n_rows, n_edges_owned, n_chunks;
+    const int64_t *row_ptr;
+    const int32_t *senders, *recv, *mirror;
+    const float *d;
+    int64_t *u_row_ptr;
+    int32_t *wslot, *u_senders, *u_recv, *u_eid, *u_mirror, *u_chunk_row;
+    float *u_d;
+};
+struct PairBatch {   // rows, edges and work items numbered across the partitions
+    int n;
+    int64_t row_start[kPairBatch + 1], edge_start[kPairBatch + 1], chunk_start[kPairBatch + 1];
+    PairArgs s[kPairBatch];
+};
+__device__ inline int pair_find(const int64_t *start, int n, int64_t w)
 {
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int64_t r = (int64_t)blockIdx.x * 4 + wave;
-    if (r >= n_rows) return;
-    const int64_t e0 = row_ptr[r], e1 = row_ptr[r + 1];
-    int nu = 0;
-    for (int64_t eb = e0; eb < e1; eb += 64) {
-        const int64_t e = eb + lane;
-        nu += __builtin_popcountll(__ballot(e < e1 && (int64_t)mirror[min(e, e1 - 1)] > e));
-    }
-    if (lane == 0) {
-        ucnt[r] = nu;
-        lcnt[r] = (int)(e1 - e0) - nu;
-    }
+    int p = 0;
+#pragma unroll
+    for (int q = 1; q < kPairBatch; ++q)
+        if (q < n && w >= start[q]) p = q;
+    return p;
 }
 
-// the compacted upper edges and every edge's index within its class
-__global__ void __launch_bounds__(256)
-k_pair_fill(int64_t n_rows, const int64_t *__restrict__ row_ptr, const int32_t *__restrict__ senders,
-            const int32_t *__restrict__ mirror, const float *__restrict__ d, const int64_t *__restrict__ u_row_ptr,
-            const int64_t *__restrict__ l_row_ptr, int32_t *__restrict__ cidx, int32_t *__restrict__ u_senders,
-            int32_t *__restrict__ u_recv, int32_t *__restrict__ u_eid, int32_t *__restrict__ u_mirror, float *__restrict__ u_d)
+// flag[e] = 1 for the upper edge of a pair (reverse edge at a larger index), over all partitions' owned-row edges
+__global__ void k_pair_flag(PairBatch B, int32_t *__restrict__ flag)
 {
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int64_t r = (int64_t)blockIdx.x * 4 + wave;
-    if (r >= n_rows) return;
-    const int64_t e0 = row_ptr[r], e1 = row_ptr[r + 1];
-    int64_t ku = u_row_ptr[r], kl = l_row_ptr[r];
-    for (int64_t eb = e0; eb < e1; eb += 64) {
-        const int64_t e = eb + lane;
-        const bool in = e < e1;
-        const int32_t m = in ? mirror[e] : 0;
-        const bool upper = in && (int64_t)m > e;
-        const unsigned long long um = __ballot(upper), lm = __ballot(in && !upper);
-        const unsigned long long below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
-        if (upper) {
-            const int64_t k = ku + __builtin_popcountll(um & below);
-            cidx[e] = (int32_t)k;
-            u_senders[k] = senders[e];
-            u_recv[k] = (int32_t)r;
-            u_eid[k] = (int32_t)e;
-            u_mirror[k] = m;
-            u_d[k] = d[e];
-        } else if (in) {
-            cidx[e] = (int32_t)(kl + __builtin_popcountll(lm & below));
-        }
-        ku += __builtin_popcountll(um);
-        kl += __builtin_popcountll(lm);
-    }
+    const int64_t ge = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (ge >= B.edge_start[B.n]) return;
+    const int part = pair_find(B.edge_start, B.n, ge);
+    const int64_t e = ge - B.edge_start[part];
+    flag[ge] = (int64_t)B.s[part].mirror[e] > e ? 1 : 0;
 }
 
-// wslot[e]: upper index of the pair of edge e; u_qslot[k]: lower index of the reverse edge of upper edge k
-__global__ void k_pair_slots(int64_t E_owned, const int32_t *__restrict__ mirror, const int32_t *__restrict__ cidx,
-                             int32_t *__restrict__ wslot, int32_t *__restrict__ u_qslot)
+// The upper edges keep their order, so an upper edge's position among them is the exclusive scan of the flags (less
+// the scan at its partition's first edge): the compacted arrays, and for every edge the position of its pair.
+__global__ void k_pair_fill(PairBatch B, const int32_t *__restrict__ scan)
 {
-    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (e >= E_owned) return;
-    const int64_t m = mirror[e];
-    if (m > e) {
-        const int32_t k = cidx[e];
-        wslot[e] = k;
-        u_qslot[k] = (m < E_owned) ? cidx[m] : -1;
+    const int64_t ge = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (ge >= B.edge_start[B.n]) return;
+    const int part = pair_find(B.edge_start, B.n, ge);
+    const PairArgs &A = B.s[part];
+    const int64_t e0 = B.edge_start[part], e = ge - e0;
+    const int32_t base = scan[e0];
+    const int32_t m = A.mirror[e];
+    if ((int64_t)m > e) {
+        const int32_t k = scan[ge] - base;
+        A.u_senders[k] = A.senders[e];
+        A.u_recv[k] = A.recv[e];
+        A.u_eid[k] = (int32_t)e;
+        A.u_mirror[k] = m;
+        A.u_d[k] = A.d[e];
+        A.wslot[e] = k;
     } else {
-        wslot[e] = cidx[m];
+        A.wslot[e] = scan[e0 + m] - base;   // (letting the upper edge store this instead was measured slower)
     }
 }
 
-// chunk_row[c] = first row whose first edge lies at or after c * kChunkEdges; chunk_row[n_chunks] = n_rows.
-__global__ void k_chunk_rows_of(int64_t n_rows, int64_t n_chunks, const int64_t *__restrict__ row_ptr,
-                                int32_t *__restrict__ chunk_row)
+// row pointers of the upper-edge graphs: the scan at the rows' first edges
+__global__ void k_pair_rowptr(PairBatch B, const int32_t *__restrict__ scan)
 {
-    const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (c > n_chunks) return;
-    int64_t lo = 0, hi = n_rows;
-    if (c == n_chunks) lo = n_rows;
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;   // row, plus one closing entry per partition
+    if (i >= B.row_start[B.n] + B.n) return;
+    int part = 0;
+    for (int q = 1; q < B.n; ++q)
+        if (i >= B.row_start[q] + q) part = q;
+    const PairArgs &A = B.s[part];
+    const int64_t r = i - (B.row_start[part] + part);   // 0 .. n_rows
+    const int64_t e0 = B.edge_start[part];
+    A.u_row_ptr[r] = (int64_t)(scan[e0 + A.row_ptr[r]] - scan[e0]);
+}
+
+// u_chunk_row[c] = first row whose first upper edge lies at or after c * kChunkEdges; u_chunk_row[n_chunks] = n_rows.
+__global__ void k_pair_chunks(PairBatch B)
+{
+    const int64_t gc = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;   // work item, plus one closing entry per partition
+    if (gc >= B.chunk_start[B.n] + B.n) return;
+    int part = 0;
+    for (int q = 1; q < B.n; ++q)
+        if (gc >= B.chunk_start[q] + q) part = q;
+    const PairArgs &A = B.s[part];
+    const int64_t c = gc - (B.chunk_start[part] + part);   // 0 .. n_chunks
+    int64_t lo = 0, hi = A.n_rows;
+    if (c == A.n_chunks) lo = A.n_rows;
     const int64_t v = c * kChunkEdges;
     while (lo < hi) {
         const int64_t mid = (lo + hi) >> 1;
-        if (row_ptr[mid] < v) lo = mid + 1; else hi = mid;
+        if (A.u_row_ptr[mid] < v) lo = mid + 1; else hi = mid;
     }
-    chunk_row[c] = (int32_t)lo;
+    A.u_chunk_row[c] = (int32_t)lo;
 }
 
 }  // namespace
 
-int build_pairs_impl(mlip_graph *g, SlabView &v, Carver *scratch)
+int build_pairs_impl(mlip_graph *g, SlabView *views, int P, Carver *scratch)
 {
-    PairGraph &Q = v.pairs;
-    if (Q.valid) return MLIP_OK;
+    bool all_valid = true;
+    for (int p = 0; p < P; ++p) all_valid = all_valid && views[p].pairs.valid;
+    if (all_valid) return MLIP_OK;
     hipStream_t s = g->stream;
-    const int64_t E = v.n_edges_owned, N = v.n_owned;
-    // every pair of two owned-row edges has one upper edge; an owned-row edge from a ghost sender is an upper edge, and
-    // the ghost rows hold exactly the reverse edges of those
-    const int64_t n_ghost_edges = v.n_edges - v.n_edges_owned;
-    Q.n_upper = (E - n_ghost_edges) / 2 + n_ghost_edges;
-    Q.n_lower = E - Q.n_upper;
-    const size_t Ncap = (size_t)std::max<int64_t>(N, 1), Ecap = (size_t)std::max<int64_t>(E, 1);
-    const size_t Ucap = (size_t)std::max<int64_t>(Q.n_upper, 1);
-    const int64_t n_chunks = chunks_of(Q.n_upper);
     auto place = [&](DevBuf &buf, size_t bytes, auto *&ptr) -> int {
         using T = std::remove_reference_t<decltype(*ptr)>;
         if (scratch) {
@@ -1354,38 +1352,86 @@ int build_pairs_impl(mlip_graph *g, SlabView &v, Carver *scratch)
         ptr = buf.as<T>();
         return MLIP_OK;
     };
-    MLIP_TRY(place(Q.b_rowcnt, 2 * Ncap * 4, Q.rowcnt));
-    MLIP_TRY(place(Q.b_u_row_ptr, (Ncap + 1) * 8, Q.u_row_ptr));
-    MLIP_TRY(place(Q.b_l_row_ptr, (Ncap + 1) * 8, Q.l_row_ptr));
-    MLIP_TRY(place(Q.b_cidx, Ecap * 4, Q.cidx));
-    MLIP_TRY(place(Q.b_wslot, Ecap * 4, Q.wslot));
-    MLIP_TRY(place(Q.b_u_senders, Ucap * 4, Q.u_senders));
-    MLIP_TRY(place(Q.b_u_recv, Ucap * 4, Q.u_recv));
-    MLIP_TRY(place(Q.b_u_eid, Ucap * 4, Q.u_eid));
-    MLIP_TRY(place(Q.b_u_mirror, Ucap * 4, Q.u_mirror));
-    MLIP_TRY(place(Q.b_u_qslot, Ucap * 4, Q.u_qslot));
-    MLIP_TRY(place(Q.b_u_d, Ucap * 4, Q.u_d));
-    MLIP_TRY(place(Q.b_u_chunk_row, (size_t)(n_chunks + 1) * 4, Q.u_chunk_row));
-    if (scratch && scratch->failed()) return MLIP_OK;   // nothing may be launched on a failed carve; the caller reports it
-    int32_t *ucnt = Q.rowcnt, *lcnt = ucnt + Ncap;
-    if (N > 0) {
-        k_pair_rowcnt<<<blocks_for(N, 4), 256, 0, s>>>(N, v.row_ptr, v.mirror, ucnt, lcnt);
+    for (int p = 0; p < P; ++p) {
+        SlabView &v = views[p];
+        PairGraph &Q = v.pairs;
+        Q.valid = false;
+        const int64_t E = v.n_edges_owned, N = v.n_owned;
+        // every pair of two owned-row edges has one upper edge; an owned-row edge from a ghost sender is an upper edge,
+        // and the ghost rows hold exactly the reverse edges of those
+        const int64_t n_ghost_edges = v.n_edges - v.n_edges_owned;
+        Q.n_upper = (E - n_ghost_edges) / 2 + n_ghost_edges;
+        Q.n_lower = E - Q.n_upper;
+        const size_t Ncap = (size_t)std::max<int64_t>(N, 1), Ecap = (size_t)std::max<int64_t>(E, 1);
+        const size_t Ucap = (size_t)std::max<int64_t>(Q.n_upper, 1);
+        MLIP_TRY(place(Q.b_u_row_ptr, (Ncap + 1) * 8, Q.u_row_ptr));
+        MLIP_TRY(place(Q.b_wslot, Ecap * 4, Q.wslot));
+        MLIP_TRY(place(Q.b_u_senders, Ucap * 4, Q.u_senders));
+        MLIP_TRY(place(Q.b_u_recv, Ucap * 4, Q.u_recv));
+        MLIP_TRY(place(Q.b_u_eid, Ucap * 4, Q.u_eid));
+        MLIP_TRY(place(Q.b_u_mirror, Ucap * 4, Q.u_mirror));
+        MLIP_TRY(place(Q.b_u_d, Ucap * 4, Q.u_d));
+        MLIP_TRY(place(Q.b_u_chunk_row, (size_t)(chunks_of(Q.n_upper) + 1) * 4, Q.u_chunk_row));
+    }
+    // flags and their scan, kPairBatch partitions at a time (their edges one after another)
+    for (int p0 = 0; p0 < P; p0 += kPairBatch) {
+        PairBatch b{};
+        b.n = std::min(kPairBatch, P - p0);
+        b.row_start[0] = b.edge_start[0] = b.chunk_start[0] = 0;
+        for (int q = 0; q < kPairBatch; ++q) {
+            if (q >= b.n) {
+                b.row_start[q + 1] = b.row_start[q];
+                b.edge_start[q + 1] = b.edge_start[q];
+                b.chunk_start[q + 1] = b.chunk_start[q];
+                continue;
+            }
+            SlabView &v = views[p0 + q];
+            PairGraph &Q = v.pairs;
+            PairArgs &a = b.s[q];
+            a.n_rows = v.n_owned;
+            a.n_edges_owned = v.n_edges_owned;
+            a.n_chunks = chunks_of(Q.n_upper);
+            a.row_ptr = v.row_ptr;
+            a.senders = v.senders;
+            a.recv = v.recv;
+            a.mirror = v.mirror;
+            a.d = v.d;
+            a.u_row_ptr = Q.u_row_ptr;
+            a.wslot = Q.wslot;
+            a.u_senders = Q.u_senders;
+            a.u_recv = Q.u_recv;
+            a.u_eid = Q.u_eid;
+            a.u_mirror = Q.u_mirror;
+            a.u_chunk_row = Q.u_chunk_row;
+            a.u_d = Q.u_d;
+            b.row_start[q + 1] = b.row_start[q] + v.n_owned;
+            b.edge_start[q + 1] = b.edge_start[q] + v.n_edges_owned;
+            b.chunk_start[q + 1] = b.chunk_start[q] + a.n_chunks;
+        }
+        const int64_t edges = b.edge_start[b.n], rows = b.row_start[b.n];
+        if (edges >= ((int64_t)1 << 31)) {
+            set_error("more than 2^31 edges in %d partitions", b.n);
+            return MLIP_EINVAL;
+        }
+        int32_t *flag = nullptr, *scan = nullptr;
+        MLIP_TRY(place(g->pair_cnt, (size_t)(edges + 1) * 4, flag));
+        MLIP_TRY(place(g->pair_scan, (size_t)(edges + 1) * 4, scan));
+        if (scratch && scratch->failed()) return MLIP_OK;   // nothing may be launched on a failed carve; the caller reports it
+        if (edges > 0) {
+            k_pair_flag<<<blocks_for(edges, 256), 256, 0, s>>>(b, flag);
+            MLIP_HIP(hipGetLastError());
+        }
+        MLIP_TRY(scan_i32_to_i32(flag, scan, edges, g->scan_tmp, s));
+        if (edges > 0) {
+            k_pair_fill<<<blocks_for(edges, 256), 256, 0, s>>>(b, scan);
+            MLIP_HIP(hipGetLastError());
+        }
+        k_pair_rowptr<<<blocks_for(rows + b.n, 256), 256, 0, s>>>(b, scan);
+        MLIP_HIP(hipGetLastError());
+        k_pair_chunks<<<blocks_for(b.chunk_start[b.n] + b.n, 256), 256, 0, s>>>(b);
         MLIP_HIP(hipGetLastError());
     }
-    MLIP_TRY(scan_i32_to_i64(ucnt, Q.u_row_ptr, N, g->scan_tmp, s));
-    MLIP_TRY(scan_i32_to_i64(lcnt, Q.l_row_ptr, N, g->scan_tmp, s));
-    if (N > 0) {
-        k_pair_fill<<<blocks_for(N, 4), 256, 0, s>>>(N, v.row_ptr, v.senders, v.mirror, v.d, Q.u_row_ptr, Q.l_row_ptr, Q.cidx,
-                                                     Q.u_senders, Q.u_recv, Q.u_eid, Q.u_mirror, Q.u_d);
-        MLIP_HIP(hipGetLastError());
-    }
-    if (E > 0) {
-        k_pair_slots<<<blocks_for(E, 256), 256, 0, s>>>(E, v.mirror, Q.cidx, Q.wslot, Q.u_qslot);
-        MLIP_HIP(hipGetLastError());
-    }
-    k_chunk_rows_of<<<blocks_for(n_chunks + 1, 256), 256, 0, s>>>(N, n_chunks, Q.u_row_ptr, Q.u_chunk_row);
-    MLIP_HIP(hipGetLastError());
-    Q.valid = (scratch == nullptr);   // arrays in a borrowed block do not outlive the call
+    for (int p = 0; p < P; ++p) views[p].pairs.valid = (scratch == nullptr);   // arrays in a borrowed block do not outlive the call
     return MLIP_OK;
 }
 

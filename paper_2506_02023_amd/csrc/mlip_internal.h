@@ -129,14 +129,11 @@ struct PairGraph {
     bool valid = false;
     int64_t n_upper = 0, n_lower = 0;
     // grow-only buffers behind the pointers below (unused when the arrays are carved from a caller-independent block)
-    DevBuf b_rowcnt, b_u_row_ptr, b_l_row_ptr, b_cidx, b_wslot, b_u_senders, b_u_recv, b_u_eid, b_u_mirror, b_u_qslot, b_u_d,
-        b_u_chunk_row;
-    int32_t *rowcnt = nullptr;                        // [2][n_owned] upper / lower edges per row (scratch)
-    int64_t *u_row_ptr = nullptr, *l_row_ptr = nullptr;   // [n_owned + 1]
-    int32_t *cidx = nullptr;                          // [E_owned] index of an edge within its class (upper or lower)
+    DevBuf b_u_row_ptr, b_wslot, b_u_senders, b_u_recv, b_u_eid, b_u_mirror, b_u_d, b_u_chunk_row;
+    int64_t *u_row_ptr = nullptr;                     // [n_owned + 1]
     int32_t *wslot = nullptr;                         // [E_owned] upper index of the edge's pair
-    // [n_upper]: sender row, receiver row, edge, reverse edge, lower index of the reverse edge (-1: it lies in a ghost row)
-    int32_t *u_senders = nullptr, *u_recv = nullptr, *u_eid = nullptr, *u_mirror = nullptr, *u_qslot = nullptr;
+    // [n_upper]: sender row, receiver row, edge, reverse edge
+    int32_t *u_senders = nullptr, *u_recv = nullptr, *u_eid = nullptr, *u_mirror = nullptr;
     float *u_d = nullptr;                             // [n_upper]
     int32_t *u_chunk_row = nullptr;                   // [chunks_of(n_upper) + 1]
 };
@@ -227,6 +224,7 @@ struct mlip_graph {
     mlip::SlabView whole;
     // forward scratch shared by all views
     mlip::DevBuf wpack, energy_part;
+    mlip::DevBuf pair_cnt, pair_scan;   // upper-edge flags over the partitions' edges and their scan (scratch)
     mlip::DevBuf work;        // work counters of the edge kernels: one set of 8 per launch of a call, zeroed per call
     int32_t *work_ptr = nullptr;
     int work_next = 0;        // launches that have taken their counters in the current call
@@ -252,9 +250,9 @@ int forward_impl(mlip_graph *g, const mlip_weights_t *w, int32_t mode, double *e
 int unpack_shifts(const mlip_graph *g, int32_t *out);
 // bond list of one partition for cutoff r_bond (kept until the graph is rebuilt or r_bond changes); synchronises
 int build_bonds_impl(mlip_graph *g, SlabView &v, double r_bond, int p_envelope);
-// Upper / lower split of a view's owned-row edges (PairGraph); does nothing if it is valid.  With a block to carve from,
+// Upper / lower split of the views' owned-row edges (PairGraph), all views in the same launches; does nothing if all are valid.  With a block to carve from,
 // the arrays are taken from it (and the caller invalidates the structure when the block is given up).
-int build_pairs_impl(mlip_graph *g, SlabView &v, Carver *scratch);
+int build_pairs_impl(mlip_graph *g, SlabView *views, int n_views, Carver *scratch);
 int forward_bonds_impl(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t *bw, int32_t mode,
                        double *energy, float *forces, float *atom_energy);
 

@@ -271,7 +271,7 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
     const bool upper = kUpperGraphs && prec == kPrecF32;
     if (upper) {
         prof_begin(g, MLIP_PROF_GRAPH);
-        for (int p = 0; p < P; ++p) MLIP_TRY(build_pairs_impl(g, views[p], scratch));
+        MLIP_TRY(build_pairs_impl(g, views, P, scratch));
         prof_end(g);
     }
     int64_t n_parts = 0;
@@ -759,13 +759,15 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
             const int kind = upper ? kEdgeBwdUpper : kEdgeBwd;
             MLIP_TRY(prec == kPrecBf16 ? (launch_edge<F, kPrecBf16>(g, eb, kind))
                      : prec == kPrecF16x3 ? (launch_edge<F, kPrecF16x3>(g, eb, kind)) : (launch_edge<F, kPrecF32>(g, eb, kind)));
-            if (upper && need_gbar) {   // second pass: the rows' lower edges, from what their pairs' upper edges handed over
+            prof_end(g);
+            if (upper && need_gbar) {   // second pass: the lower edges' terms of the rows' sums
+                prof_begin(g, MLIP_PROF_EDGE_BWD_LOWER);
                 const SmallBatch sb = small_batch(p0, U_OWNED, l);
                 if (sb.start[sb.n] > 0)
                     k_edge_lower<F, true><<<blocks_for(sb.start[sb.n], 4), 256, 0, s>>>(sb);
                 MLIP_HIP(hipGetLastError());
+                prof_end(g);
             }
-            prof_end(g);
         }
         if (any_bonds) {   // bond term: its share of gbar; this layer's abar is kept for the bonds' own reverse step
             prof_begin(g, MLIP_PROF_BOND);

@@ -53,7 +53,7 @@ def _row(label, r):
     pr = r["prof"]
     return (f"| {label} | {r['N']:,} | {r['E']:,} | {r['E'] / r['N']:.1f} | {r['ms']:.2f} | {r['N'] / r['ms'] / 1e3:.2f} | "
             f"{r['E'] / r['ms'] / 1e6:.3f} | {r['ms'] * 1e3 / r['N']:.4f} | {pr['graph']:.2f} | "
-            f"{pr['edge_fwd'] + pr['edge_fwd_lower'] + pr['edge_bwd']:.2f} | {pr['node']:.2f} | {pr['ghost']:.2f} |")
+            f"{pr['edge_fwd'] + pr['edge_fwd_lower'] + pr['edge_bwd'] + pr['edge_bwd_lower']:.2f} | {pr['node']:.2f} | {pr['ghost']:.2f} |")
 
 
 _HEAD = ("| case | atoms | edges | edges/atom | ms/step | M atoms/s | G edges/s | us/atom | graph ms | edge ms | node ms | "
@@ -116,7 +116,7 @@ def main():
             r = _time_case(np.ascontiguousarray(pos[perm]), cell, np.ascontiguousarray(sp[perm]),
                            wl.rmp_weights(8, 64, 3, seed), wl.R_CUT, wl.P_ENVELOPE, 8, args.steps)
             print(_row("lattice order" if not B else f"blocks of {B}^3 cells", r) +
-                  f" edge fwd {r['prof']['edge_fwd'] + r['prof']['edge_fwd_lower']:.2f} / bwd {r['prof']['edge_bwd']:.2f} ms", flush=True)
+                  f" edge fwd {r['prof']['edge_fwd'] + r['prof']['edge_fwd_lower']:.2f} / bwd {r['prof']['edge_bwd'] + r['prof']['edge_bwd_lower']:.2f} ms", flush=True)
     if "size" in which:
         print("\n### System size, F = 64, L = 3, 8 slabs\n\n" + _HEAD)
         for cells in (10, 20, 30, 40, 50, 63, 80):

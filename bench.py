@@ -46,8 +46,10 @@ def flops_bwd_edge(F, K=8):
 # WRITE_SIZE)
 TRAFFIC_SOURCE = ("profiled constant, not measured by this run: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this kernel on "
                   "this workload, profiles/edge_traffic_configs3_8slabs.md")
-TRAFFIC_BWD_LAUNCH_BYTES = (12288995 * 1.9976 + 998063) * 1024
-TRAFFIC_FWD_LAUNCH_BYTES = (1407226 * 1.9976 + 6368325) * 1024   # first pass of the two-pass forward step
+TRAFFIC_BWD_LAUNCH_BYTES = (6197698 * 1.9975 + 1003845) * 1024         # k_edge_bwd on the upper-edge graphs
+TRAFFIC_FWD_LAUNCH_BYTES = (1372153 * 1.9975 + 6367676) * 1024         # k_edge_fwd on the upper-edge graphs
+TRAFFIC_FWD_LOWER_LAUNCH_BYTES = (4075993 * 1.9975 + 250047) * 1024    # k_edge_lower, forward
+TRAFFIC_BWD_LOWER_LAUNCH_BYTES = (4076407 * 1.9975 + 250047) * 1024    # k_edge_lower, reverse
 
 
 # fp32 vector peak that applies to this build: 256 CUs x 4 SIMDs x 16 lanes x 2 flop per FMA x 2.4 GHz = 78.6 TFLOP/s.
@@ -226,7 +228,8 @@ def main():
     roof_lower = {}
     if two_pass:   # bound by their row traffic; compulsory bytes: per lower edge the kept filter values (read once), per
                    # atom the row that is gathered (once if the caches were perfect) and the sum (read, written)
-        for group, what in (("edge_fwd_lower", "forward"), ("edge_bwd_lower", "reverse")):
+        for group, what, traffic in (("edge_fwd_lower", "forward", TRAFFIC_FWD_LOWER_LAUNCH_BYTES),
+                                     ("edge_bwd_lower", "reverse", TRAFFIC_BWD_LOWER_LAUNCH_BYTES)):
             ms, n = prof[group]
             if n == 0:
                 continue
@@ -235,7 +238,9 @@ def main():
             ach = per_launch / (avg_ms * 1e-3) / 1e9 if avg_ms > 0 else 0.0
             roof_lower[group] = {"kernel": f"k_edge_lower<{F}> ({what} edge step, second pass: lower edges)", "bound": "hbm",
                                  "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS,
-                                 "traffic": None, "avg_launch_ms": avg_ms, "launches": int(n),
+                                 "traffic": traffic if default_workload else None,
+                                 "traffic_source": TRAFFIC_SOURCE if default_workload else None,
+                                 "avg_launch_ms": avg_ms, "launches": int(n),
                                  "bytes_per_launch": per_launch, "ms_per_step": ms / args.steps}
     roof_trip = {}
     if three_body:

@@ -161,17 +161,8 @@ int node_pass(mlip_graph *g, SlabView *views, int P, const float *P1, const floa
 constexpr int kWorkLaunches = 2 * 8 * (64 / kBatch);
 
 // The reverse edge kernel the library runs is the one whose wavefronts alternate between the two phases.  Building
-// with -DMLIP_BWD_ROLES selects the variant with specialised wavefronts instead (same results; measured slower, kept
-// for that experiment; it has no form for the upper-edge graphs, so such a build runs every mode on the full edge lists).
-#ifdef MLIP_BWD_ROLES
-constexpr bool kUpperGraphs = false;
-template <int F, int PREC, bool COMPACT> struct BwdKernel {
-    static constexpr int threads = (kStreamWaves + kDenseWaves) * 64, item_waves = kStreamWaves;
-    static constexpr size_t lds = BwdRolesLds<F>::bytes;
-    static const void *fn() { return reinterpret_cast<const void *>(&k_edge_bwd_roles<F, PREC>); }
-    static void launch(unsigned blocks, hipStream_t s, const EdgeBatch &b) { k_edge_bwd_roles<F, PREC><<<blocks, threads, lds, s>>>(b); }
-};
-#else
+// with -DMLIP_BWD_SIMD runs the fp32 mode's launches on the upper-edge graphs with the variant whose phases sit on
+// different SIMDs instead (same results; measured slightly slower, kept for that experiment).
 constexpr bool kUpperGraphs = true;
 template <int F, int PREC, bool COMPACT> struct BwdKernel {
     static constexpr int threads = kBwdWaves * 64, item_waves = kBwdWaves;
@@ -181,6 +172,13 @@ template <int F, int PREC, bool COMPACT> struct BwdKernel {
     {
         k_edge_bwd<F, PREC, COMPACT><<<blocks, threads, lds, s>>>(b);
     }
+};
+#ifdef MLIP_BWD_SIMD
+template <int F> struct BwdKernel<F, kPrecF32, true> {
+    static constexpr int threads = kSimdWaves * 64, item_waves = kSimdStream;
+    static constexpr size_t lds = BwdSimdLds<F>::bytes;
+    static const void *fn() { return reinterpret_cast<const void *>(&k_edge_bwd_simd<F>); }
+    static void launch(unsigned blocks, hipStream_t s, const EdgeBatch &b) { k_edge_bwd_simd<F><<<blocks, threads, lds, s>>>(b); }
 };
 #endif
 

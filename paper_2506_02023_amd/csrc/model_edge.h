@@ -653,70 +653,101 @@ __global__ void __launch_bounds__(kBwdWaves * 64, kBwdWaves == 4 ? 2 : 1) k_edge
 }
 
 
-#ifdef MLIP_BWD_ROLES
-// ---- Reverse edge step with specialised wavefronts (an experiment: compiled only with -DMLIP_BWD_ROLES)
+#ifdef MLIP_BWD_SIMD
+// ---- Reverse edge step on upper-edge graphs with the two phases on different SIMDs (fp32 MFMA; an experiment:
+// compiled and used only with -DMLIP_BWD_SIMD)
 //
-// The same two phases, but no wavefront alternates between them: of the 12 wavefronts of a block (one block per
-// compute unit, three wavefronts per SIMD) eight stream (phase 1) and four do the dense work (phase 2) of the pairs
-// that "their" two streaming wavefronts queued.  The idea: the streaming phase waits for memory and needs a
-// quarter of the vector pipeline, the dense phase is bound by the MFMA pipeline and touches no memory but its
-// results, so side by side they should overlap.  Measured, they do not: 5.95 ms per launch against 4.67 ms for the
-// alternating kernel on the 1M-atom benchmark (6.05 ms with four streaming wavefronts and full tiles).  While a
-// dense wavefront issues its chain of 64-cycle fp32 MFMAs, every vector instruction of the streaming wavefronts
-// on that SIMD (about 150 per step: readlanes, address arithmetic, the products) waits for the pipeline that the
-// two kinds of instruction share.
+// fp32 MFMA and vector instructions share one pipeline per SIMD, and an MFMA holds it for 64 cycles: in the kernel above,
+// whose wavefronts alternate between the phases, a streaming wavefront crawls while the other wavefront of its SIMD
+// multiplies, and the two phases' times add.  Wavefronts on DIFFERENT SIMDs do not disturb each other (micro-benchmark
+// microbench/simd_roles.hip: row gathers on one SIMD beside MFMA chains on the other three run in the time of the longer
+// of the two).  Here one block of 12 wavefronts runs per compute unit, three per SIMD.  Every wavefront reads the SIMD
+// it was placed on from the hardware id register; the three wavefronts of one SIMD stream (phase 1 above, one ring of
+// queued pairs each), two wavefronts on each other SIMD do the dense work (phase 2), the remaining three only attend the
+// barriers.  Results are identical to the alternating kernel's.  Measured on the 1M-atom benchmark: 3.70 ms per launch
+// against 3.56 ms.  The dense work alone would take about 3.0 ms on three SIMDs, but the three streaming wavefronts
+// alone take 2.98 ms: what a SIMD's register file can keep in flight with a step of loads ahead (3 x 52 rows) is too
+// little for the latency, a fourth streaming wavefront needs a 16-wave block (128 registers, and rings that no longer fit
+// the LDS), and with one round of buffering the two sides wait for each other's slowest.
 //
-// Hand-over: every streaming wavefront owns a ring of kRoleQueue slots in LDS (slot layout as above, plus the
-// partition index, since pairs of several partitions now share the ring).  All wavefronts of the block meet at one
-// barrier per round.  Before the barrier a streaming wavefront publishes how many pairs it has produced in all and
-// whether it is out of work; after it, every wavefront reads the four published pairs of numbers and derives from
-// them, by the same rule, how many pairs each dense wavefront takes in this round (kRoleTake as soon as that many
-// are there, the rest once the producer is done).  Because all derive the same numbers, nothing flows back from
-// the consumers, and all agree on the round after which everything is consumed: the loop bound of every
-// wavefront, so no barrier is left waiting.  A streaming wavefront ends its round once kRoleTake pairs are pending
-// beyond what the consumer is known to take; slots being read (at most kRoleTake) plus pending ones (less than
-// kRoleTake + kStep) plus the slot a step writes speculatively stay within the ring.
-// The published numbers alternate between two sets, so a set is rewritten only after a barrier that every reader of
-// its previous contents has passed.
-constexpr int kStreamWaves = 8;   // streaming wavefronts per block (two per SIMD), one ring each
-constexpr int kDenseWaves = 4;    // dense wavefronts per block (one per SIMD); each serves kStreamWaves / kDenseWaves rings
-constexpr int kRoleTake = 24;     // pairs a dense step takes from a ring (of the MFMA tile's 32 columns: the rings of a
-                                  // block must fit the LDS, and this is what bounds their length)
-constexpr int kRoleQueue = 65;    // slots of a ring
-static_assert(kRoleQueue >= 2 * kRoleTake + kStep + 1, "ring too small for the hand-over protocol");
-static_assert(kStreamWaves % kDenseWaves == 0, "every dense wavefront serves the same number of rings");
+// Hand-over: every streaming wavefront owns a ring of kSimdRing slots in LDS (slot layout as above, plus the partition
+// index, since pairs of several partitions share a ring).  All wavefronts of the block meet at one barrier per round.
+// Before the barrier a streaming wavefront publishes how many pairs it has produced in all and whether it is out of
+// work; after it, every wavefront reads the published numbers and derives from them, by the same rule, how many pairs
+// every ring hands out in this round (kSimdTake as soon as that many are there, the rest once the producer is done):
+// a 32-pair tile for each of the ring's two dense wavefronts.  Because all derive the same numbers, nothing flows back
+// from the consumers, and all agree on the round after which everything is consumed: the loop bound of every
+// wavefront, so no barrier is left waiting.  A streaming wavefront ends its round once kSimdTake pairs are pending
+// beyond what the consumers are known to take; slots being read (at most kSimdTake) plus pending ones (less than
+// kSimdTake + kStep) plus the slot a step writes speculatively stay within the ring.  The published numbers alternate
+// between two sets, so a set is rewritten only after a barrier that every reader of its previous contents has passed.
+constexpr int kSimdWaves = 12;    // wavefronts per block: three per SIMD
+constexpr int kSimdStream = 3;    // streaming wavefronts, one ring each
+constexpr int kSimdDense = 6;     // dense wavefronts; ring q is emptied by the dense wavefronts q and q + kSimdStream
+constexpr int kSimdTake = 64;     // pairs a ring hands out per round: one 32-pair tile for each of its two consumers
+constexpr int kSimdRing = 2 * kSimdTake + kStep + 1;   // slots of a ring
+static_assert(kSimdDense == 2 * kSimdStream && kSimdTake == 64, "two 32-pair tiles per ring and round");
 
-template <int F> struct BwdRolesLds {
+template <int F> struct BwdSimdLds {
     using D = Dims<F>;
-    static constexpr int kQueuesAt = D::PACKF + D::PACK1;                       // floats
-    static constexpr int kPubAt = kQueuesAt + kStreamWaves * kRoleQueue * D::FS;   // int32 [2][kStreamWaves][2]
-    static constexpr int kTabAt = kPubAt + 4 * kStreamWaves;                       // float* [kBatch], 8-byte aligned
+    static constexpr int kQueuesAt = D::PACKF + D::PACK1;                          // floats
+    static constexpr int kPubAt = kQueuesAt + kSimdStream * kSimdRing * D::FS;     // int32 [2][kSimdStream][2]
+    static constexpr int kSimdAt = kPubAt + 4 * kSimdStream;                       // int32 [kSimdWaves]
+    static constexpr int kTabAt = (kSimdAt + kSimdWaves + 1) & ~1;                 // float* [kBatch], 8-byte aligned
     static constexpr size_t bytes = sizeof(float) * kTabAt + sizeof(float *) * kBatch;
-    static_assert(kTabAt % 2 == 0, "pointer table must be 8-byte aligned");
 };
 
-template <int F, int PREC>
-__global__ void __launch_bounds__((kStreamWaves + kDenseWaves) * 64, 1) k_edge_bwd_roles(EdgeBatch B)
+template <int F>
+__global__ void __launch_bounds__(kSimdWaves * 64, 1) k_edge_bwd_simd(EdgeBatch B)
 {
     using D = Dims<F>;
-    using L = BwdRolesLds<F>;
+    using L = BwdSimdLds<F>;
     constexpr int FS = D::FS;
     constexpr int kRowBytes = F * 4;
-    constexpr int kThreads = (kStreamWaves + kDenseWaves) * 64;
+    constexpr int kThreads = kSimdWaves * 64;
     extern __shared__ float lds[];
     float *A2n = lds;
     float *A1l = A2n + D::PACKF;
     float *queues = lds + L::kQueuesAt;
     int32_t *pub = reinterpret_cast<int32_t *>(lds + L::kPubAt);
+    int32_t *simd_of = reinterpret_cast<int32_t *>(lds + L::kSimdAt);
     float **dsum_tab = reinterpret_cast<float **>(lds + L::kTabAt);
-    for (int i = threadIdx.x; i < (PREC == kPrecBf16 ? D::PACKF / 2 : D::PACKF); i += kThreads) A2n[i] = B.c.A2n[i];
-    for (int i = threadIdx.x; i < D::PACK1; i += kThreads) A1l[i] = B.c.A1[i];
-    if (threadIdx.x < 4 * kStreamWaves) pub[threadIdx.x] = 0;
-    if (threadIdx.x < kBatch) dsum_tab[threadIdx.x] = (threadIdx.x < B.n) ? B.s[threadIdx.x].dsum : nullptr;
-    __syncthreads();
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-    const bool streams = wave < kStreamWaves;
-    const int mine = streams ? wave : wave - kStreamWaves;   // streaming: the ring it fills; dense: the first ring it empties
+    // the SIMD this wavefront runs on: bits 5:4 of the hardware id register (HW_REG_HW_ID = 4, read whole)
+    const int simd = (int)((__builtin_amdgcn_s_getreg((31 << 11) | 4) >> 4) & 3u);
+    for (int i = threadIdx.x; i < D::PACKF; i += kThreads) A2n[i] = B.c.A2n[i];
+    for (int i = threadIdx.x; i < D::PACK1; i += kThreads) A1l[i] = B.c.A1[i];
+    if (threadIdx.x < 4 * kSimdStream) pub[threadIdx.x] = 0;
+    if (threadIdx.x < kBatch) dsum_tab[threadIdx.x] = (threadIdx.x < B.n) ? B.s[threadIdx.x].dsum : nullptr;
+    if (lane == 0) simd_of[wave] = simd;
+    __syncthreads();
+    // Roles, derived by every wavefront from the same table.  With three wavefronts on every SIMD (what the register
+    // budget of a 12-wave block allows at most, so what the hardware deals) the SIMD of wavefront 0 streams and the
+    // other three SIMDs run two dense wavefronts each, their third wavefront only attends the barriers.  Any other
+    // placement falls back to roles by wavefront index: the same results, the phases then share SIMDs.
+    enum { kStreams = 0, kDense = 1, kSpare = 2 };
+    int role, mine;   // mine: streaming: the ring it fills; dense: 0 .. kSimdDense - 1
+    {
+        int on[4] = {0, 0, 0, 0}, rank = 0;
+#pragma unroll
+        for (int w = 0; w < kSimdWaves; ++w) {
+            const int s = __builtin_amdgcn_readfirstlane(simd_of[w]);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) on[k] += (s == k) ? 1 : 0;
+            rank += (w < wave && s == simd) ? 1 : 0;
+        }
+        const int star = __builtin_amdgcn_readfirstlane(simd_of[0]);
+        const bool even = on[0] == 3 && on[1] == 3 && on[2] == 3 && on[3] == 3;
+        if (even) {
+            const int ord = simd - (simd > star ? 1 : 0);   // 0 .. 2 among the SIMDs that do not stream
+            role = (simd == star) ? kStreams : (rank < 2 ? kDense : kSpare);
+            mine = (simd == star) ? rank : ord * 2 + rank;
+        } else {
+            role = wave < kSimdStream ? kStreams : (wave < kSimdStream + kSimdDense ? kDense : kSpare);
+            mine = wave < kSimdStream ? wave : wave - kSimdStream;
+        }
+    }
+    const bool streams = role == kStreams;
     const int c32 = lane & 31;
     const int l16 = lane % kStep;
     const unsigned f = lane & (F - 1);
@@ -725,25 +756,25 @@ __global__ void __launch_bounds__((kStreamWaves + kDenseWaves) * 64, 1) k_edge_b
 
     // ---- the rounds' bookkeeping, identical in every wavefront
     int round = 0;
-    int consumed[kStreamWaves];   // pairs taken from every ring so far
-    int take[kStreamWaves];       // ... and in the current round
+    int consumed[kSimdStream];   // pairs taken from every ring so far
+    int take[kSimdStream];       // ... and in the current round
 #pragma unroll
-    for (int q = 0; q < kStreamWaves; ++q) consumed[q] = 0;
+    for (int q = 0; q < kSimdStream; ++q) consumed[q] = 0;
     int consumed_mine = 0;        // streaming: consumed[mine]
     // meets the other wavefronts; returns true if this round's takes empty every ring of a finished producer
     auto rendezvous = [&]() -> bool {
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // LDS writes done; loads in flight stay in flight
-        const int32_t *pb = pub + (round & 1) * (2 * kStreamWaves);   // (re-read: the barrier statement clobbers memory)
+        const int32_t *pb = pub + (round & 1) * (2 * kSimdStream);   // (re-read: the barrier statement clobbers memory)
         bool finished = true;
 #pragma unroll
-        for (int q = 0; q < kStreamWaves; ++q) {
+        for (int q = 0; q < kSimdStream; ++q) {
             const int produced = __builtin_amdgcn_readfirstlane(pb[2 * q]);
             const int done = __builtin_amdgcn_readfirstlane(pb[2 * q + 1]);
             const int avail = produced - consumed[q];
-            take[q] = (avail >= kRoleTake || done) ? min(avail, kRoleTake) : 0;
+            take[q] = (avail >= kSimdTake || done) ? min(avail, kSimdTake) : 0;
             consumed[q] += take[q];
             finished = finished && done && produced == consumed[q];
-            if (q == mine) consumed_mine = consumed[q];
+            if (streams && q == mine) consumed_mine = consumed[q];
         }
         ++round;
         return finished;
@@ -751,13 +782,16 @@ __global__ void __launch_bounds__((kStreamWaves + kDenseWaves) * 64, 1) k_edge_b
 
     if (!streams) {
         // ================================================================ dense wavefronts
-        constexpr int kRings = kStreamWaves / kDenseWaves;
-        int q_head[kRings];
-#pragma unroll
-        for (int j = 0; j < kRings; ++j) q_head[j] = 0;
+        // dense wavefront `mine` empties ring mine % kSimdStream as its (mine / kSimdStream)-th consumer: of the pairs
+        // a round hands out it takes the tile [32 j, 32 j + 32)
+        const int ring = mine % kSimdStream, part_j = mine / kSimdStream;
+        int q_head = 0;
         auto dense = [&](const float *Q, int head, int nval) {
+#ifdef MLIP_TIMING_SKIP_PAIR_PHASE
+            return;   // timing experiment only (results are wrong): the streaming wavefronts and the hand-over on their own
+#endif
             int slot = head + c32;
-            slot -= (slot >= kRoleQueue) ? kRoleQueue : 0;
+            slot -= (slot >= kSimdRing) ? kSimdRing : 0;
             const bool valid = c32 < nval;
             const int4 rec = *reinterpret_cast<const int4 *>(Q + slot * FS + F);   // e, m, d, partition
             const int32_t e2 = valid ? rec.x : 0, m2 = valid ? rec.y : 0;
@@ -786,12 +820,7 @@ __global__ void __launch_bounds__((kStreamWaves + kDenseWaves) * 64, 1) k_edge_b
                 }
             }
             f32x16 sb[D::NB];
-            if (PREC == kPrecBf16)   // sbar[k] = sum_f W2[k][f] wsym[f]
-                gemm_row_bf16<F>(reinterpret_cast<const __bf16 *>(A2n), Q + slot * FS, sb, lane);
-            else if (PREC == kPrecF16x3)
-                gemm_row_f16x3<F>(reinterpret_cast<const _Float16 *>(A2n), Q + slot * FS, sb, lane);
-            else
-                gemm_queue<F>(A2n, Q + slot * FS, sb, lane);
+            gemm_queue<F>(A2n, Q + slot * FS, sb, lane);   // sbar[k] = sum_f W2[k][f] wsym[f]
             float part = 0.f;
 #pragma unroll
             for (int bb = 0; bb < D::NB; ++bb)
@@ -811,17 +840,19 @@ __global__ void __launch_bounds__((kStreamWaves + kDenseWaves) * 64, 1) k_edge_b
         };
         for (;;) {
             const bool finished = rendezvous();
+            int taken = 0;
 #pragma unroll
-            for (int j = 0; j < kRings; ++j) {
-                int nval = 0;
-#pragma unroll
-                for (int q = 0; q < kStreamWaves; ++q)
-                    if (q == mine + j * kDenseWaves) nval = take[q];
+            for (int q = 0; q < kSimdStream; ++q)
+                if (q == ring) taken = take[q];
+            if (role == kDense) {
+                const int nval = min(taken - 32 * part_j, 32);
                 if (nval > 0) {
-                    dense(queues + (mine + j * kDenseWaves) * (kRoleQueue * FS), q_head[j], nval);
-                    q_head[j] += nval;
-                    q_head[j] -= (q_head[j] >= kRoleQueue) ? kRoleQueue : 0;
+                    int head = q_head + 32 * part_j;
+                    head -= (head >= kSimdRing) ? kSimdRing : 0;
+                    dense(queues + ring * (kSimdRing * FS), head, nval);
                 }
+                q_head += taken;
+                q_head -= (q_head >= kSimdRing) ? kSimdRing : 0;
             }
             if (finished) break;
         }
@@ -829,19 +860,19 @@ __global__ void __launch_bounds__((kStreamWaves + kDenseWaves) * 64, 1) k_edge_b
     }
 
     // ==================================================================== streaming wavefronts
-    float *Q = queues + mine * (kRoleQueue * FS);
+    float *Q = queues + mine * (kSimdRing * FS);
     char *Qf = reinterpret_cast<char *>(Q + f);
     int produced = 0;   // pairs queued so far
-    int q_tail = 0;     // produced % kRoleQueue
+    int q_tail = 0;     // produced % kSimdRing
     auto publish = [&](int done) {
         if (lane == 0) {
-            int32_t *pb = pub + (round & 1) * (2 * kStreamWaves) + 2 * mine;
+            int32_t *pb = pub + (round & 1) * (2 * kSimdStream) + 2 * mine;
             pb[0] = produced;
             pb[1] = done;
         }
     };
 
-    const ItemQueue items = edge_items(B.chunk_start[B.n], B.work, wave, kStreamWaves);
+    const ItemQueue items = edge_items(B.chunk_start[B.n], B.work, mine, kSimdStream);
     int64_t item = items.first;
     int32_t drawn = 0;
     for (int part = 0; part < B.n; ++part) {
@@ -865,7 +896,7 @@ __global__ void __launch_bounds__((kStreamWaves + kDenseWaves) * 64, 1) k_edge_b
     // Vector memory loads complete in order, so a stage may only contain loads and address arithmetic; anything
     // that consumes a loaded value belongs to a later stage.
     struct Ids {    // lane k (mod kStep) holds edge tb + k, clamped to the last edge of the work item
-        int32_t sj, rk, mk;
+        int32_t sj, rk, mk, ek;   // sender, receiver, and the indices of the reverse edge and of the edge in the full list
         float dk;
     };
     struct Step {
@@ -881,6 +912,7 @@ __global__ void __launch_bounds__((kStreamWaves + kDenseWaves) * 64, 1) k_edge_b
         I.rk = A.recv[e];
         I.mk = A.mirror[e];
         I.dk = A.d[e];
+        I.ek = A.eid[e];
     };
     auto load_step = [&](Step &S, const Ids &I, int32_t tb) {
         S.tb = tb;
@@ -889,31 +921,23 @@ __global__ void __launch_bounds__((kStreamWaves + kDenseWaves) * 64, 1) k_edge_b
         // every path through the pipeline then has the same number of loads in flight, which is what lets
         // the waits before the uses be partial ones.
         const int32_t sjo = I.sj * kRowBytes;
-        S.uppers = (uint32_t)__ballot(l16 < S.kmax && I.mk > tb + l16) & ((1u << kStep) - 1u);
+        S.uppers = (1u << S.kmax) - 1u;   // every edge of an upper-edge graph is the upper edge of its pair
         const int32_t row0 = __builtin_amdgcn_readfirstlane(I.rk);
         const int32_t rowl = __builtin_amdgcn_readlane(I.rk, max(S.kmax - 1, 0));
         S.ai0 = buffer_load_f32(a_rsrc, f * 4, row0 * kRowBytes, 0);
         S.gi0 = buffer_load_f32(g_rsrc, f * 4, row0 * kRowBytes, 0);
         S.ai1 = buffer_load_f32(a_rsrc, f * 4, rowl * kRowBytes, 0);
         S.gi1 = buffer_load_f32(g_rsrc, f * 4, rowl * kRowBytes, 0);
-        // w_e sits at the edge's own index or, with w_pairs, at the index of the pair's upper edge (a range of zero
-        // bytes reads 0: without gbar no w is needed).  With w_pairs the descriptor spans the partition's kept values
-        // (the host sets the flag only if they fit its 32-bit range) and a lower edge reads its reverse edge's row;
-        // an edge past the end then reads the row of the item's last edge, which goes into a sum nobody stores.
-        const bool w_pairs = C.w_pairs != 0;
-        const int32_t w_first = w_pairs ? 0 : tb;   // edge whose row the descriptor starts at
+        // w_e sits at the edge's own index in the upper-edge graph (a range of zero bytes reads 0: without gbar no w
+        // is needed)
         const __amdgpu_buffer_rsrc_t w_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-            A.wstore + (need_gbar ? (int64_t)w_first * F : 0), 0,
-            !need_gbar ? 0 : w_pairs ? (int)(uint32_t)(A.n_stored * kRowBytes) : S.kmax * kRowBytes, kBufferFlags);
-        // lane k: byte offset of edge k's row (unsigned: the kept values of a partition may span up to 4 GB)
-        const int32_t wro = (int32_t)((uint32_t)(w_pairs ? min(I.mk, tb + l16) : l16) * (uint32_t)kRowBytes);
+            A.wstore + (need_gbar ? (int64_t)tb * F : 0), 0, need_gbar ? S.kmax * kRowBytes : 0, kBufferFlags);
 #pragma unroll
         for (int k = 0; k < kStep; ++k) {
             const int32_t so = __builtin_amdgcn_readlane(sjo, k);
             S.av[k] = buffer_load_f32(a_rsrc, f * 4, so, 0);
             S.gv[k] = buffer_load_f32(g_rsrc, f * 4, so, 0);
-            S.wv[k] = buffer_load_f32_stream(w_rsrc, f * 4,
-                                             __builtin_amdgcn_readlane(wro, k));   // 0 outside the range
+            S.wv[k] = buffer_load_f32_stream(w_rsrc, f * 4, k * kRowBytes);   // 0 outside the range
         }
     };
     // rn_first: receiver of the first edge of the following step (r1 after the last step)
@@ -921,16 +945,16 @@ __global__ void __launch_bounds__((kStreamWaves + kDenseWaves) * 64, 1) k_edge_b
         if (S.kmax <= 0) return;
         const bool valid_l = l16 < S.kmax;
         const int32_t rk = valid_l ? I.rk : r1;
-        const int32_t e_l = S.tb + l16;
+        const int32_t e_l = I.ek;   // index in the full edge list
         // wave-uniform masks: bit k = edge k ends its row / edge k is the upper edge of its pair
         const int32_t up = __shfl(rk, l16 + 1, 64);
         const int32_t rnext = (l16 == kStep - 1) ? rn_first : up;
         const uint32_t ends = (uint32_t)__ballot(valid_l && rnext != rk) & ((1u << kStep) - 1u);
-        const bool upper_l = valid_l && I.mk > e_l;
+        const bool upper_l = valid_l;
         const uint32_t uppers = S.uppers;
         {   // records of the pairs queued by this step, all at once: slots follow q_tail in edge order
             int slot = q_tail + (int)__builtin_amdgcn_mbcnt_lo(uppers, 0u);   // upper edges before this lane's (lanes < kStep)
-            slot -= (slot >= kRoleQueue) ? kRoleQueue : 0;
+            slot -= (slot >= kSimdRing) ? kSimdRing : 0;
             if (upper_l && lane < kStep) {
                 float *rec = Q + slot * FS + F;
                 reinterpret_cast<int32_t *>(rec)[0] = e_l;
@@ -949,7 +973,7 @@ __global__ void __launch_bounds__((kStreamWaves + kDenseWaves) * 64, 1) k_edge_b
             // advances the slot, anything else is overwritten by the next edge
             *reinterpret_cast<float *>(Qf + q_off) = fmaf(ai, S.gv[k], S.av[k] * gi);
             q_off += (uppers & (1u << k)) ? FS * 4 : 0;
-            q_off = (q_off == kRoleQueue * FS * 4) ? 0 : q_off;
+            q_off = (q_off == kSimdRing * FS * 4) ? 0 : q_off;
             if (__builtin_expect((ends & (1u << k)) != 0, 0)) {   // unlikely: keeps the common path free of taken branches
                 const int32_t rrow = __builtin_amdgcn_readlane(rk, k);
                 const int32_t nrow = __builtin_amdgcn_readlane(rnext, k);
@@ -972,11 +996,11 @@ __global__ void __launch_bounds__((kStreamWaves + kDenseWaves) * 64, 1) k_edge_b
         const int n_new = __builtin_popcount(uppers);
         produced += n_new;
         q_tail += n_new;
-        q_tail -= (q_tail >= kRoleQueue) ? kRoleQueue : 0;
+        q_tail -= (q_tail >= kSimdRing) ? kSimdRing : 0;
     };
     // end of a round: enough pairs are pending beyond what the consumer is known to take
     auto maybe_round = [&]() {
-        if (produced - consumed_mine >= kRoleTake) {
+        if (produced - consumed_mine >= kSimdTake) {
             publish(0);
             rendezvous();
         }
@@ -1028,6 +1052,7 @@ __global__ void __launch_bounds__((kStreamWaves + kDenseWaves) * 64, 1) k_edge_b
         if (rendezvous()) break;
     }
 }
-#endif  // MLIP_BWD_ROLES
+
+#endif  // MLIP_BWD_SIMD
 
 #endif  // MLIP_MODEL_EDGE_H

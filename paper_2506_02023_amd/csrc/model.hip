@@ -233,6 +233,10 @@ template <int F, int PREC, bool COMPACT = false> int launch_edge(mlip_graph *g, 
     return MLIP_OK;
 }
 
+// Kept filter values shared by the two edges of a pair on the full edge lists: a lower edge reads its reverse edge's
+// row through one buffer descriptor, whose 32-bit range (less the largest offset a load adds) must span the partition.
+inline bool fits_pairs(const SlabView &v, int F) { return (int64_t)v.n_edges_owned * F * 4 < ((int64_t)1 << 32) - (1 << 20); }
+
 // bw != nullptr: the three-body variant
 template <int F>
 int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t *bw, int32_t mode, double *energy,
@@ -267,7 +271,15 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
     // both edges have the same length, hence bit for bit the same filter values), and row-wise kernels add the lower
     // edges' terms.  In the 16-bit product modes the matrix work is cheap and the full edge lists are faster.
     const bool upper = kUpperGraphs && prec == kPrecF32;
-    if (upper) {
+    // Their reverse step, though, streams three rows per edge whatever the precision: it runs on the upper-edge graphs in
+    // those modes too wherever the pairs share their kept filter values (fits_pairs below), which then stay where the
+    // forward step on the full lists put them, at the upper edges' own positions.
+    bool upper_bwd = upper;
+    if (kUpperGraphs && prec != kPrecF32 && L > 1) {
+        upper_bwd = true;
+        for (int p = 0; p < P; ++p) upper_bwd = upper_bwd && fits_pairs(views[p], F);
+    }
+    if (upper_bwd) {
         prof_begin(g, MLIP_PROF_GRAPH);
         MLIP_TRY(build_pairs_impl(g, views, P, scratch));
         prof_end(g);
@@ -563,7 +575,7 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
     auto w_pairs = [&](int p0, int n) {
         if (upper || prec == kPrecF32) return 0;   // upper-edge graphs keep one row per pair by construction
         for (int q = 0; q < n; ++q)
-            if ((int64_t)views[p0 + q].n_edges_owned * F * 4 >= ((int64_t)1 << 32) - (1 << 20)) return 0;
+            if (!fits_pairs(views[p0 + q], F)) return 0;
         return 1;
     };
     auto gslice = [&](SlabView &v, int l) { return v.ws.g + (size_t)l * (size_t)v.n_local * F; };
@@ -740,7 +752,7 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
                 ea.mirror = v.mirror;
                 ea.wstore = need_gbar ? wslice(v, l) : nullptr;
                 ea.n_stored = need_gbar ? v.n_edges_owned : 0;
-                if (upper) {   // on the partition's upper-edge graph
+                if (upper_bwd) {   // on the partition's upper-edge graph
                     const PairGraph &Q = v.pairs;
                     ea.n_chunks = chunks_of(Q.n_upper);
                     ea.chunk_row = Q.u_chunk_row;
@@ -750,15 +762,17 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
                     ea.d = Q.u_d;
                     ea.mirror = Q.u_mirror;
                     ea.eid = Q.u_eid;
-                    ea.n_stored = need_gbar ? Q.n_upper : 0;
+                    // kept values in the order of the upper-edge graph, or (16-bit modes) at the upper edges' positions
+                    // in the full list
+                    if (upper) ea.n_stored = need_gbar ? Q.n_upper : 0;
                 }
             }
             prof_begin(g, MLIP_PROF_EDGE_BWD);
-            const int kind = upper ? kEdgeBwdUpper : kEdgeBwd;
+            const int kind = upper_bwd ? kEdgeBwdUpper : kEdgeBwd;
             MLIP_TRY(prec == kPrecBf16 ? (launch_edge<F, kPrecBf16>(g, eb, kind))
                      : prec == kPrecF16x3 ? (launch_edge<F, kPrecF16x3>(g, eb, kind)) : (launch_edge<F, kPrecF32>(g, eb, kind)));
             prof_end(g);
-            if (upper && need_gbar) {   // second pass: the lower edges' terms of the rows' sums
+            if (upper_bwd && need_gbar) {   // second pass: the lower edges' terms of the rows' sums
                 prof_begin(g, MLIP_PROF_EDGE_BWD_LOWER);
                 const SmallBatch sb = small_batch(p0, U_OWNED, l);
                 if (sb.start[sb.n] > 0)

@@ -444,17 +444,19 @@ __global__ void __launch_bounds__(kBwdWaves * 64, kBwdWaves == 4 ? 2 : 1) k_edge
         S.gi0 = buffer_load_f32(g_rsrc, f * 4, row0 * kRowBytes, 0);
         S.ai1 = buffer_load_f32(a_rsrc, f * 4, rowl * kRowBytes, 0);
         S.gi1 = buffer_load_f32(g_rsrc, f * 4, rowl * kRowBytes, 0);
-        // w_e sits at the edge's own index or, with w_pairs, at the index of the pair's upper edge (a range of zero
-        // bytes reads 0: without gbar no w is needed).  With w_pairs the descriptor spans the partition's kept values
-        // (the host sets the flag only if they fit its 32-bit range) and a lower edge reads its reverse edge's row;
-        // an edge past the end then reads the row of the item's last edge, which goes into a sum nobody stores.
+        // w_e sits at the edge's own index or, with w_pairs, at the index of the pair's upper edge in the full list (a
+        // range of zero bytes reads 0: without gbar no w is needed).  With w_pairs the descriptor spans the partition's
+        // kept values (the host sets the flag only if they fit its 32-bit range) and a lower edge reads its reverse
+        // edge's row, an edge of an upper-edge graph the row at its index in the full list; an edge past the end then
+        // reads the row of the item's last edge, which goes into a sum nobody stores.
         const bool w_pairs = C.w_pairs != 0;
         const int32_t w_first = w_pairs ? 0 : tb;   // edge whose row the descriptor starts at
         const __amdgpu_buffer_rsrc_t w_rsrc = __builtin_amdgcn_make_buffer_rsrc(
             A.wstore + (need_gbar ? (int64_t)w_first * F : 0), 0,
             !need_gbar ? 0 : w_pairs ? (int)(uint32_t)(A.n_stored * kRowBytes) : S.kmax * kRowBytes, kBufferFlags);
         // lane k: byte offset of edge k's row (unsigned: the kept values of a partition may span up to 4 GB)
-        const int32_t wro = (int32_t)((uint32_t)(w_pairs ? min(I.mk, tb + l16) : l16) * (uint32_t)kRowBytes);
+        const int32_t wro =
+            (int32_t)((uint32_t)(w_pairs ? (COMPACT ? I.ek : min(I.mk, tb + l16)) : l16) * (uint32_t)kRowBytes);
 #pragma unroll
         for (int k = 0; k < kStep; ++k) {
             const int32_t so = __builtin_amdgcn_readlane(sjo, k);

@@ -293,7 +293,7 @@ __global__ void __launch_bounds__(256) k_edge_lower(SmallBatch B)
     for (int64_t eb = e0; eb < e1; eb += 64) {
         const int64_t el = min(eb + lane, e1 - 1);
         const int32_t jl = A.senders[el], ml = A.mirror[el];
-        const int32_t sl = A.wslot[el];   // where the pair's filter values are kept
+        const int32_t sl = A.wslot ? A.wslot[el] : ml;   // where the pair's filter values are kept (else: at the upper edge)
         unsigned long long mask = __ballot(eb + lane < e1 && (int64_t)ml < el);   // the lower edges among these 64
         while (mask != 0) {
             float wv[kLowerChunk], gv[kLowerChunk];

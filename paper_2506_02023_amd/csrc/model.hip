@@ -269,10 +269,10 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
     };
     // With fp32 MFMA the edge kernels run on the partitions' upper-edge graphs (one edge per edge / reverse-edge pair:
     // both edges have the same length, hence bit for bit the same filter values), and row-wise kernels add the lower
-    // edges' terms.  In the 16-bit product modes the matrix work is cheap and the full edge lists are faster.
+    // edges' terms.  In the 16-bit product modes the matrix work is cheap and the forward step is faster on the full edge lists.
     const bool upper = kUpperGraphs && prec == kPrecF32;
     // Their reverse step, though, streams three rows per edge whatever the precision: it runs on the upper-edge graphs in
-    // those modes too wherever the pairs share their kept filter values (fits_pairs below), which then stay where the
+    // those modes too wherever the pairs share their kept filter values (fits_pairs), which then stay where the
     // forward step on the full lists put them, at the upper edges' own positions.
     bool upper_bwd = upper;
     if (kUpperGraphs && prec != kPrecF32 && L > 1) {

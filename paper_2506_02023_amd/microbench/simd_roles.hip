@@ -11,7 +11,8 @@
 // ahead, two multiply-adds and an LDS store per row; 23 edges per row of a 100^3 lattice, work handed out in items of 1024
 // edges.  Dense = 80 v_mfma_f32_32x32x2_f32 per 32 edges, handed out in groups of 8 tiles.  The two kinds of wavefront
 // do not exchange data: the benchmark shows only whether their times overlap.  It also prints on which SIMD the
-// wavefronts of a block land.
+// wavefronts of a block land, and repeats the shared-SIMD case with the dense work as v_mfma_f32_16x16x4_f32 (twice as
+// many instructions of half the duration) and with the streaming wavefronts at a raised issue priority (s_setprio 3).
 //
 // Build and run (one MI355X):
 //   hipcc --offload-arch=gfx950 -O3 -Xclang -target-feature -Xclang -packed-fp32-ops \
@@ -25,6 +26,7 @@
 #include <vector>
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr int kF = 64, kRowBytes = kF * 4, kStep = 16, kChunk = 1024;
 constexpr int kBufferFlags = 0x00020000;
 #define CHECK(x) do { hipError_t e_ = (x); if (e_ != hipSuccess) { std::fprintf(stderr, "%s: %s\n", #x, hipGetErrorString(e_)); std::exit(1); } } while (0)
@@ -36,13 +38,13 @@ struct Args {
     unsigned long long *counters;   // [0] next chunk, [1] next tile group
     uint32_t *hwid;                 // [block][wave]
     int64_t n_rows, n_edges;
-    int what;                       // bit 0: streaming runs, bit 1: dense runs
+    int what;                       // bit 0: streaming runs, bit 1: dense runs, bit 2: streaming wavefronts raise their priority
     int stream_simds;               // mode 0: SIMDs >= 4 - stream_simds stream
 };
 
 // MODE 0: role by SIMD id; MODE 1: role by wave index (the first 4 * stream_simds... waves with (wave & 3) spread) -> waves
 // 0 .. 4*stream_simds-1 stream (one per SIMD each round if waves are dealt round-robin)
-template <int MODE>
+template <int MODE, int SMALL>
 __global__ void __launch_bounds__(1024) k_roles(Args A)
 {
     extern __shared__ float lds[];
@@ -55,6 +57,7 @@ __global__ void __launch_bounds__(1024) k_roles(Args A)
     float acc = 0.f;
     if (streamer) {
         if (!(A.what & 1)) return;
+        if (A.what & 4) __builtin_amdgcn_s_setprio(3);
         const __amdgpu_buffer_rsrc_t a_rsrc =
             __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(A.a), 0, (int)(A.n_rows * kRowBytes), kBufferFlags);
         const __amdgpu_buffer_rsrc_t g_rsrc =
@@ -110,6 +113,7 @@ __global__ void __launch_bounds__(1024) k_roles(Args A)
         if (!(A.what & 2)) return;
         const int64_t n_tiles = A.n_edges / 32;
         f32x16 c0 = {0}, c1 = {0};
+        f32x4 d0 = {0}, d1 = {0}, d2 = {0}, d3 = {0};
         float x = (float)lane * 1e-3f, y = 1.0f;
         for (;;) {
             unsigned long long c = 0;
@@ -118,20 +122,30 @@ __global__ void __launch_bounds__(1024) k_roles(Args A)
             if (tile >= n_tiles) break;
 #pragma unroll 1
             for (int t = 0; t < 8; ++t) {
+                if (SMALL) {   // the same flop as 160 MFMAs of half the duration
+#pragma unroll
+                    for (int k = 0; k < 40; ++k) {
+                        d0 = __builtin_amdgcn_mfma_f32_16x16x4f32(x, y, d0, 0, 0, 0);
+                        d1 = __builtin_amdgcn_mfma_f32_16x16x4f32(y, x, d1, 0, 0, 0);
+                        d2 = __builtin_amdgcn_mfma_f32_16x16x4f32(x, x, d2, 0, 0, 0);
+                        d3 = __builtin_amdgcn_mfma_f32_16x16x4f32(y, y, d3, 0, 0, 0);
+                    }
+                } else {
 #pragma unroll
                 for (int k = 0; k < 40; ++k) {   // 80 MFMAs per tile of 32 pairs
                     c0 = __builtin_amdgcn_mfma_f32_32x32x2f32(x, y, c0, 0, 0, 0);
                     c1 = __builtin_amdgcn_mfma_f32_32x32x2f32(y, x, c1, 0, 0, 0);
                 }
-                x = x * 0.999f + c0[0] * 1e-30f;
+                }
+                x = x * 0.999f + (c0[0] + d0[0]) * 1e-30f;
             }
         }
-        acc = c0[0] + c1[3] + x;
+        acc = c0[0] + c1[3] + x + d0[0] + d1[1] + d2[2] + d3[3];
     }
     A.out[((int64_t)blockIdx.x * 16 + wib) * 64 + lane] = acc;
 }
 
-template <int MODE>
+template <int MODE, int SMALL = 0>
 static float run(Args A, int what, int stream_simds, const char *label)
 {
     hipEvent_t e0, e1;
@@ -145,7 +159,7 @@ static float run(Args A, int what, int stream_simds, const char *label)
         CHECK(hipMemset(A.counters, 0, 256));
         CHECK(hipDeviceSynchronize());
         CHECK(hipEventRecord(e0, nullptr));
-        k_roles<MODE><<<256, 1024, 96 * 1024>>>(A);
+        k_roles<MODE, SMALL><<<256, 1024, 96 * 1024>>>(A);
         CHECK(hipGetLastError());
         CHECK(hipEventRecord(e1, nullptr));
         CHECK(hipEventSynchronize(e1));
@@ -200,8 +214,9 @@ int main()
     CHECK(hipMemset(w, 0, E * (int64_t)kRowBytes));
     CHECK(hipMemcpy(sd, senders.data(), E * 4, hipMemcpyHostToDevice));
     A.a = a; A.g = g; A.w = w; A.senders = sd; A.out = out;
-    CHECK(hipFuncSetAttribute((const void *)k_roles<0>, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024));
-    CHECK(hipFuncSetAttribute((const void *)k_roles<1>, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024));
+    CHECK(hipFuncSetAttribute((const void *)k_roles<0, 0>, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024));
+    CHECK(hipFuncSetAttribute((const void *)k_roles<1, 0>, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024));
+    CHECK(hipFuncSetAttribute((const void *)k_roles<1, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024));
     std::printf("%lld rows, %lld edges (degree %d): 3 row loads per edge, 80 fp32 MFMA per 32 edges; 256 blocks of 16 wavefronts\n",
                 (long long)N, (long long)E, deg);
     run<0>(A, 1, 1, "roles by SIMD id");
@@ -229,6 +244,10 @@ int main()
         run<1>(A, 2, ss, "roles by wave index (streamers on every SIMD)");
         run<1>(A, 3, ss, "roles by wave index (streamers on every SIMD)");
     }
+    run<1, 1>(A, 2, 1, "roles by wave index, dense work as 16x16x4 MFMAs");
+    run<1, 1>(A, 3, 1, "roles by wave index, dense work as 16x16x4 MFMAs");
+    run<1, 0>(A, 7, 1, "roles by wave index, streamers at priority 3");
+    run<1, 1>(A, 7, 1, "roles by wave index, 16x16x4 MFMAs, streamers at priority 3");
     CHECK(hipDeviceSynchronize());
     return 0;
 }

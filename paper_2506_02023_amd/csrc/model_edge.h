@@ -934,6 +934,11 @@ __global__ void __launch_bounds__(kSimdWaves * 64, 1) k_edge_bwd_simd(EdgeBatch 
         // is needed)
         const __amdgpu_buffer_rsrc_t w_rsrc = __builtin_amdgcn_make_buffer_rsrc(
             A.wstore + (need_gbar ? (int64_t)tb * F : 0), 0, need_gbar ? S.kmax * kRowBytes : 0, kBufferFlags);
+#ifdef MLIP_TIMING_SKIP_STREAM_LOADS
+        // timing experiment only (results are wrong): no row is gathered, which leaves the dense side and the hand-over
+#pragma unroll
+        for (int k = 0; k < kStep; ++k) S.av[k] = S.gv[k] = S.wv[k] = (float)(sjo & 1);
+#else
 #pragma unroll
         for (int k = 0; k < kStep; ++k) {
             const int32_t so = __builtin_amdgcn_readlane(sjo, k);
@@ -941,6 +946,7 @@ __global__ void __launch_bounds__(kSimdWaves * 64, 1) k_edge_bwd_simd(EdgeBatch 
             S.gv[k] = buffer_load_f32(g_rsrc, f * 4, so, 0);
             S.wv[k] = buffer_load_f32_stream(w_rsrc, f * 4, k * kRowBytes);   // 0 outside the range
         }
+#endif
     };
     // rn_first: receiver of the first edge of the following step (r1 after the last step)
     auto compute_step = [&](const Step &S, const Ids &I, int32_t rn_first) {

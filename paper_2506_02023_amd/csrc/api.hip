@@ -357,7 +357,8 @@ void mlip_graph_destroy(mlip_graph_t *g)
         for (DevBuf *b : vb) b->release();
         PairGraph &Q = v.pairs;
         DevBuf *pb[] = {&Q.b_u_row_ptr, &Q.b_wslot, &Q.b_u_senders, &Q.b_u_recv,
-                        &Q.b_u_eid, &Q.b_u_mirror, &Q.b_u_d, &Q.b_u_chunk_row};
+                        &Q.b_u_eid, &Q.b_u_mirror, &Q.b_u_d, &Q.b_u_chunk_row,
+                        &Q.b_l_row_ptr, &Q.b_l_senders, &Q.b_l_slot};
         for (DevBuf *b : pb) b->release();
     };
     drop_view(g->whole);

@@ -1248,8 +1248,8 @@ struct PairArgs {   // one partition
     const int64_t *row_ptr;
     const int32_t *senders, *recv, *mirror;
     const float *d;
-    int64_t *u_row_ptr;
-    int32_t *wslot, *u_senders, *u_recv, *u_eid, *u_mirror, *u_chunk_row;
+    int64_t *u_row_ptr, *l_row_ptr;
+    int32_t *wslot, *u_senders, *u_recv, *u_eid, *u_mirror, *u_chunk_row, *l_senders, *l_slot;
     float *u_d;
 };
 struct PairBatch {   // rows, edges and work items numbered across the partitions
@@ -1277,8 +1277,10 @@ __global__ void k_pair_flag(PairBatch B, int32_t *__restrict__ flag)
 }
 
 // The upper edges keep their order, so an upper edge's position among them is the exclusive scan of the flags (less
-// the scan at its partition's first edge): the compacted arrays, and for every edge the position of its pair.
-__global__ void k_pair_fill(PairBatch B, const int32_t *__restrict__ scan)
+// the scan at its partition's first edge), and a lower edge's position among the lower ones is its index less that
+// scan: the two compacted lists.  A lower edge notes where its pair's filter values are kept: at the upper edge's
+// position in the upper-edge graph or (slots_full) in the full list.
+__global__ void k_pair_fill(PairBatch B, const int32_t *__restrict__ scan, int slots_full)
 {
     const int64_t ge = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (ge >= B.edge_start[B.n]) return;
@@ -1296,11 +1298,13 @@ __global__ void k_pair_fill(PairBatch B, const int32_t *__restrict__ scan)
         A.u_d[k] = A.d[e];
         A.wslot[e] = k;
     } else {
-        A.wslot[e] = scan[e0 + m] - base;   // (letting the upper edge store this instead was measured slower)
+        const int64_t kl = e - (int64_t)(scan[ge] - base);
+        A.l_senders[kl] = A.senders[e];
+        A.l_slot[kl] = slots_full ? m : scan[e0 + m] - base;   // (letting the upper edge store this instead was measured slower)
     }
 }
 
-// row pointers of the upper-edge graphs: the scan at the rows' first edges
+// row pointers of the upper-edge graphs (the scan at the rows' first edges) and of the lower edges' lists (the rest)
 __global__ void k_pair_rowptr(PairBatch B, const int32_t *__restrict__ scan)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;   // row, plus one closing entry per partition
@@ -1311,7 +1315,9 @@ __global__ void k_pair_rowptr(PairBatch B, const int32_t *__restrict__ scan)
     const PairArgs &A = B.s[part];
     const int64_t r = i - (B.row_start[part] + part);   // 0 .. n_rows
     const int64_t e0 = B.edge_start[part];
-    A.u_row_ptr[r] = (int64_t)(scan[e0 + A.row_ptr[r]] - scan[e0]);
+    const int64_t u = (int64_t)(scan[e0 + A.row_ptr[r]] - scan[e0]);
+    A.u_row_ptr[r] = u;
+    A.l_row_ptr[r] = A.row_ptr[r] - u;
 }
 
 // u_chunk_row[c] = first row whose first upper edge lies at or after c * kChunkEdges; u_chunk_row[n_chunks] = n_rows.
@@ -1336,10 +1342,10 @@ __global__ void k_pair_chunks(PairBatch B)
 
 }  // namespace
 
-int build_pairs_impl(mlip_graph *g, SlabView *views, int P, Carver *scratch)
+int build_pairs_impl(mlip_graph *g, SlabView *views, int P, bool slots_full, Carver *scratch)
 {
     bool all_valid = true;
-    for (int p = 0; p < P; ++p) all_valid = all_valid && views[p].pairs.valid;
+    for (int p = 0; p < P; ++p) all_valid = all_valid && views[p].pairs.valid && views[p].pairs.slots_full == slots_full;
     if (all_valid) return MLIP_OK;
     hipStream_t s = g->stream;
     auto place = [&](DevBuf &buf, size_t bytes, auto *&ptr) -> int {
@@ -1372,6 +1378,10 @@ int build_pairs_impl(mlip_graph *g, SlabView *views, int P, Carver *scratch)
         MLIP_TRY(place(Q.b_u_mirror, Ucap * 4, Q.u_mirror));
         MLIP_TRY(place(Q.b_u_d, Ucap * 4, Q.u_d));
         MLIP_TRY(place(Q.b_u_chunk_row, (size_t)(chunks_of(Q.n_upper) + 1) * 4, Q.u_chunk_row));
+        const size_t Lcap = (size_t)std::max<int64_t>(Q.n_lower, 1);
+        MLIP_TRY(place(Q.b_l_row_ptr, (Ncap + 1) * 8, Q.l_row_ptr));
+        MLIP_TRY(place(Q.b_l_senders, Lcap * 4, Q.l_senders));
+        MLIP_TRY(place(Q.b_l_slot, Lcap * 4, Q.l_slot));
     }
     // flags and their scan, kPairBatch partitions at a time (their edges one after another)
     for (int p0 = 0; p0 < P; p0 += kPairBatch) {
@@ -1404,6 +1414,9 @@ int build_pairs_impl(mlip_graph *g, SlabView *views, int P, Carver *scratch)
             a.u_mirror = Q.u_mirror;
             a.u_chunk_row = Q.u_chunk_row;
             a.u_d = Q.u_d;
+            a.l_row_ptr = Q.l_row_ptr;
+            a.l_senders = Q.l_senders;
+            a.l_slot = Q.l_slot;
             b.row_start[q + 1] = b.row_start[q] + v.n_owned;
             b.edge_start[q + 1] = b.edge_start[q] + v.n_edges_owned;
             b.chunk_start[q + 1] = b.chunk_start[q] + a.n_chunks;
@@ -1423,7 +1436,7 @@ int build_pairs_impl(mlip_graph *g, SlabView *views, int P, Carver *scratch)
         }
         MLIP_TRY(scan_i32_to_i32(flag, scan, edges, g->scan_tmp, s));
         if (edges > 0) {
-            k_pair_fill<<<blocks_for(edges, 256), 256, 0, s>>>(b, scan);
+            k_pair_fill<<<blocks_for(edges, 256), 256, 0, s>>>(b, scan, slots_full ? 1 : 0);
             MLIP_HIP(hipGetLastError());
         }
         k_pair_rowptr<<<blocks_for(rows + b.n, 256), 256, 0, s>>>(b, scan);
@@ -1431,7 +1444,10 @@ int build_pairs_impl(mlip_graph *g, SlabView *views, int P, Carver *scratch)
         k_pair_chunks<<<blocks_for(b.chunk_start[b.n] + b.n, 256), 256, 0, s>>>(b);
         MLIP_HIP(hipGetLastError());
     }
-    for (int p = 0; p < P; ++p) views[p].pairs.valid = (scratch == nullptr);   // arrays in a borrowed block do not outlive the call
+    for (int p = 0; p < P; ++p) {
+        views[p].pairs.valid = (scratch == nullptr);   // arrays in a borrowed block do not outlive the call
+        views[p].pairs.slots_full = slots_full;
+    }
     return MLIP_OK;
 }
 

@@ -127,11 +127,17 @@ struct BondGraph {
 // the lower edges' terms are added by row-wise kernels.  Built on first use after a graph build.
 struct PairGraph {
     bool valid = false;
+    bool slots_full = false;   // what l_slot holds (below)
     int64_t n_upper = 0, n_lower = 0;
     // grow-only buffers behind the pointers below (unused when the arrays are carved from a caller-independent block)
     DevBuf b_u_row_ptr, b_wslot, b_u_senders, b_u_recv, b_u_eid, b_u_mirror, b_u_d, b_u_chunk_row;
+    DevBuf b_l_row_ptr, b_l_senders, b_l_slot;
     int64_t *u_row_ptr = nullptr;                     // [n_owned + 1]
-    int32_t *wslot = nullptr;                         // [E_owned] upper index of the edge's pair
+    int32_t *wslot = nullptr;                         // [E_owned] upper edges: their index in the upper-edge graph
+    // the lower edges of the owned rows, in their order: CSR [n_owned + 1], sender row, and where the pair's filter
+    // values are kept: the index of its upper edge in the upper-edge graph or (slots_full) in the full list
+    int64_t *l_row_ptr = nullptr;
+    int32_t *l_senders = nullptr, *l_slot = nullptr;  // [n_lower]
     // [n_upper]: sender row, receiver row, edge, reverse edge
     int32_t *u_senders = nullptr, *u_recv = nullptr, *u_eid = nullptr, *u_mirror = nullptr;
     float *u_d = nullptr;                             // [n_upper]
@@ -252,7 +258,7 @@ int unpack_shifts(const mlip_graph *g, int32_t *out);
 int build_bonds_impl(mlip_graph *g, SlabView &v, double r_bond, int p_envelope);
 // Upper / lower split of the views' owned-row edges (PairGraph), all views in the same launches; does nothing if all are valid.  With a block to carve from,
 // the arrays are taken from it (and the caller invalidates the structure when the block is given up).
-int build_pairs_impl(mlip_graph *g, SlabView *views, int n_views, Carver *scratch);
+int build_pairs_impl(mlip_graph *g, SlabView *views, int n_views, bool slots_full, Carver *scratch);
 int forward_bonds_impl(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t *bw, int32_t mode,
                        double *energy, float *forces, float *atom_energy);
 

@@ -281,7 +281,7 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
     }
     if (upper_bwd) {
         prof_begin(g, MLIP_PROF_GRAPH);
-        MLIP_TRY(build_pairs_impl(g, views, P, scratch));
+        MLIP_TRY(build_pairs_impl(g, views, P, /*slots_full=*/!upper, scratch));
         prof_end(g);
     }
     int64_t n_parts = 0;
@@ -356,6 +356,9 @@ int forward_t(mlip_graph *g, const mlip_weights_t *w, const mlip_bond_weights_t 
             a.d = v.d;
             a.wstore = (layer >= 0 && v.ws.wst) ? v.ws.wst + (size_t)layer * wrows(v) * F : nullptr;
             a.wslot = upper ? v.pairs.wslot : nullptr;
+            a.l_row_ptr = upper_bwd ? v.pairs.l_row_ptr : nullptr;
+            a.l_senders = upper_bwd ? v.pairs.l_senders : nullptr;
+            a.l_slot = upper_bwd ? v.pairs.l_slot : nullptr;
             a.a = (layer >= 0) ? v.ws.a + (size_t)layer * (size_t)v.n_owned * F : nullptr;
             a.bond_of_edge = (bw && v.bonds.n > 0) ? v.bonds.of_edge.as<int32_t>() : nullptr;
             a.wb_bf16 = (prec == kPrecBf16);

@@ -201,7 +201,9 @@ struct SmallArgs {   // one partition
     float *h, *g, *gbar, *abar, *floc, *eps;
     float *a;                      // the layer's receiver sums (second pass of the pair-wise forward step)
     // upper / lower split of the owned rows' edges (or nullptr: kept filter values sit at the edges' own indices)
-    const int32_t *wslot;          // [E_owned] upper index of an edge's pair: where its kept filter values are
+    const int32_t *wslot;          // [E_owned] upper edges: their index in the upper-edge graph, where their filter values are kept
+    const int64_t *l_row_ptr;      // the owned rows' lower edges: CSR, sender row, where the pair's filter values are kept
+    const int32_t *l_senders, *l_slot;
     const float *dsum, *wstore, *d;
     const int32_t *bond_of_edge;   // three-body variant (or nullptr)
     const void *wb;                // bond filter rows of the layer: fp32, or bf16 if wb_bf16
@@ -288,24 +290,22 @@ __global__ void __launch_bounds__(256) k_edge_lower(SmallBatch B)
     const SmallArgs &A = B.s[part];
     const int64_t r = gk - B.start[part];
     const unsigned f = lane & (F - 1);
-    const int64_t e0 = A.row_ptr[r], e1 = A.row_ptr[r + 1];
+    // the row's lower edges (wave-uniform, kept scalar; edge indices fit 32 bits)
+    const int64_t e0 = __builtin_amdgcn_readfirstlane((int32_t)A.l_row_ptr[r]);
+    const int64_t e1 = __builtin_amdgcn_readfirstlane((int32_t)A.l_row_ptr[r + 1]);
     float acc = 0.f;
     for (int64_t eb = e0; eb < e1; eb += 64) {
+        const int n = (int)min((int64_t)64, e1 - eb);
         const int64_t el = min(eb + lane, e1 - 1);
-        const int32_t jl = A.senders[el], ml = A.mirror[el];
-        const int32_t sl = A.wslot ? A.wslot[el] : ml;   // where the pair's filter values are kept (else: at the upper edge)
-        unsigned long long mask = __ballot(eb + lane < e1 && (int64_t)ml < el);   // the lower edges among these 64
-        while (mask != 0) {
+        const int32_t jl = A.l_senders[el];
+        const int32_t sl = A.l_slot[el];   // where the pair's filter values are kept
+        for (int c = 0; c < n; c += kLowerChunk) {
             float wv[kLowerChunk], gv[kLowerChunk];
-            int n = 0;
 #pragma unroll
             for (int t = 0; t < kLowerChunk; ++t) {
                 wv[t] = gv[t] = 0.f;
-                if (mask != 0) {   // wave-uniform: no load is issued for an edge that is not there
-                    const int idx = __builtin_ctzll(mask);
-                    mask &= mask - 1;
-                    ++n;
-                    const int64_t j = __builtin_amdgcn_readlane(jl, idx), m = __builtin_amdgcn_readlane(sl, idx);
+                if (c + t < n) {   // wave-uniform: no load is issued for an edge that is not there
+                    const int64_t j = __builtin_amdgcn_readlane(jl, c + t), m = __builtin_amdgcn_readlane(sl, c + t);
                     wv[t] = __builtin_nontemporal_load(A.wstore + m * F + f);
                     gv[t] = (REVERSE ? A.abar : A.g)[j * F + f];
                 }

@@ -42,14 +42,14 @@ def flops_bwd_edge(F, K=8):
 
 
 # HBM bytes per launch (one layer over all 8 slabs) on the default workload, from rocprofv3 --pmc FETCH_SIZE and
-# WRITE_SIZE (profiles/edge_traffic_configs3_8slabs.md): KiB x copy-kernel scale (1.9974 for FETCH_SIZE, 1.000 for
+# WRITE_SIZE (profiles/edge_traffic_configs3_8slabs.md): KiB x copy-kernel scale (1.9976 for FETCH_SIZE, 1.000 for
 # WRITE_SIZE)
 TRAFFIC_SOURCE = ("profiled constant, not measured by this run: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this kernel on "
                   "this workload, profiles/edge_traffic_configs3_8slabs.md")
-TRAFFIC_BWD_LAUNCH_BYTES = (6196793 * 1.9974 + 1003931) * 1024         # k_edge_bwd on the upper-edge graphs
-TRAFFIC_FWD_LAUNCH_BYTES = (1369410 * 1.9974 + 6367676) * 1024         # k_edge_fwd on the upper-edge graphs
-TRAFFIC_FWD_LOWER_LAUNCH_BYTES = (4075853 * 1.9974 + 250047) * 1024    # k_edge_lower, forward
-TRAFFIC_BWD_LOWER_LAUNCH_BYTES = (4076217 * 1.9974 + 250047) * 1024    # k_edge_lower, reverse
+TRAFFIC_BWD_LAUNCH_BYTES = (6196767 * 1.9976 + 1003909) * 1024         # k_edge_bwd on the upper-edge graphs
+TRAFFIC_FWD_LAUNCH_BYTES = (1369693 * 1.9976 + 6367675) * 1024         # k_edge_fwd on the upper-edge graphs
+TRAFFIC_FWD_LOWER_LAUNCH_BYTES = (3853592 * 1.9976 + 250047) * 1024    # k_edge_lower, forward
+TRAFFIC_BWD_LOWER_LAUNCH_BYTES = (3853695 * 1.9976 + 250047) * 1024    # k_edge_lower, reverse
 
 
 # fp32 vector peak that applies to this build: 256 CUs x 4 SIMDs x 16 lanes x 2 flop per FMA x 2.4 GHz = 78.6 TFLOP/s.

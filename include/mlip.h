@@ -218,8 +218,9 @@ int mlip_forward(mlip_graph_t *graph, const mlip_weights_t *weights, int32_t mod
  * weights, energy partial sums) is carved from one fixed device array inside the library of
  * mlip_static_scratch_bytes() = 64 MiB per GPU, held until the process ends; the call allocates and frees
  * nothing and clears what must start at zero with fill kernels.  A graph and model whose workspace
- * (about n_local (4 + 2 L) F 4 + n_edges (4 + (L - 1) F 4) bytes summed over the partitions of the mode, plus
- * the packed weights) exceeds the array are rejected with MLIP_EINVAL; with the event profiler enabled the call
+ * (about n_local (4 + 2 L) F 4 + n_edges (36 + L F 2) bytes summed over the partitions of the mode - the kept
+ * filter values take one row per edge pair and layer, the lists of the pairs' edges are rebuilt in the array on
+ * every call - plus the packed weights) exceeds the array are rejected with MLIP_EINVAL; with the event profiler enabled the call
  * returns MLIP_ESTATE.  All calls on one GPU, from any handle, share the array and find the previous call's
  * contents in it: calls that overlap on one GPU (two streams, two threads) race and must be serialised by the
  * caller.  Weights are packed on every call (nothing is cached in the shared array).  The graph itself must

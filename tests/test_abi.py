@@ -26,6 +26,18 @@ def test_library_exports_all_declared_symbols():
     assert b"gfx950" in lib.mlip_version()
 
 
+def test_profile_groups_of_the_binding_match_the_header():
+    """mlip_profile_read fills MLIP_PROF_COUNT entries: the binding's arrays are sized by its list of group names, which
+    must therefore name every group of the header, in the header's order."""
+    from paper_2506_02023_amd import binding as B
+    text = open(os.path.join(ROOT, "include", "mlip.h")).read()
+    groups = {name: int(value) for name, value in re.findall(r"\bMLIP_PROF_([A-Z_]+)\s*=\s*(\d+)", text)}
+    count = groups.pop("COUNT")
+    assert sorted(groups.values()) == list(range(count))
+    by_index = [name.lower() for name, _ in sorted(groups.items(), key=lambda kv: kv[1])]
+    assert list(B.PROF_GROUPS) == by_index
+
+
 def test_argument_errors_without_gpu():
     """Error paths that are decided before any HIP call."""
     from paper_2506_02023_amd import binding as B

@@ -267,6 +267,32 @@ int mlip_forward_bonds(mlip_graph_t *graph, const mlip_weights_t *weights, const
 int mlip_graph_bonds(const mlip_graph_t *graph, int32_t p, const int32_t **bond_edge, const int64_t **bond_ptr,
                      int64_t *n_bonds);
 
+/*
+ * Upper / lower split of the edges of partition p's owned rows (p = -1: of the whole graph), the form in which the
+ * fp32 edge kernels walk them.  The filter of the radial message-passing layer is a function of the edge length
+ * alone (benchmark description: w_e = MLP(basis(d_e))), and the two edges of an edge / reverse-edge pair have the
+ * same length, so the filter is evaluated for one of them, the "upper" one: the edge whose reverse edge lies at a
+ * larger index of the partition's edge list.  (An edge from a ghost sender is always upper: its reverse edge is in
+ * a ghost row, behind all owned rows.)  All other edges of the owned rows are "lower".
+ * Borrowed DEVICE pointers, valid until the next mlip_build_graph on the handle:
+ *   u_row_ptr [n_owned + 1]   CSR of the upper edges over the owned rows, the edges in the order of the full list
+ *   u_senders, u_eid, u_mirror [n_upper]   sender row, index of the edge and index of its reverse edge in the full list
+ *   u_d [n_upper]             edge length
+ *   l_row_ptr [n_owned + 1], l_senders [n_lower]   the same for the lower edges
+ *   l_slot [n_lower]          index of the pair's upper edge in the upper-edge lists
+ * Built on the handle's stream on first use after a graph build (mlip_forward does the same); n_upper and n_lower
+ * are HOST values.  Errors: MLIP_ESTATE without a graph, MLIP_EINVAL for a partition index out of range.
+ */
+typedef struct {
+    int64_t n_upper, n_lower;
+    const int64_t *u_row_ptr;
+    const int32_t *u_senders, *u_eid, *u_mirror;
+    const float *u_d;
+    const int64_t *l_row_ptr;
+    const int32_t *l_senders, *l_slot;
+} mlip_pairs_t;
+int mlip_graph_pairs(mlip_graph_t *graph, int32_t p, mlip_pairs_t *out);
+
 void mlip_graph_destroy(mlip_graph_t *graph);
 
 /*

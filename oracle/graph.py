@@ -163,3 +163,65 @@ def partition(graph, slab_of, n_slabs):
         sl.senders = local_of[send[sl.edge_ids]].astype(np.int32)
         assert (sl.senders >= 0).all()
     return slabs
+
+
+def reverse_edges(graph):
+    """mirror[e] = index of the edge with sender and receiver swapped and the image shift negated.  It exists for
+    every edge: the radius-graph predicate is symmetric (Methods, "Distributing Atom Graphs": atoms within the cutoff
+    of each other are joined in both directions)."""
+    recv = graph.receivers.astype(np.int64)
+    send = graph.senders.astype(np.int64)
+    S = graph.shifts.astype(np.int64)
+    fwd = np.lexsort((S[:, 2], S[:, 1], S[:, 0], send, recv))          # edges by (receiver, sender, shift)
+    rev = np.lexsort((-S[:, 2], -S[:, 1], -S[:, 0], recv, send))       # edges by (sender, receiver, -shift)
+    mirror = np.empty(graph.E, np.int64)
+    mirror[rev] = fwd
+    assert np.array_equal(recv[mirror], send) and np.array_equal(send[mirror], recv)
+    assert np.array_equal(S[mirror], -S)
+    return mirror
+
+
+def pair_split(graph, slab=None):
+    """Upper / lower split of the edges of a partition's owned rows (slab=None: of the whole graph), by definition:
+    the two edges of an edge / reverse-edge pair have the same length, hence the same filter values (the filter of the
+    benchmark's message-passing layer is a function of the edge length alone), so one of them, the "upper" one, stands
+    for the pair: the one that comes first in the partition's edge list (owned rows in local order, each a copy of
+    the atom's global row; rows of ghost atoms come after all owned rows, so an edge from a ghost sender is upper).
+
+    Returns a dict: u_row_ptr, u_senders (local rows), u_eid (position in the partition's list of owned-row edges),
+    u_mirror_owned (position of the reverse edge in that list, -1 if it lies in a ghost row), l_row_ptr, l_senders,
+    l_slot (index of the pair's upper edge among the upper edges)."""
+    mirror = reverse_edges(graph)
+    if slab is None:
+        n_rows = graph.N
+        row_ptr = graph.row_ptr.astype(np.int64)
+        edge_ids = np.arange(graph.E, dtype=np.int64)
+        senders = graph.senders.astype(np.int64)
+    else:
+        n_rows = len(slab.owned)
+        row_ptr = slab.row_ptr.astype(np.int64)
+        edge_ids = slab.edge_ids.astype(np.int64)
+        senders = slab.senders.astype(np.int64)
+    E_own = len(edge_ids)
+    # position of every global edge in this partition's list of owned-row edges (-1: not an owned row's edge)
+    pos_of = np.full(graph.E, -1, np.int64)
+    pos_of[edge_ids] = np.arange(E_own)
+    m_pos = pos_of[mirror[edge_ids]]
+    e_pos = np.arange(E_own)
+    upper = (m_pos < 0) | (m_pos > e_pos)
+    assert not np.any(m_pos == e_pos)
+    rows = np.repeat(np.arange(n_rows), np.diff(row_ptr))
+    out = {}
+    up = np.flatnonzero(upper)
+    lo = np.flatnonzero(~upper)
+    out["u_row_ptr"] = np.concatenate([[0], np.cumsum(np.bincount(rows[up], minlength=n_rows))]).astype(np.int64)
+    out["l_row_ptr"] = np.concatenate([[0], np.cumsum(np.bincount(rows[lo], minlength=n_rows))]).astype(np.int64)
+    out["u_senders"] = senders[up].astype(np.int32)
+    out["u_eid"] = up.astype(np.int32)
+    out["u_mirror_owned"] = m_pos[up].astype(np.int64)
+    out["l_senders"] = senders[lo].astype(np.int32)
+    index_among_upper = np.full(E_own, -1, np.int64)
+    index_among_upper[up] = np.arange(len(up))
+    out["l_slot"] = index_among_upper[m_pos[lo]].astype(np.int32)
+    assert (out["l_slot"] >= 0).all()
+    return out

@@ -47,6 +47,12 @@ _ALLOC_FN = ctypes.CFUNCTYPE(ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p)
 _FREE_FN = ctypes.CFUNCTYPE(None, ctypes.c_void_p, ctypes.c_void_p)
 
 
+class _Pairs(ctypes.Structure):
+    _fields_ = [("n_upper", ctypes.c_int64), ("n_lower", ctypes.c_int64)] + \
+               [(n, ctypes.c_void_p) for n in ("u_row_ptr", "u_senders", "u_eid", "u_mirror", "u_d",
+                                               "l_row_ptr", "l_senders", "l_slot")]
+
+
 class _Alloc(ctypes.Structure):
     _fields_ = [("alloc", _ALLOC_FN), ("free", _FREE_FN), ("ctx", ctypes.c_void_p)]
 
@@ -112,6 +118,7 @@ def lib():
         L.mlip_graph_mirror.argtypes = [vp, ctypes.POINTER(vp)]
         L.mlip_graph_slab_of.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(i32)]
         L.mlip_graph_slab.argtypes = [vp, i32, ctypes.POINTER(_SlabInfo)]
+        L.mlip_graph_pairs.argtypes = [vp, i32, ctypes.POINTER(_Pairs)]
         L.mlip_graph_from.argtypes = [vp, i32, i32, ctypes.POINTER(vp), ctypes.POINTER(i64)]
         L.mlip_graph_to.argtypes = [vp, i32, i32, ctypes.POINTER(vp), ctypes.POINTER(i64)]
         L.mlip_profile_enable.argtypes = [vp, i32]
@@ -202,6 +209,22 @@ class Graph:
         be, bp, n = ctypes.c_void_p(), ctypes.c_void_p(), ctypes.c_int64()
         _check(lib().mlip_graph_bonds(self._h, p, ctypes.byref(be), ctypes.byref(bp), ctypes.byref(n)))
         return self._host(be.value, n.value, np.int32), self._host(bp.value, rows + 1, np.int64)
+
+    def pairs(self, p=-1):
+        """dict with the upper / lower split of the owned rows' edges of partition p (-1: the whole graph)."""
+        rows = self.sizes()[0] if p < 0 else self.slab(p)["n_owned"]
+        q = _Pairs()
+        _check(lib().mlip_graph_pairs(self._h, p, ctypes.byref(q)))
+        nu, nl = q.n_upper, q.n_lower
+        d = {"n_upper": nu, "n_lower": nl}
+        d["u_row_ptr"] = self._host(q.u_row_ptr, rows + 1, np.int64)
+        d["l_row_ptr"] = self._host(q.l_row_ptr, rows + 1, np.int64)
+        for k in ("u_senders", "u_eid", "u_mirror"):
+            d[k] = self._host(getattr(q, k), nu, np.int32)
+        d["u_d"] = self._host(q.u_d, nu, np.float32)
+        for k in ("l_senders", "l_slot"):
+            d[k] = self._host(getattr(q, k), nl, np.int32)
+        return d
 
     def slab_of(self):
         N, _, _ = self.sizes()

@@ -337,6 +337,28 @@ int mlip_graph_bonds(const mlip_graph_t *g, int32_t p, const int32_t **bond_edge
     return MLIP_OK;
 }
 
+int mlip_graph_pairs(mlip_graph_t *g, int32_t p, mlip_pairs_t *out)
+{
+    if (!g || g->N <= 0) { set_error("no graph"); return MLIP_ESTATE; }
+    if (!out) { set_error("null output"); return MLIP_EINVAL; }
+    if (p < -1 || p >= g->P || (p >= 0 && g->P < 2)) { set_error("partition index out of range"); return MLIP_EINVAL; }
+    // all partitions of the mode at once, as mlip_forward builds them
+    SlabView *views = (p < 0) ? &g->whole : g->slabs.data();
+    MLIP_TRY(build_pairs_impl(g, views, p < 0 ? 1 : g->P, /*slots_full=*/false, nullptr));
+    const PairGraph &Q = (p < 0) ? g->whole.pairs : g->slabs[p].pairs;
+    out->n_upper = Q.n_upper;
+    out->n_lower = Q.n_lower;
+    out->u_row_ptr = Q.u_row_ptr;
+    out->u_senders = Q.u_senders;
+    out->u_eid = Q.u_eid;
+    out->u_mirror = Q.u_mirror;
+    out->u_d = Q.u_d;
+    out->l_row_ptr = Q.l_row_ptr;
+    out->l_senders = Q.l_senders;
+    out->l_slot = Q.l_slot;
+    return MLIP_OK;
+}
+
 void mlip_graph_destroy(mlip_graph_t *g)
 {
     if (!g) return;

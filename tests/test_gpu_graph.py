@@ -149,3 +149,54 @@ def test_mirror_index():
         assert np.array_equal(senders[m], recv) and np.array_equal(recv[m], senders)
         assert np.array_equal(shifts[m], -shifts)
         assert not np.any(m == np.arange(len(m)))
+
+
+def _check_pairs(pos, cell, sp, r_cut, P):
+    """The upper / lower split of the owned rows' edges (what the fp32 edge kernels walk) against the oracle's
+    definition, bit for bit; where the reverse edge lies in a ghost row (which the oracle's local graph does not hold)
+    the index the library gives is checked against the library's own local CSR instead."""
+    ref = og.build_graph(pos, cell, r_cut)
+    g = gpu_graph(pos, cell, sp, r_cut, n_slabs=P)
+    _, _, _, d_all = g.csr()
+    if P == 1:
+        parts = [(-1, None, ref.row_ptr, np.arange(ref.E))]
+    else:
+        slab_ref, _ = og.slab_assign(pos, cell, P)
+        parts = [(p, sl, sl.row_ptr, sl.edge_ids) for p, sl in enumerate(og.partition(ref, slab_ref, P))]
+    for p, sl, row_ptr, edge_ids in parts:
+        want = og.pair_split(ref, sl)
+        got = g.pairs(p)
+        assert got["n_upper"] == len(want["u_eid"]) and got["n_lower"] == len(want["l_slot"])
+        for k in ("u_row_ptr", "u_senders", "u_eid", "l_row_ptr", "l_senders", "l_slot"):
+            assert np.array_equal(got[k], want[k]), (p, k)
+        assert np.array_equal(got["u_d"], d_all[edge_ids[want["u_eid"]]])   # the lengths are copies, not recomputed
+        owned = want["u_mirror_owned"] >= 0
+        assert np.array_equal(got["u_mirror"][owned], want["u_mirror_owned"][owned])
+        if not owned.all():   # reverse edges in ghost rows: behind the owned rows' edges, in the sender's row, from the receiver
+            s = g.slab(p)
+            m = got["u_mirror"][~owned].astype(np.int64)
+            assert (m >= s["n_edges_owned"]).all() and (m < s["n_edges"]).all()
+            rows_of_m = np.searchsorted(s["row_ptr"], m, side="right") - 1
+            assert np.array_equal(rows_of_m, got["u_senders"][~owned])
+            recv_rows = np.repeat(np.arange(len(row_ptr) - 1), np.diff(row_ptr))[want["u_eid"][~owned]]
+            assert np.array_equal(s["senders"][m], recv_rows)
+            assert len(np.unique(m)) == len(m)
+
+
+@pytest.mark.parametrize("P", [1, 3, 8])
+def test_pair_split_config0(P):
+    c, _, _ = oracle_config(0)
+    _check_pairs(c["positions"], c["cell"], c["species"], c["r_cut"], P)
+
+
+@pytest.mark.parametrize("P", [1, 5])
+def test_pair_split_triclinic(P):
+    pos, cell, sp = wl.random_triclinic(300, 21, scale=14.0)
+    _check_pairs(pos, cell, sp, 3.0, P)
+
+
+def test_pair_split_medium_8_slabs_and_many_slabs():
+    c, _, _ = oracle_config(1)
+    _check_pairs(c["positions"], c["cell"], c["species"], c["r_cut"], 8)
+    c = wl.make_config(0, n=6)
+    _check_pairs(c["positions"], c["cell"], c["species"], c["r_cut"], 64)   # thin slabs: most edges come from ghosts

@@ -213,3 +213,40 @@ def test_wide_slabs_talk_to_neighbours_only():
         lo, hi = p * Lx / P, (p + 1) * Lx / P
         dist = np.minimum(np.abs((x - lo + Lx / 2) % Lx - Lx / 2), np.abs((x - hi + Lx / 2) % Lx - Lx / 2))
         assert np.all(dist <= r_cut + 1e-9)
+
+
+@pytest.mark.parametrize("P", [1, 3])
+def test_pair_split_against_a_python_walk(P):
+    """reverse_edges and pair_split against plain loops over the edge list of a small triclinic system: every pair of
+    owned-row edges has exactly one upper edge (the earlier one), an edge whose reverse edge is not an owned row's
+    edge is upper, and a lower edge's slot names its reverse edge among the upper ones."""
+    pos, cell, _ = wl.random_triclinic(40, 11, scale=6.0)
+    g = og.build_graph(pos, cell, 3.5)
+    recv = g.receivers
+    table = {(int(recv[e]), int(g.senders[e]), *map(int, g.shifts[e])): e for e in range(g.E)}
+    mirror = og.reverse_edges(g)
+    for e in range(g.E):
+        s = g.shifts[e]
+        assert mirror[e] == table[(int(g.senders[e]), int(recv[e]), int(-s[0]), int(-s[1]), int(-s[2]))]
+    slab_of, _ = og.slab_assign(pos, cell, P)
+    for sl in og.partition(g, slab_of, P):
+        q = og.pair_split(g, sl if P > 1 else None)
+        edge_ids = sl.edge_ids if P > 1 else np.arange(g.E)
+        pos_of = {int(ge): k for k, ge in enumerate(edge_ids)}
+        uppers, lowers = [], []
+        for k, ge in enumerate(edge_ids):
+            m = pos_of.get(int(mirror[ge]), -1)
+            (uppers if (m < 0 or m > k) else lowers).append(k)
+        assert list(q["u_eid"]) == uppers
+        n_ghost_edges = sum(1 for k in uppers if pos_of.get(int(mirror[edge_ids[k]]), -1) < 0)
+        assert len(uppers) == (len(edge_ids) - n_ghost_edges) // 2 + n_ghost_edges
+        assert len(q["l_slot"]) == len(lowers)
+        for t, k in enumerate(lowers):
+            upper_of_pair = uppers[q["l_slot"][t]]
+            assert edge_ids[upper_of_pair] == mirror[edge_ids[k]]
+        # row pointers: the upper / lower edges of every row, in order
+        row_ptr = sl.row_ptr if P > 1 else g.row_ptr
+        for r in range(len(row_ptr) - 1):
+            in_row = [k for k in uppers if row_ptr[r] <= k < row_ptr[r + 1]]
+            assert list(q["u_eid"][q["u_row_ptr"][r]: q["u_row_ptr"][r + 1]]) == in_row
+            assert q["l_row_ptr"][r + 1] - q["l_row_ptr"][r] == (row_ptr[r + 1] - row_ptr[r]) - len(in_row)
